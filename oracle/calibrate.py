@@ -1,0 +1,53 @@
+"""Algorithm 1, steps 1-6: eigenspace low-rank approximation of the compression error.
+
+Offline and not part of the GPU hot path; kept in the oracle because (a) it
+pins the forward pass on planted errors (What + B'A must reproduce W) and (b) it
+is the next step outside the hot path.  float64 numpy throughout.
+
+Paper notation (column convention): W, What are d x k; Xt (X-tilde) is k x n;
+Q, Lambda from the eigendecomposition of Xt Xt^T; Q' = Q sqrt(Lambda);
+dW' = dW Q'; rank-r SVD of dW' gives B' = U' Sigma', A' = V'^T; A = A' Q'^-1.
+"""
+import numpy as np
+
+
+def gram(Xt):
+    """Xt Xt^T (k x k), Sec. 3.  Any positive rescaling of it leaves B'A unchanged."""
+    Xt = np.asarray(Xt, dtype=np.float64)
+    return Xt @ Xt.T
+
+
+def eora_factors(W, W_hat, Xt, r, eig_floor=1e-12):
+    """Return (B', A) with B' of shape d x r and A of shape r x k.
+
+    eig_floor: eigenvalues are clamped to eig_floor * max eigenvalue before the
+    inverse square root, since the paper assumes Q' invertible without treating
+    zero eigenvalues (Sec. 3); with full-rank calibration activations the clamp
+    is inactive.
+    """
+    W = np.asarray(W, dtype=np.float64)
+    W_hat = np.asarray(W_hat, dtype=np.float64)
+    dW = W - W_hat                                   # step 1
+    lam, Q = np.linalg.eigh(gram(Xt))                # step 2
+    lam = np.maximum(lam, eig_floor * lam.max())
+    root = np.sqrt(lam)
+    Qp = Q * root[None, :]                           # step 3: Q' = Q sqrt(Lambda)
+    dWp = dW @ Qp                                    # step 4
+    U, sig, Vt = np.linalg.svd(dWp, full_matrices=False)   # step 5
+    Bp = U[:, :r] * sig[None, :r]
+    Ap = Vt[:r, :]
+    A = (Ap / root[None, :]) @ Q.T                   # step 6: A' sqrt(Lambda)^-1 Q^T
+    return Bp, A
+
+
+def plain_svd_factors(W, W_hat, r):
+    """Rank-r SVD of the raw error (Sec. 2, Eq. 2): the case Xt Xt^T = I of the above."""
+    dW = np.asarray(W, dtype=np.float64) - np.asarray(W_hat, dtype=np.float64)
+    U, sig, Vt = np.linalg.svd(dW, full_matrices=False)
+    return U[:, :r] * sig[None, :r], Vt[:r, :]
+
+
+def layer_loss(W, W_hat, B, A, Xt):
+    """|| (W - What - B A) Xt ||_F : the layer-wise compression loss (Eq. 1) left after compensation."""
+    E = np.asarray(W, dtype=np.float64) - np.asarray(W_hat, dtype=np.float64) - B @ A
+    return float(np.linalg.norm(E @ np.asarray(Xt, dtype=np.float64)))

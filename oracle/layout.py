@@ -1,0 +1,256 @@
+"""Bit-level layouts of the stored operands, written out independently of the GPU code.
+
+The paper fixes only the logical content of the formats ("3/4-bit", "group size
+128", "asymmetric", Sec. 4.1 and App. A.11; "2:4", Sec. 1; "quantise EoRA to
+4-bit", Sec. 4.5).  The byte placement below is this project's own and is
+restated here from its specification, not shared with the HIP sources.
+
+All weight-like operands (a matrix with `rows` output rows and `K` contraction
+columns) are stored TILE-MAJOR.  A tile covers 16 consecutive rows and KT
+consecutive columns and belongs to a 64-lane wavefront: lane l = 16*j + n owns
+row n of the tile and the j-th quarter of its columns.  Tiles are ordered
+row-block first:  tile index = R * (K / KT) + g,  R = row // 16, g = col // KT.
+
+Q4  (4-bit codes, KT = 128 for the backbone, min(128, K) for a factor)
+    lane owns columns  c = (KT/4)*j + 8*t + kk  (t = word of the lane, kk = 0..7)
+    word index in the array = tile*(64*KT/32) + l*(KT/32) + t
+    the code of column kk sits in nibble e = 4*(kk % 2) + kk // 2 of that word
+    (even columns fill nibbles 0..3, odd columns nibbles 4..7)
+
+Q3  (3-bit codes, KT = 128): three words per lane, word index = tile*192 + 3*l + d.
+    The lane owns 32 columns cc = 0..31 of its quarter.  Columns 0..29 form 15
+    pairs p = cc // 2 (h = cc % 2 is the 16-bit half: 0 low, 1 high); pair p
+    sits in word d = p // 5 at bits 16*h + 3*(p % 5) .. +2.  Bit 15 of each
+    half is spare; the spare bits carry the last two codes: bit b of the code
+    of column 30 + h is bit 16*h + 15 of word b.
+
+zeros   one nibble per (row, quantisation group): word 2*(R*NG + q) + n // 8,
+        nibble n % 8   (NG = K / group, q = col // group)
+scales  fp16, element (R*NG + q)*16 + n
+
+F16 (fp16 factor, KT = 32): element index = (tile*64 + l)*8 + i for column
+    32*g + 8*j + i.
+
+SP24 (2:4 sparse fp16 backbone, tile = 16 rows x 128 dense columns)
+    the lane owns dense columns 64*s + 16*j + 4*q + p  (s = 0,1 half of the
+    tile, q = 0..3 group of four, p = 0..3 position).  Each group keeps two
+    values v = 0,1 at positions p_0 < p_1.
+    values:  element tile*1024 + s*512 + l*8 + 2*q + v
+    indices: one uint32 per (tile, lane): bits 16*s + 4*q + 2*v .. +1 = p_v
+"""
+import numpy as np
+
+ROWS = 16          # rows of a tile
+LANES = 64
+
+
+def _check(rows, K, KT):
+    if rows % ROWS or K % KT or KT % 32:
+        raise ValueError("rows must be a multiple of 16 and K of the k-tile")
+
+
+# ----------------------------------------------------------------------------
+# 4-bit codes
+# ----------------------------------------------------------------------------
+def q4_locate(o, i, K, KT):
+    """(word index, bit shift) of the code of row o, column i."""
+    R, n = o // ROWS, o % ROWS
+    g, c = i // KT, i % KT
+    per_lane = KT // 4
+    j, cc = c // per_lane, c % per_lane
+    t, kk = cc // 8, cc % 8
+    e = 4 * (kk % 2) + kk // 2
+    wpl = KT // 32
+    lane = 16 * j + n
+    tile = R * (K // KT) + g
+    return tile * (LANES * wpl) + lane * wpl + t, 4 * e
+
+
+def pack_q4(codes, KT=128):
+    codes = np.asarray(codes)
+    rows, K = codes.shape
+    _check(rows, K, KT)
+    if codes.min(initial=0) < 0 or codes.max(initial=0) > 15:
+        raise ValueError("4-bit code out of range")
+    o, i = np.meshgrid(np.arange(rows), np.arange(K), indexing="ij")
+    word, shift = q4_locate(o, i, K, KT)
+    out = np.zeros(rows * K // 8, dtype=np.uint32)
+    np.bitwise_or.at(out, word.ravel(), (codes.astype(np.uint32) << shift.astype(np.uint32)).ravel())
+    return out
+
+
+def unpack_q4(words, rows, K, KT=128):
+    words = np.asarray(words, dtype=np.uint32)
+    _check(rows, K, KT)
+    if words.size != rows * K // 8:
+        raise ValueError("wrong number of words")
+    o, i = np.meshgrid(np.arange(rows), np.arange(K), indexing="ij")
+    word, shift = q4_locate(o, i, K, KT)
+    return ((words[word] >> shift.astype(np.uint32)) & 0xF).astype(np.uint8)
+
+
+# ----------------------------------------------------------------------------
+# 3-bit codes
+# ----------------------------------------------------------------------------
+def _q3_lane(o, i, K):
+    R, n = o // ROWS, o % ROWS
+    g, c = i // 128, i % 128
+    j, cc = c // 32, c % 32
+    lane = 16 * j + n
+    tile = R * (K // 128) + g
+    return tile * 192 + 3 * lane, cc
+
+
+def pack_q3(codes):
+    codes = np.asarray(codes)
+    rows, K = codes.shape
+    _check(rows, K, 128)
+    if codes.min(initial=0) < 0 or codes.max(initial=0) > 7:
+        raise ValueError("3-bit code out of range")
+    o, i = np.meshgrid(np.arange(rows), np.arange(K), indexing="ij")
+    base, cc = _q3_lane(o, i, K)
+    out = np.zeros(rows * K * 3 // 32, dtype=np.uint32)
+    q = codes.astype(np.uint32)
+    paired = cc < 30
+    p, h = cc // 2, cc % 2
+    # the fifteen in-place pairs
+    w = base + p // 5
+    s = (16 * h + 3 * (p % 5)).astype(np.uint32)
+    np.bitwise_or.at(out, w[paired], (q[paired] << s[paired]))
+    # the two codes spread over the spare bits
+    hs = (cc - 30)
+    for b in range(3):
+        bit = (q >> np.uint32(b)) & 1
+        s = (16 * hs + 15).astype(np.uint32)
+        np.bitwise_or.at(out, (base + b)[~paired], (bit[~paired] << s[~paired]))
+    return out
+
+
+def unpack_q3(words, rows, K):
+    words = np.asarray(words, dtype=np.uint32)
+    _check(rows, K, 128)
+    if words.size != rows * K * 3 // 32:
+        raise ValueError("wrong number of words")
+    o, i = np.meshgrid(np.arange(rows), np.arange(K), indexing="ij")
+    base, cc = _q3_lane(o, i, K)
+    p, h = cc // 2, cc % 2
+    pc = np.minimum(p, 14)                      # clamp so the gather below stays in range
+    s = (16 * h + 3 * (pc % 5)).astype(np.uint32)
+    inplace = (words[base + pc // 5] >> s) & 7
+    hs = np.clip(cc - 30, 0, 1)
+    s15 = (16 * hs + 15).astype(np.uint32)
+    spread = np.zeros_like(inplace)
+    for b in range(3):
+        spread |= ((words[base + b] >> s15) & 1) << np.uint32(b)
+    return np.where(cc < 30, inplace, spread).astype(np.uint8)
+
+
+# ----------------------------------------------------------------------------
+# zero-points and scales of the quantisation groups
+# ----------------------------------------------------------------------------
+def pack_zeros(zeros):
+    zeros = np.asarray(zeros)
+    rows, NG = zeros.shape
+    if rows % ROWS:
+        raise ValueError("rows must be a multiple of 16")
+    if zeros.min(initial=0) < 0 or zeros.max(initial=0) > 15:
+        raise ValueError("zero-point out of range")
+    o, q = np.meshgrid(np.arange(rows), np.arange(NG), indexing="ij")
+    R, n = o // ROWS, o % ROWS
+    word = 2 * (R * NG + q) + n // 8
+    out = np.zeros(rows * NG // 8, dtype=np.uint32)
+    np.bitwise_or.at(out, word.ravel(), (zeros.astype(np.uint32) << (4 * (n % 8)).astype(np.uint32)).ravel())
+    return out
+
+
+def unpack_zeros(words, rows, NG):
+    words = np.asarray(words, dtype=np.uint32)
+    o, q = np.meshgrid(np.arange(rows), np.arange(NG), indexing="ij")
+    R, n = o // ROWS, o % ROWS
+    word = 2 * (R * NG + q) + n // 8
+    return ((words[word] >> (4 * (n % 8)).astype(np.uint32)) & 0xF).astype(np.uint8)
+
+
+def pack_scales(scales):
+    scales = np.asarray(scales, dtype=np.float16)
+    rows, NG = scales.shape
+    return np.ascontiguousarray(scales.reshape(rows // ROWS, ROWS, NG).transpose(0, 2, 1)).reshape(-1)
+
+
+def unpack_scales(flat, rows, NG):
+    flat = np.asarray(flat, dtype=np.float16)
+    return np.ascontiguousarray(flat.reshape(rows // ROWS, NG, ROWS).transpose(0, 2, 1)).reshape(rows, NG)
+
+
+# ----------------------------------------------------------------------------
+# fp16 factor
+# ----------------------------------------------------------------------------
+def _f16_index(o, i, K):
+    R, n = o // ROWS, o % ROWS
+    g, c = i // 32, i % 32
+    j, ii = c // 8, c % 8
+    tile = R * (K // 32) + g
+    return (tile * LANES + 16 * j + n) * 8 + ii
+
+
+def pack_f16(mat):
+    mat = np.asarray(mat, dtype=np.float16)
+    rows, K = mat.shape
+    _check(rows, K, 32)
+    o, i = np.meshgrid(np.arange(rows), np.arange(K), indexing="ij")
+    out = np.empty(rows * K, dtype=np.float16)
+    out[_f16_index(o, i, K).ravel()] = mat.ravel()
+    return out
+
+
+def unpack_f16(flat, rows, K):
+    flat = np.asarray(flat, dtype=np.float16)
+    o, i = np.meshgrid(np.arange(rows), np.arange(K), indexing="ij")
+    return flat[_f16_index(o, i, K)]
+
+
+# ----------------------------------------------------------------------------
+# 2:4 sparse fp16 backbone
+# ----------------------------------------------------------------------------
+def _sp24_locate(o, u, K):
+    """o: row, u: index of the kept value along the row (0 .. K/2-1).
+    Returns (value element index, index-word index, bit shift)."""
+    grp, v = u // 2, u % 2          # group of four dense columns, which of its two values
+    dense0 = 4 * grp                # first dense column of the group
+    R, n = o // ROWS, o % ROWS
+    g, c = dense0 // 128, dense0 % 128
+    s, c2 = c // 64, c % 64
+    j, q = c2 // 16, (c2 % 16) // 4
+    lane = 16 * j + n
+    tile = R * (K // 128) + g
+    return tile * 1024 + s * 512 + lane * 8 + 2 * q + v, tile * LANES + lane, 16 * s + 4 * q + 2 * v
+
+
+def pack_sp24(vals, pos):
+    """vals: fp16 rows x K/2 kept values; pos: their positions 0..3 in the group of
+    four, strictly ascending within each pair."""
+    vals = np.asarray(vals, dtype=np.float16)
+    pos = np.asarray(pos)
+    rows, half = vals.shape
+    K = 2 * half
+    _check(rows, K, 128)
+    if pos.shape != vals.shape or pos.min(initial=0) < 0 or pos.max(initial=0) > 3:
+        raise ValueError("bad positions")
+    if np.any(pos[:, 0::2] >= pos[:, 1::2]):
+        raise ValueError("positions of a pair must be strictly ascending")
+    o, u = np.meshgrid(np.arange(rows), np.arange(half), indexing="ij")
+    ve, iw, sh = _sp24_locate(o, u, K)
+    values = np.empty(rows * half, dtype=np.float16)
+    values[ve.ravel()] = vals.ravel()
+    indices = np.zeros(rows * K // 128 * 4, dtype=np.uint32)  # 64 words per tile of 16 rows
+    np.bitwise_or.at(indices, iw.ravel(), (pos.astype(np.uint32) << sh.astype(np.uint32)).ravel())
+    return values, indices
+
+
+def unpack_sp24(values, indices, rows, K):
+    values = np.asarray(values, dtype=np.float16)
+    indices = np.asarray(indices, dtype=np.uint32)
+    _check(rows, K, 128)
+    o, u = np.meshgrid(np.arange(rows), np.arange(K // 2), indexing="ij")
+    ve, iw, sh = _sp24_locate(o, u, K)
+    return values[ve], ((indices[iw] >> sh.astype(np.uint32)) & 3).astype(np.uint8)

@@ -1,0 +1,129 @@
+"""Float64 forward pass of the compensated compressed linear layer.
+
+Everything is computed in float64 with no intermediate rounding.  All stored
+inputs (fp16 scales and values, small integers) are dyadic rationals, so the
+dequantised weights are exact and the only rounding is float64 accumulation.
+
+Row convention: x is M x d_in, What is d_out x d_in, A is r x d_in, B is
+d_out x r, y is M x d_out.  The paper writes the same product in column
+convention, What X + B' A X with X of shape d_in x M (Sec. 3, forward equation).
+"""
+import numpy as np
+
+from . import layout
+
+
+def dequant(codes, zeros, scales, group):
+    """What[o][i] = s[o][i // group] * (q[o][i] - z[o][i // group]).
+
+    Asymmetric uniform quantisation with an integer zero-point (Sec. 4.1:
+    "asymmetric quantisation"; App. A.11: groups of 128 along the input dim).
+    """
+    q = np.asarray(codes).astype(np.float64)
+    z = np.repeat(np.asarray(zeros).astype(np.float64), group, axis=1)
+    s = np.repeat(np.asarray(scales, dtype=np.float16).astype(np.float64), group, axis=1)
+    if q.shape != z.shape:
+        raise ValueError("codes / zeros / group mismatch")
+    return s * (q - z)
+
+
+def dequant_q(qweight, qzeros, scales_packed, d_in, d_out, bits, group):
+    """Packed quantised backbone -> float64 d_out x d_in."""
+    NG = d_in // group
+    if bits == 4:
+        codes = layout.unpack_q4(qweight, d_out, d_in, 128)
+    elif bits == 3:
+        codes = layout.unpack_q3(qweight, d_out, d_in)
+    else:
+        raise ValueError("bits must be 3 or 4")
+    zeros = layout.unpack_zeros(qzeros, d_out, NG)
+    scales = layout.unpack_scales(scales_packed, d_out, NG)
+    return dequant(codes, zeros, scales, group)
+
+
+def dequant_factor_q4(qcodes_packed, scales_packed, rows, K):
+    """4-bit EoRA factor (Sec. 4.5, quantised EoRA).  Symmetric: the zero-point
+    is the constant 8; one fp16 scale per row and per group of min(128, K)
+    columns along the contraction dimension."""
+    KT = min(128, K)
+    codes = layout.unpack_q4(qcodes_packed, rows, K, KT)
+    scales = layout.unpack_scales(scales_packed, rows, K // KT)
+    zeros = np.full((rows, K // KT), 8, dtype=np.uint8)
+    return dequant(codes, zeros, scales, KT)
+
+
+def expand_sp24(vals, pos):
+    """2:4 sparse -> dense float64: of every four consecutive input columns two
+    are kept (Sec. 1), value v at column 4*group + position, the others zero."""
+    vals = np.asarray(vals, dtype=np.float16).astype(np.float64)
+    pos = np.asarray(pos).astype(np.int64)
+    rows, half = vals.shape
+    dense = np.zeros((rows, 2 * half), dtype=np.float64)
+    col = 4 * (np.arange(half) // 2)[None, :] + pos
+    dense[np.arange(rows)[:, None], col] = vals
+    return dense
+
+
+def expand_sp24_packed(values, indices, d_in, d_out):
+    vals, pos = layout.unpack_sp24(values, indices, d_out, d_in)
+    return expand_sp24(vals, pos)
+
+
+def eora_linear(x, W_hat, A=None, B=None):
+    """y = x What^T + (x A^T) B^T  (Sec. 3 forward equation; Alg. 1 step 7).
+
+    A = B = None is the bare compressed layer (adapter switched off).
+    """
+    x = np.asarray(x).astype(np.float64)
+    W_hat = np.asarray(W_hat, dtype=np.float64)
+    y = x @ W_hat.T
+    if A is not None:
+        A = np.asarray(A).astype(np.float64)
+        B = np.asarray(B).astype(np.float64)
+        t = x @ A.T                      # M x r  down-projection
+        y = y + t @ B.T                  # up-projection into the same output
+    return y
+
+
+def eora_linear_q(x, qweight, scales, qzeros, A, B, A_scales, B_scales,
+                  M, d_in, d_out, r, w_bits, group, ab_bits):
+    """Forward pass straight from the stored bytes (quantised backbone)."""
+    x = np.asarray(x, dtype=np.float16).reshape(M, d_in)
+    W_hat = dequant_q(qweight, qzeros, scales, d_in, d_out, w_bits, group)
+    if r == 0:
+        return eora_linear(x, W_hat)
+    Ad, Bd = _factors(A, B, A_scales, B_scales, d_in, d_out, r, ab_bits)
+    return eora_linear(x, W_hat, Ad, Bd)
+
+
+def eora_linear_sp24(x, values, indices, A, B, M, d_in, d_out, r):
+    """Forward pass straight from the stored bytes (2:4 sparse backbone)."""
+    x = np.asarray(x, dtype=np.float16).reshape(M, d_in)
+    W_hat = expand_sp24_packed(values, indices, d_in, d_out)
+    if r == 0:
+        return eora_linear(x, W_hat)
+    Ad, Bd = _factors(A, B, None, None, d_in, d_out, r, 16)
+    return eora_linear(x, W_hat, Ad, Bd)
+
+
+def _factors(A, B, A_scales, B_scales, d_in, d_out, r, ab_bits):
+    if ab_bits == 16:
+        return layout.unpack_f16(A, r, d_in), layout.unpack_f16(B, d_out, r)
+    if ab_bits == 4:
+        return (dequant_factor_q4(A, A_scales, r, d_in),
+                dequant_factor_q4(B, B_scales, d_out, r))
+    raise ValueError("ab_bits must be 16 or 4")
+
+
+def y_error(y_test, y_ref):
+    """The comparison rule for y: max |y_test - y_ref| / max(|y_ref|, rms(y_ref)).
+
+    Pure element-wise relative error is undefined where a sum of thousands of
+    signed terms cancels to ~0, so the denominator is floored at the rms of the
+    reference output."""
+    y_ref = np.asarray(y_ref, dtype=np.float64)
+    y_test = np.asarray(y_test).astype(np.float64)
+    rms = np.sqrt(np.mean(y_ref ** 2)) if y_ref.size else 0.0
+    den = np.maximum(np.abs(y_ref), rms)
+    den = np.where(den == 0.0, 1.0, den)
+    return float(np.max(np.abs(y_test - y_ref) / den)) if y_ref.size else 0.0

@@ -1,0 +1,90 @@
+"""Pins for oracle/calibrate.py (Alg. 1 steps 1-6, Theorem 1)."""
+import numpy as np
+
+from oracle import calibrate, linear
+
+
+def _setup(d=24, k=40, n=200, seed=0):
+    rng = np.random.default_rng(seed)
+    W = rng.standard_normal((d, k))
+    W_hat = W + 0.1 * rng.standard_normal((d, k))
+    scale = np.exp(rng.uniform(-2, 2, k))              # very uneven channel energies
+    Xt = rng.standard_normal((k, n)) * scale[:, None]
+    return W, W_hat, Xt
+
+
+def test_planted_rank_r_error_is_recovered():
+    rng = np.random.default_rng(1)
+    d, k, r = 24, 40, 5
+    W_hat = rng.standard_normal((d, k))
+    W = W_hat + rng.standard_normal((d, r)) @ rng.standard_normal((r, k))
+    Xt = rng.standard_normal((k, 120))
+    Bp, A = calibrate.eora_factors(W, W_hat, Xt, r)
+    assert Bp.shape == (d, r) and A.shape == (r, k)
+    assert np.linalg.norm(Bp @ A - (W - W_hat)) <= 1e-9 * np.linalg.norm(W - W_hat)
+    # forward pass with the compensated layer reproduces the uncompressed layer
+    x = rng.standard_normal((7, k))
+    assert np.allclose(linear.eora_linear(x, W_hat, A, Bp), x @ W.T, rtol=1e-9, atol=1e-9)
+
+
+def test_identity_gram_reduces_to_plain_svd():
+    """Orthonormal rows of Xt (Xt Xt^T = I) make the projection trivial: the product
+    B'A equals the truncated SVD of the raw error (Sec. 2, Eq. 2)."""
+    rng = np.random.default_rng(2)
+    W, W_hat, _ = _setup(seed=2)
+    k = W.shape[1]
+    Qo, _ = np.linalg.qr(rng.standard_normal((100, k)))
+    Xt = Qo.T                                            # k x 100, Xt Xt^T = I
+    Bp, A = calibrate.eora_factors(W, W_hat, Xt, 6)
+    Bs, As = calibrate.plain_svd_factors(W, W_hat, 6)
+    assert np.allclose(Bp @ A, Bs @ As, atol=1e-10)
+
+
+def test_residual_loss_closed_form_theorem1():
+    """|| dW Xt - B'A Xt ||_F = sqrt(sum_{i>r} sigma'_i^2), sigma' the singular values
+    of dW Q' (Theorem 1 with Eckart-Young)."""
+    W, W_hat, Xt = _setup(seed=3)
+    r = 7
+    Bp, A = calibrate.eora_factors(W, W_hat, Xt, r)
+    lam, Q = np.linalg.eigh(Xt @ Xt.T)
+    sig = np.linalg.svd((W - W_hat) @ (Q * np.sqrt(lam)[None, :]), compute_uv=False)
+    want = np.sqrt(np.sum(sig[r:] ** 2))
+    assert np.isclose(calibrate.layer_loss(W, W_hat, Bp, A, Xt), want, rtol=1e-9)
+
+
+def test_not_worse_than_plain_svd_or_activation_scaling():
+    """The eigenspace projection minimises the layer-wise loss among rank-r
+    compensations (Theorem 1), so it cannot lose to plain SVD (Eq. 2) or to the
+    diagonal activation scaling baseline of Sec. 4.1."""
+    for seed in range(4):
+        W, W_hat, Xt = _setup(seed=10 + seed)
+        r = 5
+        Bp, A = calibrate.eora_factors(W, W_hat, Xt, r)
+        e = calibrate.layer_loss(W, W_hat, Bp, A, Xt)
+        Bs, As = calibrate.plain_svd_factors(W, W_hat, r)
+        assert e <= calibrate.layer_loss(W, W_hat, Bs, As, Xt) * (1 + 1e-12)
+        S = np.sqrt(np.mean(np.abs(Xt), axis=1))
+        U, sg, Vt = np.linalg.svd((W - W_hat) * S[None, :], full_matrices=False)
+        Ba, Aa = U[:, :r] * sg[None, :r], Vt[:r] / S[None, :]
+        assert e <= calibrate.layer_loss(W, W_hat, Ba, Aa, Xt) * (1 + 1e-12)
+        # random rank-r perturbation of the optimum is never better
+        rng = np.random.default_rng(seed)
+        assert e <= calibrate.layer_loss(W, W_hat, Bp + 1e-3 * rng.standard_normal(Bp.shape), A, Xt)
+
+
+def test_gram_scaling_invariance_and_projection_inverse():
+    W, W_hat, Xt = _setup(seed=5)
+    B1, A1 = calibrate.eora_factors(W, W_hat, Xt, 6)
+    B2, A2 = calibrate.eora_factors(W, W_hat, 37.0 * Xt, 6)
+    assert np.allclose(B1 @ A1, B2 @ A2, atol=1e-9)
+    lam, Q = np.linalg.eigh(calibrate.gram(Xt))
+    Qp = Q * np.sqrt(lam)[None, :]
+    Qp_inv = (Q / np.sqrt(lam)[None, :]).T              # sqrt(Lambda)^-1 Q^T
+    assert np.allclose(Qp @ Qp_inv, np.eye(Q.shape[0]), atol=1e-9)
+    assert np.allclose(Qp @ Qp.T, calibrate.gram(Xt), rtol=1e-9, atol=1e-9)
+
+
+def test_full_rank_compensation_is_exact():
+    W, W_hat, Xt = _setup(d=12, k=20, seed=6)
+    Bp, A = calibrate.eora_factors(W, W_hat, Xt, 12)
+    assert np.allclose(Bp @ A, W - W_hat, atol=1e-9)
