@@ -32,8 +32,8 @@ def test_factor_bytes_match_paper_size_deltas():
         if r == 0:
             continue
         delta = size - rows[(bb, 0, 0)]
-        ours = _factor_bytes(r, bits) / 1e9
-        assert abs(ours - delta) <= 0.05 + 0.05 * delta, (bb, r, bits, ours, delta)
+        ours = _factor_bytes(r, bits) / 2 ** 30       # the table's unit fits GiB: rank 512 fp16 is 2.50 exactly
+        assert abs(ours - delta) <= 0.03 + 0.03 * delta, (bb, r, bits, ours, delta)
 
 
 def test_packed_arrays_have_no_padding():
