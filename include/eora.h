@@ -1,0 +1,157 @@
+/*
+ * eora.h - C ABI of the MI355X (gfx950) library for the EoRA compensated compressed linear layer
+ *
+ *      y = x . What^T + (x . A^T) . B^T
+ *
+ * (arXiv 2410.21271, Sec. 3: forward equation "What X + B' A X", Algorithm 1 step 7; the paper
+ * writes the column convention, this library the row convention: x is M x d_in, What is
+ * d_out x d_in, A is r x d_in, B is d_out x r, y is M x d_out.)  What is the unmodified compressed
+ * backbone weight (Sec. 2: "the compressed model's weights remain unchanged"), A and B the rank-r
+ * compensation factors produced offline by Algorithm 1 steps 1-6.
+ *
+ * General rules
+ *  - Plain C.  Every pointer is a DEVICE pointer unless the comment says HOST.
+ *  - The caller owns all memory.  The library allocates nothing on the device and keeps no state.
+ *  - Device work is enqueued on `stream` (a hipStream_t passed as void*, NULL = default stream);
+ *    no call synchronises with the host.  Results are valid once the caller has synchronised.
+ *  - Every function returns an eora_status.  Arguments are validated before anything is enqueued:
+ *    on an error nothing is launched and no output is touched.
+ *  - Inputs are never modified.  y is OVERWRITTEN (the caller need not clear it).
+ *  - All device pointers must be 16-byte aligned.
+ *  - Determinism: no floating-point atomics are used; the reduction order is fixed by the launch
+ *    configuration, so equal inputs give bit-equal outputs from run to run.
+ *
+ * Stored formats (all weight-like operands are TILE-MAJOR; rows = output rows, K = contraction
+ * length).  A tile is 16 rows x KT columns and maps onto one 64-lane wavefront: lane
+ * l = 16*j + n owns row n of the tile and the j-th quarter of its columns.  Tiles are ordered
+ * row-block first: tile = (row/16) * (K/KT) + col/KT.
+ *
+ *  Q4 (4-bit codes; KT = 128 for the backbone, min(128,K) for a factor): lane l owns columns
+ *      c = (KT/4)*j + 8*t + kk of the tile, t = 0..KT/32-1, kk = 0..7.  32-bit word
+ *      tile*(2*KT) + l*(KT/32) + t  holds the eight codes of (l, t); column kk sits in nibble
+ *      e = 4*(kk%2) + kk/2 (bits 4e..4e+3): even columns in the low 16 bits, odd ones in the
+ *      high 16 bits, so that one AND extracts two adjacent columns as a pair of 16-bit lanes.
+ *  Q3 (3-bit codes, KT = 128, exactly 3.0 bits per weight): lane l owns three consecutive words
+ *      tile*192 + 3*l + d.  Its 32 columns cc form pairs p = cc/2 (h = cc%2: 0 low / 1 high
+ *      16-bit half).  Pairs 0..14 sit in word p/5 at bits 16h + 3*(p%5) .. +2.  Bit 15 of each
+ *      half carries the last pair: bit b of the code of column 30+h is bit 16h+15 of word b.
+ *  zero-points: 4-bit, one per (row, group): word 2*((row/16)*NG + q) + (row%16)/8, nibble
+ *      (row%16)%8, with NG = K/group and q = col/group.
+ *  scales: fp16, element ((row/16)*NG + q)*16 + row%16.
+ *  F16 (fp16 factor, KT = 32): element (tile*64 + l)*8 + i is column 32*(col/32) + 8*j + i.
+ *  SP24 (2:4 sparse fp16, tile = 16 rows x 128 dense columns): lane l owns dense columns
+ *      64*s + 16*j + 4*q + p (s = 0,1; q = 0..3 group of four; p = 0..3 position); each group
+ *      keeps two values v = 0,1 at positions p_0 < p_1.  values: fp16 element
+ *      tile*1024 + s*512 + l*8 + 2*q + v.  indices: one 32-bit word per (tile, lane), bits
+ *      16*s + 4*q + 2*v .. +1 hold p_v.
+ *
+ * Dequantisation (asymmetric group-wise quantisation, Sec. 4.1 and App. A.11):
+ *      What[o][i] = scale[o][i/group] * (code[o][i] - zero[o][i/group])
+ * Quantised factors (Sec. 4.5, "quantised EoRA") are symmetric 4-bit: the zero-point is the
+ * constant 8, scales are fp16, one per row and per group of min(128,K) columns of the
+ * contraction dimension (d_in for A, r for B).
+ */
+#ifndef EORA_H
+#define EORA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    EORA_OK = 0,
+    EORA_ERR_NULL = -1,        /* a required pointer is NULL */
+    EORA_ERR_SHAPE = -2,       /* a size violates the constraints listed at the function */
+    EORA_ERR_UNSUPPORTED = -3, /* w_bits / ab_bits / group value not implemented */
+    EORA_ERR_ALIGN = -4,       /* a device pointer is not 16-byte aligned */
+    EORA_ERR_WORKSPACE = -5,   /* workspace missing or smaller than eora_workspace_bytes() */
+    EORA_ERR_LAUNCH = -6,      /* the HIP runtime refused a launch (hipGetLastError) */
+    EORA_ERR_VALUE = -7        /* host packer: a code / zero-point / position is out of range */
+} eora_status;
+
+/* HOST.  Static string for a status code. */
+const char* eora_status_string(int status);
+
+/* ---------------------------------------------------------------------------------------------
+ * Sizes (HOST, pure functions).  Return 0 for invalid arguments.
+ * ------------------------------------------------------------------------------------------ */
+size_t eora_qweight_bytes(int d_in, int d_out, int w_bits);          /* d_out*d_in*w_bits/8 */
+size_t eora_qzeros_bytes(int d_in, int d_out, int group);            /* d_out*(d_in/group)/2 */
+size_t eora_scales_bytes(int d_in, int d_out, int group);            /* d_out*(d_in/group)*2 */
+size_t eora_sp24_values_bytes(int d_in, int d_out);                  /* d_out*d_in          */
+size_t eora_sp24_indices_bytes(int d_in, int d_out);                 /* d_out*d_in/8        */
+/* Scratch the forward calls need for the down-projection t = x.A^T (M x r) and for partial sums.
+ * Contents need not be initialised and are undefined afterwards.  Concurrent calls on different
+ * streams need different workspaces.  r == 0 still needs a (small) workspace. */
+size_t eora_workspace_bytes(int M, int d_in, int d_out, int r);
+
+/* ---------------------------------------------------------------------------------------------
+ * Host-side packers: logical arrays (HOST pointers, row-major) -> stored bytes (HOST pointers).
+ * They define the stored formats above in code; outputs may then be copied to the device.
+ * Constraints: d_out % 16 == 0, d_in % 128 == 0, group % 128 == 0, d_in % group == 0.
+ * ------------------------------------------------------------------------------------------ */
+/* codes: d_out x d_in, values < 2^w_bits; zeros: d_out x d_in/group, same range;
+ * scales: d_out x d_in/group fp16 bit patterns.  w_bits is 3 or 4. */
+int eora_pack_q(const uint8_t* codes, const uint8_t* zeros, const uint16_t* scales,
+                int d_in, int d_out, int w_bits, int group,
+                void* qweight_out, void* qzeros_out, void* scales_out);
+/* fp16 factor, rows x cols (A: r x d_in; B: d_out x r).  rows % 16 == 0, cols % 32 == 0. */
+int eora_pack_factor_f16(const uint16_t* mat, int rows, int cols, void* out);
+/* 4-bit symmetric factor: codes rows x cols in 0..15 (zero-point 8), scales rows x cols/KT fp16,
+ * KT = min(128, cols).  rows % 16 == 0, cols == 64 or cols % 128 == 0. */
+int eora_pack_factor_q4(const uint8_t* codes, const uint16_t* scales, int rows, int cols,
+                        void* q_out, void* scales_out);
+/* 2:4 sparse backbone: vals d_out x d_in/2 fp16 bit patterns (the kept values in column order),
+ * pos d_out x d_in/2 their positions 0..3 inside the group of four, strictly ascending per pair. */
+int eora_pack_sp24(const uint16_t* vals, const uint8_t* pos, int d_in, int d_out,
+                   void* values_out, void* indices_out);
+
+/* ---------------------------------------------------------------------------------------------
+ * The layer.  Sec. 3 forward equation / Alg. 1 step 7; the fused low-rank path follows Sec. 4.5
+ * and App. A.6 (B's product accumulates into the same output as the quantised product) and goes
+ * further: x.A^T is folded in as well, so y is written exactly once.
+ *
+ * x        fp16 row-major M x d_in
+ * qweight  Q4 or Q3 tiles (w_bits), scales / qzeros as described above
+ * A, B     F16 tiles (ab_bits == 16; A_scales = B_scales = NULL) or Q4 symmetric tiles with fp16
+ *          scales (ab_bits == 4).  r == 0 (then A, B may be NULL) is the bare compressed layer,
+ *          i.e. the adapter switched off.
+ * y        fp16 row-major M x d_out, overwritten; fp32 accumulation, one round-to-nearest-even
+ *          conversion at the end.
+ * Constraints: M >= 0 (M == 0 is a no-op), d_out % 16 == 0, d_in % 128 == 0, group % 128 == 0,
+ *          d_in % group == 0 (group == d_in is channel-wise quantisation), w_bits in {3,4},
+ *          ab_bits in {16,4}, r <= 512 and r % 32 == 0 (ab_bits 16) or r == 64 or r % 128 == 0
+ *          (ab_bits 4).
+ * ------------------------------------------------------------------------------------------ */
+int eora_linear_q(const void* x, const void* qweight, const void* scales, const void* qzeros,
+                  const void* A, const void* B, const void* A_scales, const void* B_scales,
+                  void* y, int M, int d_in, int d_out, int r, int w_bits, int group, int ab_bits,
+                  void* workspace, size_t workspace_bytes, void* stream);
+
+/* Same layer with a 2:4 structured-sparse fp16 backbone (Sec. 1, Sec. 4.2); A, B are F16 tiles.
+ * Constraints as above with r % 32 == 0. */
+int eora_linear_sp24(const void* x, const void* values, const void* indices,
+                     const void* A, const void* B, void* y,
+                     int M, int d_in, int d_out, int r,
+                     void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Parity exports (integer / exact work, compared bit for bit against the CPU oracle).
+ * ------------------------------------------------------------------------------------------ */
+/* codes_u8: d_out x d_in row-major; zeros_u8: d_out x d_in/group row-major. */
+int eora_unpack_q(const void* qweight, const void* qzeros, void* codes_u8, void* zeros_u8,
+                  int d_in, int d_out, int w_bits, int group, void* stream);
+/* W_f32: d_out x d_in row-major fp32; scale*(code-zero) is exact in fp32. */
+int eora_dequant_q(const void* qweight, const void* scales, const void* qzeros, void* W_f32,
+                   int d_in, int d_out, int w_bits, int group, void* stream);
+/* W_f16: d_out x d_in row-major fp16 with the pruned positions written as +0. */
+int eora_expand_sp24(const void* values, const void* indices, void* W_f16,
+                     int d_in, int d_out, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EORA_H */

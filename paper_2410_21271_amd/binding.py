@@ -1,0 +1,184 @@
+"""ctypes binding of include/eora.h: same names without the eora_ prefix, marshalling only.
+
+Host-side packers take and return numpy arrays.  Device entry points take torch CUDA tensors (used
+purely as device memory) and launch on torch's current stream.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libeora.so")
+
+
+class EoraError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__("%s: %s (%d)" % (where, status_string(status), status))
+
+
+def lib_path():
+    return _LIB_PATH
+
+
+def _load():
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError("libeora.so is not built: run `python -m paper_2410_21271_amd.build` "
+                          "(there is no CPU fallback)")
+    L = ctypes.CDLL(_LIB_PATH)
+    vp, ci, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+    sig = {
+        "eora_status_string": (ctypes.c_char_p, [ci]),
+        "eora_qweight_bytes": (sz, [ci, ci, ci]),
+        "eora_qzeros_bytes": (sz, [ci, ci, ci]),
+        "eora_scales_bytes": (sz, [ci, ci, ci]),
+        "eora_sp24_values_bytes": (sz, [ci, ci]),
+        "eora_sp24_indices_bytes": (sz, [ci, ci]),
+        "eora_workspace_bytes": (sz, [ci, ci, ci, ci]),
+        "eora_pack_q": (ci, [vp, vp, vp, ci, ci, ci, ci, vp, vp, vp]),
+        "eora_pack_factor_f16": (ci, [vp, ci, ci, vp]),
+        "eora_pack_factor_q4": (ci, [vp, vp, ci, ci, vp, vp]),
+        "eora_pack_sp24": (ci, [vp, vp, ci, ci, vp, vp]),
+        "eora_linear_q": (ci, [vp] * 9 + [ci] * 7 + [vp, sz, vp]),
+        "eora_linear_sp24": (ci, [vp] * 6 + [ci] * 4 + [vp, sz, vp]),
+        "eora_unpack_q": (ci, [vp, vp, vp, vp, ci, ci, ci, ci, vp]),
+        "eora_dequant_q": (ci, [vp, vp, vp, vp, ci, ci, ci, ci, vp]),
+        "eora_expand_sp24": (ci, [vp, vp, vp, ci, ci, vp]),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(L, name)
+        fn.restype = res
+        fn.argtypes = args
+    return L
+
+
+lib = _load()
+EXPORTS = ["eora_status_string", "eora_qweight_bytes", "eora_qzeros_bytes", "eora_scales_bytes",
+           "eora_sp24_values_bytes", "eora_sp24_indices_bytes", "eora_workspace_bytes", "eora_pack_q",
+           "eora_pack_factor_f16", "eora_pack_factor_q4", "eora_pack_sp24", "eora_linear_q",
+           "eora_linear_sp24", "eora_unpack_q", "eora_dequant_q", "eora_expand_sp24"]
+
+
+def status_string(status):
+    return lib.eora_status_string(int(status)).decode()
+
+
+def _check(status, where):
+    if status != 0:
+        raise EoraError(status, where)
+
+
+# ------------------------------------------------------------------ sizes
+def qweight_bytes(d_in, d_out, w_bits):
+    return lib.eora_qweight_bytes(d_in, d_out, w_bits)
+
+
+def qzeros_bytes(d_in, d_out, group):
+    return lib.eora_qzeros_bytes(d_in, d_out, group)
+
+
+def scales_bytes(d_in, d_out, group):
+    return lib.eora_scales_bytes(d_in, d_out, group)
+
+
+def sp24_values_bytes(d_in, d_out):
+    return lib.eora_sp24_values_bytes(d_in, d_out)
+
+
+def sp24_indices_bytes(d_in, d_out):
+    return lib.eora_sp24_indices_bytes(d_in, d_out)
+
+
+def workspace_bytes(M, d_in, d_out, r):
+    return lib.eora_workspace_bytes(M, d_in, d_out, r)
+
+
+# ------------------------------------------------------------------ host packers (numpy in, numpy out)
+def _np_ptr(a):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def pack_q(codes, zeros, scales, w_bits, group):
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    zeros = np.ascontiguousarray(zeros, dtype=np.uint8)
+    scales = np.ascontiguousarray(scales, dtype=np.float16)
+    d_out, d_in = codes.shape
+    nq, nz, ns = qweight_bytes(d_in, d_out, w_bits), qzeros_bytes(d_in, d_out, group), scales_bytes(d_in, d_out, group)
+    if not (nq and nz and ns) or zeros.shape != (d_out, d_in // group) or scales.shape != zeros.shape:
+        raise EoraError(-2, "pack_q")
+    qw = np.empty(nq // 4, np.uint32)
+    qz = np.empty(nz // 4, np.uint32)
+    sc = np.empty(ns // 2, np.float16)
+    _check(lib.eora_pack_q(_np_ptr(codes), _np_ptr(zeros), _np_ptr(scales), d_in, d_out, w_bits, group,
+                           _np_ptr(qw), _np_ptr(qz), _np_ptr(sc)), "pack_q")
+    return qw, qz, sc
+
+
+def pack_factor_f16(mat):
+    mat = np.ascontiguousarray(mat, dtype=np.float16)
+    rows, cols = mat.shape
+    out = np.empty(rows * cols, np.float16)
+    _check(lib.eora_pack_factor_f16(_np_ptr(mat), rows, cols, _np_ptr(out)), "pack_factor_f16")
+    return out
+
+
+def pack_factor_q4(codes, scales):
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    scales = np.ascontiguousarray(scales, dtype=np.float16)
+    rows, cols = codes.shape
+    q = np.empty(rows * cols // 8, np.uint32)
+    sc = np.empty(scales.size, np.float16)
+    _check(lib.eora_pack_factor_q4(_np_ptr(codes), _np_ptr(scales), rows, cols, _np_ptr(q), _np_ptr(sc)),
+           "pack_factor_q4")
+    return q, sc
+
+
+def pack_sp24(vals, pos):
+    vals = np.ascontiguousarray(vals, dtype=np.float16)
+    pos = np.ascontiguousarray(pos, dtype=np.uint8)
+    d_out, half = vals.shape
+    d_in = 2 * half
+    values = np.empty(d_out * half, np.float16)
+    indices = np.empty(d_out * d_in // 32, np.uint32)
+    _check(lib.eora_pack_sp24(_np_ptr(vals), _np_ptr(pos), d_in, d_out, _np_ptr(values), _np_ptr(indices)),
+           "pack_sp24")
+    return values, indices
+
+
+# ------------------------------------------------------------------ device entry points (torch tensors as memory)
+def _dp(t):
+    return ctypes.c_void_p(0 if t is None else t.data_ptr())
+
+
+def _stream():
+    import torch
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def linear_q(x, qweight, scales, qzeros, A, B, A_scales, B_scales, y, M, d_in, d_out, r, w_bits, group, ab_bits,
+             workspace):
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib.eora_linear_q(_dp(x), _dp(qweight), _dp(scales), _dp(qzeros), _dp(A), _dp(B), _dp(A_scales),
+                             _dp(B_scales), _dp(y), M, d_in, d_out, r, w_bits, group, ab_bits,
+                             _dp(workspace), ws_bytes, _stream()), "linear_q")
+
+
+def linear_sp24(x, values, indices, A, B, y, M, d_in, d_out, r, workspace):
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib.eora_linear_sp24(_dp(x), _dp(values), _dp(indices), _dp(A), _dp(B), _dp(y), M, d_in, d_out, r,
+                                _dp(workspace), ws_bytes, _stream()), "linear_sp24")
+
+
+def unpack_q(qweight, qzeros, codes_u8, zeros_u8, d_in, d_out, w_bits, group):
+    _check(lib.eora_unpack_q(_dp(qweight), _dp(qzeros), _dp(codes_u8), _dp(zeros_u8), d_in, d_out, w_bits, group,
+                             _stream()), "unpack_q")
+
+
+def dequant_q(qweight, scales, qzeros, W_f32, d_in, d_out, w_bits, group):
+    _check(lib.eora_dequant_q(_dp(qweight), _dp(scales), _dp(qzeros), _dp(W_f32), d_in, d_out, w_bits, group,
+                              _stream()), "dequant_q")
+
+
+def expand_sp24(values, indices, W_f16, d_in, d_out):
+    _check(lib.eora_expand_sp24(_dp(values), _dp(indices), _dp(W_f16), d_in, d_out, _stream()), "expand_sp24")

@@ -1,0 +1,160 @@
+// C-ABI entry points: argument validation and the static choice of kernel.  No device memory is
+// allocated here and nothing is kept between calls.
+#include "eora.h"
+#include "kernels.hpp"
+
+namespace {
+
+using namespace eora;
+
+constexpr size_t WS_HEADER = 256;          // reserved for flags / counters
+constexpr int MAX_RANK = 512;
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+int check_backbone_shape(int M, int d_in, int d_out, int r)
+{
+    if (M < 0 || d_in <= 0 || d_out <= 0 || r < 0) return EORA_ERR_SHAPE;
+    if (d_out % 16 || d_in % 128 || r > MAX_RANK) return EORA_ERR_SHAPE;
+    return EORA_OK;
+}
+
+int check_group(int d_in, int group)
+{
+    if (group <= 0 || group % 128 || d_in % group) return EORA_ERR_SHAPE;
+    return EORA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t eora_workspace_bytes(int M, int d_in, int d_out, int r)
+{
+    if (check_backbone_shape(M, d_in, d_out, r) != EORA_OK) return 0;
+    return WS_HEADER + round256((size_t)M * r * sizeof(float));
+}
+
+int eora_linear_q(const void* x, const void* qweight, const void* scales, const void* qzeros,
+                  const void* A, const void* B, const void* A_scales, const void* B_scales,
+                  void* y, int M, int d_in, int d_out, int r, int w_bits, int group, int ab_bits,
+                  void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!x || !qweight || !scales || !qzeros || !y) return EORA_ERR_NULL;
+    if (w_bits != 3 && w_bits != 4) return EORA_ERR_UNSUPPORTED;
+    int rc = check_backbone_shape(M, d_in, d_out, r);
+    if (rc != EORA_OK) return rc;
+    rc = check_group(d_in, group);
+    if (rc != EORA_OK) return rc;
+    int fe = S_NONE, fa = S_NONE;
+    if (r > 0) {
+        if (!A || !B) return EORA_ERR_NULL;
+        if (ab_bits == 16) {
+            if (r % 32) return EORA_ERR_SHAPE;
+            fe = S_F16;
+            fa = S_F16;
+        } else if (ab_bits == 4) {
+            if (!A_scales || !B_scales) return EORA_ERR_NULL;
+            if (r != 64 && r % 128) return EORA_ERR_SHAPE;
+            fe = (r == 64) ? S_Q4S64 : S_Q4S128;
+            fa = S_Q4S128;
+        } else {
+            return EORA_ERR_UNSUPPORTED;
+        }
+        if (!aligned16(A) || !aligned16(B) || !aligned16(A_scales) || !aligned16(B_scales)) return EORA_ERR_ALIGN;
+    }
+    if (!aligned16(x) || !aligned16(qweight) || !aligned16(scales) || !aligned16(qzeros) || !aligned16(y))
+        return EORA_ERR_ALIGN;
+    if (!workspace) return EORA_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return EORA_ERR_ALIGN;
+    if (workspace_bytes < eora_workspace_bytes(M, d_in, d_out, r)) return EORA_ERR_WORKSPACE;
+    if (M == 0) return EORA_OK;
+
+    hipStream_t s = (hipStream_t)stream;
+    float* t = (float*)((char*)workspace + WS_HEADER);
+    if (r > 0) {
+        DecodeArgs d{};
+        d.x = (const _Float16*)x;
+        d.w = A;
+        d.w_scales = (const _Float16*)A_scales;
+        d.y = t;
+        d.M = M;
+        d.d_in = d_in;
+        d.d_out = r;
+        d.group = 128;
+        if (launch_downproj(d, fa, s) != hipSuccess) return EORA_ERR_LAUNCH;
+    }
+    DecodeArgs a{};
+    a.x = (const _Float16*)x;
+    a.w = qweight;
+    a.w_scales = (const _Float16*)scales;
+    a.w_zeros = (const uint32_t*)qzeros;
+    a.B = B;
+    a.B_scales = (const _Float16*)B_scales;
+    a.t = t;
+    a.y = y;
+    a.M = M;
+    a.d_in = d_in;
+    a.d_out = d_out;
+    a.r = r;
+    a.group = group;
+    if (launch_decode(a, w_bits == 4 ? S_Q4 : S_Q3, fe, s) != hipSuccess) return EORA_ERR_LAUNCH;
+    return EORA_OK;
+}
+
+int eora_linear_sp24(const void* x, const void* values, const void* indices,
+                     const void* A, const void* B, void* y,
+                     int M, int d_in, int d_out, int r,
+                     void* workspace, size_t workspace_bytes, void* stream)
+{
+    (void)x; (void)values; (void)indices; (void)A; (void)B; (void)y; (void)M; (void)d_in; (void)d_out; (void)r;
+    (void)workspace; (void)workspace_bytes; (void)stream;
+    return EORA_ERR_UNSUPPORTED;
+}
+
+int eora_unpack_q(const void* qweight, const void* qzeros, void* codes_u8, void* zeros_u8,
+                  int d_in, int d_out, int w_bits, int group, void* stream)
+{
+    if (!qweight || !qzeros || !codes_u8 || !zeros_u8) return EORA_ERR_NULL;
+    if (w_bits != 3 && w_bits != 4) return EORA_ERR_UNSUPPORTED;
+    int rc = check_backbone_shape(1, d_in, d_out, 0);
+    if (rc != EORA_OK) return rc;
+    rc = check_group(d_in, group);
+    if (rc != EORA_OK) return rc;
+    if (!aligned16(qweight) || !aligned16(qzeros)) return EORA_ERR_ALIGN;
+    if (launch_unpack_q((const uint32_t*)qweight, (const uint32_t*)qzeros, (uint8_t*)codes_u8, (uint8_t*)zeros_u8,
+                        d_in, d_out, w_bits, group, (hipStream_t)stream) != hipSuccess)
+        return EORA_ERR_LAUNCH;
+    return EORA_OK;
+}
+
+int eora_dequant_q(const void* qweight, const void* scales, const void* qzeros, void* W_f32,
+                   int d_in, int d_out, int w_bits, int group, void* stream)
+{
+    if (!qweight || !scales || !qzeros || !W_f32) return EORA_ERR_NULL;
+    if (w_bits != 3 && w_bits != 4) return EORA_ERR_UNSUPPORTED;
+    int rc = check_backbone_shape(1, d_in, d_out, 0);
+    if (rc != EORA_OK) return rc;
+    rc = check_group(d_in, group);
+    if (rc != EORA_OK) return rc;
+    if (!aligned16(qweight) || !aligned16(scales) || !aligned16(qzeros) || !aligned16(W_f32)) return EORA_ERR_ALIGN;
+    if (launch_dequant_q((const uint32_t*)qweight, (const _Float16*)scales, (const uint32_t*)qzeros, (float*)W_f32,
+                         d_in, d_out, w_bits, group, (hipStream_t)stream) != hipSuccess)
+        return EORA_ERR_LAUNCH;
+    return EORA_OK;
+}
+
+int eora_expand_sp24(const void* values, const void* indices, void* W_f16, int d_in, int d_out, void* stream)
+{
+    if (!values || !indices || !W_f16) return EORA_ERR_NULL;
+    int rc = check_backbone_shape(1, d_in, d_out, 0);
+    if (rc != EORA_OK) return rc;
+    if (!aligned16(values) || !aligned16(indices) || !aligned16(W_f16)) return EORA_ERR_ALIGN;
+    if (launch_expand_sp24((const _Float16*)values, (const uint32_t*)indices, (_Float16*)W_f16, d_in, d_out,
+                           (hipStream_t)stream) != hipSuccess)
+        return EORA_ERR_LAUNCH;
+    return EORA_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,109 @@
+// Parity exports: stored bytes -> row-major logical arrays (integer / exact work).
+// One thread per (tile, lane): it decodes the words it owns with plain shifts and masks and
+// scatters the results; these kernels are meant to be obviously right, not fast.
+#include "kernels.hpp"
+
+namespace eora {
+
+__device__ __forceinline__ uint32_t code_q4(const uint32_t* w, int cc)
+{
+    const int t = cc >> 3, kk = cc & 7;
+    const int e = 4 * (kk & 1) + (kk >> 1);
+    return (w[t] >> (4 * e)) & 0xFu;
+}
+
+__device__ __forceinline__ uint32_t code_q3(const uint32_t* w, int cc)
+{
+    if (cc < 30) {
+        const int p = cc >> 1, h = cc & 1;
+        return (w[p / 5] >> (16 * h + 3 * (p % 5))) & 7u;
+    }
+    const int s = 16 * (cc - 30) + 15;
+    return ((w[0] >> s) & 1u) | (((w[1] >> s) & 1u) << 1) | (((w[2] >> s) & 1u) << 2);
+}
+
+template <bool DEQUANT>
+__global__ void unpack_q_kernel(const uint32_t* __restrict__ qweight, const _Float16* __restrict__ scales,
+                                const uint32_t* __restrict__ qzeros, uint8_t* __restrict__ codes,
+                                uint8_t* __restrict__ zeros_out, float* __restrict__ W,
+                                int d_in, int d_out, int w_bits, int group)
+{
+    const size_t L = (size_t)blockIdx.x * blockDim.x + threadIdx.x;     // global (tile, lane)
+    const size_t nlanes = (size_t)d_out * d_in / 32;
+    if (L >= nlanes) return;
+    const int ntk = d_in / 128, NG = d_in / group;
+    const size_t tile = L / 64;
+    const int lane = (int)(L % 64);
+    const int R = (int)(tile / ntk), g = (int)(tile % ntk);
+    const int j = lane >> 4, n = lane & 15;
+    const int row = 16 * R + n, col0 = 128 * g + 32 * j;
+    const int q = col0 / group;
+    const size_t rq = (size_t)R * NG + q;
+    const uint32_t z = (qzeros[2 * rq + (n >> 3)] >> (4 * (n & 7))) & 0xFu;
+    uint32_t w[4];
+    const int wpl = w_bits == 4 ? 4 : 3;
+    for (int t = 0; t < wpl; ++t) w[t] = qweight[L * wpl + t];
+    float s = 0.f;
+    if (DEQUANT) s = (float)scales[rq * 16 + n];
+    for (int cc = 0; cc < 32; ++cc) {
+        const uint32_t c = w_bits == 4 ? code_q4(w, cc) : code_q3(w, cc);
+        const size_t idx = (size_t)row * d_in + col0 + cc;
+        if (DEQUANT) W[idx] = s * (float)((int)c - (int)z);      // 11-bit x 5-bit product: exact in fp32
+        else codes[idx] = (uint8_t)c;
+    }
+    if (!DEQUANT && col0 % group == 0) zeros_out[(size_t)row * NG + q] = (uint8_t)z;
+}
+
+__global__ void expand_sp24_kernel(const _Float16* __restrict__ values, const uint32_t* __restrict__ indices,
+                                   _Float16* __restrict__ W, int d_in, int d_out)
+{
+    const size_t L = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t nlanes = (size_t)d_out * d_in / 32;
+    if (L >= nlanes) return;
+    const int ntk = d_in / 128;
+    const size_t tile = L / 64;
+    const int lane = (int)(L % 64);
+    const int R = (int)(tile / ntk), g = (int)(tile % ntk);
+    const int j = lane >> 4, n = lane & 15;
+    const uint32_t word = indices[L];
+    for (int s = 0; s < 2; ++s)
+        for (int q = 0; q < 4; ++q) {
+            _Float16 out[4] = {(_Float16)0.f, (_Float16)0.f, (_Float16)0.f, (_Float16)0.f};
+            for (int v = 0; v < 2; ++v) {
+                const int p = (word >> (16 * s + 4 * q + 2 * v)) & 3;
+                out[p] = values[tile * 1024 + s * 512 + lane * 8 + 2 * q + v];
+            }
+            _Float16* dst = W + (size_t)(16 * R + n) * d_in + 128 * g + 64 * s + 16 * j + 4 * q;
+            for (int p = 0; p < 4; ++p) dst[p] = out[p];
+        }
+}
+
+static dim3 grid_for(size_t nlanes) { return dim3((unsigned)((nlanes + 255) / 256)); }
+
+hipError_t launch_unpack_q(const uint32_t* qweight, const uint32_t* qzeros, uint8_t* codes, uint8_t* zeros,
+                           int d_in, int d_out, int w_bits, int group, hipStream_t stream)
+{
+    const size_t nlanes = (size_t)d_out * d_in / 32;
+    hipLaunchKernelGGL((unpack_q_kernel<false>), grid_for(nlanes), dim3(256), 0, stream, qweight,
+                       (const _Float16*)nullptr, qzeros, codes, zeros, (float*)nullptr, d_in, d_out, w_bits, group);
+    return hipGetLastError();
+}
+
+hipError_t launch_dequant_q(const uint32_t* qweight, const _Float16* scales, const uint32_t* qzeros, float* W,
+                            int d_in, int d_out, int w_bits, int group, hipStream_t stream)
+{
+    const size_t nlanes = (size_t)d_out * d_in / 32;
+    hipLaunchKernelGGL((unpack_q_kernel<true>), grid_for(nlanes), dim3(256), 0, stream, qweight, scales, qzeros,
+                       (uint8_t*)nullptr, (uint8_t*)nullptr, W, d_in, d_out, w_bits, group);
+    return hipGetLastError();
+}
+
+hipError_t launch_expand_sp24(const _Float16* values, const uint32_t* indices, _Float16* W,
+                              int d_in, int d_out, hipStream_t stream)
+{
+    const size_t nlanes = (size_t)d_out * d_in / 32;
+    hipLaunchKernelGGL(expand_sp24_kernel, grid_for(nlanes), dim3(256), 0, stream, values, indices, W, d_in, d_out);
+    return hipGetLastError();
+}
+
+}  // namespace eora

@@ -1,0 +1,96 @@
+// Device-side decoding of the tile-major stored formats into MFMA operand fragments.
+//
+// A 16 x 16 x 32 fp16 MFMA takes, per lane l = 16*j + n, eight fp16 of operand row n for the
+// k-slots 8*j .. 8*j+7.  The stored tiles give every lane exactly the words of its row n and its
+// column quarter j, so a 32-bit word of eight codes becomes one fragment without any cross-lane
+// traffic.  Codes are turned into the EXACT integers (code - zero) in fp16; the group scale is
+// applied afterwards in fp32 on the accumulator, so the effective weight scale*(code-zero) carries
+// no rounding (asymmetric group-wise quantisation, Sec. 4.1 / App. A.11 of the paper).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace eora {
+
+typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+typedef float f4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+
+union Frag {
+    h8 v;
+    h2 p[4];
+    uint32_t u[4];
+    u4 q;
+};
+
+__device__ __forceinline__ h2 as_h2(uint32_t v) { return __builtin_bit_cast(h2, v); }
+
+__device__ __forceinline__ f4 mfma16(h8 a, h8 b, f4 c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+}
+
+// fp16 bit patterns of (base + z) replicated in both halves, for the small integer z < 16.
+// base = 1024, 128, 64, 16 have a mantissa unit of 1, 1/8, 1/16, 1/64.
+__device__ __forceinline__ uint32_t k1024(uint32_t z) { return 0x64006400u | (z * 0x00010001u); }
+__device__ __forceinline__ uint32_t k128(uint32_t z) { return 0x58005800u | (z * 0x00080008u); }
+__device__ __forceinline__ uint32_t k64(uint32_t z) { return 0x54005400u | (z * 0x00100010u); }
+__device__ __forceinline__ uint32_t k16(uint32_t z) { return 0x4C004C00u | (z * 0x00400040u); }
+
+constexpr uint32_t MAGIC = 0x64006400u;   // fp16 1024.0 twice: OR-ing a small integer into the mantissa adds it
+
+// Eight 4-bit codes of one word -> (code - z) as eight fp16, columns in natural order.
+// Nibble e holds column 2*(e%4) + e/4, so each mask yields two adjacent columns.
+__device__ __forceinline__ h8 dq4_word(uint32_t w, uint32_t c1024, uint32_t c64)
+{
+    const h2 sixteenth = {(_Float16)0.0625f, (_Float16)0.0625f};
+    const uint32_t hi = w >> 8;
+    Frag f;
+    f.p[0] = as_h2((w & 0x000F000Fu) | MAGIC) - as_h2(c1024);                                  // 1024+q
+    f.p[1] = __builtin_elementwise_fma(as_h2((w & 0x00F000F0u) | MAGIC), sixteenth, -as_h2(c64));   // 1024+16q
+    f.p[2] = as_h2((hi & 0x000F000Fu) | MAGIC) - as_h2(c1024);
+    f.p[3] = __builtin_elementwise_fma(as_h2((hi & 0x00F000F0u) | MAGIC), sixteenth, -as_h2(c64));
+    return f.v;
+}
+
+// Thirty-two 3-bit codes of one lane (three words) -> four fragments of (code - z).
+__device__ __forceinline__ void dq3_lane(uint32_t d0, uint32_t d1, uint32_t d2, uint32_t z, h8 out[4])
+{
+    const h2 eighth = {(_Float16)0.125f, (_Float16)0.125f};
+    const h2 sixtyfourth = {(_Float16)0.015625f, (_Float16)0.015625f};
+    const h2 c1024 = as_h2(k1024(z)), c128 = as_h2(k128(z)), c16 = as_h2(k16(z));
+    h2 pr[16];
+    const uint32_t d[3] = {d0, d1, d2};
+#pragma unroll
+    for (int i = 0; i < 3; ++i) {
+        const uint32_t w = d[i], hi = w >> 9;
+        pr[5 * i + 0] = as_h2((w & 0x00070007u) | MAGIC) - c1024;                                      // 1024+q
+        pr[5 * i + 1] = __builtin_elementwise_fma(as_h2((w & 0x00380038u) | MAGIC), eighth, -c128);        // 1024+8q
+        pr[5 * i + 2] = __builtin_elementwise_fma(as_h2((w & 0x01C001C0u) | MAGIC), sixtyfourth, -c16);    // 1024+64q
+        pr[5 * i + 3] = as_h2((hi & 0x00070007u) | MAGIC) - c1024;
+        pr[5 * i + 4] = __builtin_elementwise_fma(as_h2((hi & 0x00380038u) | MAGIC), eighth, -c128);
+    }
+    uint32_t last = ((d0 >> 15) & 0x00010001u) | MAGIC;       // bit b of the last pair is bit 15 / 31 of word b
+    last |= (d1 >> 14) & 0x00020002u;
+    last |= (d2 >> 13) & 0x00040004u;
+    pr[15] = as_h2(last) - c1024;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        Frag f;
+        f.p[0] = pr[4 * t + 0];
+        f.p[1] = pr[4 * t + 1];
+        f.p[2] = pr[4 * t + 2];
+        f.p[3] = pr[4 * t + 3];
+        out[t] = f.v;
+    }
+}
+
+// zero-point nibble of row n of (row block R, quantisation group q)
+__device__ __forceinline__ uint32_t load_zero(const uint32_t* __restrict__ qzeros, size_t rq, int n)
+{
+    const uint32_t w = qzeros[2 * rq + (n >> 3)];
+    return (w >> (4 * (n & 7))) & 0xFu;
+}
+
+}  // namespace eora

@@ -1,0 +1,34 @@
+"""Helpers for the GPU parity tests: move a case to the device and call the C ABI."""
+import numpy as np
+import torch
+
+import paper_2410_21271_amd as eora
+
+
+def dev(a):
+    if a is None:
+        return None
+    a = np.ascontiguousarray(a)
+    if a.dtype == np.uint32:
+        return torch.from_numpy(a.view(np.int32)).cuda()
+    return torch.from_numpy(a).cuda()
+
+
+def run_linear_q(c, M=None, x=None, r=None, canary=True):
+    """Run eora_linear_q on case c; returns y as float16 numpy (M x d_out)."""
+    M = c.M if M is None else M
+    r = c.r if r is None else r
+    x = c.x if x is None else x
+    xd = dev(x)
+    qw, sc, qz = dev(c.qw), dev(c.sc), dev(c.qz)
+    A, B, As, Bs = (dev(c.A), dev(c.B), dev(c.As), dev(c.Bs)) if r > 0 else (None, None, None, None)
+    ws = torch.empty(eora.workspace_bytes(M, c.d_in, c.d_out, r), dtype=torch.uint8, device="cuda")
+    pad = 64
+    ybuf = torch.full((M * c.d_out + 2 * pad,), 777.0, dtype=torch.float16, device="cuda")
+    y = ybuf[pad: pad + M * c.d_out]
+    eora.linear_q(xd, qw, sc, qz, A, B, As, Bs, y, M, c.d_in, c.d_out, r, c.w_bits, c.group, c.ab_bits, ws)
+    torch.cuda.synchronize()
+    out = ybuf.cpu().numpy()
+    if canary:
+        assert np.all(out[:pad] == 777.0) and np.all(out[pad + M * c.d_out:] == 777.0), "write outside y"
+    return out[pad: pad + M * c.d_out].reshape(M, c.d_out)

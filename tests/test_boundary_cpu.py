@@ -1,0 +1,94 @@
+"""CPU-only checks of the C-ABI boundary: the library loads, exports every symbol the header
+declares, its host packers emit exactly the oracle's bytes, and argument validation returns the
+documented codes before anything touches a device."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2410_21271_amd as eora
+from paper_2410_21271_amd import binding
+from tests.cases import QCase, SparseCase
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    text = open(os.path.join(ROOT, "include", "eora.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(eora_[a-z0-9_]+)\s*\(", text))
+    assert declared, "no declarations found"
+    assert declared == set(binding.EXPORTS)
+    raw = ctypes.CDLL(eora.lib_path())
+    for name in declared:
+        assert getattr(raw, name) is not None
+
+
+@pytest.mark.parametrize("w_bits,ab_bits,r", [(4, 16, 32), (3, 16, 64), (4, 4, 64), (3, 4, 128), (4, 16, 0)])
+def test_host_packers_match_oracle_bytes(w_bits, ab_bits, r):
+    QCase(100 + w_bits + r, 256, 48, 2, r, w_bits, 128, ab_bits, packer=eora)      # asserts inside
+    QCase(200 + w_bits + r, 256, 32, 1, r, w_bits, 256, ab_bits, packer=eora)      # channel-wise group
+
+
+def test_sparse_packer_matches_oracle_bytes():
+    SparseCase(7, 256, 32, 1, 32, packer=eora)
+
+
+def test_sizes():
+    assert eora.qweight_bytes(4096, 4096, 4) == 4096 * 4096 // 2
+    assert eora.qweight_bytes(4096, 4096, 3) == 4096 * 4096 * 3 // 8
+    assert eora.qzeros_bytes(4096, 4096, 128) == 4096 * 32 // 2
+    assert eora.scales_bytes(4096, 4096, 128) == 4096 * 32 * 2
+    assert eora.sp24_values_bytes(8192, 1024) == 8192 * 1024
+    assert eora.sp24_indices_bytes(8192, 1024) == 8192 * 1024 // 8
+    assert eora.qweight_bytes(4096, 4100, 4) == 0 and eora.qweight_bytes(4096, 4096, 5) == 0
+    assert eora.workspace_bytes(1, 4096, 4096, 128) >= 4 * 128
+    assert eora.workspace_bytes(1, 4096, 4096, 1024) == 0
+
+
+def test_packers_reject_bad_values():
+    codes = np.zeros((16, 128), np.uint8)
+    zeros = np.zeros((16, 1), np.uint8)
+    scales = np.ones((16, 1), np.float16)
+    codes[3, 5] = 8
+    with pytest.raises(eora.EoraError) as ei:
+        eora.pack_q(codes, zeros, scales, 3, 128)
+    assert ei.value.status == -7
+    eora.pack_q(codes, zeros, scales, 4, 128)
+    zeros[0, 0] = 16
+    with pytest.raises(eora.EoraError):
+        eora.pack_q(codes, zeros, scales, 4, 128)
+    with pytest.raises(eora.EoraError):
+        eora.pack_sp24(np.zeros((16, 64), np.float16), np.zeros((16, 64), np.uint8))
+    with pytest.raises(eora.EoraError):
+        eora.pack_factor_f16(np.zeros((8, 32), np.float16))
+
+
+def test_linear_q_validation_codes():
+    """Every error path returns before a launch, so these calls are safe without a GPU: the
+    pointers are never dereferenced."""
+    L = eora.lib
+    good = ctypes.c_void_p(0x1000)
+    odd = ctypes.c_void_p(0x1008)
+    null = ctypes.c_void_p(0)
+
+    def call(x=good, qw=good, sc=good, qz=good, A=good, B=good, As=null, Bs=null, y=good, M=1, d_in=256, d_out=32,
+             r=32, w_bits=4, group=128, ab_bits=16, ws=good, ws_bytes=1 << 20):
+        return L.eora_linear_q(x, qw, sc, qz, A, B, As, Bs, y, M, d_in, d_out, r, w_bits, group, ab_bits, ws,
+                               ws_bytes, null)
+
+    assert call(x=null) == -1 and call(y=null) == -1 and call(A=null) == -1
+    assert call(d_out=40) == -2 and call(d_in=200) == -2 and call(group=64) == -2 and call(group=384) == -2
+    assert call(r=48) == -2 and call(r=1024) == -2 and call(M=-1) == -2
+    assert call(w_bits=2) == -3 and call(ab_bits=8) == -3
+    assert call(ab_bits=4, As=good, Bs=good, r=96) == -2 and call(ab_bits=4, r=64) == -1
+    assert call(qw=odd) == -4 and call(y=odd) == -4 and call(ws=odd) == -4
+    assert call(ws=null) == -5 and call(ws_bytes=16) == -5
+    assert call(M=0) == 0                                   # empty input: nothing to do, nothing launched
+    assert L.eora_linear_sp24(null, good, good, good, good, good, 1, 256, 32, 32, good, 1 << 20, null) != 0
+    assert L.eora_unpack_q(good, good, good, good, 256, 32, 5, 128, null) == -3
+    assert L.eora_dequant_q(good, good, good, null, 256, 32, 4, 128, null) == -1
+    assert L.eora_expand_sp24(good, odd, good, 256, 32, null) == -4
+    assert eora.status_string(-4) == "misaligned pointer"

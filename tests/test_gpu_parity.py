@@ -1,0 +1,119 @@
+"""GPU parity: the HIP path through the C ABI against the CPU oracle, element by element."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+TOL = 2e-3      # max |y - y_oracle| / max(|y_oracle|, rms(y_oracle)); fp32 accumulate, fp16 output
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    import paper_2410_21271_amd as eora
+    return eora
+
+
+def _check(y, ref, tol=TOL):
+    from oracle import linear
+    assert np.all(np.isfinite(y.astype(np.float32)))
+    err = linear.y_error(y, ref)
+    assert err <= tol, err
+    return err
+
+
+@pytest.mark.parametrize("w_bits", [4, 3])
+@pytest.mark.parametrize("group", [128, 384])
+def test_unpack_and_dequant_bit_exact(gpu, w_bits, group):
+    import torch
+    from oracle import linear
+    from tests.cases import QCase
+    from tests.gpu_util import dev
+    c = QCase(11 + w_bits, 768, 80, 1, 0, w_bits, group, packer=gpu)      # 5 row blocks x 6 k-tiles
+    qw, sc, qz = dev(c.qw), dev(c.sc), dev(c.qz)
+    codes = torch.full((80, 768), 255, dtype=torch.uint8, device="cuda")
+    zeros = torch.full((80, 768 // group), 255, dtype=torch.uint8, device="cuda")
+    gpu.unpack_q(qw, qz, codes, zeros, 768, 80, w_bits, group)
+    W = torch.full((80, 768), float("nan"), dtype=torch.float32, device="cuda")
+    gpu.dequant_q(qw, sc, qz, W, 768, 80, w_bits, group)
+    torch.cuda.synchronize()
+    assert np.array_equal(codes.cpu().numpy(), c.logical["codes"])
+    assert np.array_equal(zeros.cpu().numpy(), c.logical["zeros"])
+    ref = linear.dequant_q(c.o_qw, c.o_qz, c.o_sc, 768, 80, w_bits, group)
+    got = W.cpu().numpy()
+    assert np.array_equal(got.astype(np.float64), ref)          # exact, not just close
+    assert np.array_equal(got, ref.astype(np.float32))
+
+
+@pytest.mark.parametrize("w_bits,ab_bits,r,M", [
+    (4, 16, 0, 1), (4, 16, 32, 1), (4, 16, 128, 3), (3, 16, 0, 1), (3, 16, 64, 2),
+    (4, 4, 64, 1), (4, 4, 128, 5), (3, 4, 256, 16), (4, 16, 96, 16), (4, 16, 64, 17), (3, 16, 32, 37),
+])
+def test_linear_q_small_shapes(gpu, w_bits, ab_bits, r, M):
+    """Several row blocks and k-tiles, ragged token counts."""
+    from tests.cases import QCase
+    from tests.gpu_util import run_linear_q
+    c = QCase(1000 + 7 * r + M + w_bits, 640, 112, M, r, w_bits, 128, ab_bits, packer=gpu)
+    _check(run_linear_q(c), c.oracle_y())
+
+
+def test_adapter_off_equals_rank_zero_and_zero_factors(gpu):
+    from tests.cases import QCase
+    from tests.gpu_util import run_linear_q
+    c = QCase(5, 512, 64, 4, 32, 4, packer=gpu)
+    y0 = run_linear_q(c, r=0)
+    c0 = QCase(5, 512, 64, 4, 0, 4, packer=gpu)
+    assert np.array_equal(y0, run_linear_q(c0))
+    _check(y0, c0.oracle_y())
+    c.A = np.zeros_like(c.A)
+    c.B = np.zeros_like(c.B)
+    assert np.array_equal(run_linear_q(c), y0)
+
+
+def test_row_independence_and_determinism(gpu):
+    from tests.cases import QCase
+    from tests.gpu_util import run_linear_q
+    c = QCase(9, 1024, 256, 16, 64, 3, packer=gpu)
+    y = run_linear_q(c)
+    assert np.array_equal(y, run_linear_q(c))                          # fixed reduction order
+    ref = c.oracle_y()
+    _check(y, ref)
+    for m in (0, 7, 15):
+        y1 = run_linear_q(c, M=1, x=c.x[m:m + 1])
+        _check(y1, ref[m:m + 1])
+
+
+def test_planted_integers_are_exact_on_gpu(gpu):
+    """Small-integer codes, factors and activations: every fp32 partial sum is an exact integer,
+    so the GPU result must equal the oracle's bit for bit (after the fp16 store)."""
+    from oracle import layout, linear
+    from tests.cases import QCase
+    from tests.gpu_util import run_linear_q
+    rng = np.random.default_rng(3)
+    c = QCase(3, 256, 32, 4, 32, 4, packer=None)
+    codes = rng.integers(0, 16, (32, 256), dtype=np.uint8)
+    zeros = rng.integers(0, 16, (32, 2), dtype=np.uint8)
+    scales = np.full((32, 2), 0.5, np.float16)
+    A = rng.integers(-2, 3, (32, 256)).astype(np.float16)
+    B = rng.integers(-2, 3, (32, 32)).astype(np.float16) / 2
+    c.x = rng.integers(-3, 4, (4, 256)).astype(np.float16) / 4
+    c.logical.update(codes=codes, zeros=zeros, scales=scales, A=A, B=B)
+    c.o_qw, c.o_qz, c.o_sc = layout.pack_q4(codes), layout.pack_zeros(zeros), layout.pack_scales(scales)
+    c.o_A, c.o_B = layout.pack_f16(A), layout.pack_f16(B)
+    c.pack_with(gpu)
+    ref = c.oracle_y()
+    assert np.array_equal(ref.astype(np.float16).astype(np.float64), ref)      # representable in fp16
+    assert np.array_equal(run_linear_q(c).astype(np.float64), ref)
+
+
+@pytest.mark.parametrize("name,d_in,d_out", [("q", 4096, 4096), ("k", 4096, 1024)])
+@pytest.mark.parametrize("w_bits,M", [(4, 1), (4, 16), (3, 1)])
+def test_config_shapes_fp16_factors(gpu, name, d_in, d_out, w_bits, M):
+    """BASELINE configs 1 and 2 at full size (the oracle needs about a second each)."""
+    import synth
+    from tests.cases import QCase
+    from tests.gpu_util import run_linear_q
+    c = QCase(synth.seed_for(1 if w_bits == 4 else 2, 0 if name == "q" else 1), d_in, d_out, M, 128, w_bits,
+              packer=gpu)
+    _check(run_linear_q(c), c.oracle_y())
