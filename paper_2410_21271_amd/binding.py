@@ -26,6 +26,10 @@ def _load():
     if not os.path.exists(_LIB_PATH):
         raise ImportError("libeora.so is not built: run `python -m paper_2410_21271_amd.build` "
                           "(there is no CPU fallback)")
+    # torch must own the process's HIP runtime: loading it first makes libeora.so bind to the same
+    # libamdhip64 (same soname) instead of bringing in a second runtime whose streams and device
+    # pointers would be foreign to torch's.
+    import torch  # noqa: F401
     L = ctypes.CDLL(_LIB_PATH)
     vp, ci, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
     sig = {

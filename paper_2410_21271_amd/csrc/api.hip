@@ -3,6 +3,9 @@
 #include "eora.h"
 #include "kernels.hpp"
 
+#include <cstdio>
+#include <cstdlib>
+
 namespace {
 
 using namespace eora;
@@ -18,6 +21,14 @@ int check_backbone_shape(int M, int d_in, int d_out, int r)
     if (M < 0 || d_in <= 0 || d_out <= 0 || r < 0) return EORA_ERR_SHAPE;
     if (d_out % 16 || d_in % 128 || r > MAX_RANK) return EORA_ERR_SHAPE;
     return EORA_OK;
+}
+
+// Set EORA_VERBOSE=1 to have a refused launch explain itself on stderr.
+bool failed(hipError_t e, const char* what)
+{
+    if (e == hipSuccess) return false;
+    if (getenv("EORA_VERBOSE")) fprintf(stderr, "eora: %s: %s\n", what, hipGetErrorString(e));
+    return true;
 }
 
 int check_group(int d_in, int group)
@@ -83,7 +94,7 @@ int eora_linear_q(const void* x, const void* qweight, const void* scales, const 
         d.d_in = d_in;
         d.d_out = r;
         d.group = 128;
-        if (launch_downproj(d, fa, s) != hipSuccess) return EORA_ERR_LAUNCH;
+        if (failed(launch_downproj(d, fa, s), "down-projection")) return EORA_ERR_LAUNCH;
     }
     DecodeArgs a{};
     a.x = (const _Float16*)x;
@@ -99,7 +110,7 @@ int eora_linear_q(const void* x, const void* qweight, const void* scales, const 
     a.d_out = d_out;
     a.r = r;
     a.group = group;
-    if (launch_decode(a, w_bits == 4 ? S_Q4 : S_Q3, fe, s) != hipSuccess) return EORA_ERR_LAUNCH;
+    if (failed(launch_decode(a, w_bits == 4 ? S_Q4 : S_Q3, fe, s), "linear_q")) return EORA_ERR_LAUNCH;
     return EORA_OK;
 }
 
@@ -123,8 +134,8 @@ int eora_unpack_q(const void* qweight, const void* qzeros, void* codes_u8, void*
     rc = check_group(d_in, group);
     if (rc != EORA_OK) return rc;
     if (!aligned16(qweight) || !aligned16(qzeros)) return EORA_ERR_ALIGN;
-    if (launch_unpack_q((const uint32_t*)qweight, (const uint32_t*)qzeros, (uint8_t*)codes_u8, (uint8_t*)zeros_u8,
-                        d_in, d_out, w_bits, group, (hipStream_t)stream) != hipSuccess)
+    if (failed(launch_unpack_q((const uint32_t*)qweight, (const uint32_t*)qzeros, (uint8_t*)codes_u8,
+                               (uint8_t*)zeros_u8, d_in, d_out, w_bits, group, (hipStream_t)stream), "unpack_q"))
         return EORA_ERR_LAUNCH;
     return EORA_OK;
 }
@@ -139,8 +150,8 @@ int eora_dequant_q(const void* qweight, const void* scales, const void* qzeros, 
     rc = check_group(d_in, group);
     if (rc != EORA_OK) return rc;
     if (!aligned16(qweight) || !aligned16(scales) || !aligned16(qzeros) || !aligned16(W_f32)) return EORA_ERR_ALIGN;
-    if (launch_dequant_q((const uint32_t*)qweight, (const _Float16*)scales, (const uint32_t*)qzeros, (float*)W_f32,
-                         d_in, d_out, w_bits, group, (hipStream_t)stream) != hipSuccess)
+    if (failed(launch_dequant_q((const uint32_t*)qweight, (const _Float16*)scales, (const uint32_t*)qzeros,
+                                (float*)W_f32, d_in, d_out, w_bits, group, (hipStream_t)stream), "dequant_q"))
         return EORA_ERR_LAUNCH;
     return EORA_OK;
 }
@@ -151,8 +162,8 @@ int eora_expand_sp24(const void* values, const void* indices, void* W_f16, int d
     int rc = check_backbone_shape(1, d_in, d_out, 0);
     if (rc != EORA_OK) return rc;
     if (!aligned16(values) || !aligned16(indices) || !aligned16(W_f16)) return EORA_ERR_ALIGN;
-    if (launch_expand_sp24((const _Float16*)values, (const uint32_t*)indices, (_Float16*)W_f16, d_in, d_out,
-                           (hipStream_t)stream) != hipSuccess)
+    if (failed(launch_expand_sp24((const _Float16*)values, (const uint32_t*)indices, (_Float16*)W_f16, d_in, d_out,
+                                  (hipStream_t)stream), "expand_sp24"))
         return EORA_ERR_LAUNCH;
     return EORA_OK;
 }
