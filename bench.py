@@ -1,0 +1,201 @@
+#!/usr/bin/env python3
+"""Benchmark of the EoRA compensated compressed linear layer on one MI355X.
+
+A step is one pass over all seven linears of a LLaMA-3-8B-shaped decoder layer (q, k, v, o, gate,
+up, down) at M = 1 with a 3-bit group-128 backbone and fp16 rank-128 EoRA factors: synthetic,
+seeded inputs already resident in HBM.  Steps rotate over enough distinct copies of the weights
+that neither L2 nor the 256 MB last-level cache can hold them.  The timed region is one HIP graph
+holding exactly --steps steps, bracketed by events on the launch stream.
+
+Prints ONE JSON line (see the keys at the end of main()).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+WORKLOADS = {
+    # name: (shapes, w_bits, ab_bits, r, M, outlier_frac, config id for the seeds)
+    "llama3-8b-layer-decode-w3g128-r128fp16-M1": dict(model="8b", w_bits=3, ab_bits=16, r=128, M=1, cfg=2),
+    "llama3-8b-layer-decode-w4g128-r128fp16-M1": dict(model="8b", w_bits=4, ab_bits=16, r=128, M=1, cfg=1),
+    "llama3-8b-layer-decode-w4g128-r128q4-M1": dict(model="8b", w_bits=4, ab_bits=4, r=128, M=1, cfg=3),
+    "llama3-8b-layer-decode-w4g128-bare-M1": dict(model="8b", w_bits=4, ab_bits=16, r=0, M=1, cfg=3),
+    "llama3-8b-layer-decode-w3g128-bare-M1": dict(model="8b", w_bits=3, ab_bits=16, r=0, M=1, cfg=2),
+}
+DEFAULT = "llama3-8b-layer-decode-w3g128-r128fp16-M1"
+
+
+def algorithmic_bytes(d_in, d_out, M, r, w_bits, ab_bits, group=128):
+    """Bytes the method must move for one linear: packed codes, scales, zero-points, factors,
+    x read once and y written once (the M x r intermediate never makes a y-sized round trip)."""
+    b = d_out * d_in * w_bits / 8 + d_out * (d_in // group) * 2.5
+    if r:
+        if ab_bits == 16:
+            b += 2 * r * (d_in + d_out)
+        else:
+            KTb = min(128, r)
+            b += r * d_in / 2 + 2 * r * (d_in // 128) + d_out * r / 2 + 2 * d_out * (r // KTb)
+    return b + 2 * M * (d_in + d_out)
+
+
+class Linear:
+    """Device-resident copies of one linear's stored operands."""
+
+    def __init__(self, name, d_in, d_out, spec, seed, ncopies):
+        import numpy as np
+        import torch
+        import synth
+        import paper_2410_21271_amd as eora
+        from tests.gpu_util import dev
+        self.name, self.d_in, self.d_out = name, d_in, d_out
+        self.M, self.r, self.w_bits, self.ab_bits = spec["M"], spec["r"], spec["w_bits"], spec["ab_bits"]
+        W, A, B, x = synth.draw_layer(seed, d_in, d_out, self.M, self.r)
+        codes, zeros, scales = synth.quantize_rtn(W, self.w_bits, 128)
+        self.logical = (codes, zeros, scales, A, B, x)
+        qw, qz, sc = eora.pack_q(codes, zeros, scales, self.w_bits, 128)
+        host = [qw, sc, qz, None, None, None, None]
+        if self.r and self.ab_bits == 16:
+            host[3], host[4] = eora.pack_factor_f16(A), eora.pack_factor_f16(B)
+        elif self.r:
+            ca, sa = synth.quantize_sym4(A, 128)
+            cb, sb = synth.quantize_sym4(B, min(128, self.r))
+            host[3], host[5] = eora.pack_factor_q4(ca, sa)
+            host[4], host[6] = eora.pack_factor_q4(cb, sb)
+            self.logical = (codes, zeros, scales, (ca, sa), (cb, sb), x)
+        first = [dev(h) for h in host]
+        self.copies = [first] + [[None if t is None else t.clone() for t in first] for _ in range(ncopies - 1)]
+        self.x = dev(x)
+        self.y = torch.zeros((self.M, d_out), dtype=torch.float16, device="cuda")
+        self.ws = torch.empty(eora.workspace_bytes(self.M, d_in, d_out, self.r), dtype=torch.uint8, device="cuda")
+        self.bytes = algorithmic_bytes(d_in, d_out, self.M, self.r, self.w_bits, self.ab_bits)
+        self.flops = 2.0 * self.M * d_in * d_out + 2.0 * self.M * self.r * (d_in + d_out)
+
+    def run(self, copy):
+        import paper_2410_21271_amd as eora
+        qw, sc, qz, A, B, As, Bs = self.copies[copy % len(self.copies)]
+        eora.linear_q(self.x, qw, sc, qz, A, B, As, Bs, self.y, self.M, self.d_in, self.d_out, self.r,
+                      self.w_bits, 128, self.ab_bits, self.ws)
+
+
+def timed_graph(fn, count):
+    """Capture `count` calls fn(i) into one HIP graph, replay it once untimed and once between
+    two events on the launch stream; returns milliseconds per call."""
+    import torch
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for i in range(count):
+            fn(i)
+    torch.cuda.synchronize()
+    g.replay()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    g.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / count
+
+
+def cpu_baseline(linears, names):
+    """The float64 oracle as it stands, timed on the host cores on a bounded sample."""
+    import numpy as np
+    from oracle import layout, linear
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    total_t, total_b, worst = 0.0, 0.0, 0.0
+    for L in linears:
+        if L.name not in names:
+            continue
+        codes, zeros, scales, A, B, x = L.logical
+        qw = layout.pack_q4(codes) if L.w_bits == 4 else layout.pack_q3(codes)
+        qz, sc = layout.pack_zeros(zeros), layout.pack_scales(scales)
+        Ap = Bp = As = Bs = None
+        if L.r and L.ab_bits == 16:
+            Ap, Bp = layout.pack_f16(A), layout.pack_f16(B)
+        elif L.r:
+            Ap, As = layout.pack_q4(A[0], 128), layout.pack_scales(A[1])
+            Bp, Bs = layout.pack_q4(B[0], min(128, L.r)), layout.pack_scales(B[1])
+        t0 = time.perf_counter()
+        y = linear.eora_linear_q(x, qw, sc, qz, Ap, Bp, As, Bs, L.M, L.d_in, L.d_out, L.r, L.w_bits, 128, L.ab_bits)
+        total_t += time.perf_counter() - t0
+        total_b += L.bytes
+        worst = max(worst, linear.y_error(L.y.cpu().numpy(), y))
+    return dict(value=total_b / total_t / 1e9, unit="GB/s", cores=int(threads), kind="oracle",
+                sample="one pass of the numpy float64 oracle over the %s linears of the same layer "
+                       "(%.1f s)" % ("/".join(names), total_t)), worst
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default=DEFAULT, choices=sorted(WORKLOADS))
+    ap.add_argument("--copies", type=int, default=0, help="distinct weight copies (0 = enough for 1.2 GB)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU's share of the layer; --gpus %d is not supported "
+              "(no collective or sharding code exists here)" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import synth
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    torch.cuda.set_device(0)
+    spec = WORKLOADS[args.workload]
+    shapes = synth.LLAMA3_8B
+    layer_bytes = sum(algorithmic_bytes(di, do, spec["M"], spec["r"], spec["w_bits"], spec["ab_bits"])
+                      for _, di, do in shapes)
+    ncopies = args.copies or max(2, int(1.2e9 / layer_bytes) + 1)
+    linears = [Linear(n, di, do, spec, synth.seed_for(spec["cfg"], i), ncopies) for i, (n, di, do) in enumerate(shapes)]
+
+    def step(i):
+        for L in linears:
+            L.run(i)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    ms_per_step = timed_graph(step, args.steps)
+
+    # each linear on its own (graph of back-to-back launches over the rotating copies)
+    per_linear = {}
+    for L in linears:
+        us = 1e3 * timed_graph(L.run, 200)
+        per_linear[L.name] = dict(us=round(us, 3), GBps=round(L.bytes / us / 1e3, 1),
+                                  frac_hbm=round(L.bytes / us / 1e3 / HBM_PEAK_GBS, 4))
+    dom = max(linears, key=lambda L: L.bytes)
+    dom_us = per_linear[dom.name]["us"]
+    roofline = dict(bound="hbm", achieved=round(dom.bytes / dom_us / 1e3, 1), peak=HBM_PEAK_GBS, unit="GB/s",
+                    frac=round(dom.bytes / dom_us / 1e3 / HBM_PEAK_GBS, 4), traffic=None,
+                    kernel="decode_kernel (%s linear %dx%d)" % (dom.name, dom.d_out, dom.d_in),
+                    bytes_per_launch=int(dom.bytes), us_per_launch=dom_us)
+
+    out = dict(metric="decode HBM GB/s over one 8B decoder layer's linears (M=1)",
+               value=round(layer_bytes / ms_per_step / 1e6, 1), unit="GB/s", n_gpus=1, steps=args.steps,
+               warmup=args.warmup, ms_per_step=round(ms_per_step, 6), higher_is_better=True, scaling="weak",
+               vs_baseline=None, dtype="f16", data="synthetic",
+               config=dict(workload=args.workload, layer_bytes=int(layer_bytes), weight_copies=ncopies,
+                           layer_us=round(1e3 * ms_per_step, 3), frac_hbm_peak=round(layer_bytes / ms_per_step / 1e6 / HBM_PEAK_GBS, 4),
+                           per_linear=per_linear),
+               roofline=roofline)
+    if not args.no_cpu_baseline:
+        base, worst = cpu_baseline(linears, ("q", "k", "v", "o", "gate"))
+        out["cpu_baseline"] = base
+        out["config"]["max_err_vs_oracle"] = float("%.3g" % worst)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -67,15 +67,24 @@ def q4_locate(o, i, K, KT):
 
 
 def pack_q4(codes, KT=128):
+    """Word-walk direction: every output word gathers the eight codes it holds."""
     codes = np.asarray(codes)
     rows, K = codes.shape
     _check(rows, K, KT)
     if codes.min(initial=0) < 0 or codes.max(initial=0) > 15:
         raise ValueError("4-bit code out of range")
-    o, i = np.meshgrid(np.arange(rows), np.arange(K), indexing="ij")
-    word, shift = q4_locate(o, i, K, KT)
-    out = np.zeros(rows * K // 8, dtype=np.uint32)
-    np.bitwise_or.at(out, word.ravel(), (codes.astype(np.uint32) << shift.astype(np.uint32)).ravel())
+    wpl, ntk = KT // 32, K // KT
+    w = np.arange(rows * K // 8)
+    tile, rem = w // (LANES * wpl), w % (LANES * wpl)
+    lane, t = rem // wpl, rem % wpl
+    R, g = tile // ntk, tile % ntk
+    j, n = lane // 16, lane % 16
+    row = 16 * R + n
+    col0 = g * KT + j * (KT // 4) + 8 * t
+    out = np.zeros(w.size, dtype=np.uint32)
+    for kk in range(8):
+        e = 4 * (kk % 2) + kk // 2
+        out |= codes[row, col0 + kk].astype(np.uint32) << np.uint32(4 * e)
     return out
 
 
@@ -102,28 +111,28 @@ def _q3_lane(o, i, K):
 
 
 def pack_q3(codes):
+    """Word-walk direction: every lane gathers its 32 codes and lays them into its three words."""
     codes = np.asarray(codes)
     rows, K = codes.shape
     _check(rows, K, 128)
     if codes.min(initial=0) < 0 or codes.max(initial=0) > 7:
         raise ValueError("3-bit code out of range")
-    o, i = np.meshgrid(np.arange(rows), np.arange(K), indexing="ij")
-    base, cc = _q3_lane(o, i, K)
-    out = np.zeros(rows * K * 3 // 32, dtype=np.uint32)
-    q = codes.astype(np.uint32)
-    paired = cc < 30
-    p, h = cc // 2, cc % 2
-    # the fifteen in-place pairs
-    w = base + p // 5
-    s = (16 * h + 3 * (p % 5)).astype(np.uint32)
-    np.bitwise_or.at(out, w[paired], (q[paired] << s[paired]))
-    # the two codes spread over the spare bits
-    hs = (cc - 30)
-    for b in range(3):
-        bit = (q >> np.uint32(b)) & 1
-        s = (16 * hs + 15).astype(np.uint32)
-        np.bitwise_or.at(out, (base + b)[~paired], (bit[~paired] << s[~paired]))
-    return out
+    ntk = K // 128
+    L = np.arange(rows * K // 32)                   # global (tile, lane)
+    tile, lane = L // LANES, L % LANES
+    R, g = tile // ntk, tile % ntk
+    j, n = lane // 16, lane % 16
+    row = 16 * R + n
+    col0 = 128 * g + 32 * j
+    d = [np.zeros(L.size, dtype=np.uint32) for _ in range(3)]
+    for cc in range(30):                            # the fifteen in-place pairs
+        p, h = cc // 2, cc % 2
+        d[p // 5] |= codes[row, col0 + cc].astype(np.uint32) << np.uint32(16 * h + 3 * (p % 5))
+    for h in range(2):                              # the two codes spread over the spare bits
+        q = codes[row, col0 + 30 + h].astype(np.uint32)
+        for b in range(3):
+            d[b] |= ((q >> np.uint32(b)) & np.uint32(1)) << np.uint32(16 * h + 15)
+    return np.stack(d, axis=1).reshape(-1)
 
 
 def unpack_q3(words, rows, K):
