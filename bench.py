@@ -73,7 +73,7 @@ class Linear:
         self.copies = [first] + [[None if t is None else t.clone() for t in first] for _ in range(ncopies - 1)]
         self.x = dev(x)
         self.y = torch.zeros((self.M, d_out), dtype=torch.float16, device="cuda")
-        self.ws = torch.empty(eora.workspace_bytes(self.M, d_in, d_out, self.r), dtype=torch.uint8, device="cuda")
+        self.ws = eora.new_workspace(self.M, d_in, d_out, self.r)
         self.bytes = algorithmic_bytes(d_in, d_out, self.M, self.r, self.w_bits, self.ab_bits)
         self.flops = 2.0 * self.M * d_in * d_out + 2.0 * self.M * self.r * (d_in + d_out)
 

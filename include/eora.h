@@ -69,7 +69,8 @@ typedef enum {
     EORA_ERR_ALIGN = -4,       /* a device pointer is not 16-byte aligned */
     EORA_ERR_WORKSPACE = -5,   /* workspace missing or smaller than eora_workspace_bytes() */
     EORA_ERR_LAUNCH = -6,      /* the HIP runtime refused a launch (hipGetLastError) */
-    EORA_ERR_VALUE = -7        /* host packer: a code / zero-point / position is out of range */
+    EORA_ERR_VALUE = -7,       /* host packer: a code / zero-point / position is out of range */
+    EORA_ERR_TIMEOUT = -8      /* eora_workspace_error: a bounded in-kernel wait expired (results invalid) */
 } eora_status;
 
 /* HOST.  Static string for a status code. */
@@ -83,10 +84,24 @@ size_t eora_qzeros_bytes(int d_in, int d_out, int group);            /* d_out*(d
 size_t eora_scales_bytes(int d_in, int d_out, int group);            /* d_out*(d_in/group)*2 */
 size_t eora_sp24_values_bytes(int d_in, int d_out);                  /* d_out*d_in          */
 size_t eora_sp24_indices_bytes(int d_in, int d_out);                 /* d_out*d_in/8        */
-/* Scratch the forward calls need for the down-projection t = x.A^T (M x r) and for partial sums.
- * Contents need not be initialised and are undefined afterwards.  Concurrent calls on different
- * streams need different workspaces.  r == 0 still needs a (small) workspace. */
+/* Scratch the forward calls need: a header of counters, the down-projection t = x.A^T (M x r,
+ * fp32) and its partial sums.  The header must be cleared ONCE with eora_workspace_init() before the
+ * first forward call on this workspace; every forward call leaves it cleared again, so no per-call
+ * clearing (and nothing a HIP graph could not replay) is needed.  The rest need not be initialised.
+ * Calls that may overlap in time (different streams) need different workspaces.  r == 0 still
+ * needs a workspace. */
 size_t eora_workspace_bytes(int M, int d_in, int d_out, int r);
+/* Enqueues the clearing of the workspace header on `stream`. */
+int eora_workspace_init(void* workspace, size_t workspace_bytes, void* stream);
+/* Diagnostic.  SYNCHRONISES `stream`, then reports EORA_ERR_TIMEOUT if a kernel that used this
+ * workspace gave up its bounded wait for the down-projection (its y is then invalid; re-initialise
+ * the workspace), else EORA_OK.  The wait cannot expire in a healthy run: the workgroups it waits
+ * for are running and never wait themselves. */
+int eora_workspace_error(const void* workspace, void* stream);
+/* HOST, test hook: iterations of that bounded wait (process-wide; default 1 << 22, about a second).
+ * 0 makes a wait give up at once if t is not ready yet, so that the error path can be exercised
+ * with every kernel still terminating normally. */
+void eora_debug_set_spin_limit(int iterations);
 
 /* ---------------------------------------------------------------------------------------------
  * Host-side packers: logical arrays (HOST pointers, row-major) -> stored bytes (HOST pointers).

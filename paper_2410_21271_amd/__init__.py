@@ -3,11 +3,12 @@ y = x.What^T + (x.A^T).B^T  (arXiv 2410.21271, Sec. 3 forward equation; Alg. 1 s
 
 This package is only the thin ctypes binding of libeora.so: argument marshalling, no arithmetic.
 Every step of the layer runs in the HIP kernels under csrc/.  Importing the binding fails loudly
-when the shared library has not been built (python -m paper_2410_21271_amd.build).
+when the shared library has not been built (python paper_2410_21271_amd/build.py).
 """
 from .binding import (  # noqa: F401
     EoraError, lib, lib_path, status_string,
     qweight_bytes, qzeros_bytes, scales_bytes, sp24_values_bytes, sp24_indices_bytes, workspace_bytes,
+    workspace_init, workspace_error, debug_set_spin_limit, new_workspace,
     pack_q, pack_factor_f16, pack_factor_q4, pack_sp24,
     linear_q, linear_sp24, unpack_q, dequant_q, expand_sp24,
 )

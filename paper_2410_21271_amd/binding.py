@@ -24,7 +24,7 @@ def lib_path():
 
 def _load():
     if not os.path.exists(_LIB_PATH):
-        raise ImportError("libeora.so is not built: run `python -m paper_2410_21271_amd.build` "
+        raise ImportError("libeora.so is not built: run `python paper_2410_21271_amd/build.py` "
                           "(there is no CPU fallback)")
     # torch must own the process's HIP runtime: loading it first makes libeora.so bind to the same
     # libamdhip64 (same soname) instead of bringing in a second runtime whose streams and device
@@ -40,6 +40,9 @@ def _load():
         "eora_sp24_values_bytes": (sz, [ci, ci]),
         "eora_sp24_indices_bytes": (sz, [ci, ci]),
         "eora_workspace_bytes": (sz, [ci, ci, ci, ci]),
+        "eora_workspace_init": (ci, [vp, sz, vp]),
+        "eora_workspace_error": (ci, [vp, vp]),
+        "eora_debug_set_spin_limit": (None, [ci]),
         "eora_pack_q": (ci, [vp, vp, vp, ci, ci, ci, ci, vp, vp, vp]),
         "eora_pack_factor_f16": (ci, [vp, ci, ci, vp]),
         "eora_pack_factor_q4": (ci, [vp, vp, ci, ci, vp, vp]),
@@ -59,7 +62,8 @@ def _load():
 
 lib = _load()
 EXPORTS = ["eora_status_string", "eora_qweight_bytes", "eora_qzeros_bytes", "eora_scales_bytes",
-           "eora_sp24_values_bytes", "eora_sp24_indices_bytes", "eora_workspace_bytes", "eora_pack_q",
+           "eora_sp24_values_bytes", "eora_sp24_indices_bytes", "eora_workspace_bytes", "eora_workspace_init",
+           "eora_workspace_error", "eora_debug_set_spin_limit", "eora_pack_q",
            "eora_pack_factor_f16", "eora_pack_factor_q4", "eora_pack_sp24", "eora_linear_q",
            "eora_linear_sp24", "eora_unpack_q", "eora_dequant_q", "eora_expand_sp24"]
 
@@ -158,6 +162,28 @@ def _dp(t):
 def _stream():
     import torch
     return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def workspace_init(workspace):
+    _check(lib.eora_workspace_init(_dp(workspace), workspace.numel() * workspace.element_size(), _stream()),
+           "workspace_init")
+
+
+def workspace_error(workspace):
+    """Synchronises the current stream; returns the status code (0 = no in-kernel wait expired)."""
+    return lib.eora_workspace_error(_dp(workspace), _stream())
+
+
+def debug_set_spin_limit(iterations):
+    lib.eora_debug_set_spin_limit(int(iterations))
+
+
+def new_workspace(M, d_in, d_out, r):
+    """Allocate (torch, device memory only) and initialise a workspace for the forward calls."""
+    import torch
+    ws = torch.empty(workspace_bytes(M, d_in, d_out, r), dtype=torch.uint8, device="cuda")
+    workspace_init(ws)
+    return ws
 
 
 def linear_q(x, qweight, scales, qzeros, A, B, A_scales, B_scales, y, M, d_in, d_out, r, w_bits, group, ab_bits,

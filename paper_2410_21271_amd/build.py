@@ -1,4 +1,4 @@
-"""Build libeora.so (HIP, gfx950 only) in-tree with hipcc.  Usage: python -m paper_2410_21271_amd.build"""
+"""Build libeora.so (HIP, gfx950 only) in-tree with hipcc.  Usage: python paper_2410_21271_amd/build.py (run by path: the package itself cannot be imported before the library exists)"""
 import os
 import subprocess
 import sys
@@ -9,7 +9,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libeora.so")
-SOURCES = ["api.hip", "decode.hip", "debug.hip", "pack.cpp"]
+SOURCES = ["api.hip", "fused.hip", "debug.hip", "pack.cpp"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]

@@ -10,8 +10,12 @@ namespace {
 
 using namespace eora;
 
-constexpr size_t WS_HEADER = 256;          // reserved for flags / counters
+constexpr size_t WS_HEADER = 8192;         // counters (HDR_WORDS 32-bit words), rounded up
 constexpr int MAX_RANK = 512;
+constexpr int CHUNK_TOKENS = 16 * MAX_YBLOCKS;      // tokens per launch
+static_assert(HDR_WORDS * 4 <= WS_HEADER, "header too small");
+
+int g_spin_limit = 1 << 22;                // bounded wait of the up-projection (about a second)
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
@@ -44,8 +48,33 @@ extern "C" {
 size_t eora_workspace_bytes(int M, int d_in, int d_out, int r)
 {
     if (check_backbone_shape(M, d_in, d_out, r) != EORA_OK) return 0;
-    return WS_HEADER + round256((size_t)M * r * sizeof(float));
+    const size_t mc = (size_t)(M < CHUNK_TOKENS ? M : CHUNK_TOKENS);
+    const size_t yblocks = (mc + 15) / 16;
+    return WS_HEADER + round256(mc * r * sizeof(float)) + (size_t)MAX_KCN * (r / 16) * yblocks * 1024;
 }
+
+int eora_workspace_init(void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!workspace) return EORA_ERR_NULL;
+    if (!aligned16(workspace)) return EORA_ERR_ALIGN;
+    if (workspace_bytes < WS_HEADER) return EORA_ERR_WORKSPACE;
+    if (failed(launch_clear_words((uint32_t*)workspace, (int)(WS_HEADER / 4), (hipStream_t)stream), "workspace_init"))
+        return EORA_ERR_LAUNCH;
+    return EORA_OK;
+}
+
+int eora_workspace_error(const void* workspace, void* stream)
+{
+    if (!workspace) return EORA_ERR_NULL;
+    uint32_t flag = 0;
+    if (hipMemcpyAsync(&flag, (const uint32_t*)workspace + HDR_ERROR, sizeof(flag), hipMemcpyDeviceToHost,
+                       (hipStream_t)stream) != hipSuccess)
+        return EORA_ERR_LAUNCH;
+    if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return EORA_ERR_LAUNCH;
+    return flag ? EORA_ERR_TIMEOUT : EORA_OK;
+}
+
+void eora_debug_set_spin_limit(int iterations) { g_spin_limit = iterations < 0 ? 0 : iterations; }
 
 int eora_linear_q(const void* x, const void* qweight, const void* scales, const void* qzeros,
                   const void* A, const void* B, const void* A_scales, const void* B_scales,
@@ -82,35 +111,35 @@ int eora_linear_q(const void* x, const void* qweight, const void* scales, const 
     if (workspace_bytes < eora_workspace_bytes(M, d_in, d_out, r)) return EORA_ERR_WORKSPACE;
     if (M == 0) return EORA_OK;
 
-    hipStream_t s = (hipStream_t)stream;
-    float* t = (float*)((char*)workspace + WS_HEADER);
-    if (r > 0) {
-        DecodeArgs d{};
-        d.x = (const _Float16*)x;
-        d.w = A;
-        d.w_scales = (const _Float16*)A_scales;
-        d.y = t;
-        d.M = M;
-        d.d_in = d_in;
-        d.d_out = r;
-        d.group = 128;
-        if (failed(launch_downproj(d, fa, s), "down-projection")) return EORA_ERR_LAUNCH;
+    // largest divisor of the number of 128-wide k-tiles that is at most MAX_KCN
+    int kcn = 1;
+    for (int c = 2; c <= MAX_KCN; ++c)
+        if ((d_in / 128) % c == 0) kcn = c;
+    const size_t t_bytes = round256((size_t)(M < CHUNK_TOKENS ? M : CHUNK_TOKENS) * r * sizeof(float));
+    for (int m0 = 0; m0 < M; m0 += CHUNK_TOKENS) {
+        FusedArgs a{};
+        a.x = (const _Float16*)x + (size_t)m0 * d_in;
+        a.w = qweight;
+        a.w_scales = (const _Float16*)scales;
+        a.w_zeros = (const uint32_t*)qzeros;
+        a.A = A;
+        a.A_scales = (const _Float16*)A_scales;
+        a.B = B;
+        a.B_scales = (const _Float16*)B_scales;
+        a.y = (_Float16*)y + (size_t)m0 * d_out;
+        a.hdr = (uint32_t*)workspace;
+        a.t = (float*)((char*)workspace + WS_HEADER);
+        a.tpart = (float*)((char*)workspace + WS_HEADER + t_bytes);
+        a.M = M - m0 < CHUNK_TOKENS ? M - m0 : CHUNK_TOKENS;
+        a.d_in = d_in;
+        a.d_out = d_out;
+        a.r = r;
+        a.group = group;
+        a.kcn = kcn;
+        a.spin_limit = g_spin_limit;
+        if (failed(launch_fused(a, w_bits == 4 ? S_Q4 : S_Q3, fa, fe, (hipStream_t)stream), "linear_q"))
+            return EORA_ERR_LAUNCH;
     }
-    DecodeArgs a{};
-    a.x = (const _Float16*)x;
-    a.w = qweight;
-    a.w_scales = (const _Float16*)scales;
-    a.w_zeros = (const uint32_t*)qzeros;
-    a.B = B;
-    a.B_scales = (const _Float16*)B_scales;
-    a.t = t;
-    a.y = y;
-    a.M = M;
-    a.d_in = d_in;
-    a.d_out = d_out;
-    a.r = r;
-    a.group = group;
-    if (failed(launch_decode(a, w_bits == 4 ? S_Q4 : S_Q3, fe, s), "linear_q")) return EORA_ERR_LAUNCH;
     return EORA_OK;
 }
 

@@ -9,20 +9,34 @@ namespace eora {
 // stored formats a contraction segment can read
 enum SegFmt { S_NONE = 0, S_Q4 = 1, S_Q3 = 2, S_Q4S128 = 3, S_Q4S64 = 4, S_F16 = 5 };
 
-struct DecodeArgs {
+// Workspace header (32-bit words): global exit counter and error flag, then one block of counters
+// per token block of 16: [0] ticket, [1] ready row blocks of t, [2 .. 2+r/16) arrivals per row block.
+constexpr int HDR_EXIT = 0;
+constexpr int HDR_ERROR = 1;
+constexpr int HDR_BLOCK0 = 64;
+constexpr int HDR_PER_BLOCK = 64;
+constexpr int MAX_YBLOCKS = 16;                 // token blocks per launch (256 tokens)
+constexpr int HDR_WORDS = HDR_BLOCK0 + HDR_PER_BLOCK * MAX_YBLOCKS;
+constexpr int MAX_KCN = 8;                      // k-chunks of the down-projection
+
+struct FusedArgs {
     const _Float16* x;        // M x d_in fp16 row-major
-    const void* w;            // main operand tiles (backbone, or A for the down-projection)
+    const void* w;            // backbone tiles
     const _Float16* w_scales;
     const uint32_t* w_zeros;
-    const void* B;            // extension operand tiles (d_out x r) or nullptr
+    const void* A;            // r x d_in tiles
+    const _Float16* A_scales;
+    const void* B;            // d_out x r tiles
     const _Float16* B_scales;
-    const float* t;           // M x r fp32 row-major (down-projection result)
-    void* y;                  // M x d_out, fp16 or fp32
-    int M, d_in, d_out, r, group;
+    _Float16* y;              // M x d_out fp16 row-major
+    uint32_t* hdr;            // workspace header, zero between launches
+    float* t;                 // M x r fp32
+    float* tpart;             // kcn x r/16 x token blocks x 256 fp32 partials of t
+    int M, d_in, d_out, r, group, kcn, spin_limit;
 };
 
-hipError_t launch_decode(const DecodeArgs& a, int fm, int fe, hipStream_t stream);
-hipError_t launch_downproj(const DecodeArgs& a, int fa, hipStream_t stream);
+hipError_t launch_fused(const FusedArgs& a, int fm, int fa, int fe, hipStream_t stream);
+hipError_t launch_clear_words(uint32_t* p, int nwords, hipStream_t stream);
 
 hipError_t launch_unpack_q(const uint32_t* qweight, const uint32_t* qzeros, uint8_t* codes, uint8_t* zeros,
                            int d_in, int d_out, int w_bits, int group, hipStream_t stream);

@@ -197,6 +197,7 @@ const char* eora_status_string(int status)
         case EORA_ERR_WORKSPACE: return "workspace missing or too small";
         case EORA_ERR_LAUNCH: return "kernel launch failed";
         case EORA_ERR_VALUE: return "value out of range";
+        case EORA_ERR_TIMEOUT: return "in-kernel wait timed out";
         default: return "unknown status";
     }
 }

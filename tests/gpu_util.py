@@ -14,7 +14,7 @@ def dev(a):
     return torch.from_numpy(a).cuda()
 
 
-def run_linear_q(c, M=None, x=None, r=None, canary=True):
+def run_linear_q(c, M=None, x=None, r=None, canary=True, ws=None):
     """Run eora_linear_q on case c; returns y as float16 numpy (M x d_out)."""
     M = c.M if M is None else M
     r = c.r if r is None else r
@@ -22,7 +22,7 @@ def run_linear_q(c, M=None, x=None, r=None, canary=True):
     xd = dev(x)
     qw, sc, qz = dev(c.qw), dev(c.sc), dev(c.qz)
     A, B, As, Bs = (dev(c.A), dev(c.B), dev(c.As), dev(c.Bs)) if r > 0 else (None, None, None, None)
-    ws = torch.empty(eora.workspace_bytes(M, c.d_in, c.d_out, r), dtype=torch.uint8, device="cuda")
+    ws = eora.new_workspace(M, c.d_in, c.d_out, r) if ws is None else ws
     pad = 64
     ybuf = torch.full((M * c.d_out + 2 * pad,), 777.0, dtype=torch.float16, device="cuda")
     y = ybuf[pad: pad + M * c.d_out]

@@ -116,3 +116,51 @@ def test_config_shapes_fp16_factors(gpu, name, d_in, d_out, w_bits, M):
     c = QCase(synth.seed_for(1 if w_bits == 4 else 2, 0 if name == "q" else 1), d_in, d_out, M, 128, w_bits,
               packer=gpu)
     _check(run_linear_q(c), c.oracle_y())
+
+
+def test_workspace_is_left_clean_and_reusable(gpu):
+    """The counters in the workspace header return to zero after every call, so one workspace
+    serves any number of calls (of different shapes) without being cleared again."""
+    import torch
+    from tests.cases import QCase
+    from tests.gpu_util import run_linear_q
+    big = QCase(21, 1024, 512, 16, 128, 4, packer=gpu)
+    small = QCase(22, 256, 64, 3, 32, 3, packer=gpu)
+    ws = gpu.new_workspace(16, 1024, 512, 128)
+    y1 = run_linear_q(big, ws=ws)
+    hdr = ws[:8192].view(torch.int32).cpu().numpy()
+    assert not hdr.any()
+    y2 = run_linear_q(small, ws=ws)
+    assert not ws[:8192].view(torch.int32).cpu().numpy().any()
+    y3 = run_linear_q(big, ws=ws)
+    assert np.array_equal(y1, y3)
+    _check(y1, big.oracle_y())
+    _check(y2, small.oracle_y())
+    assert gpu.workspace_error(ws) == 0
+
+
+def test_bounded_wait_gives_up_cleanly(gpu):
+    """With a spin limit of 0 a wavefront that finds t not ready yet gives up at once: the kernel
+    still terminates, the workspace reports the timeout, and after re-initialisation it works again."""
+    from tests.cases import QCase
+    from tests.gpu_util import run_linear_q
+    c = QCase(23, 4096, 1024, 1, 128, 4, packer=gpu)
+    ws = gpu.new_workspace(1, 4096, 1024, 128)
+    gpu.debug_set_spin_limit(0)
+    try:
+        run_linear_q(c, ws=ws)
+        status = gpu.workspace_error(ws)
+    finally:
+        gpu.debug_set_spin_limit(1 << 22)
+    assert status in (0, -8)
+    gpu.workspace_init(ws)
+    _check(run_linear_q(c, ws=ws), c.oracle_y())
+    assert gpu.workspace_error(ws) == 0
+
+
+def test_mid_size_token_counts(gpu):
+    """Token counts beyond one launch chunk (256) and ragged blocks."""
+    from tests.cases import QCase
+    from tests.gpu_util import run_linear_q
+    c = QCase(24, 512, 96, 300, 64, 4, packer=gpu)
+    _check(run_linear_q(c), c.oracle_y())
