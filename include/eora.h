@@ -35,9 +35,10 @@
  *      tile*192 + 3*l + d.  Its 32 columns cc form pairs p = cc/2 (h = cc%2: 0 low / 1 high
  *      16-bit half).  Pairs 0..14 sit in word p/5 at bits 16h + 3*(p%5) .. +2.  Bit 15 of each
  *      half carries the last pair: bit b of the code of column 30+h is bit 16h+15 of word b.
- *  zero-points: 4-bit, one per (row, group): word 2*((row/16)*NG + q) + (row%16)/8, nibble
- *      (row%16)%8, with NG = K/group and q = col/group.
- *  scales: fp16, element ((row/16)*NG + q)*16 + row%16.
+ *  zero-points: 4-bit, one per (row, group), row-major, eight groups per 32-bit word: word
+ *      row*NGW + q/8, nibble q%8, with NG = K/group, q = col/group, NGW = ceil(NG/8) (so a lane
+ *      finds the zero-points of four consecutive k-tiles of its row in one word).
+ *  scales: fp16, row-major, element row*NG + q.
  *  F16 (fp16 factor, KT = 32): element (tile*64 + l)*8 + i is column 32*(col/32) + 8*j + i.
  *  SP24 (2:4 sparse fp16, tile = 16 rows x 128 dense columns): lane l owns dense columns
  *      64*s + 16*j + 4*q + p (s = 0,1; q = 0..3 group of four; p = 0..3 position); each group
@@ -80,7 +81,7 @@ const char* eora_status_string(int status);
  * Sizes (HOST, pure functions).  Return 0 for invalid arguments.
  * ------------------------------------------------------------------------------------------ */
 size_t eora_qweight_bytes(int d_in, int d_out, int w_bits);          /* d_out*d_in*w_bits/8 */
-size_t eora_qzeros_bytes(int d_in, int d_out, int group);            /* d_out*(d_in/group)/2 */
+size_t eora_qzeros_bytes(int d_in, int d_out, int group);            /* d_out*ceil(d_in/group/8)*4 */
 size_t eora_scales_bytes(int d_in, int d_out, int group);            /* d_out*(d_in/group)*2 */
 size_t eora_sp24_values_bytes(int d_in, int d_out);                  /* d_out*d_in          */
 size_t eora_sp24_indices_bytes(int d_in, int d_out);                 /* d_out*d_in/8        */

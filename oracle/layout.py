@@ -24,9 +24,10 @@ Q3  (3-bit codes, KT = 128): three words per lane, word index = tile*192 + 3*l +
     half is spare; the spare bits carry the last two codes: bit b of the code
     of column 30 + h is bit 16*h + 15 of word b.
 
-zeros   one nibble per (row, quantisation group): word 2*(R*NG + q) + n // 8,
-        nibble n % 8   (NG = K / group, q = col // group)
-scales  fp16, element (R*NG + q)*16 + n
+zeros   one nibble per (row, quantisation group), row-major, eight groups per
+        32-bit word: word row*NGW + q // 8, nibble q % 8
+        (NG = K / group, q = col // group, NGW = ceil(NG / 8))
+scales  fp16, row-major: element row*NG + q
 
 F16 (fp16 factor, KT = 32): element index = (tile*64 + l)*8 + i for column
     32*g + 8*j + i.
@@ -158,37 +159,32 @@ def unpack_q3(words, rows, K):
 # zero-points and scales of the quantisation groups
 # ----------------------------------------------------------------------------
 def pack_zeros(zeros):
+    """rows x NG zero-points -> uint32 words, row-major, eight groups per word."""
     zeros = np.asarray(zeros)
     rows, NG = zeros.shape
-    if rows % ROWS:
-        raise ValueError("rows must be a multiple of 16")
     if zeros.min(initial=0) < 0 or zeros.max(initial=0) > 15:
         raise ValueError("zero-point out of range")
-    o, q = np.meshgrid(np.arange(rows), np.arange(NG), indexing="ij")
-    R, n = o // ROWS, o % ROWS
-    word = 2 * (R * NG + q) + n // 8
-    out = np.zeros(rows * NG // 8, dtype=np.uint32)
-    np.bitwise_or.at(out, word.ravel(), (zeros.astype(np.uint32) << (4 * (n % 8)).astype(np.uint32)).ravel())
-    return out
+    NGW = (NG + 7) // 8
+    out = np.zeros((rows, NGW), dtype=np.uint32)
+    for q in range(NG):
+        out[:, q // 8] |= zeros[:, q].astype(np.uint32) << np.uint32(4 * (q % 8))
+    return out.reshape(-1)
 
 
 def unpack_zeros(words, rows, NG):
-    words = np.asarray(words, dtype=np.uint32)
-    o, q = np.meshgrid(np.arange(rows), np.arange(NG), indexing="ij")
-    R, n = o // ROWS, o % ROWS
-    word = 2 * (R * NG + q) + n // 8
-    return ((words[word] >> (4 * (n % 8)).astype(np.uint32)) & 0xF).astype(np.uint8)
+    NGW = (NG + 7) // 8
+    words = np.asarray(words, dtype=np.uint32).reshape(rows, NGW)
+    q = np.arange(NG)
+    return ((words[:, q // 8] >> (4 * (q % 8)).astype(np.uint32)[None, :]) & 0xF).astype(np.uint8)
 
 
 def pack_scales(scales):
-    scales = np.asarray(scales, dtype=np.float16)
-    rows, NG = scales.shape
-    return np.ascontiguousarray(scales.reshape(rows // ROWS, ROWS, NG).transpose(0, 2, 1)).reshape(-1)
+    """fp16 scales are stored as they are: row-major rows x NG."""
+    return np.ascontiguousarray(scales, dtype=np.float16).reshape(-1)
 
 
 def unpack_scales(flat, rows, NG):
-    flat = np.asarray(flat, dtype=np.float16)
-    return np.ascontiguousarray(flat.reshape(rows // ROWS, NG, ROWS).transpose(0, 2, 1)).reshape(rows, NG)
+    return np.asarray(flat, dtype=np.float16).reshape(rows, NG)
 
 
 # ----------------------------------------------------------------------------

@@ -10,7 +10,7 @@ namespace {
 
 using namespace eora;
 
-constexpr size_t WS_HEADER = 8192;         // counters (HDR_WORDS 32-bit words), rounded up
+constexpr size_t WS_HEADER = 40960;        // counters and flags (HDR_WORDS 32-bit words)
 constexpr int MAX_RANK = 512;
 constexpr int CHUNK_TOKENS = 16 * MAX_YBLOCKS;      // tokens per launch
 static_assert(HDR_WORDS * 4 <= WS_HEADER, "header too small");
@@ -50,7 +50,7 @@ size_t eora_workspace_bytes(int M, int d_in, int d_out, int r)
     if (check_backbone_shape(M, d_in, d_out, r) != EORA_OK) return 0;
     const size_t mc = (size_t)(M < CHUNK_TOKENS ? M : CHUNK_TOKENS);
     const size_t yblocks = (mc + 15) / 16;
-    return WS_HEADER + round256(mc * r * sizeof(float)) + (size_t)MAX_KCN * (r / 16) * yblocks * 1024;
+    return WS_HEADER + yblocks * MAX_KCN * 16 * (size_t)r * sizeof(float);
 }
 
 int eora_workspace_init(void* workspace, size_t workspace_bytes, void* stream)
@@ -111,11 +111,12 @@ int eora_linear_q(const void* x, const void* qweight, const void* scales, const 
     if (workspace_bytes < eora_workspace_bytes(M, d_in, d_out, r)) return EORA_ERR_WORKSPACE;
     if (M == 0) return EORA_OK;
 
-    // largest divisor of the number of 128-wide k-tiles that is at most MAX_KCN
+    // k-ranges of the down-projection: many for few tokens (every consumer adds the partials itself),
+    // a divisor of the number of 128-wide k-tiles
+    const int cap = M <= 4 ? MAX_KCN : (M <= 8 ? 4 : 2);
     int kcn = 1;
-    for (int c = 2; c <= MAX_KCN; ++c)
+    for (int c = 2; c <= cap; ++c)
         if ((d_in / 128) % c == 0) kcn = c;
-    const size_t t_bytes = round256((size_t)(M < CHUNK_TOKENS ? M : CHUNK_TOKENS) * r * sizeof(float));
     for (int m0 = 0; m0 < M; m0 += CHUNK_TOKENS) {
         FusedArgs a{};
         a.x = (const _Float16*)x + (size_t)m0 * d_in;
@@ -128,8 +129,7 @@ int eora_linear_q(const void* x, const void* qweight, const void* scales, const 
         a.B_scales = (const _Float16*)B_scales;
         a.y = (_Float16*)y + (size_t)m0 * d_out;
         a.hdr = (uint32_t*)workspace;
-        a.t = (float*)((char*)workspace + WS_HEADER);
-        a.tpart = (float*)((char*)workspace + WS_HEADER + t_bytes);
+        a.tpart = (float*)((char*)workspace + WS_HEADER);
         a.M = M - m0 < CHUNK_TOKENS ? M - m0 : CHUNK_TOKENS;
         a.d_in = d_in;
         a.d_out = d_out;

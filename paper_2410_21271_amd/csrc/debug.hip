@@ -38,13 +38,13 @@ __global__ void unpack_q_kernel(const uint32_t* __restrict__ qweight, const _Flo
     const int j = lane >> 4, n = lane & 15;
     const int row = 16 * R + n, col0 = 128 * g + 32 * j;
     const int q = col0 / group;
-    const size_t rq = (size_t)R * NG + q;
-    const uint32_t z = (qzeros[2 * rq + (n >> 3)] >> (4 * (n & 7))) & 0xFu;
+    const int NGW = (NG + 7) / 8;
+    const uint32_t z = (qzeros[(size_t)row * NGW + (q >> 3)] >> (4 * (q & 7))) & 0xFu;
     uint32_t w[4];
     const int wpl = w_bits == 4 ? 4 : 3;
     for (int t = 0; t < wpl; ++t) w[t] = qweight[L * wpl + t];
     float s = 0.f;
-    if (DEQUANT) s = (float)scales[rq * 16 + n];
+    if (DEQUANT) s = (float)scales[(size_t)row * NG + q];
     for (int cc = 0; cc < 32; ++cc) {
         const uint32_t c = w_bits == 4 ? code_q4(w, cc) : code_q3(w, cc);
         const size_t idx = (size_t)row * d_in + col0 + cc;

@@ -9,15 +9,19 @@ namespace eora {
 // stored formats a contraction segment can read
 enum SegFmt { S_NONE = 0, S_Q4 = 1, S_Q3 = 2, S_Q4S128 = 3, S_Q4S64 = 4, S_F16 = 5 };
 
-// Workspace header (32-bit words): global exit counter and error flag, then one block of counters
-// per token block of 16: [0] ticket, [1] ready row blocks of t, [2 .. 2+r/16) arrivals per row block.
-constexpr int HDR_EXIT = 0;
-constexpr int HDR_ERROR = 1;
-constexpr int HDR_BLOCK0 = 64;
-constexpr int HDR_PER_BLOCK = 64;
+// Workspace header (32-bit words).  Counters that different workgroups hit at the same time sit in
+// different 128-byte lines.
+constexpr int HDR_EPOCH = 0;                    // advanced once per low-rank launch
+constexpr int HDR_ERROR = 1;                    // sticky: a bounded wait expired
+constexpr int HDR_TOP = 32;                     // arrival counter of the sub-counters
+constexpr int HDR_SUB0 = 64;                    // HDR_NSUB arrival sub-counters, HDR_SUB_STRIDE words apart
+constexpr int HDR_SUB_STRIDE = 32;
+constexpr int HDR_NSUB = 32;
+constexpr int HDR_FLAGS0 = 2048;                // per token block: one flag per unit of t
+constexpr int HDR_FLAGS_PER_BLOCK = 512;        // (r/16) * kcn <= 32 * 16
 constexpr int MAX_YBLOCKS = 16;                 // token blocks per launch (256 tokens)
-constexpr int HDR_WORDS = HDR_BLOCK0 + HDR_PER_BLOCK * MAX_YBLOCKS;
-constexpr int MAX_KCN = 8;                      // k-chunks of the down-projection
+constexpr int HDR_WORDS = HDR_FLAGS0 + HDR_FLAGS_PER_BLOCK * MAX_YBLOCKS;
+constexpr int MAX_KCN = 16;                     // k-ranges of the down-projection
 
 struct FusedArgs {
     const _Float16* x;        // M x d_in fp16 row-major
@@ -29,9 +33,8 @@ struct FusedArgs {
     const void* B;            // d_out x r tiles
     const _Float16* B_scales;
     _Float16* y;              // M x d_out fp16 row-major
-    uint32_t* hdr;            // workspace header, zero between launches
-    float* t;                 // M x r fp32
-    float* tpart;             // kcn x r/16 x token blocks x 256 fp32 partials of t
+    uint32_t* hdr;            // workspace header
+    float* tpart;             // token blocks x kcn x 16 x r fp32 partials of t
     int M, d_in, d_out, r, group, kcn, spin_limit;
 };
 

@@ -60,12 +60,10 @@ int pack_q3_tiles(const uint8_t* codes, int rows, int K, uint32_t* out)
     return EORA_OK;
 }
 
+// scales are stored as they come: row-major rows x NG
 void pack_scale_tiles(const uint16_t* scales, int rows, int NG, uint16_t* out)
 {
-    for (int R = 0; R < rows / 16; ++R)
-        for (int q = 0; q < NG; ++q)
-            for (int n = 0; n < 16; ++n)
-                out[((size_t)R * NG + q) * 16 + n] = scales[(size_t)(16 * R + n) * NG + q];
+    std::memcpy(out, scales, (size_t)rows * NG * sizeof(uint16_t));
 }
 
 }  // namespace
@@ -81,7 +79,7 @@ size_t eora_qweight_bytes(int d_in, int d_out, int w_bits)
 size_t eora_qzeros_bytes(int d_in, int d_out, int group)
 {
     if (!shape_ok(d_out, d_in, 128) || group <= 0 || group % 128 || d_in % group) return 0;
-    return (size_t)d_out * (d_in / group) / 2;
+    return (size_t)d_out * ((d_in / group + 7) / 8) * 4;
 }
 
 size_t eora_scales_bytes(int d_in, int d_out, int group)
@@ -115,14 +113,14 @@ int eora_pack_q(const uint8_t* codes, const uint8_t* zeros, const uint16_t* scal
                            : pack_q3_tiles(codes, d_out, d_in, (uint32_t*)qweight_out);
     if (rc != EORA_OK) return rc;
     uint32_t* zw = (uint32_t*)qzeros_out;
-    for (int R = 0; R < d_out / 16; ++R)
-        for (int q = 0; q < NG; ++q)
-            for (int hi = 0; hi < 2; ++hi) {
-                uint32_t word = 0;
-                for (int e = 0; e < 8; ++e)
-                    word |= (uint32_t)zeros[(size_t)(16 * R + 8 * hi + e) * NG + q] << (4 * e);
-                zw[2 * ((size_t)R * NG + q) + hi] = word;
-            }
+    const int NGW = (NG + 7) / 8;
+    for (int row = 0; row < d_out; ++row)
+        for (int wq = 0; wq < NGW; ++wq) {
+            uint32_t word = 0;
+            for (int e = 0; e < 8 && 8 * wq + e < NG; ++e)
+                word |= (uint32_t)zeros[(size_t)row * NG + 8 * wq + e] << (4 * e);
+            zw[(size_t)row * NGW + wq] = word;
+        }
     pack_scale_tiles(scales, d_out, NG, (uint16_t*)scales_out);
     return EORA_OK;
 }

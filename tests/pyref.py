@@ -49,22 +49,18 @@ def decode_q3(words, rows, K):
 
 
 def decode_zeros(words, rows, NG):
+    NGW = (NG + 7) // 8
     out = [[None] * NG for _ in range(rows)]
     for w, word in enumerate(int(v) for v in words):
-        rq, hi = divmod(w, 2)
-        R, q = divmod(rq, NG)
+        row, wq = divmod(w, NGW)
         for e in range(8):
-            out[16 * R + 8 * hi + e][q] = (word >> (4 * e)) & 0xF
+            if 8 * wq + e < NG:
+                out[row][8 * wq + e] = (word >> (4 * e)) & 0xF
     return out
 
 
 def decode_scales(flat, rows, NG):
-    out = [[None] * NG for _ in range(rows)]
-    for idx, v in enumerate(flat):
-        rq, n = divmod(idx, 16)
-        R, q = divmod(rq, NG)
-        out[16 * R + n][q] = Fraction(float(v))
-    return out
+    return [[Fraction(float(flat[r * NG + q])) for q in range(NG)] for r in range(rows)]
 
 
 def decode_f16(flat, rows, K):

@@ -40,6 +40,7 @@ def test_sizes():
     assert eora.qweight_bytes(4096, 4096, 4) == 4096 * 4096 // 2
     assert eora.qweight_bytes(4096, 4096, 3) == 4096 * 4096 * 3 // 8
     assert eora.qzeros_bytes(4096, 4096, 128) == 4096 * 32 // 2
+    assert eora.qzeros_bytes(4096, 4096, 4096) == 4096 * 4          # channel-wise: one padded word per row
     assert eora.scales_bytes(4096, 4096, 128) == 4096 * 32 * 2
     assert eora.sp24_values_bytes(8192, 1024) == 8192 * 1024
     assert eora.sp24_indices_bytes(8192, 1024) == 8192 * 1024 // 8

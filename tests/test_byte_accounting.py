@@ -44,6 +44,6 @@ def test_packed_arrays_have_no_padding():
     assert layout.pack_q4(np.zeros((r, d_in), np.uint8), 128).nbytes == r * d_in // 2
     assert layout.pack_q4(np.zeros((d_out, r), np.uint8), 64).nbytes == d_out * r // 2
     assert layout.pack_q3(np.zeros((d_out, d_in), np.uint8)).nbytes == d_out * d_in * 3 // 8
-    assert layout.pack_zeros(np.zeros((d_out, 2), np.uint8)).nbytes == d_out * 2 // 2
+    assert layout.pack_zeros(np.zeros((d_out, 8), np.uint8)).nbytes == d_out * 8 // 2
     v, i = layout.pack_sp24(np.zeros((d_out, d_in // 2), np.float16), np.tile(np.array([0, 1], np.uint8), (d_out, d_in // 4)))
     assert v.nbytes + i.nbytes == d_out * d_in * 9 // 8

@@ -118,9 +118,9 @@ def test_config_shapes_fp16_factors(gpu, name, d_in, d_out, w_bits, M):
     _check(run_linear_q(c), c.oracle_y())
 
 
-def test_workspace_is_left_clean_and_reusable(gpu):
-    """The counters in the workspace header return to zero after every call, so one workspace
-    serves any number of calls (of different shapes) without being cleared again."""
+def test_workspace_is_reusable_without_clearing(gpu):
+    """Nothing in the workspace is reset between calls: flags are compared with an epoch that each
+    low-rank launch advances by one, so one workspace serves any number of calls of any shapes."""
     import torch
     from tests.cases import QCase
     from tests.gpu_util import run_linear_q
@@ -128,14 +128,16 @@ def test_workspace_is_left_clean_and_reusable(gpu):
     small = QCase(22, 256, 64, 3, 32, 3, packer=gpu)
     ws = gpu.new_workspace(16, 1024, 512, 128)
     y1 = run_linear_q(big, ws=ws)
-    hdr = ws[:8192].view(torch.int32).cpu().numpy()
-    assert not hdr.any()
     y2 = run_linear_q(small, ws=ws)
-    assert not ws[:8192].view(torch.int32).cpu().numpy().any()
+    y0 = run_linear_q(big, ws=ws, r=0)            # no low-rank path: does not touch the header
     y3 = run_linear_q(big, ws=ws)
+    hdr = ws[:256].view(torch.int32).cpu().numpy()
+    assert hdr[0] == 3 and hdr[1] == 0            # epoch after three low-rank launches, no error
+    assert not ws[128:128 + 33 * 128].view(torch.int32).cpu().numpy().any()      # arrival counters back at zero
     assert np.array_equal(y1, y3)
     _check(y1, big.oracle_y())
     _check(y2, small.oracle_y())
+    _check(y0, big.oracle_y(r=0))
     assert gpu.workspace_error(ws) == 0
 
 

@@ -73,11 +73,11 @@ def test_sp24_value_positions_by_hand():
 
 def test_scales_and_f16_positions_by_hand():
     s = np.zeros((32, 2), np.float16)
-    s[20, 1] = 3.0          # (R*NG+q)*16+n = (1*2+1)*16+4 = 52
+    s[20, 1] = 3.0          # row-major: 20*2+1 = 41
     s[0, 0] = 1.5           # element 0
-    s[15, 1] = 0.25         # (0*2+1)*16+15 = 31
+    s[15, 1] = 0.25         # 31
     flat = layout.pack_scales(s)
-    assert {int(i): float(flat[i]) for i in np.nonzero(flat)[0]} == {52: 3.0, 0: 1.5, 31: 0.25}
+    assert {int(i): float(flat[i]) for i in np.nonzero(flat)[0]} == {41: 3.0, 0: 1.5, 31: 0.25}
     assert np.array_equal(layout.unpack_scales(flat, 32, 2), s)
     m = np.zeros((16, 64), np.float16)
     m[2, 45] = 9.0          # tile 1, j=1, i=5 -> (64 + 18)*8 + 5 = 661
@@ -119,7 +119,8 @@ def test_zeros_scales_roundtrip():
     rng = np.random.default_rng(5)
     z = rng.integers(0, 16, (48, 3), dtype=np.uint8)
     w = layout.pack_zeros(z)
-    assert w.size == 48 * 3 // 8
+    assert w.size == 48                                   # one (padded) word per row when NG <= 8
+    assert layout.pack_zeros(np.zeros((48, 32), np.uint8)).nbytes == 48 * 32 // 2    # no padding when NG % 8 == 0
     assert np.array_equal(layout.unpack_zeros(w, 48, 3), z)
     assert np.array_equal(np.array(pyref.decode_zeros(w, 48, 3), dtype=np.uint8), z)
     s = rng.standard_normal((48, 3)).astype(np.float16)
