@@ -137,8 +137,11 @@ int eora_linear_q(const void* x, const void* qweight, const void* scales, const 
         a.group = group;
         a.kcn = kcn;
         a.spin_limit = g_spin_limit;
-        if (failed(launch_fused(a, w_bits == 4 ? S_Q4 : S_Q3, fa, fe, (hipStream_t)stream), "linear_q"))
-            return EORA_ERR_LAUNCH;
+        int nw = 0, nq = 0;
+        const int fm = w_bits == 4 ? S_Q4 : S_Q3;
+        const hipError_t e = small_kernel_fits(a, &nw, &nq) ? launch_small(a, fm, fa, fe, nw, nq, (hipStream_t)stream)
+                                                            : launch_fused(a, fm, fa, fe, (hipStream_t)stream);
+        if (failed(e, "linear_q")) return EORA_ERR_LAUNCH;
     }
     return EORA_OK;
 }

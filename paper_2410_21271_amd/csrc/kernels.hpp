@@ -21,7 +21,7 @@ constexpr int HDR_FLAGS0 = 2048;                // per token block: one flag per
 constexpr int HDR_FLAGS_PER_BLOCK = 512;        // (r/16) * kcn <= 32 * 16
 constexpr int MAX_YBLOCKS = 16;                 // token blocks per launch (256 tokens)
 constexpr int HDR_WORDS = HDR_FLAGS0 + HDR_FLAGS_PER_BLOCK * MAX_YBLOCKS;
-constexpr int MAX_KCN = 16;                     // k-ranges of the down-projection
+constexpr int MAX_KCN = 8;                      // k-ranges of the down-projection
 
 struct FusedArgs {
     const _Float16* x;        // M x d_in fp16 row-major
@@ -39,6 +39,9 @@ struct FusedArgs {
 };
 
 hipError_t launch_fused(const FusedArgs& a, int fm, int fa, int fe, hipStream_t stream);
+// decode kernel for 1..4 tokens (small.hip): whether the shape fits, with its wavefront / quad split
+bool small_kernel_fits(const FusedArgs& a, int* nw, int* nq);
+hipError_t launch_small(const FusedArgs& a, int fm, int fa, int fe, int nw, int nq, hipStream_t stream);
 hipError_t launch_clear_words(uint32_t* p, int nwords, hipStream_t stream);
 
 hipError_t launch_unpack_q(const uint32_t* qweight, const uint32_t* qzeros, uint8_t* codes, uint8_t* zeros,

@@ -1,0 +1,331 @@
+// Decode kernel for one to four tokens: the same layer as fused.hip,
+//
+//      y = x.What^T + (x.A^T).B^T          (Sec. 3 forward equation, Alg. 1 step 7)
+//
+// written as straight-line code for the shapes where the contraction dimension is an exact number
+// of quads per wavefront (d_in / 512 == NW * NQ).  Nothing a load depends on is behind a divergent
+// branch: out-of-range lanes read clamped (valid) addresses and their results are never stored, so
+// the compiler can keep every request of a wavefront in flight and consume tiles as they arrive.
+//
+// Roles are split by workgroup index.  The first `units` workgroups are PRODUCERS: each computes one
+// unit of t = x.A^T ((16 rows of A) x (one of kcn ranges of k-tiles)), writes its fp32 partial
+// through to memory and raises flag[u] = epoch + 1; it owns no output rows, so nothing waits on its
+// critical path but the consumers.  The other workgroups are CONSUMERS: one strip of 16 output rows
+// each; backbone first, then one wavefront polls the flags, adds the kcn partials in a fixed order
+// into t (fp32, in LDS), and the wavefronts that own tiles of B continue the same accumulators with
+// t split into a high and a low fp16 part.  Producers come first in dispatch order and never wait.
+#include "segments.hpp"
+
+namespace eora {
+
+constexpr int XSTAGE = 4;   // 16-byte chunks of x a thread may stage
+
+template <int FM, int FA, int FE, int NW, int NQ>
+__global__ __launch_bounds__(NW * 64) void small_kernel(FusedArgs a)
+{
+    constexpr bool LOWRANK = FA != S_NONE;
+    constexpr int NT = NW * 64;
+    constexpr int WORDS = Fmt<FM>::WORDS;
+    __shared__ float red[NW][4][16];
+    __shared__ uint32_t s_epoch, s_ok;
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int n = lane & 15, j = lane >> 4;
+    const int mt = a.M;                                  // 1..4 tokens, one token block
+    const int mrow = n < mt ? n : 0;                     // lanes beyond the tokens re-read row 0; their results are dropped
+    const int nprod = LOWRANK ? (a.r / 16) * a.kcn : 0;  // producer workgroups
+    const int ldxs = a.d_in + 32;                        // LDS row stride of x in halves (64 bytes of padding)
+    _Float16* xs = (_Float16*)eora_smem;
+    float* ts = (float*)(eora_smem + (size_t)mt * ldxs * 2);     // t, fp32 mt x r (consumers)
+
+    CheckIn ci{0u, 0u, 0u};
+    if constexpr (LOWRANK) {
+        if (tid == 0) check_in_load(ci, a.hdr);          // first request of the kernel: it returns first
+    }
+
+    // ---- x: requested first, by everyone ---------------------------------------------------------
+    const int xchunks = a.d_in / 8, xtotal = mt * xchunks;
+    u4 xstage[XSTAGE];
+    int xc[XSTAGE];
+#pragma unroll
+    for (int k = 0; k < XSTAGE; ++k) {
+        const int c = tid + k * NT;
+        xc[k] = c < xtotal ? c : xtotal - 1;             // surplus threads duplicate the last chunk
+        xstage[k] = *((const u4*)(a.x + (size_t)(xc[k] / xchunks) * a.d_in) + xc[k] % xchunks);
+    }
+
+    if constexpr (LOWRANK) {
+    if ((int)blockIdx.x < nprod) {
+        // ======================================================================= producer
+        constexpr int KTA = Fmt<FA>::KT, NMF = KTA / 32;
+        const int NRB = a.r / 16;
+        const int u = blockIdx.x, rho = u % NRB, kc = u / NRB;
+        const Factor fa{(const uint32_t*)a.A, a.A_scales, a.d_in / KTA};
+        const int tpc = fa.ntk / a.kcn;                  // k-tiles of this unit
+        const int first = kc * tpc + wave;
+        const int nsteps = wave < tpc ? (tpc - wave + NW - 1) / NW : 0;
+        constexpr int PD = 4;
+        FTile<FA> buf[PD];
+#pragma unroll
+        for (int s = 0; s < PD; ++s) {
+            const int ss = s < nsteps ? s : (nsteps > 0 ? nsteps - 1 : 0);
+            load_ftile<FA>(buf[s], fa, rho, (nsteps > 0 ? first : kc * tpc) + ss * NW, lane);
+        }
+        if (tid == 0) {
+            check_in_issue(ci, a.hdr, blockIdx.x);
+            s_epoch = ci.epoch;
+        }
+#pragma unroll
+        for (int k = 0; k < XSTAGE; ++k) *(u4*)(xs + (size_t)(xc[k] / xchunks) * ldxs + (xc[k] % xchunks) * 8) = xstage[k];
+        __syncthreads();
+        const uint32_t epoch = s_epoch;
+        f4 acc = {0.f, 0.f, 0.f, 0.f};
+        for (int base = 0; base < nsteps; base += PD) {
+#pragma unroll
+            for (int s = 0; s < PD; ++s) {
+                if (base + s < nsteps) {
+                    const FTile<FA> cur = buf[s];
+                    const int g = first + (base + s) * NW;
+                    if (base + s + PD < nsteps) load_ftile<FA>(buf[s], fa, rho, first + (base + s + PD) * NW, lane);
+                    h8 xa[NMF], b[NMF];
+                    const _Float16* px = xs + mrow * ldxs + g * KTA + (KTA / 4) * j;
+#pragma unroll
+                    for (int t = 0; t < NMF; ++t) xa[t] = *(const h8*)(px + 8 * t);
+                    decode_tile<FA>(cur.w, 8u, b);
+                    if constexpr (FA == S_F16) {
+                        acc = mfma16(xa[0], b[0], acc);
+                    } else {
+                        f4 part = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                        for (int t = 0; t < NMF; ++t) part = mfma16(xa[t], b[t], part);
+                        acc += (float)cur.sc * part;
+                    }
+                }
+            }
+        }
+        // token rows 0..3 live in lanes j == 0, register i = row
+        if (j == 0) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) red[wave][i][n] = acc[i];
+        }
+        __syncthreads();
+        if (tid < 16 * mt) {
+            const int i = tid >> 4, col = tid & 15;
+            float v = 0.f;
+#pragma unroll
+            for (int w2 = 0; w2 < NW; ++w2) v += red[w2][i][col];
+            // partial layout: [kc][token row (16)][r]; written through to memory (system scope)
+            *(volatile float*)&a.tpart[((size_t)kc * 16 + i) * a.r + 16 * rho + col] = v;
+        }
+        // wait until the write-through stores are acknowledged (at system scope: in memory), so that
+        // the flag below cannot overtake them; no L2 write-back of an agent-scope release is needed
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (tid == 0) {
+            __hip_atomic_store(&a.hdr[HDR_FLAGS0 + u], epoch + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            check_in_finish(ci, a.hdr, gridDim.x);
+        }
+        return;
+    }
+    }
+
+    // =========================================================================== consumer
+    const int R = blockIdx.x - nprod;
+    const size_t row = (size_t)R * 16 + n;
+    const int G = a.d_in / 128;                          // == 4 * NW * NQ, one quantisation group per k-tile
+    uint2 sc[NQ];
+    uint32_t zq[NQ];
+    uint32_t wd[NQ][4][WORDS];
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) {
+        const int g0 = 4 * (wave + q * NW);
+        sc[q] = *(const uint2*)(a.w_scales + row * G + g0);
+        zq[q] = a.w_zeros[row * (G / 8) + (g0 >> 3)];
+    }
+    const Factor fb{(const uint32_t*)a.B, a.B_scales, LOWRANK ? a.r / Fmt<LOWRANK ? FE : S_F16>::KT : 0};
+    FTile<LOWRANK ? FE : S_F16> bpre;
+    if constexpr (LOWRANK) load_ftile<FE>(bpre, fb, R, wave < fb.ntk ? wave : 0, lane);
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const size_t tile = (size_t)R * G + 4 * (wave + q * NW) + i;
+            load_words<WORDS>(wd[q][i], (const uint32_t*)a.w + (tile * 64 + lane) * WORDS);
+        }
+    }
+    if constexpr (LOWRANK) {
+        if (tid == 0) {
+            check_in_issue(ci, a.hdr, blockIdx.x);
+            s_epoch = ci.epoch;
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < XSTAGE; ++k) *(u4*)(xs + (size_t)(xc[k] / xchunks) * ldxs + (xc[k] % xchunks) * 8) = xstage[k];
+    __syncthreads();
+
+    // ---- backbone ------------------------------------------------------------------------------------
+    f4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) {
+        const int g0 = 4 * (wave + q * NW);
+        const uint32_t z4 = zq[q] >> (4 * (g0 & 7));
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            h8 xa[4], b[4];
+            const _Float16* px = xs + mrow * ldxs + (g0 + i) * 128 + 32 * j;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) xa[t] = *(const h8*)(px + 8 * t);
+            decode_tile<FM>(wd[q][i], (z4 >> (4 * i)) & 0xFu, b);
+            f4 part = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int t = 0; t < 4; ++t) part = mfma16(xa[t], b[t], part);
+            const uint32_t sw = (i < 2) ? sc[q].x : sc[q].y;
+            const _Float16 s16 = __builtin_bit_cast(_Float16, (uint16_t)((i & 1) ? (sw >> 16) : (sw & 0xFFFFu)));
+            acc += (float)s16 * part;                    // exact integers times x, scaled once per group in fp32
+        }
+    }
+
+    // ---- low-rank continuation ---------------------------------------------------------------------
+    if constexpr (LOWRANK) {
+        const uint32_t epoch = s_epoch;
+        if (wave == 0) {
+            const uint32_t* flags = a.hdr + HDR_FLAGS0;
+            bool ok = false;
+            for (int spins = 0; spins <= a.spin_limit; ++spins) {
+                bool all = true;
+                for (int f = lane; f < nprod; f += 64) all = all && (ld_relaxed(&flags[f]) == epoch + 1);
+                if (__all(all)) { ok = true; break; }
+                __builtin_amdgcn_s_sleep(2);
+            }
+            if (ok) {
+                // Ordinary (cached) loads, no agent-scope acquire fence: the partials were written
+                // through to memory before their flags, no line of them is read in this launch before
+                // all flags are up, and caches hold nothing of them from before the launch.
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+                const int T = mt * a.r;                  // elements of t; a.r is a multiple of 32
+                for (int e = 4 * lane; e < T; e += 256) {
+                    const int i = e / a.r, col = e % a.r;
+                    const float* p = a.tpart + (size_t)i * a.r + col;
+                    f4 v = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
+                    for (int kc = 0; kc < a.kcn; ++kc) v += *(const f4*)(p + (size_t)kc * 16 * a.r);   // fixed order
+                    *(f4*)(ts + e) = v;
+                }
+            }
+            if (lane == 0) {
+                s_ok = ok ? 1u : 0u;
+                if (!ok) atomicOr(&a.hdr[HDR_ERROR], 1u);          // never expected: producers do not wait
+            }
+        }
+        __syncthreads();
+        if (s_ok) {
+            constexpr int KTB = Fmt<FE>::KT, NMF = KTB / 32;
+            for (int g = wave; g < fb.ntk; g += NW) {
+                FTile<FE> cur;
+                if (g == wave) cur = bpre;
+                else load_ftile<FE>(cur, fb, R, g, lane);
+                h8 b[NMF];
+                decode_tile<FE>(cur.w, 8u, b);
+                f4 part = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int q = 0; q < NMF; ++q) {
+                    const float* p = ts + mrow * a.r + g * KTB + (KTB / 4) * j + 8 * q;
+                    const f4 v0 = *(const f4*)p, v1 = *(const f4*)(p + 4);
+                    h8 hi, lo;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const _Float16 h0 = (_Float16)v0[i], h1 = (_Float16)v1[i];
+                        hi[i] = h0;
+                        hi[4 + i] = h1;
+                        lo[i] = (_Float16)(v0[i] - (float)h0);
+                        lo[4 + i] = (_Float16)(v1[i] - (float)h1);
+                    }
+                    part = mfma16(hi, b[q], part);
+                    part = mfma16(lo, b[q], part);
+                }
+                acc += (float)cur.sc * part;
+            }
+        }
+    }
+
+    // ---- combine, convert, store -------------------------------------------------------------------
+    if (j == 0) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) red[wave][i][n] = acc[i];
+    }
+    __syncthreads();
+    if (tid < 16 * mt) {
+        const int i = tid >> 4, col = tid & 15;
+        float v = 0.f;
+#pragma unroll
+        for (int w2 = 0; w2 < NW; ++w2) v += red[w2][i][col];
+        a.y[(size_t)i * a.d_out + R * 16 + col] = (_Float16)v;
+    }
+    if constexpr (LOWRANK) {
+        if (tid == 0) check_in_finish(ci, a.hdr, gridDim.x);
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+template <int FM, int FA, int FE, int NW, int NQ>
+static hipError_t launch_small_one(const FusedArgs& a, hipStream_t stream)
+{
+    auto kern = small_kernel<FM, FA, FE, NW, NQ>;
+    const size_t lds = (size_t)a.M * (a.d_in + 32) * 2 + (size_t)a.M * a.r * 4;
+    if (lds > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    const int nprod = (FA != S_NONE) ? (a.r / 16) * a.kcn : 0;
+    hipLaunchKernelGGL(kern, dim3(a.d_out / 16 + nprod), dim3(NW * 64), lds, stream, a);
+    return hipGetLastError();
+}
+
+template <int FM, int FA, int FE>
+static hipError_t launch_small_shape(const FusedArgs& a, int nw, int nq, hipStream_t stream)
+{
+    if (nw == 8 && nq == 1) return launch_small_one<FM, FA, FE, 8, 1>(a, stream);
+    if (nw == 8 && nq == 2) return launch_small_one<FM, FA, FE, 8, 2>(a, stream);
+    if (nw == 14 && nq == 2) return launch_small_one<FM, FA, FE, 14, 2>(a, stream);
+    if (nw == 14 && nq == 4) return launch_small_one<FM, FA, FE, 14, 4>(a, stream);
+    if (nw == 4 && nq == 1) return launch_small_one<FM, FA, FE, 4, 1>(a, stream);
+    return hipErrorInvalidValue;
+}
+
+template <int FM>
+static hipError_t launch_small_ab(const FusedArgs& a, int fa, int fe, int nw, int nq, hipStream_t stream)
+{
+    if (fe == S_NONE) return launch_small_shape<FM, S_NONE, S_NONE>(a, nw, nq, stream);
+    if (fa == S_F16 && fe == S_F16) return launch_small_shape<FM, S_F16, S_F16>(a, nw, nq, stream);
+    if (fa == S_Q4S128 && fe == S_Q4S128) return launch_small_shape<FM, S_Q4S128, S_Q4S128>(a, nw, nq, stream);
+    if (fa == S_Q4S128 && fe == S_Q4S64) return launch_small_shape<FM, S_Q4S128, S_Q4S64>(a, nw, nq, stream);
+    return hipErrorInvalidValue;
+}
+
+// Shapes this kernel takes: 1..4 tokens, one quantisation group per k-tile, d_in / 512 an exact
+// number of quads per wavefront from the table below, x small enough to stage.
+bool small_kernel_fits(const FusedArgs& a, int* nw, int* nq)
+{
+    if (a.M < 1 || a.M > 4 || a.group != 128 || a.d_in % 512) return false;
+    const int Q = a.d_in / 512;
+    static const int table[][2] = {{8, 1}, {14, 2}, {8, 2}, {14, 4}, {4, 1}};
+    for (const auto& t : table) {
+        if (t[0] * t[1] == Q && (size_t)a.M * (a.d_in / 8) <= (size_t)XSTAGE * t[0] * 64) {
+            *nw = t[0];
+            *nq = t[1];
+            return true;
+        }
+    }
+    return false;
+}
+
+hipError_t launch_small(const FusedArgs& a, int fm, int fa, int fe, int nw, int nq, hipStream_t stream)
+{
+    switch (fm) {
+        case S_Q4: return launch_small_ab<S_Q4>(a, fa, fe, nw, nq, stream);
+        case S_Q3: return launch_small_ab<S_Q3>(a, fa, fe, nw, nq, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace eora
