@@ -16,9 +16,18 @@
 // t split into a high and a low fp16 part.  Producers come first in dispatch order and never wait.
 #include "segments.hpp"
 
+#include <cstdlib>
+
 namespace eora {
 
 constexpr int XSTAGE = 4;   // 16-byte chunks of x a thread may stage
+
+#ifdef EORA_TIMELINE
+// debug build only: per-workgroup time stamps (100 MHz counter) behind the partials of t
+#define TL_STAMP(slot) do { if (tid == 0) ((unsigned long long*)(a.tpart + (1 << 20)))[blockIdx.x * 8 + (slot)] = wall_clock64(); } while (0)
+#else
+#define TL_STAMP(slot) do { } while (0)
+#endif
 
 template <int FM, int FA, int FE, int NW, int NQ>
 __global__ __launch_bounds__(NW * 64) void small_kernel(FusedArgs a)
@@ -39,6 +48,7 @@ __global__ __launch_bounds__(NW * 64) void small_kernel(FusedArgs a)
     float* ts = (float*)(eora_smem + (size_t)mt * ldxs * 2);     // t, fp32 mt x r (consumers)
 
     CheckIn ci{0u, 0u, 0u};
+    TL_STAMP(0);
     if constexpr (LOWRANK) {
         if (tid == 0) check_in_load(ci, a.hdr);          // first request of the kernel: it returns first
     }
@@ -78,6 +88,7 @@ __global__ __launch_bounds__(NW * 64) void small_kernel(FusedArgs a)
 #pragma unroll
         for (int k = 0; k < XSTAGE; ++k) *(u4*)(xs + (size_t)(xc[k] / xchunks) * ldxs + (xc[k] % xchunks) * 8) = xstage[k];
         __syncthreads();
+        TL_STAMP(1);
         const uint32_t epoch = s_epoch;
         f4 acc = {0.f, 0.f, 0.f, 0.f};
         for (int base = 0; base < nsteps; base += PD) {
@@ -109,6 +120,7 @@ __global__ __launch_bounds__(NW * 64) void small_kernel(FusedArgs a)
             for (int i = 0; i < 4; ++i) red[wave][i][n] = acc[i];
         }
         __syncthreads();
+        TL_STAMP(2);
         if (tid < 16 * mt) {
             const int i = tid >> 4, col = tid & 15;
             float v = 0.f;
@@ -121,6 +133,7 @@ __global__ __launch_bounds__(NW * 64) void small_kernel(FusedArgs a)
         // the flag below cannot overtake them; no L2 write-back of an agent-scope release is needed
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
+        TL_STAMP(3);
         if (tid == 0) {
             __hip_atomic_store(&a.hdr[HDR_FLAGS0 + u], epoch + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             check_in_finish(ci, a.hdr, gridDim.x);
@@ -163,6 +176,7 @@ __global__ __launch_bounds__(NW * 64) void small_kernel(FusedArgs a)
     for (int k = 0; k < XSTAGE; ++k) *(u4*)(xs + (size_t)(xc[k] / xchunks) * ldxs + (xc[k] % xchunks) * 8) = xstage[k];
     __syncthreads();
 
+    TL_STAMP(1);
     // ---- backbone ------------------------------------------------------------------------------------
     f4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -185,6 +199,7 @@ __global__ __launch_bounds__(NW * 64) void small_kernel(FusedArgs a)
         }
     }
 
+    TL_STAMP(2);
     // ---- low-rank continuation ---------------------------------------------------------------------
     if constexpr (LOWRANK) {
         const uint32_t epoch = s_epoch;
@@ -197,6 +212,7 @@ __global__ __launch_bounds__(NW * 64) void small_kernel(FusedArgs a)
                 if (__all(all)) { ok = true; break; }
                 __builtin_amdgcn_s_sleep(2);
             }
+            TL_STAMP(4);
             if (ok) {
                 // Ordinary (cached) loads, no agent-scope acquire fence: the partials were written
                 // through to memory before their flags, no line of them is read in this launch before
@@ -212,6 +228,7 @@ __global__ __launch_bounds__(NW * 64) void small_kernel(FusedArgs a)
                     *(f4*)(ts + e) = v;
                 }
             }
+            TL_STAMP(5);
             if (lane == 0) {
                 s_ok = ok ? 1u : 0u;
                 if (!ok) atomicOr(&a.hdr[HDR_ERROR], 1u);          // never expected: producers do not wait
@@ -261,6 +278,7 @@ __global__ __launch_bounds__(NW * 64) void small_kernel(FusedArgs a)
         for (int w2 = 0; w2 < NW; ++w2) v += red[w2][i][col];
         a.y[(size_t)i * a.d_out + R * 16 + col] = (_Float16)v;
     }
+    TL_STAMP(6);
     if constexpr (LOWRANK) {
         if (tid == 0) check_in_finish(ci, a.hdr, gridDim.x);
     }
@@ -289,6 +307,9 @@ static hipError_t launch_small_shape(const FusedArgs& a, int nw, int nq, hipStre
     if (nw == 14 && nq == 2) return launch_small_one<FM, FA, FE, 14, 2>(a, stream);
     if (nw == 14 && nq == 4) return launch_small_one<FM, FA, FE, 14, 4>(a, stream);
     if (nw == 4 && nq == 1) return launch_small_one<FM, FA, FE, 4, 1>(a, stream);
+    if (nw == 4 && nq == 2) return launch_small_one<FM, FA, FE, 4, 2>(a, stream);
+    if (nw == 7 && nq == 4) return launch_small_one<FM, FA, FE, 7, 4>(a, stream);
+    if (nw == 16 && nq == 1) return launch_small_one<FM, FA, FE, 16, 1>(a, stream);
     return hipErrorInvalidValue;
 }
 
@@ -308,7 +329,18 @@ bool small_kernel_fits(const FusedArgs& a, int* nw, int* nq)
 {
     if (a.M < 1 || a.M > 4 || a.group != 128 || a.d_in % 512) return false;
     const int Q = a.d_in / 512;
-    static const int table[][2] = {{8, 1}, {14, 2}, {8, 2}, {14, 4}, {4, 1}};
+    static const int table[][2] = {{4, 2}, {7, 4}, {8, 2}, {14, 4}, {4, 1}, {8, 1}, {14, 2}, {16, 1}};   // first match wins
+    const char* force = getenv("EORA_SMALL_NW");         // experiment knob: preferred wavefront count
+    const int want = force ? atoi(force) : 0;
+    if (want) {
+        for (const auto& t : table) {
+            if (t[0] == want && t[0] * t[1] == Q && (size_t)a.M * (a.d_in / 8) <= (size_t)XSTAGE * t[0] * 64) {
+                *nw = t[0];
+                *nq = t[1];
+                return true;
+            }
+        }
+    }
     for (const auto& t : table) {
         if (t[0] * t[1] == Q && (size_t)a.M * (a.d_in / 8) <= (size_t)XSTAGE * t[0] * 64) {
             *nw = t[0];
