@@ -151,9 +151,42 @@ int eora_linear_sp24(const void* x, const void* values, const void* indices,
                      int M, int d_in, int d_out, int r,
                      void* workspace, size_t workspace_bytes, void* stream)
 {
-    (void)x; (void)values; (void)indices; (void)A; (void)B; (void)y; (void)M; (void)d_in; (void)d_out; (void)r;
-    (void)workspace; (void)workspace_bytes; (void)stream;
-    return EORA_ERR_UNSUPPORTED;
+    if (!x || !values || !indices || !y) return EORA_ERR_NULL;
+    int rc = check_backbone_shape(M, d_in, d_out, r);
+    if (rc != EORA_OK) return rc;
+    if (r > 0) {
+        if (!A || !B) return EORA_ERR_NULL;
+        if (r % 32) return EORA_ERR_SHAPE;
+        if (!aligned16(A) || !aligned16(B)) return EORA_ERR_ALIGN;
+    }
+    if (!aligned16(x) || !aligned16(values) || !aligned16(indices) || !aligned16(y)) return EORA_ERR_ALIGN;
+    if (!workspace) return EORA_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return EORA_ERR_ALIGN;
+    if (workspace_bytes < eora_workspace_bytes(M, d_in, d_out, r)) return EORA_ERR_WORKSPACE;
+    if (M == 0) return EORA_OK;
+    const int cap = M <= 4 ? MAX_KCN : (M <= 8 ? 4 : 2);
+    int kcn = 1;
+    for (int c = 2; c <= cap; ++c)
+        if ((d_in / 128) % c == 0) kcn = c;
+    for (int m0 = 0; m0 < M; m0 += CHUNK_TOKENS) {
+        SparseArgs a{};
+        a.x = (const _Float16*)x + (size_t)m0 * d_in;
+        a.values = (const _Float16*)values;
+        a.indices = (const uint32_t*)indices;
+        a.A = A;
+        a.B = B;
+        a.y = (_Float16*)y + (size_t)m0 * d_out;
+        a.hdr = (uint32_t*)workspace;
+        a.tpart = (float*)((char*)workspace + WS_HEADER);
+        a.M = M - m0 < CHUNK_TOKENS ? M - m0 : CHUNK_TOKENS;
+        a.d_in = d_in;
+        a.d_out = d_out;
+        a.r = r;
+        a.kcn = kcn;
+        a.spin_limit = g_spin_limit;
+        if (failed(launch_sparse(a, (hipStream_t)stream), "linear_sp24")) return EORA_ERR_LAUNCH;
+    }
+    return EORA_OK;
 }
 
 int eora_unpack_q(const void* qweight, const void* qzeros, void* codes_u8, void* zeros_u8,

@@ -44,6 +44,20 @@ bool small_kernel_fits(const FusedArgs& a, int* nw, int* nq);
 hipError_t launch_small(const FusedArgs& a, int fm, int fa, int fe, int nw, int nq, hipStream_t stream);
 hipError_t launch_clear_words(uint32_t* p, int nwords, hipStream_t stream);
 
+struct SparseArgs {
+    const _Float16* x;        // M x d_in fp16 row-major
+    const _Float16* values;   // SP24 kept values
+    const uint32_t* indices;  // SP24 positions
+    const void* A;            // r x d_in F16 tiles
+    const void* B;            // d_out x r F16 tiles
+    _Float16* y;              // M x d_out fp16 row-major
+    uint32_t* hdr;            // workspace header
+    float* tpart;             // token blocks x kcn x 16 x r fp32 partials of t
+    int M, d_in, d_out, r, kcn, spin_limit;
+};
+
+hipError_t launch_sparse(const SparseArgs& a, hipStream_t stream);
+
 hipError_t launch_unpack_q(const uint32_t* qweight, const uint32_t* qzeros, uint8_t* codes, uint8_t* zeros,
                            int d_in, int d_out, int w_bits, int group, hipStream_t stream);
 hipError_t launch_dequant_q(const uint32_t* qweight, const _Float16* scales, const uint32_t* qzeros, float* W,

@@ -1,0 +1,288 @@
+// The compensated layer with a 2:4 structured-sparse fp16 backbone (Sec. 1 and Sec. 4.2 of the
+// paper use 2:4 as the pruning format that hardware accelerates):
+//
+//      y = x.What^T + (x.A^T).B^T          (Sec. 3 forward equation, Alg. 1 step 7)
+//
+// HBM-bound: 1.125 bytes per dense weight position are read once.  The stored tile of a wavefront
+// (16 rows x 128 dense columns: per lane two 16-byte groups of kept values and one word of 2-bit
+// positions) is exactly the sparse operand of two v_smfmac_f32_16x16x64_f16, so nothing is expanded
+// or decoded: the matrix core skips the pruned positions.  The instruction wants the sparse matrix
+// as its row operand, hence the accumulator is D[output row][token] here (lane l: rows 4*(l/16)+i,
+// token l%16), the transpose of the quantised kernels' orientation.  Per lane the dense operand of
+// block s is x[64s + 8j .. +7] and x[64s + 32 + 8j .. +7] (j = l/16).
+//
+// Launch structure, flag protocol and the low-rank continuation are those of the decode kernel:
+// producer workgroups first (one unit of t = x.A^T each, per token block), then one consumer
+// workgroup per (16 output rows, token block of 16).  For 1..4 tokens x is staged in LDS by direct
+// global-to-LDS loads (no registers); otherwise the fragments come from global memory.
+#include "segments.hpp"
+
+namespace eora {
+
+struct SpTile {
+    u4 v0, v1;        // kept values of the two 64-column blocks
+    uint32_t idx;     // positions: low 16 bits block 0, high 16 bits block 1
+};
+
+typedef _Float16 h16 __attribute__((ext_vector_type(16)));
+
+__device__ __forceinline__ void load_sptile(SpTile& t, const _Float16* __restrict__ values,
+                                            const uint32_t* __restrict__ indices, size_t tile, int lane)
+{
+    t.idx = indices[tile * 64 + lane];
+    const u4* p = (const u4*)(values + tile * 1024) + lane;
+    t.v0 = p[0];
+    t.v1 = p[64];
+}
+
+__device__ __forceinline__ h8 as_h8(u4 v) { return __builtin_bit_cast(h8, v); }
+
+// direct global -> LDS copy of the token block's x (mt rows of d_in fp16, d_in a multiple of 512):
+// one 1 KiB chunk per wavefront instruction, rows padded by 64 bytes in LDS
+template <int NW>
+__device__ __forceinline__ void stage_x_dma(const _Float16* __restrict__ x, int mt, int d_in, int wave, int lane)
+{
+    const int cpr = d_in / 512;                           // chunks per row
+    const int total = mt * cpr;
+    for (int c = wave; c < total; c += NW) {
+        const int row = c / cpr, cc = c % cpr;
+        __builtin_amdgcn_global_load_lds(
+            (const __attribute__((address_space(1))) void*)(x + (size_t)row * d_in + cc * 512 + lane * 8),
+            (__attribute__((address_space(3))) void*)(eora_smem + (size_t)row * (d_in + 32) * 2 + cc * 1024), 16, 0, 0);
+    }
+}
+
+template <int FA, int FE, int NW, bool XLDS>
+__global__ __launch_bounds__(NW * 64) void sparse_kernel(SparseArgs a)
+{
+    constexpr bool LOWRANK = FA != S_NONE;
+    constexpr int PD = 4;                                 // tiles of loads in flight per wavefront
+    __shared__ f4 red[NW][64];
+    __shared__ float redp[NW][16][16];
+    __shared__ uint32_t s_epoch, s_ok;
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int n = lane & 15, j = lane >> 4;
+    const int yblocks = (a.M + 15) / 16;
+    const int units = LOWRANK ? (a.r / 16) * a.kcn : 0;
+    const int nprod = units * yblocks;
+    const int bid = blockIdx.x;
+    const bool producer = bid < nprod;
+    const int yb = producer ? bid / (units > 0 ? units : 1) : (bid - nprod) % yblocks;
+    const int m_blk = 16 * yb;
+    const int mt = a.M - m_blk < 16 ? a.M - m_blk : 16;
+    const int mrow = n < mt ? n : 0;                      // lanes beyond the tokens re-read row 0; results dropped
+    const int ldxs = a.d_in + 32;
+    const _Float16* xg = a.x + (size_t)m_blk * a.d_in;
+    const ActSrc<XLDS> act{xg, a.d_in, 0, ldxs};
+    float* ts = (float*)(eora_smem + (XLDS ? (size_t)mt * ldxs * 2 : 0));      // t of this token block: 16 x r fp32
+
+    CheckIn ci{0u, 0u, 0u};
+    if constexpr (LOWRANK) {
+        if (tid == 0) check_in_load(ci, a.hdr);           // first request: it returns first
+    }
+    if constexpr (XLDS) {
+        stage_x_dma<NW>(xg, mt, a.d_in, wave, lane);
+        asm volatile("" ::: "memory");                    // later requests stay behind the copy: the waits below count them
+    }
+
+    if constexpr (LOWRANK) {
+        if (producer) {
+            // ===================================================================== producer
+            constexpr int KTA = Fmt<FA>::KT;
+            const int NRB = a.r / 16;
+            const int u = bid % units, rho = u % NRB, kc = u / NRB;
+            const Factor fa{(const uint32_t*)a.A, nullptr, a.d_in / KTA};
+            const int tpc = fa.ntk / a.kcn;
+            if (tid == 0) {
+                check_in_issue(ci, a.hdr, bid);
+                s_epoch = ci.epoch;
+            }
+            if constexpr (XLDS) {
+                asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");      // x has landed in LDS
+                __builtin_amdgcn_s_barrier();
+            } else {
+                __syncthreads();
+            }
+            const f4 part = run_factor_a<FA, NW, XLDS>(fa, rho, kc * tpc, (kc + 1) * tpc, wave, lane, act, mrow, true);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) redp[wave][4 * j + i][n] = part[i];       // register i is token row 4*j+i, column n
+            __syncthreads();
+            if (tid < 256) {
+                const int i = tid >> 4, col = tid & 15;
+                if (i < mt) {
+                    float v = 0.f;
+#pragma unroll
+                    for (int w2 = 0; w2 < NW; ++w2) v += redp[w2][i][col];
+                    // partial layout: [token block][kc][token row (16)][r]; written through to memory
+                    *(volatile float*)&a.tpart[((size_t)(yb * a.kcn + kc) * 16 + i) * a.r + 16 * rho + col] = v;
+                }
+            }
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // write-through stores acknowledged
+            __syncthreads();
+            if (tid == 0) {
+                __hip_atomic_store(&a.hdr[HDR_FLAGS0 + HDR_FLAGS_PER_BLOCK * yb + u], s_epoch + 1, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+                check_in_finish(ci, a.hdr, gridDim.x);
+            }
+            return;
+        }
+    }
+
+    // ========================================================================= consumer
+    const int R = (bid - nprod) / yblocks;
+    const int G = a.d_in / 128;
+    const int nsteps = wave < G ? (G - wave + NW - 1) / NW : 0;
+    SpTile buf[PD];
+#pragma unroll
+    for (int s = 0; s < PD; ++s) {
+        const int ss = s < nsteps ? s : (nsteps > 0 ? nsteps - 1 : 0);           // clamped: always a valid tile
+        load_sptile(buf[s], a.values, a.indices, (size_t)R * G + (nsteps > 0 ? wave : 0) + ss * NW, lane);
+    }
+    const Factor fb{(const uint32_t*)a.B, nullptr, LOWRANK ? a.r / 32 : 0};
+    FTile<S_F16> bpre;
+    if constexpr (LOWRANK) load_ftile<S_F16>(bpre, fb, R, wave < fb.ntk ? wave : 0, lane);
+    if constexpr (LOWRANK) {
+        if (tid == 0) {
+            check_in_issue(ci, a.hdr, bid);
+            s_epoch = ci.epoch;
+        }
+    }
+    if constexpr (XLDS) {
+        // everything after the x copy: PD tiles of three loads (+ B's first tile); the check-in atomic of
+        // wavefront 0 comes later in order and only makes its wait longer
+        if constexpr (LOWRANK) asm volatile("s_waitcnt vmcnt(13) lgkmcnt(0)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(12) lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+    } else {
+        __syncthreads();
+    }
+
+    f4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int base = 0; base < nsteps; base += PD) {
+#pragma unroll
+        for (int s = 0; s < PD; ++s) {
+            if (base + s < nsteps) {
+                const SpTile cur = buf[s];
+                const int g = wave + (base + s) * NW;
+                if (base + s + PD < nsteps) load_sptile(buf[s], a.values, a.indices, (size_t)R * G + g + PD * NW, lane);
+#pragma unroll
+                for (int blk = 0; blk < 2; ++blk) {
+                    h8 x0, x1;
+                    const int col = g * 128 + 64 * blk + 8 * j;
+                    if constexpr (XLDS) {
+                        const _Float16* px = (const _Float16*)eora_smem + mrow * ldxs + col;
+                        x0 = *(const h8*)px;
+                        x1 = *(const h8*)(px + 32);
+                    } else {
+                        const _Float16* px = xg + (size_t)mrow * a.d_in + col;
+                        x0 = *(const h8*)px;
+                        x1 = *(const h8*)(px + 32);
+                    }
+                    const h16 xb = __builtin_shufflevector(x0, x1, 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15);
+                    if (blk == 0) acc = __builtin_amdgcn_smfmac_f32_16x16x64_f16(as_h8(cur.v0), xb, acc, (int)cur.idx, 0, 0);
+                    else acc = __builtin_amdgcn_smfmac_f32_16x16x64_f16(as_h8(cur.v1), xb, acc, (int)cur.idx, 0, 1);
+                }
+            }
+        }
+    }
+
+    // ---- low-rank continuation: acc[row][token] += B[row][:] . t[token][:] -------------------------
+    if constexpr (LOWRANK) {
+        const uint32_t epoch = s_epoch;
+        if (wave == 0) {
+            const uint32_t* flags = a.hdr + HDR_FLAGS0 + HDR_FLAGS_PER_BLOCK * yb;
+            bool ok = false;
+            for (int spins = 0; spins <= a.spin_limit; ++spins) {
+                bool all = true;
+                for (int f = lane; f < units; f += 64) all = all && (ld_relaxed(&flags[f]) == epoch + 1);
+                if (__all(all)) { ok = true; break; }
+                __builtin_amdgcn_s_sleep(2);
+            }
+            if (ok) {
+                // ordinary cached loads: the partials were written through before their flags, none of
+                // their lines is read in this launch before all flags are up, caches hold nothing older
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+                const int T = mt * a.r;
+                for (int e = 4 * lane; e < T; e += 256) {
+                    const float* p = a.tpart + ((size_t)(yb * a.kcn) * 16) * a.r + e;     // row e / r, column e % r
+                    f4 v = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
+                    for (int kc = 0; kc < a.kcn; ++kc) v += *(const f4*)(p + (size_t)kc * 16 * a.r);   // fixed order
+                    *(f4*)(ts + e) = v;
+                }
+            }
+            if (lane == 0) {
+                s_ok = ok ? 1u : 0u;
+                if (!ok) atomicOr(&a.hdr[HDR_ERROR], 1u);
+            }
+        }
+        __syncthreads();
+        if (s_ok) {
+            for (int g = wave; g < fb.ntk; g += NW) {
+                FTile<S_F16> cur;
+                if (g == wave) cur = bpre;
+                else load_ftile<S_F16>(cur, fb, R, g, lane);
+                h8 b[1];
+                decode_tile<S_F16>(cur.w, 0u, b);
+                const float* p = ts + mrow * a.r + g * 32 + 8 * j;
+                const f4 v0 = *(const f4*)p, v1 = *(const f4*)(p + 4);
+                h8 hi, lo;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const _Float16 h0 = (_Float16)v0[i], h1 = (_Float16)v1[i];
+                    hi[i] = h0;
+                    hi[4 + i] = h1;
+                    lo[i] = (_Float16)(v0[i] - (float)h0);
+                    lo[4 + i] = (_Float16)(v1[i] - (float)h1);
+                }
+                acc = mfma16(b[0], hi, acc);             // B's rows are the row operand, t the column operand
+                acc = mfma16(b[0], lo, acc);
+            }
+        }
+    }
+
+    // ---- combine, convert, store: lane holds rows 4*j+i of the strip for token n ----------------------
+    red[wave][lane] = acc;
+    __syncthreads();
+    if (wave == 0) {
+        f4 v = red[0][lane];
+#pragma unroll
+        for (int w2 = 1; w2 < NW; ++w2) v += red[w2][lane];
+        if (n < mt) {
+            typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+            const h4 o = {(_Float16)v[0], (_Float16)v[1], (_Float16)v[2], (_Float16)v[3]};
+            *(h4*)(a.y + (size_t)(m_blk + n) * a.d_out + R * 16 + 4 * j) = o;
+        }
+    }
+    if constexpr (LOWRANK) {
+        if (tid == 0) check_in_finish(ci, a.hdr, gridDim.x);
+    }
+}
+
+template <int FA, int FE, int NW, bool XLDS>
+static hipError_t launch_sparse_one(const SparseArgs& a, hipStream_t stream)
+{
+    auto kern = sparse_kernel<FA, FE, NW, XLDS>;
+    const int mt = a.M < 16 ? a.M : 16;
+    const size_t lds = (XLDS ? (size_t)mt * (a.d_in + 32) * 2 : 0) + (size_t)16 * a.r * 4;
+    if (lds > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    const int yblocks = (a.M + 15) / 16;
+    const int nprod = (FA != S_NONE) ? (a.r / 16) * a.kcn * yblocks : 0;
+    hipLaunchKernelGGL(kern, dim3((a.d_out / 16) * yblocks + nprod), dim3(NW * 64), lds, stream, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_sparse(const SparseArgs& a, hipStream_t stream)
+{
+    // x in LDS for 1..4 tokens when it fits next to t (d_in a multiple of 512 for the 1 KiB copy chunks)
+    const bool xlds = a.M <= 4 && a.d_in % 512 == 0 && (size_t)a.M * (a.d_in + 32) * 2 + 16 * (size_t)a.r * 4 <= 150 * 1024;
+    if (a.r == 0) return xlds ? launch_sparse_one<S_NONE, S_NONE, 8, true>(a, stream)
+                              : launch_sparse_one<S_NONE, S_NONE, 8, false>(a, stream);
+    return xlds ? launch_sparse_one<S_F16, S_F16, 8, true>(a, stream) : launch_sparse_one<S_F16, S_F16, 8, false>(a, stream);
+}
+
+}  // namespace eora

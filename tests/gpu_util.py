@@ -32,3 +32,21 @@ def run_linear_q(c, M=None, x=None, r=None, canary=True, ws=None):
     if canary:
         assert np.all(out[:pad] == 777.0) and np.all(out[pad + M * c.d_out:] == 777.0), "write outside y"
     return out[pad: pad + M * c.d_out].reshape(M, c.d_out)
+
+
+def run_linear_sp24(c, M=None, x=None, r=None, ws=None):
+    """Run eora_linear_sp24 on case c; returns y as float16 numpy (M x d_out)."""
+    M = c.M if M is None else M
+    r = c.r if r is None else r
+    x = c.x if x is None else x
+    xd, values, indices = dev(x), dev(c.values), dev(c.indices)
+    A, B = (dev(c.A), dev(c.B)) if r > 0 else (None, None)
+    ws = eora.new_workspace(M, c.d_in, c.d_out, r) if ws is None else ws
+    pad = 64
+    ybuf = torch.full((M * c.d_out + 2 * pad,), 777.0, dtype=torch.float16, device="cuda")
+    y = ybuf[pad: pad + M * c.d_out]
+    eora.linear_sp24(xd, values, indices, A, B, y, M, c.d_in, c.d_out, r, ws)
+    torch.cuda.synchronize()
+    out = ybuf.cpu().numpy()
+    assert np.all(out[:pad] == 777.0) and np.all(out[pad + M * c.d_out:] == 777.0), "write outside y"
+    return out[pad: pad + M * c.d_out].reshape(M, c.d_out)

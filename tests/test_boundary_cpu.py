@@ -88,7 +88,10 @@ def test_linear_q_validation_codes():
     assert call(qw=odd) == -4 and call(y=odd) == -4 and call(ws=odd) == -4
     assert call(ws=null) == -5 and call(ws_bytes=16) == -5
     assert call(M=0) == 0                                   # empty input: nothing to do, nothing launched
-    assert L.eora_linear_sp24(null, good, good, good, good, good, 1, 256, 32, 32, good, 1 << 20, null) != 0
+    assert L.eora_linear_sp24(null, good, good, good, good, good, 1, 256, 32, 32, good, 1 << 20, null) == -1
+    assert L.eora_linear_sp24(good, good, good, good, good, good, 1, 256, 32, 48, good, 1 << 20, null) == -2
+    assert L.eora_linear_sp24(good, good, odd, good, good, good, 1, 256, 32, 32, good, 1 << 20, null) == -4
+    assert L.eora_linear_sp24(good, good, good, good, good, good, 1, 256, 32, 32, good, 16, null) == -5
     assert L.eora_unpack_q(good, good, good, good, 256, 32, 5, 128, null) == -3
     assert L.eora_dequant_q(good, good, good, null, 256, 32, 4, 128, null) == -1
     assert L.eora_expand_sp24(good, odd, good, 256, 32, null) == -4

@@ -166,3 +166,43 @@ def test_mid_size_token_counts(gpu):
     from tests.gpu_util import run_linear_q
     c = QCase(24, 512, 96, 300, 64, 4, packer=gpu)
     _check(run_linear_q(c), c.oracle_y())
+
+
+def test_expand_sp24_bit_exact(gpu):
+    import torch
+    from oracle import linear
+    from tests.cases import SparseCase
+    from tests.gpu_util import dev
+    c = SparseCase(31, 640, 80, 1, 0, packer=gpu)
+    W = torch.full((80, 640), float("nan"), dtype=torch.float16, device="cuda")
+    gpu.expand_sp24(dev(c.values), dev(c.indices), W, 640, 80)
+    torch.cuda.synchronize()
+    ref = linear.expand_sp24_packed(c.o_values, c.o_indices, 640, 80)
+    assert np.array_equal(W.cpu().numpy().astype(np.float64), ref)
+
+
+@pytest.mark.parametrize("r,M", [(0, 1), (32, 1), (128, 2), (64, 4), (32, 5), (96, 16), (64, 37)])
+def test_linear_sp24_small_shapes(gpu, r, M):
+    from tests.cases import SparseCase
+    from tests.gpu_util import run_linear_sp24
+    c = SparseCase(2000 + 3 * r + M, 1024, 112, M, r, packer=gpu)
+    _check(run_linear_sp24(c), c.oracle_y())
+
+
+def test_linear_sp24_ragged_k_and_determinism(gpu):
+    from tests.cases import SparseCase
+    from tests.gpu_util import run_linear_sp24
+    c = SparseCase(41, 640, 48, 3, 32, packer=gpu)           # d_in not a multiple of 512: fragments from global memory
+    y = run_linear_sp24(c)
+    _check(y, c.oracle_y())
+    assert np.array_equal(y, run_linear_sp24(c))
+
+
+@pytest.mark.parametrize("M", [1, 64])
+def test_config5_shape_k_projection(gpu, M):
+    """BASELINE config 5, the 8192 -> 1024 linear of a 70B-shaped layer at full size."""
+    import synth
+    from tests.cases import SparseCase
+    from tests.gpu_util import run_linear_sp24
+    c = SparseCase(synth.seed_for(5, 1), 8192, 1024, M, 128, packer=gpu)
+    _check(run_linear_sp24(c), c.oracle_y())
