@@ -28,14 +28,25 @@ WORKLOADS = {
     "llama3-8b-layer-decode-w4g128-r128q4-M1": dict(model="8b", w_bits=4, ab_bits=4, r=128, M=1, cfg=3),
     "llama3-8b-layer-decode-w4g128-bare-M1": dict(model="8b", w_bits=4, ab_bits=16, r=0, M=1, cfg=3),
     "llama3-8b-layer-decode-w3g128-bare-M1": dict(model="8b", w_bits=3, ab_bits=16, r=0, M=1, cfg=2),
+    "llama3-8b-layer-decode-w4g128-r128fp16-M16": dict(model="8b", w_bits=4, ab_bits=16, r=128, M=16, cfg=1),
+    "llama3-8b-layer-decode-w4g128-r128q4-M8": dict(model="8b", w_bits=4, ab_bits=4, r=128, M=8, cfg=3),
+    "llama3-8b-layer-decode-w4g128-bare-M8": dict(model="8b", w_bits=4, ab_bits=4, r=0, M=8, cfg=3),
+    "llama3-70b-layer-decode-sp24-r128fp16-M1": dict(model="70b", w_bits=0, ab_bits=16, r=128, M=1, cfg=5),
+    "llama3-70b-layer-decode-sp24-bare-M1": dict(model="70b", w_bits=0, ab_bits=16, r=0, M=1, cfg=5),
+    "llama3-70b-layer-decode-sp24-r128fp16-M64": dict(model="70b", w_bits=0, ab_bits=16, r=128, M=64, cfg=5),
 }
+for _r in (64, 256, 512):
+    WORKLOADS["llama3-8b-layer-decode-w4g128-r%dq4-M1" % _r] = dict(model="8b", w_bits=4, ab_bits=4, r=_r, M=1, cfg=3)
 DEFAULT = "llama3-8b-layer-decode-w3g128-r128fp16-M1"
 
 
 def algorithmic_bytes(d_in, d_out, M, r, w_bits, ab_bits, group=128):
     """Bytes the method must move for one linear: packed codes, scales, zero-points, factors,
     x read once and y written once (the M x r intermediate never makes a y-sized round trip)."""
-    b = d_out * d_in * w_bits / 8 + d_out * (d_in // group) * 2.5
+    if w_bits == 0:                                          # 2:4 sparse fp16: two values + 4 index bits per four positions
+        b = d_out * d_in * 1.125
+    else:
+        b = d_out * d_in * w_bits / 8 + d_out * (d_in // group) * 2.5
     if r:
         if ab_bits == 16:
             b += 2 * r * (d_in + d_out)
@@ -57,10 +68,18 @@ class Linear:
         self.name, self.d_in, self.d_out = name, d_in, d_out
         self.M, self.r, self.w_bits, self.ab_bits = spec["M"], spec["r"], spec["w_bits"], spec["ab_bits"]
         W, A, B, x = synth.draw_layer(seed, d_in, d_out, self.M, self.r)
-        codes, zeros, scales = synth.quantize_rtn(W, self.w_bits, 128)
-        self.logical = (codes, zeros, scales, A, B, x)
-        qw, qz, sc = eora.pack_q(codes, zeros, scales, self.w_bits, 128)
-        host = [qw, sc, qz, None, None, None, None]
+        if self.w_bits == 0:
+            vals, pos = synth.prune_24(W.astype(np.float16))
+            del W
+            self.logical = (vals, pos, None, A, B, x)
+            values, indices = eora.pack_sp24(vals, pos)
+            host = [values, indices, None, None, None, None, None]
+        else:
+            codes, zeros, scales = synth.quantize_rtn(W, self.w_bits, 128)
+            del W
+            self.logical = (codes, zeros, scales, A, B, x)
+            qw, qz, sc = eora.pack_q(codes, zeros, scales, self.w_bits, 128)
+            host = [qw, sc, qz, None, None, None, None]
         if self.r and self.ab_bits == 16:
             host[3], host[4] = eora.pack_factor_f16(A), eora.pack_factor_f16(B)
         elif self.r:
@@ -80,6 +99,9 @@ class Linear:
     def run(self, copy):
         import paper_2410_21271_amd as eora
         qw, sc, qz, A, B, As, Bs = self.copies[copy % len(self.copies)]
+        if self.w_bits == 0:
+            eora.linear_sp24(self.x, qw, sc, A, B, self.y, self.M, self.d_in, self.d_out, self.r, self.ws)
+            return
         eora.linear_q(self.x, qw, sc, qz, A, B, As, Bs, self.y, self.M, self.d_in, self.d_out, self.r,
                       self.w_bits, 128, self.ab_bits, self.ws)
 
@@ -117,6 +139,15 @@ def cpu_baseline(linears, names):
         if L.name not in names:
             continue
         codes, zeros, scales, A, B, x = L.logical
+        if L.w_bits == 0:
+            values, indices = layout.pack_sp24(codes, zeros)
+            Ap, Bp = (layout.pack_f16(A), layout.pack_f16(B)) if L.r else (None, None)
+            t0 = time.perf_counter()
+            y = linear.eora_linear_sp24(x, values, indices, Ap, Bp, L.M, L.d_in, L.d_out, L.r)
+            total_t += time.perf_counter() - t0
+            total_b += L.bytes
+            worst = max(worst, linear.y_error(L.y.cpu().numpy(), y))
+            continue
         qw = layout.pack_q4(codes) if L.w_bits == 4 else layout.pack_q3(codes)
         qz, sc = layout.pack_zeros(zeros), layout.pack_scales(scales)
         Ap = Bp = As = Bs = None
@@ -165,10 +196,12 @@ def main():
         print(json.dumps({"copy_probe_bytes_read": src.numel(), "copy_probe_bytes_written": src.numel(), "copies": 10}))
         return
     spec = WORKLOADS[args.workload]
-    shapes = synth.LLAMA3_8B
+    shapes = synth.LLAMA3_8B if spec["model"] == "8b" else synth.LLAMA3_70B
     layer_bytes = sum(algorithmic_bytes(di, do, spec["M"], spec["r"], spec["w_bits"], spec["ab_bits"])
                       for _, di, do in shapes)
     ncopies = args.copies or max(2, int(1.2e9 / layer_bytes) + 1)
+    if spec["M"] > 16:
+        args.steps = min(args.steps, 50)
     linears = [Linear(n, di, do, spec, synth.seed_for(spec["cfg"], i), ncopies) for i, (n, di, do) in enumerate(shapes)]
 
     def step(i):
@@ -192,7 +225,7 @@ def main():
     # o, gate, up: six of the seven launches of a step, 69 % of its bytes).  Its average launch moves
     # the average algorithmic bytes of those six shapes; its average duration is the mean of their
     # event-timed back-to-back launches (which includes the gap between consecutive launches).
-    dom = [L for L in linears if L.d_in == 4096]
+    dom = [L for L in linears if L.d_in == linears[0].d_in]
     dom_bytes = sum(L.bytes for L in dom) / len(dom)
     dom_us = sum(per_linear[L.name]["us"] for L in dom) / len(dom)
     traffic = None
@@ -202,7 +235,7 @@ def main():
             traffic = json.load(f).get(args.workload)
     roofline = dict(bound="hbm", achieved=round(dom_bytes / dom_us / 1e3, 1), peak=HBM_PEAK_GBS, unit="GB/s",
                     frac=round(dom_bytes / dom_us / 1e3 / HBM_PEAK_GBS, 4), traffic=traffic,
-                    kernel="eora::small_kernel (d_in=4096 instantiation; q,k,v,o,gate,up)",
+                    kernel="layer kernel instantiation of the d_in=%d linears (%s)" % (dom[0].d_in, ",".join(L.name for L in dom)),
                     bytes_per_launch=int(dom_bytes), us_per_launch=round(dom_us, 3))
 
     out = dict(metric="decode HBM GB/s over one 8B decoder layer's linears (M=1)",
@@ -214,7 +247,7 @@ def main():
                            per_linear=per_linear),
                roofline=roofline)
     if not args.no_cpu_baseline:
-        base, worst = cpu_baseline(linears, ("q", "k", "v", "o", "gate"))
+        base, worst = cpu_baseline(linears, ("q", "k", "v", "o", "gate") if spec["model"] == "8b" else ("k", "v"))
         out["cpu_baseline"] = base
         out["config"]["max_err_vs_oracle"] = float("%.3g" % worst)
     print(json.dumps(out))
