@@ -12,7 +12,8 @@ using namespace eora;
 
 constexpr size_t WS_HEADER = 40960;        // counters and flags (HDR_WORDS 32-bit words)
 constexpr int MAX_RANK = 512;
-constexpr int CHUNK_TOKENS = 16 * MAX_YBLOCKS;      // tokens per launch
+constexpr int CHUNK_TOKENS = 16 * MAX_YBLOCKS;      // tokens per launch of the small-M kernels
+constexpr int PREFILL_MIN_TOKENS = 128;             // from here on the GEMM kernel takes over
 static_assert(HDR_WORDS * 4 <= WS_HEADER, "header too small");
 
 int g_spin_limit = 1 << 22;                // bounded wait of the up-projection (about a second)
@@ -50,7 +51,8 @@ size_t eora_workspace_bytes(int M, int d_in, int d_out, int r)
     if (check_backbone_shape(M, d_in, d_out, r) != EORA_OK) return 0;
     const size_t mc = (size_t)(M < CHUNK_TOKENS ? M : CHUNK_TOKENS);
     const size_t yblocks = (mc + 15) / 16;
-    return WS_HEADER + yblocks * MAX_KCN * 16 * (size_t)r * sizeof(float);
+    // partials of t for the small-M kernels, and t itself as fp16 M x r for the prefill GEMM
+    return WS_HEADER + yblocks * MAX_KCN * 16 * (size_t)r * sizeof(float) + round256((size_t)M * r * 2);
 }
 
 int eora_workspace_init(void* workspace, size_t workspace_bytes, void* stream)
@@ -110,6 +112,29 @@ int eora_linear_q(const void* x, const void* qweight, const void* scales, const 
     if (!aligned16(workspace)) return EORA_ERR_ALIGN;
     if (workspace_bytes < eora_workspace_bytes(M, d_in, d_out, r)) return EORA_ERR_WORKSPACE;
     if (M == 0) return EORA_OK;
+
+    // Many tokens: MFMA-bound GEMM (t = x.A^T first, then one GEMM over d_in and r).
+    if (M >= PREFILL_MIN_TOKENS && (r == 0 || (ab_bits == 16 && r % 128 == 0))) {
+        const size_t mc = (size_t)(M < CHUNK_TOKENS ? M : CHUNK_TOKENS);
+        _Float16* T = (_Float16*)((char*)workspace + WS_HEADER + ((mc + 15) / 16) * MAX_KCN * 16 * (size_t)r * sizeof(float));
+        if (r > 0) {
+            PrefillArgs p{};
+            p.x = (const _Float16*)x; p.ldx = d_in;
+            p.w = A; p.K1 = d_in;
+            p.y = T; p.ldy = r;
+            p.M = M; p.N = r;
+            if (failed(launch_prefill(p, S_F16, false, (hipStream_t)stream), "prefill down-projection")) return EORA_ERR_LAUNCH;
+        }
+        PrefillArgs p{};
+        p.x = (const _Float16*)x; p.ldx = d_in;
+        p.w = qweight; p.w_scales = (const _Float16*)scales; p.w_zeros = (const uint32_t*)qzeros; p.group = group;
+        p.K1 = d_in;
+        p.x2 = T; p.ldx2 = r; p.w2 = B; p.K2 = r;
+        p.y = y; p.ldy = d_out;
+        p.M = M; p.N = d_out;
+        if (failed(launch_prefill(p, w_bits == 4 ? S_Q4 : S_Q3, r > 0, (hipStream_t)stream), "prefill")) return EORA_ERR_LAUNCH;
+        return EORA_OK;
+    }
 
     // k-ranges of the down-projection: many for few tokens (every consumer adds the partials itself),
     // a divisor of the number of 128-wide k-tiles

@@ -58,6 +58,24 @@ struct SparseArgs {
 
 hipError_t launch_sparse(const SparseArgs& a, hipStream_t stream);
 
+// Prefill GEMM (prefill.hip): y[M x N] = act[M x K1] . W1^T (+ act2[M x K2] . W2^T), fp16 output
+struct PrefillArgs {
+    const _Float16* x;        // first segment's activations, row stride ldx
+    int ldx;
+    const void* w;            // first segment's weight tiles (N rows, K1 columns)
+    const _Float16* w_scales;
+    const uint32_t* w_zeros;
+    int group;
+    const _Float16* x2;       // second segment's activations (t), row stride ldx2
+    int ldx2;
+    const void* w2;           // second segment's fp16 tiles (N rows, K2 columns)
+    void* y;                  // fp16, row stride ldy
+    int ldy;
+    int M, N, K1, K2;
+};
+
+hipError_t launch_prefill(const PrefillArgs& a, int fm, bool ext, hipStream_t stream);
+
 hipError_t launch_unpack_q(const uint32_t* qweight, const uint32_t* qzeros, uint8_t* codes, uint8_t* zeros,
                            int d_in, int d_out, int w_bits, int group, hipStream_t stream);
 hipError_t launch_dequant_q(const uint32_t* qweight, const _Float16* scales, const uint32_t* qzeros, float* W,

@@ -206,3 +206,26 @@ def test_config5_shape_k_projection(gpu, M):
     from tests.gpu_util import run_linear_sp24
     c = SparseCase(synth.seed_for(5, 1), 8192, 1024, M, 128, packer=gpu)
     _check(run_linear_sp24(c), c.oracle_y())
+
+
+@pytest.mark.parametrize("w_bits,r,M,d_out", [(4, 0, 128, 128), (4, 128, 200, 192), (3, 256, 333, 144), (4, 128, 129, 16)])
+def test_prefill_gemm_small_shapes(gpu, w_bits, r, M, d_out):
+    """The many-token GEMM path: ragged token and row tiles, with and without the low-rank extension."""
+    from tests.cases import QCase
+    from tests.gpu_util import run_linear_q
+    c = QCase(3000 + r + M, 512, d_out, M, r, w_bits, packer=gpu)
+    _check(run_linear_q(c), c.oracle_y())
+
+
+def test_prefill_config4_shape_sampled_rows(gpu):
+    """BASELINE config 4: M = 2048, 4096 -> 4096, 4-bit backbone, fp16 rank-256 factors, 1 % outlier
+    channels scaled by 20.  The oracle is evaluated on a seeded subset of token rows (first and last
+    rows of tiles included) over all output columns."""
+    import synth
+    from tests.cases import QCase
+    from tests.gpu_util import run_linear_q
+    c = QCase(synth.seed_for(4, 0), 4096, 4096, 2048, 256, 4, outlier_frac=0.01, packer=gpu)
+    y = run_linear_q(c)
+    rows = np.unique(np.concatenate([np.array([0, 1, 63, 64, 127, 128, 255, 256, 1023, 1024, 2046, 2047]),
+                                     np.random.default_rng(0).integers(0, 2048, 52)]))
+    _check(y[rows], c.oracle_y(rows=rows))
