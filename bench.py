@@ -31,6 +31,8 @@ WORKLOADS = {
     "llama3-8b-layer-decode-w4g128-r128fp16-M16": dict(model="8b", w_bits=4, ab_bits=16, r=128, M=16, cfg=1),
     "llama3-8b-layer-decode-w4g128-r128q4-M8": dict(model="8b", w_bits=4, ab_bits=4, r=128, M=8, cfg=3),
     "llama3-8b-layer-decode-w4g128-bare-M8": dict(model="8b", w_bits=4, ab_bits=4, r=0, M=8, cfg=3),
+    "llama3-8b-layer-prefill-w4g128-r256fp16-M2048": dict(model="8b", w_bits=4, ab_bits=16, r=256, M=2048, cfg=4, outlier=0.01),
+    "llama3-8b-layer-prefill-w4g128-bare-M2048": dict(model="8b", w_bits=4, ab_bits=16, r=0, M=2048, cfg=4, outlier=0.01),
     "llama3-70b-layer-decode-sp24-r128fp16-M1": dict(model="70b", w_bits=0, ab_bits=16, r=128, M=1, cfg=5),
     "llama3-70b-layer-decode-sp24-bare-M1": dict(model="70b", w_bits=0, ab_bits=16, r=0, M=1, cfg=5),
     "llama3-70b-layer-decode-sp24-r128fp16-M64": dict(model="70b", w_bits=0, ab_bits=16, r=128, M=64, cfg=5),
@@ -67,7 +69,7 @@ class Linear:
         from tests.gpu_util import dev
         self.name, self.d_in, self.d_out = name, d_in, d_out
         self.M, self.r, self.w_bits, self.ab_bits = spec["M"], spec["r"], spec["w_bits"], spec["ab_bits"]
-        W, A, B, x = synth.draw_layer(seed, d_in, d_out, self.M, self.r)
+        W, A, B, x = synth.draw_layer(seed, d_in, d_out, self.M, self.r, spec.get("outlier", 0.0))
         if self.w_bits == 0:
             vals, pos = synth.prune_24(W.astype(np.float16))
             del W
@@ -216,9 +218,10 @@ def main():
     # each linear on its own (graph of back-to-back launches over the rotating copies)
     per_linear = {}
     for L in linears:
-        us = 1e3 * timed_graph(L.run, 200)
+        us = 1e3 * timed_graph(L.run, 200 if spec["M"] <= 16 else 40)
         per_linear[L.name] = dict(us=round(us, 3), GBps=round(L.bytes / us / 1e3, 1),
-                                  frac_hbm=round(L.bytes / us / 1e3 / HBM_PEAK_GBS, 4))
+                                  frac_hbm=round(L.bytes / us / 1e3 / HBM_PEAK_GBS, 4),
+                                  TFLOPs=round(L.flops / us / 1e6, 1))
     # launch floor: an empty-bodied call does not exist in the library, so the floor is the smallest
     # linear of the bare layer; reported for context only.
     # Dominant kernel: the decode kernel instantiation that serves the d_in = 4096 linears (q, k, v,

@@ -10,7 +10,7 @@ namespace {
 
 using namespace eora;
 
-constexpr size_t WS_HEADER = 40960;        // counters and flags (HDR_WORDS 32-bit words)
+constexpr size_t WS_HEADER = 270336;       // counters and flags (HDR_WORDS 32-bit words)
 constexpr int MAX_RANK = 512;
 constexpr int CHUNK_TOKENS = 16 * MAX_YBLOCKS;      // tokens per launch of the small-M kernels
 constexpr int PREFILL_MIN_TOKENS = 128;             // from here on the GEMM kernel takes over

@@ -20,7 +20,9 @@ constexpr int HDR_NSUB = 32;
 constexpr int HDR_FLAGS0 = 2048;                // per token block: one flag per unit of t
 constexpr int HDR_FLAGS_PER_BLOCK = 512;        // (r/16) * kcn <= 32 * 16
 constexpr int MAX_YBLOCKS = 16;                 // token blocks per launch (256 tokens)
-constexpr int HDR_WORDS = HDR_FLAGS0 + HDR_FLAGS_PER_BLOCK * MAX_YBLOCKS;
+constexpr int HDR_FLAG_REPLICAS = 8;             // the decode kernels keep 8 copies of the flags, one per group of pollers
+constexpr int HDR_FLAGS_REPLICA_STRIDE = HDR_FLAGS_PER_BLOCK * MAX_YBLOCKS;
+constexpr int HDR_WORDS = HDR_FLAGS0 + HDR_FLAGS_REPLICA_STRIDE * HDR_FLAG_REPLICAS;
 constexpr int MAX_KCN = 8;                      // k-ranges of the down-projection
 
 struct FusedArgs {

@@ -135,7 +135,9 @@ __global__ __launch_bounds__(NW * 64) void small_kernel(FusedArgs a)
         __syncthreads();
         TL_STAMP(3);
         if (tid == 0) {
-            __hip_atomic_store(&a.hdr[HDR_FLAGS0 + u], epoch + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            for (int rep = 0; rep < HDR_FLAG_REPLICAS; ++rep)      // one copy per group of pollers
+                __hip_atomic_store(&a.hdr[HDR_FLAGS0 + HDR_FLAGS_REPLICA_STRIDE * rep + u], epoch + 1, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
             check_in_finish(ci, a.hdr, gridDim.x);
         }
         return;
@@ -204,7 +206,7 @@ __global__ __launch_bounds__(NW * 64) void small_kernel(FusedArgs a)
     if constexpr (LOWRANK) {
         const uint32_t epoch = s_epoch;
         if (wave == 0) {
-            const uint32_t* flags = a.hdr + HDR_FLAGS0;
+            const uint32_t* flags = a.hdr + HDR_FLAGS0 + HDR_FLAGS_REPLICA_STRIDE * (blockIdx.x % HDR_FLAG_REPLICAS);
             bool ok = false;
             for (int spins = 0; spins <= a.spin_limit; ++spins) {
                 bool all = true;

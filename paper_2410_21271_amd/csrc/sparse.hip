@@ -121,8 +121,9 @@ __global__ __launch_bounds__(NW * 64) void sparse_kernel(SparseArgs a)
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // write-through stores acknowledged
             __syncthreads();
             if (tid == 0) {
-                __hip_atomic_store(&a.hdr[HDR_FLAGS0 + HDR_FLAGS_PER_BLOCK * yb + u], s_epoch + 1, __ATOMIC_RELAXED,
-                                   __HIP_MEMORY_SCOPE_AGENT);
+                for (int rep = 0; rep < HDR_FLAG_REPLICAS; ++rep)  // one copy per group of pollers
+                    __hip_atomic_store(&a.hdr[HDR_FLAGS0 + HDR_FLAGS_REPLICA_STRIDE * rep + HDR_FLAGS_PER_BLOCK * yb + u],
+                                       s_epoch + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 check_in_finish(ci, a.hdr, gridDim.x);
             }
             return;
@@ -191,7 +192,7 @@ __global__ __launch_bounds__(NW * 64) void sparse_kernel(SparseArgs a)
     if constexpr (LOWRANK) {
         const uint32_t epoch = s_epoch;
         if (wave == 0) {
-            const uint32_t* flags = a.hdr + HDR_FLAGS0 + HDR_FLAGS_PER_BLOCK * yb;
+            const uint32_t* flags = a.hdr + HDR_FLAGS0 + HDR_FLAGS_REPLICA_STRIDE * (blockIdx.x % HDR_FLAG_REPLICAS) + HDR_FLAGS_PER_BLOCK * yb;
             bool ok = false;
             for (int spins = 0; spins <= a.spin_limit; ++spins) {
                 bool all = true;
