@@ -29,7 +29,7 @@ constexpr int XSTAGE = 4;   // 16-byte chunks of x a thread may stage
 #define TL_STAMP(slot) do { } while (0)
 #endif
 
-template <int FM, int FA, int FE, int NW, int NQ>
+template <int FM, int FA, int FE, int NW, int NQ, bool M1>
 __global__ __launch_bounds__(NW * 64) void small_kernel(FusedArgs a)
 {
     constexpr bool LOWRANK = FA != S_NONE;
@@ -40,7 +40,7 @@ __global__ __launch_bounds__(NW * 64) void small_kernel(FusedArgs a)
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int n = lane & 15, j = lane >> 4;
-    const int mt = a.M;                                  // 1..4 tokens, one token block
+    const int mt = M1 ? 1 : a.M;                         // 1..4 tokens, one token block (M1: exactly one)
     const int mrow = n < mt ? n : 0;                     // lanes beyond the tokens re-read row 0; their results are dropped
     const int nprod = LOWRANK ? (a.r / 16) * a.kcn : 0;  // producer workgroups
     const int ldxs = a.d_in + 32;                        // LDS row stride of x in halves (64 bytes of padding)
@@ -54,14 +54,14 @@ __global__ __launch_bounds__(NW * 64) void small_kernel(FusedArgs a)
     }
 
     // ---- x: requested first, by everyone ---------------------------------------------------------
-    const int xchunks = a.d_in / 8, xtotal = mt * xchunks;
-    u4 xstage[XSTAGE];
-    int xc[XSTAGE];
+    // A row of x is d_in / 8 = NQ * NT chunks of 16 bytes, so chunk (tid + k * NT) of the staged block is
+    // chunk tid + (k % NQ) * NT of token row k / NQ: no division.  Rows beyond the tokens repeat row 0.
+    constexpr int XS = M1 ? NQ : XSTAGE;
+    u4 xstage[XS];
 #pragma unroll
-    for (int k = 0; k < XSTAGE; ++k) {
-        const int c = tid + k * NT;
-        xc[k] = c < xtotal ? c : xtotal - 1;             // surplus threads duplicate the last chunk
-        xstage[k] = *((const u4*)(a.x + (size_t)(xc[k] / xchunks) * a.d_in) + xc[k] % xchunks);
+    for (int k = 0; k < XS; ++k) {
+        const int xrow = (k / NQ) < mt ? (k / NQ) : 0;
+        xstage[k] = *((const u4*)(a.x + (size_t)xrow * a.d_in) + tid + (k % NQ) * NT);
     }
 
     if constexpr (LOWRANK) {
@@ -86,7 +86,7 @@ __global__ __launch_bounds__(NW * 64) void small_kernel(FusedArgs a)
             s_epoch = ci.epoch;
         }
 #pragma unroll
-        for (int k = 0; k < XSTAGE; ++k) *(u4*)(xs + (size_t)(xc[k] / xchunks) * ldxs + (xc[k] % xchunks) * 8) = xstage[k];
+        for (int k = 0; k < XS; ++k) *(u4*)(xs + ((k / NQ) < mt ? (k / NQ) : 0) * ldxs + (tid + (k % NQ) * NT) * 8) = xstage[k];
         __syncthreads();
         TL_STAMP(1);
         const uint32_t epoch = s_epoch;
@@ -175,7 +175,7 @@ __global__ __launch_bounds__(NW * 64) void small_kernel(FusedArgs a)
         }
     }
 #pragma unroll
-    for (int k = 0; k < XSTAGE; ++k) *(u4*)(xs + (size_t)(xc[k] / xchunks) * ldxs + (xc[k] % xchunks) * 8) = xstage[k];
+    for (int k = 0; k < XS; ++k) *(u4*)(xs + ((k / NQ) < mt ? (k / NQ) : 0) * ldxs + (tid + (k % NQ) * NT) * 8) = xstage[k];
     __syncthreads();
 
     TL_STAMP(1);
@@ -197,7 +197,9 @@ __global__ __launch_bounds__(NW * 64) void small_kernel(FusedArgs a)
             for (int t = 0; t < 4; ++t) part = mfma16(xa[t], b[t], part);
             const uint32_t sw = (i < 2) ? sc[q].x : sc[q].y;
             const _Float16 s16 = __builtin_bit_cast(_Float16, (uint16_t)((i & 1) ? (sw >> 16) : (sw & 0xFFFFu)));
-            acc += (float)s16 * part;                    // exact integers times x, scaled once per group in fp32
+            // exact integers times x, scaled once per group in fp32 (one token: only register 0 is ever stored)
+            if constexpr (M1) acc[0] += (float)s16 * part[0];
+            else acc += (float)s16 * part;
         }
     }
 
@@ -262,7 +264,8 @@ __global__ __launch_bounds__(NW * 64) void small_kernel(FusedArgs a)
                     part = mfma16(hi, b[q], part);
                     part = mfma16(lo, b[q], part);
                 }
-                acc += (float)cur.sc * part;
+                if constexpr (M1) acc[0] += (float)cur.sc * part[0];
+                else acc += (float)cur.sc * part;
             }
         }
     }
@@ -270,7 +273,7 @@ __global__ __launch_bounds__(NW * 64) void small_kernel(FusedArgs a)
     // ---- combine, convert, store -------------------------------------------------------------------
     if (j == 0) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) red[wave][i][n] = acc[i];
+        for (int i = 0; i < (M1 ? 1 : 4); ++i) red[wave][i][n] = acc[i];
     }
     __syncthreads();
     if (tid < 16 * mt) {
@@ -287,10 +290,10 @@ __global__ __launch_bounds__(NW * 64) void small_kernel(FusedArgs a)
 }
 
 // ------------------------------------------------------------------------------------------------
-template <int FM, int FA, int FE, int NW, int NQ>
-static hipError_t launch_small_one(const FusedArgs& a, hipStream_t stream)
+template <int FM, int FA, int FE, int NW, int NQ, bool M1>
+static hipError_t launch_small_m(const FusedArgs& a, hipStream_t stream)
 {
-    auto kern = small_kernel<FM, FA, FE, NW, NQ>;
+    auto kern = small_kernel<FM, FA, FE, NW, NQ, M1>;
     const size_t lds = (size_t)a.M * (a.d_in + 32) * 2 + (size_t)a.M * a.r * 4;
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -299,6 +302,14 @@ static hipError_t launch_small_one(const FusedArgs& a, hipStream_t stream)
     const int nprod = (FA != S_NONE) ? (a.r / 16) * a.kcn : 0;
     hipLaunchKernelGGL(kern, dim3(a.d_out / 16 + nprod), dim3(NW * 64), lds, stream, a);
     return hipGetLastError();
+}
+
+template <int FM, int FA, int FE, int NW, int NQ>
+static hipError_t launch_small_one(const FusedArgs& a, hipStream_t stream)
+{
+    if (a.M == 1) return launch_small_m<FM, FA, FE, NW, NQ, true>(a, stream);
+    if constexpr (NQ <= XSTAGE / 2) return launch_small_m<FM, FA, FE, NW, NQ, false>(a, stream);   // M * NQ <= XSTAGE
+    return hipErrorInvalidValue;
 }
 
 template <int FM, int FA, int FE>
