@@ -85,14 +85,14 @@ size_t eora_qzeros_bytes(int d_in, int d_out, int group);            /* d_out*ce
 size_t eora_scales_bytes(int d_in, int d_out, int group);            /* d_out*(d_in/group)*2 */
 size_t eora_sp24_values_bytes(int d_in, int d_out);                  /* d_out*d_in          */
 size_t eora_sp24_indices_bytes(int d_in, int d_out);                 /* d_out*d_in/8        */
-/* Scratch the forward calls need: a header of counters, the down-projection t = x.A^T (M x r,
- * fp32) and its partial sums.  The header must be cleared ONCE with eora_workspace_init() before the
- * first forward call on this workspace; every forward call leaves it cleared again, so no per-call
- * clearing (and nothing a HIP graph could not replay) is needed.  The rest need not be initialised.
- * Calls that may overlap in time (different streams) need different workspaces.  r == 0 still
- * needs a workspace. */
+/* Scratch the forward calls need: a header of counters, the down-projection t = x.A^T (M x r)
+ * and its partial sums.  The workspace must be cleared ONCE with eora_workspace_init() before the
+ * first forward call on it; every forward call leaves it usable for the next, so no per-call
+ * clearing (and nothing a HIP graph could not replay) is needed.  Calls that may overlap in time
+ * (different streams) need different workspaces.  r == 0 still needs a workspace.  A workspace of
+ * the size of the largest (M, r) serves smaller calls too. */
 size_t eora_workspace_bytes(int M, int d_in, int d_out, int r);
-/* Enqueues the clearing of the workspace header on `stream`. */
+/* Enqueues the clearing of all `workspace_bytes` bytes on `stream`. */
 int eora_workspace_init(void* workspace, size_t workspace_bytes, void* stream);
 /* Diagnostic.  SYNCHRONISES `stream`, then reports EORA_ERR_TIMEOUT if a kernel that used this
  * workspace gave up its bounded wait for the down-projection (its y is then invalid; re-initialise

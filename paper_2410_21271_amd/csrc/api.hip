@@ -42,6 +42,14 @@ int check_group(int d_in, int group)
     return EORA_OK;
 }
 
+// workspace = header | tagged partials (decode kernel) | fp32 partials (fused.hip, sparse.hip) | t (fp16, prefill).
+// The regions sit at fixed offsets whatever (M, r) a call has, so that calls of different shapes on one
+// workspace never read one region's bytes as another's.  (token blocks) x kcn <= 32 and r <= 512.
+constexpr size_t MAX_PART_ELEMS = 32 * 16 * 512;
+constexpr size_t WS_PAIRS = WS_HEADER;
+constexpr size_t WS_PARTS = WS_PAIRS + MAX_PART_ELEMS * 8;
+constexpr size_t WS_T = WS_PARTS + MAX_PART_ELEMS * 4;
+
 }  // namespace
 
 extern "C" {
@@ -49,10 +57,8 @@ extern "C" {
 size_t eora_workspace_bytes(int M, int d_in, int d_out, int r)
 {
     if (check_backbone_shape(M, d_in, d_out, r) != EORA_OK) return 0;
-    const size_t mc = (size_t)(M < CHUNK_TOKENS ? M : CHUNK_TOKENS);
-    const size_t yblocks = (mc + 15) / 16;
     // partials of t for the small-M kernels, and t itself as fp16 M x r for the prefill GEMM
-    return WS_HEADER + yblocks * MAX_KCN * 16 * (size_t)r * sizeof(float) + round256((size_t)M * r * 2);
+    return WS_T + round256((size_t)M * r * 2);
 }
 
 int eora_workspace_init(void* workspace, size_t workspace_bytes, void* stream)
@@ -60,7 +66,10 @@ int eora_workspace_init(void* workspace, size_t workspace_bytes, void* stream)
     if (!workspace) return EORA_ERR_NULL;
     if (!aligned16(workspace)) return EORA_ERR_ALIGN;
     if (workspace_bytes < WS_HEADER) return EORA_ERR_WORKSPACE;
-    if (failed(launch_clear_words((uint32_t*)workspace, (int)(WS_HEADER / 4), (hipStream_t)stream), "workspace_init"))
+    // everything is cleared, not only the header: the tagged partials must not hold a leftover word
+    // that reads as the tag of a coming launch
+    if (workspace_bytes / 4 > 0x7fffffffull) return EORA_ERR_WORKSPACE;
+    if (failed(launch_clear_words((uint32_t*)workspace, (int)(workspace_bytes / 4), (hipStream_t)stream), "workspace_init"))
         return EORA_ERR_LAUNCH;
     return EORA_OK;
 }
@@ -115,8 +124,7 @@ int eora_linear_q(const void* x, const void* qweight, const void* scales, const 
 
     // Many tokens: MFMA-bound GEMM (t = x.A^T first, then one GEMM over d_in and r).
     if (M >= PREFILL_MIN_TOKENS && (r == 0 || (ab_bits == 16 && r % 128 == 0))) {
-        const size_t mc = (size_t)(M < CHUNK_TOKENS ? M : CHUNK_TOKENS);
-        _Float16* T = (_Float16*)((char*)workspace + WS_HEADER + ((mc + 15) / 16) * MAX_KCN * 16 * (size_t)r * sizeof(float));
+        _Float16* T = (_Float16*)((char*)workspace + WS_T);
         if (r > 0) {
             PrefillArgs p{};
             p.x = (const _Float16*)x; p.ldx = d_in;
@@ -154,7 +162,8 @@ int eora_linear_q(const void* x, const void* qweight, const void* scales, const 
         a.B_scales = (const _Float16*)B_scales;
         a.y = (_Float16*)y + (size_t)m0 * d_out;
         a.hdr = (uint32_t*)workspace;
-        a.tpart = (float*)((char*)workspace + WS_HEADER);
+        a.tpart = (float*)((char*)workspace + WS_PARTS);
+        a.tpair = (unsigned long long*)((char*)workspace + WS_PAIRS);
         a.M = M - m0 < CHUNK_TOKENS ? M - m0 : CHUNK_TOKENS;
         a.d_in = d_in;
         a.d_out = d_out;
@@ -202,7 +211,7 @@ int eora_linear_sp24(const void* x, const void* values, const void* indices,
         a.B = B;
         a.y = (_Float16*)y + (size_t)m0 * d_out;
         a.hdr = (uint32_t*)workspace;
-        a.tpart = (float*)((char*)workspace + WS_HEADER);
+        a.tpart = (float*)((char*)workspace + WS_PARTS);
         a.M = M - m0 < CHUNK_TOKENS ? M - m0 : CHUNK_TOKENS;
         a.d_in = d_in;
         a.d_out = d_out;

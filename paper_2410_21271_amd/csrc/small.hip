@@ -67,6 +67,7 @@ __global__ __launch_bounds__(NW * 64) void small_kernel(FusedArgs a)
     if constexpr (LOWRANK) {
     if ((int)blockIdx.x < nprod) {
         // ======================================================================= producer
+        __builtin_amdgcn_s_setprio(3);                   // everyone's critical path: issue ahead of the consumers' dequant
         constexpr int KTA = Fmt<FA>::KT, NMF = KTA / 32;
         const int NRB = a.r / 16;
         const int u = blockIdx.x, rho = u % NRB, kc = u / NRB;
@@ -126,13 +127,14 @@ __global__ __launch_bounds__(NW * 64) void small_kernel(FusedArgs a)
             float v = 0.f;
 #pragma unroll
             for (int w2 = 0; w2 < NW; ++w2) v += red[w2][i][col];
-            // partial layout: [kc][token row (16)][r]; written through to memory (system scope)
-            *(volatile float*)&a.tpart[((size_t)kc * 16 + i) * a.r + 16 * rho + col] = v;
+            // partial layout: [kc][token row (16)][r], every element an 8-byte (value, epoch + 1) pair
+            // written by ONE write-through store: a reader that finds this launch's tag has this
+            // launch's value, so the flag below need not wait for these stores to be acknowledged
+            const unsigned long long pr = ((unsigned long long)(epoch + 1) << 32) | __builtin_bit_cast(uint32_t, v);
+            __hip_atomic_store(&a.tpair[((size_t)kc * 16 + i) * a.r + 16 * rho + col], pr, __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
         }
-        // wait until the write-through stores are acknowledged (at system scope: in memory), so that
-        // the flag below cannot overtake them; no L2 write-back of an agent-scope release is needed
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
+        // (tid < 16 * mt) is within wavefront 0, whose lane 0 raises the flag: same wavefront, later instruction
         TL_STAMP(3);
         if (tid == 0) {
             for (int rep = 0; rep < HDR_FLAG_REPLICAS; ++rep)      // one copy per group of pollers
@@ -179,6 +181,14 @@ __global__ __launch_bounds__(NW * 64) void small_kernel(FusedArgs a)
     __syncthreads();
 
     TL_STAMP(1);
+    // a first look at the flags, requested now and examined after the backbone: when the producers
+    // are done by the time this request reaches memory, the poll below costs no round trip
+    uint32_t early = 0;
+    if constexpr (LOWRANK) {
+        if (wave == 0)
+            early = ld_relaxed(a.hdr + HDR_FLAGS0 + HDR_FLAGS_REPLICA_STRIDE * (blockIdx.x % HDR_FLAG_REPLICAS) +
+                               (lane < nprod ? lane : nprod - 1));
+    }
     // ---- backbone ------------------------------------------------------------------------------------
     f4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -209,8 +219,8 @@ __global__ __launch_bounds__(NW * 64) void small_kernel(FusedArgs a)
         const uint32_t epoch = s_epoch;
         if (wave == 0) {
             const uint32_t* flags = a.hdr + HDR_FLAGS0 + HDR_FLAGS_REPLICA_STRIDE * (blockIdx.x % HDR_FLAG_REPLICAS);
-            bool ok = false;
-            for (int spins = 0; spins <= a.spin_limit; ++spins) {
+            bool ok = nprod <= 64 && __all(early == epoch + 1);
+            for (int spins = 0; !ok && spins <= a.spin_limit; ++spins) {
                 bool all = true;
                 for (int f = lane; f < nprod; f += 64) all = all && (ld_relaxed(&flags[f]) == epoch + 1);
                 if (__all(all)) { ok = true; break; }
@@ -218,19 +228,47 @@ __global__ __launch_bounds__(NW * 64) void small_kernel(FusedArgs a)
             }
             TL_STAMP(4);
             if (ok) {
-                // Ordinary (cached) loads, no agent-scope acquire fence: the partials were written
-                // through to memory before their flags, no line of them is read in this launch before
-                // all flags are up, and caches hold nothing of them from before the launch.
-                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+                // The partials are read with ordinary (cached) loads first: the flags are up, so their
+                // stores were issued long ago and have all but certainly landed, and caches hold
+                // nothing of them from before the launch.  The tags say whether that held; a lane
+                // that finds an old tag reads again past the caches until it does (bounded).
                 const int T = mt * a.r;                  // elements of t; a.r is a multiple of 32
                 for (int e = 4 * lane; e < T; e += 256) {
                     const int i = e / a.r, col = e % a.r;
-                    const float* p = a.tpart + (size_t)i * a.r + col;
-                    f4 v = {0.f, 0.f, 0.f, 0.f};
+                    const unsigned long long* p = a.tpair + (size_t)i * a.r + col;
+                    float v0 = 0.f, v1 = 0.f, v2 = 0.f, v3 = 0.f;
+                    uint32_t bad = 0;
 #pragma unroll 4
-                    for (int kc = 0; kc < a.kcn; ++kc) v += *(const f4*)(p + (size_t)kc * 16 * a.r);   // fixed order
+                    for (int kc = 0; kc < a.kcn; ++kc) {                       // fixed order
+                        const uint2* pk = (const uint2*)(p + (size_t)kc * 16 * a.r);
+                        const uint2 p0 = pk[0], p1 = pk[1], p2 = pk[2], p3 = pk[3];      // .x value, .y tag
+                        bad |= (p0.y ^ (epoch + 1)) | (p1.y ^ (epoch + 1)) | (p2.y ^ (epoch + 1)) | (p3.y ^ (epoch + 1));
+                        v0 += __builtin_bit_cast(float, p0.x);
+                        v1 += __builtin_bit_cast(float, p1.x);
+                        v2 += __builtin_bit_cast(float, p2.x);
+                        v3 += __builtin_bit_cast(float, p3.x);
+                    }
+                    bool good = bad == 0;
+                    for (int spins = 0; !good && spins <= a.spin_limit; ++spins) {
+                        bad = 0;
+                        float w[4] = {0.f, 0.f, 0.f, 0.f};
+                        for (int kc = 0; kc < a.kcn; ++kc) {
+#pragma unroll
+                            for (int c = 0; c < 4; ++c) {
+                                const unsigned long long pr = __hip_atomic_load(p + (size_t)kc * 16 * a.r + c, __ATOMIC_RELAXED,
+                                                                                __HIP_MEMORY_SCOPE_AGENT);
+                                bad |= (uint32_t)(pr >> 32) ^ (epoch + 1);
+                                w[c] += __builtin_bit_cast(float, (uint32_t)pr);
+                            }
+                        }
+                        good = bad == 0;
+                        v0 = w[0]; v1 = w[1]; v2 = w[2]; v3 = w[3];
+                    }
+                    const f4 v = {v0, v1, v2, v3};
+                    ok = ok && good;
                     *(f4*)(ts + e) = v;
                 }
+                ok = __all(ok);
             }
             TL_STAMP(5);
             if (lane == 0) {

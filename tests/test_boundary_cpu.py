@@ -76,7 +76,7 @@ def test_linear_q_validation_codes():
     null = ctypes.c_void_p(0)
 
     def call(x=good, qw=good, sc=good, qz=good, A=good, B=good, As=null, Bs=null, y=good, M=1, d_in=256, d_out=32,
-             r=32, w_bits=4, group=128, ab_bits=16, ws=good, ws_bytes=1 << 20):
+             r=32, w_bits=4, group=128, ab_bits=16, ws=good, ws_bytes=1 << 24):
         return L.eora_linear_q(x, qw, sc, qz, A, B, As, Bs, y, M, d_in, d_out, r, w_bits, group, ab_bits, ws,
                                ws_bytes, null)
 
