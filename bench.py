@@ -37,6 +37,12 @@ WORKLOADS = {
     "llama3-70b-layer-decode-sp24-bare-M1": dict(model="70b", w_bits=0, ab_bits=16, r=0, M=1, cfg=5),
     "llama3-70b-layer-decode-sp24-r128fp16-M64": dict(model="70b", w_bits=0, ab_bits=16, r=128, M=64, cfg=5),
 }
+# the same layers with the linears that read the same x sharing a launch (q/k/v and gate/up): four launches a step
+for _n in ("llama3-8b-layer-decode-w3g128-r128fp16-M1", "llama3-8b-layer-decode-w3g128-bare-M1",
+           "llama3-8b-layer-decode-w4g128-r128fp16-M1", "llama3-8b-layer-decode-w4g128-r128q4-M1",
+           "llama3-8b-layer-decode-w4g128-bare-M1"):
+    WORKLOADS[_n + "-grouped"] = dict(WORKLOADS[_n], grouped=True)
+GROUPS = (("q", "k", "v"), ("o",), ("gate", "up"), ("down",))
 for _r in (64, 256, 512):
     WORKLOADS["llama3-8b-layer-decode-w4g128-r%dq4-M1" % _r] = dict(model="8b", w_bits=4, ab_bits=4, r=_r, M=1, cfg=3)
 DEFAULT = "llama3-8b-layer-decode-w3g128-r128fp16-M1"
@@ -106,6 +112,29 @@ class Linear:
             return
         eora.linear_q(self.x, qw, sc, qz, A, B, As, Bs, self.y, self.M, self.d_in, self.d_out, self.r,
                       self.w_bits, 128, self.ab_bits, self.ws)
+
+
+class Group:
+    """Linears that read the same x, served by one eora_linear_q_group call (x is the first member's)."""
+
+    def __init__(self, members):
+        import paper_2410_21271_amd as eora
+        self.members = members
+        self.name = "+".join(L.name for L in members)
+        self.d_in = members[0].d_in
+        m0 = members[0]
+        self.ws = eora.new_workspace(m0.M, m0.d_in, max(L.d_out for L in members), m0.r)
+        # x is read once per launch, not once per member
+        self.bytes = sum(L.bytes for L in members) - 2 * m0.M * m0.d_in * (len(members) - 1)
+        self.flops = sum(L.flops for L in members)
+
+    def run(self, copy):
+        import paper_2410_21271_amd as eora
+        m0 = self.members[0]
+        if len(self.members) == 1:
+            return m0.run(copy)
+        mem = [tuple(L.copies[copy % len(L.copies)]) + (L.y, L.d_out) for L in self.members]
+        eora.linear_q_group(m0.x, mem, m0.M, m0.d_in, m0.r, m0.w_bits, 128, m0.ab_bits, self.ws)
 
 
 def timed_graph(fn, count):
@@ -206,8 +235,13 @@ def main():
         args.steps = min(args.steps, 50)
     linears = [Linear(n, di, do, spec, synth.seed_for(spec["cfg"], i), ncopies) for i, (n, di, do) in enumerate(shapes)]
 
+    launches = linears
+    if spec.get("grouped"):
+        launches = [Group([L for L in linears if L.name in g]) for g in GROUPS]
+        layer_bytes = sum(G.bytes for G in launches)
+
     def step(i):
-        for L in linears:
+        for L in launches:
             L.run(i)
 
     for i in range(args.warmup):
@@ -217,7 +251,7 @@ def main():
 
     # each linear on its own (graph of back-to-back launches over the rotating copies)
     per_linear = {}
-    for L in linears:
+    for L in launches:
         us = 1e3 * timed_graph(L.run, 200 if spec["M"] <= 16 else 40)
         per_linear[L.name] = dict(us=round(us, 3), GBps=round(L.bytes / us / 1e3, 1),
                                   frac_hbm=round(L.bytes / us / 1e3 / HBM_PEAK_GBS, 4),
@@ -228,7 +262,7 @@ def main():
     # o, gate, up: six of the seven launches of a step, 69 % of its bytes).  Its average launch moves
     # the average algorithmic bytes of those six shapes; its average duration is the mean of their
     # event-timed back-to-back launches (which includes the gap between consecutive launches).
-    dom = [L for L in linears if L.d_in == linears[0].d_in]
+    dom = [L for L in launches if L.d_in == linears[0].d_in]
     dom_bytes = sum(L.bytes for L in dom) / len(dom)
     dom_us = sum(per_linear[L.name]["us"] for L in dom) / len(dom)
     traffic = None

@@ -147,6 +147,31 @@ int eora_linear_q(const void* x, const void* qweight, const void* scales, const 
                   void* y, int M, int d_in, int d_out, int r, int w_bits, int group, int ab_bits,
                   void* workspace, size_t workspace_bytes, void* stream);
 
+/* Several layers that read the SAME x in one launch: the query / key / value projections, or the
+ * gate / up projections, of a decoder layer (the paper compensates every linear of the model the
+ * same way, Sec. 3; which of them share an input is the transformer's structure).  Member m is an
+ * eora_linear_q layer of its own (own weights, factors, output and d_out); M, d_in, r, w_bits,
+ * group and ab_bits are common.  Results are bit-identical to n_members separate eora_linear_q
+ * calls.  For one to four tokens and group == 128 this is one launch, which pays the launch and
+ * the hand-over of x.A^T once; other shapes run the members one after the other.
+ * members: HOST array (read during the call only) of 1..4 entries; pointers inside are DEVICE
+ * pointers with the meaning and constraints of the eora_linear_q arguments of the same name.
+ * workspace: at least the largest eora_workspace_bytes(M, d_in, d_out_m, r). */
+typedef struct {
+    const void* qweight;
+    const void* scales;
+    const void* qzeros;
+    const void* A;
+    const void* B;
+    const void* A_scales;
+    const void* B_scales;
+    void* y;
+    int d_out;
+} eora_q_member;
+int eora_linear_q_group(const void* x, const eora_q_member* members, int n_members,
+                        int M, int d_in, int r, int w_bits, int group, int ab_bits,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
 /* Same layer with a 2:4 structured-sparse fp16 backbone (Sec. 1, Sec. 4.2); A, B are F16 tiles.
  * Constraints as above with r % 32 == 0. */
 int eora_linear_sp24(const void* x, const void* values, const void* indices,

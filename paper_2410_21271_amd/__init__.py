@@ -10,5 +10,5 @@ from .binding import (  # noqa: F401
     qweight_bytes, qzeros_bytes, scales_bytes, sp24_values_bytes, sp24_indices_bytes, workspace_bytes,
     workspace_init, workspace_error, debug_set_spin_limit, new_workspace,
     pack_q, pack_factor_f16, pack_factor_q4, pack_sp24,
-    linear_q, linear_sp24, unpack_q, dequant_q, expand_sp24,
+    linear_q, linear_q_group, linear_sp24, unpack_q, dequant_q, expand_sp24,
 )

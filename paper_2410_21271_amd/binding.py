@@ -22,6 +22,12 @@ def lib_path():
     return _LIB_PATH
 
 
+class QMember(ctypes.Structure):
+    """eora_q_member of include/eora.h: one layer of a group that shares x."""
+    _fields_ = [(n, ctypes.c_void_p) for n in ("qweight", "scales", "qzeros", "A", "B", "A_scales", "B_scales", "y")] + \
+               [("d_out", ctypes.c_int)]
+
+
 def _load():
     if not os.path.exists(_LIB_PATH):
         raise ImportError("libeora.so is not built: run `python paper_2410_21271_amd/build.py` "
@@ -48,6 +54,7 @@ def _load():
         "eora_pack_factor_q4": (ci, [vp, vp, ci, ci, vp, vp]),
         "eora_pack_sp24": (ci, [vp, vp, ci, ci, vp, vp]),
         "eora_linear_q": (ci, [vp] * 9 + [ci] * 7 + [vp, sz, vp]),
+        "eora_linear_q_group": (ci, [vp, ctypes.POINTER(QMember), ci] + [ci] * 6 + [vp, sz, vp]),
         "eora_linear_sp24": (ci, [vp] * 6 + [ci] * 4 + [vp, sz, vp]),
         "eora_unpack_q": (ci, [vp, vp, vp, vp, ci, ci, ci, ci, vp]),
         "eora_dequant_q": (ci, [vp, vp, vp, vp, ci, ci, ci, ci, vp]),
@@ -65,7 +72,7 @@ EXPORTS = ["eora_status_string", "eora_qweight_bytes", "eora_qzeros_bytes", "eor
            "eora_sp24_values_bytes", "eora_sp24_indices_bytes", "eora_workspace_bytes", "eora_workspace_init",
            "eora_workspace_error", "eora_debug_set_spin_limit", "eora_pack_q",
            "eora_pack_factor_f16", "eora_pack_factor_q4", "eora_pack_sp24", "eora_linear_q",
-           "eora_linear_sp24", "eora_unpack_q", "eora_dequant_q", "eora_expand_sp24"]
+           "eora_linear_q_group", "eora_linear_sp24", "eora_unpack_q", "eora_dequant_q", "eora_expand_sp24"]
 
 
 def status_string(status):
@@ -192,6 +199,17 @@ def linear_q(x, qweight, scales, qzeros, A, B, A_scales, B_scales, y, M, d_in, d
     _check(lib.eora_linear_q(_dp(x), _dp(qweight), _dp(scales), _dp(qzeros), _dp(A), _dp(B), _dp(A_scales),
                              _dp(B_scales), _dp(y), M, d_in, d_out, r, w_bits, group, ab_bits,
                              _dp(workspace), ws_bytes, _stream()), "linear_q")
+
+
+def linear_q_group(x, members, M, d_in, r, w_bits, group, ab_bits, workspace):
+    """members: sequence of (qweight, scales, qzeros, A, B, A_scales, B_scales, y, d_out)."""
+    arr = (QMember * len(members))()
+    for e, m in zip(arr, members):
+        (e.qweight, e.scales, e.qzeros, e.A, e.B, e.A_scales, e.B_scales, e.y) = [_dp(t) for t in m[:8]]
+        e.d_out = m[8]
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib.eora_linear_q_group(_dp(x), arr, len(members), M, d_in, r, w_bits, group, ab_bits,
+                                   _dp(workspace), ws_bytes, _stream()), "linear_q_group")
 
 
 def linear_sp24(x, values, indices, A, B, y, M, d_in, d_out, r, workspace):

@@ -50,6 +50,66 @@ constexpr size_t WS_PAIRS = WS_HEADER;
 constexpr size_t WS_PARTS = WS_PAIRS + MAX_PART_ELEMS * 8;
 constexpr size_t WS_T = WS_PARTS + MAX_PART_ELEMS * 4;
 
+// factor formats of the (r, ab_bits) a call names
+int factor_formats(int r, int ab_bits, int* fa, int* fe)
+{
+    *fa = *fe = S_NONE;
+    if (r == 0) return EORA_OK;
+    if (ab_bits == 16) {
+        if (r % 32) return EORA_ERR_SHAPE;
+        *fa = *fe = S_F16;
+    } else if (ab_bits == 4) {
+        if (r != 64 && r % 128) return EORA_ERR_SHAPE;
+        *fe = (r == 64) ? S_Q4S64 : S_Q4S128;
+        *fa = S_Q4S128;
+    } else {
+        return EORA_ERR_UNSUPPORTED;
+    }
+    return EORA_OK;
+}
+
+// k-ranges of the down-projection: many for few tokens (every consumer adds the partials itself),
+// a divisor of the number of 128-wide k-tiles
+int pick_kcn(int M, int d_in)
+{
+    const int cap = M <= 4 ? MAX_KCN : (M <= 8 ? 4 : 2);
+    int kcn = 1;
+    for (int c = 2; c <= cap; ++c)
+        if ((d_in / 128) % c == 0) kcn = c;
+    return kcn;
+}
+
+// one launch of the decode kernel for validated members that share x
+int launch_group(const void* x, const eora_q_member* members, int n, int M, int d_in, int r, int w_bits, int group,
+                 int fa, int fe, int nw, int nq, void* workspace, hipStream_t stream)
+{
+    if (M == 0) return EORA_OK;
+    GroupArgs a{};
+    a.x = (const _Float16*)x;
+    for (int m = 0; m < n; ++m) {
+        a.w[m] = members[m].qweight;
+        a.w_scales[m] = (const _Float16*)members[m].scales;
+        a.w_zeros[m] = (const uint32_t*)members[m].qzeros;
+        a.A[m] = members[m].A;
+        a.A_scales[m] = (const _Float16*)members[m].A_scales;
+        a.B[m] = members[m].B;
+        a.B_scales[m] = (const _Float16*)members[m].B_scales;
+        a.y[m] = (_Float16*)members[m].y;
+        a.d_out[m] = members[m].d_out;
+    }
+    a.n = n;
+    a.hdr = (uint32_t*)workspace;
+    a.tpair = (unsigned long long*)((char*)workspace + WS_PAIRS);
+    a.M = M;
+    a.d_in = d_in;
+    a.r = r;
+    a.group = group;
+    a.kcn = pick_kcn(M, d_in);
+    a.spin_limit = g_spin_limit;
+    if (failed(launch_small(a, w_bits == 4 ? S_Q4 : S_Q3, fa, fe, nw, nq, stream), "linear_q (decode)")) return EORA_ERR_LAUNCH;
+    return EORA_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -87,39 +147,40 @@ int eora_workspace_error(const void* workspace, void* stream)
 
 void eora_debug_set_spin_limit(int iterations) { g_spin_limit = iterations < 0 ? 0 : iterations; }
 
-int eora_linear_q(const void* x, const void* qweight, const void* scales, const void* qzeros,
-                  const void* A, const void* B, const void* A_scales, const void* B_scales,
-                  void* y, int M, int d_in, int d_out, int r, int w_bits, int group, int ab_bits,
-                  void* workspace, size_t workspace_bytes, void* stream)
+// every check of one quantised layer; nothing is enqueued
+static int validate_linear_q(const void* x, const eora_q_member& e, int M, int d_in, int r, int w_bits, int group,
+                             int ab_bits, const void* workspace, size_t workspace_bytes, int* fa, int* fe)
 {
-    if (!x || !qweight || !scales || !qzeros || !y) return EORA_ERR_NULL;
+    if (!x || !e.qweight || !e.scales || !e.qzeros || !e.y) return EORA_ERR_NULL;
     if (w_bits != 3 && w_bits != 4) return EORA_ERR_UNSUPPORTED;
-    int rc = check_backbone_shape(M, d_in, d_out, r);
+    int rc = check_backbone_shape(M, d_in, e.d_out, r);
     if (rc != EORA_OK) return rc;
     rc = check_group(d_in, group);
     if (rc != EORA_OK) return rc;
-    int fe = S_NONE, fa = S_NONE;
+    *fe = *fa = S_NONE;
     if (r > 0) {
-        if (!A || !B) return EORA_ERR_NULL;
-        if (ab_bits == 16) {
-            if (r % 32) return EORA_ERR_SHAPE;
-            fe = S_F16;
-            fa = S_F16;
-        } else if (ab_bits == 4) {
-            if (!A_scales || !B_scales) return EORA_ERR_NULL;
-            if (r != 64 && r % 128) return EORA_ERR_SHAPE;
-            fe = (r == 64) ? S_Q4S64 : S_Q4S128;
-            fa = S_Q4S128;
-        } else {
-            return EORA_ERR_UNSUPPORTED;
-        }
-        if (!aligned16(A) || !aligned16(B) || !aligned16(A_scales) || !aligned16(B_scales)) return EORA_ERR_ALIGN;
+        if (!e.A || !e.B) return EORA_ERR_NULL;
+        if (ab_bits == 4 && (!e.A_scales || !e.B_scales)) return EORA_ERR_NULL;
+        rc = factor_formats(r, ab_bits, fa, fe);
+        if (rc != EORA_OK) return rc;
+        if (!aligned16(e.A) || !aligned16(e.B) || !aligned16(e.A_scales) || !aligned16(e.B_scales)) return EORA_ERR_ALIGN;
     }
-    if (!aligned16(x) || !aligned16(qweight) || !aligned16(scales) || !aligned16(qzeros) || !aligned16(y))
+    if (!aligned16(x) || !aligned16(e.qweight) || !aligned16(e.scales) || !aligned16(e.qzeros) || !aligned16(e.y))
         return EORA_ERR_ALIGN;
     if (!workspace) return EORA_ERR_WORKSPACE;
     if (!aligned16(workspace)) return EORA_ERR_ALIGN;
-    if (workspace_bytes < eora_workspace_bytes(M, d_in, d_out, r)) return EORA_ERR_WORKSPACE;
+    if (workspace_bytes < eora_workspace_bytes(M, d_in, e.d_out, r)) return EORA_ERR_WORKSPACE;
+    return EORA_OK;
+}
+
+// one validated quantised layer
+static int run_linear_q(const void* x, const eora_q_member& e, int M, int d_in, int r, int w_bits, int group, int ab_bits,
+                        int fa, int fe, void* workspace, void* stream)
+{
+    const void *qweight = e.qweight, *scales = e.scales, *qzeros = e.qzeros, *A = e.A, *B = e.B;
+    const void *A_scales = e.A_scales, *B_scales = e.B_scales;
+    void* y = e.y;
+    const int d_out = e.d_out;
     if (M == 0) return EORA_OK;
 
     // Many tokens: MFMA-bound GEMM (t = x.A^T first, then one GEMM over d_in and r).
@@ -144,12 +205,12 @@ int eora_linear_q(const void* x, const void* qweight, const void* scales, const 
         return EORA_OK;
     }
 
-    // k-ranges of the down-projection: many for few tokens (every consumer adds the partials itself),
-    // a divisor of the number of 128-wide k-tiles
-    const int cap = M <= 4 ? MAX_KCN : (M <= 8 ? 4 : 2);
-    int kcn = 1;
-    for (int c = 2; c <= cap; ++c)
-        if ((d_in / 128) % c == 0) kcn = c;
+    int nw = 0, nq = 0;
+    if (small_kernel_fits(M, d_in, group, &nw, &nq))
+        return launch_group(x, &e, 1, M, d_in, r, w_bits, group, fa, fe, nw, nq, workspace, (hipStream_t)stream);
+
+    // k-ranges of the down-projection: a divisor of the number of 128-wide k-tiles
+    const int kcn = pick_kcn(M, d_in);
     for (int m0 = 0; m0 < M; m0 += CHUNK_TOKENS) {
         FusedArgs a{};
         a.x = (const _Float16*)x + (size_t)m0 * d_in;
@@ -163,7 +224,6 @@ int eora_linear_q(const void* x, const void* qweight, const void* scales, const 
         a.y = (_Float16*)y + (size_t)m0 * d_out;
         a.hdr = (uint32_t*)workspace;
         a.tpart = (float*)((char*)workspace + WS_PARTS);
-        a.tpair = (unsigned long long*)((char*)workspace + WS_PAIRS);
         a.M = M - m0 < CHUNK_TOKENS ? M - m0 : CHUNK_TOKENS;
         a.d_in = d_in;
         a.d_out = d_out;
@@ -171,11 +231,41 @@ int eora_linear_q(const void* x, const void* qweight, const void* scales, const 
         a.group = group;
         a.kcn = kcn;
         a.spin_limit = g_spin_limit;
-        int nw = 0, nq = 0;
-        const int fm = w_bits == 4 ? S_Q4 : S_Q3;
-        const hipError_t e = small_kernel_fits(a, &nw, &nq) ? launch_small(a, fm, fa, fe, nw, nq, (hipStream_t)stream)
-                                                            : launch_fused(a, fm, fa, fe, (hipStream_t)stream);
-        if (failed(e, "linear_q")) return EORA_ERR_LAUNCH;
+        if (failed(launch_fused(a, w_bits == 4 ? S_Q4 : S_Q3, fa, fe, (hipStream_t)stream), "linear_q")) return EORA_ERR_LAUNCH;
+    }
+    return EORA_OK;
+}
+
+int eora_linear_q(const void* x, const void* qweight, const void* scales, const void* qzeros,
+                  const void* A, const void* B, const void* A_scales, const void* B_scales,
+                  void* y, int M, int d_in, int d_out, int r, int w_bits, int group, int ab_bits,
+                  void* workspace, size_t workspace_bytes, void* stream)
+{
+    const eora_q_member e{qweight, scales, qzeros, A, B, A_scales, B_scales, y, d_out};
+    int fa, fe;
+    const int rc = validate_linear_q(x, e, M, d_in, r, w_bits, group, ab_bits, workspace, workspace_bytes, &fa, &fe);
+    if (rc != EORA_OK) return rc;
+    return run_linear_q(x, e, M, d_in, r, w_bits, group, ab_bits, fa, fe, workspace, stream);
+}
+
+int eora_linear_q_group(const void* x, const eora_q_member* members, int n_members,
+                        int M, int d_in, int r, int w_bits, int group, int ab_bits,
+                        void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!x || !members) return EORA_ERR_NULL;
+    if (n_members < 1 || n_members > MAX_GROUP) return EORA_ERR_SHAPE;
+    int fa = S_NONE, fe = S_NONE;
+    for (int m = 0; m < n_members; ++m) {               // every member is validated before anything is enqueued
+        const int rc = validate_linear_q(x, members[m], M, d_in, r, w_bits, group, ab_bits, workspace, workspace_bytes, &fa, &fe);
+        if (rc != EORA_OK) return rc;
+    }
+    int nw = 0, nq = 0;
+    if (small_kernel_fits(M, d_in, group, &nw, &nq) &&
+        (r == 0 || (r / 16) * pick_kcn(M, d_in) * n_members <= HDR_FLAGS_PER_BLOCK))
+        return launch_group(x, members, n_members, M, d_in, r, w_bits, group, fa, fe, nw, nq, workspace, (hipStream_t)stream);
+    for (int m = 0; m < n_members; ++m) {               // shapes the decode kernel does not take: one after the other
+        const int rc = run_linear_q(x, members[m], M, d_in, r, w_bits, group, ab_bits, fa, fe, workspace, stream);
+        if (rc != EORA_OK) return rc;
     }
     return EORA_OK;
 }
@@ -198,10 +288,7 @@ int eora_linear_sp24(const void* x, const void* values, const void* indices,
     if (!aligned16(workspace)) return EORA_ERR_ALIGN;
     if (workspace_bytes < eora_workspace_bytes(M, d_in, d_out, r)) return EORA_ERR_WORKSPACE;
     if (M == 0) return EORA_OK;
-    const int cap = M <= 4 ? MAX_KCN : (M <= 8 ? 4 : 2);
-    int kcn = 1;
-    for (int c = 2; c <= cap; ++c)
-        if ((d_in / 128) % c == 0) kcn = c;
+    const int kcn = pick_kcn(M, d_in);
     for (int m0 = 0; m0 < M; m0 += CHUNK_TOKENS) {
         SparseArgs a{};
         a.x = (const _Float16*)x + (size_t)m0 * d_in;

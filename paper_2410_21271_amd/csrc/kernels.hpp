@@ -36,15 +36,35 @@ struct FusedArgs {
     const _Float16* B_scales;
     _Float16* y;              // M x d_out fp16 row-major
     uint32_t* hdr;            // workspace header
-    float* tpart;             // token blocks x kcn x 16 x r fp32 partials of t (fused.hip)
-    unsigned long long* tpair;   // kcn x 16 x r (value, tag) pairs: partials of t of the decode kernel (small.hip)
+    float* tpart;             // token blocks x kcn x 16 x r fp32 partials of t
     int M, d_in, d_out, r, group, kcn, spin_limit;
 };
 
 hipError_t launch_fused(const FusedArgs& a, int fm, int fa, int fe, hipStream_t stream);
-// decode kernel for 1..4 tokens (small.hip): whether the shape fits, with its wavefront / quad split
-bool small_kernel_fits(const FusedArgs& a, int* nw, int* nq);
-hipError_t launch_small(const FusedArgs& a, int fm, int fa, int fe, int nw, int nq, hipStream_t stream);
+
+// Decode kernel for 1..4 tokens (small.hip).  One launch serves up to MAX_GROUP linears that read the
+// same x (the q/k/v or the gate/up projections of a decoder layer): same d_in, rank and formats,
+// own weights, factors, output and d_out.
+constexpr int MAX_GROUP = 4;
+struct GroupArgs {
+    const _Float16* x;                  // M x d_in fp16 row-major, shared
+    const void* w[MAX_GROUP];           // backbone tiles
+    const _Float16* w_scales[MAX_GROUP];
+    const uint32_t* w_zeros[MAX_GROUP];
+    const void* A[MAX_GROUP];           // r x d_in tiles
+    const _Float16* A_scales[MAX_GROUP];
+    const void* B[MAX_GROUP];           // d_out x r tiles
+    const _Float16* B_scales[MAX_GROUP];
+    _Float16* y[MAX_GROUP];             // M x d_out fp16 row-major
+    int d_out[MAX_GROUP];
+    int n;                              // members, 1..MAX_GROUP
+    uint32_t* hdr;                      // workspace header
+    unsigned long long* tpair;          // members x kcn x 16 x r (value, tag) pairs: partials of t
+    int M, d_in, r, group, kcn, spin_limit;
+};
+// whether the shape fits the decode kernel, with its wavefront / quad split
+bool small_kernel_fits(int M, int d_in, int group, int* nw, int* nq);
+hipError_t launch_small(const GroupArgs& a, int fm, int fa, int fe, int nw, int nq, hipStream_t stream);
 hipError_t launch_clear_words(uint32_t* p, int nwords, hipStream_t stream);
 
 struct SparseArgs {

@@ -24,13 +24,13 @@ constexpr int XSTAGE = 4;   // 16-byte chunks of x a thread may stage
 
 #ifdef EORA_TIMELINE
 // debug build only: per-workgroup time stamps (100 MHz counter) behind the partials of t
-#define TL_STAMP(slot) do { if (tid == 0) ((unsigned long long*)(a.tpart + (1 << 20)))[blockIdx.x * 8 + (slot)] = wall_clock64(); } while (0)
+#define TL_STAMP(slot) do { if (tid == 0) (a.tpair + (1 << 20))[blockIdx.x * 8 + (slot)] = wall_clock64(); } while (0)
 #else
 #define TL_STAMP(slot) do { } while (0)
 #endif
 
 template <int FM, int FA, int FE, int NW, int NQ, bool M1>
-__global__ __launch_bounds__(NW * 64) void small_kernel(FusedArgs a)
+__global__ __launch_bounds__(NW * 64) void small_kernel(GroupArgs a)
 {
     constexpr bool LOWRANK = FA != S_NONE;
     constexpr int NT = NW * 64;
@@ -42,7 +42,8 @@ __global__ __launch_bounds__(NW * 64) void small_kernel(FusedArgs a)
     const int n = lane & 15, j = lane >> 4;
     const int mt = M1 ? 1 : a.M;                         // 1..4 tokens, one token block (M1: exactly one)
     const int mrow = n < mt ? n : 0;                     // lanes beyond the tokens re-read row 0; their results are dropped
-    const int nprod = LOWRANK ? (a.r / 16) * a.kcn : 0;  // producer workgroups
+    const int upl = LOWRANK ? (a.r / 16) * a.kcn : 0;    // units of t (= producer workgroups) per member
+    const int nprod = upl * a.n;                         // producer workgroups
     const int ldxs = a.d_in + 32;                        // LDS row stride of x in halves (64 bytes of padding)
     _Float16* xs = (_Float16*)eora_smem;
     float* ts = (float*)(eora_smem + (size_t)mt * ldxs * 2);     // t, fp32 mt x r (consumers)
@@ -70,8 +71,8 @@ __global__ __launch_bounds__(NW * 64) void small_kernel(FusedArgs a)
         __builtin_amdgcn_s_setprio(3);                   // everyone's critical path: issue ahead of the consumers' dequant
         constexpr int KTA = Fmt<FA>::KT, NMF = KTA / 32;
         const int NRB = a.r / 16;
-        const int u = blockIdx.x, rho = u % NRB, kc = u / NRB;
-        const Factor fa{(const uint32_t*)a.A, a.A_scales, a.d_in / KTA};
+        const int u = blockIdx.x, mem = u / upl, ul = u % upl, rho = ul % NRB, kc = ul / NRB;
+        const Factor fa{(const uint32_t*)a.A[mem], a.A_scales[mem], a.d_in / KTA};
         const int tpc = fa.ntk / a.kcn;                  // k-tiles of this unit
         const int first = kc * tpc + wave;
         const int nsteps = wave < tpc ? (tpc - wave + NW - 1) / NW : 0;
@@ -131,7 +132,7 @@ __global__ __launch_bounds__(NW * 64) void small_kernel(FusedArgs a)
             // written by ONE write-through store: a reader that finds this launch's tag has this
             // launch's value, so the flag below need not wait for these stores to be acknowledged
             const unsigned long long pr = ((unsigned long long)(epoch + 1) << 32) | __builtin_bit_cast(uint32_t, v);
-            __hip_atomic_store(&a.tpair[((size_t)kc * 16 + i) * a.r + 16 * rho + col], pr, __ATOMIC_RELAXED,
+            __hip_atomic_store(&a.tpair[(((size_t)mem * a.kcn + kc) * 16 + i) * a.r + 16 * rho + col], pr, __ATOMIC_RELAXED,
                                __HIP_MEMORY_SCOPE_AGENT);
         }
         // (tid < 16 * mt) is within wavefront 0, whose lane 0 raises the flag: same wavefront, later instruction
@@ -147,7 +148,14 @@ __global__ __launch_bounds__(NW * 64) void small_kernel(FusedArgs a)
     }
 
     // =========================================================================== consumer
-    const int R = blockIdx.x - nprod;
+    int R = blockIdx.x - nprod, mem = 0;                 // row block within its member
+    while (mem + 1 < a.n && R >= a.d_out[mem] / 16) {
+        R -= a.d_out[mem] / 16;
+        ++mem;
+    }
+    const _Float16* const w_scales = a.w_scales[mem];
+    const uint32_t* const w_zeros = a.w_zeros[mem];
+    const uint32_t* const w_tiles = (const uint32_t*)a.w[mem];
     const size_t row = (size_t)R * 16 + n;
     const int G = a.d_in / 128;                          // == 4 * NW * NQ, one quantisation group per k-tile
     uint2 sc[NQ];
@@ -156,10 +164,10 @@ __global__ __launch_bounds__(NW * 64) void small_kernel(FusedArgs a)
 #pragma unroll
     for (int q = 0; q < NQ; ++q) {
         const int g0 = 4 * (wave + q * NW);
-        sc[q] = *(const uint2*)(a.w_scales + row * G + g0);
-        zq[q] = a.w_zeros[row * (G / 8) + (g0 >> 3)];
+        sc[q] = *(const uint2*)(w_scales + row * G + g0);
+        zq[q] = w_zeros[row * (G / 8) + (g0 >> 3)];
     }
-    const Factor fb{(const uint32_t*)a.B, a.B_scales, LOWRANK ? a.r / Fmt<LOWRANK ? FE : S_F16>::KT : 0};
+    const Factor fb{(const uint32_t*)a.B[mem], a.B_scales[mem], LOWRANK ? a.r / Fmt<LOWRANK ? FE : S_F16>::KT : 0};
     FTile<LOWRANK ? FE : S_F16> bpre;
     if constexpr (LOWRANK) load_ftile<FE>(bpre, fb, R, wave < fb.ntk ? wave : 0, lane);
 #pragma unroll
@@ -167,7 +175,7 @@ __global__ __launch_bounds__(NW * 64) void small_kernel(FusedArgs a)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const size_t tile = (size_t)R * G + 4 * (wave + q * NW) + i;
-            load_words<WORDS>(wd[q][i], (const uint32_t*)a.w + (tile * 64 + lane) * WORDS);
+            load_words<WORDS>(wd[q][i], w_tiles + (tile * 64 + lane) * WORDS);
         }
     }
     if constexpr (LOWRANK) {
@@ -186,8 +194,8 @@ __global__ __launch_bounds__(NW * 64) void small_kernel(FusedArgs a)
     uint32_t early = 0;
     if constexpr (LOWRANK) {
         if (wave == 0)
-            early = ld_relaxed(a.hdr + HDR_FLAGS0 + HDR_FLAGS_REPLICA_STRIDE * (blockIdx.x % HDR_FLAG_REPLICAS) +
-                               (lane < nprod ? lane : nprod - 1));
+            early = ld_relaxed(a.hdr + HDR_FLAGS0 + HDR_FLAGS_REPLICA_STRIDE * (blockIdx.x % HDR_FLAG_REPLICAS) + mem * upl +
+                               (lane < upl ? lane : upl - 1));
     }
     // ---- backbone ------------------------------------------------------------------------------------
     f4 acc = {0.f, 0.f, 0.f, 0.f};
@@ -218,11 +226,12 @@ __global__ __launch_bounds__(NW * 64) void small_kernel(FusedArgs a)
     if constexpr (LOWRANK) {
         const uint32_t epoch = s_epoch;
         if (wave == 0) {
-            const uint32_t* flags = a.hdr + HDR_FLAGS0 + HDR_FLAGS_REPLICA_STRIDE * (blockIdx.x % HDR_FLAG_REPLICAS);
-            bool ok = nprod <= 64 && __all(early == epoch + 1);
+            // the units of this workgroup's own member only
+            const uint32_t* flags = a.hdr + HDR_FLAGS0 + HDR_FLAGS_REPLICA_STRIDE * (blockIdx.x % HDR_FLAG_REPLICAS) + mem * upl;
+            bool ok = upl <= 64 && __all(early == epoch + 1);
             for (int spins = 0; !ok && spins <= a.spin_limit; ++spins) {
                 bool all = true;
-                for (int f = lane; f < nprod; f += 64) all = all && (ld_relaxed(&flags[f]) == epoch + 1);
+                for (int f = lane; f < upl; f += 64) all = all && (ld_relaxed(&flags[f]) == epoch + 1);
                 if (__all(all)) { ok = true; break; }
                 __builtin_amdgcn_s_sleep(2);
             }
@@ -235,7 +244,7 @@ __global__ __launch_bounds__(NW * 64) void small_kernel(FusedArgs a)
                 const int T = mt * a.r;                  // elements of t; a.r is a multiple of 32
                 for (int e = 4 * lane; e < T; e += 256) {
                     const int i = e / a.r, col = e % a.r;
-                    const unsigned long long* p = a.tpair + (size_t)i * a.r + col;
+                    const unsigned long long* p = a.tpair + ((size_t)mem * a.kcn * 16 + i) * a.r + col;
                     float v0 = 0.f, v1 = 0.f, v2 = 0.f, v3 = 0.f;
                     uint32_t bad = 0;
 #pragma unroll 4
@@ -319,7 +328,7 @@ __global__ __launch_bounds__(NW * 64) void small_kernel(FusedArgs a)
         float v = 0.f;
 #pragma unroll
         for (int w2 = 0; w2 < NW; ++w2) v += red[w2][i][col];
-        a.y[(size_t)i * a.d_out + R * 16 + col] = (_Float16)v;
+        a.y[mem][(size_t)i * a.d_out[mem] + R * 16 + col] = (_Float16)v;
     }
     TL_STAMP(6);
     if constexpr (LOWRANK) {
@@ -329,7 +338,7 @@ __global__ __launch_bounds__(NW * 64) void small_kernel(FusedArgs a)
 
 // ------------------------------------------------------------------------------------------------
 template <int FM, int FA, int FE, int NW, int NQ, bool M1>
-static hipError_t launch_small_m(const FusedArgs& a, hipStream_t stream)
+static hipError_t launch_small_m(const GroupArgs& a, hipStream_t stream)
 {
     auto kern = small_kernel<FM, FA, FE, NW, NQ, M1>;
     const size_t lds = (size_t)a.M * (a.d_in + 32) * 2 + (size_t)a.M * a.r * 4;
@@ -337,13 +346,14 @@ static hipError_t launch_small_m(const FusedArgs& a, hipStream_t stream)
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    const int nprod = (FA != S_NONE) ? (a.r / 16) * a.kcn : 0;
-    hipLaunchKernelGGL(kern, dim3(a.d_out / 16 + nprod), dim3(NW * 64), lds, stream, a);
+    int blocks = (FA != S_NONE) ? (a.r / 16) * a.kcn * a.n : 0;     // producers first
+    for (int m = 0; m < a.n; ++m) blocks += a.d_out[m] / 16;
+    hipLaunchKernelGGL(kern, dim3(blocks), dim3(NW * 64), lds, stream, a);
     return hipGetLastError();
 }
 
 template <int FM, int FA, int FE, int NW, int NQ>
-static hipError_t launch_small_one(const FusedArgs& a, hipStream_t stream)
+static hipError_t launch_small_one(const GroupArgs& a, hipStream_t stream)
 {
     if (a.M == 1) return launch_small_m<FM, FA, FE, NW, NQ, true>(a, stream);
     if constexpr (NQ <= XSTAGE / 2) return launch_small_m<FM, FA, FE, NW, NQ, false>(a, stream);   // M * NQ <= XSTAGE
@@ -351,7 +361,7 @@ static hipError_t launch_small_one(const FusedArgs& a, hipStream_t stream)
 }
 
 template <int FM, int FA, int FE>
-static hipError_t launch_small_shape(const FusedArgs& a, int nw, int nq, hipStream_t stream)
+static hipError_t launch_small_shape(const GroupArgs& a, int nw, int nq, hipStream_t stream)
 {
     if (nw == 8 && nq == 1) return launch_small_one<FM, FA, FE, 8, 1>(a, stream);
     if (nw == 8 && nq == 2) return launch_small_one<FM, FA, FE, 8, 2>(a, stream);
@@ -365,7 +375,7 @@ static hipError_t launch_small_shape(const FusedArgs& a, int nw, int nq, hipStre
 }
 
 template <int FM>
-static hipError_t launch_small_ab(const FusedArgs& a, int fa, int fe, int nw, int nq, hipStream_t stream)
+static hipError_t launch_small_ab(const GroupArgs& a, int fa, int fe, int nw, int nq, hipStream_t stream)
 {
     if (fe == S_NONE) return launch_small_shape<FM, S_NONE, S_NONE>(a, nw, nq, stream);
     if (fa == S_F16 && fe == S_F16) return launch_small_shape<FM, S_F16, S_F16>(a, nw, nq, stream);
@@ -376,16 +386,16 @@ static hipError_t launch_small_ab(const FusedArgs& a, int fa, int fe, int nw, in
 
 // Shapes this kernel takes: 1..4 tokens, one quantisation group per k-tile, d_in / 512 an exact
 // number of quads per wavefront from the table below, x small enough to stage.
-bool small_kernel_fits(const FusedArgs& a, int* nw, int* nq)
+bool small_kernel_fits(int M, int d_in, int group, int* nw, int* nq)
 {
-    if (a.M < 1 || a.M > 4 || a.group != 128 || a.d_in % 512) return false;
-    const int Q = a.d_in / 512;
+    if (M < 1 || M > 4 || group != 128 || d_in % 512) return false;
+    const int Q = d_in / 512;
     static const int table[][2] = {{4, 2}, {7, 4}, {8, 2}, {14, 4}, {4, 1}, {8, 1}, {14, 2}, {16, 1}};   // first match wins
     const char* force = getenv("EORA_SMALL_NW");         // experiment knob: preferred wavefront count
     const int want = force ? atoi(force) : 0;
     if (want) {
         for (const auto& t : table) {
-            if (t[0] == want && t[0] * t[1] == Q && (size_t)a.M * (a.d_in / 8) <= (size_t)XSTAGE * t[0] * 64) {
+            if (t[0] == want && t[0] * t[1] == Q && (size_t)M * (d_in / 8) <= (size_t)XSTAGE * t[0] * 64) {
                 *nw = t[0];
                 *nq = t[1];
                 return true;
@@ -393,7 +403,7 @@ bool small_kernel_fits(const FusedArgs& a, int* nw, int* nq)
         }
     }
     for (const auto& t : table) {
-        if (t[0] * t[1] == Q && (size_t)a.M * (a.d_in / 8) <= (size_t)XSTAGE * t[0] * 64) {
+        if (t[0] * t[1] == Q && (size_t)M * (d_in / 8) <= (size_t)XSTAGE * t[0] * 64) {
             *nw = t[0];
             *nq = t[1];
             return true;
@@ -402,7 +412,7 @@ bool small_kernel_fits(const FusedArgs& a, int* nw, int* nq)
     return false;
 }
 
-hipError_t launch_small(const FusedArgs& a, int fm, int fa, int fe, int nw, int nq, hipStream_t stream)
+hipError_t launch_small(const GroupArgs& a, int fm, int fa, int fe, int nw, int nq, hipStream_t stream)
 {
     switch (fm) {
         case S_Q4: return launch_small_ab<S_Q4>(a, fa, fe, nw, nq, stream);

@@ -51,9 +51,10 @@ class QCase:
             assert np.array_equal(self.As.view(np.uint16), self.o_As.view(np.uint16))
             assert np.array_equal(self.Bs.view(np.uint16), self.o_Bs.view(np.uint16))
 
-    def oracle_y(self, rows=None, r=None):
+    def oracle_y(self, rows=None, r=None, x=None):
         from oracle import linear
-        x = self.x if rows is None else self.x[rows]
+        x = self.x if x is None else x
+        x = x if rows is None else x[rows]
         r = self.r if r is None else r
         return linear.eora_linear_q(x, self.o_qw, self.o_sc, self.o_qz, self.o_A, self.o_B, self.o_As, self.o_Bs,
                                     x.shape[0], self.d_in, self.d_out, r, self.w_bits, self.group, self.ab_bits)

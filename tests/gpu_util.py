@@ -34,6 +34,26 @@ def run_linear_q(c, M=None, x=None, r=None, canary=True, ws=None):
     return out[pad: pad + M * c.d_out].reshape(M, c.d_out)
 
 
+def run_linear_q_group(cases, x, r=None, ws=None):
+    """Run eora_linear_q_group on cases that share d_in, r and formats, all fed the activations x
+    (M x d_in fp16 numpy); returns the list of y (M x d_out fp16 numpy)."""
+    c0 = cases[0]
+    M = x.shape[0]
+    r = c0.r if r is None else r
+    xd = dev(x)
+    keep, members, ys = [], [], []
+    for c in cases:
+        t = [dev(c.qw), dev(c.sc), dev(c.qz)] + ([dev(c.A), dev(c.B), dev(c.As), dev(c.Bs)] if r > 0 else [None] * 4)
+        y = torch.full((M * c.d_out,), 777.0, dtype=torch.float16, device="cuda")
+        keep.append(t)
+        ys.append(y)
+        members.append(tuple(t) + (y, c.d_out))
+    ws = eora.new_workspace(M, c0.d_in, max(c.d_out for c in cases), r) if ws is None else ws
+    eora.linear_q_group(xd, members, M, c0.d_in, r, c0.w_bits, c0.group, c0.ab_bits, ws)
+    torch.cuda.synchronize()
+    return [y.cpu().numpy().reshape(M, c.d_out) for y, c in zip(ys, cases)]
+
+
 def run_linear_sp24(c, M=None, x=None, r=None, ws=None):
     """Run eora_linear_sp24 on case c; returns y as float16 numpy (M x d_out)."""
     M = c.M if M is None else M

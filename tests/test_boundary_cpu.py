@@ -88,10 +88,27 @@ def test_linear_q_validation_codes():
     assert call(qw=odd) == -4 and call(y=odd) == -4 and call(ws=odd) == -4
     assert call(ws=null) == -5 and call(ws_bytes=16) == -5
     assert call(M=0) == 0                                   # empty input: nothing to do, nothing launched
-    assert L.eora_linear_sp24(null, good, good, good, good, good, 1, 256, 32, 32, good, 1 << 20, null) == -1
-    assert L.eora_linear_sp24(good, good, good, good, good, good, 1, 256, 32, 48, good, 1 << 20, null) == -2
-    assert L.eora_linear_sp24(good, good, odd, good, good, good, 1, 256, 32, 32, good, 1 << 20, null) == -4
+    assert L.eora_linear_sp24(null, good, good, good, good, good, 1, 256, 32, 32, good, 1 << 24, null) == -1
+    assert L.eora_linear_sp24(good, good, good, good, good, good, 1, 256, 32, 48, good, 1 << 24, null) == -2
+    assert L.eora_linear_sp24(good, good, odd, good, good, good, 1, 256, 32, 32, good, 1 << 24, null) == -4
     assert L.eora_linear_sp24(good, good, good, good, good, good, 1, 256, 32, 32, good, 16, null) == -5
+    # a group of layers that share x: validated member by member before anything is enqueued
+    Q = eora.binding.QMember
+    g, n0 = 0x1000, None
+
+    def group(members, n=None, M=1, d_in=512, r=32, w_bits=4, group_=128, ab_bits=16, ws=good, ws_bytes=1 << 24, x=good):
+        arr = (Q * max(1, len(members)))(*members)
+        return L.eora_linear_q_group(x, arr, len(members) if n is None else n, M, d_in, r, w_bits, group_, ab_bits, ws,
+                                     ws_bytes, null)
+
+    ok = Q(g, g, g, g, g, n0, n0, g, 32)
+    assert group([ok], n=0) == -2 and group([ok] * 5) == -2 and group([ok], x=null) == -1
+    assert group([ok, Q(g, g, g, g, g, n0, n0, n0, 32)]) == -1            # second member without y
+    assert group([ok, Q(g, g, g, g, g, n0, n0, g, 40)]) == -2             # d_out not a multiple of 16
+    assert group([ok, Q(g, 0x1008, g, g, g, n0, n0, g, 32)]) == -4
+    assert group([ok, ok], w_bits=5) == -3 and group([ok, ok], ws_bytes=16) == -5 and group([ok, ok], ws=null) == -5
+    assert group([ok, ok], M=8, d_in=256, ws_bytes=16) == -5              # the member-by-member path validates too
+    assert group([ok, ok], M=0) == 0
     assert L.eora_unpack_q(good, good, good, good, 256, 32, 5, 128, null) == -3
     assert L.eora_dequant_q(good, good, good, null, 256, 32, 4, 128, null) == -1
     assert L.eora_expand_sp24(good, odd, good, 256, 32, null) == -4

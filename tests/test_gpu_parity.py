@@ -118,6 +118,26 @@ def test_config_shapes_fp16_factors(gpu, name, d_in, d_out, w_bits, M):
     _check(run_linear_q(c), c.oracle_y())
 
 
+@pytest.mark.parametrize("w_bits,ab_bits,r,M,d_in,d_outs", [
+    (3, 16, 128, 1, 4096, (4096, 1024, 1024)),      # query / key / value of the 8B layer, config 2
+    (4, 4, 128, 1, 4096, (1024, 2048)),             # 4-bit factors, config 3
+    (4, 16, 32, 3, 1024, (64, 16, 48, 32)),         # four members, three tokens
+    (4, 16, 0, 2, 2048, (128, 64)),                 # adapter off
+    (3, 16, 64, 8, 512, (64, 32)),                  # a shape the decode kernel does not take: members run in turn
+])
+def test_group_of_layers_sharing_x(gpu, w_bits, ab_bits, r, M, d_in, d_outs):
+    """Layers that read the same x in one call (query/key/value, gate/up): every member equals the
+    oracle on its own weights and factors, and is bit-identical to a separate eora_linear_q call."""
+    from tests.cases import QCase
+    from tests.gpu_util import run_linear_q, run_linear_q_group
+    cases = [QCase(500 + 7 * i + d_in, d_in, d, M, r, w_bits, ab_bits=ab_bits, packer=gpu) for i, d in enumerate(d_outs)]
+    x = cases[0].x
+    ys = run_linear_q_group(cases, x)
+    for c, y in zip(cases, ys):
+        _check(y, c.oracle_y(x=x))
+        assert np.array_equal(y, run_linear_q(c, x=x))
+
+
 def test_workspace_is_reusable_without_clearing(gpu):
     """Nothing in the workspace is reset between calls: flags are compared with an epoch that each
     low-rank launch advances by one, so one workspace serves any number of calls of any shapes."""
