@@ -45,7 +45,7 @@ for _n in ("llama3-8b-layer-decode-w3g128-r128fp16-M1", "llama3-8b-layer-decode-
 GROUPS = (("q", "k", "v"), ("o",), ("gate", "up"), ("down",))
 for _r in (64, 256, 512):
     WORKLOADS["llama3-8b-layer-decode-w4g128-r%dq4-M1" % _r] = dict(model="8b", w_bits=4, ab_bits=4, r=_r, M=1, cfg=3)
-DEFAULT = "llama3-8b-layer-decode-w3g128-r128fp16-M1"
+DEFAULT = "llama3-8b-layer-decode-w3g128-r128fp16-M1-grouped"
 
 
 def algorithmic_bytes(d_in, d_out, M, r, w_bits, ab_bits, group=128):

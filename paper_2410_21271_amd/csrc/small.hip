@@ -21,6 +21,7 @@
 namespace eora {
 
 constexpr int XSTAGE = 4;   // 16-byte chunks of x a thread may stage
+constexpr int TWO_BLOCKS_FROM = 1024;   // row blocks of a launch from which a workgroup takes two
 
 #ifdef EORA_TIMELINE
 // debug build only: per-workgroup time stamps (100 MHz counter) behind the partials of t
@@ -29,13 +30,13 @@ constexpr int XSTAGE = 4;   // 16-byte chunks of x a thread may stage
 #define TL_STAMP(slot) do { } while (0)
 #endif
 
-template <int FM, int FA, int FE, int NW, int NQ, bool M1>
-__global__ __launch_bounds__(NW * 64) void small_kernel(GroupArgs a)
+template <int FM, int FA, int FE, int NW, int NQ, bool M1, int RB>
+__global__ __launch_bounds__(NW * 64, (16 + NW - 1) / NW) void small_kernel(GroupArgs a)   // second bound: wavefronts per SIMD, i.e. at most 128 registers for four-wavefront workgroups
 {
     constexpr bool LOWRANK = FA != S_NONE;
     constexpr int NT = NW * 64;
     constexpr int WORDS = Fmt<FM>::WORDS;
-    __shared__ float red[NW][4][16];
+    __shared__ float red[NW][RB][4][16];
     __shared__ uint32_t s_epoch, s_ok;
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -83,13 +84,12 @@ __global__ __launch_bounds__(NW * 64) void small_kernel(GroupArgs a)
             const int ss = s < nsteps ? s : (nsteps > 0 ? nsteps - 1 : 0);
             load_ftile<FA>(buf[s], fa, rho, (nsteps > 0 ? first : kc * tpc) + ss * NW, lane);
         }
-        if (tid == 0) {
-            check_in_issue(ci, a.hdr, blockIdx.x);
-            s_epoch = ci.epoch;
-        }
+        __builtin_amdgcn_sched_barrier(0);               // all requests are out before the first result is used
+        if (tid == 0) s_epoch = ci.epoch;
 #pragma unroll
         for (int k = 0; k < XS; ++k) *(u4*)(xs + ((k / NQ) < mt ? (k / NQ) : 0) * ldxs + (tid + (k % NQ) * NT) * 8) = xstage[k];
         __syncthreads();
+        if (tid == 0) check_in_issue(ci, a.hdr, blockIdx.x);
         TL_STAMP(1);
         const uint32_t epoch = s_epoch;
         f4 acc = {0.f, 0.f, 0.f, 0.f};
@@ -119,7 +119,7 @@ __global__ __launch_bounds__(NW * 64) void small_kernel(GroupArgs a)
         // token rows 0..3 live in lanes j == 0, register i = row
         if (j == 0) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) red[wave][i][n] = acc[i];
+            for (int i = 0; i < 4; ++i) red[wave][0][i][n] = acc[i];
         }
         __syncthreads();
         TL_STAMP(2);
@@ -127,7 +127,7 @@ __global__ __launch_bounds__(NW * 64) void small_kernel(GroupArgs a)
             const int i = tid >> 4, col = tid & 15;
             float v = 0.f;
 #pragma unroll
-            for (int w2 = 0; w2 < NW; ++w2) v += red[w2][i][col];
+            for (int w2 = 0; w2 < NW; ++w2) v += red[w2][0][i][col];
             // partial layout: [kc][token row (16)][r], every element an 8-byte (value, epoch + 1) pair
             // written by ONE write-through store: a reader that finds this launch's tag has this
             // launch's value, so the flag below need not wait for these stores to be acknowledged
@@ -148,82 +148,105 @@ __global__ __launch_bounds__(NW * 64) void small_kernel(GroupArgs a)
     }
 
     // =========================================================================== consumer
-    int R = blockIdx.x - nprod, mem = 0;                 // row block within its member
-    while (mem + 1 < a.n && R >= a.d_out[mem] / 16) {
-        R -= a.d_out[mem] / 16;
+    int R = blockIdx.x - nprod, mem = 0;                 // strip of RB row blocks within its member
+    while (mem + 1 < a.n && R >= a.d_out[mem] / (16 * RB)) {
+        R -= a.d_out[mem] / (16 * RB);
         ++mem;
     }
     const _Float16* const w_scales = a.w_scales[mem];
     const uint32_t* const w_zeros = a.w_zeros[mem];
     const uint32_t* const w_tiles = (const uint32_t*)a.w[mem];
-    const size_t row = (size_t)R * 16 + n;
     const int G = a.d_in / 128;                          // == 4 * NW * NQ, one quantisation group per k-tile
-    uint2 sc[NQ];
-    uint32_t zq[NQ];
-    uint32_t wd[NQ][4][WORDS];
+    uint2 sc[RB][NQ];
+    uint32_t zq[RB][NQ];
+    uint32_t wd[RB][NQ][4][WORDS];
 #pragma unroll
-    for (int q = 0; q < NQ; ++q) {
-        const int g0 = 4 * (wave + q * NW);
-        sc[q] = *(const uint2*)(w_scales + row * G + g0);
-        zq[q] = w_zeros[row * (G / 8) + (g0 >> 3)];
+    for (int rb = 0; rb < RB; ++rb) {
+        const size_t row = (size_t)(R * RB + rb) * 16 + n;
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) {
+            const int g0 = 4 * (wave + q * NW);
+            sc[rb][q] = *(const uint2*)(w_scales + row * G + g0);
+            zq[rb][q] = w_zeros[row * (G / 8) + (g0 >> 3)];
+        }
     }
     const Factor fb{(const uint32_t*)a.B[mem], a.B_scales[mem], LOWRANK ? a.r / Fmt<LOWRANK ? FE : S_F16>::KT : 0};
-    FTile<LOWRANK ? FE : S_F16> bpre;
-    if constexpr (LOWRANK) load_ftile<FE>(bpre, fb, R, wave < fb.ntk ? wave : 0, lane);
+    FTile<LOWRANK ? FE : S_F16> bpre[RB];
+    if constexpr (LOWRANK) {
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) load_ftile<FE>(bpre[rb], fb, R * RB + rb, wave < fb.ntk ? wave : 0, lane);
+    }
+    // the first row block's tiles now; a further row block's quad q is requested when quad q of the
+    // row block before it has been consumed (same registers, no second buffer)
+    // this lane's words of tile (R * RB) * G + 4 * wave; every other tile it reads is a compile-time
+    // number of tiles further on (32-bit word index: a matrix of this format stays far below 16 GiB)
+    const uint32_t* const wp = w_tiles + (uint32_t)((((uint32_t)(R * RB) * G + 4 * wave) * 64 + lane) * WORDS);
 #pragma unroll
     for (int q = 0; q < NQ; ++q) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const size_t tile = (size_t)R * G + 4 * (wave + q * NW) + i;
-            load_words<WORDS>(wd[q][i], w_tiles + (tile * 64 + lane) * WORDS);
-        }
+        for (int i = 0; i < 4; ++i) load_words<WORDS>(wd[0][q][i], wp + (4 * q * NW + i) * 64 * WORDS);
     }
+    // Every request above is in flight before anything below consumes one: without this fence the
+    // scheduler moves uses of the first results (zero-point constants, x to LDS) in between the
+    // requests, and the tiles requested after such a use wait a whole round trip longer.
+    __builtin_amdgcn_sched_barrier(0);
     if constexpr (LOWRANK) {
-        if (tid == 0) {
-            check_in_issue(ci, a.hdr, blockIdx.x);
-            s_epoch = ci.epoch;
-        }
+        if (tid == 0) s_epoch = ci.epoch;
     }
 #pragma unroll
     for (int k = 0; k < XS; ++k) *(u4*)(xs + ((k / NQ) < mt ? (k / NQ) : 0) * ldxs + (tid + (k % NQ) * NT) * 8) = xstage[k];
     __syncthreads();
 
     TL_STAMP(1);
-    // a first look at the flags, requested now and examined after the backbone: when the producers
-    // are done by the time this request reaches memory, the poll below costs no round trip
     uint32_t early = 0;
-    if constexpr (LOWRANK) {
-        if (wave == 0)
-            early = ld_relaxed(a.hdr + HDR_FLAGS0 + HDR_FLAGS_REPLICA_STRIDE * (blockIdx.x % HDR_FLAG_REPLICAS) + mem * upl +
-                               (lane < upl ? lane : upl - 1));
-    }
     // ---- backbone ------------------------------------------------------------------------------------
-    f4 acc = {0.f, 0.f, 0.f, 0.f};
+    f4 acc[RB];
 #pragma unroll
-    for (int q = 0; q < NQ; ++q) {
-        const int g0 = 4 * (wave + q * NW);
-        const uint32_t z4 = zq[q] >> (4 * (g0 & 7));
+    for (int rb = 0; rb < RB; ++rb) acc[rb] = f4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            h8 xa[4], b[4];
-            const _Float16* px = xs + mrow * ldxs + (g0 + i) * 128 + 32 * j;
+    for (int rb = 0; rb < RB; ++rb) {
+        // a first look at the flags, requested before the last row block and examined after it: when
+        // the producers are done by the time this request reaches memory, the poll below costs no
+        // round trip
+        if constexpr (LOWRANK) {
+            if (rb == RB - 1 && wave == 0)
+                early = ld_relaxed(a.hdr + HDR_FLAGS0 + HDR_FLAGS_REPLICA_STRIDE * (blockIdx.x % HDR_FLAG_REPLICAS) + mem * upl +
+                                   (lane < upl ? lane : upl - 1));
+        }
 #pragma unroll
-            for (int t = 0; t < 4; ++t) xa[t] = *(const h8*)(px + 8 * t);
-            decode_tile<FM>(wd[q][i], (z4 >> (4 * i)) & 0xFu, b);
-            f4 part = {0.f, 0.f, 0.f, 0.f};
+        for (int q = 0; q < NQ; ++q) {
+            const int g0 = 4 * (wave + q * NW);
 #pragma unroll
-            for (int t = 0; t < 4; ++t) part = mfma16(xa[t], b[t], part);
-            const uint32_t sw = (i < 2) ? sc[q].x : sc[q].y;
-            const _Float16 s16 = __builtin_bit_cast(_Float16, (uint16_t)((i & 1) ? (sw >> 16) : (sw & 0xFFFFu)));
-            // exact integers times x, scaled once per group in fp32 (one token: only register 0 is ever stored)
-            if constexpr (M1) acc[0] += (float)s16 * part[0];
-            else acc += (float)s16 * part;
+            for (int i = 0; i < 4; ++i) {
+                h8 xa[4], b[4];
+                const _Float16* px = xs + mrow * ldxs + (g0 + i) * 128 + 32 * j;
+#pragma unroll
+                for (int t = 0; t < 4; ++t) xa[t] = *(const h8*)(px + 8 * t);
+                decode_tile<FM>(wd[rb][q][i], (zq[rb][q] >> (4 * ((g0 & 7) + i))) & 0xFu, b);
+                f4 part = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int t = 0; t < 4; ++t) part = mfma16(xa[t], b[t], part);
+                const uint32_t sw = (i < 2) ? sc[rb][q].x : sc[rb][q].y;
+                const _Float16 s16 = __builtin_bit_cast(_Float16, (uint16_t)((i & 1) ? (sw >> 16) : (sw & 0xFFFFu)));
+                // exact integers times x, scaled once per group in fp32 (one token: only register 0 is ever stored)
+                if constexpr (M1) acc[rb][0] += (float)s16 * part[0];
+                else acc[rb] += (float)s16 * part;
+            }
+            if constexpr (RB > 1) {
+                if (rb + 1 < RB) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        load_words<WORDS>(wd[rb + 1][q][i], wp + ((size_t)(rb + 1) * G + 4 * q * NW + i) * 64 * WORDS);
+                }
+            }
         }
     }
 
     TL_STAMP(2);
     // ---- low-rank continuation ---------------------------------------------------------------------
     if constexpr (LOWRANK) {
+        // checks in now, with every tile consumed: the atomic's answer is needed at the very end only
+        if (tid == 0) check_in_issue(ci, a.hdr, blockIdx.x);
         const uint32_t epoch = s_epoch;
         if (wave == 0) {
             // the units of this workgroup's own member only
@@ -289,30 +312,36 @@ __global__ __launch_bounds__(NW * 64) void small_kernel(GroupArgs a)
         if (s_ok) {
             constexpr int KTB = Fmt<FE>::KT, NMF = KTB / 32;
             for (int g = wave; g < fb.ntk; g += NW) {
-                FTile<FE> cur;
-                if (g == wave) cur = bpre;
-                else load_ftile<FE>(cur, fb, R, g, lane);
-                h8 b[NMF];
-                decode_tile<FE>(cur.w, 8u, b);
-                f4 part = {0.f, 0.f, 0.f, 0.f};
+                h8 hi[NMF], lo[NMF];                     // t split once, used for the RB row blocks
 #pragma unroll
                 for (int q = 0; q < NMF; ++q) {
                     const float* p = ts + mrow * a.r + g * KTB + (KTB / 4) * j + 8 * q;
                     const f4 v0 = *(const f4*)p, v1 = *(const f4*)(p + 4);
-                    h8 hi, lo;
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
                         const _Float16 h0 = (_Float16)v0[i], h1 = (_Float16)v1[i];
-                        hi[i] = h0;
-                        hi[4 + i] = h1;
-                        lo[i] = (_Float16)(v0[i] - (float)h0);
-                        lo[4 + i] = (_Float16)(v1[i] - (float)h1);
+                        hi[q][i] = h0;
+                        hi[q][4 + i] = h1;
+                        lo[q][i] = (_Float16)(v0[i] - (float)h0);
+                        lo[q][4 + i] = (_Float16)(v1[i] - (float)h1);
                     }
-                    part = mfma16(hi, b[q], part);
-                    part = mfma16(lo, b[q], part);
                 }
-                if constexpr (M1) acc[0] += (float)cur.sc * part[0];
-                else acc += (float)cur.sc * part;
+#pragma unroll
+                for (int rb = 0; rb < RB; ++rb) {
+                    FTile<FE> cur;
+                    if (g == wave) cur = bpre[rb];
+                    else load_ftile<FE>(cur, fb, R * RB + rb, g, lane);
+                    h8 b[NMF];
+                    decode_tile<FE>(cur.w, 8u, b);
+                    f4 part = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int q = 0; q < NMF; ++q) {
+                        part = mfma16(hi[q], b[q], part);
+                        part = mfma16(lo[q], b[q], part);
+                    }
+                    if constexpr (M1) acc[rb][0] += (float)cur.sc * part[0];
+                    else acc[rb] += (float)cur.sc * part;
+                }
             }
         }
     }
@@ -320,15 +349,20 @@ __global__ __launch_bounds__(NW * 64) void small_kernel(GroupArgs a)
     // ---- combine, convert, store -------------------------------------------------------------------
     if (j == 0) {
 #pragma unroll
-        for (int i = 0; i < (M1 ? 1 : 4); ++i) red[wave][i][n] = acc[i];
+        for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+            for (int i = 0; i < (M1 ? 1 : 4); ++i) red[wave][rb][i][n] = acc[rb][i];
     }
     __syncthreads();
     if (tid < 16 * mt) {
         const int i = tid >> 4, col = tid & 15;
-        float v = 0.f;
 #pragma unroll
-        for (int w2 = 0; w2 < NW; ++w2) v += red[w2][i][col];
-        a.y[mem][(size_t)i * a.d_out[mem] + R * 16 + col] = (_Float16)v;
+        for (int rb = 0; rb < RB; ++rb) {
+            float v = 0.f;
+#pragma unroll
+            for (int w2 = 0; w2 < NW; ++w2) v += red[w2][rb][i][col];
+            a.y[mem][(size_t)i * a.d_out[mem] + (R * RB + rb) * 16 + col] = (_Float16)v;
+        }
     }
     TL_STAMP(6);
     if constexpr (LOWRANK) {
@@ -337,17 +371,17 @@ __global__ __launch_bounds__(NW * 64) void small_kernel(GroupArgs a)
 }
 
 // ------------------------------------------------------------------------------------------------
-template <int FM, int FA, int FE, int NW, int NQ, bool M1>
+template <int FM, int FA, int FE, int NW, int NQ, bool M1, int RB>
 static hipError_t launch_small_m(const GroupArgs& a, hipStream_t stream)
 {
-    auto kern = small_kernel<FM, FA, FE, NW, NQ, M1>;
+    auto kern = small_kernel<FM, FA, FE, NW, NQ, M1, RB>;
     const size_t lds = (size_t)a.M * (a.d_in + 32) * 2 + (size_t)a.M * a.r * 4;
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
     int blocks = (FA != S_NONE) ? (a.r / 16) * a.kcn * a.n : 0;     // producers first
-    for (int m = 0; m < a.n; ++m) blocks += a.d_out[m] / 16;
+    for (int m = 0; m < a.n; ++m) blocks += a.d_out[m] / (16 * RB);
     hipLaunchKernelGGL(kern, dim3(blocks), dim3(NW * 64), lds, stream, a);
     return hipGetLastError();
 }
@@ -355,8 +389,21 @@ static hipError_t launch_small_m(const GroupArgs& a, hipStream_t stream)
 template <int FM, int FA, int FE, int NW, int NQ>
 static hipError_t launch_small_one(const GroupArgs& a, hipStream_t stream)
 {
-    if (a.M == 1) return launch_small_m<FM, FA, FE, NW, NQ, true>(a, stream);
-    if constexpr (NQ <= XSTAGE / 2) return launch_small_m<FM, FA, FE, NW, NQ, false>(a, stream);   // M * NQ <= XSTAGE
+    if (a.M == 1) {
+        // Launches of more row blocks than can be resident at once give every workgroup two of them:
+        // then all workgroups start together and each pays the wait for t once, at its very end.
+        if constexpr (NQ <= 2 && FA != S_NONE) {           // (the bare layer has no such wait: one row block each streams best)
+            int blocks = 0;
+            bool even = true;
+            for (int m = 0; m < a.n; ++m) {
+                blocks += a.d_out[m] / 16;
+                even = even && a.d_out[m] % 32 == 0;
+            }
+            if (even && blocks > TWO_BLOCKS_FROM) return launch_small_m<FM, FA, FE, NW, NQ, true, 2>(a, stream);
+        }
+        return launch_small_m<FM, FA, FE, NW, NQ, true, 1>(a, stream);
+    }
+    if constexpr (NQ <= XSTAGE / 2) return launch_small_m<FM, FA, FE, NW, NQ, false, 1>(a, stream);   // M * NQ <= XSTAGE
     return hipErrorInvalidValue;
 }
 

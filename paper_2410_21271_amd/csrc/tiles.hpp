@@ -41,27 +41,34 @@ __device__ __forceinline__ uint32_t k16(uint32_t z) { return 0x4C004C00u | (z * 
 constexpr uint32_t MAGIC = 0x64006400u;   // fp16 1024.0 twice: OR-ing a small integer into the mantissa adds it
 
 // (w & mask) | base in one instruction.  The compiler splits this into v_and + v_or when both
-// constants are literals (a three-operand instruction takes no literal on this target); with the
-// mask in a scalar register and the base in a vector register it is a single v_and_or_b32, which
-// halves the bit-field extraction work that bounds the decode kernels.
-__device__ __forceinline__ uint32_t and_or(uint32_t w, uint32_t mask, uint32_t base)
+// constants are literals (a three-operand instruction takes no literal on this target).  Hiding the
+// constants' values behind empty asm statements (no instruction is emitted) makes it see a scalar and
+// a vector REGISTER operand, for which it selects the single v_and_or_b32 itself: that halves the
+// bit-field extraction work that bounds the decode kernels.  (Writing the instruction as inline asm
+// is not an option: the compiler inserts no MFMA wait states around instructions it cannot see.)
+__device__ __forceinline__ uint32_t in_sgpr(uint32_t v)
 {
-    uint32_t r;
-    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(w), "s"(mask), "v"(base));
-    return r;
+    asm("" : "+s"(v));
+    return v;
 }
+__device__ __forceinline__ uint32_t in_vgpr(uint32_t v)
+{
+    asm("" : "+v"(v));
+    return v;
+}
+__device__ __forceinline__ uint32_t and_or(uint32_t w, uint32_t mask, uint32_t base) { return (w & in_sgpr(mask)) | base; }
 
 // Eight 4-bit codes of one word -> (code - z) as eight fp16, columns in natural order.
 // Nibble e holds column 2*(e%4) + e/4, so each mask yields two adjacent columns.
 __device__ __forceinline__ h8 dq4_word(uint32_t w, uint32_t c1024, uint32_t c64)
 {
     const h2 sixteenth = {(_Float16)0.0625f, (_Float16)0.0625f};
-    const uint32_t hi = w >> 8;
+    const uint32_t hi = w >> 8, magic = in_vgpr(MAGIC);
     Frag f;
-    f.p[0] = as_h2(and_or(w, 0x000F000Fu, MAGIC)) - as_h2(c1024);                                  // 1024+q
-    f.p[1] = __builtin_elementwise_fma(as_h2(and_or(w, 0x00F000F0u, MAGIC)), sixteenth, -as_h2(c64));   // 1024+16q
-    f.p[2] = as_h2(and_or(hi, 0x000F000Fu, MAGIC)) - as_h2(c1024);
-    f.p[3] = __builtin_elementwise_fma(as_h2(and_or(hi, 0x00F000F0u, MAGIC)), sixteenth, -as_h2(c64));
+    f.p[0] = as_h2(and_or(w, 0x000F000Fu, magic)) - as_h2(c1024);                                  // 1024+q
+    f.p[1] = __builtin_elementwise_fma(as_h2(and_or(w, 0x00F000F0u, magic)), sixteenth, -as_h2(c64));   // 1024+16q
+    f.p[2] = as_h2(and_or(hi, 0x000F000Fu, magic)) - as_h2(c1024);
+    f.p[3] = __builtin_elementwise_fma(as_h2(and_or(hi, 0x00F000F0u, magic)), sixteenth, -as_h2(c64));
     return f.v;
 }
 
@@ -73,16 +80,17 @@ __device__ __forceinline__ void dq3_lane(uint32_t d0, uint32_t d1, uint32_t d2, 
     const h2 c1024 = as_h2(k1024(z)), c128 = as_h2(k128(z)), c16 = as_h2(k16(z));
     h2 pr[16];
     const uint32_t d[3] = {d0, d1, d2};
+    const uint32_t MAGICV = in_vgpr(MAGIC);
 #pragma unroll
     for (int i = 0; i < 3; ++i) {
         const uint32_t w = d[i], hi = w >> 9;
-        pr[5 * i + 0] = as_h2(and_or(w, 0x00070007u, MAGIC)) - c1024;                                      // 1024+q
-        pr[5 * i + 1] = __builtin_elementwise_fma(as_h2(and_or(w, 0x00380038u, MAGIC)), eighth, -c128);        // 1024+8q
-        pr[5 * i + 2] = __builtin_elementwise_fma(as_h2(and_or(w, 0x01C001C0u, MAGIC)), sixtyfourth, -c16);    // 1024+64q
-        pr[5 * i + 3] = as_h2(and_or(hi, 0x00070007u, MAGIC)) - c1024;
-        pr[5 * i + 4] = __builtin_elementwise_fma(as_h2(and_or(hi, 0x00380038u, MAGIC)), eighth, -c128);
+        pr[5 * i + 0] = as_h2(and_or(w, 0x00070007u, MAGICV)) - c1024;                                      // 1024+q
+        pr[5 * i + 1] = __builtin_elementwise_fma(as_h2(and_or(w, 0x00380038u, MAGICV)), eighth, -c128);        // 1024+8q
+        pr[5 * i + 2] = __builtin_elementwise_fma(as_h2(and_or(w, 0x01C001C0u, MAGICV)), sixtyfourth, -c16);    // 1024+64q
+        pr[5 * i + 3] = as_h2(and_or(hi, 0x00070007u, MAGICV)) - c1024;
+        pr[5 * i + 4] = __builtin_elementwise_fma(as_h2(and_or(hi, 0x00380038u, MAGICV)), eighth, -c128);
     }
-    uint32_t last = and_or(d0 >> 15, 0x00010001u, MAGIC);     // bit b of the last pair is bit 15 / 31 of word b
+    uint32_t last = and_or(d0 >> 15, 0x00010001u, MAGICV);     // bit b of the last pair is bit 15 / 31 of word b
     last = and_or(d1 >> 14, 0x00020002u, last);
     last = and_or(d2 >> 13, 0x00040004u, last);
     pr[15] = as_h2(last) - c1024;

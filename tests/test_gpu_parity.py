@@ -120,6 +120,7 @@ def test_config_shapes_fp16_factors(gpu, name, d_in, d_out, w_bits, M):
 
 @pytest.mark.parametrize("w_bits,ab_bits,r,M,d_in,d_outs", [
     (3, 16, 128, 1, 4096, (4096, 1024, 1024)),      # query / key / value of the 8B layer, config 2
+    (3, 16, 128, 1, 4096, (14336, 14336)),          # gate / up: enough row blocks that a workgroup takes two
     (4, 4, 128, 1, 4096, (1024, 2048)),             # 4-bit factors, config 3
     (4, 16, 32, 3, 1024, (64, 16, 48, 32)),         # four members, three tokens
     (4, 16, 0, 2, 2048, (128, 64)),                 # adapter off
