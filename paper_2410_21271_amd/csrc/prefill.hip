@@ -6,79 +6,118 @@
 // per output tile would cost r / 128 times the backbone's MFMA work.
 //
 // Workgroup: 4 wavefronts (2 x 2), tile = 128 tokens x 128 output rows, contraction in steps of 128
-// (one quantisation group).  At 4096 flop/clk per compute unit this tile needs about 40 bytes/clk of
-// L2 -> compute-unit traffic at MFMA peak (x as fp16, weights as 4-bit codes), inside the 64 bytes/clk
-// a compute unit can take; a 256 x 64 tile would need 68.  Per step
+// (one quantisation group); each wavefront owns 64 tokens x 64 rows = 2 x 2 accumulator blocks of
+// v_mfma_f32_32x32x16_f16, the instruction with the highest sustained rate here (measured with
+// register-only loops: 2.2 PFLOP/s against 1.9 for the 16x16x32 form).  Its operand layout is:
+// lane l holds 8 consecutive k (8*(l/32) ..) of token / output row l%32; result register v of lane l
+// is token 8*(v/4) + 4*(l/32) + v%4, output row l%32 (checked on the device against a host matmul).
+//   - Weights never touch LDS.  The stored tiles (16 rows x 128 columns, lane (n, j) = row n, columns
+//     32j .. 32j+31, tiles.hpp) feed this MFMA as well: lane l = n + 16*h + 32*kg of the wavefront loads,
+//     for jp = 0, 1, the 16 bytes of stored lane (n, 2*jp + kg) of the tile of row block 2*rp + h; word
+//     t of that load decodes to the operand of the k-slice (jp, t): columns 32*(2jp+kg) + 8t .. +7 of
+//     output row 32*rp + 16*h + n.  Every wavefront loads its own four tiles one step ahead, decodes
+//     them to the exact integers code - zero and multiplies by the fp16 group scale (one fp16
+//     rounding of scale*(code-zero), relative error <= 2^-11 per weight; scaling the accumulators per
+//     group instead would cost as many VALU cycles as the group's MFMAs).  The two wavefronts that
+//     share row blocks decode them twice; in exchange LDS carries only x, half the fragment traffic
+//     of staging both operands.
 //   - x: the 128 x 128 slab is read with coalesced 16-byte loads (256 bytes per token row) into
-//     registers one step ahead and written to LDS as MFMA operand fragments (16 tokens x 32 columns =
-//     1 KiB, one conflict-free ds_read_b128 each; a swizzle keeps the scattered writes conflict-free);
-//   - weights: each wavefront takes two stored tiles (their words ARE the lane's fragments,
-//     tiles.hpp), one step ahead, decodes them to the exact integers code - zero, multiplies by the
-//     fp16 group scale and writes the four fragments to LDS; fp16 tiles (A, B) are copied as they are.
-//     The scale is folded in here (one fp16 rounding of scale*(code-zero), relative error <= 2^-11 per
-//     weight) instead of on the accumulators as in decode: scaling 16 accumulator blocks per group
-//     would cost as many VALU cycles as the group's MFMAs;
-//   - each wavefront owns 64 tokens x 64 rows: 4 x 4 accumulator blocks, 8 fragment reads per 16 MFMAs.
-// LDS is single-buffered (64 KiB, so two workgroups share a compute unit and one computes while the
-// other refills): barrier, refill from the prefetch registers, barrier, issue the next prefetch,
-// contract.  The epilogue transposes through LDS so that y is written in 128-byte rows.
+//     registers two steps ahead and written one step ahead to the other of two LDS buffers as MFMA
+//     operand fragments (32 tokens x 16 columns = 1 KiB, one ds_read_b128 each; an XOR of the token
+//     slot with the slice number keeps both the scattered writes and the reads free of bank
+//     conflicts): one barrier per step.
+// Two workgroups share a compute unit (64 KiB LDS, at most 256 registers).  The epilogue transposes
+// through LDS so that y is written in 128-byte rows.
 #include "segments.hpp"
 
 namespace eora {
 
-constexpr int PF_BM = 128, PF_BN = 128;
-constexpr int PF_XS = 32 * 1024;                      // x slab: 8 token blocks x 4 slices x 1 KiB
-constexpr int PF_WS = 32 * 1024;                      // weights: 8 row blocks x 4 slices x 1 KiB
-constexpr int PF_LDS = PF_XS + PF_WS;
+typedef float f16v __attribute__((ext_vector_type(16)));
 
-struct WReg {
-    uint32_t w[4];
-    uint32_t zw;
-    _Float16 sc;
+constexpr int PF_BM = 128, PF_BN = 128;
+constexpr int PF_XS = 32 * 1024;                      // one x slab: 4 token blocks x 8 slices x 1 KiB
+constexpr int PF_LDS = 2 * PF_XS;
+
+__device__ __forceinline__ f16v mfma32(h8 a, h8 b, f16v c) { return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0); }
+
+// weights of one 128-wide step for the wavefront's two pairs of row blocks, exactly as loaded: nothing
+// here is touched before decode_wpre(), a whole step later (any arithmetic on a loaded value at load
+// time would make the wavefront wait for the request it has just issued)
+template <int FMT>
+struct WPre {
+    uint32_t w[2][2][Fmt<FMT>::WORDS];                // [row-block pair rp][jp]
+    uint32_t zraw[2];                                 // the word that holds the group's zero-point nibble
+    uint32_t sraw[2];                                 // fp16 scale bits, zero-extended
+    int zshift;                                       // 4 * (group index % 8)
+};
+template <>
+struct WPre<S_F16> {
+    u4 v[2][8];                                       // [rp][slice]: four tiles of 32 columns = eight slices of 16
 };
 
-// quantised tile of row block R, k-tile g of the first segment
+// Rl[rp]: the row block (2*rp + h, clamped) whose row n this lane supplies
 template <int FMT>
-__device__ __forceinline__ void load_wtile(WReg& r, const PrefillArgs& a, int R, int g, int lane)
+__device__ __forceinline__ void load_wpre(WPre<FMT>& r, const PrefillArgs& a, const int (&Rl)[2], int g, int lane)
 {
-    const int n = lane & 15;
-    const int G = a.K1 / 128;
-    const size_t tile = (size_t)R * G + g;
-    load_words<Fmt<FMT>::WORDS>(*(uint32_t(*)[Fmt<FMT>::WORDS])r.w, (const uint32_t*)a.w + (tile * 64 + lane) * Fmt<FMT>::WORDS);
-    const size_t row = (size_t)R * 16 + n;
-    if constexpr (Fmt<FMT>::ASYM) {
-        const int NG = a.K1 / a.group, grp = (g * 128) / a.group;
-        r.sc = a.w_scales[row * NG + grp];
-        r.zw = (a.w_zeros[row * ((NG + 7) / 8) + (grp >> 3)] >> (4 * (grp & 7))) & 0xFu;
+    const int n = lane & 15, kg = lane >> 5;
+    if constexpr (FMT == S_F16) {
+#pragma unroll
+        for (int rp = 0; rp < 2; ++rp) {
+            const u4* p = (const u4*)a.w + ((size_t)Rl[rp] * (a.K1 / 32) + 4 * g) * 64 + n;
+#pragma unroll
+            for (int f = 0; f < 8; ++f) r.v[rp][f] = p[(f >> 1) * 64 + 16 * (2 * (f & 1) + kg)];
+        }
     } else {
-        r.sc = a.w_scales[row * G + g];
-        r.zw = 8u;
+        constexpr int WORDS = Fmt<FMT>::WORDS;
+        const int G = a.K1 / 128;
+        const int NG = Fmt<FMT>::ASYM ? a.K1 / a.group : G, grp = Fmt<FMT>::ASYM ? (g * 128) / a.group : g;
+        r.zshift = 4 * (grp & 7);
+#pragma unroll
+        for (int rp = 0; rp < 2; ++rp) {
+            const uint32_t* tile = (const uint32_t*)a.w + ((size_t)Rl[rp] * G + g) * 64 * WORDS;
+#pragma unroll
+            for (int jp = 0; jp < 2; ++jp) load_words<WORDS>(r.w[rp][jp], tile + (16 * (2 * jp + kg) + n) * WORDS);
+            const size_t row = (size_t)Rl[rp] * 16 + n;
+            r.sraw[rp] = ((const uint16_t*)a.w_scales)[row * NG + grp];
+            if constexpr (Fmt<FMT>::ASYM) r.zraw[rp] = a.w_zeros[row * ((NG + 7) / 8) + (grp >> 3)];
+        }
     }
 }
 
-// decode, scale in fp16, write the four fragments of row block slot `rbs` (0..7)
+// decode to operands bf[rp][slice], slice = 4*jp + t, scale folded in fp16
 template <int FMT>
-__device__ __forceinline__ void store_wtile(const WReg& r, int rbs, int lane)
+__device__ __forceinline__ void decode_wpre(const WPre<FMT>& r, h8 (&bf)[2][8])
 {
-    h8 b[4];
-    decode_tile<FMT>(*(const uint32_t(*)[Fmt<FMT>::WORDS])r.w, r.zw, b);
-    const h8 s = {r.sc, r.sc, r.sc, r.sc, r.sc, r.sc, r.sc, r.sc};
 #pragma unroll
-    for (int t = 0; t < 4; ++t) *(h8*)(eora_smem + PF_XS + (rbs * 4 + t) * 1024 + lane * 16) = b[t] * s;
+    for (int rp = 0; rp < 2; ++rp) {
+        if constexpr (FMT == S_F16) {
+#pragma unroll
+            for (int f = 0; f < 8; ++f) bf[rp][f] = __builtin_bit_cast(h8, r.v[rp][f]);
+        } else {
+            const uint32_t z = Fmt<FMT>::ASYM ? (r.zraw[rp] >> r.zshift) & 0xFu : 8u;
+            const _Float16 sc = __builtin_bit_cast(_Float16, (uint16_t)r.sraw[rp]);
+            const h8 s = {sc, sc, sc, sc, sc, sc, sc, sc};
+#pragma unroll
+            for (int jp = 0; jp < 2; ++jp) {
+                h8 b[4];
+                decode_tile<FMT>(r.w[rp][jp], z, b);
+#pragma unroll
+                for (int t = 0; t < 4; ++t) bf[rp][4 * jp + t] = b[t] * s;
+            }
+        }
+    }
 }
 
-// fp16 tiles (KT = 32): the four tiles of a 128-wide step of row block R are the four fragments
-__device__ __forceinline__ void load_f16_tiles(u4 (&v)[4], const void* __restrict__ tiles, int K, int R, int step, int lane)
+// second segment: B's fp16 tiles straight into operands (two steps at most: no prefetch)
+__device__ __forceinline__ void load_b_frags(h8 (&bf)[2][8], const void* __restrict__ tiles, int K, const int (&Rl)[2], int step, int lane)
 {
-    const u4* p = (const u4*)tiles + ((size_t)R * (K / 32) + 4 * step) * 64 + lane;
+    const int n = lane & 15, kg = lane >> 5;
 #pragma unroll
-    for (int t = 0; t < 4; ++t) v[t] = p[t * 64];
-}
-
-__device__ __forceinline__ void store_f16_tiles(const u4 (&v)[4], int rbs, int lane)
-{
+    for (int rp = 0; rp < 2; ++rp) {
+        const u4* p = (const u4*)tiles + ((size_t)Rl[rp] * (K / 32) + 4 * step) * 64 + n;
 #pragma unroll
-    for (int t = 0; t < 4; ++t) *(u4*)(eora_smem + PF_XS + (rbs * 4 + t) * 1024 + lane * 16) = v[t];
+        for (int f = 0; f < 8; ++f) bf[rp][f] = __builtin_bit_cast(h8, p[(f >> 1) * 64 + 16 * (2 * (f & 1) + kg)]);
+    }
 }
 
 // x slab of one step: thread tid owns the 16-byte chunks c = tid + 256*i, i = 0..7; chunk c is token row
@@ -94,45 +133,44 @@ __device__ __forceinline__ void load_x(u4 (&v)[8], const _Float16* __restrict__ 
     }
 }
 
-// The fragment (token block mb, slice t) holds for lane (n, j) the columns that the weight fragment of
-// that slice holds: 32j + 8t + i for a quantised tile (quarter_major: a lane owns a contiguous quarter
-// of the 128 columns), 32t + 8j + i for four fp16 tiles of 32 columns.  Slot n is XOR-ed with 4t so
-// that the 64 lanes of a store (4 rows x 16 chunks) spread over all LDS banks.
-__device__ __forceinline__ void store_x(const u4 (&v)[8], bool quarter_major, int tid)
+// The operand (token block tb of 32, slice f) holds for lane (token slot, kg) the eight columns that the
+// weight operand of slice f holds for kg: chunk kc = 4*(2*jp + kg) + t, f = 4*jp + t, for a quantised
+// tile (quarter_major); chunk kc = 4*tile + 2*s + kg, f = 2*tile + s, for four fp16 tiles.  The token slot
+// is XOR-ed with 2*f + kg: the 16 lanes that write one token row's chunks, and the 16 lanes of a read
+// that differ in token, then hit 16 different bank groups.
+__device__ __forceinline__ int x_slot(int tb, int f, int kg, int tr) { return ((tb * 8 + f) * 64 + 32 * kg + (tr ^ (2 * f + kg))) * 16; }
+
+__device__ __forceinline__ void store_x(const u4 (&v)[8], unsigned char* buf, bool quarter_major, int tid)
 {
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         const int c = tid + 256 * i;
         const int row = c >> 4, kc = c & 15;
-        const int j = quarter_major ? kc >> 2 : kc & 3, t = quarter_major ? kc & 3 : kc >> 2;
-        const int mb = row >> 4, n = row & 15;
-        *(u4*)(eora_smem + ((mb * 4 + t) * 64 + 16 * j + (n ^ (4 * t))) * 16) = v[i];
+        const int f = quarter_major ? ((kc >> 3) << 2) | (kc & 3) : kc >> 1;
+        const int kg = quarter_major ? (kc >> 2) & 1 : kc & 1;
+        *(u4*)(buf + x_slot(row >> 5, f, kg, row & 31)) = v[i];
     }
 }
 
-__device__ __forceinline__ void contract_step(f4 (&acc)[4][4], int wm, int wn, int lane)
+__device__ __forceinline__ void contract_step(f16v (&acc)[2][2], const h8 (&bf)[2][8], const unsigned char* buf, int wm, int lane)
 {
-    const int n = lane & 15, j = lane >> 4;
+    const int tr = lane & 31, kg = lane >> 5;
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
-        h8 af[4], bf[4];
+    for (int f = 0; f < 8; ++f) {
+        h8 af[2];
 #pragma unroll
-        for (int mb = 0; mb < 4; ++mb)
-            af[mb] = *(const h8*)(eora_smem + (((4 * wm + mb) * 4 + t) * 64 + 16 * j + (n ^ (4 * t))) * 16);
+        for (int mb = 0; mb < 2; ++mb) af[mb] = *(const h8*)(buf + x_slot(2 * wm + mb, f, kg, tr));
 #pragma unroll
-        for (int rb = 0; rb < 4; ++rb)
-            bf[rb] = *(const h8*)(eora_smem + PF_XS + (((4 * wn + rb) * 4 + t) * 64 + lane) * 16);
+        for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-        for (int mb = 0; mb < 4; ++mb)
-#pragma unroll
-            for (int rb = 0; rb < 4; ++rb) acc[mb][rb] = mfma16(af[mb], bf[rb], acc[mb][rb]);
+            for (int rp = 0; rp < 2; ++rp) acc[mb][rp] = mfma32(af[mb], bf[rp][f], acc[mb][rp]);
     }
 }
 
 // FM: format of the first segment's weights (S_Q4, S_Q3 asymmetric; S_Q4S128; S_F16).  EXT: continue over a
 // second segment of fp16 tiles (B) with its own activations (t).
 template <int FM, bool EXT>
-__global__ __launch_bounds__(256) void prefill_kernel(PrefillArgs a)
+__global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a)
 {
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int wm = wave >> 1, wn = wave & 1;                      // this wavefront's 64 x 64 quadrant
@@ -140,76 +178,67 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillArgs a)
     const int m0 = (blockIdx.x / ntn) * PF_BM;
     const int R0 = (blockIdx.x % ntn) * 8;
     const int nblk = a.N / 16;
-    // the two row blocks (slots 2*wave, 2*wave+1) this wavefront decodes, clamped to valid ones
-    const int Ra = R0 + 2 * wave < nblk ? R0 + 2 * wave : nblk - 1;
-    const int Rb = R0 + 2 * wave + 1 < nblk ? R0 + 2 * wave + 1 : nblk - 1;
+    const int h = (lane >> 4) & 1;
+    int Rl[2];                                                    // the row blocks this lane supplies rows of, clamped to valid ones
+#pragma unroll
+    for (int rp = 0; rp < 2; ++rp) Rl[rp] = R0 + 4 * wn + 2 * rp + h < nblk ? R0 + 4 * wn + 2 * rp + h : nblk - 1;
     const int G1 = a.K1 / 128, G2 = EXT ? a.K2 / 128 : 0, GT = G1 + G2;
     constexpr bool W16 = FM == S_F16;                             // first segment's weights are fp16 tiles
+    unsigned char* const buf0 = eora_smem;
+    unsigned char* const buf1 = eora_smem + PF_XS;
 
-    f4 acc[4][4];
+    f16v acc[2][2];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int k = 0; k < 4; ++k) acc[i][k] = f4{0.f, 0.f, 0.f, 0.f};
+        for (int k = 0; k < 2; ++k)
+#pragma unroll
+            for (int q = 0; q < 16; ++q) acc[i][k][q] = 0.f;
 
-    u4 xr[8];                                                     // prefetched x slab of the next step
-    WReg wa, wb;                                                  // prefetched quantised tiles
-    u4 fa[4], fb[4];                                              // prefetched fp16 tiles
-    load_x(xr, a.x, a.ldx, a.M, m0, 0, tid);
-    if constexpr (W16) {
-        load_f16_tiles(fa, a.w, a.K1, Ra, 0, lane);
-        load_f16_tiles(fb, a.w, a.K1, Rb, 0, lane);
-    } else {
-        load_wtile<FM>(wa, a, Ra, 0, lane);
-        load_wtile<FM>(wb, a, Rb, 0, lane);
-    }
+    // x slab of step s into registers (steps past the end re-read the last one; never stored)
+    auto fetch_x = [&](u4 (&v)[8], int s) {
+        s = s < GT ? s : GT - 1;
+        if (EXT && s >= G1) load_x(v, a.x2, a.ldx2, a.M, m0, (s - G1) * 128, tid);
+        else load_x(v, a.x, a.ldx, a.M, m0, s * 128, tid);
+    };
+    u4 xr[8];
+    WPre<FM> wp;
+    fetch_x(xr, 0);
+    load_wpre<FM>(wp, a, Rl, 0, lane);
+    store_x(xr, buf0, !W16, tid);
+    fetch_x(xr, 1);                                               // xr always holds the slab of the step after the one in LDS
+    __syncthreads();
 
     for (int s = 0; s < GT; ++s) {
-        const bool seg2 = EXT && s >= G1;
-        const bool cur16 = W16 || seg2;
-        __syncthreads();                                          // everyone has finished reading the previous step
-        store_x(xr, !cur16, tid);
-        if (cur16) {
-            store_f16_tiles(fa, 2 * wave, lane);
-            store_f16_tiles(fb, 2 * wave + 1, lane);
+        unsigned char* const cur = (s & 1) ? buf1 : buf0;
+        unsigned char* const nxt = (s & 1) ? buf0 : buf1;
+        h8 bf[2][8];
+        if (EXT && s >= G1) {
+            load_b_frags(bf, a.w2, a.K2, Rl, s - G1, lane);
         } else {
-            if constexpr (!W16) {
-                store_wtile<FM>(wa, 2 * wave, lane);
-                store_wtile<FM>(wb, 2 * wave + 1, lane);
-            }
+            decode_wpre<FM>(wp, bf);
+            load_wpre<FM>(wp, a, Rl, s + 1 < G1 ? s + 1 : G1 - 1, lane);     // past the end: re-read, never used
         }
-        __syncthreads();                                          // the step's operands are in LDS
-        if (s + 1 < GT) {
-            const bool n2 = EXT && s + 1 >= G1;
-            if (n2) {
-                load_x(xr, a.x2, a.ldx2, a.M, m0, (s + 1 - G1) * 128, tid);
-                load_f16_tiles(fa, a.w2, a.K2, Ra, s + 1 - G1, lane);
-                load_f16_tiles(fb, a.w2, a.K2, Rb, s + 1 - G1, lane);
-            } else {
-                load_x(xr, a.x, a.ldx, a.M, m0, (s + 1) * 128, tid);
-                if constexpr (W16) {
-                    load_f16_tiles(fa, a.w, a.K1, Ra, s + 1, lane);
-                    load_f16_tiles(fb, a.w, a.K1, Rb, s + 1, lane);
-                } else {
-                    load_wtile<FM>(wa, a, Ra, s + 1, lane);
-                    load_wtile<FM>(wb, a, Rb, s + 1, lane);
-                }
-            }
-        }
-        contract_step(acc, wm, wn, lane);
+        // nothing crosses this point: left alone, the scheduler sinks the requests for the next step's
+        // weights below the MFMAs, and the next step then starts by waiting for them
+        __builtin_amdgcn_sched_barrier(0);
+        contract_step(acc, bf, cur, wm, lane);
+        // the next step's slab goes to the other buffer (free since the barrier of the step before)
+        store_x(xr, nxt, !(W16 || (EXT && s + 1 >= G1)), tid);
+        fetch_x(xr, s + 2);
+        __syncthreads();
     }
 
     // ---- epilogue: fp32 -> fp16, transpose through LDS, 128-byte row stores ----------------------------
-    __syncthreads();                                              // all fragment reads done: LDS is free
     constexpr int TS = 72;                                        // halves per token row in the staging tile (64 + pad)
     _Float16* tile = (_Float16*)eora_smem + wave * 64 * TS;
-    const int n = lane & 15, j = lane >> 4;
 #pragma unroll
-    for (int mb = 0; mb < 4; ++mb)
+    for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-        for (int rb = 0; rb < 4; ++rb)
+        for (int rp = 0; rp < 2; ++rp)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) tile[(16 * mb + 4 * j + i) * TS + 16 * rb + n] = (_Float16)acc[mb][rb][i];
+            for (int v = 0; v < 16; ++v)
+                tile[(32 * mb + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3)) * TS + 32 * rp + (lane & 31)] = (_Float16)acc[mb][rp][v];
     __syncthreads();
 #pragma unroll
     for (int it = 0; it < 8; ++it) {
