@@ -79,6 +79,20 @@ int pick_kcn(int M, int d_in)
     return kcn;
 }
 
+// Parts the prefill down-projection t = x.A^T (few output tiles: r / 128 per 128 tokens) splits its
+// contraction into so that the launch fills the chip; their fp32 tiles are added in a fixed order.
+int pick_ksplit(int M, int d_in, int r)
+{
+    if (r == 0) return 1;
+    const int tiles = ((M + 127) / 128) * ((r + 127) / 128), G = d_in / 128;
+    int want = (256 + tiles - 1) / tiles;
+    want = want > 8 ? 8 : want;
+    int ks = 1;
+    for (int c = 2; c <= want; ++c)
+        if (G % c == 0) ks = c;
+    return ks;
+}
+
 // one launch of the decode kernel for validated members that share x
 int launch_group(const void* x, const eora_q_member* members, int n, int M, int d_in, int r, int w_bits, int group,
                  int fa, int fe, int nw, int nq, void* workspace, hipStream_t stream)
@@ -118,7 +132,8 @@ size_t eora_workspace_bytes(int M, int d_in, int d_out, int r)
 {
     if (check_backbone_shape(M, d_in, d_out, r) != EORA_OK) return 0;
     // partials of t for the small-M kernels, and t itself as fp16 M x r for the prefill GEMM
-    return WS_T + round256((size_t)M * r * 2);
+    const int ks = (M >= PREFILL_MIN_TOKENS) ? pick_ksplit(M, d_in, r) : 1;
+    return WS_T + round256((size_t)M * r * 2) + (ks > 1 ? (size_t)ks * M * r * sizeof(float) : 0);
 }
 
 int eora_workspace_init(void* workspace, size_t workspace_bytes, void* stream)
@@ -192,7 +207,11 @@ static int run_linear_q(const void* x, const eora_q_member& e, int M, int d_in, 
             p.w = A; p.K1 = d_in;
             p.y = T; p.ldy = r;
             p.M = M; p.N = r;
+            p.ksplit = pick_ksplit(M, d_in, r);
+            p.part = (float*)((char*)workspace + WS_T + round256((size_t)M * r * 2));
             if (failed(launch_prefill(p, S_F16, false, (hipStream_t)stream), "prefill down-projection")) return EORA_ERR_LAUNCH;
+            if (p.ksplit > 1 && failed(launch_reduce_parts(p.part, T, (size_t)M * r, p.ksplit, (hipStream_t)stream), "prefill down-projection sum"))
+                return EORA_ERR_LAUNCH;
         }
         PrefillArgs p{};
         p.x = (const _Float16*)x; p.ldx = d_in;
@@ -201,6 +220,7 @@ static int run_linear_q(const void* x, const eora_q_member& e, int M, int d_in, 
         p.x2 = T; p.ldx2 = r; p.w2 = B; p.K2 = r;
         p.y = y; p.ldy = d_out;
         p.M = M; p.N = d_out;
+        p.ksplit = 1;
         if (failed(launch_prefill(p, w_bits == 4 ? S_Q4 : S_Q3, r > 0, (hipStream_t)stream), "prefill")) return EORA_ERR_LAUNCH;
         return EORA_OK;
     }

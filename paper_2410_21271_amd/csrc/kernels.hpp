@@ -95,7 +95,11 @@ struct PrefillArgs {
     void* y;                  // fp16, row stride ldy
     int ldy;
     int M, N, K1, K2;
+    int ksplit;               // > 1: workgroup (tile, ks) contracts the ks-th part of K1 only and writes its
+    float* part;              //      fp32 tile to part[ks][M][N] instead of y (no second segment then)
 };
+// T[i] = fp16(sum over ks, in order, of part[ks][i]), i < count (count % 4 == 0)
+hipError_t launch_reduce_parts(const float* part, void* T, size_t count, int ksplit, hipStream_t stream);
 
 hipError_t launch_prefill(const PrefillArgs& a, int fm, bool ext, hipStream_t stream);
 

@@ -174,15 +174,18 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a)
 {
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int wm = wave >> 1, wn = wave & 1;                      // this wavefront's 64 x 64 quadrant
-    const int ntn = (a.N + PF_BN - 1) / PF_BN;
-    const int m0 = (blockIdx.x / ntn) * PF_BM;
-    const int R0 = (blockIdx.x % ntn) * 8;
+    const int ntn = (a.N + PF_BN - 1) / PF_BN, ntm = (a.M + PF_BM - 1) / PF_BM;
+    const int tile_id = blockIdx.x % (ntn * ntm), ks = blockIdx.x / (ntn * ntm);     // ks > 0 only with ksplit > 1
+    const int m0 = (tile_id / ntn) * PF_BM;
+    const int R0 = (tile_id % ntn) * 8;
     const int nblk = a.N / 16;
     const int h = (lane >> 4) & 1;
     int Rl[2];                                                    // the row blocks this lane supplies rows of, clamped to valid ones
 #pragma unroll
     for (int rp = 0; rp < 2; ++rp) Rl[rp] = R0 + 4 * wn + 2 * rp + h < nblk ? R0 + 4 * wn + 2 * rp + h : nblk - 1;
-    const int G1 = a.K1 / 128, G2 = EXT ? a.K2 / 128 : 0, GT = G1 + G2;
+    const int G1 = a.K1 / 128, G2 = EXT ? a.K2 / 128 : 0;
+    const int sb = EXT ? 0 : ks * (G1 / a.ksplit);               // this workgroup's steps: [sb, GT)
+    const int GT = EXT ? G1 + G2 : sb + G1 / a.ksplit;
     constexpr bool W16 = FM == S_F16;                             // first segment's weights are fp16 tiles
     unsigned char* const buf0 = eora_smem;
     unsigned char* const buf1 = eora_smem + PF_XS;
@@ -203,21 +206,21 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a)
     };
     u4 xr[8];
     WPre<FM> wp;
-    fetch_x(xr, 0);
-    load_wpre<FM>(wp, a, Rl, 0, lane);
+    fetch_x(xr, sb);
+    load_wpre<FM>(wp, a, Rl, sb, lane);
     store_x(xr, buf0, !W16, tid);
-    fetch_x(xr, 1);                                               // xr always holds the slab of the step after the one in LDS
+    fetch_x(xr, sb + 1);                                          // xr always holds the slab of the step after the one in LDS
     __syncthreads();
 
-    for (int s = 0; s < GT; ++s) {
-        unsigned char* const cur = (s & 1) ? buf1 : buf0;
-        unsigned char* const nxt = (s & 1) ? buf0 : buf1;
+    for (int s = sb; s < GT; ++s) {
+        unsigned char* const cur = ((s - sb) & 1) ? buf1 : buf0;
+        unsigned char* const nxt = ((s - sb) & 1) ? buf0 : buf1;
         h8 bf[2][8];
         if (EXT && s >= G1) {
             load_b_frags(bf, a.w2, a.K2, Rl, s - G1, lane);
         } else {
             decode_wpre<FM>(wp, bf);
-            load_wpre<FM>(wp, a, Rl, s + 1 < G1 ? s + 1 : G1 - 1, lane);     // past the end: re-read, never used
+            load_wpre<FM>(wp, a, Rl, s + 1 < (EXT ? G1 : GT) ? s + 1 : s, lane);     // past the end: re-read, never used
         }
         // nothing crosses this point: left alone, the scheduler sinks the requests for the next step's
         // weights below the MFMAs, and the next step then starts by waiting for them
@@ -229,6 +232,20 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a)
         __syncthreads();
     }
 
+    // ---- split contraction: this part's fp32 tile, 128-byte rows straight from the accumulators ------
+    if (!EXT && a.ksplit > 1) {
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int rp = 0; rp < 2; ++rp)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int m = m0 + 64 * wm + 32 * mb + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+                    const int o = (R0 + 4 * wn) * 16 + 32 * rp + (lane & 31);
+                    if (m < a.M && o < a.N) a.part[((size_t)ks * a.M + m) * a.N + o] = acc[mb][rp][v];
+                }
+        return;
+    }
     // ---- epilogue: fp32 -> fp16, transpose through LDS, 128-byte row stores ----------------------------
     constexpr int TS = 72;                                        // halves per token row in the staging tile (64 + pad)
     _Float16* tile = (_Float16*)eora_smem + wave * 64 * TS;
@@ -256,7 +273,23 @@ static hipError_t launch_pf(const PrefillArgs& a, hipStream_t stream)
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, PF_LDS);
     if (e != hipSuccess) return e;
     const int ntn = (a.N + PF_BN - 1) / PF_BN, ntm = (a.M + PF_BM - 1) / PF_BM;
-    hipLaunchKernelGGL(kern, dim3(ntn * ntm), dim3(256), PF_LDS, stream, a);
+    hipLaunchKernelGGL(kern, dim3(ntn * ntm * (EXT ? 1 : a.ksplit)), dim3(256), PF_LDS, stream, a);
+    return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void reduce_parts_kernel(const float* __restrict__ part, _Float16* __restrict__ T, size_t count, int ksplit)
+{
+    const size_t i = 4 * ((size_t)blockIdx.x * 256 + threadIdx.x);
+    if (i >= count) return;
+    f4 v = *(const f4*)(part + i);
+    for (int ks = 1; ks < ksplit; ++ks) v += *(const f4*)(part + ks * count + i);      // fixed order
+    typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+    *(h4*)(T + i) = h4{(_Float16)v[0], (_Float16)v[1], (_Float16)v[2], (_Float16)v[3]};
+}
+
+hipError_t launch_reduce_parts(const float* part, void* T, size_t count, int ksplit, hipStream_t stream)
+{
+    hipLaunchKernelGGL(reduce_parts_kernel, dim3((unsigned)((count / 4 + 255) / 256)), dim3(256), 0, stream, part, (_Float16*)T, count, ksplit);
     return hipGetLastError();
 }
 
