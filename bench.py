@@ -20,6 +20,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+MFMA_PEAK_TFLOPS = 2500.0         # dense fp16
 
 WORKLOADS = {
     # name: (shapes, w_bits, ab_bits, r, M, outlier_frac, config id for the seeds)
@@ -40,7 +41,8 @@ WORKLOADS = {
 # the same layers with the linears that read the same x sharing a launch (q/k/v and gate/up): four launches a step
 for _n in ("llama3-8b-layer-decode-w3g128-r128fp16-M1", "llama3-8b-layer-decode-w3g128-bare-M1",
            "llama3-8b-layer-decode-w4g128-r128fp16-M1", "llama3-8b-layer-decode-w4g128-r128q4-M1",
-           "llama3-8b-layer-decode-w4g128-bare-M1"):
+           "llama3-8b-layer-decode-w4g128-bare-M1", "llama3-8b-layer-prefill-w4g128-r256fp16-M2048",
+           "llama3-8b-layer-prefill-w4g128-bare-M2048"):
     WORKLOADS[_n + "-grouped"] = dict(WORKLOADS[_n], grouped=True)
 GROUPS = (("q", "k", "v"), ("o",), ("gate", "up"), ("down",))
 for _r in (64, 256, 512):
@@ -123,7 +125,7 @@ class Group:
         self.name = "+".join(L.name for L in members)
         self.d_in = members[0].d_in
         m0 = members[0]
-        self.ws = eora.new_workspace(m0.M, m0.d_in, max(L.d_out for L in members), m0.r)
+        self.ws = eora.new_workspace(m0.M, m0.d_in, max(L.d_out for L in members), m0.r, n_members=len(members))
         # x is read once per launch, not once per member
         self.bytes = sum(L.bytes for L in members) - 2 * m0.M * m0.d_in * (len(members) - 1)
         self.flops = sum(L.flops for L in members)
@@ -270,16 +272,31 @@ def main():
     if os.path.exists(tpath):
         with open(tpath) as f:
             traffic = json.load(f).get(args.workload)
-    roofline = dict(bound="hbm", achieved=round(dom_bytes / dom_us / 1e3, 1), peak=HBM_PEAK_GBS, unit="GB/s",
-                    frac=round(dom_bytes / dom_us / 1e3 / HBM_PEAK_GBS, 4), traffic=traffic,
-                    kernel="layer kernel instantiation of the d_in=%d linears (%s)" % (dom[0].d_in, ",".join(L.name for L in dom)),
-                    bytes_per_launch=int(dom_bytes), us_per_launch=round(dom_us, 3))
-
-    out = dict(metric="decode HBM GB/s over one 8B decoder layer's linears (M=1)",
-               value=round(layer_bytes / ms_per_step / 1e6, 1), unit="GB/s", n_gpus=1, steps=args.steps,
+    prefill = spec["M"] >= 128
+    if prefill:
+        # dominant kernel: the GEMM kernel; a launch contracts one linear (or one group of them)
+        dom_flops = sum(L.flops for L in dom) / len(dom)
+        roofline = dict(bound="mfma", achieved=round(dom_flops / dom_us / 1e6, 1), peak=MFMA_PEAK_TFLOPS, unit="TFLOP/s",
+                        frac=round(dom_flops / dom_us / 1e6 / MFMA_PEAK_TFLOPS, 4), traffic=None,
+                        kernel="prefill GEMM kernel on the d_in=%d launches (%s)" % (dom[0].d_in, ",".join(L.name for L in dom)),
+                        flops_per_launch=int(dom_flops), us_per_launch=round(dom_us, 3))
+    else:
+        roofline = dict(bound="hbm", achieved=round(dom_bytes / dom_us / 1e3, 1), peak=HBM_PEAK_GBS, unit="GB/s",
+                        frac=round(dom_bytes / dom_us / 1e3 / HBM_PEAK_GBS, 4), traffic=traffic,
+                        kernel="layer kernel instantiation of the d_in=%d launches (%s)" % (dom[0].d_in, ",".join(L.name for L in dom)),
+                        bytes_per_launch=int(dom_bytes), us_per_launch=round(dom_us, 3))
+    layer_flops = sum(L.flops for L in linears)
+    if prefill:
+        out = dict(metric="prefill TFLOP/s over one 8B decoder layer's linears (M=%d)" % spec["M"],
+                   value=round(layer_flops / ms_per_step / 1e9, 1), unit="TFLOP/s")
+    else:
+        out = dict(metric="decode HBM GB/s over one %s decoder layer's linears (M=%d)" % (spec["model"].upper(), spec["M"]),
+                   value=round(layer_bytes / ms_per_step / 1e6, 1), unit="GB/s")
+    out.update(n_gpus=1, steps=args.steps,
                warmup=args.warmup, ms_per_step=round(ms_per_step, 6), higher_is_better=True, scaling="weak",
                vs_baseline=None, dtype="f16", data="synthetic",
-               config=dict(workload=args.workload, layer_bytes=int(layer_bytes), weight_copies=ncopies,
+               config=dict(workload=args.workload, layer_bytes=int(layer_bytes), layer_flops=int(layer_flops), weight_copies=ncopies,
+                           launches_per_step=len(launches),
                            layer_us=round(1e3 * ms_per_step, 3), frac_hbm_peak=round(layer_bytes / ms_per_step / 1e6 / HBM_PEAK_GBS, 4),
                            per_linear=per_linear),
                roofline=roofline)

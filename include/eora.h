@@ -92,6 +92,10 @@ size_t eora_sp24_indices_bytes(int d_in, int d_out);                 /* d_out*d_
  * (different streams) need different workspaces.  r == 0 still needs a workspace.  A workspace of
  * the size of the largest (M, r) serves smaller calls too. */
 size_t eora_workspace_bytes(int M, int d_in, int d_out, int r);
+/* Size that lets eora_linear_q_group() serve n_members members in one pass also for M >= 128 (the
+ * down-projections of all members then sit side by side in the scratch).  With a workspace of only
+ * eora_workspace_bytes() such a call still works, member by member. */
+size_t eora_workspace_bytes_group(int M, int d_in, int r, int n_members);
 /* Enqueues the clearing of all `workspace_bytes` bytes on `stream`. */
 int eora_workspace_init(void* workspace, size_t workspace_bytes, void* stream);
 /* Diagnostic.  SYNCHRONISES `stream`, then reports EORA_ERR_TIMEOUT if a kernel that used this
@@ -153,10 +157,13 @@ int eora_linear_q(const void* x, const void* qweight, const void* scales, const 
  * eora_linear_q layer of its own (own weights, factors, output and d_out); M, d_in, r, w_bits,
  * group and ab_bits are common.  Results are bit-identical to n_members separate eora_linear_q
  * calls.  For one to four tokens and group == 128 this is one launch, which pays the launch and
- * the hand-over of x.A^T once; other shapes run the members one after the other.
+ * the hand-over of x.A^T once; for M >= 128 (fp16 factors, r % 128 == 0, or r == 0) the members'
+ * rows form one GEMM, which keeps narrow members (d_out = 1024) from leaving most of the chip
+ * idle; other shapes run the members one after the other.
  * members: HOST array (read during the call only) of 1..4 entries; pointers inside are DEVICE
  * pointers with the meaning and constraints of the eora_linear_q arguments of the same name.
- * workspace: at least the largest eora_workspace_bytes(M, d_in, d_out_m, r). */
+ * workspace: at least the largest eora_workspace_bytes(M, d_in, d_out_m, r); see
+ * eora_workspace_bytes_group(). */
 typedef struct {
     const void* qweight;
     const void* scales;

@@ -46,6 +46,7 @@ def _load():
         "eora_sp24_values_bytes": (sz, [ci, ci]),
         "eora_sp24_indices_bytes": (sz, [ci, ci]),
         "eora_workspace_bytes": (sz, [ci, ci, ci, ci]),
+        "eora_workspace_bytes_group": (sz, [ci, ci, ci, ci]),
         "eora_workspace_init": (ci, [vp, sz, vp]),
         "eora_workspace_error": (ci, [vp, vp]),
         "eora_debug_set_spin_limit": (None, [ci]),
@@ -69,7 +70,7 @@ def _load():
 
 lib = _load()
 EXPORTS = ["eora_status_string", "eora_qweight_bytes", "eora_qzeros_bytes", "eora_scales_bytes",
-           "eora_sp24_values_bytes", "eora_sp24_indices_bytes", "eora_workspace_bytes", "eora_workspace_init",
+           "eora_sp24_values_bytes", "eora_sp24_indices_bytes", "eora_workspace_bytes", "eora_workspace_bytes_group", "eora_workspace_init",
            "eora_workspace_error", "eora_debug_set_spin_limit", "eora_pack_q",
            "eora_pack_factor_f16", "eora_pack_factor_q4", "eora_pack_sp24", "eora_linear_q",
            "eora_linear_q_group", "eora_linear_sp24", "eora_unpack_q", "eora_dequant_q", "eora_expand_sp24"]
@@ -185,10 +186,15 @@ def debug_set_spin_limit(iterations):
     lib.eora_debug_set_spin_limit(int(iterations))
 
 
-def new_workspace(M, d_in, d_out, r):
+def workspace_bytes_group(M, d_in, r, n_members):
+    return lib.eora_workspace_bytes_group(M, d_in, r, n_members)
+
+
+def new_workspace(M, d_in, d_out, r, n_members=1):
     """Allocate (torch, device memory only) and initialise a workspace for the forward calls."""
     import torch
-    ws = torch.empty(workspace_bytes(M, d_in, d_out, r), dtype=torch.uint8, device="cuda")
+    nbytes = max(workspace_bytes(M, d_in, d_out, r), workspace_bytes_group(M, d_in, r, n_members))
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
     workspace_init(ws)
     return ws
 

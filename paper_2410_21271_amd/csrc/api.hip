@@ -93,6 +93,59 @@ int pick_ksplit(int M, int d_in, int r)
     return ks;
 }
 
+// Many tokens: MFMA-bound GEMM (t = x.A^T first, then one GEMM over d_in and r)
+bool prefill_fits(int M, int r, int ab_bits) { return M >= PREFILL_MIN_TOKENS && (r == 0 || (ab_bits == 16 && r % 128 == 0)); }
+
+// scratch of the prefill path for n members: t (fp16, M x n*r) and the fp32 parts of its split contraction
+size_t prefill_scratch_bytes(int M, int d_in, int r, int n)
+{
+    const int ks = pick_ksplit(M, d_in, n * r);
+    return round256((size_t)M * n * r * 2) + (ks > 1 ? (size_t)ks * M * n * r * sizeof(float) : 0);
+}
+
+// validated members that share x, as GEMMs: one launch for every member's t (the members' A side by side), one
+// for every member's y
+int launch_prefill_group(const void* x, const eora_q_member* members, int n, int M, int d_in, int r, int w_bits, int group,
+                         void* workspace, hipStream_t stream)
+{
+    _Float16* T = (_Float16*)((char*)workspace + WS_T);           // M x (n * r): member m owns columns m*r ..
+    if (r > 0) {
+        PrefillArgs p{};
+        p.x = (const _Float16*)x; p.ldx = d_in;
+        p.M = M; p.K1 = d_in;
+        p.n = n;
+        p.ksplit = pick_ksplit(M, d_in, n * r);
+        p.part = (float*)((char*)workspace + WS_T + round256((size_t)M * n * r * 2));
+        p.ldp = n * r;
+        for (int m = 0; m < n; ++m) {
+            p.w[m] = members[m].A;
+            p.y[m] = T + (size_t)m * r; p.ldy[m] = n * r;
+            p.N[m] = r; p.pcol[m] = m * r;
+        }
+        if (failed(launch_prefill(p, S_F16, false, stream), "prefill down-projection")) return EORA_ERR_LAUNCH;
+        if (p.ksplit > 1 && failed(launch_reduce_parts(p.part, T, (size_t)M * n * r, p.ksplit, stream), "prefill down-projection sum"))
+            return EORA_ERR_LAUNCH;
+    }
+    PrefillArgs p{};
+    p.x = (const _Float16*)x; p.ldx = d_in;
+    p.group = group;
+    p.M = M; p.K1 = d_in; p.K2 = r;
+    p.ldx2 = n * r;
+    p.n = n;
+    p.ksplit = 1;
+    for (int m = 0; m < n; ++m) {
+        p.w[m] = members[m].qweight;
+        p.w_scales[m] = (const _Float16*)members[m].scales;
+        p.w_zeros[m] = (const uint32_t*)members[m].qzeros;
+        p.x2[m] = T + (size_t)m * r;
+        p.w2[m] = members[m].B;
+        p.y[m] = members[m].y; p.ldy[m] = members[m].d_out;
+        p.N[m] = members[m].d_out;
+    }
+    if (failed(launch_prefill(p, w_bits == 4 ? S_Q4 : S_Q3, r > 0, stream), "prefill")) return EORA_ERR_LAUNCH;
+    return EORA_OK;
+}
+
 // one launch of the decode kernel for validated members that share x
 int launch_group(const void* x, const eora_q_member* members, int n, int M, int d_in, int r, int w_bits, int group,
                  int fa, int fe, int nw, int nq, void* workspace, hipStream_t stream)
@@ -132,8 +185,13 @@ size_t eora_workspace_bytes(int M, int d_in, int d_out, int r)
 {
     if (check_backbone_shape(M, d_in, d_out, r) != EORA_OK) return 0;
     // partials of t for the small-M kernels, and t itself as fp16 M x r for the prefill GEMM
-    const int ks = (M >= PREFILL_MIN_TOKENS) ? pick_ksplit(M, d_in, r) : 1;
-    return WS_T + round256((size_t)M * r * 2) + (ks > 1 ? (size_t)ks * M * r * sizeof(float) : 0);
+    return WS_T + (M >= PREFILL_MIN_TOKENS ? prefill_scratch_bytes(M, d_in, r, 1) : 0);
+}
+
+size_t eora_workspace_bytes_group(int M, int d_in, int r, int n_members)
+{
+    if (n_members < 1 || n_members > MAX_GROUP || check_backbone_shape(M, d_in, 16, r) != EORA_OK) return 0;
+    return WS_T + (M >= PREFILL_MIN_TOKENS ? prefill_scratch_bytes(M, d_in, r, n_members) : 0);
 }
 
 int eora_workspace_init(void* workspace, size_t workspace_bytes, void* stream)
@@ -198,32 +256,7 @@ static int run_linear_q(const void* x, const eora_q_member& e, int M, int d_in, 
     const int d_out = e.d_out;
     if (M == 0) return EORA_OK;
 
-    // Many tokens: MFMA-bound GEMM (t = x.A^T first, then one GEMM over d_in and r).
-    if (M >= PREFILL_MIN_TOKENS && (r == 0 || (ab_bits == 16 && r % 128 == 0))) {
-        _Float16* T = (_Float16*)((char*)workspace + WS_T);
-        if (r > 0) {
-            PrefillArgs p{};
-            p.x = (const _Float16*)x; p.ldx = d_in;
-            p.w = A; p.K1 = d_in;
-            p.y = T; p.ldy = r;
-            p.M = M; p.N = r;
-            p.ksplit = pick_ksplit(M, d_in, r);
-            p.part = (float*)((char*)workspace + WS_T + round256((size_t)M * r * 2));
-            if (failed(launch_prefill(p, S_F16, false, (hipStream_t)stream), "prefill down-projection")) return EORA_ERR_LAUNCH;
-            if (p.ksplit > 1 && failed(launch_reduce_parts(p.part, T, (size_t)M * r, p.ksplit, (hipStream_t)stream), "prefill down-projection sum"))
-                return EORA_ERR_LAUNCH;
-        }
-        PrefillArgs p{};
-        p.x = (const _Float16*)x; p.ldx = d_in;
-        p.w = qweight; p.w_scales = (const _Float16*)scales; p.w_zeros = (const uint32_t*)qzeros; p.group = group;
-        p.K1 = d_in;
-        p.x2 = T; p.ldx2 = r; p.w2 = B; p.K2 = r;
-        p.y = y; p.ldy = d_out;
-        p.M = M; p.N = d_out;
-        p.ksplit = 1;
-        if (failed(launch_prefill(p, w_bits == 4 ? S_Q4 : S_Q3, r > 0, (hipStream_t)stream), "prefill")) return EORA_ERR_LAUNCH;
-        return EORA_OK;
-    }
+    if (prefill_fits(M, r, ab_bits)) return launch_prefill_group(x, &e, 1, M, d_in, r, w_bits, group, workspace, (hipStream_t)stream);
 
     int nw = 0, nq = 0;
     if (small_kernel_fits(M, d_in, group, &nw, &nq))
@@ -283,7 +316,9 @@ int eora_linear_q_group(const void* x, const eora_q_member* members, int n_membe
     if (small_kernel_fits(M, d_in, group, &nw, &nq) &&
         (r == 0 || (r / 16) * pick_kcn(M, d_in) * n_members <= HDR_FLAGS_PER_BLOCK))
         return launch_group(x, members, n_members, M, d_in, r, w_bits, group, fa, fe, nw, nq, workspace, (hipStream_t)stream);
-    for (int m = 0; m < n_members; ++m) {               // shapes the decode kernel does not take: one after the other
+    if (prefill_fits(M, r, ab_bits) && workspace_bytes >= eora_workspace_bytes_group(M, d_in, r, n_members))
+        return launch_prefill_group(x, members, n_members, M, d_in, r, w_bits, group, workspace, (hipStream_t)stream);
+    for (int m = 0; m < n_members; ++m) {               // other shapes (or a workspace sized for one member): one after the other
         const int rc = run_linear_q(x, members[m], M, d_in, r, w_bits, group, ab_bits, fa, fe, workspace, stream);
         if (rc != EORA_OK) return rc;
     }

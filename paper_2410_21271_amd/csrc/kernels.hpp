@@ -81,23 +81,31 @@ struct SparseArgs {
 
 hipError_t launch_sparse(const SparseArgs& a, hipStream_t stream);
 
-// Prefill GEMM (prefill.hip): y[M x N] = act[M x K1] . W1^T (+ act2[M x K2] . W2^T), fp16 output
+// Prefill GEMM (prefill.hip): y[M x N] = act[M x K1] . W1^T (+ act2[M x K2] . W2^T), fp16 output, for up to
+// MAX_GROUP members that read the same act (own weights, second-segment operands, output and N).
 struct PrefillArgs {
-    const _Float16* x;        // first segment's activations, row stride ldx
+    const _Float16* x;        // first segment's activations, row stride ldx (shared)
     int ldx;
-    const void* w;            // first segment's weight tiles (N rows, K1 columns)
-    const _Float16* w_scales;
-    const uint32_t* w_zeros;
     int group;
-    const _Float16* x2;       // second segment's activations (t), row stride ldx2
-    int ldx2;
-    const void* w2;           // second segment's fp16 tiles (N rows, K2 columns)
-    void* y;                  // fp16, row stride ldy
-    int ldy;
-    int M, N, K1, K2;
+    int ldx2;                 // row stride of the second segment's activations
+    int M, K1, K2;
     int ksplit;               // > 1: workgroup (tile, ks) contracts the ks-th part of K1 only and writes its
-    float* part;              //      fp32 tile to part[ks][M][N] instead of y (no second segment then)
+    float* part;              //      fp32 tile to part[ks][M][ldp] (columns pcol ..) instead of y; no second segment then
+    int ldp;
+    int n;                    // members
+    const void* w[MAX_GROUP];            // first segment's weight tiles (N rows, K1 columns)
+    const _Float16* w_scales[MAX_GROUP];
+    const uint32_t* w_zeros[MAX_GROUP];
+    const _Float16* x2[MAX_GROUP];       // second segment's activations (t)
+    const void* w2[MAX_GROUP];           // second segment's fp16 tiles (N rows, K2 columns)
+    void* y[MAX_GROUP];                  // fp16, row stride ldy
+    int ldy[MAX_GROUP];
+    int N[MAX_GROUP];
+    int pcol[MAX_GROUP];
 };
+
+hipError_t launch_prefill(const PrefillArgs& a, int fm, bool ext, hipStream_t stream);
+
 // T[i] = fp16(sum over ks, in order, of part[ks][i]), i < count (count % 4 == 0)
 hipError_t launch_reduce_parts(const float* part, void* T, size_t count, int ksplit, hipStream_t stream);
 

@@ -34,6 +34,25 @@ namespace eora {
 
 typedef float f16v __attribute__((ext_vector_type(16)));
 
+// one member of a launch, as the helpers below see it
+struct PfView {
+    const _Float16* x;
+    int ldx;
+    const void* w;
+    const _Float16* w_scales;
+    const uint32_t* w_zeros;
+    int group;
+    const _Float16* x2;
+    int ldx2;
+    const void* w2;
+    void* y;
+    int ldy;
+    int M, N, K1, K2;
+    int ksplit;
+    float* part;
+    int ldp, pcol;
+};
+
 constexpr int PF_BM = 128, PF_BN = 128;
 constexpr int PF_XS = 32 * 1024;                      // one x slab: 4 token blocks x 8 slices x 1 KiB
 constexpr int PF_LDS = 2 * PF_XS;
@@ -57,7 +76,7 @@ struct WPre<S_F16> {
 
 // Rl[rp]: the row block (2*rp + h, clamped) whose row n this lane supplies
 template <int FMT>
-__device__ __forceinline__ void load_wpre(WPre<FMT>& r, const PrefillArgs& a, const int (&Rl)[2], int g, int lane)
+__device__ __forceinline__ void load_wpre(WPre<FMT>& r, const PfView& a, const int (&Rl)[2], int g, int lane)
 {
     const int n = lane & 15, kg = lane >> 5;
     if constexpr (FMT == S_F16) {
@@ -170,14 +189,23 @@ __device__ __forceinline__ void contract_step(f16v (&acc)[2][2], const h8 (&bf)[
 // FM: format of the first segment's weights (S_Q4, S_Q3 asymmetric; S_Q4S128; S_F16).  EXT: continue over a
 // second segment of fp16 tiles (B) with its own activations (t).
 template <int FM, bool EXT>
-__global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a)
+__global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs ga)
 {
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int wm = wave >> 1, wn = wave & 1;                      // this wavefront's 64 x 64 quadrant
-    const int ntn = (a.N + PF_BN - 1) / PF_BN, ntm = (a.M + PF_BM - 1) / PF_BM;
+    int ntn = 0;                                                  // column tiles of all members
+    for (int m = 0; m < ga.n; ++m) ntn += (ga.N[m] + PF_BN - 1) / PF_BN;
+    const int ntm = (ga.M + PF_BM - 1) / PF_BM;
     const int tile_id = blockIdx.x % (ntn * ntm), ks = blockIdx.x / (ntn * ntm);     // ks > 0 only with ksplit > 1
     const int m0 = (tile_id / ntn) * PF_BM;
-    const int R0 = (tile_id % ntn) * 8;
+    int nt = tile_id % ntn, mem = 0;                              // column tile within its member
+    while (mem + 1 < ga.n && nt >= (ga.N[mem] + PF_BN - 1) / PF_BN) {
+        nt -= (ga.N[mem] + PF_BN - 1) / PF_BN;
+        ++mem;
+    }
+    const PfView a{ga.x, ga.ldx, ga.w[mem], ga.w_scales[mem], ga.w_zeros[mem], ga.group, ga.x2[mem], ga.ldx2, ga.w2[mem],
+                   ga.y[mem], ga.ldy[mem], ga.M, ga.N[mem], ga.K1, ga.K2, ga.ksplit, ga.part, ga.ldp, ga.pcol[mem]};
+    const int R0 = nt * 8;
     const int nblk = a.N / 16;
     const int h = (lane >> 4) & 1;
     int Rl[2];                                                    // the row blocks this lane supplies rows of, clamped to valid ones
@@ -242,7 +270,7 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a)
                 for (int v = 0; v < 16; ++v) {
                     const int m = m0 + 64 * wm + 32 * mb + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
                     const int o = (R0 + 4 * wn) * 16 + 32 * rp + (lane & 31);
-                    if (m < a.M && o < a.N) a.part[((size_t)ks * a.M + m) * a.N + o] = acc[mb][rp][v];
+                    if (m < a.M && o < a.N) a.part[((size_t)ks * a.M + m) * a.ldp + a.pcol + o] = acc[mb][rp][v];
                 }
         return;
     }
@@ -272,7 +300,9 @@ static hipError_t launch_pf(const PrefillArgs& a, hipStream_t stream)
     auto kern = prefill_kernel<FM, EXT>;
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, PF_LDS);
     if (e != hipSuccess) return e;
-    const int ntn = (a.N + PF_BN - 1) / PF_BN, ntm = (a.M + PF_BM - 1) / PF_BM;
+    int ntn = 0;
+    for (int m = 0; m < a.n; ++m) ntn += (a.N[m] + PF_BN - 1) / PF_BN;
+    const int ntm = (a.M + PF_BM - 1) / PF_BM;
     hipLaunchKernelGGL(kern, dim3(ntn * ntm * (EXT ? 1 : a.ksplit)), dim3(256), PF_LDS, stream, a);
     return hipGetLastError();
 }

@@ -48,7 +48,7 @@ def run_linear_q_group(cases, x, r=None, ws=None):
         keep.append(t)
         ys.append(y)
         members.append(tuple(t) + (y, c.d_out))
-    ws = eora.new_workspace(M, c0.d_in, max(c.d_out for c in cases), r) if ws is None else ws
+    ws = eora.new_workspace(M, c0.d_in, max(c.d_out for c in cases), r, n_members=len(cases)) if ws is None else ws
     eora.linear_q_group(xd, members, M, c0.d_in, r, c0.w_bits, c0.group, c0.ab_bits, ws)
     torch.cuda.synchronize()
     return [y.cpu().numpy().reshape(M, c.d_out) for y, c in zip(ys, cases)]

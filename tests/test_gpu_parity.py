@@ -125,6 +125,8 @@ def test_config_shapes_fp16_factors(gpu, name, d_in, d_out, w_bits, M):
     (4, 16, 32, 3, 1024, (64, 16, 48, 32)),         # four members, three tokens
     (4, 16, 0, 2, 2048, (128, 64)),                 # adapter off
     (3, 16, 64, 8, 512, (64, 32)),                  # a shape the decode kernel does not take: members run in turn
+    (4, 16, 128, 200, 512, (192, 64, 144)),         # many tokens: the members' rows form one GEMM (ragged tiles)
+    (3, 16, 0, 130, 256, (16, 128)),                # the same with the adapter off
 ])
 def test_group_of_layers_sharing_x(gpu, w_bits, ab_bits, r, M, d_in, d_outs):
     """Layers that read the same x in one call (query/key/value, gate/up): every member equals the
@@ -136,7 +138,8 @@ def test_group_of_layers_sharing_x(gpu, w_bits, ab_bits, r, M, d_in, d_outs):
     ys = run_linear_q_group(cases, x)
     for c, y in zip(cases, ys):
         _check(y, c.oracle_y(x=x))
-        assert np.array_equal(y, run_linear_q(c, x=x))
+        if M < 128 or r == 0:                        # (with many tokens t is summed in a different split: not bit-identical)
+            assert np.array_equal(y, run_linear_q(c, x=x))
 
 
 def test_workspace_is_reusable_without_clearing(gpu):
