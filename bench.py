@@ -38,11 +38,15 @@ WORKLOADS = {
     "llama3-70b-layer-decode-sp24-bare-M1": dict(model="70b", w_bits=0, ab_bits=16, r=0, M=1, cfg=5),
     "llama3-70b-layer-decode-sp24-r128fp16-M64": dict(model="70b", w_bits=0, ab_bits=16, r=128, M=64, cfg=5),
 }
+# the paper's speed table is on a 70B model: the quantised layer at those shapes (not a BASELINE config)
+WORKLOADS["llama3-70b-layer-decode-w3g128-r128fp16-M1"] = dict(model="70b", w_bits=3, ab_bits=16, r=128, M=1, cfg=2)
+WORKLOADS["llama3-70b-layer-decode-w3g128-bare-M1"] = dict(model="70b", w_bits=3, ab_bits=16, r=0, M=1, cfg=2)
 # the same layers with the linears that read the same x sharing a launch (q/k/v and gate/up): four launches a step
 for _n in ("llama3-8b-layer-decode-w3g128-r128fp16-M1", "llama3-8b-layer-decode-w3g128-bare-M1",
            "llama3-8b-layer-decode-w4g128-r128fp16-M1", "llama3-8b-layer-decode-w4g128-r128q4-M1",
            "llama3-8b-layer-decode-w4g128-bare-M1", "llama3-8b-layer-prefill-w4g128-r256fp16-M2048",
-           "llama3-8b-layer-prefill-w4g128-bare-M2048"):
+           "llama3-8b-layer-prefill-w4g128-bare-M2048", "llama3-70b-layer-decode-w3g128-r128fp16-M1",
+           "llama3-70b-layer-decode-w3g128-bare-M1"):
     WORKLOADS[_n + "-grouped"] = dict(WORKLOADS[_n], grouped=True)
 GROUPS = (("q", "k", "v"), ("o",), ("gate", "up"), ("down",))
 for _r in (64, 256, 512):
