@@ -84,7 +84,7 @@ int pick_kcn(int M, int d_in)
 int pick_ksplit(int M, int d_in, int r)
 {
     if (r == 0) return 1;
-    const int tiles = ((M + 127) / 128) * ((r + 127) / 128), G = d_in / 128;
+    const int tiles = ((M + 127) / 128) * ((r + 255) / 256), G = d_in / 128;       // the GEMM kernel's tile is 128 x 256
     int want = (256 + tiles - 1) / tiles;
     want = want > 8 ? 8 : want;
     int ks = 1;

@@ -5,7 +5,7 @@
 // launch of the same kernel with A as the weight operand (fp16 M x r into scratch): recomputing it
 // per output tile would cost r / 128 times the backbone's MFMA work.
 //
-// Workgroup: 4 wavefronts (2 x 2), tile = 128 tokens x 128 output rows, contraction in steps of 128
+// Workgroup: 8 wavefronts (2 x 4), tile = 128 tokens x 256 output rows, contraction in steps of 128
 // (one quantisation group); each wavefront owns 64 tokens x 64 rows = 2 x 2 accumulator blocks of
 // v_mfma_f32_32x32x16_f16, the instruction with the highest sustained rate here (measured with
 // register-only loops: 2.2 PFLOP/s against 1.9 for the 16x16x32 form).  Its operand layout is:
@@ -26,8 +26,10 @@
 //     operand fragments (32 tokens x 16 columns = 1 KiB, one ds_read_b128 each; an XOR of the token
 //     slot with the slice number keeps both the scattered writes and the reads free of bank
 //     conflicts): one barrier per step.
-// Two workgroups share a compute unit (64 KiB LDS, at most 256 registers).  The epilogue transposes
-// through LDS so that y is written in 128-byte rows.
+//   - The two wavefronts of a SIMD (w and w + 4) run the two halves of a step, decode (VALU) and
+//     contraction (MFMA), in opposite order, so that the two pipes are busy at the same time.
+// One workgroup per compute unit (two wavefronts per SIMD, at most 256 registers).  The epilogue
+// transposes through LDS so that y is written in 128-byte rows.
 #include "segments.hpp"
 
 namespace eora {
@@ -53,9 +55,10 @@ struct PfView {
     int ldp, pcol;
 };
 
-constexpr int PF_BM = 128, PF_BN = 128;
+constexpr int PF_BM = 128, PF_BN = 256;
+constexpr int PF_NW = 8, PF_NT = PF_NW * 64;         // wavefronts: 2 (tokens) x 4 (rows)
 constexpr int PF_XS = 32 * 1024;                      // one x slab: 4 token blocks x 8 slices x 1 KiB
-constexpr int PF_LDS = 2 * PF_XS;
+constexpr int PF_LDS = PF_NW * 64 * 72 * 2;           // the epilogue's staging tiles need more than the two x slabs (64 KiB)
 
 __device__ __forceinline__ f16v mfma32(h8 a, h8 b, f16v c) { return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0); }
 
@@ -141,11 +144,12 @@ __device__ __forceinline__ void load_b_frags(h8 (&bf)[2][8], const void* __restr
 
 // x slab of one step: thread tid owns the 16-byte chunks c = tid + 256*i, i = 0..7; chunk c is token row
 // c / 16 of the tile and columns 8*(c % 16) .. +7 of the step (coalesced: 256 bytes per row).
-__device__ __forceinline__ void load_x(u4 (&v)[8], const _Float16* __restrict__ act, int ld, int M, int m0, int col0, int tid)
+constexpr int PF_XC = 2048 / PF_NT;                   // 16-byte chunks of the slab per thread
+__device__ __forceinline__ void load_x(u4 (&v)[PF_XC], const _Float16* __restrict__ act, int ld, int M, int m0, int col0, int tid)
 {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const int c = tid + 256 * i;
+    for (int i = 0; i < PF_XC; ++i) {
+        const int c = tid + PF_NT * i;
         int row = m0 + (c >> 4);
         row = row < M ? row : M - 1;                  // rows beyond M re-read the last row; never stored
         v[i] = *(const u4*)(act + (size_t)row * ld + col0 + 8 * (c & 15));
@@ -159,11 +163,11 @@ __device__ __forceinline__ void load_x(u4 (&v)[8], const _Float16* __restrict__ 
 // that differ in token, then hit 16 different bank groups.
 __device__ __forceinline__ int x_slot(int tb, int f, int kg, int tr) { return ((tb * 8 + f) * 64 + 32 * kg + (tr ^ (2 * f + kg))) * 16; }
 
-__device__ __forceinline__ void store_x(const u4 (&v)[8], unsigned char* buf, bool quarter_major, int tid)
+__device__ __forceinline__ void store_x(const u4 (&v)[PF_XC], unsigned char* buf, bool quarter_major, int tid)
 {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const int c = tid + 256 * i;
+    for (int i = 0; i < PF_XC; ++i) {
+        const int c = tid + PF_NT * i;
         const int row = c >> 4, kc = c & 15;
         const int f = quarter_major ? ((kc >> 3) << 2) | (kc & 3) : kc >> 1;
         const int kg = quarter_major ? (kc >> 2) & 1 : kc & 1;
@@ -189,10 +193,10 @@ __device__ __forceinline__ void contract_step(f16v (&acc)[2][2], const h8 (&bf)[
 // FM: format of the first segment's weights (S_Q4, S_Q3 asymmetric; S_Q4S128; S_F16).  EXT: continue over a
 // second segment of fp16 tiles (B) with its own activations (t).
 template <int FM, bool EXT>
-__global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs ga)
+__global__ __launch_bounds__(PF_NT, 2) void prefill_kernel(PrefillArgs ga)
 {
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int wm = wave >> 1, wn = wave & 1;                      // this wavefront's 64 x 64 quadrant
+    const int wm = wave >> 2, wn = wave & 3;                      // this wavefront's 64 x 64 block of the 128 x 256 tile
     int ntn = 0;                                                  // column tiles of all members
     for (int m = 0; m < ga.n; ++m) ntn += (ga.N[m] + PF_BN - 1) / PF_BN;
     const int ntm = (ga.M + PF_BM - 1) / PF_BM;
@@ -205,7 +209,7 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs ga)
     }
     const PfView a{ga.x, ga.ldx, ga.w[mem], ga.w_scales[mem], ga.w_zeros[mem], ga.group, ga.x2[mem], ga.ldx2, ga.w2[mem],
                    ga.y[mem], ga.ldy[mem], ga.M, ga.N[mem], ga.K1, ga.K2, ga.ksplit, ga.part, ga.ldp, ga.pcol[mem]};
-    const int R0 = nt * 8;
+    const int R0 = nt * (PF_BN / 16);
     const int nblk = a.N / 16;
     const int h = (lane >> 4) & 1;
     int Rl[2];                                                    // the row blocks this lane supplies rows of, clamped to valid ones
@@ -227,38 +231,83 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs ga)
             for (int q = 0; q < 16; ++q) acc[i][k][q] = 0.f;
 
     // x slab of step s into registers (steps past the end re-read the last one; never stored)
-    auto fetch_x = [&](u4 (&v)[8], int s) {
+    auto fetch_x = [&](u4 (&v)[PF_XC], int s) {
         s = s < GT ? s : GT - 1;
         if (EXT && s >= G1) load_x(v, a.x2, a.ldx2, a.M, m0, (s - G1) * 128, tid);
         else load_x(v, a.x, a.ldx, a.M, m0, s * 128, tid);
     };
-    u4 xr[8];
-    WPre<FM> wp;
+    u4 xr[PF_XC];
+    WPre<W16 ? S_Q4 : FM> wp;                                     // (unused for fp16 tiles)
     fetch_x(xr, sb);
-    load_wpre<FM>(wp, a, Rl, sb, lane);
+    if constexpr (!W16) load_wpre<FM>(wp, a, Rl, sb, lane);
     store_x(xr, buf0, !W16, tid);
     fetch_x(xr, sb + 1);                                          // xr always holds the slab of the step after the one in LDS
     __syncthreads();
 
-    for (int s = sb; s < GT; ++s) {
-        unsigned char* const cur = ((s - sb) & 1) ? buf1 : buf0;
-        unsigned char* const nxt = ((s - sb) & 1) ? buf0 : buf1;
-        h8 bf[2][8];
+#ifdef EORA_TIMELINE
+    long long tl[5] = {0, 0, 0, 0, 0}, tl0 = clock64(), tlstart = tl0;
+#define PF_STAMP(i) do { const long long now = clock64(); tl[i] += now - tl0; tl0 = now; } while (0)
+#else
+#define PF_STAMP(i) do { } while (0)
+#endif
+    // Operands of step s into bf: decode of the prefetched tiles (and the request for the following
+    // step's), or B's tiles for the second segment.  Steps past the end repeat the last one; never used.
+    h8 bf[2][8];
+    auto prep = [&](int s) {
+        s = s < GT ? s : GT - 1;
         if (EXT && s >= G1) {
             load_b_frags(bf, a.w2, a.K2, Rl, s - G1, lane);
+        } else if constexpr (W16) {
+            load_b_frags(bf, a.w, a.K1, Rl, s, lane);             // fp16 tiles are operands as they are: no prefetch copy
         } else {
-            decode_wpre<FM>(wp, bf);
-            load_wpre<FM>(wp, a, Rl, s + 1 < (EXT ? G1 : GT) ? s + 1 : s, lane);     // past the end: re-read, never used
+            if constexpr (!W16) {
+                decode_wpre<FM>(wp, bf);
+                const int last1 = (EXT ? G1 : GT) - 1;
+                load_wpre<FM>(wp, a, Rl, s + 1 < last1 ? s + 1 : last1, lane);
+            }
         }
-        // nothing crosses this point: left alone, the scheduler sinks the requests for the next step's
-        // weights below the MFMAs, and the next step then starts by waiting for them
-        __builtin_amdgcn_sched_barrier(0);
+    };
+    // The two wavefronts that share a SIMD (w and w + 4) run the two halves of a step in opposite order,
+    // so that one decodes (VALU) while the other contracts (MFMA): wavefronts 0..3 decode step s at the
+    // top of iteration s, wavefronts 4..7 decoded it at the bottom of iteration s - 1.  Measured with
+    // both in the same order: the second decoder waits for the first, and its MFMAs then run alone.
+    const bool late = wave >= PF_NW / 2;
+    if (late) prep(sb);
+    for (int s = sb; s < GT; ++s) {
+        PF_STAMP(4);
+        unsigned char* const cur = ((s - sb) & 1) ? buf1 : buf0;
+        unsigned char* const nxt = ((s - sb) & 1) ? buf0 : buf1;
+        if (!late) {
+            prep(s);
+            // nothing crosses this point: left alone, the scheduler sinks the requests for the next step's
+            // weights below the MFMAs, and the next step then starts by waiting for them
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        PF_STAMP(0);
         contract_step(acc, bf, cur, wm, lane);
+#ifdef EORA_TIMELINE
+        __builtin_amdgcn_sched_barrier(0);
+        PF_STAMP(1);
+#endif
         // the next step's slab goes to the other buffer (free since the barrier of the step before)
         store_x(xr, nxt, !(W16 || (EXT && s + 1 >= G1)), tid);
         fetch_x(xr, s + 2);
+        if (late) {
+            __builtin_amdgcn_sched_barrier(0);
+            prep(s + 1);
+        }
+#ifdef EORA_TIMELINE
+        __builtin_amdgcn_sched_barrier(0);
+        PF_STAMP(2);
+#endif
         __syncthreads();
+        PF_STAMP(3);
     }
+#ifdef EORA_TIMELINE
+    if ((blockIdx.x == 0 || blockIdx.x == 700) && lane == 0)
+        printf("wg %d wave %d: decode+wload %lld  contract %lld  storex+fetch %lld  barrier %lld  loop-top %lld  total %lld (clock64 ticks, %d steps)\n",
+               (int)blockIdx.x, wave, tl[0], tl[1], tl[2], tl[3], tl[4], clock64() - tlstart, GT - sb);
+#endif
 
     // ---- split contraction: this part's fp32 tile, 128-byte rows straight from the accumulators ------
     if (!EXT && a.ksplit > 1) {
@@ -303,7 +352,7 @@ static hipError_t launch_pf(const PrefillArgs& a, hipStream_t stream)
     int ntn = 0;
     for (int m = 0; m < a.n; ++m) ntn += (a.N[m] + PF_BN - 1) / PF_BN;
     const int ntm = (a.M + PF_BM - 1) / PF_BM;
-    hipLaunchKernelGGL(kern, dim3(ntn * ntm * (EXT ? 1 : a.ksplit)), dim3(256), PF_LDS, stream, a);
+    hipLaunchKernelGGL(kern, dim3(ntn * ntm * (EXT ? 1 : a.ksplit)), dim3(PF_NT), PF_LDS, stream, a);
     return hipGetLastError();
 }
 
