@@ -5,22 +5,21 @@
 // launch of the same kernel with A as the weight operand (fp16 M x r into scratch): recomputing it
 // per output tile would cost r / 128 times the backbone's MFMA work.
 //
-// Workgroup: 8 wavefronts (2 x 4), tile = 128 tokens x 256 output rows, contraction in steps of 128
-// (one quantisation group); each wavefront owns 64 tokens x 64 rows = 2 x 2 accumulator blocks of
+// Workgroup: 8 wavefronts, tile = 128 tokens x 256 output rows, contraction in steps of 128 (one
+// quantisation group); each wavefront owns all 128 tokens x 32 rows = 4 accumulator blocks of
 // v_mfma_f32_32x32x16_f16, the instruction with the highest sustained rate here (measured with
 // register-only loops: 2.2 PFLOP/s against 1.9 for the 16x16x32 form).  Its operand layout is:
 // lane l holds 8 consecutive k (8*(l/32) ..) of token / output row l%32; result register v of lane l
 // is token 8*(v/4) + 4*(l/32) + v%4, output row l%32 (checked on the device against a host matmul).
 //   - Weights never touch LDS.  The stored tiles (16 rows x 128 columns, lane (n, j) = row n, columns
 //     32j .. 32j+31, tiles.hpp) feed this MFMA as well: lane l = n + 16*h + 32*kg of the wavefront loads,
-//     for jp = 0, 1, the 16 bytes of stored lane (n, 2*jp + kg) of the tile of row block 2*rp + h; word
+//     for jp = 0, 1, the 16 bytes of stored lane (n, 2*jp + kg) of the tile of its row block h; word
 //     t of that load decodes to the operand of the k-slice (jp, t): columns 32*(2jp+kg) + 8t .. +7 of
-//     output row 32*rp + 16*h + n.  Every wavefront loads its own four tiles one step ahead, decodes
-//     them to the exact integers code - zero and multiplies by the fp16 group scale (one fp16
-//     rounding of scale*(code-zero), relative error <= 2^-11 per weight; scaling the accumulators per
-//     group instead would cost as many VALU cycles as the group's MFMAs).  The two wavefronts that
-//     share row blocks decode them twice; in exchange LDS carries only x, half the fragment traffic
-//     of staging both operands.
+//     output row 16*h + n of the wavefront's 32.  Every wavefront loads its own two tiles one step
+//     ahead, decodes them to the exact integers code - zero and multiplies by the fp16 group scale
+//     (one fp16 rounding of scale*(code-zero), relative error <= 2^-11 per weight; scaling the
+//     accumulators per group instead would cost as many VALU cycles as the group's MFMAs).  Every
+//     weight is decoded exactly once per workgroup, and LDS carries only x.
 //   - x: the 128 x 128 slab is read with coalesced 16-byte loads (256 bytes per token row) into
 //     registers two steps ahead and written one step ahead to the other of two LDS buffers as MFMA
 //     operand fragments (32 tokens x 16 columns = 1 KiB, one ds_read_b128 each; an XOR of the token
@@ -58,7 +57,7 @@ struct PfView {
 constexpr int PF_BM = 128, PF_BN = 256;
 constexpr int PF_NW = 8, PF_NT = PF_NW * 64;         // wavefronts: 2 (tokens) x 4 (rows)
 constexpr int PF_XS = 32 * 1024;                      // one x slab: 4 token blocks x 8 slices x 1 KiB
-constexpr int PF_LDS = PF_NW * 64 * 72 * 2;           // the epilogue's staging tiles need more than the two x slabs (64 KiB)
+constexpr int PF_LDS = PF_NW * 128 * 40 * 2;          // the epilogue's staging tiles (80 KiB) need more than the two x slabs (64 KiB)
 
 __device__ __forceinline__ f16v mfma32(h8 a, h8 b, f16v c) { return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0); }
 
@@ -67,79 +66,56 @@ __device__ __forceinline__ f16v mfma32(h8 a, h8 b, f16v c) { return __builtin_am
 // time would make the wavefront wait for the request it has just issued)
 template <int FMT>
 struct WPre {
-    uint32_t w[2][2][Fmt<FMT>::WORDS];                // [row-block pair rp][jp]
-    uint32_t zraw[2];                                 // the word that holds the group's zero-point nibble
-    uint32_t sraw[2];                                 // fp16 scale bits, zero-extended
+    uint32_t w[2][Fmt<FMT>::WORDS];                   // [jp]
+    uint32_t zraw;                                    // the word that holds the group's zero-point nibble
+    uint32_t sraw;                                    // fp16 scale bits, zero-extended
     int zshift;                                       // 4 * (group index % 8)
 };
 template <>
 struct WPre<S_F16> {
-    u4 v[2][8];                                       // [rp][slice]: four tiles of 32 columns = eight slices of 16
+    u4 v[8];                                          // [slice]: four tiles of 32 columns = eight slices of 16
 };
 
-// Rl[rp]: the row block (2*rp + h, clamped) whose row n this lane supplies
+// Rl: the row block (2*wn + h, clamped) whose row n this lane supplies
 template <int FMT>
-__device__ __forceinline__ void load_wpre(WPre<FMT>& r, const PfView& a, const int (&Rl)[2], int g, int lane)
+__device__ __forceinline__ void load_wpre(WPre<FMT>& r, const PfView& a, int Rl, int g, int lane)
 {
     const int n = lane & 15, kg = lane >> 5;
-    if constexpr (FMT == S_F16) {
+    constexpr int WORDS = Fmt<FMT>::WORDS;
+    const int G = a.K1 / 128;
+    const int NG = Fmt<FMT>::ASYM ? a.K1 / a.group : G, grp = Fmt<FMT>::ASYM ? (g * 128) / a.group : g;
+    r.zshift = 4 * (grp & 7);
+    const uint32_t* tile = (const uint32_t*)a.w + ((size_t)Rl * G + g) * 64 * WORDS;
 #pragma unroll
-        for (int rp = 0; rp < 2; ++rp) {
-            const u4* p = (const u4*)a.w + ((size_t)Rl[rp] * (a.K1 / 32) + 4 * g) * 64 + n;
+    for (int jp = 0; jp < 2; ++jp) load_words<WORDS>(r.w[jp], tile + (16 * (2 * jp + kg) + n) * WORDS);
+    const size_t row = (size_t)Rl * 16 + n;
+    r.sraw = ((const uint16_t*)a.w_scales)[row * NG + grp];
+    if constexpr (Fmt<FMT>::ASYM) r.zraw = a.w_zeros[row * ((NG + 7) / 8) + (grp >> 3)];
+}
+
+// decode to operands bf[slice], slice = 4*jp + t, scale folded in fp16
+template <int FMT>
+__device__ __forceinline__ void decode_wpre(const WPre<FMT>& r, h8 (&bf)[8])
+{
+    const uint32_t z = Fmt<FMT>::ASYM ? (r.zraw >> r.zshift) & 0xFu : 8u;
+    const _Float16 sc = __builtin_bit_cast(_Float16, (uint16_t)r.sraw);
+    const h8 s = {sc, sc, sc, sc, sc, sc, sc, sc};
 #pragma unroll
-            for (int f = 0; f < 8; ++f) r.v[rp][f] = p[(f >> 1) * 64 + 16 * (2 * (f & 1) + kg)];
-        }
-    } else {
-        constexpr int WORDS = Fmt<FMT>::WORDS;
-        const int G = a.K1 / 128;
-        const int NG = Fmt<FMT>::ASYM ? a.K1 / a.group : G, grp = Fmt<FMT>::ASYM ? (g * 128) / a.group : g;
-        r.zshift = 4 * (grp & 7);
+    for (int jp = 0; jp < 2; ++jp) {
+        h8 b[4];
+        decode_tile<FMT>(r.w[jp], z, b);
 #pragma unroll
-        for (int rp = 0; rp < 2; ++rp) {
-            const uint32_t* tile = (const uint32_t*)a.w + ((size_t)Rl[rp] * G + g) * 64 * WORDS;
-#pragma unroll
-            for (int jp = 0; jp < 2; ++jp) load_words<WORDS>(r.w[rp][jp], tile + (16 * (2 * jp + kg) + n) * WORDS);
-            const size_t row = (size_t)Rl[rp] * 16 + n;
-            r.sraw[rp] = ((const uint16_t*)a.w_scales)[row * NG + grp];
-            if constexpr (Fmt<FMT>::ASYM) r.zraw[rp] = a.w_zeros[row * ((NG + 7) / 8) + (grp >> 3)];
-        }
+        for (int t = 0; t < 4; ++t) bf[4 * jp + t] = b[t] * s;
     }
 }
 
-// decode to operands bf[rp][slice], slice = 4*jp + t, scale folded in fp16
-template <int FMT>
-__device__ __forceinline__ void decode_wpre(const WPre<FMT>& r, h8 (&bf)[2][8])
-{
-#pragma unroll
-    for (int rp = 0; rp < 2; ++rp) {
-        if constexpr (FMT == S_F16) {
-#pragma unroll
-            for (int f = 0; f < 8; ++f) bf[rp][f] = __builtin_bit_cast(h8, r.v[rp][f]);
-        } else {
-            const uint32_t z = Fmt<FMT>::ASYM ? (r.zraw[rp] >> r.zshift) & 0xFu : 8u;
-            const _Float16 sc = __builtin_bit_cast(_Float16, (uint16_t)r.sraw[rp]);
-            const h8 s = {sc, sc, sc, sc, sc, sc, sc, sc};
-#pragma unroll
-            for (int jp = 0; jp < 2; ++jp) {
-                h8 b[4];
-                decode_tile<FMT>(r.w[rp][jp], z, b);
-#pragma unroll
-                for (int t = 0; t < 4; ++t) bf[rp][4 * jp + t] = b[t] * s;
-            }
-        }
-    }
-}
-
-// second segment: B's fp16 tiles straight into operands (two steps at most: no prefetch)
-__device__ __forceinline__ void load_b_frags(h8 (&bf)[2][8], const void* __restrict__ tiles, int K, const int (&Rl)[2], int step, int lane)
+// fp16 tiles (A for the down-projection launch, B in the second segment) straight into operands
+__device__ __forceinline__ void load_b_frags(h8 (&bf)[8], const void* __restrict__ tiles, int K, int Rl, int step, int lane)
 {
     const int n = lane & 15, kg = lane >> 5;
+    const u4* p = (const u4*)tiles + ((size_t)Rl * (K / 32) + 4 * step) * 64 + n;
 #pragma unroll
-    for (int rp = 0; rp < 2; ++rp) {
-        const u4* p = (const u4*)tiles + ((size_t)Rl[rp] * (K / 32) + 4 * step) * 64 + n;
-#pragma unroll
-        for (int f = 0; f < 8; ++f) bf[rp][f] = __builtin_bit_cast(h8, p[(f >> 1) * 64 + 16 * (2 * (f & 1) + kg)]);
-    }
+    for (int f = 0; f < 8; ++f) bf[f] = __builtin_bit_cast(h8, p[(f >> 1) * 64 + 16 * (2 * (f & 1) + kg)]);
 }
 
 // x slab of one step: thread tid owns the 16-byte chunks c = tid + 256*i, i = 0..7; chunk c is token row
@@ -175,18 +151,16 @@ __device__ __forceinline__ void store_x(const u4 (&v)[PF_XC], unsigned char* buf
     }
 }
 
-__device__ __forceinline__ void contract_step(f16v (&acc)[2][2], const h8 (&bf)[2][8], const unsigned char* buf, int wm, int lane)
+__device__ __forceinline__ void contract_step(f16v (&acc)[4], const h8 (&bf)[8], const unsigned char* buf, int lane)
 {
     const int tr = lane & 31, kg = lane >> 5;
 #pragma unroll
     for (int f = 0; f < 8; ++f) {
-        h8 af[2];
+        h8 af[4];
 #pragma unroll
-        for (int mb = 0; mb < 2; ++mb) af[mb] = *(const h8*)(buf + x_slot(2 * wm + mb, f, kg, tr));
+        for (int mb = 0; mb < 4; ++mb) af[mb] = *(const h8*)(buf + x_slot(mb, f, kg, tr));
 #pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-            for (int rp = 0; rp < 2; ++rp) acc[mb][rp] = mfma32(af[mb], bf[rp][f], acc[mb][rp]);
+        for (int mb = 0; mb < 4; ++mb) acc[mb] = mfma32(af[mb], bf[f], acc[mb]);
     }
 }
 
@@ -196,7 +170,7 @@ template <int FM, bool EXT>
 __global__ __launch_bounds__(PF_NT, 2) void prefill_kernel(PrefillArgs ga)
 {
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int wm = wave >> 2, wn = wave & 3;                      // this wavefront's 64 x 64 block of the 128 x 256 tile
+    const int wn = wave;                                          // this wavefront's 128 tokens x 32 rows of the 128 x 256 tile
     int ntn = 0;                                                  // column tiles of all members
     for (int m = 0; m < ga.n; ++m) ntn += (ga.N[m] + PF_BN - 1) / PF_BN;
     const int ntm = (ga.M + PF_BM - 1) / PF_BM;
@@ -212,9 +186,7 @@ __global__ __launch_bounds__(PF_NT, 2) void prefill_kernel(PrefillArgs ga)
     const int R0 = nt * (PF_BN / 16);
     const int nblk = a.N / 16;
     const int h = (lane >> 4) & 1;
-    int Rl[2];                                                    // the row blocks this lane supplies rows of, clamped to valid ones
-#pragma unroll
-    for (int rp = 0; rp < 2; ++rp) Rl[rp] = R0 + 4 * wn + 2 * rp + h < nblk ? R0 + 4 * wn + 2 * rp + h : nblk - 1;
+    const int Rl = R0 + 2 * wn + h < nblk ? R0 + 2 * wn + h : nblk - 1;   // the row block this lane supplies a row of, clamped to a valid one
     const int G1 = a.K1 / 128, G2 = EXT ? a.K2 / 128 : 0;
     const int sb = EXT ? 0 : ks * (G1 / a.ksplit);               // this workgroup's steps: [sb, GT)
     const int GT = EXT ? G1 + G2 : sb + G1 / a.ksplit;
@@ -222,13 +194,11 @@ __global__ __launch_bounds__(PF_NT, 2) void prefill_kernel(PrefillArgs ga)
     unsigned char* const buf0 = eora_smem;
     unsigned char* const buf1 = eora_smem + PF_XS;
 
-    f16v acc[2][2];
+    f16v acc[4];                                                  // token blocks of 32
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int k = 0; k < 2; ++k)
-#pragma unroll
-            for (int q = 0; q < 16; ++q) acc[i][k][q] = 0.f;
+        for (int q = 0; q < 16; ++q) acc[i][q] = 0.f;
 
     // x slab of step s into registers (steps past the end re-read the last one; never stored)
     auto fetch_x = [&](u4 (&v)[PF_XC], int s) {
@@ -252,7 +222,7 @@ __global__ __launch_bounds__(PF_NT, 2) void prefill_kernel(PrefillArgs ga)
 #endif
     // Operands of step s into bf: decode of the prefetched tiles (and the request for the following
     // step's), or B's tiles for the second segment.  Steps past the end repeat the last one; never used.
-    h8 bf[2][8];
+    h8 bf[8];
     auto prep = [&](int s) {
         s = s < GT ? s : GT - 1;
         if (EXT && s >= G1) {
@@ -284,7 +254,7 @@ __global__ __launch_bounds__(PF_NT, 2) void prefill_kernel(PrefillArgs ga)
             __builtin_amdgcn_sched_barrier(0);
         }
         PF_STAMP(0);
-        contract_step(acc, bf, cur, wm, lane);
+        contract_step(acc, bf, cur, lane);
 #ifdef EORA_TIMELINE
         __builtin_amdgcn_sched_barrier(0);
         PF_STAMP(1);
@@ -312,32 +282,28 @@ __global__ __launch_bounds__(PF_NT, 2) void prefill_kernel(PrefillArgs ga)
     // ---- split contraction: this part's fp32 tile, 128-byte rows straight from the accumulators ------
     if (!EXT && a.ksplit > 1) {
 #pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
+        for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
-            for (int rp = 0; rp < 2; ++rp)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int m = m0 + 64 * wm + 32 * mb + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-                    const int o = (R0 + 4 * wn) * 16 + 32 * rp + (lane & 31);
-                    if (m < a.M && o < a.N) a.part[((size_t)ks * a.M + m) * a.ldp + a.pcol + o] = acc[mb][rp][v];
-                }
+            for (int v = 0; v < 16; ++v) {
+                const int m = m0 + 32 * mb + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+                const int o = (R0 + 2 * wn) * 16 + (lane & 31);
+                if (m < a.M && o < a.N) a.part[((size_t)ks * a.M + m) * a.ldp + a.pcol + o] = acc[mb][v];
+            }
         return;
     }
     // ---- epilogue: fp32 -> fp16, transpose through LDS, 128-byte row stores ----------------------------
-    constexpr int TS = 72;                                        // halves per token row in the staging tile (64 + pad)
-    _Float16* tile = (_Float16*)eora_smem + wave * 64 * TS;
+    constexpr int TS = 40;                                        // halves per token row in the staging tile (32 + pad)
+    _Float16* tile = (_Float16*)eora_smem + wave * 128 * TS;
 #pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
+    for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
-        for (int rp = 0; rp < 2; ++rp)
-#pragma unroll
-            for (int v = 0; v < 16; ++v)
-                tile[(32 * mb + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3)) * TS + 32 * rp + (lane & 31)] = (_Float16)acc[mb][rp][v];
+        for (int v = 0; v < 16; ++v)
+            tile[(32 * mb + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3)) * TS + (lane & 31)] = (_Float16)acc[mb][v];
     __syncthreads();
 #pragma unroll
     for (int it = 0; it < 8; ++it) {
-        const int tok = 8 * it + (lane >> 3), chunk = lane & 7;
-        const int m = m0 + 64 * wm + tok, o = (R0 + 4 * wn) * 16 + chunk * 8;
+        const int tok = 16 * it + (lane >> 2), chunk = lane & 3;      // 64-byte rows: four 16-byte chunks
+        const int m = m0 + tok, o = (R0 + 2 * wn) * 16 + chunk * 8;
         const u4 v = *(const u4*)(tile + tok * TS + chunk * 8);
         if (m < a.M && o < a.N) *(u4*)((_Float16*)a.y + (size_t)m * a.ldy + o) = v;
     }
