@@ -222,6 +222,35 @@ def test_linear_sp24_ragged_k_and_determinism(gpu):
     assert np.array_equal(y, run_linear_sp24(c))
 
 
+@pytest.mark.parametrize("w_bits,ab_bits,r,M,d_in,d_out", [
+    (3, 16, 128, 1, 14336, 4096),      # config 2, the down projection: the seven-wavefront instantiation
+    (3, 16, 128, 2, 14336, 1024),      # the same contraction length with two tokens (fourteen wavefronts)
+    (4, 4, 64, 1, 4096, 1024),         # config 3: 4-bit factors, rank 64 (64-column tiles of B)
+    (4, 4, 512, 1, 4096, 1024),        # config 3: rank 512 (256 producer units)
+    (4, 4, 256, 8, 4096, 1024),        # config 3 at eight tokens
+    (4, 16, 128, 1, 8192, 1024),       # 70B-shaped quantised layers: eight wavefronts
+    (3, 16, 128, 1, 28672, 512),       # and the 28672-long contraction
+    (4, 16, 128, 4, 8192, 256),        # four tokens
+])
+def test_more_config_shapes(gpu, w_bits, ab_bits, r, M, d_in, d_out):
+    """Full contraction lengths of the configured layers that the other tests do not reach (every
+    instantiation of the decode kernel the benchmark workloads launch)."""
+    import synth
+    from tests.cases import QCase
+    from tests.gpu_util import run_linear_q
+    c = QCase(synth.seed_for(3, d_in // 512 + r + M), d_in, d_out, M, r, w_bits, ab_bits=ab_bits, packer=gpu)
+    _check(run_linear_q(c), c.oracle_y())
+
+
+def test_config5_shape_long_contraction(gpu):
+    """BASELINE config 5, the 28672-long contraction of the 70B-shaped down projection (1024 of its rows)."""
+    import synth
+    from tests.cases import SparseCase
+    from tests.gpu_util import run_linear_sp24
+    c = SparseCase(synth.seed_for(5, 6), 28672, 1024, 1, 128, packer=gpu)
+    _check(run_linear_sp24(c), c.oracle_y())
+
+
 @pytest.mark.parametrize("M", [1, 64])
 def test_config5_shape_k_projection(gpu, M):
     """BASELINE config 5, the 8192 -> 1024 linear of a 70B-shaped layer at full size."""
