@@ -72,7 +72,9 @@ int factor_formats(int r, int ab_bits, int* fa, int* fe)
 // a divisor of the number of 128-wide k-tiles
 int pick_kcn(int M, int d_in)
 {
-    const int cap = M <= 4 ? MAX_KCN : (M <= 8 ? 4 : 2);
+    // (token blocks) x kcn <= 32: the partials' region is sized for that
+    const int yblocks = ((M < CHUNK_TOKENS ? M : CHUNK_TOKENS) + 15) / 16;
+    const int cap = 32 / yblocks < MAX_KCN ? 32 / yblocks : MAX_KCN;
     int kcn = 1;
     for (int c = 2; c <= cap; ++c)
         if ((d_in / 128) % c == 0) kcn = c;

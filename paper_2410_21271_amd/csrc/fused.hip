@@ -17,9 +17,10 @@
 // The low-rank path is folded into the same launch and the same accumulators (the paper, Sec. 4.5
 // and App. A.6, fuses only B's product and leaves x.A^T to a separate launch):
 //   phase A  t = x.A^T is cut into units (16 rows of A) x (one of kcn ranges of k-tiles).  Unit u
-//            belongs to workgroup u (workgroups are dispatched in index order, and an owner runs its
-//            units before anything else and never waits, so no owner can be starved by a waiter).
-//            The owner writes its fp32 partial to scratch and then publishes flag[u] = epoch + 1.
+//            belongs to workgroup u of the token block, a producer that owns no output rows
+//            (workgroups are dispatched in index order and a producer never waits, so no producer
+//            can be starved by a waiter).  It writes its fp32 partial to scratch and then publishes
+//            flag[u] = epoch + 1.
 //   phase W  backbone tiles of the strip (independent of t; hides phase A's latency).
 //   phase B  one wavefront polls the flags (bounded), then the wavefronts that own tiles of B add
 //            the kcn partials in a fixed order to get their slice of t (fp32), split it into a high
@@ -45,8 +46,12 @@ __global__ __launch_bounds__(NW * 64) void fused_kernel(FusedArgs a)
     const int m_blk = 16 * yb;               // first token of this block
     const int mt = a.M - m_blk < 16 ? a.M - m_blk : 16;      // tokens in this block
     const bool row_ok = n < mt;              // lane feeds token row n of the block as the activation operand
-    const int R0 = blockIdx.x * RB;
     constexpr bool LOWRANK = FA != S_NONE;
+    // The first `units` workgroups of a token block are PRODUCERS: one unit of t = x.A^T each, no output
+    // rows, so nothing but the consumers waits on them; the others own a strip of RB row blocks.
+    const int units = LOWRANK ? (a.r / 16) * a.kcn : 0;
+    const bool producer = (int)blockIdx.x < units;
+    const int R0 = producer ? 0 : ((int)blockIdx.x - units) * RB;
 
     // ---- requests, small operands first ------------------------------------------------------
     const int ldxs = a.d_in + 32;            // LDS row stride (halves): 64 bytes of padding against bank conflicts
@@ -67,7 +72,7 @@ __global__ __launch_bounds__(NW * 64) void fused_kernel(FusedArgs a)
     const int Q = (bb.G + 3) / 4;
     constexpr int PDQ = RB == 1 ? 2 : 1;     // quads of weight loads in flight per wavefront
     Quad<FM, RB> qbuf[PDQ];
-    const int nq = wave < Q ? (Q - wave + NW - 1) / NW : 0;
+    const int nq = (!producer && wave < Q) ? (Q - wave + NW - 1) / NW : 0;
 #pragma unroll
     for (int u = 0; u < PDQ; ++u)
         if (u < nq) load_quad_meta<FM, RB>(qbuf[u], bb, R0, wave + u * NW, lane);
@@ -76,7 +81,7 @@ __global__ __launch_bounds__(NW * 64) void fused_kernel(FusedArgs a)
     const Factor fb{(const uint32_t*)a.B, a.B_scales, LOWRANK ? a.r / Fmt<LOWRANK ? FE : S_F16>::KT : 0};
     FTile<LOWRANK ? FE : S_F16> bpre[RB];
     if constexpr (LOWRANK) {
-        if (wave < fb.ntk) {
+        if (!producer && wave < fb.ntk) {
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb) load_ftile<FE>(bpre[rb], fb, R0 + rb, wave, lane);
         }
@@ -111,11 +116,11 @@ __global__ __launch_bounds__(NW * 64) void fused_kernel(FusedArgs a)
     if constexpr (LOWRANK) {
         constexpr int KTA = Fmt<FA>::KT;
         const int NRB = a.r / 16;
-        const int units = NRB * a.kcn;
         const Factor fa{(const uint32_t*)a.A, a.A_scales, a.d_in / KTA};
         const int tiles_per_chunk = fa.ntk / a.kcn;
         uint32_t* flags = a.hdr + HDR_FLAGS0 + HDR_FLAGS_PER_BLOCK * yb;
-        for (int u = blockIdx.x; u < units; u += gridDim.x) {
+        if (producer) {
+            const int u = blockIdx.x;
             const int rho = u % NRB, kc = u / NRB;
             const f4 part = run_factor_a<FA, NW, XLDS>(fa, rho, kc * tiles_per_chunk, (kc + 1) * tiles_per_chunk, wave, lane,
                                                  act, n, row_ok);
@@ -136,10 +141,16 @@ __global__ __launch_bounds__(NW * 64) void fused_kernel(FusedArgs a)
                 asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
                 if (lane == 0) __hip_atomic_store(&flags[u], epoch + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
-            __syncthreads();
+            if (threadIdx.x == 0) check_in_finish(ci, a.hdr, gridDim.x * gridDim.y);
+            return;
         }
     }
 
+    // a first look at the flags, requested now and examined after the backbone
+    uint32_t early = 0;
+    if constexpr (LOWRANK) {
+        if (wave == 0) early = ld_relaxed(a.hdr + HDR_FLAGS0 + HDR_FLAGS_PER_BLOCK * yb + (lane < units ? lane : units - 1));
+    }
     // ---- phase W: backbone -----------------------------------------------------------------------
     f4 acc[RB];
 #pragma unroll
@@ -162,11 +173,10 @@ __global__ __launch_bounds__(NW * 64) void fused_kernel(FusedArgs a)
 
     // ---- phase B: += t.B^T -----------------------------------------------------------------------
     if constexpr (LOWRANK) {
-        const int units = (a.r / 16) * a.kcn;
         const uint32_t* flags = a.hdr + HDR_FLAGS0 + HDR_FLAGS_PER_BLOCK * yb;
         if (wave == 0) {
-            bool ok = false;
-            for (int spins = 0; spins <= a.spin_limit; ++spins) {
+            bool ok = units <= 64 && __all(early == epoch + 1);
+            for (int spins = 0; !ok && spins <= a.spin_limit; ++spins) {
                 bool all = true;
                 for (int f = lane; f < units; f += 64) all = all && (ld_relaxed(&flags[f]) == epoch + 1);
                 if (__all(all)) { ok = true; break; }
@@ -192,9 +202,21 @@ __global__ __launch_bounds__(NW * 64) void fused_kernel(FusedArgs a)
                     f4 v0 = {0.f, 0.f, 0.f, 0.f}, v1 = {0.f, 0.f, 0.f, 0.f};
                     if (row_ok) {
                         const float* p = a.tpart + ((size_t)(yb * a.kcn) * 16 + n) * a.r + g * KTB + (KTB / 4) * j + 8 * q;
-                        for (int kc = 0; kc < a.kcn; ++kc) {       // fixed order: the result does not depend on timing
-                            v0 += *(const f4*)(p + (size_t)kc * 16 * a.r);
-                            v1 += *(const f4*)(p + (size_t)kc * 16 * a.r + 4);
+                        // all k-ranges are requested at once (a loop that loads and adds one at a time pays a
+                        // memory round trip per k-range); ranges beyond kcn re-read the last one and are not added
+                        f4 p0[MAX_KCN], p1[MAX_KCN];
+#pragma unroll
+                        for (int kc = 0; kc < MAX_KCN; ++kc) {
+                            const float* pk = p + (size_t)(kc < a.kcn ? kc : a.kcn - 1) * 16 * a.r;
+                            p0[kc] = *(const f4*)pk;
+                            p1[kc] = *(const f4*)(pk + 4);
+                        }
+#pragma unroll
+                        for (int kc = 0; kc < MAX_KCN; ++kc) {     // fixed order: the result does not depend on timing
+                            if (kc < a.kcn) {
+                                v0 += p0[kc];
+                                v1 += p1[kc];
+                            }
                         }
                     }
 #pragma unroll
@@ -270,12 +292,13 @@ static hipError_t launch_cfg(const FusedArgs& a, hipStream_t stream)
     // global memory and strips of 4 (or 2) row blocks reuse them.
     const int mt = a.M < 16 ? a.M : 16;
     const size_t xbytes = (size_t)mt * (a.d_in + 32) * 2;
+    const int units = (FA != S_NONE) ? (a.r / 16) * a.kcn : 0;      // producer workgroups per token block, first in x
     if (mt <= 4 && (size_t)mt * a.d_in * 2 <= 4 * 8 * 64 * 16)
-        return launch_one<FM, FA, FE, 1, 8, true>(a, dim3(nblk, yblocks), xbytes, stream);
+        return launch_one<FM, FA, FE, 1, 8, true>(a, dim3(nblk + units, yblocks), xbytes, stream);
     int rb = 1;
     if (nblk % 4 == 0 && nblk / 4 >= 256) rb = 4;
     else if (nblk % 2 == 0 && nblk / 2 >= 256) rb = 2;
-    const dim3 grid(nblk / rb, yblocks);
+    const dim3 grid(nblk / rb + units, yblocks);
     if (rb == 4) return launch_one<FM, FA, FE, 4, 8, false>(a, grid, 0, stream);
     if (rb == 2) return launch_one<FM, FA, FE, 2, 8, false>(a, grid, 0, stream);
     return launch_one<FM, FA, FE, 1, 8, false>(a, grid, 0, stream);
