@@ -3,7 +3,7 @@
 //      y = x.What^T + (x.A^T).B^T          (Sec. 3 forward equation, Alg. 1 step 7)
 //
 // HBM-bound: every stored byte is read once, decoded in registers (tiles.hpp) and fed to
-// 16x16x32 fp16 MFMAs whose 16-row operand is the token block (rows beyond M are zero).
+// 16x16x32 fp16 MFMAs whose 16-row operand is the token block (rows beyond M repeat row 0; never stored).
 //
 // A workgroup of NW wavefronts owns a strip of RB row blocks (16 output rows each).  Its wavefronts
 // split the contraction dimension in quads of four consecutive 128-wide k-tiles (one 8-byte load
@@ -32,6 +32,13 @@
 
 namespace eora {
 
+#ifdef EORA_TIMELINE
+// debug build only: per-workgroup time stamps (100 MHz counter) behind the partials of t
+#define FTL_STAMP(slot) do { if (threadIdx.x == 0) ((unsigned long long*)(a.tpart + (1 << 20)))[(blockIdx.y * gridDim.x + blockIdx.x) * 8 + (slot)] = wall_clock64(); } while (0)
+#else
+#define FTL_STAMP(slot) do { } while (0)
+#endif
+
 // grid: x = strips of 16*RB output rows, y = token blocks of 16.  NW*64 threads.
 // XLDS: x of this token block is staged in dynamic LDS (row stride d_in + 32 halves).
 template <int FM, int FA, int FE, int RB, int NW, bool XLDS>
@@ -53,6 +60,55 @@ __global__ __launch_bounds__(NW * 64) void fused_kernel(FusedArgs a)
     const bool producer = (int)blockIdx.x < units;
     const int R0 = producer ? 0 : ((int)blockIdx.x - units) * RB;
 
+    if constexpr (LOWRANK) {
+        if (producer) {
+            // ===================================================================== producer
+            __builtin_amdgcn_s_setprio(3);                 // everyone's critical path
+            FTL_STAMP(0);
+            constexpr int KTA = Fmt<FA>::KT;
+            CheckIn pci{0u, 0u, 0u};
+            if (threadIdx.x == 0) check_in_load(pci, a.hdr);
+            const int NRB = a.r / 16;
+            const int u = blockIdx.x, rho = u % NRB, kc = u / NRB;
+            const Factor fa{(const uint32_t*)a.A, a.A_scales, a.d_in / KTA};
+            const int tpc = fa.ntk / a.kcn;
+            const f4 part = run_factor_a_eager<FA, NW>(fa, rho, kc * tpc, (kc + 1) * tpc, wave, lane,
+                                                       a.x + (size_t)m_blk * a.d_in, a.d_in, n, row_ok);
+            if (threadIdx.x == 0) {
+                check_in_issue(pci, a.hdr, blockIdx.y * gridDim.x + blockIdx.x);
+                s_epoch = pci.epoch;
+            }
+            FTL_STAMP(1);
+            if (wave > 0) red[wave - 1][0][lane] = part;
+            __syncthreads();
+            if (wave == 0) {
+                f4 v = part;
+#pragma unroll
+                for (int w2 = 0; w2 < NW - 1; ++w2) v += red[w2][0][lane];
+                // partial layout: [token block][kc][token row][r], every element an 8-byte (value, epoch + 1)
+                // pair written by ONE write-through store: a reader that finds this launch's tag has this
+                // launch's value, so the flag (same wavefront, later instruction) need not wait for these
+                // stores to be acknowledged.  Register i is token row 4*j+i, column n.
+                unsigned long long* dst = a.tpair + ((size_t)(yb * a.kcn + kc) * 16) * a.r + 16 * rho + n;
+                const float vs[4] = {v.x, v.y, v.z, v.w};
+                const unsigned long long tag = (unsigned long long)(s_epoch + 1) << 32;
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (4 * j + i < mt)
+                        __hip_atomic_store(&dst[(size_t)(4 * j + i) * a.r], tag | __builtin_bit_cast(uint32_t, vs[i]),
+                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                FTL_STAMP(2);
+                if (lane == 0) {
+                    __hip_atomic_store(&a.hdr[HDR_FLAGS0 + HDR_FLAGS_PER_BLOCK * yb + u], pci.epoch + 1, __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT);
+                    check_in_finish(pci, a.hdr, gridDim.x * gridDim.y);
+                }
+            }
+            return;
+        }
+    }
+
+    FTL_STAMP(0);
     // ---- requests, small operands first ------------------------------------------------------
     const int ldxs = a.d_in + 32;            // LDS row stride (halves): 64 bytes of padding against bank conflicts
     _Float16* xs = (_Float16*)eora_smem;
@@ -112,40 +168,7 @@ __global__ __launch_bounds__(NW * 64) void fused_kernel(FusedArgs a)
     __syncthreads();
     if constexpr (LOWRANK) epoch = s_epoch;
 
-    // ---- phase A: this workgroup's units of t = x.A^T ---------------------------------------------
-    if constexpr (LOWRANK) {
-        constexpr int KTA = Fmt<FA>::KT;
-        const int NRB = a.r / 16;
-        const Factor fa{(const uint32_t*)a.A, a.A_scales, a.d_in / KTA};
-        const int tiles_per_chunk = fa.ntk / a.kcn;
-        uint32_t* flags = a.hdr + HDR_FLAGS0 + HDR_FLAGS_PER_BLOCK * yb;
-        if (producer) {
-            const int u = blockIdx.x;
-            const int rho = u % NRB, kc = u / NRB;
-            const f4 part = run_factor_a<FA, NW, XLDS>(fa, rho, kc * tiles_per_chunk, (kc + 1) * tiles_per_chunk, wave, lane,
-                                                 act, n, row_ok);
-            if (wave > 0) red[wave - 1][0][lane] = part;
-            __syncthreads();
-            if (wave == 0) {
-                f4 v = part;
-#pragma unroll
-                for (int w2 = 0; w2 < NW - 1; ++w2) v += red[w2][0][lane];
-                // partial layout: [token block][kc][token row][r]; register i is token row 4*j+i, column n
-                float* dst = a.tpart + ((size_t)(yb * a.kcn + kc) * 16) * a.r + 16 * rho + n;
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    if (4 * j + i < mt) *(volatile float*)&dst[(size_t)(4 * j + i) * a.r] = v[i];
-                // The partial was written with system-scope write-through (volatile) stores, which are
-                // acknowledged at that scope: waiting for them orders them before the flag without
-                // the L2 write-back of an agent-scope release fence.
-                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-                if (lane == 0) __hip_atomic_store(&flags[u], epoch + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
-            if (threadIdx.x == 0) check_in_finish(ci, a.hdr, gridDim.x * gridDim.y);
-            return;
-        }
-    }
-
+    FTL_STAMP(1);
     // a first look at the flags, requested now and examined after the backbone
     uint32_t early = 0;
     if constexpr (LOWRANK) {
@@ -171,6 +194,7 @@ __global__ __launch_bounds__(NW * 64) void fused_kernel(FusedArgs a)
         }
     }
 
+    FTL_STAMP(2);
     // ---- phase B: += t.B^T -----------------------------------------------------------------------
     if constexpr (LOWRANK) {
         const uint32_t* flags = a.hdr + HDR_FLAGS0 + HDR_FLAGS_PER_BLOCK * yb;
@@ -187,38 +211,67 @@ __global__ __launch_bounds__(NW * 64) void fused_kernel(FusedArgs a)
                 if (!ok) atomicOr(&a.hdr[HDR_ERROR], 1u);          // never expected: owners of units do not wait
             }
         }
+        FTL_STAMP(3);
+        __syncthreads();
+        float* ts = (float*)(eora_smem + (XLDS ? (size_t)mt * ldxs * 2 : 0));      // t of this token block: mt x r fp32
+        if (s_ok) {
+            // Every thread adds the kcn partials of four elements of t, in a fixed order, into LDS.  Ordinary
+            // cached loads first: the flags are up, so the stores were issued long ago and have all but
+            // certainly landed; the tags say whether that held, and a thread that finds an old tag reads
+            // again past the caches until it does (bounded).
+            const int T = mt * a.r;
+            bool good_all = true;
+            for (int e = 4 * (int)threadIdx.x; e < T; e += 4 * NW * 64) {
+                const unsigned long long* p = a.tpair + ((size_t)(yb * a.kcn) * 16) * a.r + e;     // row e / r, column e % r
+                uint2 pr[MAX_KCN][4];
+#pragma unroll
+                for (int kc = 0; kc < MAX_KCN; ++kc) {                 // all k-ranges requested at once
+                    const uint2* pk = (const uint2*)(p + (size_t)(kc < a.kcn ? kc : a.kcn - 1) * 16 * a.r);
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) pr[kc][c] = pk[c];
+                }
+                float v[4] = {0.f, 0.f, 0.f, 0.f};
+                uint32_t bad = 0;
+#pragma unroll
+                for (int kc = 0; kc < MAX_KCN; ++kc) {                 // fixed order
+                    if (kc < a.kcn) {
+#pragma unroll
+                        for (int c = 0; c < 4; ++c) {
+                            bad |= pr[kc][c].y ^ (epoch + 1);
+                            v[c] += __builtin_bit_cast(float, pr[kc][c].x);
+                        }
+                    }
+                }
+                bool good = bad == 0;
+                for (int spins = 0; !good && spins <= a.spin_limit; ++spins) {
+                    bad = 0;
+                    float w[4] = {0.f, 0.f, 0.f, 0.f};
+                    for (int kc = 0; kc < a.kcn; ++kc) {
+#pragma unroll
+                        for (int c = 0; c < 4; ++c) {
+                            const unsigned long long q = __hip_atomic_load(p + (size_t)kc * 16 * a.r + c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            bad |= (uint32_t)(q >> 32) ^ (epoch + 1);
+                            w[c] += __builtin_bit_cast(float, (uint32_t)q);
+                        }
+                    }
+                    good = bad == 0;
+                    v[0] = w[0]; v[1] = w[1]; v[2] = w[2]; v[3] = w[3];
+                }
+                good_all = good_all && good;
+                *(f4*)(ts + e) = f4{v[0], v[1], v[2], v[3]};
+            }
+            if (!good_all) atomicOr(&a.hdr[HDR_ERROR], 1u);            // never expected
+        }
         __syncthreads();
         if (s_ok && wave < fb.ntk) {
-            // The partials are read with ordinary loads and no agent-scope acquire fence (whose cache
-            // invalidation every workgroup would pay for).  That is safe here: they were written
-            // through to memory before their flag, no line of them is read in this launch before
-            // all flags are up, and caches hold nothing of them from before the launch.
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
             constexpr int KTB = Fmt<FE>::KT, NMF = KTB / 32;
             for (int g = wave; g < fb.ntk; g += NW) {
                 h8 hi[NMF], lo[NMF];
 #pragma unroll
                 for (int q = 0; q < NMF; ++q) {
-                    f4 v0 = {0.f, 0.f, 0.f, 0.f}, v1 = {0.f, 0.f, 0.f, 0.f};
-                    if (row_ok) {
-                        const float* p = a.tpart + ((size_t)(yb * a.kcn) * 16 + n) * a.r + g * KTB + (KTB / 4) * j + 8 * q;
-                        // all k-ranges are requested at once (a loop that loads and adds one at a time pays a
-                        // memory round trip per k-range); ranges beyond kcn re-read the last one and are not added
-                        f4 p0[MAX_KCN], p1[MAX_KCN];
-#pragma unroll
-                        for (int kc = 0; kc < MAX_KCN; ++kc) {
-                            const float* pk = p + (size_t)(kc < a.kcn ? kc : a.kcn - 1) * 16 * a.r;
-                            p0[kc] = *(const f4*)pk;
-                            p1[kc] = *(const f4*)(pk + 4);
-                        }
-#pragma unroll
-                        for (int kc = 0; kc < MAX_KCN; ++kc) {     // fixed order: the result does not depend on timing
-                            if (kc < a.kcn) {
-                                v0 += p0[kc];
-                                v1 += p1[kc];
-                            }
-                        }
-                    }
+                    // (token rows beyond the block read row 0: their results are never stored)
+                    const float* p = ts + (row_ok ? n : 0) * a.r + g * KTB + (KTB / 4) * j + 8 * q;
+                    const f4 v0 = *(const f4*)p, v1 = *(const f4*)(p + 4);
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
                         const _Float16 h0 = (_Float16)v0[i], h1 = (_Float16)v1[i];
@@ -247,6 +300,7 @@ __global__ __launch_bounds__(NW * 64) void fused_kernel(FusedArgs a)
         }
     }
 
+    FTL_STAMP(4);
     // ---- combine, convert, store -------------------------------------------------------------------
     if (wave > 0) {
 #pragma unroll
@@ -265,6 +319,7 @@ __global__ __launch_bounds__(NW * 64) void fused_kernel(FusedArgs a)
                 if (4 * j + i < mt) a.y[(size_t)(m_blk + 4 * j + i) * a.d_out + o] = (_Float16)v[i];
         }
     }
+    FTL_STAMP(5);
     if constexpr (LOWRANK) {
         if (threadIdx.x == 0) check_in_finish(ci, a.hdr, gridDim.x * gridDim.y);
     }
@@ -293,15 +348,16 @@ static hipError_t launch_cfg(const FusedArgs& a, hipStream_t stream)
     const int mt = a.M < 16 ? a.M : 16;
     const size_t xbytes = (size_t)mt * (a.d_in + 32) * 2;
     const int units = (FA != S_NONE) ? (a.r / 16) * a.kcn : 0;      // producer workgroups per token block, first in x
+    const size_t tbytes = (FA != S_NONE) ? (size_t)mt * a.r * 4 : 0;   // t of a token block, fp32, in LDS
     if (mt <= 4 && (size_t)mt * a.d_in * 2 <= 4 * 8 * 64 * 16)
-        return launch_one<FM, FA, FE, 1, 8, true>(a, dim3(nblk + units, yblocks), xbytes, stream);
+        return launch_one<FM, FA, FE, 1, 8, true>(a, dim3(nblk + units, yblocks), xbytes + tbytes, stream);
     int rb = 1;
     if (nblk % 4 == 0 && nblk / 4 >= 256) rb = 4;
     else if (nblk % 2 == 0 && nblk / 2 >= 256) rb = 2;
     const dim3 grid(nblk / rb + units, yblocks);
-    if (rb == 4) return launch_one<FM, FA, FE, 4, 8, false>(a, grid, 0, stream);
-    if (rb == 2) return launch_one<FM, FA, FE, 2, 8, false>(a, grid, 0, stream);
-    return launch_one<FM, FA, FE, 1, 8, false>(a, grid, 0, stream);
+    if (rb == 4) return launch_one<FM, FA, FE, 4, 8, false>(a, grid, tbytes, stream);
+    if (rb == 2) return launch_one<FM, FA, FE, 2, 8, false>(a, grid, tbytes, stream);
+    return launch_one<FM, FA, FE, 1, 8, false>(a, grid, tbytes, stream);
 }
 
 template <int FM>

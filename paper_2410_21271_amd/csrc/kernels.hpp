@@ -36,7 +36,8 @@ struct FusedArgs {
     const _Float16* B_scales;
     _Float16* y;              // M x d_out fp16 row-major
     uint32_t* hdr;            // workspace header
-    float* tpart;             // token blocks x kcn x 16 x r fp32 partials of t
+    float* tpart;             // (timeline builds: stamps)
+    unsigned long long* tpair;   // token blocks x kcn x 16 x r (value, tag) pairs: partials of t
     int M, d_in, d_out, r, group, kcn, spin_limit;
 };
 

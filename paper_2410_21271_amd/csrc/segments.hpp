@@ -48,25 +48,22 @@ struct ActSrc {
 
 extern __shared__ __attribute__((aligned(16))) unsigned char eora_smem[];
 
+// Activation fragments of token row m.  Lanes beyond the token block (row_ok false) read row 0 instead:
+// rows of a matmul are independent and their results are never stored, and a load that every lane
+// executes keeps the requests of a wavefront free of divergent branches (which would make the
+// compiler wait for all outstanding requests at each of them).
 template <int NMF, bool XLDS>
 __device__ __forceinline__ void load_act(h8 (&xa)[NMF], const ActSrc<XLDS>& src, int col, int m, bool row_ok)
 {
+    const int mr = row_ok ? m : 0;
+    if constexpr (XLDS) {
+        const _Float16* px = (const _Float16*)(eora_smem + src.lds_off) + mr * src.lds_ld + col;
 #pragma unroll
-    for (int t = 0; t < NMF; ++t) {
-        Frag f;
-        f.q = u4{0u, 0u, 0u, 0u};
-        xa[t] = f.v;
-    }
-    if (row_ok) {
-        if constexpr (XLDS) {
-            const _Float16* px = (const _Float16*)(eora_smem + src.lds_off) + m * src.lds_ld + col;
+        for (int t = 0; t < NMF; ++t) xa[t] = *(const h8*)(px + 8 * t);
+    } else {
+        const _Float16* px = src.g + (size_t)mr * src.ldg + col;
 #pragma unroll
-            for (int t = 0; t < NMF; ++t) xa[t] = *(const h8*)(px + 8 * t);
-        } else {
-            const _Float16* px = src.g + (size_t)m * src.ldg + col;
-#pragma unroll
-            for (int t = 0; t < NMF; ++t) xa[t] = *(const h8*)(px + 8 * t);
-        }
+        for (int t = 0; t < NMF; ++t) xa[t] = *(const h8*)(px + 8 * t);
     }
 }
 
@@ -240,6 +237,49 @@ __device__ __forceinline__ f4 run_factor_a(const Factor& f, int R, int g_begin, 
     return acc;
 }
 
+
+// The same partial for a PRODUCER workgroup, which has nothing else to do: the tiles of A and the
+// activation fragments of up to PD steps are all requested before the first one is used (one memory
+// round trip for the whole unit when it has at most PD steps per wavefront).
+template <int FMT, int NW>
+__device__ __forceinline__ f4 run_factor_a_eager(const Factor& f, int R, int g_begin, int g_end, int wave, int lane,
+                                                 const _Float16* __restrict__ xg, int ldg, int m, bool row_ok)
+{
+    constexpr int KT = Fmt<FMT>::KT, NMF = KT / 32, PD = NMF == 1 ? 8 : 2;
+    const int j = lane >> 4;
+    const int first = g_begin + wave;
+    const int nsteps = first < g_end ? (g_end - first + NW - 1) / NW : 0;
+    const _Float16* xrow = xg + (size_t)(row_ok ? m : 0) * ldg + (KT / 4) * j;
+    f4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int base = 0; base < nsteps; base += PD) {
+        FTile<FMT> buf[PD];
+        h8 xa[PD][NMF];
+#pragma unroll
+        for (int u = 0; u < PD; ++u) {
+            const int s = base + u < nsteps ? base + u : nsteps - 1;         // clamped: always a valid tile
+            const int g = first + s * NW;
+            load_ftile<FMT>(buf[u], f, R, g, lane);
+#pragma unroll
+            for (int t = 0; t < NMF; ++t) xa[u][t] = *(const h8*)(xrow + (size_t)g * KT + 8 * t);
+        }
+#pragma unroll
+        for (int u = 0; u < PD; ++u) {
+            if (base + u < nsteps) {
+                h8 b[NMF];
+                decode_tile<FMT>(buf[u].w, 8u, b);
+                if constexpr (FMT == S_F16) {
+                    acc = mfma16(xa[u][0], b[0], acc);
+                } else {
+                    f4 part = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int t = 0; t < NMF; ++t) part = mfma16(xa[u][t], b[t], part);
+                    acc += (float)buf[u].sc * part;
+                }
+            }
+        }
+    }
+    return acc;
+}
 
 // Every workgroup of a low-rank launch reads the epoch and then checks in on one of HDR_NSUB
 // spread-out counters; the last one to check in advances the epoch for the next launch.  One thread
