@@ -68,7 +68,14 @@ __global__ __launch_bounds__(NW * 64) void sparse_kernel(SparseArgs a)
     const int nprod = units * yblocks;
     const int bid = blockIdx.x;
     const bool producer = bid < nprod;
-    const int yb = producer ? bid / (units > 0 ? units : 1) : (bid - nprod) % yblocks;
+    // Consumers: workgroups are handed to the 8 XCDs round-robin, each with an L2 of its own.  With several
+    // token blocks the blocks of one row block are therefore given indices 8 apart: they land on the same
+    // XCD one after the other and the row block's weights come from HBM once, not once per token block.
+    const int cidx = bid - nprod;
+    const bool xcd_map = yblocks > 1 && (a.d_out / 16) % 8 == 0;
+    const int c_yb = xcd_map ? (cidx / 8) % yblocks : cidx % yblocks;
+    const int c_R = xcd_map ? (cidx / (8 * yblocks)) * 8 + cidx % 8 : cidx / yblocks;
+    const int yb = producer ? bid / (units > 0 ? units : 1) : c_yb;
     const int m_blk = 16 * yb;
     const int mt = a.M - m_blk < 16 ? a.M - m_blk : 16;
     const int mrow = n < mt ? n : 0;                      // lanes beyond the tokens re-read row 0; results dropped
@@ -131,7 +138,7 @@ __global__ __launch_bounds__(NW * 64) void sparse_kernel(SparseArgs a)
     }
 
     // ========================================================================= consumer
-    const int R = (bid - nprod) / yblocks;
+    const int R = c_R;
     const int G = a.d_in / 128;
     const int nsteps = wave < G ? (G - wave + NW - 1) / NW : 0;
     SpTile buf[PD];
@@ -261,6 +268,292 @@ __global__ __launch_bounds__(NW * 64) void sparse_kernel(SparseArgs a)
     }
 }
 
+
+// ---------------------------------------------------------------------------------------------------
+// More than 4 tokens and many output rows: one wavefront per row block (whole contraction length), NW row
+// blocks and up to TB token blocks of 16 per workgroup.  A token block's x is 1.8x the bytes of a row
+// block's weights, so x is shared through LDS by the NW wavefronts, and a stored tile, once in registers,
+// serves all TB token blocks.  Per step one 128-column chunk: x[16 TB tokens][128] goes global ->
+// registers (requested XW_D steps before its LDS write) -> one of two LDS slots, and the wavefront's stored
+// tile of the same columns is requested XW_D steps ahead as well.  All requests are plain loads: with
+// global -> LDS copies among them the compiler would no longer count on in-order answers and would drain
+// every request before each use.  One barrier per step: after it chunk c is visible to everyone and
+// everyone has left the other slot, which is rewritten at once.
+//
+// LDS slot layout: 16-byte piece q of token row t (columns 8q .. 8q+7 of the chunk) sits at piece index
+// 16 t + (q ^ (t & 15)): the 16 lanes that read one q for 16 tokens hit 16 different bank groups.
+// Producers, flags, partials and the continuation are those of the kernel above.
+template <int FA, int NW, int TB, int XW_D>      // XW_D: steps between a request and its use; divides d_in / 128
+__global__ __launch_bounds__(NW * 64) void sparse_wide_kernel(SparseArgs a)
+{
+    constexpr bool LOWRANK = FA != S_NONE;
+    constexpr int SLOT = TB * 16 * 256;                   // bytes per slot
+    constexpr int NCP = TB * 4;                           // 1 KiB pieces of a chunk of x (4 token rows each)
+    static_assert(NCP % NW == 0, "the pieces divide evenly over the wavefronts");
+    constexpr int XN = NCP / NW;                          // per wavefront
+    __shared__ float redp[NW][16][16];
+    __shared__ uint32_t s_epoch, s_ok;
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int n = lane & 15, j = lane >> 4;
+    const int yblocks = (a.M + 15) / 16;
+    const int units = LOWRANK ? (a.r / 16) * a.kcn : 0;
+    const int nprod = units * yblocks;
+    const int bid = blockIdx.x;
+    const bool producer = bid < nprod;
+
+    CheckIn ci{0u, 0u, 0u};
+    if constexpr (LOWRANK) {
+        if (tid == 0) check_in_load(ci, a.hdr);
+        if (producer) {
+            // ===================================================================== producer
+            constexpr int KTA = Fmt<FA>::KT;
+            const int yb = bid / units;
+            const int m_blk = 16 * yb;
+            const int mt = a.M - m_blk < 16 ? a.M - m_blk : 16;
+            const int mrow = n < mt ? n : 0;
+            const ActSrc<false> act{a.x + (size_t)m_blk * a.d_in, a.d_in, 0, 0};
+            const int NRB = a.r / 16;
+            const int u = bid % units, rho = u % NRB, kc = u / NRB;
+            const Factor fa{(const uint32_t*)a.A, nullptr, a.d_in / KTA};
+            const int tpc = fa.ntk / a.kcn;
+            if (tid == 0) {
+                check_in_issue(ci, a.hdr, bid);
+                s_epoch = ci.epoch;
+            }
+            __syncthreads();
+            const f4 part = run_factor_a<FA, NW, false>(fa, rho, kc * tpc, (kc + 1) * tpc, wave, lane, act, mrow, true);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) redp[wave][4 * j + i][n] = part[i];
+            __syncthreads();
+            for (int e = tid; e < 256; e += NW * 64) {
+                const int i = e >> 4, col = e & 15;
+                if (i < mt) {
+                    float v = 0.f;
+#pragma unroll
+                    for (int w2 = 0; w2 < NW; ++w2) v += redp[w2][i][col];
+                    *(volatile float*)&a.tpart[((size_t)(yb * a.kcn + kc) * 16 + i) * a.r + 16 * rho + col] = v;
+                }
+            }
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // write-through stores acknowledged
+            __syncthreads();
+            if (tid == 0) {
+                for (int rep = 0; rep < HDR_FLAG_REPLICAS; ++rep)
+                    __hip_atomic_store(&a.hdr[HDR_FLAGS0 + HDR_FLAGS_REPLICA_STRIDE * rep + HDR_FLAGS_PER_BLOCK * yb + u],
+                                       s_epoch + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                check_in_finish(ci, a.hdr, gridDim.x);
+            }
+            return;
+        }
+    }
+
+    // ========================================================================= consumer
+    const int RBs = a.d_out / 16;
+    const int NTG = (yblocks + TB - 1) / TB;              // groups of TB token blocks
+    const int cidx = bid - nprod;
+    const int tg = cidx % NTG, rg = cidx / NTG;
+    const int m0 = tg * TB * 16;                          // first token of the group
+    const int Rw = rg * NW + wave;
+    const bool active = Rw < RBs;                         // a ragged last row group: the wavefront only helps staging
+    const int R = active ? Rw : RBs - 1;
+    const int G = a.d_in / 128;                           // chunks = stored tiles per row block
+    // piece q of a chunk: token rows 4 q .. 4 q + 3, lane -> row 4 q + lane / 16, 16-byte piece lane % 16
+    const _Float16* xsrc[XN];
+    int xdst[XN];
+#pragma unroll
+    for (int i = 0; i < XN; ++i) {
+        const int trow = 4 * (wave + i * NW) + (lane >> 4);
+        const int grow = m0 + trow < a.M ? m0 + trow : a.M - 1;      // rows beyond the tokens: a valid row, results dropped
+        xsrc[i] = a.x + (size_t)grow * a.d_in + 8 * (lane & 15);
+        xdst[i] = (trow * 16 + ((lane & 15) ^ (trow & 15))) * 16;
+    }
+    const uint32_t* ibase = a.indices + (size_t)R * G * 64 + lane;
+    const u4* vbase = (const u4*)(a.values + (size_t)R * G * 1024) + lane;
+    auto load_tile = [&](SpTile& t, int c) {
+        t.idx = ibase[c * 64];
+        t.v0 = vbase[c * 128];
+        t.v1 = vbase[c * 128 + 64];
+    };
+    SpTile buf[XW_D];
+    u4 xr[XW_D][XN];
+#pragma unroll
+    for (int s = 0; s < XW_D; ++s) {                      // G is a multiple of XW_D
+#pragma unroll
+        for (int i = 0; i < XN; ++i) xr[s][i] = *(const u4*)(xsrc[i] + s * 128);
+        load_tile(buf[s], s);
+    }
+    if constexpr (LOWRANK) {
+        if (tid == 0) {
+            check_in_issue(ci, a.hdr, bid);
+            s_epoch = ci.epoch;
+        }
+    }
+    // chunk 0 -> slot 0; its registers take chunk XW_D
+#pragma unroll
+    for (int i = 0; i < XN; ++i) {
+        *(u4*)(eora_smem + xdst[i]) = xr[0][i];
+        xr[0][i] = *(const u4*)(xsrc[i] + (XW_D < G ? XW_D : G - 1) * 128);
+    }
+
+    f4 acc[TB];
+#pragma unroll
+    for (int tb = 0; tb < TB; ++tb) acc[tb] = f4{0.f, 0.f, 0.f, 0.f};
+    // piece offsets of this lane's four dense-operand reads of a token block: (blk, half) -> piece 8 blk + 4 half + j
+    int poff[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) poff[q] = (n * 16 + ((8 * (q >> 1) + 4 * (q & 1) + j) ^ n)) * 16;
+
+    for (int base = 0; base < G; base += XW_D) {
+#pragma unroll
+        for (int s = 0; s < XW_D; ++s) {
+            const int c = base + s;
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");       // own LDS writes of chunk c done
+            __builtin_amdgcn_s_barrier();
+            // chunk c + 1 -> the slot everyone has just left; its registers take the chunk XW_D further on
+            // (past the end: the last chunk again, never used)
+            const int s1 = (s + 1) % XW_D;
+            const int cx = c + 1 + XW_D < G ? c + 1 + XW_D : G - 1;
+#pragma unroll
+            for (int i = 0; i < XN; ++i) {
+                *(u4*)(eora_smem + ((c + 1) & 1) * SLOT + xdst[i]) = xr[s1][i];
+                xr[s1][i] = *(const u4*)(xsrc[i] + cx * 128);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            const unsigned char* xs = eora_smem + (c & 1) * SLOT;
+#pragma unroll
+            for (int tb = 0; tb < TB; ++tb) {
+                const unsigned char* px = xs + tb * 4096;
+                const h8 x00 = *(const h8*)(px + poff[0]), x01 = *(const h8*)(px + poff[1]);
+                const h8 x10 = *(const h8*)(px + poff[2]), x11 = *(const h8*)(px + poff[3]);
+                const h16 xa = __builtin_shufflevector(x00, x01, 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15);
+                const h16 xb = __builtin_shufflevector(x10, x11, 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15);
+                acc[tb] = __builtin_amdgcn_smfmac_f32_16x16x64_f16(as_h8(buf[s].v0), xa, acc[tb], (int)buf[s].idx, 0, 0);
+                acc[tb] = __builtin_amdgcn_smfmac_f32_16x16x64_f16(as_h8(buf[s].v1), xb, acc[tb], (int)buf[s].idx, 0, 1);
+            }
+            // the tile's registers are free again: the request for the tile XW_D chunks on goes out last
+            __builtin_amdgcn_sched_barrier(0);
+            load_tile(buf[s], c + XW_D < G ? c + XW_D : G - 1);
+        }
+    }
+
+    // ---- low-rank continuation, one token block at a time: acc[row][token] += B[row][:] . t[token][:] -----
+    if constexpr (LOWRANK) {
+        float* ts = (float*)eora_smem;                    // t of one token block (16 x r fp32) over the x slots
+        __syncthreads();                                  // ... once nobody reads x any more
+        const uint32_t epoch = s_epoch;
+        if (wave == 0) {
+            bool ok = true;
+#pragma unroll
+            for (int tb = 0; tb < TB; ++tb) {
+                const int yb = tg * TB + tb;
+                if (yb >= yblocks || !ok) continue;
+                const uint32_t* flags = a.hdr + HDR_FLAGS0 + HDR_FLAGS_REPLICA_STRIDE * (blockIdx.x % HDR_FLAG_REPLICAS) + HDR_FLAGS_PER_BLOCK * yb;
+                bool up = false;
+                for (int spins = 0; spins <= a.spin_limit; ++spins) {
+                    bool all = true;
+                    for (int f = lane; f < units; f += 64) all = all && (ld_relaxed(&flags[f]) == epoch + 1);
+                    if (__all(all)) { up = true; break; }
+                    __builtin_amdgcn_s_sleep(2);
+                }
+                ok = up;
+            }
+            if (lane == 0) {
+                s_ok = ok ? 1u : 0u;
+                if (!ok) atomicOr(&a.hdr[HDR_ERROR], 1u);
+            }
+        }
+        __syncthreads();
+        if (s_ok) {
+            // ordinary cached loads: the partials were written through before their flags, none of their
+            // lines is read in this launch before all flags are up, caches hold nothing older
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+            const Factor fb{(const uint32_t*)a.B, nullptr, a.r / 32};
+#pragma unroll
+            for (int tb = 0; tb < TB; ++tb) {
+                const int yb = tg * TB + tb;
+                if (yb < yblocks) {                       // uniform over the workgroup
+                    const int mt = a.M - 16 * yb < 16 ? a.M - 16 * yb : 16;
+                    const int mrow = n < mt ? n : 0;
+                    const int T = mt * a.r;
+                    for (int e = 4 * tid; e < T; e += NW * 256) {
+                        const float* p = a.tpart + ((size_t)(yb * a.kcn) * 16) * a.r + e;
+                        f4 v = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
+                        for (int kc = 0; kc < a.kcn; ++kc) v += *(const f4*)(p + (size_t)kc * 16 * a.r);   // fixed order
+                        *(f4*)(ts + e) = v;
+                    }
+                    __syncthreads();
+                    for (int g = 0; g < fb.ntk; ++g) {
+                        FTile<S_F16> cur;
+                        load_ftile<S_F16>(cur, fb, R, g, lane);
+                        h8 b[1];
+                        decode_tile<S_F16>(cur.w, 0u, b);
+                        const float* p = ts + mrow * a.r + g * 32 + 8 * j;
+                        const f4 v0 = *(const f4*)p, v1 = *(const f4*)(p + 4);
+                        h8 hi, lo;
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const _Float16 h0 = (_Float16)v0[i], h1 = (_Float16)v1[i];
+                            hi[i] = h0;
+                            hi[4 + i] = h1;
+                            lo[i] = (_Float16)(v0[i] - (float)h0);
+                            lo[4 + i] = (_Float16)(v1[i] - (float)h1);
+                        }
+                        acc[tb] = mfma16(b[0], hi, acc[tb]);
+                        acc[tb] = mfma16(b[0], lo, acc[tb]);
+                    }
+                    __syncthreads();                      // ts is rewritten for the next token block
+                }
+            }
+        }
+    }
+
+    // ---- convert, store: lane holds rows 4*j+i of its row block for token n of each token block ----------
+#pragma unroll
+    for (int tb = 0; tb < TB; ++tb) {
+        const int m = m0 + 16 * tb + n;
+        if (active && m < a.M) {
+            typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+            const f4 v = acc[tb];
+            const h4 o = {(_Float16)v.x, (_Float16)v.y, (_Float16)v.z, (_Float16)v.w};
+            *(h4*)(a.y + (size_t)m * a.d_out + R * 16 + 4 * j) = o;
+        }
+    }
+    if constexpr (LOWRANK) {
+        if (tid == 0) check_in_finish(ci, a.hdr, gridDim.x);
+    }
+}
+
+constexpr int WIDE_NW = 4;
+
+template <int FA, int TB, int XW_D>
+static hipError_t launch_sparse_wide(const SparseArgs& a, hipStream_t stream)
+{
+    auto kern = sparse_wide_kernel<FA, WIDE_NW, TB, XW_D>;
+    const size_t xb = (size_t)2 * TB * 4096, tb = (size_t)16 * a.r * 4;
+    const size_t lds = xb > tb ? xb : tb;
+    if (lds > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    const int yblocks = (a.M + 15) / 16;
+    const int nprod = (FA != S_NONE) ? (a.r / 16) * a.kcn * yblocks : 0;
+    const int nrg = (a.d_out / 16 + WIDE_NW - 1) / WIDE_NW;
+    hipLaunchKernelGGL(kern, dim3(nrg * ((yblocks + TB - 1) / TB) + nprod), dim3(WIDE_NW * 64), lds, stream, a);
+    return hipGetLastError();
+}
+
+template <int FA>
+static hipError_t launch_sparse_wide_tb(const SparseArgs& a, int tb, hipStream_t stream)
+{
+    switch (tb) {
+    case 1: return launch_sparse_wide<FA, 1, 4>(a, stream);
+    case 2: return launch_sparse_wide<FA, 2, 4>(a, stream);
+    case 3: return launch_sparse_wide<FA, 3, 4>(a, stream);
+    default: return launch_sparse_wide<FA, 4, 4>(a, stream);
+    }
+}
+
 template <int FA, int FE, int NW, bool XLDS>
 static hipError_t launch_sparse_one(const SparseArgs& a, hipStream_t stream)
 {
@@ -281,6 +574,16 @@ hipError_t launch_sparse(const SparseArgs& a, hipStream_t stream)
 {
     // x in LDS for 1..4 tokens when it fits next to t (d_in a multiple of 512 for the 1 KiB copy chunks)
     const bool xlds = a.M <= 4 && a.d_in % 512 == 0 && (size_t)a.M * (a.d_in + 32) * 2 + 16 * (size_t)a.r * 4 <= 150 * 1024;
+    // several tokens and enough row groups to fill the chip: x shared through LDS, as many token blocks
+    // per workgroup (at most 4) as still leave 256 workgroups
+    const int yblocks = (a.M + 15) / 16;
+    const int nrg = (a.d_out / 16 + WIDE_NW - 1) / WIDE_NW;
+    if (a.M > 4 && a.d_in % 512 == 0 && a.r <= 512) {
+        int tb = yblocks < 4 ? yblocks : 4;
+        while (tb > 1 && nrg * ((yblocks + tb - 1) / tb) < 256) --tb;
+        if (nrg * ((yblocks + tb - 1) / tb) >= 256)
+            return a.r == 0 ? launch_sparse_wide_tb<S_NONE>(a, tb, stream) : launch_sparse_wide_tb<S_F16>(a, tb, stream);
+    }
     if (a.r == 0) return xlds ? launch_sparse_one<S_NONE, S_NONE, 8, true>(a, stream)
                               : launch_sparse_one<S_NONE, S_NONE, 8, false>(a, stream);
     return xlds ? launch_sparse_one<S_F16, S_F16, 8, true>(a, stream) : launch_sparse_one<S_F16, S_F16, 8, false>(a, stream);

@@ -261,6 +261,23 @@ def test_config5_shape_k_projection(gpu, M):
     _check(run_linear_sp24(c), c.oracle_y())
 
 
+@pytest.mark.parametrize("r,M,d_in,d_out", [
+    (0, 37, 1024, 5488),       # three token blocks (ragged), a ragged last group of row blocks, no low-rank term
+    (32, 37, 1024, 5488),
+    (128, 64, 2048, 4096),     # four full token blocks, XCD-aware order of the workgroups
+    (512, 16, 512, 16384),     # one token block, one chunk, the largest rank (t fills the x buffers' LDS)
+])
+def test_linear_sp24_many_tokens_many_rows(gpu, r, M, d_in, d_out):
+    """The kernel that shares a token block's x between row blocks through LDS (more than 4 tokens and
+    enough rows to fill the chip)."""
+    from tests.cases import SparseCase
+    from tests.gpu_util import run_linear_sp24
+    c = SparseCase(2300 + r + M, d_in, d_out, M, r, packer=gpu)
+    y = run_linear_sp24(c)
+    _check(y, c.oracle_y())
+    assert np.array_equal(y, run_linear_sp24(c))
+
+
 @pytest.mark.parametrize("w_bits,r,M,d_out", [(4, 0, 128, 128), (4, 128, 200, 192), (3, 256, 333, 144), (4, 128, 129, 16)])
 def test_prefill_gemm_small_shapes(gpu, w_bits, r, M, d_out):
     """The many-token GEMM path: ragged token and row tiles, with and without the low-rank extension."""
