@@ -436,10 +436,19 @@ __global__ __launch_bounds__(NW * 64) void sparse_wide_kernel(SparseArgs a)
         }
     }
 
-    // ---- low-rank continuation, one token block at a time: acc[row][token] += B[row][:] . t[token][:] -----
+    // ---- low-rank continuation: acc[row][token] += B[row][:] . t[token][:] ----------------------------------
     if constexpr (LOWRANK) {
-        float* ts = (float*)eora_smem;                    // t of one token block (16 x r fp32) over the x slots
-        __syncthreads();                                  // ... once nobody reads x any more
+        // t (16 x r fp32 per token block) goes over the x slots, as many token blocks at a time as fit
+        float* ts = (float*)eora_smem;
+        const int tsz = 16 * a.r;                         // floats per token block
+        const int lds_floats = 2 * SLOT / 4 > tsz ? 2 * SLOT / 4 : tsz;
+        const int nb = lds_floats / tsz;                  // >= 1
+        const Factor fb{(const uint32_t*)a.B, nullptr, a.r / 32};
+        constexpr int BPRE = 4;                           // B's first tiles are requested before the wait for t
+        FTile<S_F16> bt[BPRE];
+#pragma unroll
+        for (int g = 0; g < BPRE; ++g) load_ftile<S_F16>(bt[g], fb, R, g < fb.ntk ? g : 0, lane);
+        __syncthreads();                                  // nobody reads x any more
         const uint32_t epoch = s_epoch;
         if (wave == 0) {
             bool ok = true;
@@ -467,42 +476,56 @@ __global__ __launch_bounds__(NW * 64) void sparse_wide_kernel(SparseArgs a)
             // ordinary cached loads: the partials were written through before their flags, none of their
             // lines is read in this launch before all flags are up, caches hold nothing older
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-            const Factor fb{(const uint32_t*)a.B, nullptr, a.r / 32};
 #pragma unroll
             for (int tb = 0; tb < TB; ++tb) {
-                const int yb = tg * TB + tb;
-                if (yb < yblocks) {                       // uniform over the workgroup
-                    const int mt = a.M - 16 * yb < 16 ? a.M - 16 * yb : 16;
-                    const int mrow = n < mt ? n : 0;
-                    const int T = mt * a.r;
-                    for (int e = 4 * tid; e < T; e += NW * 256) {
-                        const float* p = a.tpart + ((size_t)(yb * a.kcn) * 16) * a.r + e;
-                        f4 v = {0.f, 0.f, 0.f, 0.f};
+                if (tb % nb == 0) {                       // uniform over the workgroup: the next nb token blocks' t
+                    if (tb > 0) __syncthreads();          // the previous ones have been used
+                    for (int q = 0; q < nb && tb + q < TB; ++q) {
+                        const int yq = tg * TB + tb + q;
+                        if (yq >= yblocks) break;
+                        const int mq = a.M - 16 * yq < 16 ? a.M - 16 * yq : 16;
+                        const int T = mq * a.r;
+                        for (int e = 4 * tid; e < T; e += NW * 256) {
+                            const float* p = a.tpart + ((size_t)(yq * a.kcn) * 16) * a.r + e;
+                            f4 v = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll 4
-                        for (int kc = 0; kc < a.kcn; ++kc) v += *(const f4*)(p + (size_t)kc * 16 * a.r);   // fixed order
-                        *(f4*)(ts + e) = v;
+                            for (int kc = 0; kc < a.kcn; ++kc) v += *(const f4*)(p + (size_t)kc * 16 * a.r);   // fixed order
+                            *(f4*)(ts + q * tsz + e) = v;
+                        }
                     }
                     __syncthreads();
-                    for (int g = 0; g < fb.ntk; ++g) {
-                        FTile<S_F16> cur;
-                        load_ftile<S_F16>(cur, fb, R, g, lane);
+                }
+                const int yb = tg * TB + tb;
+                if (yb < yblocks) {
+                    const int mt = a.M - 16 * yb < 16 ? a.M - 16 * yb : 16;
+                    const int mrow = n < mt ? n : 0;
+                    const float* tq = ts + (tb % nb) * tsz + mrow * a.r + 8 * j;
+                    auto contract = [&](const FTile<S_F16>& cur, int g) {
                         h8 b[1];
                         decode_tile<S_F16>(cur.w, 0u, b);
-                        const float* p = ts + mrow * a.r + g * 32 + 8 * j;
+                        const float* p = tq + g * 32;
                         const f4 v0 = *(const f4*)p, v1 = *(const f4*)(p + 4);
+                        const float e0[4] = {v0.x, v0.y, v0.z, v0.w}, e1[4] = {v1.x, v1.y, v1.z, v1.w};
                         h8 hi, lo;
 #pragma unroll
                         for (int i = 0; i < 4; ++i) {
-                            const _Float16 h0 = (_Float16)v0[i], h1 = (_Float16)v1[i];
+                            const _Float16 h0 = (_Float16)e0[i], h1 = (_Float16)e1[i];
                             hi[i] = h0;
                             hi[4 + i] = h1;
-                            lo[i] = (_Float16)(v0[i] - (float)h0);
-                            lo[4 + i] = (_Float16)(v1[i] - (float)h1);
+                            lo[i] = (_Float16)(e0[i] - (float)h0);
+                            lo[4 + i] = (_Float16)(e1[i] - (float)h1);
                         }
                         acc[tb] = mfma16(b[0], hi, acc[tb]);
                         acc[tb] = mfma16(b[0], lo, acc[tb]);
+                    };
+#pragma unroll
+                    for (int g = 0; g < BPRE; ++g)
+                        if (g < fb.ntk) contract(bt[g], g);
+                    for (int g = BPRE; g < fb.ntk; ++g) {
+                        FTile<S_F16> cur;
+                        load_ftile<S_F16>(cur, fb, R, g, lane);
+                        contract(cur, g);
                     }
-                    __syncthreads();                      // ts is rewritten for the next token block
                 }
             }
         }
@@ -580,7 +603,7 @@ hipError_t launch_sparse(const SparseArgs& a, hipStream_t stream)
     const int nrg = (a.d_out / 16 + WIDE_NW - 1) / WIDE_NW;
     if (a.M > 4 && a.d_in % 512 == 0 && a.r <= 512) {
         int tb = yblocks < 4 ? yblocks : 4;
-        while (tb > 1 && nrg * ((yblocks + tb - 1) / tb) < 256) --tb;
+        while (tb > 1 && nrg * ((yblocks + tb - 1) / tb) < 256) tb = (tb + 1) / 2;
         if (nrg * ((yblocks + tb - 1) / tb) >= 256)
             return a.r == 0 ? launch_sparse_wide_tb<S_NONE>(a, tb, stream) : launch_sparse_wide_tb<S_F16>(a, tb, stream);
     }
