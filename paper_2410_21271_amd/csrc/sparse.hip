@@ -37,18 +37,32 @@ __device__ __forceinline__ void load_sptile(SpTile& t, const _Float16* __restric
 
 __device__ __forceinline__ h8 as_h8(u4 v) { return __builtin_bit_cast(h8, v); }
 
-// direct global -> LDS copy of the token block's x (mt rows of d_in fp16, d_in a multiple of 512):
-// one 1 KiB chunk per wavefront instruction, rows padded by 64 bytes in LDS
+// the token block's x (mt <= 4 rows of d_in fp16) -> LDS, rows padded by 64 bytes, through registers: all
+// requests of the kernel stay plain loads (with global -> LDS copies among them the compiler no longer counts
+// on in-order answers and drains every request before each use)
 template <int NW>
-__device__ __forceinline__ void stage_x_dma(const _Float16* __restrict__ x, int mt, int d_in, int wave, int lane)
+__device__ __forceinline__ void stage_x(const _Float16* __restrict__ x, int mt, int d_in, int tid)
 {
-    const int cpr = d_in / 512;                           // chunks per row
-    const int total = mt * cpr;
-    for (int c = wave; c < total; c += NW) {
-        const int row = c / cpr, cc = c % cpr;
-        __builtin_amdgcn_global_load_lds(
-            (const __attribute__((address_space(1))) void*)(x + (size_t)row * d_in + cc * 512 + lane * 8),
-            (__attribute__((address_space(3))) void*)(eora_smem + (size_t)row * (d_in + 32) * 2 + cc * 1024), 16, 0, 0);
+    constexpr int T = NW * 64;
+    const int ppr = d_in / 8;                             // 16-byte pieces per row
+    for (int p0 = tid; p0 < ppr; p0 += 2 * T) {
+        const int p1 = p0 + T < ppr ? p0 + T : p0;
+        u4 v[4][2];
+#pragma unroll
+        for (int row = 0; row < 4; ++row) {
+            if (row < mt) {
+                v[row][0] = *(const u4*)(x + (size_t)row * d_in + p0 * 8);
+                v[row][1] = *(const u4*)(x + (size_t)row * d_in + p1 * 8);
+            }
+        }
+#pragma unroll
+        for (int row = 0; row < 4; ++row) {
+            if (row < mt) {
+                unsigned char* d = eora_smem + (size_t)row * (d_in + 32) * 2;
+                *(u4*)(d + p0 * 16) = v[row][0];
+                if (p0 + T < ppr) *(u4*)(d + p1 * 16) = v[row][1];
+            }
+        }
     }
 }
 
@@ -88,11 +102,6 @@ __global__ __launch_bounds__(NW * 64) void sparse_kernel(SparseArgs a)
     if constexpr (LOWRANK) {
         if (tid == 0) check_in_load(ci, a.hdr);           // first request: it returns first
     }
-    if constexpr (XLDS) {
-        stage_x_dma<NW>(xg, mt, a.d_in, wave, lane);
-        asm volatile("" ::: "memory");                    // later requests stay behind the copy: the waits below count them
-    }
-
     if constexpr (LOWRANK) {
         if (producer) {
             // ===================================================================== producer
@@ -105,12 +114,8 @@ __global__ __launch_bounds__(NW * 64) void sparse_kernel(SparseArgs a)
                 check_in_issue(ci, a.hdr, bid);
                 s_epoch = ci.epoch;
             }
-            if constexpr (XLDS) {
-                asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");      // x has landed in LDS
-                __builtin_amdgcn_s_barrier();
-            } else {
-                __syncthreads();
-            }
+            if constexpr (XLDS) stage_x<NW>(xg, mt, a.d_in, tid);
+            __syncthreads();
             const f4 part = run_factor_a<FA, NW, XLDS>(fa, rho, kc * tpc, (kc + 1) * tpc, wave, lane, act, mrow, true);
 #pragma unroll
             for (int i = 0; i < 4; ++i) redp[wave][4 * j + i][n] = part[i];       // register i is token row 4*j+i, column n
@@ -141,12 +146,13 @@ __global__ __launch_bounds__(NW * 64) void sparse_kernel(SparseArgs a)
     const int R = c_R;
     const int G = a.d_in / 128;
     const int nsteps = wave < G ? (G - wave + NW - 1) / NW : 0;
+    // step s of this wavefront is stored tile wave + s NW of the row block; requests past the end fetch the
+    // last one again (never used): every step issues the same requests, refilled into the registers just used
+    const int last = nsteps > 0 ? nsteps - 1 : 0;
+    const size_t tile0 = (size_t)R * G + (nsteps > 0 ? wave : 0);
     SpTile buf[PD];
 #pragma unroll
-    for (int s = 0; s < PD; ++s) {
-        const int ss = s < nsteps ? s : (nsteps > 0 ? nsteps - 1 : 0);           // clamped: always a valid tile
-        load_sptile(buf[s], a.values, a.indices, (size_t)R * G + (nsteps > 0 ? wave : 0) + ss * NW, lane);
-    }
+    for (int s = 0; s < PD; ++s) load_sptile(buf[s], a.values, a.indices, tile0 + (size_t)(s < nsteps ? s : last) * NW, lane);
     const Factor fb{(const uint32_t*)a.B, nullptr, LOWRANK ? a.r / 32 : 0};
     FTile<S_F16> bpre;
     if constexpr (LOWRANK) load_ftile<S_F16>(bpre, fb, R, wave < fb.ntk ? wave : 0, lane);
@@ -157,10 +163,8 @@ __global__ __launch_bounds__(NW * 64) void sparse_kernel(SparseArgs a)
         }
     }
     if constexpr (XLDS) {
-        // everything after the x copy: PD tiles of three loads (+ B's first tile); the check-in atomic of
-        // wavefront 0 comes later in order and only makes its wait longer
-        if constexpr (LOWRANK) asm volatile("s_waitcnt vmcnt(13) lgkmcnt(0)" ::: "memory");
-        else asm volatile("s_waitcnt vmcnt(12) lgkmcnt(0)" ::: "memory");
+        stage_x<NW>(xg, mt, a.d_in, tid);
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");           // own LDS writes done; tile requests stay in flight
         __builtin_amdgcn_s_barrier();
     } else {
         __syncthreads();
@@ -171,9 +175,7 @@ __global__ __launch_bounds__(NW * 64) void sparse_kernel(SparseArgs a)
 #pragma unroll
         for (int s = 0; s < PD; ++s) {
             if (base + s < nsteps) {
-                const SpTile cur = buf[s];
                 const int g = wave + (base + s) * NW;
-                if (base + s + PD < nsteps) load_sptile(buf[s], a.values, a.indices, (size_t)R * G + g + PD * NW, lane);
 #pragma unroll
                 for (int blk = 0; blk < 2; ++blk) {
                     h8 x0, x1;
@@ -188,10 +190,13 @@ __global__ __launch_bounds__(NW * 64) void sparse_kernel(SparseArgs a)
                         x1 = *(const h8*)(px + 32);
                     }
                     const h16 xb = __builtin_shufflevector(x0, x1, 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15);
-                    if (blk == 0) acc = __builtin_amdgcn_smfmac_f32_16x16x64_f16(as_h8(cur.v0), xb, acc, (int)cur.idx, 0, 0);
-                    else acc = __builtin_amdgcn_smfmac_f32_16x16x64_f16(as_h8(cur.v1), xb, acc, (int)cur.idx, 0, 1);
+                    if (blk == 0) acc = __builtin_amdgcn_smfmac_f32_16x16x64_f16(as_h8(buf[s].v0), xb, acc, (int)buf[s].idx, 0, 0);
+                    else acc = __builtin_amdgcn_smfmac_f32_16x16x64_f16(as_h8(buf[s].v1), xb, acc, (int)buf[s].idx, 0, 1);
                 }
             }
+            __builtin_amdgcn_sched_barrier(0);
+            const int sn = base + s + PD;
+            load_sptile(buf[s], a.values, a.indices, tile0 + (size_t)(sn < nsteps ? sn : last) * NW, lane);
         }
     }
 
