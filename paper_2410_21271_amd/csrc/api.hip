@@ -357,6 +357,7 @@ int eora_linear_sp24(const void* x, const void* values, const void* indices,
         a.y = (_Float16*)y + (size_t)m0 * d_out;
         a.hdr = (uint32_t*)workspace;
         a.tpart = (float*)((char*)workspace + WS_PARTS);
+        a.tpair = (unsigned long long*)((char*)workspace + WS_PAIRS);
         a.M = M - m0 < CHUNK_TOKENS ? M - m0 : CHUNK_TOKENS;
         a.d_in = d_in;
         a.d_out = d_out;

@@ -76,7 +76,8 @@ struct SparseArgs {
     const void* B;            // d_out x r F16 tiles
     _Float16* y;              // M x d_out fp16 row-major
     uint32_t* hdr;            // workspace header
-    float* tpart;             // token blocks x kcn x 16 x r fp32 partials of t
+    float* tpart;             // token blocks x kcn x 16 x r fp32 partials of t (kernel for many tokens and rows)
+    unsigned long long* tpair;   // the same as (value, tag) pairs (decode kernel)
     int M, d_in, d_out, r, kcn, spin_limit;
 };
 

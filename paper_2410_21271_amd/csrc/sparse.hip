@@ -45,34 +45,28 @@ __device__ __forceinline__ void stage_x(const _Float16* __restrict__ x, int mt, 
 {
     constexpr int T = NW * 64;
     const int ppr = d_in / 8;                             // 16-byte pieces per row
-    for (int p0 = tid; p0 < ppr; p0 += 2 * T) {
-        const int p1 = p0 + T < ppr ? p0 + T : p0;
-        u4 v[4][2];
-#pragma unroll
-        for (int row = 0; row < 4; ++row) {
-            if (row < mt) {
-                v[row][0] = *(const u4*)(x + (size_t)row * d_in + p0 * 8);
-                v[row][1] = *(const u4*)(x + (size_t)row * d_in + p1 * 8);
-            }
-        }
-#pragma unroll
-        for (int row = 0; row < 4; ++row) {
-            if (row < mt) {
-                unsigned char* d = eora_smem + (size_t)row * (d_in + 32) * 2;
-                *(u4*)(d + p0 * 16) = v[row][0];
-                if (p0 + T < ppr) *(u4*)(d + p1 * 16) = v[row][1];
-            }
+    for (int row = 0; row < mt; ++row) {                  // one row at a time: few registers
+        const _Float16* src = x + (size_t)row * d_in;
+        unsigned char* d = eora_smem + (size_t)row * (d_in + 32) * 2;
+        for (int p0 = tid; p0 < ppr; p0 += 2 * T) {
+            const int p1 = p0 + T < ppr ? p0 + T : p0;
+            const u4 v0 = *(const u4*)(src + p0 * 8);
+            const u4 v1 = *(const u4*)(src + p1 * 8);
+            *(u4*)(d + p0 * 16) = v0;
+            if (p0 + T < ppr) *(u4*)(d + p1 * 16) = v1;
         }
     }
 }
 
 template <int FA, int FE, int NW, bool XLDS>
-__global__ __launch_bounds__(NW * 64) void sparse_kernel(SparseArgs a)
+__global__ __launch_bounds__(NW * 64, 6) void sparse_kernel(SparseArgs a)
 {
     constexpr bool LOWRANK = FA != S_NONE;
     constexpr int PD = 4;                                 // tiles of loads in flight per wavefront
-    __shared__ f4 red[NW][64];
-    __shared__ float redp[NW][16][16];
+    // one buffer for the cross-wavefront sums: producers and consumers are different workgroups
+    __shared__ f4 red_raw[NW][64];
+    f4 (*red)[64] = red_raw;
+    float (*redp)[16][16] = (float (*)[16][16])red_raw;
     __shared__ uint32_t s_epoch, s_ok;
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -126,12 +120,15 @@ __global__ __launch_bounds__(NW * 64) void sparse_kernel(SparseArgs a)
                     float v = 0.f;
 #pragma unroll
                     for (int w2 = 0; w2 < NW; ++w2) v += redp[w2][i][col];
-                    // partial layout: [token block][kc][token row (16)][r]; written through to memory
-                    *(volatile float*)&a.tpart[((size_t)(yb * a.kcn + kc) * 16 + i) * a.r + 16 * rho + col] = v;
+                    // partial layout: [token block][kc][token row (16)][r], every element an 8-byte
+                    // (value, epoch + 1) pair written by ONE write-through store: a reader that finds this
+                    // launch's tag has this launch's value, so the flag need not wait for acknowledgements
+                    const unsigned long long pr = ((unsigned long long)(s_epoch + 1) << 32) | __builtin_bit_cast(uint32_t, v);
+                    __hip_atomic_store(&a.tpair[((size_t)(yb * a.kcn + kc) * 16 + i) * a.r + 16 * rho + col], pr,
+                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 }
             }
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // write-through stores acknowledged
-            __syncthreads();
+            __syncthreads();                                      // all pairs are on their way
             if (tid == 0) {
                 for (int rep = 0; rep < HDR_FLAG_REPLICAS; ++rep)  // one copy per group of pollers
                     __hip_atomic_store(&a.hdr[HDR_FLAGS0 + HDR_FLAGS_REPLICA_STRIDE * rep + HDR_FLAGS_PER_BLOCK * yb + u],
@@ -161,6 +158,14 @@ __global__ __launch_bounds__(NW * 64) void sparse_kernel(SparseArgs a)
             check_in_issue(ci, a.hdr, bid);
             s_epoch = ci.epoch;
         }
+    }
+    // a first look at the flags, examined after the backbone: for all but the first workgroups on a CU the
+    // producers are done by now and the wait below costs no round trip
+    uint32_t early = 0;
+    if constexpr (LOWRANK) {
+        if (wave == 0)
+            early = ld_relaxed(a.hdr + HDR_FLAGS0 + HDR_FLAGS_REPLICA_STRIDE * (blockIdx.x % HDR_FLAG_REPLICAS) +
+                               HDR_FLAGS_PER_BLOCK * yb + (lane < units ? lane : units - 1));
     }
     if constexpr (XLDS) {
         stage_x<NW>(xg, mt, a.d_in, tid);
@@ -205,25 +210,54 @@ __global__ __launch_bounds__(NW * 64) void sparse_kernel(SparseArgs a)
         const uint32_t epoch = s_epoch;
         if (wave == 0) {
             const uint32_t* flags = a.hdr + HDR_FLAGS0 + HDR_FLAGS_REPLICA_STRIDE * (blockIdx.x % HDR_FLAG_REPLICAS) + HDR_FLAGS_PER_BLOCK * yb;
-            bool ok = false;
-            for (int spins = 0; spins <= a.spin_limit; ++spins) {
+            bool ok = units <= 64 && __all(early == epoch + 1);
+            for (int spins = 0; !ok && spins <= a.spin_limit; ++spins) {
                 bool all = true;
                 for (int f = lane; f < units; f += 64) all = all && (ld_relaxed(&flags[f]) == epoch + 1);
                 if (__all(all)) { ok = true; break; }
                 __builtin_amdgcn_s_sleep(2);
             }
             if (ok) {
-                // ordinary cached loads: the partials were written through before their flags, none of
-                // their lines is read in this launch before all flags are up, caches hold nothing older
-                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-                const int T = mt * a.r;
+                // The partials are read with ordinary (cached) loads first: the flags are up, so their stores
+                // were issued long ago and have all but certainly landed, and caches hold nothing of them from
+                // before the launch.  The tags say whether that held; a lane that finds an old tag reads again
+                // past the caches until it does (bounded).
+                const int T = mt * a.r;                  // a.r is a multiple of 32
                 for (int e = 4 * lane; e < T; e += 256) {
-                    const float* p = a.tpart + ((size_t)(yb * a.kcn) * 16) * a.r + e;     // row e / r, column e % r
-                    f4 v = {0.f, 0.f, 0.f, 0.f};
+                    const unsigned long long* p = a.tpair + ((size_t)(yb * a.kcn) * 16) * a.r + e;     // row e / r, column e % r
+                    float v0 = 0.f, v1 = 0.f, v2 = 0.f, v3 = 0.f;
+                    uint32_t bad = 0;
 #pragma unroll 4
-                    for (int kc = 0; kc < a.kcn; ++kc) v += *(const f4*)(p + (size_t)kc * 16 * a.r);   // fixed order
+                    for (int kc = 0; kc < a.kcn; ++kc) {                       // fixed order
+                        const uint2* pk = (const uint2*)(p + (size_t)kc * 16 * a.r);
+                        const uint2 p0 = pk[0], p1 = pk[1], p2 = pk[2], p3 = pk[3];      // .x value, .y tag
+                        bad |= (p0.y ^ (epoch + 1)) | (p1.y ^ (epoch + 1)) | (p2.y ^ (epoch + 1)) | (p3.y ^ (epoch + 1));
+                        v0 += __builtin_bit_cast(float, p0.x);
+                        v1 += __builtin_bit_cast(float, p1.x);
+                        v2 += __builtin_bit_cast(float, p2.x);
+                        v3 += __builtin_bit_cast(float, p3.x);
+                    }
+                    bool good = bad == 0;
+                    for (int spins = 0; !good && spins <= a.spin_limit; ++spins) {
+                        bad = 0;
+                        float w[4] = {0.f, 0.f, 0.f, 0.f};
+                        for (int kc = 0; kc < a.kcn; ++kc) {
+#pragma unroll
+                            for (int c = 0; c < 4; ++c) {
+                                const unsigned long long pr = __hip_atomic_load(p + (size_t)kc * 16 * a.r + c, __ATOMIC_RELAXED,
+                                                                                __HIP_MEMORY_SCOPE_AGENT);
+                                bad |= (uint32_t)(pr >> 32) ^ (epoch + 1);
+                                w[c] += __builtin_bit_cast(float, (uint32_t)pr);
+                            }
+                        }
+                        good = bad == 0;
+                        v0 = w[0]; v1 = w[1]; v2 = w[2]; v3 = w[3];
+                    }
+                    const f4 v = {v0, v1, v2, v3};
+                    ok = ok && good;
                     *(f4*)(ts + e) = v;
                 }
+                ok = __all(ok);
             }
             if (lane == 0) {
                 s_ok = ok ? 1u : 0u;
@@ -587,7 +621,7 @@ static hipError_t launch_sparse_one(const SparseArgs& a, hipStream_t stream)
 {
     auto kern = sparse_kernel<FA, FE, NW, XLDS>;
     const int mt = a.M < 16 ? a.M : 16;
-    const size_t lds = (XLDS ? (size_t)mt * (a.d_in + 32) * 2 : 0) + (size_t)16 * a.r * 4;
+    const size_t lds = (XLDS ? (size_t)mt * (a.d_in + 32) * 2 : 0) + (size_t)mt * a.r * 4;      // x, then t
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
@@ -601,7 +635,7 @@ static hipError_t launch_sparse_one(const SparseArgs& a, hipStream_t stream)
 hipError_t launch_sparse(const SparseArgs& a, hipStream_t stream)
 {
     // x in LDS for 1..4 tokens when it fits next to t (d_in a multiple of 512 for the 1 KiB copy chunks)
-    const bool xlds = a.M <= 4 && a.d_in % 512 == 0 && (size_t)a.M * (a.d_in + 32) * 2 + 16 * (size_t)a.r * 4 <= 150 * 1024;
+    const bool xlds = a.M <= 4 && a.d_in % 512 == 0 && (size_t)a.M * (a.d_in + 32) * 2 + a.M * (size_t)a.r * 4 <= 140 * 1024;
     // several tokens and enough row groups to fill the chip: x shared through LDS, as many token blocks
     // per workgroup (at most 4) as still leave 256 workgroups
     const int yblocks = (a.M + 15) / 16;
