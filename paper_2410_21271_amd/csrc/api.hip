@@ -74,7 +74,9 @@ int pick_kcn(int M, int d_in)
 {
     // (token blocks) x kcn <= 32: the partials' region is sized for that
     const int yblocks = ((M < CHUNK_TOKENS ? M : CHUNK_TOKENS) + 15) / 16;
-    const int cap = 32 / yblocks < MAX_KCN ? 32 / yblocks : MAX_KCN;
+    int cap = 32 / yblocks < MAX_KCN ? 32 / yblocks : MAX_KCN;
+    // with more than 4 tokens every consumer reads (tokens x r x kcn) partials: few ranges
+    if (M > 4 && cap > 4) cap = 4;
     int kcn = 1;
     for (int c = 2; c <= cap; ++c)
         if ((d_in / 128) % c == 0) kcn = c;
@@ -287,7 +289,10 @@ static int run_linear_q(const void* x, const eora_q_member& e, int M, int d_in, 
         a.group = group;
         a.kcn = kcn;
         a.spin_limit = g_spin_limit;
-        if (failed(launch_fused(a, w_bits == 4 ? S_Q4 : S_Q3, fa, fe, (hipStream_t)stream), "linear_q")) return EORA_ERR_LAUNCH;
+        const int fm = w_bits == 4 ? S_Q4 : S_Q3;
+        const hipError_t e = wide_q_fits(a.M, d_in, d_out, r) ? launch_wide_q(a, fm, fa, fe, (hipStream_t)stream)
+                                                               : launch_fused(a, fm, fa, fe, (hipStream_t)stream);
+        if (failed(e, "linear_q")) return EORA_ERR_LAUNCH;
     }
     return EORA_OK;
 }

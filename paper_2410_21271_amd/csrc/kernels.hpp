@@ -43,6 +43,10 @@ struct FusedArgs {
 
 hipError_t launch_fused(const FusedArgs& a, int fm, int fa, int fe, hipStream_t stream);
 
+// Kernel for 5 .. 127 tokens (wideq.hip): x shared through LDS by the wavefronts of a workgroup.
+bool wide_q_fits(int M, int d_in, int d_out, int r);
+hipError_t launch_wide_q(const FusedArgs& a, int fm, int fa, int fe, hipStream_t stream);
+
 // Decode kernel for 1..4 tokens (small.hip).  One launch serves up to MAX_GROUP linears that read the
 // same x (the q/k/v or the gate/up projections of a decoder layer): same d_in, rank and formats,
 // own weights, factors, output and d_out.

@@ -242,6 +242,28 @@ def test_more_config_shapes(gpu, w_bits, ab_bits, r, M, d_in, d_out):
     _check(run_linear_q(c), c.oracle_y())
 
 
+@pytest.mark.parametrize("w_bits,ab_bits,r,M,d_in,d_out,group", [
+    (4, 16, 128, 16, 2048, 8192, 128),     # 2 row blocks x 4 ranges per workgroup
+    (3, 16, 64, 37, 2048, 8208, 128),      # three token blocks (ragged), a ragged last pair of row blocks
+    (4, 4, 128, 8, 4096, 4096, 128),       # config 3 at eight tokens: 1 row block x 8 ranges, 4-bit factors
+    (4, 4, 64, 16, 4096, 4096, 128),       # 64-column tiles of B
+    (3, 16, 0, 16, 14336, 4096, 128),      # the down projection's contraction length: 1 x 4, bare
+    (3, 16, 128, 16, 14336, 1024, 128),    # few rows: the finest split, with the low-rank term
+    (4, 16, 512, 16, 2048, 4096, 128),     # the largest rank: t fills the LDS of the x slots
+    (4, 16, 32, 5, 2048, 4096, 2048),      # channel-wise groups
+    (4, 16, 128, 127, 4096, 512, 128),     # eight token blocks, the last one ragged
+])
+def test_linear_q_mid_token_counts(gpu, w_bits, ab_bits, r, M, d_in, d_out, group):
+    """The kernel for 5..127 tokens (x shared through LDS), every split of a workgroup it launches."""
+    import synth
+    from tests.cases import QCase
+    from tests.gpu_util import run_linear_q
+    c = QCase(synth.seed_for(1, d_in // 512 + r + M + d_out // 16), d_in, d_out, M, r, w_bits, group=group, ab_bits=ab_bits, packer=gpu)
+    y = run_linear_q(c)
+    _check(y, c.oracle_y())
+    assert np.array_equal(y, run_linear_q(c))
+
+
 def test_config5_shape_long_contraction(gpu):
     """BASELINE config 5, the 28672-long contraction of the 70B-shaped down projection (1024 of its rows)."""
     import synth
