@@ -321,3 +321,32 @@ def test_prefill_config4_shape_sampled_rows(gpu):
     rows = np.unique(np.concatenate([np.array([0, 1, 63, 64, 127, 128, 255, 256, 1023, 1024, 2046, 2047]),
                                      np.random.default_rng(0).integers(0, 2048, 52)]))
     _check(y[rows], c.oracle_y(rows=rows))
+
+
+@pytest.mark.parametrize("w_bits,r,M,d_in,d_out", [
+    (4, 128, 2043, 512, 16400),      # 16 token tiles (ragged) x 65 row tiles (ragged): low-rank extension
+    (3, 0, 2048, 640, 16384),        # bare, five steps (odd: both LDS buffers end the loop)
+])
+def test_prefill_gemm_large_row_tiles(gpu, w_bits, r, M, d_in, d_out):
+    """The many-token GEMM with many row tiles (as gate+up of a decoder layer at 2048 tokens), ragged in both
+    directions.  The oracle is evaluated on a seeded subset of token rows over all output columns."""
+    from tests.cases import QCase
+    from tests.gpu_util import run_linear_q
+    c = QCase(3300 + r + w_bits, d_in, d_out, M, r, w_bits, packer=gpu)
+    y = run_linear_q(c)
+    rows = np.unique(np.concatenate([np.array([0, 31, 32, 127, 128, 1023, 1024, M - 2, M - 1]),
+                                     np.random.default_rng(1).integers(0, M, 40)]))
+    _check(y[rows], c.oracle_y(rows=rows))
+
+
+def test_prefill_config4_gate_up_group_sampled_rows(gpu):
+    """BASELINE config 4, the gate and up projections (4096 -> 14336 each) as one grouped call at 2048 tokens:
+    the launch bench.py times.  Sampled token rows, all output columns of both members."""
+    import synth
+    from tests.cases import QCase
+    from tests.gpu_util import run_linear_q_group
+    cs = [QCase(synth.seed_for(4, 4 + i), 4096, 14336, 2048, 256, 4, outlier_frac=0.01, packer=gpu) for i in range(2)]
+    ys = run_linear_q_group(cs, cs[0].x)
+    rows = np.unique(np.concatenate([np.array([0, 127, 128, 2047]), np.random.default_rng(2).integers(0, 2048, 12)]))
+    for c, y in zip(cs, ys):
+        _check(y[rows], c.oracle_y(rows=rows, x=cs[0].x))
