@@ -38,6 +38,12 @@ SP24 (2:4 sparse fp16 backbone, tile = 16 rows x 128 dense columns)
     values v = 0,1 at positions p_0 < p_1.
     values:  element tile*1024 + s*512 + l*8 + 2*q + v
     indices: one uint32 per (tile, lane): bits 16*s + 4*q + 2*v .. +1 = p_v
+
+SP24Q4 (2:4 sparse backbone whose kept values are 4-bit codes, tile = 16 rows x 128 dense columns)
+    positions: the SP24 index words, unchanged.
+    codes: one uint32 per (tile, half s, lane): word tile*128 + s*64 + l holds the lane's eight kept
+    values of the half, element e = 2*q + v in nibble 4*(e % 2) + e // 2 (the Q4 nibble order).
+    zeros / scales: as for the quantised backbone, one per (row, group of `group` DENSE columns).
 """
 import numpy as np
 
@@ -259,3 +265,54 @@ def unpack_sp24(values, indices, rows, K):
     o, u = np.meshgrid(np.arange(rows), np.arange(K // 2), indexing="ij")
     ve, iw, sh = _sp24_locate(o, u, K)
     return values[ve], ((indices[iw] >> sh.astype(np.uint32)) & 3).astype(np.uint8)
+
+
+# ----------------------------------------------------------------------------
+# 2:4 sparse backbone with 4-bit kept values
+# ----------------------------------------------------------------------------
+def _sp24q4_locate(o, u, K):
+    """o: row, u: index of the kept value along the row (0 .. K/2-1).
+    Returns (code word index, code bit shift, index-word index, index bit shift)."""
+    grp, v = u // 2, u % 2
+    dense0 = 4 * grp
+    R, n = o // ROWS, o % ROWS
+    g, c = dense0 // 128, dense0 % 128
+    s, c2 = c // 64, c % 64
+    j, q = c2 // 16, (c2 % 16) // 4
+    lane = 16 * j + n
+    tile = R * (K // 128) + g
+    e = 2 * q + v
+    return tile * 128 + s * 64 + lane, 4 * (4 * (e % 2) + e // 2), tile * LANES + lane, 16 * s + 4 * q + 2 * v
+
+
+def pack_sp24q4(codes, pos):
+    """codes: uint8 rows x K/2 (4-bit codes of the kept values); pos: their positions 0..3, strictly
+    ascending within each pair.  Returns (code words uint32, index words uint32)."""
+    codes = np.asarray(codes)
+    pos = np.asarray(pos)
+    rows, half = codes.shape
+    K = 2 * half
+    _check(rows, K, 128)
+    if codes.min(initial=0) < 0 or codes.max(initial=0) > 15:
+        raise ValueError("codes must be 4-bit")
+    if pos.shape != codes.shape or pos.min(initial=0) < 0 or pos.max(initial=0) > 3:
+        raise ValueError("bad positions")
+    if np.any(pos[:, 0::2] >= pos[:, 1::2]):
+        raise ValueError("positions of a pair must be strictly ascending")
+    o, u = np.meshgrid(np.arange(rows), np.arange(half), indexing="ij")
+    cw, csh, iw, ish = _sp24q4_locate(o, u, K)
+    qvalues = np.zeros(rows * K // 128 * 8, dtype=np.uint32)       # 128 words per tile of 16 rows
+    indices = np.zeros(rows * K // 128 * 4, dtype=np.uint32)       # 64 words per tile
+    np.bitwise_or.at(qvalues, cw.ravel(), (codes.astype(np.uint32) << csh.astype(np.uint32)).ravel())
+    np.bitwise_or.at(indices, iw.ravel(), (pos.astype(np.uint32) << ish.astype(np.uint32)).ravel())
+    return qvalues, indices
+
+
+def unpack_sp24q4(qvalues, indices, rows, K):
+    qvalues = np.asarray(qvalues, dtype=np.uint32)
+    indices = np.asarray(indices, dtype=np.uint32)
+    _check(rows, K, 128)
+    o, u = np.meshgrid(np.arange(rows), np.arange(K // 2), indexing="ij")
+    cw, csh, iw, ish = _sp24q4_locate(o, u, K)
+    return (((qvalues[cw] >> csh.astype(np.uint32)) & 15).astype(np.uint8),
+            ((indices[iw] >> ish.astype(np.uint32)) & 3).astype(np.uint8))

@@ -69,6 +69,30 @@ def expand_sp24_packed(values, indices, d_in, d_out):
     return expand_sp24(vals, pos)
 
 
+def dequant_sp24q4(codes, pos, zeros, scales, group):
+    """2:4 pruned, then quantised (the combined compression of Sec. 4.2): kept value u of row o lies at
+    dense column c = 4*(u // 2) + pos and is s[o][c // group] * (q - z[o][c // group]); the pruned
+    columns are zero."""
+    q = np.asarray(codes).astype(np.float64)
+    pos = np.asarray(pos).astype(np.int64)
+    rows, half = q.shape
+    col = 4 * (np.arange(half) // 2)[None, :] + pos
+    grp = col // group
+    r_idx = np.arange(rows)[:, None]
+    z = np.asarray(zeros).astype(np.float64)[r_idx, grp]
+    s = np.asarray(scales, dtype=np.float16).astype(np.float64)[r_idx, grp]
+    dense = np.zeros((rows, 2 * half), dtype=np.float64)
+    dense[r_idx, col] = s * (q - z)
+    return dense
+
+
+def dequant_sp24q4_packed(qvalues, indices, qzeros, scales_packed, d_in, d_out, group):
+    codes, pos = layout.unpack_sp24q4(qvalues, indices, d_out, d_in)
+    NG = d_in // group
+    return dequant_sp24q4(codes, pos, layout.unpack_zeros(qzeros, d_out, NG),
+                          layout.unpack_scales(scales_packed, d_out, NG), group)
+
+
 def eora_linear(x, W_hat, A=None, B=None):
     """y = x What^T + (x A^T) B^T  (Sec. 3 forward equation; Alg. 1 step 7).
 
@@ -100,6 +124,16 @@ def eora_linear_sp24(x, values, indices, A, B, M, d_in, d_out, r):
     """Forward pass straight from the stored bytes (2:4 sparse backbone)."""
     x = np.asarray(x, dtype=np.float16).reshape(M, d_in)
     W_hat = expand_sp24_packed(values, indices, d_in, d_out)
+    if r == 0:
+        return eora_linear(x, W_hat)
+    Ad, Bd = _factors(A, B, None, None, d_in, d_out, r, 16)
+    return eora_linear(x, W_hat, Ad, Bd)
+
+
+def eora_linear_sp24q4(x, qvalues, indices, scales, qzeros, A, B, M, d_in, d_out, r, group):
+    """Forward pass straight from the stored bytes (2:4 sparse backbone with 4-bit kept values)."""
+    x = np.asarray(x, dtype=np.float16).reshape(M, d_in)
+    W_hat = dequant_sp24q4_packed(qvalues, indices, qzeros, scales, d_in, d_out, group)
     if r == 0:
         return eora_linear(x, W_hat)
     Ad, Bd = _factors(A, B, None, None, d_in, d_out, r, 16)

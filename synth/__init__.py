@@ -83,6 +83,29 @@ def prune_24(W16):
     return vals, pos
 
 
+def quantize_kept_rtn(vals, pos, group, bits=4):
+    """Round-to-nearest min/max asymmetric quantiser of the KEPT values of a 2:4-pruned matrix, per
+    (row, group of `group` dense columns); the group of a kept value is that of its dense column.
+    Returns codes u8 (rows x K/2), zeros u8 and scales fp16 (rows x K/group).  The range always
+    contains 0; the fp16-rounded scale is the one used to form the codes."""
+    vals = np.asarray(vals, dtype=np.float32)
+    rows, half = vals.shape
+    K = 2 * half
+    kept_per_group = group // 2                      # every four dense columns keep two
+    qmax = (1 << bits) - 1
+    Vg = vals.reshape(rows, K // group, kept_per_group)
+    lo = np.minimum(Vg.min(axis=2), 0.0)
+    hi = np.maximum(Vg.max(axis=2), 0.0)
+    s32 = (hi - lo) / qmax
+    s32 = np.where(s32 == 0, 1.0, s32)
+    s16 = s32.astype(np.float16)
+    s16 = np.where(s16 == 0, np.float16(1.0), s16).astype(np.float16)
+    s = s16.astype(np.float32)
+    z = np.clip(np.rint(-lo / s), 0, qmax)
+    q = np.clip(np.rint(Vg / s[:, :, None]) + z[:, :, None], 0, qmax)
+    return q.reshape(rows, half).astype(np.uint8), z.astype(np.uint8), s16
+
+
 def draw_layer(seed, d_in, d_out, M, r, outlier_frac=0.0, outlier_scale=20.0):
     """Draw (W fp32, A fp16, B fp16, x fp16) in that order from PCG64(seed)."""
     rng = np.random.default_rng(seed)

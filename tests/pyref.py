@@ -92,6 +92,29 @@ def decode_sp24(values, indices, rows, K):
     return out
 
 
+def decode_sp24q4(qvalues, indices, zeros, scales, rows, K, group):
+    """-> dense rows x K matrix of Fractions, walking the stored words: every index word names the
+    dense columns of its lane's sixteen kept values, the two code words of the lane hold their nibbles.
+    zeros / scales: decoded lists rows x K/group."""
+    out = [[Fraction(0)] * K for _ in range(rows)]
+    ntk = K // 128
+    for w, word in enumerate(int(v) for v in indices):
+        tile, lane = divmod(w, 64)
+        R, g = divmod(tile, ntk)
+        j, n = divmod(lane, 16)
+        o = 16 * R + n
+        for s in range(2):
+            cw = int(qvalues[tile * 128 + s * 64 + lane])
+            for q in range(4):
+                for v in range(2):
+                    p = (word >> (16 * s + 4 * q + 2 * v)) & 3
+                    e = 2 * q + v
+                    code = (cw >> (4 * (4 * (e % 2) + e // 2))) & 0xF
+                    col = 128 * g + 64 * s + 16 * j + 4 * q + p
+                    out[o][col] = scales[o][col // group] * (code - zeros[o][col // group])
+    return out
+
+
 def exact_forward(x, What, A=None, B=None):
     """Exact rational y = x What^T + (x A^T) B^T; inputs are lists of Fractions."""
     M, K = len(x), len(x[0])

@@ -39,6 +39,14 @@ def _run_case(kind, prm, sets, expect):
         _, words = layout.pack_sp24(vals, codes)
         _, back = layout.unpack_sp24(*layout.pack_sp24(vals, codes), rows, K)
         default = 0x44444444
+    elif kind == "sp24q4":
+        rows, K = prm["rows"], prm["K"]
+        pos = np.tile(np.array([0, 1], np.uint8), (rows, K // 4))
+        codes = np.zeros((rows, K // 2), np.uint8)
+        for o, u, c in sets:
+            codes[o, u] = c
+        words, _ = layout.pack_sp24q4(codes, pos)
+        back, _ = layout.unpack_sp24q4(*layout.pack_sp24q4(codes, pos), rows, K)
     else:
         raise AssertionError(kind)
     default = 0x44444444 if kind == "sp24" else 0
@@ -143,6 +151,59 @@ def test_sp24_roundtrip_and_word_walk():
     mask[np.arange(32)[:, None], 4 * (np.arange(128) // 2)[None, :] + pos] = True
     assert np.array_equal(dense, np.where(mask, W.astype(np.float64), 0.0))
     assert np.all(mask.reshape(32, 64, 4).sum(axis=2) == 2)
+
+
+def test_sp24q4_code_positions_by_hand():
+    # Same (row, kept index) cases as the SP24 test above; derivation in layout_misc.txt.
+    # o=3 u=37: group 18, v=1, dense col 72: tile 0, s=1, c2=8, j=0, q=2, lane 3, e=5 -> word 64+3=67, nibble 4*1+2=6
+    # o=0 u=1:  group 0, v=1: s=0, j=0, q=0, lane 0, e=1 -> word 0, nibble 4
+    # o=9 u=63: group 31, v=1, dense col 124: s=1, c2=60, j=3, q=3, lane 57, e=7 -> word 64+57=121, nibble 7
+    rows, K = 16, 128
+    pos = np.tile(np.array([0, 1], np.uint8), (rows, K // 4))
+    codes = np.zeros((rows, K // 2), np.uint8)
+    codes[3, 37] = 0xB
+    codes[0, 1] = 0x5
+    codes[9, 63] = 0xF
+    qvalues, indices = layout.pack_sp24q4(codes, pos)
+    nz = {int(i): int(qvalues[i]) for i in np.nonzero(qvalues)[0]}
+    assert nz == {67: 0xB << 24, 0: 0x5 << 16, 121: 0xF << 28}
+    # the index words are those of the fp16 format
+    _, ref_idx = layout.pack_sp24(np.zeros((rows, K // 2), np.float16), pos)
+    assert np.array_equal(indices, ref_idx)
+
+
+def test_sp24q4_roundtrip_word_walk_and_size():
+    import synth
+    rng = np.random.default_rng(12)
+    W = rng.standard_normal((32, 512)).astype(np.float16)
+    vals, pos = synth.prune_24(W)
+    codes, zeros, scales = synth.quantize_kept_rtn(vals, pos, 128)
+    qvalues, indices = layout.pack_sp24q4(codes, pos)
+    assert qvalues.size * 4 == 32 * 512 // 4 and indices.size * 4 == 32 * 512 // 8     # 0.25 + 0.125 B per dense weight
+    c2, p2 = layout.unpack_sp24q4(qvalues, indices, 32, 512)
+    assert np.array_equal(c2, codes) and np.array_equal(p2, pos)
+    from oracle import linear
+    dense = linear.dequant_sp24q4(codes, pos, zeros, scales, 128)
+    walked = pyref.decode_sp24q4(qvalues, indices, pyref.decode_zeros(layout.pack_zeros(zeros), 32, 4),
+                                 pyref.decode_scales(layout.pack_scales(scales), 32, 4), 32, 512, 128)
+    assert np.array_equal(np.array(walked, dtype=np.float64), dense)
+    # exactly two non-pruned positions per group of four (a kept value may still dequantise to zero)
+    mask = np.zeros((32, 512), bool)
+    mask[np.arange(32)[:, None], 4 * (np.arange(256) // 2)[None, :] + pos] = True
+    assert np.all(dense[~mask] == 0) and np.all(mask.reshape(32, 128, 4).sum(axis=2) == 2)
+
+
+def test_sp24q4_with_unit_scale_is_the_fp16_format():
+    """Scale 1 and zero-point 0 make the codes the kept values themselves: the dequantised matrix must be
+    the expansion of the fp16 2:4 format holding the same numbers (which has its own pins)."""
+    import synth
+    from oracle import linear
+    rng = np.random.default_rng(13)
+    W = rng.standard_normal((16, 256)).astype(np.float16)
+    _, pos = synth.prune_24(W)
+    codes = rng.integers(0, 16, (16, 128)).astype(np.uint8)
+    dense = linear.dequant_sp24q4(codes, pos, np.zeros((16, 2), np.uint8), np.ones((16, 2), np.float16), 128)
+    assert np.array_equal(dense, linear.expand_sp24(codes.astype(np.float16), pos))
 
 
 def test_pack_rejects_bad_input():

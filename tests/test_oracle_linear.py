@@ -79,6 +79,25 @@ def test_sparse_forward_exact_rational():
             assert abs(Fraction(float(y[m, o])) - e) <= abs(e) * Fraction(1, 10 ** 12) + Fraction(1, 10 ** 15)
 
 
+def test_sparse_quantised_forward_exact_rational():
+    W, A, B, x = synth.draw_layer(4, 256, 16, 2, 32)
+    vals, pos = synth.prune_24(W.astype(np.float16))
+    codes, zeros, scales = synth.quantize_kept_rtn(vals, pos, 128)
+    qvalues, indices = layout.pack_sp24q4(codes, pos)
+    qz, sc = layout.pack_zeros(zeros), layout.pack_scales(scales)
+    y = linear.eora_linear_sp24q4(x, qvalues, indices, sc, qz, layout.pack_f16(A), layout.pack_f16(B), 2, 256, 16, 32, 128)
+    What = pyref.decode_sp24q4(qvalues, indices, pyref.decode_zeros(qz, 16, 2), pyref.decode_scales(sc, 16, 2), 16, 256, 128)
+    exact = pyref.exact_forward(pyref.frac_matrix(x), What, pyref.frac_matrix(A), pyref.frac_matrix(B))
+    for m in range(2):
+        for o in range(16):
+            e = exact[m][o]
+            assert abs(Fraction(float(y[m, o])) - e) <= abs(e) * Fraction(1, 10 ** 12) + Fraction(1, 10 ** 15)
+    # the quantiser keeps every kept value within half a step of its code (a property of the generator)
+    Wd = linear.dequant_sp24q4(codes, pos, zeros, scales, 128)
+    step = np.repeat(scales.astype(np.float64), 128, axis=1)
+    assert np.all(np.abs(Wd - linear.expand_sp24(vals, pos)) <= 0.5 * step + 1e-12)
+
+
 @pytest.mark.parametrize("bits", [3, 4])
 def test_zero_factors_equal_bare_layer(bits):
     d = _tiny_q(bits, rows=32, K=256, M=4, r=32, seed=7)
