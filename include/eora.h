@@ -45,6 +45,11 @@
  *      keeps two values v = 0,1 at positions p_0 < p_1.  values: fp16 element
  *      tile*1024 + s*512 + l*8 + 2*q + v.  indices: one 32-bit word per (tile, lane), bits
  *      16*s + 4*q + 2*v .. +1 hold p_v.
+ *  SP24Q4 (2:4 sparse, kept values as 4-bit codes: pruned, then quantised, Sec. 4.2): the SP24 index
+ *      words unchanged; codes: one 32-bit word per (tile, half s, lane), word tile*128 + s*64 + l,
+ *      kept element e = 2*q + v of the lane's half in nibble 4*(e%2) + e/2; zero-points and scales as
+ *      for the quantised backbone, one per (row, group of `group` DENSE columns): a kept value at dense
+ *      column c is scale[o][c/group] * (code - zero[o][c/group]).  0.39 bytes per dense weight.
  *
  * Dequantisation (asymmetric group-wise quantisation, Sec. 4.1 and App. A.11):
  *      What[o][i] = scale[o][i/group] * (code[o][i] - zero[o][i/group])
@@ -85,6 +90,7 @@ size_t eora_qzeros_bytes(int d_in, int d_out, int group);            /* d_out*ce
 size_t eora_scales_bytes(int d_in, int d_out, int group);            /* d_out*(d_in/group)*2 */
 size_t eora_sp24_values_bytes(int d_in, int d_out);                  /* d_out*d_in          */
 size_t eora_sp24_indices_bytes(int d_in, int d_out);                 /* d_out*d_in/8        */
+size_t eora_sp24q4_codes_bytes(int d_in, int d_out);                 /* d_out*d_in/4        */
 /* Scratch the forward calls need: a header of counters, the down-projection t = x.A^T (M x r)
  * and its partial sums.  The workspace must be cleared ONCE with eora_workspace_init() before the
  * first forward call on it; every forward call leaves it usable for the next, so no per-call
@@ -128,6 +134,13 @@ int eora_pack_factor_q4(const uint8_t* codes, const uint16_t* scales, int rows, 
  * pos d_out x d_in/2 their positions 0..3 inside the group of four, strictly ascending per pair. */
 int eora_pack_sp24(const uint16_t* vals, const uint8_t* pos, int d_in, int d_out,
                    void* values_out, void* indices_out);
+/* 2:4 sparse backbone with 4-bit kept values: codes d_out x d_in/2 in 0..15 (the kept values in column
+ * order), pos as above, zeros / scales d_out x d_in/group as for eora_pack_q (the group of a kept value
+ * is that of its dense column).  indices_out takes eora_sp24_indices_bytes, qvalues_out
+ * eora_sp24q4_codes_bytes, qzeros_out / scales_out eora_qzeros_bytes / eora_scales_bytes. */
+int eora_pack_sp24q4(const uint8_t* codes, const uint8_t* pos, const uint8_t* zeros, const uint16_t* scales,
+                     int d_in, int d_out, int group,
+                     void* qvalues_out, void* indices_out, void* qzeros_out, void* scales_out);
 
 /* ---------------------------------------------------------------------------------------------
  * The layer.  Sec. 3 forward equation / Alg. 1 step 7; the fused low-rank path follows Sec. 4.5
@@ -186,6 +199,15 @@ int eora_linear_sp24(const void* x, const void* values, const void* indices,
                      int M, int d_in, int d_out, int r,
                      void* workspace, size_t workspace_bytes, void* stream);
 
+/* Same layer with a backbone that is 2:4 pruned and then quantised to 4 bits (Sec. 4.2 evaluates the
+ * combination; stored format SP24Q4 above); A, B are F16 tiles.  All pointers DEVICE.  The kept values
+ * enter the sparse MFMA as fp16(scale * (code - zero)): one fp16 rounding per weight.
+ * Constraints as for eora_linear_sp24, and group % 128 == 0, d_in % group == 0.  Errors as above. */
+int eora_linear_sp24q4(const void* x, const void* qvalues, const void* indices, const void* scales, const void* qzeros,
+                       const void* A, const void* B, void* y,
+                       int M, int d_in, int d_out, int r, int group,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
 /* ---------------------------------------------------------------------------------------------
  * Parity exports (integer / exact work, compared bit for bit against the CPU oracle).
  * ------------------------------------------------------------------------------------------ */
@@ -198,6 +220,9 @@ int eora_dequant_q(const void* qweight, const void* scales, const void* qzeros, 
 /* W_f16: d_out x d_in row-major fp16 with the pruned positions written as +0. */
 int eora_expand_sp24(const void* values, const void* indices, void* W_f16,
                      int d_in, int d_out, void* stream);
+/* W_f32: d_out x d_in row-major fp32: scale*(code-zero) at the kept positions (exact in fp32), +0 elsewhere. */
+int eora_expand_sp24q4(const void* qvalues, const void* indices, const void* scales, const void* qzeros,
+                       void* W_f32, int d_in, int d_out, int group, void* stream);
 
 #ifdef __cplusplus
 }

@@ -45,6 +45,7 @@ def _load():
         "eora_scales_bytes": (sz, [ci, ci, ci]),
         "eora_sp24_values_bytes": (sz, [ci, ci]),
         "eora_sp24_indices_bytes": (sz, [ci, ci]),
+        "eora_sp24q4_codes_bytes": (sz, [ci, ci]),
         "eora_workspace_bytes": (sz, [ci, ci, ci, ci]),
         "eora_workspace_bytes_group": (sz, [ci, ci, ci, ci]),
         "eora_workspace_init": (ci, [vp, sz, vp]),
@@ -54,12 +55,15 @@ def _load():
         "eora_pack_factor_f16": (ci, [vp, ci, ci, vp]),
         "eora_pack_factor_q4": (ci, [vp, vp, ci, ci, vp, vp]),
         "eora_pack_sp24": (ci, [vp, vp, ci, ci, vp, vp]),
+        "eora_pack_sp24q4": (ci, [vp, vp, vp, vp, ci, ci, ci, vp, vp, vp, vp]),
         "eora_linear_q": (ci, [vp] * 9 + [ci] * 7 + [vp, sz, vp]),
         "eora_linear_q_group": (ci, [vp, ctypes.POINTER(QMember), ci] + [ci] * 6 + [vp, sz, vp]),
         "eora_linear_sp24": (ci, [vp] * 6 + [ci] * 4 + [vp, sz, vp]),
+        "eora_linear_sp24q4": (ci, [vp] * 8 + [ci] * 5 + [vp, sz, vp]),
         "eora_unpack_q": (ci, [vp, vp, vp, vp, ci, ci, ci, ci, vp]),
         "eora_dequant_q": (ci, [vp, vp, vp, vp, ci, ci, ci, ci, vp]),
         "eora_expand_sp24": (ci, [vp, vp, vp, ci, ci, vp]),
+        "eora_expand_sp24q4": (ci, [vp, vp, vp, vp, vp, ci, ci, ci, vp]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(L, name)
@@ -73,7 +77,8 @@ EXPORTS = ["eora_status_string", "eora_qweight_bytes", "eora_qzeros_bytes", "eor
            "eora_sp24_values_bytes", "eora_sp24_indices_bytes", "eora_workspace_bytes", "eora_workspace_bytes_group", "eora_workspace_init",
            "eora_workspace_error", "eora_debug_set_spin_limit", "eora_pack_q",
            "eora_pack_factor_f16", "eora_pack_factor_q4", "eora_pack_sp24", "eora_linear_q",
-           "eora_linear_q_group", "eora_linear_sp24", "eora_unpack_q", "eora_dequant_q", "eora_expand_sp24"]
+           "eora_linear_q_group", "eora_linear_sp24", "eora_unpack_q", "eora_dequant_q", "eora_expand_sp24",
+           "eora_sp24q4_codes_bytes", "eora_pack_sp24q4", "eora_linear_sp24q4", "eora_expand_sp24q4"]
 
 
 def status_string(status):
@@ -104,6 +109,10 @@ def sp24_values_bytes(d_in, d_out):
 
 def sp24_indices_bytes(d_in, d_out):
     return lib.eora_sp24_indices_bytes(d_in, d_out)
+
+
+def sp24q4_codes_bytes(d_in, d_out):
+    return lib.eora_sp24q4_codes_bytes(d_in, d_out)
 
 
 def workspace_bytes(M, d_in, d_out, r):
@@ -160,6 +169,26 @@ def pack_sp24(vals, pos):
     _check(lib.eora_pack_sp24(_np_ptr(vals), _np_ptr(pos), d_in, d_out, _np_ptr(values), _np_ptr(indices)),
            "pack_sp24")
     return values, indices
+
+
+def pack_sp24q4(codes, pos, zeros, scales, group):
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    pos = np.ascontiguousarray(pos, dtype=np.uint8)
+    zeros = np.ascontiguousarray(zeros, dtype=np.uint8)
+    scales = np.ascontiguousarray(scales, dtype=np.float16)
+    d_out, half = codes.shape
+    d_in = 2 * half
+    nq, ni = sp24q4_codes_bytes(d_in, d_out), sp24_indices_bytes(d_in, d_out)
+    nz, ns = qzeros_bytes(d_in, d_out, group), scales_bytes(d_in, d_out, group)
+    if not (nq and ni and nz and ns) or pos.shape != codes.shape or zeros.shape != (d_out, d_in // group) or scales.shape != zeros.shape:
+        raise EoraError(-2, "pack_sp24q4")
+    qv = np.empty(nq // 4, np.uint32)
+    idx = np.empty(ni // 4, np.uint32)
+    qz = np.empty(nz // 4, np.uint32)
+    sc = np.empty(ns // 2, np.float16)
+    _check(lib.eora_pack_sp24q4(_np_ptr(codes), _np_ptr(pos), _np_ptr(zeros), _np_ptr(scales), d_in, d_out, group,
+                                _np_ptr(qv), _np_ptr(idx), _np_ptr(qz), _np_ptr(sc)), "pack_sp24q4")
+    return qv, idx, qz, sc
 
 
 # ------------------------------------------------------------------ device entry points (torch tensors as memory)
@@ -224,6 +253,12 @@ def linear_sp24(x, values, indices, A, B, y, M, d_in, d_out, r, workspace):
                                 _dp(workspace), ws_bytes, _stream()), "linear_sp24")
 
 
+def linear_sp24q4(x, qvalues, indices, scales, qzeros, A, B, y, M, d_in, d_out, r, group, workspace):
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib.eora_linear_sp24q4(_dp(x), _dp(qvalues), _dp(indices), _dp(scales), _dp(qzeros), _dp(A), _dp(B), _dp(y),
+                                  M, d_in, d_out, r, group, _dp(workspace), ws_bytes, _stream()), "linear_sp24q4")
+
+
 def unpack_q(qweight, qzeros, codes_u8, zeros_u8, d_in, d_out, w_bits, group):
     _check(lib.eora_unpack_q(_dp(qweight), _dp(qzeros), _dp(codes_u8), _dp(zeros_u8), d_in, d_out, w_bits, group,
                              _stream()), "unpack_q")
@@ -236,3 +271,8 @@ def dequant_q(qweight, scales, qzeros, W_f32, d_in, d_out, w_bits, group):
 
 def expand_sp24(values, indices, W_f16, d_in, d_out):
     _check(lib.eora_expand_sp24(_dp(values), _dp(indices), _dp(W_f16), d_in, d_out, _stream()), "expand_sp24")
+
+
+def expand_sp24q4(qvalues, indices, scales, qzeros, W_f32, d_in, d_out, group):
+    _check(lib.eora_expand_sp24q4(_dp(qvalues), _dp(indices), _dp(scales), _dp(qzeros), _dp(W_f32), d_in, d_out, group,
+                                  _stream()), "expand_sp24q4")

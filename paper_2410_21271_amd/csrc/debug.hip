@@ -78,6 +78,41 @@ __global__ void expand_sp24_kernel(const _Float16* __restrict__ values, const ui
         }
 }
 
+// 2:4 sparse with 4-bit kept values -> dense fp32: scale*(code - zero) at the kept positions (exact in
+// fp32), +0 elsewhere.  One thread per (tile, lane), plain shifts and masks.
+__global__ void expand_sp24q4_kernel(const uint32_t* __restrict__ qvalues, const uint32_t* __restrict__ indices,
+                                     const _Float16* __restrict__ scales, const uint32_t* __restrict__ qzeros,
+                                     float* __restrict__ W, int d_in, int d_out, int group)
+{
+    const size_t L = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t nlanes = (size_t)d_out * d_in / 32;
+    if (L >= nlanes) return;
+    const int ntk = d_in / 128;
+    const size_t tile = L / 64;
+    const int lane = (int)(L % 64);
+    const int R = (int)(tile / ntk), g = (int)(tile % ntk);
+    const int j = lane >> 4, n = lane & 15;
+    const int NG = d_in / group, NGW = (NG + 7) / 8, grp = (128 * g) / group;
+    const size_t row = (size_t)16 * R + n;
+    const float sc = (float)scales[row * NG + grp];
+    const int z = (int)((qzeros[row * NGW + (grp >> 3)] >> (4 * (grp & 7))) & 0xFu);
+    const uint32_t word = indices[L];
+    for (int s = 0; s < 2; ++s) {
+        const uint32_t cw = qvalues[tile * 128 + s * 64 + lane];
+        for (int q = 0; q < 4; ++q) {
+            float out[4] = {0.f, 0.f, 0.f, 0.f};
+            for (int v = 0; v < 2; ++v) {
+                const int p = (word >> (16 * s + 4 * q + 2 * v)) & 3;
+                const int e = 2 * q + v;
+                const int code = (int)((cw >> (4 * (4 * (e % 2) + e / 2))) & 0xFu);
+                out[p] = sc * (float)(code - z);
+            }
+            float* dst = W + row * d_in + 128 * g + 64 * s + 16 * j + 4 * q;
+            for (int p = 0; p < 4; ++p) dst[p] = out[p];
+        }
+    }
+}
+
 static dim3 grid_for(size_t nlanes) { return dim3((unsigned)((nlanes + 255) / 256)); }
 
 hipError_t launch_unpack_q(const uint32_t* qweight, const uint32_t* qzeros, uint8_t* codes, uint8_t* zeros,
@@ -103,6 +138,15 @@ hipError_t launch_expand_sp24(const _Float16* values, const uint32_t* indices, _
 {
     const size_t nlanes = (size_t)d_out * d_in / 32;
     hipLaunchKernelGGL(expand_sp24_kernel, grid_for(nlanes), dim3(256), 0, stream, values, indices, W, d_in, d_out);
+    return hipGetLastError();
+}
+
+hipError_t launch_expand_sp24q4(const uint32_t* qvalues, const uint32_t* indices, const _Float16* scales,
+                                const uint32_t* qzeros, float* W, int d_in, int d_out, int group, hipStream_t stream)
+{
+    const size_t nlanes = (size_t)d_out * d_in / 32;
+    hipLaunchKernelGGL(expand_sp24q4_kernel, grid_for(nlanes), dim3(256), 0, stream, qvalues, indices, scales, qzeros, W,
+                       d_in, d_out, group);
     return hipGetLastError();
 }
 

@@ -184,6 +184,60 @@ int eora_pack_sp24(const uint16_t* vals, const uint8_t* pos, int d_in, int d_out
     return EORA_OK;
 }
 
+size_t eora_sp24q4_codes_bytes(int d_in, int d_out)
+{
+    return shape_ok(d_out, d_in, 128) ? (size_t)d_out * d_in / 4 : 0;
+}
+
+int eora_pack_sp24q4(const uint8_t* codes, const uint8_t* pos, const uint8_t* zeros, const uint16_t* scales,
+                     int d_in, int d_out, int group,
+                     void* qvalues_out, void* indices_out, void* qzeros_out, void* scales_out)
+{
+    if (!codes || !pos || !zeros || !scales || !qvalues_out || !indices_out || !qzeros_out || !scales_out) return EORA_ERR_NULL;
+    if (!shape_ok(d_out, d_in, 128) || group <= 0 || group % 128 || d_in % group) return EORA_ERR_SHAPE;
+    const int NG = d_in / group;
+    for (size_t i = 0; i < (size_t)d_out * NG; ++i)
+        if (zeros[i] > 15) return EORA_ERR_VALUE;
+    uint32_t* qo = (uint32_t*)qvalues_out;
+    uint32_t* io = (uint32_t*)indices_out;
+    const int ntk = d_in / 128, half = d_in / 2;
+    const size_t nlanes = (size_t)d_out * d_in / 32;         // one index word and two code words per (tile, lane)
+    for (size_t L = 0; L < nlanes; ++L) {
+        const size_t tile = L / 64;
+        const int lane = (int)(L % 64);
+        const int R = (int)(tile / ntk), g = (int)(tile % ntk);
+        const int j = lane / 16, n = lane % 16;
+        uint32_t word = 0;
+        for (int s = 0; s < 2; ++s) {
+            uint32_t cw = 0;
+            for (int q = 0; q < 4; ++q) {
+                const int dense0 = 128 * g + 64 * s + 16 * j + 4 * q;
+                const size_t u = (size_t)(16 * R + n) * half + dense0 / 2;
+                if (pos[u] > 3 || pos[u + 1] > 3 || pos[u] >= pos[u + 1]) return EORA_ERR_VALUE;
+                for (int v = 0; v < 2; ++v) {
+                    if (codes[u + v] > 15) return EORA_ERR_VALUE;
+                    const int e = 2 * q + v;
+                    word |= (uint32_t)pos[u + v] << (16 * s + 4 * q + 2 * v);
+                    cw |= (uint32_t)codes[u + v] << (4 * (4 * (e % 2) + e / 2));
+                }
+            }
+            qo[tile * 128 + s * 64 + lane] = cw;
+        }
+        io[L] = word;
+    }
+    uint32_t* zw = (uint32_t*)qzeros_out;
+    const int NGW = (NG + 7) / 8;
+    for (int row = 0; row < d_out; ++row)
+        for (int wq = 0; wq < NGW; ++wq) {
+            uint32_t w = 0;
+            for (int e = 0; e < 8 && 8 * wq + e < NG; ++e)
+                w |= (uint32_t)zeros[(size_t)row * NG + 8 * wq + e] << (4 * e);
+            zw[(size_t)row * NGW + wq] = w;
+        }
+    pack_scale_tiles(scales, d_out, NG, (uint16_t*)scales_out);
+    return EORA_OK;
+}
+
 const char* eora_status_string(int status)
 {
     switch (status) {

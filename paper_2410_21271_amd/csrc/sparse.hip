@@ -19,23 +19,64 @@
 
 namespace eora {
 
-struct SpTile {
+// one stored tile of a wavefront.  VQ: the kept values are 4-bit codes (Sec. 4.2: pruned, then quantised)
+template <bool VQ> struct SpT;
+template <> struct SpT<false> {
     u4 v0, v1;        // kept values of the two 64-column blocks
     uint32_t idx;     // positions: low 16 bits block 0, high 16 bits block 1
+};
+template <> struct SpT<true> {
+    uint32_t c0, c1;  // eight codes per block, element e = 2q + v in nibble 4(e%2) + e/2
+    uint32_t idx;
+    uint32_t zraw;    // the word that holds the zero-point nibble of (row n, group)
+    uint32_t sraw;    // fp16 scale bits
+    int zshift;
 };
 
 typedef _Float16 h16 __attribute__((ext_vector_type(16)));
 
-__device__ __forceinline__ void load_sptile(SpTile& t, const _Float16* __restrict__ values,
-                                            const uint32_t* __restrict__ indices, size_t tile, int lane)
+// tile g of row block R (G tiles per row block).  Nothing loaded is touched here.
+template <bool VQ>
+__device__ __forceinline__ void load_sptile(SpT<VQ>& t, const SparseArgs& a, int R, int g, int G, int lane)
 {
-    t.idx = indices[tile * 64 + lane];
-    const u4* p = (const u4*)(values + tile * 1024) + lane;
-    t.v0 = p[0];
-    t.v1 = p[64];
+    const size_t tile = (size_t)R * G + g;
+    t.idx = a.indices[tile * 64 + lane];
+    if constexpr (!VQ) {
+        const u4* p = (const u4*)(a.values + tile * 1024) + lane;
+        t.v0 = p[0];
+        t.v1 = p[64];
+    } else {
+        const uint32_t* p = a.qvalues + tile * 128 + lane;
+        t.c0 = p[0];
+        t.c1 = p[64];
+        const int gdiv = a.group >> 7, grp = gdiv == 1 ? g : g / gdiv, NG = a.d_in / a.group;
+        const size_t row = (size_t)R * 16 + (lane & 15);
+        t.sraw = ((const uint16_t*)a.w_scales)[row * NG + grp];
+        t.zraw = a.w_zeros[row * ((NG + 7) / 8) + (grp >> 3)];
+        t.zshift = 4 * (grp & 7);
+    }
 }
 
 __device__ __forceinline__ h8 as_h8(u4 v) { return __builtin_bit_cast(h8, v); }
+
+// the sparse operands of the tile's two blocks.  Quantised: code - zero exact, times the fp16 group scale
+// (one fp16 rounding of scale*(code - zero), relative error <= 2^-11 per weight: the accumulator holds four
+// rows per lane, so scaling it per group instead would need four row scales per lane and tile).
+template <bool VQ>
+__device__ __forceinline__ void sp_operands(const SpT<VQ>& t, h8& a0, h8& a1)
+{
+    if constexpr (!VQ) {
+        a0 = as_h8(t.v0);
+        a1 = as_h8(t.v1);
+    } else {
+        const uint32_t z = (t.zraw >> t.zshift) & 0xFu;
+        const uint32_t c1024 = k1024(z), c64 = k64(z);
+        const _Float16 sc = __builtin_bit_cast(_Float16, (uint16_t)t.sraw);
+        const h8 sv = {sc, sc, sc, sc, sc, sc, sc, sc};
+        a0 = dq4_word(t.c0, c1024, c64) * sv;
+        a1 = dq4_word(t.c1, c1024, c64) * sv;
+    }
+}
 
 // the token block's x (mt <= 4 rows of d_in fp16) -> LDS, rows padded by 64 bytes, through registers: all
 // requests of the kernel stay plain loads (with global -> LDS copies among them the compiler no longer counts
@@ -58,7 +99,7 @@ __device__ __forceinline__ void stage_x(const _Float16* __restrict__ x, int mt, 
     }
 }
 
-template <int FA, int FE, int NW, bool XLDS>
+template <int FA, int FE, int NW, bool XLDS, bool VQ>
 __global__ __launch_bounds__(NW * 64, 6) void sparse_kernel(SparseArgs a)
 {
     constexpr bool LOWRANK = FA != S_NONE;
@@ -146,10 +187,10 @@ __global__ __launch_bounds__(NW * 64, 6) void sparse_kernel(SparseArgs a)
     // step s of this wavefront is stored tile wave + s NW of the row block; requests past the end fetch the
     // last one again (never used): every step issues the same requests, refilled into the registers just used
     const int last = nsteps > 0 ? nsteps - 1 : 0;
-    const size_t tile0 = (size_t)R * G + (nsteps > 0 ? wave : 0);
-    SpTile buf[PD];
+    const int g_first = nsteps > 0 ? wave : 0;
+    SpT<VQ> buf[PD];
 #pragma unroll
-    for (int s = 0; s < PD; ++s) load_sptile(buf[s], a.values, a.indices, tile0 + (size_t)(s < nsteps ? s : last) * NW, lane);
+    for (int s = 0; s < PD; ++s) load_sptile<VQ>(buf[s], a, R, g_first + (s < nsteps ? s : last) * NW, G, lane);
     const Factor fb{(const uint32_t*)a.B, nullptr, LOWRANK ? a.r / 32 : 0};
     FTile<S_F16> bpre;
     if constexpr (LOWRANK) load_ftile<S_F16>(bpre, fb, R, wave < fb.ntk ? wave : 0, lane);
@@ -181,6 +222,8 @@ __global__ __launch_bounds__(NW * 64, 6) void sparse_kernel(SparseArgs a)
         for (int s = 0; s < PD; ++s) {
             if (base + s < nsteps) {
                 const int g = wave + (base + s) * NW;
+                h8 sa[2];
+                sp_operands<VQ>(buf[s], sa[0], sa[1]);
 #pragma unroll
                 for (int blk = 0; blk < 2; ++blk) {
                     h8 x0, x1;
@@ -195,13 +238,13 @@ __global__ __launch_bounds__(NW * 64, 6) void sparse_kernel(SparseArgs a)
                         x1 = *(const h8*)(px + 32);
                     }
                     const h16 xb = __builtin_shufflevector(x0, x1, 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15);
-                    if (blk == 0) acc = __builtin_amdgcn_smfmac_f32_16x16x64_f16(as_h8(buf[s].v0), xb, acc, (int)buf[s].idx, 0, 0);
-                    else acc = __builtin_amdgcn_smfmac_f32_16x16x64_f16(as_h8(buf[s].v1), xb, acc, (int)buf[s].idx, 0, 1);
+                    if (blk == 0) acc = __builtin_amdgcn_smfmac_f32_16x16x64_f16(sa[0], xb, acc, (int)buf[s].idx, 0, 0);
+                    else acc = __builtin_amdgcn_smfmac_f32_16x16x64_f16(sa[1], xb, acc, (int)buf[s].idx, 0, 1);
                 }
             }
             __builtin_amdgcn_sched_barrier(0);
             const int sn = base + s + PD;
-            load_sptile(buf[s], a.values, a.indices, tile0 + (size_t)(sn < nsteps ? sn : last) * NW, lane);
+            load_sptile<VQ>(buf[s], a, R, g_first + (sn < nsteps ? sn : last) * NW, G, lane);
         }
     }
 
@@ -322,7 +365,7 @@ __global__ __launch_bounds__(NW * 64, 6) void sparse_kernel(SparseArgs a)
 // LDS slot layout: 16-byte piece q of token row t (columns 8q .. 8q+7 of the chunk) sits at piece index
 // 16 t + (q ^ (t & 15)): the 16 lanes that read one q for 16 tokens hit 16 different bank groups.
 // Producers, flags, partials and the continuation are those of the kernel above.
-template <int FA, int NW, int TB, int XW_D>      // XW_D: steps between a request and its use; divides d_in / 128
+template <int FA, int NW, int TB, int XW_D, bool VQ>      // XW_D: steps between a request and its use; divides d_in / 128
 __global__ __launch_bounds__(NW * 64) void sparse_wide_kernel(SparseArgs a)
 {
     constexpr bool LOWRANK = FA != S_NONE;
@@ -406,14 +449,8 @@ __global__ __launch_bounds__(NW * 64) void sparse_wide_kernel(SparseArgs a)
         xsrc[i] = a.x + (size_t)grow * a.d_in + 8 * (lane & 15);
         xdst[i] = (trow * 16 + ((lane & 15) ^ (trow & 15))) * 16;
     }
-    const uint32_t* ibase = a.indices + (size_t)R * G * 64 + lane;
-    const u4* vbase = (const u4*)(a.values + (size_t)R * G * 1024) + lane;
-    auto load_tile = [&](SpTile& t, int c) {
-        t.idx = ibase[c * 64];
-        t.v0 = vbase[c * 128];
-        t.v1 = vbase[c * 128 + 64];
-    };
-    SpTile buf[XW_D];
+    auto load_tile = [&](SpT<VQ>& t, int c) { load_sptile<VQ>(t, a, R, c, G, lane); };
+    SpT<VQ> buf[XW_D];
     u4 xr[XW_D][XN];
 #pragma unroll
     for (int s = 0; s < XW_D; ++s) {                      // G is a multiple of XW_D
@@ -459,6 +496,8 @@ __global__ __launch_bounds__(NW * 64) void sparse_wide_kernel(SparseArgs a)
             }
             __builtin_amdgcn_sched_barrier(0);
             const unsigned char* xs = eora_smem + (c & 1) * SLOT;
+            h8 sa0, sa1;
+            sp_operands<VQ>(buf[s], sa0, sa1);
 #pragma unroll
             for (int tb = 0; tb < TB; ++tb) {
                 const unsigned char* px = xs + tb * 4096;
@@ -466,8 +505,8 @@ __global__ __launch_bounds__(NW * 64) void sparse_wide_kernel(SparseArgs a)
                 const h8 x10 = *(const h8*)(px + poff[2]), x11 = *(const h8*)(px + poff[3]);
                 const h16 xa = __builtin_shufflevector(x00, x01, 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15);
                 const h16 xb = __builtin_shufflevector(x10, x11, 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15);
-                acc[tb] = __builtin_amdgcn_smfmac_f32_16x16x64_f16(as_h8(buf[s].v0), xa, acc[tb], (int)buf[s].idx, 0, 0);
-                acc[tb] = __builtin_amdgcn_smfmac_f32_16x16x64_f16(as_h8(buf[s].v1), xb, acc[tb], (int)buf[s].idx, 0, 1);
+                acc[tb] = __builtin_amdgcn_smfmac_f32_16x16x64_f16(sa0, xa, acc[tb], (int)buf[s].idx, 0, 0);
+                acc[tb] = __builtin_amdgcn_smfmac_f32_16x16x64_f16(sa1, xb, acc[tb], (int)buf[s].idx, 0, 1);
             }
             // the tile's registers are free again: the request for the tile XW_D chunks on goes out last
             __builtin_amdgcn_sched_barrier(0);
@@ -588,10 +627,10 @@ __global__ __launch_bounds__(NW * 64) void sparse_wide_kernel(SparseArgs a)
 
 constexpr int WIDE_NW = 4;
 
-template <int FA, int TB, int XW_D>
+template <int FA, int TB, int XW_D, bool VQ>
 static hipError_t launch_sparse_wide(const SparseArgs& a, hipStream_t stream)
 {
-    auto kern = sparse_wide_kernel<FA, WIDE_NW, TB, XW_D>;
+    auto kern = sparse_wide_kernel<FA, WIDE_NW, TB, XW_D, VQ>;
     const size_t xb = (size_t)2 * TB * 4096, tb = (size_t)16 * a.r * 4;
     const size_t lds = xb > tb ? xb : tb;
     if (lds > 48 * 1024) {
@@ -605,21 +644,21 @@ static hipError_t launch_sparse_wide(const SparseArgs& a, hipStream_t stream)
     return hipGetLastError();
 }
 
-template <int FA>
+template <int FA, bool VQ>
 static hipError_t launch_sparse_wide_tb(const SparseArgs& a, int tb, hipStream_t stream)
 {
     switch (tb) {
-    case 1: return launch_sparse_wide<FA, 1, 4>(a, stream);
-    case 2: return launch_sparse_wide<FA, 2, 4>(a, stream);
-    case 3: return launch_sparse_wide<FA, 3, 4>(a, stream);
-    default: return launch_sparse_wide<FA, 4, 4>(a, stream);
+    case 1: return launch_sparse_wide<FA, 1, 4, VQ>(a, stream);
+    case 2: return launch_sparse_wide<FA, 2, 4, VQ>(a, stream);
+    case 3: return launch_sparse_wide<FA, 3, 4, VQ>(a, stream);
+    default: return launch_sparse_wide<FA, 4, 4, VQ>(a, stream);
     }
 }
 
-template <int FA, int FE, int NW, bool XLDS>
+template <int FA, int FE, int NW, bool XLDS, bool VQ>
 static hipError_t launch_sparse_one(const SparseArgs& a, hipStream_t stream)
 {
-    auto kern = sparse_kernel<FA, FE, NW, XLDS>;
+    auto kern = sparse_kernel<FA, FE, NW, XLDS, VQ>;
     const int mt = a.M < 16 ? a.M : 16;
     const size_t lds = (XLDS ? (size_t)mt * (a.d_in + 32) * 2 : 0) + (size_t)mt * a.r * 4;      // x, then t
     if (lds > 48 * 1024) {
@@ -632,7 +671,8 @@ static hipError_t launch_sparse_one(const SparseArgs& a, hipStream_t stream)
     return hipGetLastError();
 }
 
-hipError_t launch_sparse(const SparseArgs& a, hipStream_t stream)
+template <bool VQ>
+static hipError_t launch_sparse_vq(const SparseArgs& a, hipStream_t stream)
 {
     // x in LDS for 1..4 tokens when it fits next to t (d_in a multiple of 512 for the 1 KiB copy chunks)
     const bool xlds = a.M <= 4 && a.d_in % 512 == 0 && (size_t)a.M * (a.d_in + 32) * 2 + a.M * (size_t)a.r * 4 <= 140 * 1024;
@@ -644,11 +684,16 @@ hipError_t launch_sparse(const SparseArgs& a, hipStream_t stream)
         int tb = yblocks < 4 ? yblocks : 4;
         while (tb > 1 && nrg * ((yblocks + tb - 1) / tb) < 256) tb = (tb + 1) / 2;
         if (nrg * ((yblocks + tb - 1) / tb) >= 256)
-            return a.r == 0 ? launch_sparse_wide_tb<S_NONE>(a, tb, stream) : launch_sparse_wide_tb<S_F16>(a, tb, stream);
+            return a.r == 0 ? launch_sparse_wide_tb<S_NONE, VQ>(a, tb, stream) : launch_sparse_wide_tb<S_F16, VQ>(a, tb, stream);
     }
-    if (a.r == 0) return xlds ? launch_sparse_one<S_NONE, S_NONE, 8, true>(a, stream)
-                              : launch_sparse_one<S_NONE, S_NONE, 8, false>(a, stream);
-    return xlds ? launch_sparse_one<S_F16, S_F16, 8, true>(a, stream) : launch_sparse_one<S_F16, S_F16, 8, false>(a, stream);
+    if (a.r == 0) return xlds ? launch_sparse_one<S_NONE, S_NONE, 8, true, VQ>(a, stream)
+                              : launch_sparse_one<S_NONE, S_NONE, 8, false, VQ>(a, stream);
+    return xlds ? launch_sparse_one<S_F16, S_F16, 8, true, VQ>(a, stream) : launch_sparse_one<S_F16, S_F16, 8, false, VQ>(a, stream);
+}
+
+hipError_t launch_sparse(const SparseArgs& a, hipStream_t stream)
+{
+    return a.qvalues ? launch_sparse_vq<true>(a, stream) : launch_sparse_vq<false>(a, stream);
 }
 
 }  // namespace eora

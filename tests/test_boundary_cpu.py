@@ -34,6 +34,9 @@ def test_host_packers_match_oracle_bytes(w_bits, ab_bits, r):
 
 def test_sparse_packer_matches_oracle_bytes():
     SparseCase(7, 256, 32, 1, 32, packer=eora)
+    from tests.cases import SparseQCase
+    SparseQCase(8, 512, 32, 1, 32, packer=eora)             # host packer = oracle layout, word for word
+    SparseQCase(9, 512, 32, 1, 0, group=256, packer=eora)
 
 
 def test_sizes():
@@ -44,6 +47,7 @@ def test_sizes():
     assert eora.scales_bytes(4096, 4096, 128) == 4096 * 32 * 2
     assert eora.sp24_values_bytes(8192, 1024) == 8192 * 1024
     assert eora.sp24_indices_bytes(8192, 1024) == 8192 * 1024 // 8
+    assert eora.sp24q4_codes_bytes(8192, 1024) == 8192 * 1024 // 4 and eora.sp24q4_codes_bytes(8192, 1000) == 0
     assert eora.qweight_bytes(4096, 4100, 4) == 0 and eora.qweight_bytes(4096, 4096, 5) == 0
     assert eora.workspace_bytes(1, 4096, 4096, 128) >= 4 * 128
     assert eora.workspace_bytes(1, 4096, 4096, 1024) == 0
@@ -65,6 +69,13 @@ def test_packers_reject_bad_values():
         eora.pack_sp24(np.zeros((16, 64), np.float16), np.zeros((16, 64), np.uint8))
     with pytest.raises(eora.EoraError):
         eora.pack_factor_f16(np.zeros((8, 32), np.float16))
+    pos = np.tile(np.array([0, 1], np.uint8), (16, 32))
+    c4 = np.zeros((16, 64), np.uint8)
+    eora.pack_sp24q4(c4, pos, np.zeros((16, 1), np.uint8), np.ones((16, 1), np.float16), 128)
+    c4[2, 7] = 16
+    with pytest.raises(eora.EoraError) as ei:
+        eora.pack_sp24q4(c4, pos, np.zeros((16, 1), np.uint8), np.ones((16, 1), np.float16), 128)
+    assert ei.value.status == -7
 
 
 def test_linear_q_validation_codes():
@@ -112,4 +123,13 @@ def test_linear_q_validation_codes():
     assert L.eora_unpack_q(good, good, good, good, 256, 32, 5, 128, null) == -3
     assert L.eora_dequant_q(good, good, good, null, 256, 32, 4, 128, null) == -1
     assert L.eora_expand_sp24(good, odd, good, 256, 32, null) == -4
+    sq = L.eora_linear_sp24q4
+    assert sq(good, null, good, good, good, good, good, good, 1, 256, 32, 32, 128, good, 1 << 24, null) == -1
+    assert sq(good, good, good, good, good, good, good, good, 1, 256, 32, 32, 64, good, 1 << 24, null) == -2
+    assert sq(good, good, good, good, good, good, good, good, 1, 256, 32, 32, 384, good, 1 << 24, null) == -2
+    assert sq(good, odd, good, good, good, good, good, good, 1, 256, 32, 32, 128, good, 1 << 24, null) == -4
+    assert sq(good, good, good, good, good, good, good, good, 1, 256, 32, 32, 128, good, 16, null) == -5
+    assert sq(good, good, good, good, good, good, good, good, 0, 256, 32, 32, 128, good, 1 << 24, null) == 0
+    assert L.eora_expand_sp24q4(good, good, good, good, null, 256, 32, 128, null) == -1
+    assert L.eora_expand_sp24q4(good, good, good, good, good, 256, 32, 96, null) == -2
     assert eora.status_string(-4) == "misaligned pointer"

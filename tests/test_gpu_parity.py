@@ -350,3 +350,43 @@ def test_prefill_config4_gate_up_group_sampled_rows(gpu):
     rows = np.unique(np.concatenate([np.array([0, 127, 128, 2047]), np.random.default_rng(2).integers(0, 2048, 12)]))
     for c, y in zip(cs, ys):
         _check(y[rows], c.oracle_y(rows=rows, x=cs[0].x))
+
+
+def test_expand_sp24q4_bit_exact(gpu):
+    """Unpack + dequantise + expand of the 2:4 + 4-bit format: scale*(code - zero) is exact in fp32."""
+    import torch
+    from tests.cases import SparseQCase
+    from tests.gpu_util import dev
+    from oracle import linear
+    for group in (128, 384):
+        c = SparseQCase(31 + group, 768, 80, 1, 0, group=group, packer=gpu)
+        W = torch.full((80, 768), 7.0, dtype=torch.float32, device="cuda")
+        gpu.expand_sp24q4(dev(c.qvalues), dev(c.indices), dev(c.sc), dev(c.qz), W, 768, 80, group)
+        torch.cuda.synchronize()
+        ref = linear.dequant_sp24q4_packed(c.o_qvalues, c.o_indices, c.o_qz, c.o_sc, 768, 80, group)
+        assert np.array_equal(W.cpu().numpy().astype(np.float64), ref)
+
+
+@pytest.mark.parametrize("r,M,d_in,d_out,group", [
+    (0, 1, 1024, 112, 128), (32, 1, 1024, 112, 128), (128, 2, 1024, 112, 256), (64, 4, 640, 48, 128),
+    (32, 5, 1024, 112, 128), (96, 16, 1024, 112, 1024), (64, 37, 1024, 5488, 128), (128, 64, 2048, 4096, 128),
+])
+def test_linear_sp24q4_shapes(gpu, r, M, d_in, d_out, group):
+    """The layer on the 2:4 + 4-bit backbone: the decode kernel (x in LDS or from global memory), coarser
+    groups, and the kernel for many tokens and rows."""
+    from tests.cases import SparseQCase
+    from tests.gpu_util import run_linear_sp24q4
+    c = SparseQCase(2600 + r + M, d_in, d_out, M, r, group=group, packer=gpu)
+    y = run_linear_sp24q4(c)
+    _check(y, c.oracle_y())
+    assert np.array_equal(y, run_linear_sp24q4(c))
+
+
+@pytest.mark.parametrize("M", [1, 64])
+def test_sp24q4_70b_shape_k_projection(gpu, M):
+    """The 8192 -> 1024 linear of a 70B-shaped layer at full size on the 2:4 + 4-bit backbone."""
+    import synth
+    from tests.cases import SparseQCase
+    from tests.gpu_util import run_linear_sp24q4
+    c = SparseQCase(synth.seed_for(5, 11), 8192, 1024, M, 128, packer=gpu)
+    _check(run_linear_sp24q4(c), c.oracle_y())
