@@ -37,6 +37,10 @@ WORKLOADS = {
     "llama3-70b-layer-decode-sp24-r128fp16-M1": dict(model="70b", w_bits=0, ab_bits=16, r=128, M=1, cfg=5),
     "llama3-70b-layer-decode-sp24-bare-M1": dict(model="70b", w_bits=0, ab_bits=16, r=0, M=1, cfg=5),
     "llama3-70b-layer-decode-sp24-r128fp16-M64": dict(model="70b", w_bits=0, ab_bits=16, r=128, M=64, cfg=5),
+    # 2:4 pruned, then the kept values quantised to 4 bits (the paper's combined compression)
+    "llama3-70b-layer-decode-sp24q4-r128fp16-M1": dict(model="70b", w_bits=0, sq=True, ab_bits=16, r=128, M=1, cfg=5),
+    "llama3-70b-layer-decode-sp24q4-bare-M1": dict(model="70b", w_bits=0, sq=True, ab_bits=16, r=0, M=1, cfg=5),
+    "llama3-70b-layer-decode-sp24q4-r128fp16-M64": dict(model="70b", w_bits=0, sq=True, ab_bits=16, r=128, M=64, cfg=5),
 }
 # the paper's speed table is on a 70B model: the quantised layer at those shapes (not a BASELINE config)
 WORKLOADS["llama3-70b-layer-decode-w3g128-r128fp16-M1"] = dict(model="70b", w_bits=3, ab_bits=16, r=128, M=1, cfg=2)
@@ -54,10 +58,12 @@ for _r in (64, 256, 512):
 DEFAULT = "llama3-8b-layer-decode-w3g128-r128fp16-M1-grouped"
 
 
-def algorithmic_bytes(d_in, d_out, M, r, w_bits, ab_bits, group=128):
+def algorithmic_bytes(d_in, d_out, M, r, w_bits, ab_bits, group=128, sq=False):
     """Bytes the method must move for one linear: packed codes, scales, zero-points, factors,
     x read once and y written once (the M x r intermediate never makes a y-sized round trip)."""
-    if w_bits == 0:                                          # 2:4 sparse fp16: two values + 4 index bits per four positions
+    if w_bits == 0 and sq:                                   # 2:4 sparse, 4-bit kept values: 8 + 4 bits per four positions
+        b = d_out * d_in * 0.375 + d_out * (d_in // group) * 2.5
+    elif w_bits == 0:                                        # 2:4 sparse fp16: two values + 4 index bits per four positions
         b = d_out * d_in * 1.125
     else:
         b = d_out * d_in * w_bits / 8 + d_out * (d_in // group) * 2.5
@@ -81,8 +87,16 @@ class Linear:
         from tests.gpu_util import dev
         self.name, self.d_in, self.d_out = name, d_in, d_out
         self.M, self.r, self.w_bits, self.ab_bits = spec["M"], spec["r"], spec["w_bits"], spec["ab_bits"]
+        self.sq = bool(spec.get("sq", False))
         W, A, B, x = synth.draw_layer(seed, d_in, d_out, self.M, self.r, spec.get("outlier", 0.0))
-        if self.w_bits == 0:
+        if self.w_bits == 0 and self.sq:
+            vals, pos = synth.prune_24(W.astype(np.float16))
+            del W
+            codes, zeros, scales = synth.quantize_kept_rtn(vals, pos, 128)
+            self.logical = (codes, pos, (zeros, scales), A, B, x)
+            qv, idx, qz, sc = eora.pack_sp24q4(codes, pos, zeros, scales, 128)
+            host = [qv, idx, None, None, None, sc, qz]               # scales and zero-points ride in the factor-scale slots
+        elif self.w_bits == 0:
             vals, pos = synth.prune_24(W.astype(np.float16))
             del W
             self.logical = (vals, pos, None, A, B, x)
@@ -107,12 +121,15 @@ class Linear:
         self.x = dev(x)
         self.y = torch.zeros((self.M, d_out), dtype=torch.float16, device="cuda")
         self.ws = eora.new_workspace(self.M, d_in, d_out, self.r)
-        self.bytes = algorithmic_bytes(d_in, d_out, self.M, self.r, self.w_bits, self.ab_bits)
+        self.bytes = algorithmic_bytes(d_in, d_out, self.M, self.r, self.w_bits, self.ab_bits, sq=self.sq)
         self.flops = 2.0 * self.M * d_in * d_out + 2.0 * self.M * self.r * (d_in + d_out)
 
     def run(self, copy):
         import paper_2410_21271_amd as eora
         qw, sc, qz, A, B, As, Bs = self.copies[copy % len(self.copies)]
+        if self.sq:
+            eora.linear_sp24q4(self.x, qw, sc, As, Bs, A, B, self.y, self.M, self.d_in, self.d_out, self.r, 128, self.ws)
+            return
         if self.w_bits == 0:
             eora.linear_sp24(self.x, qw, sc, A, B, self.y, self.M, self.d_in, self.d_out, self.r, self.ws)
             return
@@ -179,6 +196,16 @@ def cpu_baseline(linears, names):
         if L.name not in names:
             continue
         codes, zeros, scales, A, B, x = L.logical
+        if L.w_bits == 0 and L.sq:
+            qv, idx = layout.pack_sp24q4(codes, zeros)
+            qz, sc = layout.pack_zeros(scales[0]), layout.pack_scales(scales[1])
+            Ap, Bp = (layout.pack_f16(A), layout.pack_f16(B)) if L.r else (None, None)
+            t0 = time.perf_counter()
+            y = linear.eora_linear_sp24q4(x, qv, idx, sc, qz, Ap, Bp, L.M, L.d_in, L.d_out, L.r, 128)
+            total_t += time.perf_counter() - t0
+            total_b += L.bytes
+            worst = max(worst, linear.y_error(L.y.cpu().numpy(), y))
+            continue
         if L.w_bits == 0:
             values, indices = layout.pack_sp24(codes, zeros)
             Ap, Bp = (layout.pack_f16(A), layout.pack_f16(B)) if L.r else (None, None)
@@ -237,7 +264,7 @@ def main():
         return
     spec = WORKLOADS[args.workload]
     shapes = synth.LLAMA3_8B if spec["model"] == "8b" else synth.LLAMA3_70B
-    layer_bytes = sum(algorithmic_bytes(di, do, spec["M"], spec["r"], spec["w_bits"], spec["ab_bits"])
+    layer_bytes = sum(algorithmic_bytes(di, do, spec["M"], spec["r"], spec["w_bits"], spec["ab_bits"], sq=bool(spec.get("sq")))
                       for _, di, do in shapes)
     ncopies = args.copies or max(2, int(1.2e9 / layer_bytes) + 1)
     if spec["M"] > 16:
