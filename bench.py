@@ -62,7 +62,7 @@ def algorithmic_bytes(d_in, d_out, M, r, w_bits, ab_bits, group=128, sq=False):
     """Bytes the method must move for one linear: packed codes, scales, zero-points, factors,
     x read once and y written once (the M x r intermediate never makes a y-sized round trip)."""
     if w_bits == 0 and sq:                                   # 2:4 sparse, 4-bit kept values: 8 + 4 bits per four positions
-        b = d_out * d_in * 0.375 + d_out * (d_in // group) * 2.5
+        b = d_out * d_in * 0.375 + d_out * (d_in // 128) * 4        # tile words, one scale/zero word per (row, tile)
     elif w_bits == 0:                                        # 2:4 sparse fp16: two values + 4 index bits per four positions
         b = d_out * d_in * 1.125
     else:
@@ -94,8 +94,8 @@ class Linear:
             del W
             codes, zeros, scales = synth.quantize_kept_rtn(vals, pos, 128)
             self.logical = (codes, pos, (zeros, scales), A, B, x)
-            qv, idx, qz, sc = eora.pack_sp24q4(codes, pos, zeros, scales, 128)
-            host = [qv, idx, None, None, None, sc, qz]               # scales and zero-points ride in the factor-scale slots
+            tiles, meta = eora.pack_sp24q4(codes, pos, zeros, scales, 128)
+            host = [tiles, meta, None, None, None, None, None]
         elif self.w_bits == 0:
             vals, pos = synth.prune_24(W.astype(np.float16))
             del W
@@ -128,7 +128,7 @@ class Linear:
         import paper_2410_21271_amd as eora
         qw, sc, qz, A, B, As, Bs = self.copies[copy % len(self.copies)]
         if self.sq:
-            eora.linear_sp24q4(self.x, qw, sc, As, Bs, A, B, self.y, self.M, self.d_in, self.d_out, self.r, 128, self.ws)
+            eora.linear_sp24q4(self.x, qw, sc, A, B, self.y, self.M, self.d_in, self.d_out, self.r, self.ws)
             return
         if self.w_bits == 0:
             eora.linear_sp24(self.x, qw, sc, A, B, self.y, self.M, self.d_in, self.d_out, self.r, self.ws)
@@ -197,11 +197,10 @@ def cpu_baseline(linears, names):
             continue
         codes, zeros, scales, A, B, x = L.logical
         if L.w_bits == 0 and L.sq:
-            qv, idx = layout.pack_sp24q4(codes, zeros)
-            qz, sc = layout.pack_zeros(scales[0]), layout.pack_scales(scales[1])
+            tiles, meta = layout.pack_sp24q4(codes, zeros, scales[0], scales[1], 128)
             Ap, Bp = (layout.pack_f16(A), layout.pack_f16(B)) if L.r else (None, None)
             t0 = time.perf_counter()
-            y = linear.eora_linear_sp24q4(x, qv, idx, sc, qz, Ap, Bp, L.M, L.d_in, L.d_out, L.r, 128)
+            y = linear.eora_linear_sp24q4(x, tiles, meta, Ap, Bp, L.M, L.d_in, L.d_out, L.r)
             total_t += time.perf_counter() - t0
             total_b += L.bytes
             worst = max(worst, linear.y_error(L.y.cpu().numpy(), y))

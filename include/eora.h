@@ -45,11 +45,13 @@
  *      keeps two values v = 0,1 at positions p_0 < p_1.  values: fp16 element
  *      tile*1024 + s*512 + l*8 + 2*q + v.  indices: one 32-bit word per (tile, lane), bits
  *      16*s + 4*q + 2*v .. +1 hold p_v.
- *  SP24Q4 (2:4 sparse, kept values as 4-bit codes: pruned, then quantised, Sec. 4.2): the SP24 index
- *      words unchanged; codes: one 32-bit word per (tile, half s, lane), word tile*128 + s*64 + l,
- *      kept element e = 2*q + v of the lane's half in nibble 4*(e%2) + e/2; zero-points and scales as
- *      for the quantised backbone, one per (row, group of `group` DENSE columns): a kept value at dense
- *      column c is scale[o][c/group] * (code - zero[o][c/group]).  0.39 bytes per dense weight.
+ *  SP24Q4 (2:4 sparse, kept values as 4-bit codes: pruned, then quantised, Sec. 4.2): tiles as SP24.
+ *      qtiles: three 32-bit words per (tile, lane), words (tile*64 + l)*3 + 0, 1, 2: word s = 0, 1 holds
+ *      the lane's eight kept values of half s, element e = 2*q + v in nibble 4*(e%2) + e/2; word 2 is
+ *      the SP24 index word.  qmeta: one word per (tile, row n), word tile*16 + n: bits 0..15 the fp16
+ *      scale, bits 16..19 the zero-point of the quantisation group that holds the tile's columns (a
+ *      group of `group` DENSE columns, a multiple of 128, spans group/128 tiles, which repeat them).
+ *      A kept value at dense column c of row o is scale * (code - zero).  0.41 bytes per dense weight.
  *
  * Dequantisation (asymmetric group-wise quantisation, Sec. 4.1 and App. A.11):
  *      What[o][i] = scale[o][i/group] * (code[o][i] - zero[o][i/group])
@@ -90,7 +92,8 @@ size_t eora_qzeros_bytes(int d_in, int d_out, int group);            /* d_out*ce
 size_t eora_scales_bytes(int d_in, int d_out, int group);            /* d_out*(d_in/group)*2 */
 size_t eora_sp24_values_bytes(int d_in, int d_out);                  /* d_out*d_in          */
 size_t eora_sp24_indices_bytes(int d_in, int d_out);                 /* d_out*d_in/8        */
-size_t eora_sp24q4_codes_bytes(int d_in, int d_out);                 /* d_out*d_in/4        */
+size_t eora_sp24q4_tiles_bytes(int d_in, int d_out);                 /* d_out*d_in*3/8      */
+size_t eora_sp24q4_meta_bytes(int d_in, int d_out);                  /* d_out*(d_in/128)*4  */
 /* Scratch the forward calls need: a header of counters, the down-projection t = x.A^T (M x r)
  * and its partial sums.  The workspace must be cleared ONCE with eora_workspace_init() before the
  * first forward call on it; every forward call leaves it usable for the next, so no per-call
@@ -136,11 +139,9 @@ int eora_pack_sp24(const uint16_t* vals, const uint8_t* pos, int d_in, int d_out
                    void* values_out, void* indices_out);
 /* 2:4 sparse backbone with 4-bit kept values: codes d_out x d_in/2 in 0..15 (the kept values in column
  * order), pos as above, zeros / scales d_out x d_in/group as for eora_pack_q (the group of a kept value
- * is that of its dense column).  indices_out takes eora_sp24_indices_bytes, qvalues_out
- * eora_sp24q4_codes_bytes, qzeros_out / scales_out eora_qzeros_bytes / eora_scales_bytes. */
+ * is that of its dense column).  qtiles_out takes eora_sp24q4_tiles_bytes, qmeta_out eora_sp24q4_meta_bytes. */
 int eora_pack_sp24q4(const uint8_t* codes, const uint8_t* pos, const uint8_t* zeros, const uint16_t* scales,
-                     int d_in, int d_out, int group,
-                     void* qvalues_out, void* indices_out, void* qzeros_out, void* scales_out);
+                     int d_in, int d_out, int group, void* qtiles_out, void* qmeta_out);
 
 /* ---------------------------------------------------------------------------------------------
  * The layer.  Sec. 3 forward equation / Alg. 1 step 7; the fused low-rank path follows Sec. 4.5
@@ -202,10 +203,10 @@ int eora_linear_sp24(const void* x, const void* values, const void* indices,
 /* Same layer with a backbone that is 2:4 pruned and then quantised to 4 bits (Sec. 4.2 evaluates the
  * combination; stored format SP24Q4 above); A, B are F16 tiles.  All pointers DEVICE.  The kept values
  * enter the sparse MFMA as fp16(scale * (code - zero)): one fp16 rounding per weight.
- * Constraints as for eora_linear_sp24, and group % 128 == 0, d_in % group == 0.  Errors as above. */
-int eora_linear_sp24q4(const void* x, const void* qvalues, const void* indices, const void* scales, const void* qzeros,
+ * Constraints and errors as for eora_linear_sp24 (the quantisation groups are part of the stored bytes). */
+int eora_linear_sp24q4(const void* x, const void* qtiles, const void* qmeta,
                        const void* A, const void* B, void* y,
-                       int M, int d_in, int d_out, int r, int group,
+                       int M, int d_in, int d_out, int r,
                        void* workspace, size_t workspace_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
@@ -221,8 +222,7 @@ int eora_dequant_q(const void* qweight, const void* scales, const void* qzeros, 
 int eora_expand_sp24(const void* values, const void* indices, void* W_f16,
                      int d_in, int d_out, void* stream);
 /* W_f32: d_out x d_in row-major fp32: scale*(code-zero) at the kept positions (exact in fp32), +0 elsewhere. */
-int eora_expand_sp24q4(const void* qvalues, const void* indices, const void* scales, const void* qzeros,
-                       void* W_f32, int d_in, int d_out, int group, void* stream);
+int eora_expand_sp24q4(const void* qtiles, const void* qmeta, void* W_f32, int d_in, int d_out, void* stream);
 
 #ifdef __cplusplus
 }

@@ -40,10 +40,12 @@ SP24 (2:4 sparse fp16 backbone, tile = 16 rows x 128 dense columns)
     indices: one uint32 per (tile, lane): bits 16*s + 4*q + 2*v .. +1 = p_v
 
 SP24Q4 (2:4 sparse backbone whose kept values are 4-bit codes, tile = 16 rows x 128 dense columns)
-    positions: the SP24 index words, unchanged.
-    codes: one uint32 per (tile, half s, lane): word tile*128 + s*64 + l holds the lane's eight kept
-    values of the half, element e = 2*q + v in nibble 4*(e % 2) + e // 2 (the Q4 nibble order).
-    zeros / scales: as for the quantised backbone, one per (row, group of `group` DENSE columns).
+    tiles: three uint32 per (tile, lane), words (tile*64 + l)*3 + 0, 1, 2:
+        word s = 0, 1: the lane's eight kept values of half s, element e = 2*q + v in nibble
+        4*(e % 2) + e // 2 (the Q4 nibble order); word 2: the SP24 index word.
+    meta: one uint32 per (tile, row n), word tile*16 + n: bits 0..15 the fp16 scale, bits 16..19 the
+        zero-point of the quantisation group that holds the tile's columns (a group of `group` DENSE
+        columns, group a multiple of 128, covers group/128 tiles, which repeat its scale and zero).
 """
 import numpy as np
 
@@ -282,37 +284,53 @@ def _sp24q4_locate(o, u, K):
     lane = 16 * j + n
     tile = R * (K // 128) + g
     e = 2 * q + v
-    return tile * 128 + s * 64 + lane, 4 * (4 * (e % 2) + e // 2), tile * LANES + lane, 16 * s + 4 * q + 2 * v
+    base = (tile * LANES + lane) * 3
+    return base + s, 4 * (4 * (e % 2) + e // 2), base + 2, 16 * s + 4 * q + 2 * v
 
 
-def pack_sp24q4(codes, pos):
+def pack_sp24q4(codes, pos, zeros, scales, group):
     """codes: uint8 rows x K/2 (4-bit codes of the kept values); pos: their positions 0..3, strictly
-    ascending within each pair.  Returns (code words uint32, index words uint32)."""
+    ascending within each pair; zeros uint8 / scales fp16: rows x K/group.
+    Returns (tile words uint32, meta words uint32)."""
     codes = np.asarray(codes)
     pos = np.asarray(pos)
+    zeros = np.asarray(zeros)
+    scales = np.asarray(scales, dtype=np.float16)
     rows, half = codes.shape
     K = 2 * half
     _check(rows, K, 128)
-    if codes.min(initial=0) < 0 or codes.max(initial=0) > 15:
-        raise ValueError("codes must be 4-bit")
+    if group % 128 or K % group or zeros.shape != (rows, K // group) or scales.shape != zeros.shape:
+        raise ValueError("bad quantisation groups")
+    if codes.min(initial=0) < 0 or codes.max(initial=0) > 15 or zeros.min(initial=0) < 0 or zeros.max(initial=0) > 15:
+        raise ValueError("codes and zero-points must be 4-bit")
     if pos.shape != codes.shape or pos.min(initial=0) < 0 or pos.max(initial=0) > 3:
         raise ValueError("bad positions")
     if np.any(pos[:, 0::2] >= pos[:, 1::2]):
         raise ValueError("positions of a pair must be strictly ascending")
     o, u = np.meshgrid(np.arange(rows), np.arange(half), indexing="ij")
     cw, csh, iw, ish = _sp24q4_locate(o, u, K)
-    qvalues = np.zeros(rows * K // 128 * 8, dtype=np.uint32)       # 128 words per tile of 16 rows
-    indices = np.zeros(rows * K // 128 * 4, dtype=np.uint32)       # 64 words per tile
-    np.bitwise_or.at(qvalues, cw.ravel(), (codes.astype(np.uint32) << csh.astype(np.uint32)).ravel())
-    np.bitwise_or.at(indices, iw.ravel(), (pos.astype(np.uint32) << ish.astype(np.uint32)).ravel())
-    return qvalues, indices
+    tiles = np.zeros(rows * K // 128 * 12, dtype=np.uint32)        # 192 words per tile of 16 rows
+    np.bitwise_or.at(tiles, cw.ravel(), (codes.astype(np.uint32) << csh.astype(np.uint32)).ravel())
+    np.bitwise_or.at(tiles, iw.ravel(), (pos.astype(np.uint32) << ish.astype(np.uint32)).ravel())
+    ntk = K // 128
+    meta = np.zeros(rows // ROWS * ntk * ROWS, dtype=np.uint32)
+    oo, gg = np.meshgrid(np.arange(rows), np.arange(ntk), indexing="ij")
+    q = (gg * 128) // group
+    word = scales.view(np.uint16)[oo, q].astype(np.uint32) | (zeros[oo, q].astype(np.uint32) << 16)
+    meta[((oo // ROWS) * ntk + gg) * ROWS + oo % ROWS] = word
+    return tiles, meta
 
 
-def unpack_sp24q4(qvalues, indices, rows, K):
-    qvalues = np.asarray(qvalues, dtype=np.uint32)
-    indices = np.asarray(indices, dtype=np.uint32)
+def unpack_sp24q4(tiles, meta, rows, K):
+    """-> (codes, positions, zeros per (row, tile), scales per (row, tile))."""
+    tiles = np.asarray(tiles, dtype=np.uint32)
+    meta = np.asarray(meta, dtype=np.uint32)
     _check(rows, K, 128)
     o, u = np.meshgrid(np.arange(rows), np.arange(K // 2), indexing="ij")
     cw, csh, iw, ish = _sp24q4_locate(o, u, K)
-    return (((qvalues[cw] >> csh.astype(np.uint32)) & 15).astype(np.uint8),
-            ((indices[iw] >> ish.astype(np.uint32)) & 3).astype(np.uint8))
+    ntk = K // 128
+    oo, gg = np.meshgrid(np.arange(rows), np.arange(ntk), indexing="ij")
+    m = meta[((oo // ROWS) * ntk + gg) * ROWS + oo % ROWS]
+    return (((tiles[cw] >> csh.astype(np.uint32)) & 15).astype(np.uint8),
+            ((tiles[iw] >> ish.astype(np.uint32)) & 3).astype(np.uint8),
+            ((m >> 16) & 15).astype(np.uint8), (m & 0xFFFF).astype(np.uint16).view(np.float16))

@@ -86,11 +86,10 @@ def dequant_sp24q4(codes, pos, zeros, scales, group):
     return dense
 
 
-def dequant_sp24q4_packed(qvalues, indices, qzeros, scales_packed, d_in, d_out, group):
-    codes, pos = layout.unpack_sp24q4(qvalues, indices, d_out, d_in)
-    NG = d_in // group
-    return dequant_sp24q4(codes, pos, layout.unpack_zeros(qzeros, d_out, NG),
-                          layout.unpack_scales(scales_packed, d_out, NG), group)
+def dequant_sp24q4_packed(tiles, meta, d_in, d_out):
+    """From the stored bytes: every tile carries its rows' scale and zero-point, i.e. groups of 128."""
+    codes, pos, zeros, scales = layout.unpack_sp24q4(tiles, meta, d_out, d_in)
+    return dequant_sp24q4(codes, pos, zeros, scales, 128)
 
 
 def eora_linear(x, W_hat, A=None, B=None):
@@ -130,10 +129,10 @@ def eora_linear_sp24(x, values, indices, A, B, M, d_in, d_out, r):
     return eora_linear(x, W_hat, Ad, Bd)
 
 
-def eora_linear_sp24q4(x, qvalues, indices, scales, qzeros, A, B, M, d_in, d_out, r, group):
+def eora_linear_sp24q4(x, tiles, meta, A, B, M, d_in, d_out, r):
     """Forward pass straight from the stored bytes (2:4 sparse backbone with 4-bit kept values)."""
     x = np.asarray(x, dtype=np.float16).reshape(M, d_in)
-    W_hat = dequant_sp24q4_packed(qvalues, indices, qzeros, scales, d_in, d_out, group)
+    W_hat = dequant_sp24q4_packed(tiles, meta, d_in, d_out)
     if r == 0:
         return eora_linear(x, W_hat)
     Ad, Bd = _factors(A, B, None, None, d_in, d_out, r, 16)

@@ -45,7 +45,8 @@ def _load():
         "eora_scales_bytes": (sz, [ci, ci, ci]),
         "eora_sp24_values_bytes": (sz, [ci, ci]),
         "eora_sp24_indices_bytes": (sz, [ci, ci]),
-        "eora_sp24q4_codes_bytes": (sz, [ci, ci]),
+        "eora_sp24q4_tiles_bytes": (sz, [ci, ci]),
+        "eora_sp24q4_meta_bytes": (sz, [ci, ci]),
         "eora_workspace_bytes": (sz, [ci, ci, ci, ci]),
         "eora_workspace_bytes_group": (sz, [ci, ci, ci, ci]),
         "eora_workspace_init": (ci, [vp, sz, vp]),
@@ -55,15 +56,15 @@ def _load():
         "eora_pack_factor_f16": (ci, [vp, ci, ci, vp]),
         "eora_pack_factor_q4": (ci, [vp, vp, ci, ci, vp, vp]),
         "eora_pack_sp24": (ci, [vp, vp, ci, ci, vp, vp]),
-        "eora_pack_sp24q4": (ci, [vp, vp, vp, vp, ci, ci, ci, vp, vp, vp, vp]),
+        "eora_pack_sp24q4": (ci, [vp, vp, vp, vp, ci, ci, ci, vp, vp]),
         "eora_linear_q": (ci, [vp] * 9 + [ci] * 7 + [vp, sz, vp]),
         "eora_linear_q_group": (ci, [vp, ctypes.POINTER(QMember), ci] + [ci] * 6 + [vp, sz, vp]),
         "eora_linear_sp24": (ci, [vp] * 6 + [ci] * 4 + [vp, sz, vp]),
-        "eora_linear_sp24q4": (ci, [vp] * 8 + [ci] * 5 + [vp, sz, vp]),
+        "eora_linear_sp24q4": (ci, [vp] * 6 + [ci] * 4 + [vp, sz, vp]),
         "eora_unpack_q": (ci, [vp, vp, vp, vp, ci, ci, ci, ci, vp]),
         "eora_dequant_q": (ci, [vp, vp, vp, vp, ci, ci, ci, ci, vp]),
         "eora_expand_sp24": (ci, [vp, vp, vp, ci, ci, vp]),
-        "eora_expand_sp24q4": (ci, [vp, vp, vp, vp, vp, ci, ci, ci, vp]),
+        "eora_expand_sp24q4": (ci, [vp, vp, vp, ci, ci, vp]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(L, name)
@@ -78,7 +79,7 @@ EXPORTS = ["eora_status_string", "eora_qweight_bytes", "eora_qzeros_bytes", "eor
            "eora_workspace_error", "eora_debug_set_spin_limit", "eora_pack_q",
            "eora_pack_factor_f16", "eora_pack_factor_q4", "eora_pack_sp24", "eora_linear_q",
            "eora_linear_q_group", "eora_linear_sp24", "eora_unpack_q", "eora_dequant_q", "eora_expand_sp24",
-           "eora_sp24q4_codes_bytes", "eora_pack_sp24q4", "eora_linear_sp24q4", "eora_expand_sp24q4"]
+           "eora_sp24q4_tiles_bytes", "eora_sp24q4_meta_bytes", "eora_pack_sp24q4", "eora_linear_sp24q4", "eora_expand_sp24q4"]
 
 
 def status_string(status):
@@ -111,8 +112,12 @@ def sp24_indices_bytes(d_in, d_out):
     return lib.eora_sp24_indices_bytes(d_in, d_out)
 
 
-def sp24q4_codes_bytes(d_in, d_out):
-    return lib.eora_sp24q4_codes_bytes(d_in, d_out)
+def sp24q4_tiles_bytes(d_in, d_out):
+    return lib.eora_sp24q4_tiles_bytes(d_in, d_out)
+
+
+def sp24q4_meta_bytes(d_in, d_out):
+    return lib.eora_sp24q4_meta_bytes(d_in, d_out)
 
 
 def workspace_bytes(M, d_in, d_out, r):
@@ -178,17 +183,15 @@ def pack_sp24q4(codes, pos, zeros, scales, group):
     scales = np.ascontiguousarray(scales, dtype=np.float16)
     d_out, half = codes.shape
     d_in = 2 * half
-    nq, ni = sp24q4_codes_bytes(d_in, d_out), sp24_indices_bytes(d_in, d_out)
-    nz, ns = qzeros_bytes(d_in, d_out, group), scales_bytes(d_in, d_out, group)
-    if not (nq and ni and nz and ns) or pos.shape != codes.shape or zeros.shape != (d_out, d_in // group) or scales.shape != zeros.shape:
+    nt, nm = sp24q4_tiles_bytes(d_in, d_out), sp24q4_meta_bytes(d_in, d_out)
+    if not (nt and nm) or group <= 0 or d_in % group or pos.shape != codes.shape or zeros.shape != (d_out, d_in // group) \
+            or scales.shape != zeros.shape:
         raise EoraError(-2, "pack_sp24q4")
-    qv = np.empty(nq // 4, np.uint32)
-    idx = np.empty(ni // 4, np.uint32)
-    qz = np.empty(nz // 4, np.uint32)
-    sc = np.empty(ns // 2, np.float16)
+    tiles = np.empty(nt // 4, np.uint32)
+    meta = np.empty(nm // 4, np.uint32)
     _check(lib.eora_pack_sp24q4(_np_ptr(codes), _np_ptr(pos), _np_ptr(zeros), _np_ptr(scales), d_in, d_out, group,
-                                _np_ptr(qv), _np_ptr(idx), _np_ptr(qz), _np_ptr(sc)), "pack_sp24q4")
-    return qv, idx, qz, sc
+                                _np_ptr(tiles), _np_ptr(meta)), "pack_sp24q4")
+    return tiles, meta
 
 
 # ------------------------------------------------------------------ device entry points (torch tensors as memory)
@@ -253,10 +256,10 @@ def linear_sp24(x, values, indices, A, B, y, M, d_in, d_out, r, workspace):
                                 _dp(workspace), ws_bytes, _stream()), "linear_sp24")
 
 
-def linear_sp24q4(x, qvalues, indices, scales, qzeros, A, B, y, M, d_in, d_out, r, group, workspace):
+def linear_sp24q4(x, qtiles, qmeta, A, B, y, M, d_in, d_out, r, workspace):
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
-    _check(lib.eora_linear_sp24q4(_dp(x), _dp(qvalues), _dp(indices), _dp(scales), _dp(qzeros), _dp(A), _dp(B), _dp(y),
-                                  M, d_in, d_out, r, group, _dp(workspace), ws_bytes, _stream()), "linear_sp24q4")
+    _check(lib.eora_linear_sp24q4(_dp(x), _dp(qtiles), _dp(qmeta), _dp(A), _dp(B), _dp(y),
+                                  M, d_in, d_out, r, _dp(workspace), ws_bytes, _stream()), "linear_sp24q4")
 
 
 def unpack_q(qweight, qzeros, codes_u8, zeros_u8, d_in, d_out, w_bits, group):
@@ -273,6 +276,5 @@ def expand_sp24(values, indices, W_f16, d_in, d_out):
     _check(lib.eora_expand_sp24(_dp(values), _dp(indices), _dp(W_f16), d_in, d_out, _stream()), "expand_sp24")
 
 
-def expand_sp24q4(qvalues, indices, scales, qzeros, W_f32, d_in, d_out, group):
-    _check(lib.eora_expand_sp24q4(_dp(qvalues), _dp(indices), _dp(scales), _dp(qzeros), _dp(W_f32), d_in, d_out, group,
-                                  _stream()), "expand_sp24q4")
+def expand_sp24q4(qtiles, qmeta, W_f32, d_in, d_out):
+    _check(lib.eora_expand_sp24q4(_dp(qtiles), _dp(qmeta), _dp(W_f32), d_in, d_out, _stream()), "expand_sp24q4")

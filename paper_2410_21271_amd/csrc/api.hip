@@ -335,8 +335,8 @@ int eora_linear_q_group(const void* x, const eora_q_member* members, int n_membe
 
 namespace {
 // both 2:4 entry points: exactly one of values / qvalues is given
-int run_linear_sparse(const void* x, const void* values, const void* qvalues, const void* scales, const void* qzeros,
-                      int group, const void* indices, const void* A, const void* B, void* y,
+int run_linear_sparse(const void* x, const void* values, const void* indices, const void* qtiles, const void* qmeta,
+                      const void* A, const void* B, void* y,
                       int M, int d_in, int d_out, int r, void* workspace, size_t workspace_bytes, void* stream)
 {
     int rc = check_backbone_shape(M, d_in, d_out, r);
@@ -346,7 +346,7 @@ int run_linear_sparse(const void* x, const void* values, const void* qvalues, co
         if (r % 32) return EORA_ERR_SHAPE;
         if (!aligned16(A) || !aligned16(B)) return EORA_ERR_ALIGN;
     }
-    if (!aligned16(x) || !aligned16(values) || !aligned16(qvalues) || !aligned16(indices) || !aligned16(y)) return EORA_ERR_ALIGN;
+    if (!aligned16(x) || !aligned16(values) || !aligned16(qtiles) || !aligned16(qmeta) || !aligned16(indices) || !aligned16(y)) return EORA_ERR_ALIGN;
     if (!workspace) return EORA_ERR_WORKSPACE;
     if (!aligned16(workspace)) return EORA_ERR_ALIGN;
     if (workspace_bytes < eora_workspace_bytes(M, d_in, d_out, r)) return EORA_ERR_WORKSPACE;
@@ -356,11 +356,9 @@ int run_linear_sparse(const void* x, const void* values, const void* qvalues, co
         SparseArgs a{};
         a.x = (const _Float16*)x + (size_t)m0 * d_in;
         a.values = (const _Float16*)values;
-        a.qvalues = (const uint32_t*)qvalues;
-        a.w_scales = (const _Float16*)scales;
-        a.w_zeros = (const uint32_t*)qzeros;
-        a.group = group;
         a.indices = (const uint32_t*)indices;
+        a.qtiles = (const uint32_t*)qtiles;
+        a.qmeta = (const uint32_t*)qmeta;
         a.A = A;
         a.B = B;
         a.y = (_Float16*)y + (size_t)m0 * d_out;
@@ -385,19 +383,17 @@ int eora_linear_sp24(const void* x, const void* values, const void* indices,
                      void* workspace, size_t workspace_bytes, void* stream)
 {
     if (!x || !values || !indices || !y) return EORA_ERR_NULL;
-    return run_linear_sparse(x, values, nullptr, nullptr, nullptr, 128, indices, A, B, y, M, d_in, d_out, r,
+    return run_linear_sparse(x, values, indices, nullptr, nullptr, A, B, y, M, d_in, d_out, r,
                              workspace, workspace_bytes, stream);
 }
 
-int eora_linear_sp24q4(const void* x, const void* qvalues, const void* indices, const void* scales, const void* qzeros,
+int eora_linear_sp24q4(const void* x, const void* qtiles, const void* qmeta,
                        const void* A, const void* B, void* y,
-                       int M, int d_in, int d_out, int r, int group,
+                       int M, int d_in, int d_out, int r,
                        void* workspace, size_t workspace_bytes, void* stream)
 {
-    if (!x || !qvalues || !indices || !scales || !qzeros || !y) return EORA_ERR_NULL;
-    if (group <= 0 || group % 128 || (d_in > 0 && d_in % group)) return EORA_ERR_SHAPE;
-    if (((uintptr_t)scales & 1) || ((uintptr_t)qzeros & 3)) return EORA_ERR_ALIGN;
-    return run_linear_sparse(x, nullptr, qvalues, scales, qzeros, group, indices, A, B, y, M, d_in, d_out, r,
+    if (!x || !qtiles || !qmeta || !y) return EORA_ERR_NULL;
+    return run_linear_sparse(x, nullptr, nullptr, qtiles, qmeta, A, B, y, M, d_in, d_out, r,
                              workspace, workspace_bytes, stream);
 }
 
@@ -445,17 +441,14 @@ int eora_expand_sp24(const void* values, const void* indices, void* W_f16, int d
     return EORA_OK;
 }
 
-int eora_expand_sp24q4(const void* qvalues, const void* indices, const void* scales, const void* qzeros,
-                       void* W_f32, int d_in, int d_out, int group, void* stream)
+int eora_expand_sp24q4(const void* qtiles, const void* qmeta, void* W_f32, int d_in, int d_out, void* stream)
 {
-    if (!qvalues || !indices || !scales || !qzeros || !W_f32) return EORA_ERR_NULL;
+    if (!qtiles || !qmeta || !W_f32) return EORA_ERR_NULL;
     int rc = check_backbone_shape(1, d_in, d_out, 0);
     if (rc != EORA_OK) return rc;
-    if (group <= 0 || group % 128 || d_in % group) return EORA_ERR_SHAPE;
-    if (!aligned16(qvalues) || !aligned16(indices) || !aligned16(W_f32)) return EORA_ERR_ALIGN;
-    if (failed(launch_expand_sp24q4((const uint32_t*)qvalues, (const uint32_t*)indices, (const _Float16*)scales,
-                                    (const uint32_t*)qzeros, (float*)W_f32, d_in, d_out, group, (hipStream_t)stream),
-               "expand_sp24q4"))
+    if (!aligned16(qtiles) || !aligned16(qmeta) || !aligned16(W_f32)) return EORA_ERR_ALIGN;
+    if (failed(launch_expand_sp24q4((const uint32_t*)qtiles, (const uint32_t*)qmeta, (float*)W_f32, d_in, d_out,
+                                    (hipStream_t)stream), "expand_sp24q4"))
         return EORA_ERR_LAUNCH;
     return EORA_OK;
 }

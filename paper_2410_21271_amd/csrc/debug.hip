@@ -80,9 +80,8 @@ __global__ void expand_sp24_kernel(const _Float16* __restrict__ values, const ui
 
 // 2:4 sparse with 4-bit kept values -> dense fp32: scale*(code - zero) at the kept positions (exact in
 // fp32), +0 elsewhere.  One thread per (tile, lane), plain shifts and masks.
-__global__ void expand_sp24q4_kernel(const uint32_t* __restrict__ qvalues, const uint32_t* __restrict__ indices,
-                                     const _Float16* __restrict__ scales, const uint32_t* __restrict__ qzeros,
-                                     float* __restrict__ W, int d_in, int d_out, int group)
+__global__ void expand_sp24q4_kernel(const uint32_t* __restrict__ qtiles, const uint32_t* __restrict__ qmeta,
+                                     float* __restrict__ W, int d_in, int d_out)
 {
     const size_t L = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     const size_t nlanes = (size_t)d_out * d_in / 32;
@@ -92,13 +91,13 @@ __global__ void expand_sp24q4_kernel(const uint32_t* __restrict__ qvalues, const
     const int lane = (int)(L % 64);
     const int R = (int)(tile / ntk), g = (int)(tile % ntk);
     const int j = lane >> 4, n = lane & 15;
-    const int NG = d_in / group, NGW = (NG + 7) / 8, grp = (128 * g) / group;
     const size_t row = (size_t)16 * R + n;
-    const float sc = (float)scales[row * NG + grp];
-    const int z = (int)((qzeros[row * NGW + (grp >> 3)] >> (4 * (grp & 7))) & 0xFu);
-    const uint32_t word = indices[L];
+    const uint32_t m = qmeta[tile * 16 + n];
+    const float sc = (float)__builtin_bit_cast(_Float16, (uint16_t)(m & 0xFFFFu));
+    const int z = (int)((m >> 16) & 0xFu);
+    const uint32_t word = qtiles[3 * L + 2];
     for (int s = 0; s < 2; ++s) {
-        const uint32_t cw = qvalues[tile * 128 + s * 64 + lane];
+        const uint32_t cw = qtiles[3 * L + s];
         for (int q = 0; q < 4; ++q) {
             float out[4] = {0.f, 0.f, 0.f, 0.f};
             for (int v = 0; v < 2; ++v) {
@@ -141,12 +140,10 @@ hipError_t launch_expand_sp24(const _Float16* values, const uint32_t* indices, _
     return hipGetLastError();
 }
 
-hipError_t launch_expand_sp24q4(const uint32_t* qvalues, const uint32_t* indices, const _Float16* scales,
-                                const uint32_t* qzeros, float* W, int d_in, int d_out, int group, hipStream_t stream)
+hipError_t launch_expand_sp24q4(const uint32_t* qtiles, const uint32_t* qmeta, float* W, int d_in, int d_out, hipStream_t stream)
 {
     const size_t nlanes = (size_t)d_out * d_in / 32;
-    hipLaunchKernelGGL(expand_sp24q4_kernel, grid_for(nlanes), dim3(256), 0, stream, qvalues, indices, scales, qzeros, W,
-                       d_in, d_out, group);
+    hipLaunchKernelGGL(expand_sp24q4_kernel, grid_for(nlanes), dim3(256), 0, stream, qtiles, qmeta, W, d_in, d_out);
     return hipGetLastError();
 }
 

@@ -75,11 +75,9 @@ hipError_t launch_clear_words(uint32_t* p, int nwords, hipStream_t stream);
 struct SparseArgs {
     const _Float16* x;        // M x d_in fp16 row-major
     const _Float16* values;   // SP24 kept values (fp16 backbone), or
-    const uint32_t* qvalues;  // SP24Q4 codes of the kept values with
-    const _Float16* w_scales; //   fp16 scales and
-    const uint32_t* w_zeros;  //   4-bit zero-points per (row, group of `group` dense columns)
-    int group;
-    const uint32_t* indices;  // SP24 positions
+    const uint32_t* indices;  // SP24 positions, or
+    const uint32_t* qtiles;   // SP24Q4: three words per (tile, lane): codes of both halves, positions
+    const uint32_t* qmeta;    // SP24Q4: one word per (tile, row): fp16 scale | zero-point << 16
     const void* A;            // r x d_in F16 tiles
     const void* B;            // d_out x r F16 tiles
     _Float16* y;              // M x d_out fp16 row-major
@@ -127,7 +125,6 @@ hipError_t launch_dequant_q(const uint32_t* qweight, const _Float16* scales, con
                             int d_in, int d_out, int w_bits, int group, hipStream_t stream);
 hipError_t launch_expand_sp24(const _Float16* values, const uint32_t* indices, _Float16* W,
                               int d_in, int d_out, hipStream_t stream);
-hipError_t launch_expand_sp24q4(const uint32_t* qvalues, const uint32_t* indices, const _Float16* scales,
-                                const uint32_t* qzeros, float* W, int d_in, int d_out, int group, hipStream_t stream);
+hipError_t launch_expand_sp24q4(const uint32_t* qtiles, const uint32_t* qmeta, float* W, int d_in, int d_out, hipStream_t stream);
 
 }  // namespace eora

@@ -184,24 +184,28 @@ int eora_pack_sp24(const uint16_t* vals, const uint8_t* pos, int d_in, int d_out
     return EORA_OK;
 }
 
-size_t eora_sp24q4_codes_bytes(int d_in, int d_out)
+size_t eora_sp24q4_tiles_bytes(int d_in, int d_out)
 {
-    return shape_ok(d_out, d_in, 128) ? (size_t)d_out * d_in / 4 : 0;
+    return shape_ok(d_out, d_in, 128) ? (size_t)d_out * d_in * 3 / 8 : 0;
+}
+
+size_t eora_sp24q4_meta_bytes(int d_in, int d_out)
+{
+    return shape_ok(d_out, d_in, 128) ? (size_t)d_out * (d_in / 128) * 4 : 0;
 }
 
 int eora_pack_sp24q4(const uint8_t* codes, const uint8_t* pos, const uint8_t* zeros, const uint16_t* scales,
-                     int d_in, int d_out, int group,
-                     void* qvalues_out, void* indices_out, void* qzeros_out, void* scales_out)
+                     int d_in, int d_out, int group, void* qtiles_out, void* qmeta_out)
 {
-    if (!codes || !pos || !zeros || !scales || !qvalues_out || !indices_out || !qzeros_out || !scales_out) return EORA_ERR_NULL;
+    if (!codes || !pos || !zeros || !scales || !qtiles_out || !qmeta_out) return EORA_ERR_NULL;
     if (!shape_ok(d_out, d_in, 128) || group <= 0 || group % 128 || d_in % group) return EORA_ERR_SHAPE;
     const int NG = d_in / group;
     for (size_t i = 0; i < (size_t)d_out * NG; ++i)
         if (zeros[i] > 15) return EORA_ERR_VALUE;
-    uint32_t* qo = (uint32_t*)qvalues_out;
-    uint32_t* io = (uint32_t*)indices_out;
+    uint32_t* to = (uint32_t*)qtiles_out;
+    uint32_t* mo = (uint32_t*)qmeta_out;
     const int ntk = d_in / 128, half = d_in / 2;
-    const size_t nlanes = (size_t)d_out * d_in / 32;         // one index word and two code words per (tile, lane)
+    const size_t nlanes = (size_t)d_out * d_in / 32;         // three words per (tile, lane)
     for (size_t L = 0; L < nlanes; ++L) {
         const size_t tile = L / 64;
         const int lane = (int)(L % 64);
@@ -221,20 +225,14 @@ int eora_pack_sp24q4(const uint8_t* codes, const uint8_t* pos, const uint8_t* ze
                     cw |= (uint32_t)codes[u + v] << (4 * (4 * (e % 2) + e / 2));
                 }
             }
-            qo[tile * 128 + s * 64 + lane] = cw;
+            to[3 * L + s] = cw;
         }
-        io[L] = word;
+        to[3 * L + 2] = word;
+        if (j == 0) {                                        // the tile's meta word of row n
+            const size_t q = (size_t)(16 * R + n) * NG + (128 * g) / group;
+            mo[tile * 16 + n] = (uint32_t)scales[q] | ((uint32_t)zeros[q] << 16);
+        }
     }
-    uint32_t* zw = (uint32_t*)qzeros_out;
-    const int NGW = (NG + 7) / 8;
-    for (int row = 0; row < d_out; ++row)
-        for (int wq = 0; wq < NGW; ++wq) {
-            uint32_t w = 0;
-            for (int e = 0; e < 8 && 8 * wq + e < NG; ++e)
-                w |= (uint32_t)zeros[(size_t)row * NG + 8 * wq + e] << (4 * e);
-            zw[(size_t)row * NGW + wq] = w;
-        }
-    pack_scale_tiles(scales, d_out, NG, (uint16_t*)scales_out);
     return EORA_OK;
 }
 

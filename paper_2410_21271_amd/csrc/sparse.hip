@@ -26,11 +26,8 @@ template <> struct SpT<false> {
     uint32_t idx;     // positions: low 16 bits block 0, high 16 bits block 1
 };
 template <> struct SpT<true> {
-    uint32_t c0, c1;  // eight codes per block, element e = 2q + v in nibble 4(e%2) + e/2
-    uint32_t idx;
-    uint32_t zraw;    // the word that holds the zero-point nibble of (row n, group)
-    uint32_t sraw;    // fp16 scale bits
-    int zshift;
+    uint32_t w[3];    // eight codes per block (element e = 2q + v in nibble 4(e%2) + e/2), then the positions
+    uint32_t meta;    // fp16 scale | zero-point << 16 of (tile, row n)
 };
 
 typedef _Float16 h16 __attribute__((ext_vector_type(16)));
@@ -40,24 +37,21 @@ template <bool VQ>
 __device__ __forceinline__ void load_sptile(SpT<VQ>& t, const SparseArgs& a, int R, int g, int G, int lane)
 {
     const size_t tile = (size_t)R * G + g;
-    t.idx = a.indices[tile * 64 + lane];
     if constexpr (!VQ) {
+        t.idx = a.indices[tile * 64 + lane];
         const u4* p = (const u4*)(a.values + tile * 1024) + lane;
         t.v0 = p[0];
         t.v1 = p[64];
     } else {
-        const uint32_t* p = a.qvalues + tile * 128 + lane;
-        t.c0 = p[0];
-        t.c1 = p[64];
-        const int gdiv = a.group >> 7, grp = gdiv == 1 ? g : g / gdiv, NG = a.d_in / a.group;
-        const size_t row = (size_t)R * 16 + (lane & 15);
-        t.sraw = ((const uint16_t*)a.w_scales)[row * NG + grp];
-        t.zraw = a.w_zeros[row * ((NG + 7) / 8) + (grp >> 3)];
-        t.zshift = 4 * (grp & 7);
+        load_words<3>(t.w, a.qtiles + (tile * 64 + lane) * 3);       // one 12-byte request
+        t.meta = a.qmeta[tile * 16 + (lane & 15)];
     }
 }
 
 __device__ __forceinline__ h8 as_h8(u4 v) { return __builtin_bit_cast(h8, v); }
+
+__device__ __forceinline__ int sp_idx(const SpT<false>& t) { return (int)t.idx; }
+__device__ __forceinline__ int sp_idx(const SpT<true>& t) { return (int)t.w[2]; }
 
 // the sparse operands of the tile's two blocks.  Quantised: code - zero exact, times the fp16 group scale
 // (one fp16 rounding of scale*(code - zero), relative error <= 2^-11 per weight: the accumulator holds four
@@ -69,12 +63,12 @@ __device__ __forceinline__ void sp_operands(const SpT<VQ>& t, h8& a0, h8& a1)
         a0 = as_h8(t.v0);
         a1 = as_h8(t.v1);
     } else {
-        const uint32_t z = (t.zraw >> t.zshift) & 0xFu;
+        const uint32_t z = (t.meta >> 16) & 0xFu;
         const uint32_t c1024 = k1024(z), c64 = k64(z);
-        const _Float16 sc = __builtin_bit_cast(_Float16, (uint16_t)t.sraw);
+        const _Float16 sc = __builtin_bit_cast(_Float16, (uint16_t)(t.meta & 0xFFFFu));
         const h8 sv = {sc, sc, sc, sc, sc, sc, sc, sc};
-        a0 = dq4_word(t.c0, c1024, c64) * sv;
-        a1 = dq4_word(t.c1, c1024, c64) * sv;
+        a0 = dq4_word(t.w[0], c1024, c64) * sv;
+        a1 = dq4_word(t.w[1], c1024, c64) * sv;
     }
 }
 
@@ -238,8 +232,8 @@ __global__ __launch_bounds__(NW * 64, 6) void sparse_kernel(SparseArgs a)
                         x1 = *(const h8*)(px + 32);
                     }
                     const h16 xb = __builtin_shufflevector(x0, x1, 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15);
-                    if (blk == 0) acc = __builtin_amdgcn_smfmac_f32_16x16x64_f16(sa[0], xb, acc, (int)buf[s].idx, 0, 0);
-                    else acc = __builtin_amdgcn_smfmac_f32_16x16x64_f16(sa[1], xb, acc, (int)buf[s].idx, 0, 1);
+                    if (blk == 0) acc = __builtin_amdgcn_smfmac_f32_16x16x64_f16(sa[0], xb, acc, sp_idx(buf[s]), 0, 0);
+                    else acc = __builtin_amdgcn_smfmac_f32_16x16x64_f16(sa[1], xb, acc, sp_idx(buf[s]), 0, 1);
                 }
             }
             __builtin_amdgcn_sched_barrier(0);
@@ -505,8 +499,8 @@ __global__ __launch_bounds__(NW * 64) void sparse_wide_kernel(SparseArgs a)
                 const h8 x10 = *(const h8*)(px + poff[2]), x11 = *(const h8*)(px + poff[3]);
                 const h16 xa = __builtin_shufflevector(x00, x01, 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15);
                 const h16 xb = __builtin_shufflevector(x10, x11, 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15);
-                acc[tb] = __builtin_amdgcn_smfmac_f32_16x16x64_f16(sa0, xa, acc[tb], (int)buf[s].idx, 0, 0);
-                acc[tb] = __builtin_amdgcn_smfmac_f32_16x16x64_f16(sa1, xb, acc[tb], (int)buf[s].idx, 0, 1);
+                acc[tb] = __builtin_amdgcn_smfmac_f32_16x16x64_f16(sa0, xa, acc[tb], sp_idx(buf[s]), 0, 0);
+                acc[tb] = __builtin_amdgcn_smfmac_f32_16x16x64_f16(sa1, xb, acc[tb], sp_idx(buf[s]), 0, 1);
             }
             // the tile's registers are free again: the request for the tile XW_D chunks on goes out last
             __builtin_amdgcn_sched_barrier(0);
@@ -693,7 +687,7 @@ static hipError_t launch_sparse_vq(const SparseArgs& a, hipStream_t stream)
 
 hipError_t launch_sparse(const SparseArgs& a, hipStream_t stream)
 {
-    return a.qvalues ? launch_sparse_vq<true>(a, stream) : launch_sparse_vq<false>(a, stream);
+    return a.qtiles ? launch_sparse_vq<true>(a, stream) : launch_sparse_vq<false>(a, stream);
 }
 
 }  // namespace eora

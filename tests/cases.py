@@ -100,8 +100,7 @@ class SparseQCase:
         codes, zeros, scales = synth.quantize_kept_rtn(vals, pos, group)
         self.logical = dict(codes=codes, pos=pos, zeros=zeros, scales=scales, A=A, B=B)
         self.x = x
-        self.o_qvalues, self.o_indices = layout.pack_sp24q4(codes, pos)
-        self.o_qz, self.o_sc = layout.pack_zeros(zeros), layout.pack_scales(scales)
+        self.o_tiles, self.o_meta = layout.pack_sp24q4(codes, pos, zeros, scales, group)
         self.o_A = self.o_B = None
         if r > 0:
             self.o_A, self.o_B = layout.pack_f16(A), layout.pack_f16(B)
@@ -110,9 +109,8 @@ class SparseQCase:
 
     def pack_with(self, e):
         L = self.logical
-        self.qvalues, self.indices, self.qz, self.sc = e.pack_sp24q4(L["codes"], L["pos"], L["zeros"], L["scales"], self.group)
-        assert np.array_equal(self.qvalues, self.o_qvalues) and np.array_equal(self.indices, self.o_indices)
-        assert np.array_equal(self.qz, self.o_qz) and np.array_equal(self.sc.view(np.uint16), self.o_sc.view(np.uint16))
+        self.tiles, self.meta = e.pack_sp24q4(L["codes"], L["pos"], L["zeros"], L["scales"], self.group)
+        assert np.array_equal(self.tiles, self.o_tiles) and np.array_equal(self.meta, self.o_meta)
         self.A = self.B = None
         if self.r > 0:
             self.A, self.B = e.pack_factor_f16(L["A"]), e.pack_factor_f16(L["B"])
@@ -120,5 +118,5 @@ class SparseQCase:
     def oracle_y(self, rows=None):
         from oracle import linear
         x = self.x if rows is None else self.x[rows]
-        return linear.eora_linear_sp24q4(x, self.o_qvalues, self.o_indices, self.o_sc, self.o_qz, self.o_A, self.o_B,
-                                         x.shape[0], self.d_in, self.d_out, self.r, self.group)
+        return linear.eora_linear_sp24q4(x, self.o_tiles, self.o_meta, self.o_A, self.o_B,
+                                         x.shape[0], self.d_in, self.d_out, self.r)

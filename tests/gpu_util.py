@@ -75,10 +75,10 @@ def run_linear_sp24(c, M=None, x=None, r=None, ws=None):
 def run_linear_sp24q4(c, ws=None):
     """Run eora_linear_sp24q4 on case c; returns y as float16 numpy (M x d_out)."""
     xd = dev(c.x)
-    t = [dev(c.qvalues), dev(c.indices), dev(c.sc), dev(c.qz)]
+    t = [dev(c.tiles), dev(c.meta)]
     A, B = (dev(c.A), dev(c.B)) if c.r > 0 else (None, None)
     y = torch.full((c.M * c.d_out,), 777.0, dtype=torch.float16, device="cuda")
     ws = eora.new_workspace(c.M, c.d_in, c.d_out, c.r) if ws is None else ws
-    eora.linear_sp24q4(xd, t[0], t[1], t[2], t[3], A, B, y, c.M, c.d_in, c.d_out, c.r, c.group, ws)
+    eora.linear_sp24q4(xd, t[0], t[1], A, B, y, c.M, c.d_in, c.d_out, c.r, ws)
     torch.cuda.synchronize()
     return y.cpu().numpy().reshape(c.M, c.d_out)

@@ -92,26 +92,30 @@ def decode_sp24(values, indices, rows, K):
     return out
 
 
-def decode_sp24q4(qvalues, indices, zeros, scales, rows, K, group):
-    """-> dense rows x K matrix of Fractions, walking the stored words: every index word names the
-    dense columns of its lane's sixteen kept values, the two code words of the lane hold their nibbles.
-    zeros / scales: decoded lists rows x K/group."""
+def decode_sp24q4(tiles, meta, rows, K):
+    """-> dense rows x K matrix of Fractions, walking the stored words: the third word of a lane names the
+    dense columns of its sixteen kept values, the first two hold their nibbles, the tile's meta word of
+    the lane's row the scale and the zero-point."""
+    import numpy as np
     out = [[Fraction(0)] * K for _ in range(rows)]
     ntk = K // 128
-    for w, word in enumerate(int(v) for v in indices):
-        tile, lane = divmod(w, 64)
+    for tl in range(len(tiles) // 3):
+        tile, lane = divmod(tl, 64)
         R, g = divmod(tile, ntk)
         j, n = divmod(lane, 16)
         o = 16 * R + n
+        m = int(meta[tile * 16 + n])
+        scale = Fraction(float(np.array([m & 0xFFFF], dtype=np.uint16).view(np.float16)[0]))
+        zero = (m >> 16) & 0xF
+        word = int(tiles[3 * tl + 2])
         for s in range(2):
-            cw = int(qvalues[tile * 128 + s * 64 + lane])
+            cw = int(tiles[3 * tl + s])
             for q in range(4):
                 for v in range(2):
                     p = (word >> (16 * s + 4 * q + 2 * v)) & 3
                     e = 2 * q + v
                     code = (cw >> (4 * (4 * (e % 2) + e // 2))) & 0xF
-                    col = 128 * g + 64 * s + 16 * j + 4 * q + p
-                    out[o][col] = scales[o][col // group] * (code - zeros[o][col // group])
+                    out[o][128 * g + 64 * s + 16 * j + 4 * q + p] = scale * (code - zero)
     return out
 
 

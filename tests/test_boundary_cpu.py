@@ -47,7 +47,8 @@ def test_sizes():
     assert eora.scales_bytes(4096, 4096, 128) == 4096 * 32 * 2
     assert eora.sp24_values_bytes(8192, 1024) == 8192 * 1024
     assert eora.sp24_indices_bytes(8192, 1024) == 8192 * 1024 // 8
-    assert eora.sp24q4_codes_bytes(8192, 1024) == 8192 * 1024 // 4 and eora.sp24q4_codes_bytes(8192, 1000) == 0
+    assert eora.sp24q4_tiles_bytes(8192, 1024) == 8192 * 1024 * 3 // 8 and eora.sp24q4_tiles_bytes(8192, 1000) == 0
+    assert eora.sp24q4_meta_bytes(8192, 1024) == 1024 * 64 * 4
     assert eora.qweight_bytes(4096, 4100, 4) == 0 and eora.qweight_bytes(4096, 4096, 5) == 0
     assert eora.workspace_bytes(1, 4096, 4096, 128) >= 4 * 128
     assert eora.workspace_bytes(1, 4096, 4096, 1024) == 0
@@ -124,12 +125,12 @@ def test_linear_q_validation_codes():
     assert L.eora_dequant_q(good, good, good, null, 256, 32, 4, 128, null) == -1
     assert L.eora_expand_sp24(good, odd, good, 256, 32, null) == -4
     sq = L.eora_linear_sp24q4
-    assert sq(good, null, good, good, good, good, good, good, 1, 256, 32, 32, 128, good, 1 << 24, null) == -1
-    assert sq(good, good, good, good, good, good, good, good, 1, 256, 32, 32, 64, good, 1 << 24, null) == -2
-    assert sq(good, good, good, good, good, good, good, good, 1, 256, 32, 32, 384, good, 1 << 24, null) == -2
-    assert sq(good, odd, good, good, good, good, good, good, 1, 256, 32, 32, 128, good, 1 << 24, null) == -4
-    assert sq(good, good, good, good, good, good, good, good, 1, 256, 32, 32, 128, good, 16, null) == -5
-    assert sq(good, good, good, good, good, good, good, good, 0, 256, 32, 32, 128, good, 1 << 24, null) == 0
-    assert L.eora_expand_sp24q4(good, good, good, good, null, 256, 32, 128, null) == -1
-    assert L.eora_expand_sp24q4(good, good, good, good, good, 256, 32, 96, null) == -2
+    assert sq(good, null, good, good, good, good, 1, 256, 32, 32, good, 1 << 24, null) == -1
+    assert sq(good, good, good, good, good, good, 1, 200, 32, 32, good, 1 << 24, null) == -2
+    assert sq(good, good, good, good, good, good, 1, 256, 32, 48, good, 1 << 24, null) == -2
+    assert sq(good, odd, good, good, good, good, 1, 256, 32, 32, good, 1 << 24, null) == -4
+    assert sq(good, good, good, good, good, good, 1, 256, 32, 32, good, 16, null) == -5
+    assert sq(good, good, good, good, good, good, 0, 256, 32, 32, good, 1 << 24, null) == 0
+    assert L.eora_expand_sp24q4(good, good, null, 256, 32, null) == -1
+    assert L.eora_expand_sp24q4(good, good, good, 256, 40, null) == -2
     assert eora.status_string(-4) == "misaligned pointer"

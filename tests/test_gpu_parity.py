@@ -361,9 +361,11 @@ def test_expand_sp24q4_bit_exact(gpu):
     for group in (128, 384):
         c = SparseQCase(31 + group, 768, 80, 1, 0, group=group, packer=gpu)
         W = torch.full((80, 768), 7.0, dtype=torch.float32, device="cuda")
-        gpu.expand_sp24q4(dev(c.qvalues), dev(c.indices), dev(c.sc), dev(c.qz), W, 768, 80, group)
+        gpu.expand_sp24q4(dev(c.tiles), dev(c.meta), W, 768, 80)
         torch.cuda.synchronize()
-        ref = linear.dequant_sp24q4_packed(c.o_qvalues, c.o_indices, c.o_qz, c.o_sc, 768, 80, group)
+        ref = linear.dequant_sp24q4_packed(c.o_tiles, c.o_meta, 768, 80)
+        L = c.logical
+        assert np.array_equal(ref, linear.dequant_sp24q4(L["codes"], L["pos"], L["zeros"], L["scales"], group))
         assert np.array_equal(W.cpu().numpy().astype(np.float64), ref)
 
 

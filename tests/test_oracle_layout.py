@@ -45,12 +45,15 @@ def _run_case(kind, prm, sets, expect):
         codes = np.zeros((rows, K // 2), np.uint8)
         for o, u, c in sets:
             codes[o, u] = c
-        words, _ = layout.pack_sp24q4(codes, pos)
-        back, _ = layout.unpack_sp24q4(*layout.pack_sp24q4(codes, pos), rows, K)
+        z1, s1 = np.zeros((rows, K // 128), np.uint8), np.ones((rows, K // 128), np.float16)
+        words, _ = layout.pack_sp24q4(codes, pos, z1, s1, 128)
+        back = layout.unpack_sp24q4(*layout.pack_sp24q4(codes, pos, z1, s1, 128), rows, K)[0]
     else:
         raise AssertionError(kind)
     default = 0x44444444 if kind == "sp24" else 0
     want = np.full(words.shape, default, np.uint32)
+    if kind == "sp24q4":
+        want[2::3] = 0x44444444                      # the index word of every lane
     for w, v in expect.items():
         want[w] = v
     assert np.array_equal(words, want), [(i, hex(a), hex(b)) for i, (a, b) in enumerate(zip(words, want)) if a != b][:8]
@@ -155,21 +158,26 @@ def test_sp24_roundtrip_and_word_walk():
 
 def test_sp24q4_code_positions_by_hand():
     # Same (row, kept index) cases as the SP24 test above; derivation in layout_misc.txt.
-    # o=3 u=37: group 18, v=1, dense col 72: tile 0, s=1, c2=8, j=0, q=2, lane 3, e=5 -> word 64+3=67, nibble 4*1+2=6
-    # o=0 u=1:  group 0, v=1: s=0, j=0, q=0, lane 0, e=1 -> word 0, nibble 4
-    # o=9 u=63: group 31, v=1, dense col 124: s=1, c2=60, j=3, q=3, lane 57, e=7 -> word 64+57=121, nibble 7
+    # o=3 u=37: group 18, v=1, dense col 72: tile 0, s=1, c2=8, j=0, q=2, lane 3, e=5 -> half 1 of lane 3, nibble 4*1+2=6
+    # o=0 u=1:  group 0, v=1: s=0, j=0, q=0, lane 0, e=1 -> half 0 of lane 0, nibble 4
+    # o=9 u=63: group 31, v=1, dense col 124: s=1, c2=60, j=3, q=3, lane 57, e=7 -> half 1 of lane 57, nibble 7
     rows, K = 16, 128
     pos = np.tile(np.array([0, 1], np.uint8), (rows, K // 4))
     codes = np.zeros((rows, K // 2), np.uint8)
     codes[3, 37] = 0xB
     codes[0, 1] = 0x5
     codes[9, 63] = 0xF
-    qvalues, indices = layout.pack_sp24q4(codes, pos)
-    nz = {int(i): int(qvalues[i]) for i in np.nonzero(qvalues)[0]}
-    assert nz == {67: 0xB << 24, 0: 0x5 << 16, 121: 0xF << 28}
+    zeros = np.zeros((rows, 1), np.uint8)
+    scales = np.ones((rows, 1), np.float16)
+    zeros[9, 0], scales[9, 0] = 7, 0.5                  # fp16 0.5 = 0x3800: meta word of (tile 0, row 9) = 0x00073800
+    tiles, meta = layout.pack_sp24q4(codes, pos, zeros, scales, 128)
+    cw = np.concatenate([tiles[0::3], tiles[1::3]])       # the code words: half 0 of every lane, then half 1
+    nz = {int(i): int(cw[i]) for i in np.nonzero(cw)[0]}
+    assert nz == {64 + 3: 0xB << 24, 0: 0x5 << 16, 64 + 57: 0xF << 28}
     # the index words are those of the fp16 format
     _, ref_idx = layout.pack_sp24(np.zeros((rows, K // 2), np.float16), pos)
-    assert np.array_equal(indices, ref_idx)
+    assert np.array_equal(tiles[2::3], ref_idx)
+    assert int(meta[9]) == 0x00073800 and int(meta[0]) == 0x00003C00 and meta.size == 16
 
 
 def test_sp24q4_roundtrip_word_walk_and_size():
@@ -177,16 +185,19 @@ def test_sp24q4_roundtrip_word_walk_and_size():
     rng = np.random.default_rng(12)
     W = rng.standard_normal((32, 512)).astype(np.float16)
     vals, pos = synth.prune_24(W)
-    codes, zeros, scales = synth.quantize_kept_rtn(vals, pos, 128)
-    qvalues, indices = layout.pack_sp24q4(codes, pos)
-    assert qvalues.size * 4 == 32 * 512 // 4 and indices.size * 4 == 32 * 512 // 8     # 0.25 + 0.125 B per dense weight
-    c2, p2 = layout.unpack_sp24q4(qvalues, indices, 32, 512)
-    assert np.array_equal(c2, codes) and np.array_equal(p2, pos)
     from oracle import linear
-    dense = linear.dequant_sp24q4(codes, pos, zeros, scales, 128)
-    walked = pyref.decode_sp24q4(qvalues, indices, pyref.decode_zeros(layout.pack_zeros(zeros), 32, 4),
-                                 pyref.decode_scales(layout.pack_scales(scales), 32, 4), 32, 512, 128)
-    assert np.array_equal(np.array(walked, dtype=np.float64), dense)
+    for group in (128, 256):
+        codes, zeros, scales = synth.quantize_kept_rtn(vals, pos, group)
+        tiles, meta = layout.pack_sp24q4(codes, pos, zeros, scales, group)
+        assert tiles.size * 4 == 32 * 512 * 3 // 8 and meta.size * 4 == 32 * 512 // 32     # 0.375 + 0.031 B per dense weight
+        c2, p2, z2, s2 = layout.unpack_sp24q4(tiles, meta, 32, 512)
+        assert np.array_equal(c2, codes) and np.array_equal(p2, pos)
+        assert np.array_equal(z2, np.repeat(zeros, group // 128, axis=1))
+        assert np.array_equal(s2.view(np.uint16), np.repeat(scales, group // 128, axis=1).view(np.uint16))
+        dense = linear.dequant_sp24q4(codes, pos, zeros, scales, group)
+        assert np.array_equal(linear.dequant_sp24q4_packed(tiles, meta, 512, 32), dense)
+        walked = pyref.decode_sp24q4(tiles, meta, 32, 512)
+        assert np.array_equal(np.array(walked, dtype=np.float64), dense)
     # exactly two non-pruned positions per group of four (a kept value may still dequantise to zero)
     mask = np.zeros((32, 512), bool)
     mask[np.arange(32)[:, None], 4 * (np.arange(256) // 2)[None, :] + pos] = True

@@ -83,10 +83,9 @@ def test_sparse_quantised_forward_exact_rational():
     W, A, B, x = synth.draw_layer(4, 256, 16, 2, 32)
     vals, pos = synth.prune_24(W.astype(np.float16))
     codes, zeros, scales = synth.quantize_kept_rtn(vals, pos, 128)
-    qvalues, indices = layout.pack_sp24q4(codes, pos)
-    qz, sc = layout.pack_zeros(zeros), layout.pack_scales(scales)
-    y = linear.eora_linear_sp24q4(x, qvalues, indices, sc, qz, layout.pack_f16(A), layout.pack_f16(B), 2, 256, 16, 32, 128)
-    What = pyref.decode_sp24q4(qvalues, indices, pyref.decode_zeros(qz, 16, 2), pyref.decode_scales(sc, 16, 2), 16, 256, 128)
+    tiles, meta = layout.pack_sp24q4(codes, pos, zeros, scales, 128)
+    y = linear.eora_linear_sp24q4(x, tiles, meta, layout.pack_f16(A), layout.pack_f16(B), 2, 256, 16, 32)
+    What = pyref.decode_sp24q4(tiles, meta, 16, 256)
     exact = pyref.exact_forward(pyref.frac_matrix(x), What, pyref.frac_matrix(A), pyref.frac_matrix(B))
     for m in range(2):
         for o in range(16):
