@@ -47,3 +47,7 @@ def test_packed_arrays_have_no_padding():
     assert layout.pack_zeros(np.zeros((d_out, 8), np.uint8)).nbytes == d_out * 8 // 2
     v, i = layout.pack_sp24(np.zeros((d_out, d_in // 2), np.float16), np.tile(np.array([0, 1], np.uint8), (d_out, d_in // 4)))
     assert v.nbytes + i.nbytes == d_out * d_in * 9 // 8
+    pos = np.tile(np.array([0, 1], np.uint8), (d_out, d_in // 4))
+    t, m = layout.pack_sp24q4(np.zeros((d_out, d_in // 2), np.uint8), pos, np.zeros((d_out, 2), np.uint8),
+                              np.ones((d_out, 2), np.float16), 128)
+    assert t.nbytes == d_out * d_in * 3 // 8 and m.nbytes == d_out * (d_in // 128) * 4      # 0.375 + 0.031 B per dense weight
