@@ -399,15 +399,19 @@ __global__ __launch_bounds__(NWR * NWK * 64, 4) void wide_q_kernel(FusedArgs a)
 struct WideCfg { int nwr, nwk, tb; };
 
 // the split of a workgroup into row blocks and ranges, and the token blocks per workgroup, for a shape
-static bool pick_wide(int M, int d_in, int d_out, WideCfg* out)
+static bool pick_wide(int M, int d_in, int d_out, int r, WideCfg* out)
 {
     if (M <= 4 || d_in % 512 != 0) return false;
     const int yblocks = (M + 15) / 16, rbs = d_out / 16;
-    static const int cand[3][2] = {{2, 4}, {1, 8}, {1, 4}};       // more row blocks first: x is fetched once per workgroup
-    for (int c = 0; c < 3; ++c) {
+    // More row blocks per workgroup first: x is fetched once per workgroup, and that traffic (workgroups x 16
+    // tokens x d_in) is what bounds these launches.  Measured on the 8B shapes: with the low-rank term half as
+    // many workgroups as compute units still win; the bare layer wants the chip filled.
+    static const int cand[4][2] = {{4, 2}, {2, 4}, {1, 8}, {1, 4}};
+    for (int c = 0; c < 4; ++c) {
         const int nwr = cand[c][0], nwk = cand[c][1];
         if (d_in % (512 * nwk) != 0) continue;
-        if (((rbs + nwr - 1) / nwr) * yblocks >= 256) { *out = {nwr, nwk, 1}; return true; }
+        const int need = r > 0 ? 128 : (c == 0 ? 192 : 256);
+        if (((rbs + nwr - 1) / nwr) * yblocks >= need) { *out = {nwr, nwk, 1}; return true; }
     }
     return false;                                         // too few rows to fill the chip this way
 }
@@ -415,7 +419,7 @@ static bool pick_wide(int M, int d_in, int d_out, WideCfg* out)
 bool wide_q_fits(int M, int d_in, int d_out, int r)
 {
     WideCfg c;
-    return r <= 512 && pick_wide(M, d_in, d_out, &c);
+    return r <= 512 && pick_wide(M, d_in, d_out, r, &c);
 }
 
 template <int FM, int FA, int FE, int NWR, int NWK, int TB>
@@ -439,7 +443,8 @@ template <int FM, int FA, int FE>
 static hipError_t launch_wide_cfg(const FusedArgs& a, hipStream_t stream)
 {
     WideCfg c;
-    if (!pick_wide(a.M, a.d_in, a.d_out, &c)) return hipErrorInvalidValue;
+    if (!pick_wide(a.M, a.d_in, a.d_out, a.r, &c)) return hipErrorInvalidValue;
+    if (c.nwr == 4) return launch_wide_one<FM, FA, FE, 4, 2, 1>(a, stream);
     if (c.nwr == 2) return launch_wide_one<FM, FA, FE, 2, 4, 1>(a, stream);
     if (c.nwk == 8) return launch_wide_one<FM, FA, FE, 1, 8, 1>(a, stream);
     return launch_wide_one<FM, FA, FE, 1, 4, 1>(a, stream);
