@@ -127,8 +127,10 @@ __global__ __launch_bounds__(NWR * NWK * 64, 4) void wide_q_kernel(FusedArgs a)
 #pragma unroll
     for (int i = 0; i < XN; ++i) {
         const int trow = 4 * (wr + i * NWR) + (lane >> 4);
-        const int grow = m0 + trow < a.M ? m0 + trow : a.M - 1;      // rows beyond the tokens: a valid row, results dropped
-        xsrc[i] = a.x + (size_t)grow * a.d_in + (size_t)wk * GK * 128 + 8 * (lane & 15);
+        // rows beyond the tokens: all their lanes read one and the same valid piece (one cache line per request
+        // instead of sixteen; no divergent branch); their results are dropped
+        const bool live = m0 + trow < a.M;
+        xsrc[i] = a.x + (size_t)(live ? m0 + trow : m0) * a.d_in + (size_t)wk * GK * 128 + (live ? 8 * (lane & 15) : 0);
         xdst[i] = (trow * 16 + ((lane & 15) ^ (trow & 15))) * 16;
     }
     // Workgroups walk their ranges from different starting chunks (quads rotated by rq, the tiles inside a quad
