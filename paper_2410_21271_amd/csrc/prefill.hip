@@ -151,17 +151,34 @@ __device__ __forceinline__ void store_x(const u4 (&v)[PF_XC], unsigned char* buf
     }
 }
 
+// The activation fragments of slice f + 2 are requested from LDS right after the MFMAs of slice f have been
+// issued (two register sets): left to itself the compiler keeps two fragments and waits for each pair of
+// LDS reads right before the two MFMAs that use them, and the LDS latency, not the MFMA pipe, then sets the
+// pace of this phase.
 __device__ __forceinline__ void contract_step(f16v (&acc)[4], const h8 (&bf)[8], const unsigned char* buf, int lane)
 {
     const int tr = lane & 31, kg = lane >> 5;
+    h8 af[2][4];
+#pragma unroll
+    for (int f = 0; f < 2; ++f)
+#pragma unroll
+        for (int mb = 0; mb < 4; ++mb) af[f][mb] = *(const h8*)(buf + x_slot(mb, f, kg, tr));
 #pragma unroll
     for (int f = 0; f < 8; ++f) {
-        h8 af[4];
 #pragma unroll
-        for (int mb = 0; mb < 4; ++mb) af[mb] = *(const h8*)(buf + x_slot(mb, f, kg, tr));
+        for (int mb = 0; mb < 4; ++mb) acc[mb] = mfma32(af[f & 1][mb], bf[f], acc[mb]);
+        if (f + 2 < 8) {
 #pragma unroll
-        for (int mb = 0; mb < 4; ++mb) acc[mb] = mfma32(af[mb], bf[f], acc[mb]);
+            for (int mb = 0; mb < 4; ++mb) af[f & 1][mb] = *(const h8*)(buf + x_slot(mb, f + 2, kg, tr));
+        }
     }
+    __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);            // LDS reads of slices 0 and 1
+#pragma unroll
+    for (int f = 0; f < 6; ++f) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);        // the MFMAs of slice f
+        __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);        // the LDS reads of slice f + 2
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
 }
 
 // FM: format of the first segment's weights (S_Q4, S_Q3 asymmetric; S_Q4S128; S_F16).  EXT: continue over a
