@@ -181,6 +181,8 @@ __device__ __forceinline__ void contract_step(f16v (&acc)[4], const h8 (&bf)[8],
     __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
 }
 
+template <bool V> struct PfFlag { static constexpr bool value = V; };
+
 // FM: format of the first segment's weights (S_Q4, S_Q3 asymmetric; S_Q4S128; S_F16).  EXT: continue over a
 // second segment of fp16 tiles (B) with its own activations (t).
 template <int FM, bool EXT>
@@ -237,35 +239,39 @@ __global__ __launch_bounds__(PF_NT, 2) void prefill_kernel(PrefillArgs ga)
 #else
 #define PF_STAMP(i) do { } while (0)
 #endif
-    // Operands of step s into bf: decode of the prefetched tiles (and the request for the following
-    // step's), or B's tiles for the second segment.  Steps past the end repeat the last one; never used.
+    // Operands of step s into bf.  First segment: decode of the prefetched tiles and the request for the
+    // following step's (fp16 tiles are operands as they are: no prefetch copy).  Second segment: B's tiles.
     h8 bf[8];
-    auto prep = [&](int s) {
-        s = s < GT ? s : GT - 1;
-        if (EXT && s >= G1) {
-            load_b_frags(bf, a.w2, a.K2, Rl, s - G1, lane);
-        } else if constexpr (W16) {
-            load_b_frags(bf, a.w, a.K1, Rl, s, lane);             // fp16 tiles are operands as they are: no prefetch copy
+    const int last1 = (EXT ? G1 : GT) - 1;                        // last step of the first segment
+    auto prep_main = [&](int s) {
+        s = s < last1 ? s : last1;                                // past the end: the last one again, never used
+        if constexpr (W16) {
+            load_b_frags(bf, a.w, a.K1, Rl, s, lane);
         } else {
-            if constexpr (!W16) {
-                decode_wpre<FM>(wp, bf);
-                const int last1 = (EXT ? G1 : GT) - 1;
-                load_wpre<FM>(wp, a, Rl, s + 1 < last1 ? s + 1 : last1, lane);
-            }
+            decode_wpre<FM>(wp, bf);
+            load_wpre<FM>(wp, a, Rl, s + 1 < last1 ? s + 1 : last1, lane);
         }
+    };
+    auto prep_ext = [&](int s) {
+        s = s < GT ? s : GT - 1;
+        load_b_frags(bf, a.w2, a.K2, Rl, s - G1, lane);
     };
     // The two wavefronts that share a SIMD (w and w + 4) run the two halves of a step in opposite order,
     // so that one decodes (VALU) while the other contracts (MFMA): wavefronts 0..3 decode step s at the
     // top of iteration s, wavefronts 4..7 decoded it at the bottom of iteration s - 1.  Measured with
     // both in the same order: the second decoder waits for the first, and its MFMAs then run alone.
-    const bool late = wave >= PF_NW / 2;
-    if (late) prep(sb);
-    for (int s = sb; s < GT; ++s) {
+    // Each order, and each kind of operand preparation, gets a loop of its own under wavefront-uniform
+    // branches: with "if (late)" or "if (second segment)" inside one loop the compiler no longer knows how
+    // many requests follow the one it needs and waits for all of them, i.e. for the x slab requested a
+    // moment ago, at every decode.
+    auto step = [&](auto late_tag, auto ext_tag, int s) {
+        constexpr bool LATE = decltype(late_tag)::value, EXTP = decltype(ext_tag)::value;
         PF_STAMP(4);
         unsigned char* const cur = ((s - sb) & 1) ? buf1 : buf0;
         unsigned char* const nxt = ((s - sb) & 1) ? buf0 : buf1;
-        if (!late) {
-            prep(s);
+        if constexpr (!LATE) {
+            if constexpr (EXTP) prep_ext(s);
+            else prep_main(s);
             // nothing crosses this point: left alone, the scheduler sinks the requests for the next step's
             // weights below the MFMAs, and the next step then starts by waiting for them
             __builtin_amdgcn_sched_barrier(0);
@@ -279,9 +285,10 @@ __global__ __launch_bounds__(PF_NT, 2) void prefill_kernel(PrefillArgs ga)
         // the next step's slab goes to the other buffer (free since the barrier of the step before)
         store_x(xr, nxt, !(W16 || (EXT && s + 1 >= G1)), tid);
         fetch_x(xr, s + 2);
-        if (late) {
+        if constexpr (LATE) {
             __builtin_amdgcn_sched_barrier(0);
-            prep(s + 1);
+            if constexpr (EXTP) prep_ext(s + 1);
+            else prep_main(s + 1);
         }
 #ifdef EORA_TIMELINE
         __builtin_amdgcn_sched_barrier(0);
@@ -289,6 +296,20 @@ __global__ __launch_bounds__(PF_NT, 2) void prefill_kernel(PrefillArgs ga)
 #endif
         __syncthreads();
         PF_STAMP(3);
+    };
+    const int s1 = last1 + 1;                                     // first step of the second segment (= GT without one)
+    if (__builtin_amdgcn_readfirstlane(wave) >= PF_NW / 2) {
+        prep_main(sb);
+        if constexpr (EXT) {
+            for (int s = sb; s < s1 - 1; ++s) step(PfFlag<true>{}, PfFlag<false>{}, s);
+            for (int s = s1 - 1; s < GT; ++s) step(PfFlag<true>{}, PfFlag<true>{}, s);
+        } else {
+            for (int s = sb; s < GT; ++s) step(PfFlag<true>{}, PfFlag<false>{}, s);
+        }
+    } else {
+        for (int s = sb; s < s1; ++s) step(PfFlag<false>{}, PfFlag<false>{}, s);
+        if constexpr (EXT)
+            for (int s = s1; s < GT; ++s) step(PfFlag<false>{}, PfFlag<true>{}, s);
     }
 #ifdef EORA_TIMELINE
     if ((blockIdx.x == 0 || blockIdx.x == 700) && lane == 0)
