@@ -226,9 +226,15 @@ __global__ __launch_bounds__(PF_NT, 2) void prefill_kernel(PrefillArgs ga)
         else load_x(v, a.x, a.ldx, a.M, m0, s * 128, tid);
     };
     u4 xr[PF_XC];
-    WPre<W16 ? S_Q4 : FM> wp;                                     // (unused for fp16 tiles)
+    // the stored tiles of two steps are in flight: one step (about 2 us) is less than a memory round trip
+    // under load.  Step sb + i uses set i & 1 (the loops below are unrolled in pairs: no run-time index).
+    WPre<W16 ? S_Q4 : FM> wp[2];                                  // (unused for fp16 tiles)
     fetch_x(xr, sb);
-    if constexpr (!W16) load_wpre<FM>(wp, a, Rl, sb, lane);
+    if constexpr (!W16) {
+        const int lastw = (EXT ? G1 : GT) - 1;
+        load_wpre<FM>(wp[0], a, Rl, sb, lane);
+        load_wpre<FM>(wp[1], a, Rl, sb + 1 < lastw ? sb + 1 : lastw, lane);
+    }
     store_x(xr, buf0, !W16, tid);
     fetch_x(xr, sb + 1);                                          // xr always holds the slab of the step after the one in LDS
     __syncthreads();
@@ -243,13 +249,14 @@ __global__ __launch_bounds__(PF_NT, 2) void prefill_kernel(PrefillArgs ga)
     // following step's (fp16 tiles are operands as they are: no prefetch copy).  Second segment: B's tiles.
     h8 bf[8];
     const int last1 = (EXT ? G1 : GT) - 1;                        // last step of the first segment
-    auto prep_main = [&](int s) {
+    auto prep_main = [&](auto par_tag, int s) {                   // par_tag: (s - sb) & 1
+        constexpr int PAR = decltype(par_tag)::value ? 1 : 0;
         s = s < last1 ? s : last1;                                // past the end: the last one again, never used
         if constexpr (W16) {
             load_b_frags(bf, a.w, a.K1, Rl, s, lane);
         } else {
-            decode_wpre<FM>(wp, bf);
-            load_wpre<FM>(wp, a, Rl, s + 1 < last1 ? s + 1 : last1, lane);
+            decode_wpre<FM>(wp[PAR], bf);
+            load_wpre<FM>(wp[PAR], a, Rl, s + 2 < last1 ? s + 2 : last1, lane);
         }
     };
     auto prep_ext = [&](int s) {
@@ -264,14 +271,14 @@ __global__ __launch_bounds__(PF_NT, 2) void prefill_kernel(PrefillArgs ga)
     // branches: with "if (late)" or "if (second segment)" inside one loop the compiler no longer knows how
     // many requests follow the one it needs and waits for all of them, i.e. for the x slab requested a
     // moment ago, at every decode.
-    auto step = [&](auto late_tag, auto ext_tag, int s) {
-        constexpr bool LATE = decltype(late_tag)::value, EXTP = decltype(ext_tag)::value;
+    auto step = [&](auto late_tag, auto ext_tag, auto par_tag, int s) {     // par_tag: (s - sb) & 1
+        constexpr bool LATE = decltype(late_tag)::value, EXTP = decltype(ext_tag)::value, PAR = decltype(par_tag)::value;
         PF_STAMP(4);
         unsigned char* const cur = ((s - sb) & 1) ? buf1 : buf0;
         unsigned char* const nxt = ((s - sb) & 1) ? buf0 : buf1;
         if constexpr (!LATE) {
             if constexpr (EXTP) prep_ext(s);
-            else prep_main(s);
+            else prep_main(PfFlag<PAR>{}, s);
             // nothing crosses this point: left alone, the scheduler sinks the requests for the next step's
             // weights below the MFMAs, and the next step then starts by waiting for them
             __builtin_amdgcn_sched_barrier(0);
@@ -288,7 +295,7 @@ __global__ __launch_bounds__(PF_NT, 2) void prefill_kernel(PrefillArgs ga)
         if constexpr (LATE) {
             __builtin_amdgcn_sched_barrier(0);
             if constexpr (EXTP) prep_ext(s + 1);
-            else prep_main(s + 1);
+            else prep_main(PfFlag<!PAR>{}, s + 1);
         }
 #ifdef EORA_TIMELINE
         __builtin_amdgcn_sched_barrier(0);
@@ -298,18 +305,30 @@ __global__ __launch_bounds__(PF_NT, 2) void prefill_kernel(PrefillArgs ga)
         PF_STAMP(3);
     };
     const int s1 = last1 + 1;                                     // first step of the second segment (= GT without one)
+    // steps [from, to) in pairs, so that the parity of a step is known at compile time
+    auto run = [&](auto late_tag, auto ext_tag, int from, int to) {
+        int s = from;
+        if ((s - sb) & 1) {
+            if (s < to) step(late_tag, ext_tag, PfFlag<true>{}, s);
+            ++s;
+        }
+        for (; s + 1 < to; s += 2) {
+            step(late_tag, ext_tag, PfFlag<false>{}, s);
+            step(late_tag, ext_tag, PfFlag<true>{}, s + 1);
+        }
+        if (s < to) step(late_tag, ext_tag, PfFlag<false>{}, s);
+    };
     if (__builtin_amdgcn_readfirstlane(wave) >= PF_NW / 2) {
-        prep_main(sb);
+        prep_main(PfFlag<false>{}, sb);
         if constexpr (EXT) {
-            for (int s = sb; s < s1 - 1; ++s) step(PfFlag<true>{}, PfFlag<false>{}, s);
-            for (int s = s1 - 1; s < GT; ++s) step(PfFlag<true>{}, PfFlag<true>{}, s);
+            run(PfFlag<true>{}, PfFlag<false>{}, sb, s1 - 1);
+            run(PfFlag<true>{}, PfFlag<true>{}, s1 - 1, GT);
         } else {
-            for (int s = sb; s < GT; ++s) step(PfFlag<true>{}, PfFlag<false>{}, s);
+            run(PfFlag<true>{}, PfFlag<false>{}, sb, GT);
         }
     } else {
-        for (int s = sb; s < s1; ++s) step(PfFlag<false>{}, PfFlag<false>{}, s);
-        if constexpr (EXT)
-            for (int s = s1; s < GT; ++s) step(PfFlag<false>{}, PfFlag<true>{}, s);
+        run(PfFlag<false>{}, PfFlag<false>{}, sb, s1);
+        if constexpr (EXT) run(PfFlag<false>{}, PfFlag<true>{}, s1, GT);
     }
 #ifdef EORA_TIMELINE
     if ((blockIdx.x == 0 || blockIdx.x == 700) && lane == 0)
