@@ -78,7 +78,8 @@ typedef enum {
     EORA_ERR_WORKSPACE = -5,   /* workspace missing or smaller than eora_workspace_bytes() */
     EORA_ERR_LAUNCH = -6,      /* the HIP runtime refused a launch (hipGetLastError) */
     EORA_ERR_VALUE = -7,       /* host packer: a code / zero-point / position is out of range */
-    EORA_ERR_TIMEOUT = -8      /* eora_workspace_error: a bounded in-kernel wait expired (results invalid) */
+    EORA_ERR_TIMEOUT = -8,     /* eora_workspace_error: a bounded in-kernel wait expired (results invalid) */
+    EORA_ERR_NOT_CONVERGED = -9 /* eora_factors: the Jacobi sweeps did not settle within their limit */
 } eora_status;
 
 /* HOST.  Static string for a status code. */
@@ -223,6 +224,29 @@ int eora_expand_sp24(const void* values, const void* indices, void* W_f16,
                      int d_in, int d_out, void* stream);
 /* W_f32: d_out x d_in row-major fp32: scale*(code-zero) at the kept positions (exact in fp32), +0 elsewhere. */
 int eora_expand_sp24q4(const void* qtiles, const void* qmeta, void* W_f32, int d_in, int d_out, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Calibration: the factors themselves (Sec. 3, Algorithm 1, steps 1-6), in fp64 on the device.
+ * ------------------------------------------------------------------------------------------ */
+/* HOST.  Scratch eora_factors() needs (five matrices of the size of the weight or of the Gram matrix
+ * in fp64); 0 for invalid arguments. */
+size_t eora_factors_workspace_bytes(int d_in, int d_out, int r);
+/* All pointers DEVICE, 16-byte aligned, row-major.  W_f32, W_hat_f32: d_out x d_in fp32, the weight and
+ * its compressed version (e.g. from eora_dequant_q).  Xt_f32: d_in x n_tokens fp32, the calibration
+ * activations X~ with one column per token.  Outputs: B_f64 = B' = U' Sigma' (d_out x r), A_f64 = A
+ * (r x d_in), sigma_f64 (r singular values of dW Q', descending; may be NULL), so that What + B'A
+ * minimises || (W - What - B'A) X~ ||_F over rank-r corrections (Theorem 1).  Signs of the r components
+ * are arbitrary (B'A is not).  eig_floor in [0, 1): eigenvalues of X~ X~^T below eig_floor times the
+ * largest are raised to it before the inverse square root of step 6 (the paper assumes an invertible Q').
+ * The eigendecomposition and the SVD are one-sided Jacobi iterations; the call SYNCHRONISES `stream`
+ * once per sweep and before returning, and allocates nothing on the device.
+ * Constraints: d_in, d_out even and <= 16384, 1 <= r <= min(d_in, d_out), n_tokens >= 1.
+ * Errors: EORA_ERR_NULL / SHAPE / VALUE (eig_floor) / WORKSPACE / ALIGN / LAUNCH, and
+ * EORA_ERR_NOT_CONVERGED (outputs then undefined). */
+int eora_factors(const void* W_f32, const void* W_hat_f32, const void* Xt_f32,
+                 int n_tokens, int d_in, int d_out, int r, double eig_floor,
+                 void* B_f64, void* A_f64, void* sigma_f64,
+                 void* workspace, size_t workspace_bytes, void* stream);
 
 #ifdef __cplusplus
 }

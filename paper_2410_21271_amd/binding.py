@@ -65,6 +65,8 @@ def _load():
         "eora_dequant_q": (ci, [vp, vp, vp, vp, ci, ci, ci, ci, vp]),
         "eora_expand_sp24": (ci, [vp, vp, vp, ci, ci, vp]),
         "eora_expand_sp24q4": (ci, [vp, vp, vp, ci, ci, vp]),
+        "eora_factors_workspace_bytes": (sz, [ci, ci, ci]),
+        "eora_factors": (ci, [vp, vp, vp, ci, ci, ci, ci, ctypes.c_double, vp, vp, vp, vp, sz, vp]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(L, name)
@@ -79,7 +81,8 @@ EXPORTS = ["eora_status_string", "eora_qweight_bytes", "eora_qzeros_bytes", "eor
            "eora_workspace_error", "eora_debug_set_spin_limit", "eora_pack_q",
            "eora_pack_factor_f16", "eora_pack_factor_q4", "eora_pack_sp24", "eora_linear_q",
            "eora_linear_q_group", "eora_linear_sp24", "eora_unpack_q", "eora_dequant_q", "eora_expand_sp24",
-           "eora_sp24q4_tiles_bytes", "eora_sp24q4_meta_bytes", "eora_pack_sp24q4", "eora_linear_sp24q4", "eora_expand_sp24q4"]
+           "eora_sp24q4_tiles_bytes", "eora_sp24q4_meta_bytes", "eora_pack_sp24q4", "eora_linear_sp24q4", "eora_expand_sp24q4",
+           "eora_factors_workspace_bytes", "eora_factors"]
 
 
 def status_string(status):
@@ -278,3 +281,14 @@ def expand_sp24(values, indices, W_f16, d_in, d_out):
 
 def expand_sp24q4(qtiles, qmeta, W_f32, d_in, d_out):
     _check(lib.eora_expand_sp24q4(_dp(qtiles), _dp(qmeta), _dp(W_f32), d_in, d_out, _stream()), "expand_sp24q4")
+
+
+# ------------------------------------------------------------------ calibration (Alg. 1 steps 1-6)
+def factors_workspace_bytes(d_in, d_out, r):
+    return lib.eora_factors_workspace_bytes(d_in, d_out, r)
+
+
+def factors(W_f32, W_hat_f32, Xt_f32, B_f64, A_f64, sigma_f64, n_tokens, d_in, d_out, r, eig_floor, workspace):
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib.eora_factors(_dp(W_f32), _dp(W_hat_f32), _dp(Xt_f32), n_tokens, d_in, d_out, r, float(eig_floor),
+                            _dp(B_f64), _dp(A_f64), _dp(sigma_f64), _dp(workspace), ws_bytes, _stream()), "factors")

@@ -1,0 +1,482 @@
+// Algorithm 1 (Sec. 3), steps 1-6, in fp64 on the device: the factors B' (d_out x r) and A (r x d_in) that
+// compensate a compressed weight, from the weight, its compressed version and calibration activations.
+//
+//   1  dW = W - What
+//   2  X~ X~^T = Q Lambda Q^T          one-sided Jacobi on the rows of the Gram matrix (rotations accumulated)
+//   3  Q' = Q sqrt(Lambda)
+//   4  dW' = dW Q'
+//   5  rank-r SVD of dW'               one-sided Jacobi on the rows of dW' (or of its transpose, whichever
+//                                      has fewer rows), top r rows by norm
+//   6  A = A' sqrt(Lambda)^-1 Q^T
+//
+// One-sided (Hestenes) Jacobi: plane rotations of row pairs until all rows are mutually orthogonal.  For a
+// symmetric positive semi-definite G, R G with orthogonal rows means R G^2 R^T is diagonal, so the rows of the
+// accumulated rotation R are eigenvectors of G and r_p . (R G)_p its eigenvalues.  For a general matrix T,
+// R T with orthogonal rows is Sigma V^T (row norms = singular values, R = U^T).  A round of the round-robin
+// schedule rotates m/2 disjoint pairs, one workgroup per pair, rows held in registers; m-1 rounds visit every
+// pair once (a sweep); sweeps repeat until one passes without a rotation.
+#include "eora.h"
+
+#include <hip/hip_runtime.h>
+#include <cmath>
+#include <cstdint>
+#include <cstdio>
+#include <cstdlib>
+
+namespace eora {
+namespace {
+
+constexpr int JPT = 8;                 // double2 items per thread and row
+constexpr int MAX_DIM = 16384;         // 2 * JPT * 1024
+constexpr int MAX_SWEEPS = 60;
+
+__device__ inline double wave_sum(double v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+// One round: workgroup i rotates the row pair (p, q) of the round-robin schedule.  H: m x L row-major;
+// V: m x m row-major or nullptr.  rows with squared norm <= abs_floor count as zero.
+template <int NT>
+__global__ __launch_bounds__(NT) void jacobi_round_kernel(double* __restrict__ H, int L, double* __restrict__ V,
+                                                          int m, int round, double tol, double abs_floor,
+                                                          unsigned* __restrict__ rotations)
+{
+    const int i = blockIdx.x, mm = m - 1, tid = threadIdx.x;
+    int p, q;
+    if (i == 0) {
+        p = round;
+        q = mm;
+    } else {
+        p = (round + i) % mm;
+        q = (round + mm - i) % mm;
+    }
+    const int L2 = L >> 1;
+    double2* rp = reinterpret_cast<double2*>(H + (size_t)p * L);
+    double2* rq = reinterpret_cast<double2*>(H + (size_t)q * L);
+    double2 hp[JPT], hq[JPT];
+    double app = 0, aqq = 0, apq = 0;
+#pragma unroll
+    for (int k = 0; k < JPT; ++k) {
+        const int idx = tid + k * NT;
+        hp[k] = hq[k] = make_double2(0.0, 0.0);
+        if (idx < L2) {
+            hp[k] = rp[idx];
+            hq[k] = rq[idx];
+        }
+        app += hp[k].x * hp[k].x + hp[k].y * hp[k].y;
+        aqq += hq[k].x * hq[k].x + hq[k].y * hq[k].y;
+        apq += hp[k].x * hq[k].x + hp[k].y * hq[k].y;
+    }
+    __shared__ double red[3][16];
+    __shared__ double cs[2];
+    __shared__ int go;
+    app = wave_sum(app);
+    aqq = wave_sum(aqq);
+    apq = wave_sum(apq);
+    constexpr int NWV = NT / 64;
+    if ((tid & 63) == 0) {
+        red[0][tid >> 6] = app;
+        red[1][tid >> 6] = aqq;
+        red[2][tid >> 6] = apq;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        double a = 0, b = 0, c = 0;
+        for (int w = 0; w < NWV; ++w) {
+            a += red[0][w];
+            b += red[1][w];
+            c += red[2][w];
+        }
+        int rotate = 0;
+        if (a > abs_floor && b > abs_floor && fabs(c) > tol * sqrt(a) * sqrt(b)) {
+            const double zeta = (b - a) / (2.0 * c);
+            const double t = copysign(1.0, zeta) / (fabs(zeta) + sqrt(1.0 + zeta * zeta));
+            const double co = 1.0 / sqrt(1.0 + t * t);
+            cs[0] = co;
+            cs[1] = co * t;
+            rotate = 1;
+            atomicAdd(rotations, 1u);
+        }
+        go = rotate;
+    }
+    __syncthreads();
+    if (!go) return;
+    const double co = cs[0], si = cs[1];
+#pragma unroll
+    for (int k = 0; k < JPT; ++k) {
+        const int idx = tid + k * NT;
+        if (idx < L2) {
+            rp[idx] = make_double2(co * hp[k].x - si * hq[k].x, co * hp[k].y - si * hq[k].y);
+            rq[idx] = make_double2(si * hp[k].x + co * hq[k].x, si * hp[k].y + co * hq[k].y);
+        }
+    }
+    if (V) {
+        double2* vp = reinterpret_cast<double2*>(V + (size_t)p * m);
+        double2* vq = reinterpret_cast<double2*>(V + (size_t)q * m);
+        for (int idx = tid; idx < (m >> 1); idx += NT) {
+            const double2 a = vp[idx], b = vq[idx];
+            vp[idx] = make_double2(co * a.x - si * b.x, co * a.y - si * b.y);
+            vq[idx] = make_double2(si * a.x + co * b.x, si * a.y + co * b.y);
+        }
+    }
+}
+
+// C[i][j] = sum_k A[i*ai + k*ak] * B[j*bj + k*bk], i < M, j < N, k < K.  64 x 64 outputs per workgroup of
+// 256 threads, 4 x 4 per thread, operands staged through LDS sixteen k at a time.
+template <typename TA, typename TB>
+__global__ __launch_bounds__(256) void gemm_kernel(const TA* __restrict__ A, long ai, long ak, const TB* __restrict__ B,
+                                                   long bj, long bk, double* __restrict__ C, long ldc, int M, int N, int K)
+{
+    __shared__ double As[16][65], Bs[16][65];
+    const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+    const int i0 = blockIdx.y * 64, j0 = blockIdx.x * 64;
+    double acc[4][4] = {};
+    for (int k0 = 0; k0 < K; k0 += 16) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            int ii, kk;
+            if (ak == 1) {
+                kk = tid & 15;
+                ii = (tid >> 4) + 16 * e;
+            } else {
+                ii = tid & 63;
+                kk = (tid >> 6) + 4 * e;
+            }
+            const int gi = i0 + ii, gk = k0 + kk;
+            As[kk][ii] = (gi < M && gk < K) ? (double)A[(size_t)gi * ai + (size_t)gk * ak] : 0.0;
+            int jj, kb;
+            if (bk == 1) {
+                kb = tid & 15;
+                jj = (tid >> 4) + 16 * e;
+            } else {
+                jj = tid & 63;
+                kb = (tid >> 6) + 4 * e;
+            }
+            const int gj = j0 + jj, gkb = k0 + kb;
+            Bs[kb][jj] = (gj < N && gkb < K) ? (double)B[(size_t)gj * bj + (size_t)gkb * bk] : 0.0;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            double a[4], b[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                a[e] = As[k][ty + 16 * e];
+                b[e] = Bs[k][tx + 16 * e];
+            }
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+#pragma unroll
+                for (int f = 0; f < 4; ++f) acc[e][f] += a[e] * b[f];
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+#pragma unroll
+        for (int f = 0; f < 4; ++f) {
+            const int gi = i0 + ty + 16 * e, gj = j0 + tx + 16 * f;
+            if (gi < M && gj < N) C[(size_t)gi * ldc + gj] = acc[e][f];
+        }
+}
+
+__global__ void sub_kernel(const float* __restrict__ W, const float* __restrict__ What, double* __restrict__ dW, size_t n)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dW[i] = (double)W[i] - (double)What[i];
+}
+
+__global__ void identity_kernel(double* __restrict__ V, int m)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < (size_t)m * m) V[i] = (i / m == i % m) ? 1.0 : 0.0;
+}
+
+__global__ void copy_kernel(const double* __restrict__ src, double* __restrict__ dst, size_t n)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = src[i];
+}
+
+__global__ void clear_counter_kernel(unsigned* c) { *c = 0; }
+
+// out[p] = sum_k X[p][k] * Y[p][k]; one workgroup of 256 per row
+__global__ __launch_bounds__(256) void row_dot_kernel(const double* __restrict__ X, const double* __restrict__ Y, int L,
+                                                      double* __restrict__ out)
+{
+    const int p = blockIdx.x;
+    double s = 0;
+    for (int k = threadIdx.x; k < L; k += 256) s += X[(size_t)p * L + k] * Y[(size_t)p * L + k];
+    __shared__ double red[4];
+    s = wave_sum(s);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) out[p] = red[0] + red[1] + red[2] + red[3];
+}
+
+// root[p] = sqrt(max(lam[p], floor * max lam)), inv[p] = 1 / root[p]; one workgroup
+__global__ __launch_bounds__(1024) void eig_roots_kernel(const double* __restrict__ lam, int m, double floor_rel,
+                                                         double* __restrict__ root, double* __restrict__ inv)
+{
+    __shared__ double red[16];
+    __shared__ double top;
+    double mx = -INFINITY;
+    for (int k = threadIdx.x; k < m; k += 1024) mx = fmax(mx, lam[k]);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) mx = fmax(mx, __shfl_xor(mx, o, 64));
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = mx;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double t = red[0];
+        for (int w = 1; w < 16; ++w) t = fmax(t, red[w]);
+        top = t;
+    }
+    __syncthreads();
+    for (int k = threadIdx.x; k < m; k += 1024) {
+        const double r = sqrt(fmax(lam[k], floor_rel * top));
+        root[k] = r;
+        inv[k] = 1.0 / r;
+    }
+}
+
+// X[p][k] *= (by_row ? s[p] : s[k])
+__global__ void scale_kernel(double* __restrict__ X, int rows, int L, const double* __restrict__ s, int by_row)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < (size_t)rows * L) X[i] *= by_row ? s[i / L] : s[i % L];
+}
+
+// idx[rank] = p for the r rows of largest sq (ties: lower row first); sigma[rank] = sqrt(sq[p])
+__global__ void top_rows_kernel(const double* __restrict__ sq, int m, int r, int* __restrict__ idx, double* __restrict__ sigma)
+{
+    const int p = blockIdx.x * blockDim.x + threadIdx.x;
+    if (p >= m) return;
+    const double v = sq[p];
+    int rank = 0;
+    for (int q = 0; q < m; ++q) {
+        const double u = sq[q];
+        rank += (u > v) || (u == v && q < p);
+    }
+    if (rank < r) {
+        idx[rank] = p;
+        sigma[rank] = sqrt(v);
+    }
+}
+
+// dst[i][k] = src[idx[i]][k] * sigma[i]^power   (power = -1: unit rows; 0: copy; -2: divided by the square)
+__global__ void gather_rows_kernel(const double* __restrict__ src, int L, const int* __restrict__ idx,
+                                   const double* __restrict__ sigma, int power, double* __restrict__ dst, int r)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= (size_t)r * L) return;
+    const int row = (int)(i / L), k = (int)(i % L);
+    const double s = sigma[row];
+    const double f = power == 0 ? 1.0 : (power == -1 ? 1.0 / s : 1.0 / (s * s));
+    dst[i] = src[(size_t)idx[row] * L + k] * f;
+}
+
+// dst[o][i] = src[idx[i]][o]   (dst: L x r)
+__global__ void gather_rows_transposed_kernel(const double* __restrict__ src, int L, const int* __restrict__ idx,
+                                              double* __restrict__ dst, int r)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= (size_t)r * L) return;
+    const int o = (int)(i / r), c = (int)(i % r);
+    dst[i] = src[(size_t)idx[c] * L + o];
+}
+
+inline unsigned blocks(size_t n, int per = 256) { return (unsigned)((n + per - 1) / per); }
+
+template <typename TA, typename TB>
+void gemm(const TA* A, long ai, long ak, const TB* B, long bj, long bk, double* C, long ldc, int M, int N, int K,
+          hipStream_t st)
+{
+    hipLaunchKernelGGL((gemm_kernel<TA, TB>), dim3((N + 63) / 64, (M + 63) / 64), dim3(256), 0, st, A, ai, ak, B, bj, bk, C,
+                       ldc, M, N, K);
+}
+
+void jacobi_round(double* H, int L, double* V, int m, int round, double tol, double abs_floor, unsigned* rot, hipStream_t st)
+{
+    const dim3 g(m / 2);
+    const int need = (L / 2 + JPT - 1) / JPT;          // threads that cover a row
+    if (need <= 64)
+        hipLaunchKernelGGL(jacobi_round_kernel<64>, g, dim3(64), 0, st, H, L, V, m, round, tol, abs_floor, rot);
+    else if (need <= 128)
+        hipLaunchKernelGGL(jacobi_round_kernel<128>, g, dim3(128), 0, st, H, L, V, m, round, tol, abs_floor, rot);
+    else if (need <= 256)
+        hipLaunchKernelGGL(jacobi_round_kernel<256>, g, dim3(256), 0, st, H, L, V, m, round, tol, abs_floor, rot);
+    else if (need <= 512)
+        hipLaunchKernelGGL(jacobi_round_kernel<512>, g, dim3(512), 0, st, H, L, V, m, round, tol, abs_floor, rot);
+    else
+        hipLaunchKernelGGL(jacobi_round_kernel<1024>, g, dim3(1024), 0, st, H, L, V, m, round, tol, abs_floor, rot);
+}
+
+// Sweeps until one passes without a rotation.  Synchronises the stream once per sweep.  sq: m doubles of
+// scratch.  Returns the number of sweeps, or -1 if MAX_SWEEPS did not suffice, or -2 on a runtime error.
+int jacobi(double* H, int L, double* V, int m, double* sq, unsigned* rot, hipStream_t st)
+{
+    // rows far below the largest are zero for every purpose here, and rotating them would never settle
+    hipLaunchKernelGGL(row_dot_kernel, dim3(m), dim3(256), 0, st, H, H, L, sq);
+    double* host = (double*)malloc(sizeof(double) * m);
+    if (!host) return -2;
+    if (hipMemcpyAsync(host, sq, sizeof(double) * m, hipMemcpyDeviceToHost, st) != hipSuccess ||
+        hipStreamSynchronize(st) != hipSuccess) {
+        free(host);
+        return -2;
+    }
+    double top = 0;
+    for (int p = 0; p < m; ++p) top = host[p] > top ? host[p] : top;
+    free(host);
+    const double abs_floor = top * 1e-30;
+    const double tol = sqrt((double)L) * 1.1102230246251565e-16;
+    for (int sweep = 1; sweep <= MAX_SWEEPS; ++sweep) {
+        hipLaunchKernelGGL(clear_counter_kernel, dim3(1), dim3(1), 0, st, rot);
+        for (int round = 0; round < m - 1; ++round) jacobi_round(H, L, V, m, round, tol, abs_floor, rot, st);
+        unsigned n = 0;
+        if (hipMemcpyAsync(&n, rot, sizeof(n), hipMemcpyDeviceToHost, st) != hipSuccess ||
+            hipStreamSynchronize(st) != hipSuccess)
+            return -2;
+        if (getenv("EORA_VERBOSE")) fprintf(stderr, "eora: jacobi m=%d L=%d sweep %d: %u rotations\n", m, L, sweep, n);
+        if (n == 0) return sweep;
+    }
+    return -1;
+}
+
+inline size_t r256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+struct Layout {
+    size_t dW, H, V, T, T0, lam, root, inv, sq, sigma, idx, Ap, Bn, rot, total;
+};
+
+Layout layout(int d_in, int d_out, int r)
+{
+    Layout l;
+    size_t o = 0;
+    auto take = [&](size_t bytes) {
+        const size_t at = o;
+        o += r256(bytes);
+        return at;
+    };
+    const size_t big = (size_t)(d_in > d_out ? d_in : d_out);
+    l.dW = take(8 * (size_t)d_out * d_in);
+    l.H = take(8 * (size_t)d_in * d_in);
+    l.V = take(8 * (size_t)d_in * d_in);
+    l.T = take(8 * (size_t)d_out * d_in);
+    l.T0 = take(8 * (size_t)d_out * d_in);
+    l.lam = take(8 * (size_t)d_in);
+    l.root = take(8 * (size_t)d_in);
+    l.inv = take(8 * (size_t)d_in);
+    l.sq = take(8 * big);
+    l.sigma = take(8 * (size_t)r);
+    l.idx = take(4 * (size_t)r);
+    l.Ap = take(8 * (size_t)r * d_in);
+    l.Bn = take(8 * (size_t)r * d_out);
+    l.rot = take(256);
+    l.total = o;
+    return l;
+}
+
+int check_shape(int n_tokens, int d_in, int d_out, int r)
+{
+    if (n_tokens < 1 || d_in < 2 || d_out < 2 || r < 1) return EORA_ERR_SHAPE;
+    if (d_in % 2 || d_out % 2 || d_in > MAX_DIM || d_out > MAX_DIM) return EORA_ERR_SHAPE;
+    if (r > d_in || r > d_out) return EORA_ERR_SHAPE;
+    return EORA_OK;
+}
+
+}  // namespace
+}  // namespace eora
+
+using namespace eora;
+
+extern "C" size_t eora_factors_workspace_bytes(int d_in, int d_out, int r)
+{
+    if (check_shape(1, d_in, d_out, r) != EORA_OK) return 0;
+    return layout(d_in, d_out, r).total;
+}
+
+extern "C" int eora_factors(const void* W_f32, const void* W_hat_f32, const void* Xt_f32, int n_tokens, int d_in, int d_out,
+                            int r, double eig_floor, void* B_f64, void* A_f64, void* sigma_f64, void* workspace,
+                            size_t workspace_bytes, void* stream)
+{
+    if (!W_f32 || !W_hat_f32 || !Xt_f32 || !B_f64 || !A_f64) return EORA_ERR_NULL;
+    const int rc = check_shape(n_tokens, d_in, d_out, r);
+    if (rc != EORA_OK) return rc;
+    if (!(eig_floor >= 0.0) || eig_floor >= 1.0) return EORA_ERR_VALUE;
+    const Layout l = layout(d_in, d_out, r);
+    if (!workspace || workspace_bytes < l.total) return EORA_ERR_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(workspace) & 15u) return EORA_ERR_ALIGN;
+    hipStream_t st = (hipStream_t)stream;
+    char* ws = (char*)workspace;
+    double* dW = (double*)(ws + l.dW);
+    double* H = (double*)(ws + l.H);
+    double* V = (double*)(ws + l.V);
+    double* T = (double*)(ws + l.T);
+    double* T0 = (double*)(ws + l.T0);
+    double* lam = (double*)(ws + l.lam);
+    double* root = (double*)(ws + l.root);
+    double* inv = (double*)(ws + l.inv);
+    double* sq = (double*)(ws + l.sq);
+    double* sigma = (double*)(ws + l.sigma);
+    int* idx = (int*)(ws + l.idx);
+    double* Ap = (double*)(ws + l.Ap);
+    double* Bn = (double*)(ws + l.Bn);
+    unsigned* rot = (unsigned*)(ws + l.rot);
+    const float* W = (const float*)W_f32;
+    const float* What = (const float*)W_hat_f32;
+    const float* Xt = (const float*)Xt_f32;
+    const size_t nw = (size_t)d_out * d_in;
+    const int k = d_in;
+
+    // steps 1, 2: error and Gram matrix, eigenvectors as the rows of V
+    hipLaunchKernelGGL(sub_kernel, dim3(blocks(nw)), dim3(256), 0, st, W, What, dW, nw);
+    gemm(Xt, (long)n_tokens, 1L, Xt, (long)n_tokens, 1L, H, (long)k, k, k, n_tokens, st);
+    hipLaunchKernelGGL(identity_kernel, dim3(blocks((size_t)k * k)), dim3(256), 0, st, V, k);
+    int sweeps = jacobi(H, k, V, k, sq, rot, st);
+    if (sweeps < 0) return sweeps == -1 ? EORA_ERR_NOT_CONVERGED : EORA_ERR_LAUNCH;
+    hipLaunchKernelGGL(row_dot_kernel, dim3(k), dim3(256), 0, st, H, V, k, lam);
+    // step 3: sqrt(Lambda), with eigenvalues below eig_floor * max raised to it
+    hipLaunchKernelGGL(eig_roots_kernel, dim3(1), dim3(1024), 0, st, lam, k, eig_floor, root, inv);
+
+    const bool by_rows = d_out <= d_in;         // which side of dW' has fewer rows to rotate
+    if (by_rows) {
+        // step 4: T = dW' (d_out x k): T[o][j] = root[j] * sum_i dW[o][i] V[j][i]
+        gemm(dW, (long)k, 1L, V, (long)k, 1L, T, (long)k, d_out, k, k, st);
+        hipLaunchKernelGGL(scale_kernel, dim3(blocks(nw)), dim3(256), 0, st, T, d_out, k, root, 0);
+        hipLaunchKernelGGL(copy_kernel, dim3(blocks(nw)), dim3(256), 0, st, T, T0, nw);
+        // step 5: rows of T -> sigma_i v_i^T
+        sweeps = jacobi(T, k, nullptr, d_out, sq, rot, st);
+        if (sweeps < 0) return sweeps == -1 ? EORA_ERR_NOT_CONVERGED : EORA_ERR_LAUNCH;
+        hipLaunchKernelGGL(row_dot_kernel, dim3(d_out), dim3(256), 0, st, T, T, k, sq);
+        hipLaunchKernelGGL(top_rows_kernel, dim3(blocks(d_out)), dim3(256), 0, st, sq, d_out, r, idx, sigma);
+        hipLaunchKernelGGL(gather_rows_kernel, dim3(blocks((size_t)r * k)), dim3(256), 0, st, T, k, idx, sigma, -1, Ap, r);
+        // B' = U' Sigma' = dW' A'^T
+        gemm(T0, (long)k, 1L, Ap, (long)k, 1L, (double*)B_f64, (long)r, d_out, r, k, st);
+    } else {
+        // step 4, transposed: T = dW'^T (k x d_out): T[j][o] = root[j] * sum_i V[j][i] dW[o][i]
+        gemm(V, (long)k, 1L, dW, (long)k, 1L, T, (long)d_out, k, d_out, k, st);
+        hipLaunchKernelGGL(scale_kernel, dim3(blocks(nw)), dim3(256), 0, st, T, k, d_out, root, 1);
+        hipLaunchKernelGGL(copy_kernel, dim3(blocks(nw)), dim3(256), 0, st, T, T0, nw);
+        // step 5: rows of T -> sigma_i u_i^T, the columns of B'
+        sweeps = jacobi(T, d_out, nullptr, k, sq, rot, st);
+        if (sweeps < 0) return sweeps == -1 ? EORA_ERR_NOT_CONVERGED : EORA_ERR_LAUNCH;
+        hipLaunchKernelGGL(row_dot_kernel, dim3(k), dim3(256), 0, st, T, T, d_out, sq);
+        hipLaunchKernelGGL(top_rows_kernel, dim3(blocks(k)), dim3(256), 0, st, sq, k, r, idx, sigma);
+        hipLaunchKernelGGL(gather_rows_transposed_kernel, dim3(blocks((size_t)r * d_out)), dim3(256), 0, st, T, d_out, idx,
+                           (double*)B_f64, r);
+        // A' = Sigma'^-1 U'^T dW' : A'[i][j] = sum_o (sigma_i u_i[o] / sigma_i^2) dW'[o][j]
+        hipLaunchKernelGGL(gather_rows_kernel, dim3(blocks((size_t)r * d_out)), dim3(256), 0, st, T, d_out, idx, sigma, -2, Bn,
+                           r);
+        gemm(Bn, (long)d_out, 1L, T0, (long)d_out, 1L, Ap, (long)k, r, k, d_out, st);
+    }
+    // step 6: A = A' sqrt(Lambda)^-1 Q^T : A[i][j] = sum_e A'[i][e] inv[e] V[e][j]
+    hipLaunchKernelGGL(scale_kernel, dim3(blocks((size_t)r * k)), dim3(256), 0, st, Ap, r, k, inv, 0);
+    gemm(Ap, (long)k, 1L, V, 1L, (long)k, (double*)A_f64, (long)k, r, k, k, st);
+    if (sigma_f64) hipLaunchKernelGGL(copy_kernel, dim3(blocks(r)), dim3(256), 0, st, sigma, (double*)sigma_f64, (size_t)r);
+    if (hipGetLastError() != hipSuccess) return EORA_ERR_LAUNCH;
+    if (hipStreamSynchronize(st) != hipSuccess) return EORA_ERR_LAUNCH;
+    return EORA_OK;
+}

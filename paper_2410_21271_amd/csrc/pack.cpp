@@ -248,6 +248,7 @@ const char* eora_status_string(int status)
         case EORA_ERR_LAUNCH: return "kernel launch failed";
         case EORA_ERR_VALUE: return "value out of range";
         case EORA_ERR_TIMEOUT: return "in-kernel wait timed out";
+        case EORA_ERR_NOT_CONVERGED: return "Jacobi sweeps did not converge";
         default: return "unknown status";
     }
 }

@@ -122,3 +122,17 @@ def draw_layer(seed, d_in, d_out, M, r, outlier_frac=0.0, outlier_scale=20.0):
         ch = rng.choice(d_in, size=n_out, replace=False)
         x[:, ch] *= np.float32(outlier_scale)
     return W, A, B, x.astype(np.float16)
+
+
+def draw_calibration(seed, d_in, n_tokens, outlier_frac=0.01, outlier_scale=20.0):
+    """Calibration activations X-tilde (d_in x n_tokens fp32, one column per token) from PCG64(seed):
+    N(0,1) with per-channel energies spread over e^-1 .. e^1 and a fraction of outlier channels, the
+    shape activation statistics of LLM layers have (stand-in for the paper's calibration sets, Sec. 4.1)."""
+    rng = np.random.default_rng(seed)
+    Xt = rng.standard_normal((d_in, n_tokens), dtype=np.float32)
+    scale = np.exp(rng.uniform(-1.0, 1.0, d_in)).astype(np.float32)
+    if outlier_frac > 0:
+        n_out = max(1, int(round(outlier_frac * d_in)))
+        ch = rng.choice(d_in, size=n_out, replace=False)
+        scale[ch] *= np.float32(outlier_scale)
+    return Xt * scale[:, None]

@@ -1,0 +1,144 @@
+"""GPU parity of Algorithm 1 steps 1-6 (eora_factors, fp64 one-sided Jacobi) against the numpy oracle.
+
+The r components are unique up to sign (distinct singular values), so sigma and the product B'A are
+compared directly and the factors after aligning each component's sign.  Tolerances: both sides work
+in fp64 (unit roundoff 1.1e-16); the Jacobi sweeps stop at relative orthogonality sqrt(L) * 1.1e-16 and
+the eigenvectors of the Gram matrix enter through sqrt(Lambda)^-1 (condition of the synthetic Gram
+matrix <= 2e6), so products agree to about 1e-10 relative; the tests allow 1e-8, and 1e-6 on single
+components, whose sensitivity is 1 / (relative gap between neighbouring singular values, ~1e-3 here).
+"""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    import paper_2410_21271_amd as eora
+    return eora
+
+
+def _inputs(seed, d_in, d_out, n_tokens, w_bits=4, group=128):
+    import synth
+    from oracle import linear
+    W, _, _, _ = synth.draw_layer(seed, d_in, d_out, 1, 0)
+    codes, zeros, scales = synth.quantize_rtn(W, w_bits, group)
+    W_hat = linear.dequant(codes, zeros, scales, group).astype(np.float32)      # exact in fp32
+    Xt = synth.draw_calibration(seed + 1, d_in, n_tokens)
+    return W, W_hat, Xt
+
+
+def _run(eora, W, W_hat, Xt, r, eig_floor=1e-12):
+    import torch
+    d_out, d_in = W.shape
+    n = Xt.shape[1]
+    Wd, Whd, Xd = (torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda() for a in (W, W_hat, Xt))
+    B = torch.full((d_out, r), float("nan"), dtype=torch.float64, device="cuda")
+    A = torch.full((r, d_in), float("nan"), dtype=torch.float64, device="cuda")
+    sig = torch.full((r,), float("nan"), dtype=torch.float64, device="cuda")
+    ws = torch.empty(eora.factors_workspace_bytes(d_in, d_out, r), dtype=torch.uint8, device="cuda")
+    eora.factors(Wd, Whd, Xd, B, A, sig, n, d_in, d_out, r, eig_floor, ws)
+    torch.cuda.synchronize()
+    return B.cpu().numpy(), A.cpu().numpy(), sig.cpu().numpy()
+
+
+def _compare(W, W_hat, Xt, r, B, A, sig):
+    from oracle import calibrate
+    Bo, Ao = calibrate.eora_factors(W, W_hat, Xt, r)
+    sig_o = np.linalg.norm(Bo, axis=0)                      # B' = U' Sigma'
+    assert np.all(np.isfinite(B)) and np.all(np.isfinite(A))
+    assert np.allclose(sig, sig_o, rtol=1e-9, atol=0), np.abs(sig / sig_o - 1).max()
+    P, Po = B @ A, Bo @ Ao
+    assert np.abs(P - Po).max() <= 1e-8 * np.abs(Po).max(), np.abs(P - Po).max() / np.abs(Po).max()
+    sign = np.sign(np.sum(B * Bo, axis=0))
+    assert np.all(sign != 0)
+    assert np.abs(B * sign[None, :] - Bo).max() <= 1e-6 * np.abs(Bo).max()
+    assert np.abs(A * sign[:, None] - Ao).max() <= 1e-6 * np.abs(Ao).max()
+    # Theorem 1 with Eckart-Young: the loss left is the tail of the singular values of dW Q'
+    lam, Q = np.linalg.eigh(calibrate.gram(Xt))
+    tail = np.linalg.svd((W.astype(np.float64) - W_hat) @ (Q * np.sqrt(lam)[None, :]), compute_uv=False)[r:]
+    assert np.isclose(calibrate.layer_loss(W, W_hat, B, A, Xt), np.sqrt(np.sum(tail ** 2)), rtol=1e-8)
+
+
+SHAPES = [
+    # d_in, d_out, n_tokens, r
+    (128, 64, 300, 16),          # fewer output rows: the rows of dW' are rotated
+    (128, 192, 256, 32),         # more output rows: the rows of dW'^T are rotated
+    (256, 256, 600, 32),
+    (384, 130, 1000, 2),         # ragged tiles of the GEMM, tiny rank
+    (640, 256, 1300, 64),        # rows longer than one 64-lane pass
+]
+
+
+@pytest.mark.parametrize("d_in,d_out,n_tokens,r", SHAPES)
+def test_factors_match_oracle(gpu, d_in, d_out, n_tokens, r):
+    W, W_hat, Xt = _inputs(7000 + d_in + d_out, d_in, d_out, n_tokens)
+    B, A, sig = _run(gpu, W, W_hat, Xt, r)
+    _compare(W, W_hat, Xt, r, B, A, sig)
+
+
+def test_planted_rank_r_error_is_recovered_and_served(gpu):
+    """W = What + (rank-r term): Algorithm 1 returns that term, and the compensated quantised layer
+    (steps 1-6 here, step 7 through eora_linear_q) reproduces x.W^T."""
+    import torch
+    import synth
+    from oracle import linear
+    from tests.cases import QCase
+    from tests.gpu_util import dev
+    d_in, d_out, r, M = 256, 128, 32, 5
+    c = QCase(7100, d_in, d_out, M, 0, 4, 128, packer=gpu)
+    L = c.logical
+    W_hat = linear.dequant(L["codes"], L["zeros"], L["scales"], 128)
+    rng = np.random.default_rng(7101)
+    low = (rng.standard_normal((d_out, r)) @ rng.standard_normal((r, d_in)) * 0.002).astype(np.float32)
+    W = (W_hat + low).astype(np.float32)
+    dW = W.astype(np.float64) - W_hat
+    Xt = synth.draw_calibration(7102, d_in, 700)
+    B, A, _ = _run(gpu, W, W_hat.astype(np.float32), Xt, r)
+    # W is rounded to fp32 after the rank-r term was added, so dW is rank r only up to 6e-8 |W|
+    assert np.abs(B @ A - dW).max() <= 1e-5 * np.abs(dW).max()
+    # rebalance the two factors (any invertible r x r matrix between them leaves B'A unchanged) so that
+    # both sit well inside fp16's range, then serve them
+    s = np.sqrt(np.linalg.norm(B, axis=0) / np.linalg.norm(A, axis=1))
+    A16, B16 = (A * s[:, None]).astype(np.float16), (B / s[None, :]).astype(np.float16)
+    qw, sc, qz = dev(c.qw), dev(c.sc), dev(c.qz)
+    Ad, Bd = dev(gpu.pack_factor_f16(A16)), dev(gpu.pack_factor_f16(B16))
+    y = torch.full((M * d_out,), 777.0, dtype=torch.float16, device="cuda")
+    ws = gpu.new_workspace(M, d_in, d_out, r)
+    gpu.linear_q(dev(c.x), qw, sc, qz, Ad, Bd, None, None, y, M, d_in, d_out, r, 4, 128, 16, ws)
+    torch.cuda.synchronize()
+    assert gpu.workspace_error(ws) == 0
+    ref = c.x.astype(np.float64) @ W.astype(np.float64).T
+    err = linear.y_error(y.cpu().numpy().reshape(M, d_out), ref)
+    assert err <= 2e-3, err
+
+
+def test_identity_gram_reduces_to_plain_svd(gpu):
+    """Orthonormal rows of X~ make the projection trivial (Sec. 2, Eq. 2): B'A is the truncated SVD of dW."""
+    from oracle import calibrate
+    d_in, d_out, r = 128, 96, 8
+    W, W_hat, _ = _inputs(7200, d_in, d_out, 16)
+    Qo, _ = np.linalg.qr(np.random.default_rng(7201).standard_normal((512, d_in)))
+    Xt = np.ascontiguousarray(Qo.T, dtype=np.float32)
+    B, A, _ = _run(gpu, W, W_hat, Xt, r)
+    Bs, As = calibrate.plain_svd_factors(W, W_hat, r)
+    # X~ is orthonormal only up to its rounding to fp32 (1e-7), and so is the match
+    assert np.abs(B @ A - Bs @ As).max() <= 1e-4 * np.abs(Bs @ As).max()
+
+
+def test_factors_validation(gpu):
+    import torch
+    t = torch.zeros(64, dtype=torch.float64, device="cuda")
+    ws = torch.empty(gpu.factors_workspace_bytes(128, 64, 8), dtype=torch.uint8, device="cuda")
+    args = lambda **kw: dict(dict(W_f32=t, W_hat_f32=t, Xt_f32=t, B_f64=t, A_f64=t, sigma_f64=None, n_tokens=4, d_in=128,
+                                  d_out=64, r=8, eig_floor=1e-12, workspace=ws), **kw)
+    for bad, code in ((dict(W_f32=None), -1), (dict(d_in=127), -2), (dict(r=65), -2), (dict(r=0), -2),
+                      (dict(n_tokens=0), -2), (dict(d_out=16386), -2), (dict(eig_floor=1.0), -7),
+                      (dict(workspace=None), -5), (dict(workspace=ws[:1024]), -5)):
+        with pytest.raises(gpu.EoraError) as e:
+            gpu.factors(**args(**bad))
+        assert e.value.status == code, (bad, e.value.status)
+    assert gpu.factors_workspace_bytes(127, 64, 8) == 0
