@@ -56,6 +56,13 @@ GROUPS = (("q", "k", "v"), ("o",), ("gate", "up"), ("down",))
 for _r in (64, 256, 512):
     WORKLOADS["llama3-8b-layer-decode-w4g128-r%dq4-M1" % _r] = dict(model="8b", w_bits=4, ab_bits=4, r=_r, M=1, cfg=3)
 DEFAULT = "llama3-8b-layer-decode-w3g128-r128fp16-M1-grouped"
+# Algorithm 1 steps 1-6 (the factors themselves) for one 4096 x 4096 linear of the 8B model, W4 g128 backbone,
+# 8192 calibration tokens; a different metric (seconds per linear), run by calibration_main()
+CALIBRATION = {
+    "llama3-8b-q-factors-w4g128-r128-n8192": dict(d_in=4096, d_out=4096, n_tokens=8192, r=128, w_bits=4, sample=1536),
+    "llama3-8b-k-factors-w4g128-r128-n8192": dict(d_in=4096, d_out=1024, n_tokens=8192, r=128, w_bits=4, sample=1536),
+    "small-factors-w4g128-r64-n2048": dict(d_in=1024, d_out=1024, n_tokens=2048, r=64, w_bits=4, sample=1024),
+}
 
 
 def algorithmic_bytes(d_in, d_out, M, r, w_bits, ab_bits, group=128, sq=False):
@@ -232,12 +239,91 @@ def cpu_baseline(linears, names):
                        "(%.1f s)" % ("/".join(names), total_t)), worst
 
 
+def calibration_inputs(eora, synth, np, torch, seed, d_in, d_out, n_tokens, w_bits):
+    """W (fp32), its compressed version from the library's own dequantisation, and X-tilde, all on the device."""
+    from tests.gpu_util import dev
+    W, _, _, _ = synth.draw_layer(seed, d_in, d_out, 1, 0)
+    codes, zeros, scales = synth.quantize_rtn(W, w_bits, 128)
+    qw, qz, sc = eora.pack_q(codes, zeros, scales, w_bits, 128)
+    W_hat = torch.empty((d_out, d_in), dtype=torch.float32, device="cuda")
+    eora.dequant_q(dev(qw), dev(sc), dev(qz), W_hat, d_in, d_out, w_bits, 128)
+    Xt = synth.draw_calibration(seed + 1, d_in, n_tokens)
+    return torch.from_numpy(W).cuda(), W_hat, torch.from_numpy(Xt).cuda()
+
+
+def calibration_main(args):
+    """One step = Algorithm 1 steps 1-6 for one linear (eora_factors).  The call synchronises, so steps are
+    timed with the host clock between device synchronisations; the dominant kernel (a Jacobi round of the
+    eigendecomposition: two rows of the Gram matrix and of the eigenvector matrix per workgroup) is timed by
+    the library with events on the launch stream."""
+    import numpy as np
+    import torch
+    import synth
+    import paper_2410_21271_amd as eora
+    spec = CALIBRATION[args.workload]
+    d_in, d_out, n, r = spec["d_in"], spec["d_out"], spec["n_tokens"], spec["r"]
+    steps, warmup = min(args.steps, 3), min(args.warmup, 1)
+
+    def run(W, W_hat, Xt, d_in, d_out, n, r):
+        B = torch.zeros((d_out, r), dtype=torch.float64, device="cuda")
+        A = torch.zeros((r, d_in), dtype=torch.float64, device="cuda")
+        ws = torch.empty(eora.factors_workspace_bytes(d_in, d_out, r), dtype=torch.uint8, device="cuda")
+        st = eora.factors(W, W_hat, Xt, B, A, None, n, d_in, d_out, r, 1e-12, ws, stats=True)
+        return B, A, st
+
+    W, W_hat, Xt = calibration_inputs(eora, synth, np, torch, 4242, d_in, d_out, n, spec["w_bits"])
+    for _ in range(warmup):
+        run(W, W_hat, Xt, d_in, d_out, n, r)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        _, _, st = run(W, W_hat, Xt, d_in, d_out, n, r)
+    torch.cuda.synchronize()
+    sec = (time.perf_counter() - t0) / steps
+    # dominant kernel: Jacobi rounds of the eigendecomposition.  Algorithmic bytes of a round: every row of
+    # the Gram matrix read once; a rotated pair also writes its two rows and reads and writes two rows of V.
+    rounds = st["eig_sweeps"] * (d_in - 1)
+    bytes_total = rounds * 8.0 * d_in * d_in + st["eig_rotations"] * 8.0 * (2 * d_in + 4 * d_in)
+    us_round = 1e3 * st["eig_ms"] / rounds
+    roofline = dict(bound="hbm", achieved=round(bytes_total / rounds / us_round / 1e3, 1), peak=HBM_PEAK_GBS, unit="GB/s",
+                    frac=round(bytes_total / rounds / us_round / 1e3 / HBM_PEAK_GBS, 4), traffic=None,
+                    kernel="Jacobi round of the eigendecomposition (rows of length %d, with eigenvector rows)" % d_in,
+                    bytes_per_launch=int(bytes_total / rounds), us_per_launch=round(us_round, 3), launches=rounds)
+    out = dict(metric="seconds for Algorithm 1 steps 1-6 of one %d x %d linear (rank %d, %d calibration tokens)" % (d_out, d_in, r, n),
+               value=round(sec, 4), unit="s", n_gpus=1, steps=steps, warmup=warmup, ms_per_step=round(1e3 * sec, 3),
+               higher_is_better=False, scaling="weak", vs_baseline=None, dtype="f64", data="synthetic",
+               config=dict(workload=args.workload, eig_sweeps=st["eig_sweeps"], eig_seconds=round(st["eig_ms"] / 1e3, 4),
+                           svd_sweeps=st["svd_sweeps"], svd_seconds=round(st["svd_ms"] / 1e3, 4)),
+               roofline=roofline)
+    if not args.no_cpu_baseline:
+        from oracle import calibrate
+        try:
+            from threadpoolctl import threadpool_info
+            threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            threads = os.cpu_count() or 1
+        sd = spec["sample"]                                   # the oracle on a smaller linear of the same recipe
+        so = min(sd, d_out)
+        Ws, Whs, Xs = calibration_inputs(eora, synth, np, torch, 4343, sd, so, 2 * sd, spec["w_bits"])
+        Bg, Ag, _ = run(Ws, Whs, Xs, sd, so, 2 * sd, min(r, so))
+        t0 = time.perf_counter()
+        Bo, Ao = calibrate.eora_factors(Ws.cpu().numpy(), Whs.cpu().numpy(), Xs.cpu().numpy(), min(r, so))
+        cpu_s = time.perf_counter() - t0
+        Po = Bo @ Ao
+        out["config"]["max_err_vs_oracle"] = float("%.3g" % (np.abs((Bg @ Ag).cpu().numpy() - Po).max() / np.abs(Po).max()))
+        scale = (d_in / sd) ** 3 * (0.5 + 0.5 * d_out / d_in) / (0.5 + 0.5 * so / sd)
+        out["cpu_baseline"] = dict(value=round(cpu_s * scale, 2), unit="s", cores=int(threads), kind="oracle",
+                                   sample="numpy float64 oracle on a %d x %d linear with %d tokens took %.2f s; scaled by the "
+                                          "cubic cost of the eigendecomposition and SVD to the full shape" % (so, sd, 2 * sd, cpu_s))
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default=DEFAULT, choices=sorted(WORKLOADS))
+    ap.add_argument("--workload", default=DEFAULT, choices=sorted(WORKLOADS) + sorted(CALIBRATION))
     ap.add_argument("--copies", type=int, default=0, help="distinct weight copies (0 = enough for 1.2 GB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
@@ -261,6 +347,8 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"copy_probe_bytes_read": src.numel(), "copy_probe_bytes_written": src.numel(), "copies": 10}))
         return
+    if args.workload in CALIBRATION:
+        return calibration_main(args)
     spec = WORKLOADS[args.workload]
     shapes = synth.LLAMA3_8B if spec["model"] == "8b" else synth.LLAMA3_70B
     layer_bytes = sum(algorithmic_bytes(di, do, spec["M"], spec["r"], spec["w_bits"], spec["ab_bits"], sq=bool(spec.get("sq")))

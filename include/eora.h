@@ -240,13 +240,15 @@ size_t eora_factors_workspace_bytes(int d_in, int d_out, int r);
  * largest are raised to it before the inverse square root of step 6 (the paper assumes an invertible Q').
  * The eigendecomposition and the SVD are one-sided Jacobi iterations; the call SYNCHRONISES `stream`
  * once per sweep and before returning, and allocates nothing on the device.
+ * stats: HOST pointer to six doubles or NULL: for the eigendecomposition, then for the SVD, the number
+ * of sweeps, the milliseconds its rounds took (events on `stream`) and the rotations applied.
  * Constraints: d_in, d_out even and <= 16384, 1 <= r <= min(d_in, d_out), n_tokens >= 1.
  * Errors: EORA_ERR_NULL / SHAPE / VALUE (eig_floor) / WORKSPACE / ALIGN / LAUNCH, and
  * EORA_ERR_NOT_CONVERGED (outputs then undefined). */
 int eora_factors(const void* W_f32, const void* W_hat_f32, const void* Xt_f32,
                  int n_tokens, int d_in, int d_out, int r, double eig_floor,
                  void* B_f64, void* A_f64, void* sigma_f64,
-                 void* workspace, size_t workspace_bytes, void* stream);
+                 void* workspace, size_t workspace_bytes, void* stream, double* stats);
 
 #ifdef __cplusplus
 }

@@ -66,7 +66,7 @@ def _load():
         "eora_expand_sp24": (ci, [vp, vp, vp, ci, ci, vp]),
         "eora_expand_sp24q4": (ci, [vp, vp, vp, ci, ci, vp]),
         "eora_factors_workspace_bytes": (sz, [ci, ci, ci]),
-        "eora_factors": (ci, [vp, vp, vp, ci, ci, ci, ci, ctypes.c_double, vp, vp, vp, vp, sz, vp]),
+        "eora_factors": (ci, [vp, vp, vp, ci, ci, ci, ci, ctypes.c_double, vp, vp, vp, vp, sz, vp, ctypes.POINTER(ctypes.c_double)]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(L, name)
@@ -288,7 +288,11 @@ def factors_workspace_bytes(d_in, d_out, r):
     return lib.eora_factors_workspace_bytes(d_in, d_out, r)
 
 
-def factors(W_f32, W_hat_f32, Xt_f32, B_f64, A_f64, sigma_f64, n_tokens, d_in, d_out, r, eig_floor, workspace):
+def factors(W_f32, W_hat_f32, Xt_f32, B_f64, A_f64, sigma_f64, n_tokens, d_in, d_out, r, eig_floor, workspace, stats=False):
+    """stats=True returns the six counters of eora_factors' `stats` argument as a dict."""
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    st = (ctypes.c_double * 6)() if stats else None
     _check(lib.eora_factors(_dp(W_f32), _dp(W_hat_f32), _dp(Xt_f32), n_tokens, d_in, d_out, r, float(eig_floor),
-                            _dp(B_f64), _dp(A_f64), _dp(sigma_f64), _dp(workspace), ws_bytes, _stream()), "factors")
+                            _dp(B_f64), _dp(A_f64), _dp(sigma_f64), _dp(workspace), ws_bytes, _stream(), st), "factors")
+    if stats:
+        return dict(eig_sweeps=int(st[0]), eig_ms=st[1], eig_rotations=st[2], svd_sweeps=int(st[3]), svd_ms=st[4], svd_rotations=st[5])

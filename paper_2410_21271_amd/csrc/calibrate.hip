@@ -316,7 +316,31 @@ void jacobi_round(double* H, int L, double* V, int m, int round, double tol, dou
 
 // Sweeps until one passes without a rotation.  Synchronises the stream once per sweep.  sq: m doubles of
 // scratch.  Returns the number of sweeps, or -1 if MAX_SWEEPS did not suffice, or -2 on a runtime error.
-int jacobi(double* H, int L, double* V, int m, double* sq, unsigned* rot, hipStream_t st)
+// stats (may be null): sweeps, milliseconds between two events around the sweeps, rotations applied.
+int jacobi_sweeps(double* H, int L, double* V, int m, double* sq, unsigned* rot, hipStream_t st, double* rotations);
+
+int jacobi(double* H, int L, double* V, int m, double* sq, unsigned* rot, hipStream_t st, double* stats)
+{
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    const bool timed = stats && hipEventCreate(&e0) == hipSuccess && hipEventCreate(&e1) == hipSuccess;
+    if (timed) hipEventRecord(e0, st);
+    double rotations = 0;
+    const int sweeps = jacobi_sweeps(H, L, V, m, sq, rot, st, &rotations);
+    if (timed) {
+        float ms = 0;
+        hipEventRecord(e1, st);
+        hipEventSynchronize(e1);
+        hipEventElapsedTime(&ms, e0, e1);
+        stats[0] = sweeps;
+        stats[1] = ms;
+        stats[2] = rotations;
+    }
+    if (e0) hipEventDestroy(e0);
+    if (e1) hipEventDestroy(e1);
+    return sweeps;
+}
+
+int jacobi_sweeps(double* H, int L, double* V, int m, double* sq, unsigned* rot, hipStream_t st, double* rotations)
 {
     // rows far below the largest are zero for every purpose here, and rotating them would never settle
     hipLaunchKernelGGL(row_dot_kernel, dim3(m), dim3(256), 0, st, H, H, L, sq);
@@ -340,6 +364,7 @@ int jacobi(double* H, int L, double* V, int m, double* sq, unsigned* rot, hipStr
             hipStreamSynchronize(st) != hipSuccess)
             return -2;
         if (getenv("EORA_VERBOSE")) fprintf(stderr, "eora: jacobi m=%d L=%d sweep %d: %u rotations\n", m, L, sweep, n);
+        *rotations += n;
         if (n == 0) return sweep;
     }
     return -1;
@@ -400,7 +425,7 @@ extern "C" size_t eora_factors_workspace_bytes(int d_in, int d_out, int r)
 
 extern "C" int eora_factors(const void* W_f32, const void* W_hat_f32, const void* Xt_f32, int n_tokens, int d_in, int d_out,
                             int r, double eig_floor, void* B_f64, void* A_f64, void* sigma_f64, void* workspace,
-                            size_t workspace_bytes, void* stream)
+                            size_t workspace_bytes, void* stream, double* stats)
 {
     if (!W_f32 || !W_hat_f32 || !Xt_f32 || !B_f64 || !A_f64) return EORA_ERR_NULL;
     const int rc = check_shape(n_tokens, d_in, d_out, r);
@@ -435,7 +460,7 @@ extern "C" int eora_factors(const void* W_f32, const void* W_hat_f32, const void
     hipLaunchKernelGGL(sub_kernel, dim3(blocks(nw)), dim3(256), 0, st, W, What, dW, nw);
     gemm(Xt, (long)n_tokens, 1L, Xt, (long)n_tokens, 1L, H, (long)k, k, k, n_tokens, st);
     hipLaunchKernelGGL(identity_kernel, dim3(blocks((size_t)k * k)), dim3(256), 0, st, V, k);
-    int sweeps = jacobi(H, k, V, k, sq, rot, st);
+    int sweeps = jacobi(H, k, V, k, sq, rot, st, stats);
     if (sweeps < 0) return sweeps == -1 ? EORA_ERR_NOT_CONVERGED : EORA_ERR_LAUNCH;
     hipLaunchKernelGGL(row_dot_kernel, dim3(k), dim3(256), 0, st, H, V, k, lam);
     // step 3: sqrt(Lambda), with eigenvalues below eig_floor * max raised to it
@@ -448,7 +473,7 @@ extern "C" int eora_factors(const void* W_f32, const void* W_hat_f32, const void
         hipLaunchKernelGGL(scale_kernel, dim3(blocks(nw)), dim3(256), 0, st, T, d_out, k, root, 0);
         hipLaunchKernelGGL(copy_kernel, dim3(blocks(nw)), dim3(256), 0, st, T, T0, nw);
         // step 5: rows of T -> sigma_i v_i^T
-        sweeps = jacobi(T, k, nullptr, d_out, sq, rot, st);
+        sweeps = jacobi(T, k, nullptr, d_out, sq, rot, st, stats ? stats + 3 : nullptr);
         if (sweeps < 0) return sweeps == -1 ? EORA_ERR_NOT_CONVERGED : EORA_ERR_LAUNCH;
         hipLaunchKernelGGL(row_dot_kernel, dim3(d_out), dim3(256), 0, st, T, T, k, sq);
         hipLaunchKernelGGL(top_rows_kernel, dim3(blocks(d_out)), dim3(256), 0, st, sq, d_out, r, idx, sigma);
@@ -461,7 +486,7 @@ extern "C" int eora_factors(const void* W_f32, const void* W_hat_f32, const void
         hipLaunchKernelGGL(scale_kernel, dim3(blocks(nw)), dim3(256), 0, st, T, k, d_out, root, 1);
         hipLaunchKernelGGL(copy_kernel, dim3(blocks(nw)), dim3(256), 0, st, T, T0, nw);
         // step 5: rows of T -> sigma_i u_i^T, the columns of B'
-        sweeps = jacobi(T, d_out, nullptr, k, sq, rot, st);
+        sweeps = jacobi(T, d_out, nullptr, k, sq, rot, st, stats ? stats + 3 : nullptr);
         if (sweeps < 0) return sweeps == -1 ? EORA_ERR_NOT_CONVERGED : EORA_ERR_LAUNCH;
         hipLaunchKernelGGL(row_dot_kernel, dim3(k), dim3(256), 0, st, T, T, d_out, sq);
         hipLaunchKernelGGL(top_rows_kernel, dim3(blocks(k)), dim3(256), 0, st, sq, k, r, idx, sigma);
