@@ -134,3 +134,22 @@ def test_linear_q_validation_codes():
     assert L.eora_expand_sp24q4(good, good, null, 256, 32, null) == -1
     assert L.eora_expand_sp24q4(good, good, good, 256, 40, null) == -2
     assert eora.status_string(-4) == "misaligned pointer"
+
+
+def test_factors_validation_codes_and_sizes():
+    """eora_factors validates before its first launch (no pointer is dereferenced on these paths)."""
+    L = eora.lib
+    good, odd, null = ctypes.c_void_p(0x1000), ctypes.c_void_p(0x1008), ctypes.c_void_p(0)
+
+    def call(W=good, Wh=good, Xt=good, n=8, d_in=128, d_out=64, r=8, floor=1e-12, B=good, A=good, ws=good, ws_bytes=1 << 30):
+        return L.eora_factors(W, Wh, Xt, n, d_in, d_out, r, floor, B, A, null, ws, ws_bytes, null, None)
+
+    assert call(W=null) == -1 and call(Xt=null) == -1 and call(A=null) == -1
+    assert call(d_in=127) == -2 and call(d_out=16386) == -2 and call(r=0) == -2 and call(r=65) == -2 and call(n=0) == -2
+    assert call(floor=1.0) == -7 and call(floor=-1e-3) == -7 and call(floor=float("nan")) == -7
+    assert call(ws=null) == -5 and call(ws_bytes=1 << 10) == -5 and call(ws=odd) == -4
+    # five fp64 matrices (dW, G, V, dW', its copy) plus vectors and the r-row staging buffers
+    n = eora.factors_workspace_bytes(4096, 4096, 128)
+    assert 5 * 8 * 4096 * 4096 <= n <= 5 * 8 * 4096 * 4096 + (1 << 24)
+    assert eora.factors_workspace_bytes(4096, 4097, 128) == 0 and eora.factors_workspace_bytes(64, 64, 65) == 0
+    assert eora.status_string(-9) == "Jacobi sweeps did not converge"
