@@ -139,6 +139,42 @@ def eora_linear_sp24q4(x, tiles, meta, A, B, M, d_in, d_out, r):
     return eora_linear(x, W_hat, Ad, Bd)
 
 
+def eora_linear_multi(x, W_hat, adapters, adapter_of_row):
+    """One compressed backbone, several compensations: token row m gets
+    y[m] = x[m] What^T + (x[m] A_a^T) B_a^T with a = adapter_of_row[m], and the bare
+    y[m] = x[m] What^T for a = -1.
+
+    The compensation is a separate residual path that never alters What (Sec. 1, Sec. 3), so
+    requests with different (B', A) pairs, or none, can share one batch; row by row this is the
+    forward equation of Sec. 3 with that row's pair.  adapters: list of (A, B).
+    """
+    x = np.asarray(x).astype(np.float64)
+    W_hat = np.asarray(W_hat, dtype=np.float64)
+    y = np.empty((x.shape[0], W_hat.shape[0]), dtype=np.float64)
+    for m in range(x.shape[0]):
+        a = int(adapter_of_row[m])
+        if a < -1 or a >= len(adapters):
+            raise ValueError("adapter index out of range")
+        y[m] = W_hat @ x[m]
+        if a >= 0:
+            A = np.asarray(adapters[a][0]).astype(np.float64)
+            B = np.asarray(adapters[a][1]).astype(np.float64)
+            y[m] += B @ (A @ x[m])
+    return y
+
+
+def eora_linear_q_multi(x, qweight, scales, qzeros, A_all, B_all, A_scales, B_scales, adapter_of_row,
+                        M, d_in, d_out, r, n_adapters, w_bits, group, ab_bits):
+    """The same from stored bytes: A_all holds the adapters' A stacked by rows (n_adapters*r x d_in),
+    B_all their B side by side (d_out x n_adapters*r), each packed as one factor."""
+    x = np.asarray(x, dtype=np.float16).reshape(M, d_in)
+    W_hat = dequant_q(qweight, qzeros, scales, d_in, d_out, w_bits, group)
+    R = n_adapters * r
+    Ad, Bd = _factors(A_all, B_all, A_scales, B_scales, d_in, d_out, R, ab_bits)
+    adapters = [(Ad[a * r:(a + 1) * r], Bd[:, a * r:(a + 1) * r]) for a in range(n_adapters)]
+    return eora_linear_multi(x, W_hat, adapters, adapter_of_row)
+
+
 def _factors(A, B, A_scales, B_scales, d_in, d_out, r, ab_bits):
     if ab_bits == 16:
         return layout.unpack_f16(A, r, d_in), layout.unpack_f16(B, d_out, r)

@@ -191,3 +191,77 @@ def test_y_error_rule():
     got = ref + np.array([[0.1, 0.0, 0.2, 0.0]])
     assert np.isclose(linear.y_error(got, ref), 0.2 / rms)   # the zero entry is floored at rms
     assert linear.y_error(ref, ref) == 0.0
+
+
+# ---------------------------------------------------------------- several adapters over one backbone
+def _multi_setup(seed, d_in=256, d_out=32, M=9, r=32, n=3):
+    rng = np.random.default_rng(seed)
+    W_hat = rng.integers(-7, 8, (d_out, d_in)).astype(np.float64)
+    ads = [(rng.integers(-3, 4, (r, d_in)).astype(np.float64), rng.integers(-3, 4, (d_out, r)).astype(np.float64))
+           for _ in range(n)]
+    x = rng.integers(-4, 5, (M, d_in)).astype(np.float64)
+    sel = rng.integers(-1, n, M)
+    sel[0], sel[1] = -1, n - 1                      # both ends of the range are present
+    return W_hat, ads, x, sel
+
+
+def test_multi_adapter_exact_rational_brute_force():
+    """Integer-valued operands: every row's result is an exact integer, computed here with Python
+    integers element by element from the per-row definition."""
+    W_hat, ads, x, sel = _multi_setup(40, d_in=24, d_out=5, M=6, r=3, n=3)
+    got = linear.eora_linear_multi(x, W_hat, ads, sel)
+    for m in range(x.shape[0]):
+        for o in range(W_hat.shape[0]):
+            want = sum(int(W_hat[o, i]) * int(x[m, i]) for i in range(x.shape[1]))
+            if sel[m] >= 0:
+                A, B = ads[sel[m]]
+                for k in range(A.shape[0]):
+                    t = sum(int(A[k, i]) * int(x[m, i]) for i in range(x.shape[1]))
+                    want += int(B[o, k]) * t
+            assert got[m, o] == want
+
+
+def test_multi_adapter_special_cases():
+    W_hat, ads, x, sel = _multi_setup(41)
+    M, n = x.shape[0], len(ads)
+    # one adapter for every row is the single-adapter layer; none is the bare layer
+    for a in range(n):
+        assert np.array_equal(linear.eora_linear_multi(x, W_hat, ads, np.full(M, a)), linear.eora_linear(x, W_hat, *ads[a]))
+    assert np.array_equal(linear.eora_linear_multi(x, W_hat, ads, np.full(M, -1)), linear.eora_linear(x, W_hat))
+    # rows are independent: a row's result depends on its own selection only
+    full = linear.eora_linear_multi(x, W_hat, ads, sel)
+    for m in range(M):
+        one = linear.eora_linear_multi(x[m:m + 1], W_hat, ads, sel[m:m + 1])
+        assert np.array_equal(one[0], full[m])
+    with pytest.raises(ValueError):
+        linear.eora_linear_multi(x, W_hat, ads, np.full(M, n))
+
+
+def test_multi_adapter_equals_masked_stacked_factors():
+    """Stacking the A's by rows and the B's side by side, and zeroing in t = x A_all^T every column that
+    does not belong to the row's adapter, is the same map (the identity the GPU path is built on)."""
+    W_hat, ads, x, sel = _multi_setup(42)
+    r = ads[0][0].shape[0]
+    A_all = np.vstack([A for A, _ in ads])
+    B_all = np.hstack([B for _, B in ads])
+    t = x @ A_all.T
+    mask = (np.arange(A_all.shape[0])[None, :] // r) == sel[:, None]
+    want = x @ W_hat.T + (t * mask) @ B_all.T
+    assert np.array_equal(linear.eora_linear_multi(x, W_hat, ads, sel), want)
+
+
+def test_multi_adapter_from_stored_bytes():
+    d_in, d_out, M, r, n = 256, 32, 5, 32, 2
+    W, _, _, x = synth.draw_layer(43, d_in, d_out, M, 0)
+    codes, zeros, scales = synth.quantize_rtn(W, 4, 128)
+    qw, qz, sc = layout.pack_q4(codes), layout.pack_zeros(zeros), layout.pack_scales(scales)
+    rng = np.random.default_rng(44)
+    As = [(rng.standard_normal((r, d_in)) * 0.01).astype(np.float16) for _ in range(n)]
+    Bs = [(rng.standard_normal((d_out, r)) * 0.01).astype(np.float16) for _ in range(n)]
+    sel = np.array([1, -1, 0, 0, 1])
+    got = linear.eora_linear_q_multi(x, qw, sc, qz, layout.pack_f16(np.vstack(As)), layout.pack_f16(np.hstack(Bs)), None, None,
+                                     sel, M, d_in, d_out, r, n, 4, 128, 16)
+    W_hat = linear.dequant(codes, zeros, scales, 128)
+    for m in range(M):
+        want = linear.eora_linear(x[m:m + 1], W_hat, *((As[sel[m]], Bs[sel[m]]) if sel[m] >= 0 else (None, None)))
+        assert np.allclose(got[m], want[0], rtol=1e-13, atol=1e-15)
