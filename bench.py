@@ -42,6 +42,11 @@ WORKLOADS = {
     "llama3-70b-layer-decode-sp24q4-bare-M1": dict(model="70b", w_bits=0, sq=True, ab_bits=16, r=0, M=1, cfg=5),
     "llama3-70b-layer-decode-sp24q4-r128fp16-M64": dict(model="70b", w_bits=0, sq=True, ab_bits=16, r=128, M=64, cfg=5),
 }
+# four rank-128 adapters over one backbone, chosen per request (token row); r is their ranks together
+WORKLOADS["llama3-8b-layer-decode-w4g128-4xr128fp16-M64-multi"] = dict(model="8b", w_bits=4, ab_bits=16, r=512, M=64, cfg=1, multi=4)
+WORKLOADS["llama3-8b-layer-decode-w4g128-4xr128fp16-M8-multi"] = dict(model="8b", w_bits=4, ab_bits=16, r=512, M=8, cfg=1, multi=4)
+WORKLOADS["llama3-8b-layer-decode-w4g128-r512fp16-M64"] = dict(model="8b", w_bits=4, ab_bits=16, r=512, M=64, cfg=1)    # same bytes, one adapter
+WORKLOADS["llama3-8b-layer-decode-w4g128-r128fp16-M64"] = dict(model="8b", w_bits=4, ab_bits=16, r=128, M=64, cfg=1)
 # the paper's speed table is on a 70B model: the quantised layer at those shapes (not a BASELINE config)
 WORKLOADS["llama3-70b-layer-decode-w3g128-r128fp16-M1"] = dict(model="70b", w_bits=3, ab_bits=16, r=128, M=1, cfg=2)
 WORKLOADS["llama3-70b-layer-decode-w3g128-bare-M1"] = dict(model="70b", w_bits=3, ab_bits=16, r=0, M=1, cfg=2)
@@ -95,6 +100,10 @@ class Linear:
         self.name, self.d_in, self.d_out = name, d_in, d_out
         self.M, self.r, self.w_bits, self.ab_bits = spec["M"], spec["r"], spec["w_bits"], spec["ab_bits"]
         self.sq = bool(spec.get("sq", False))
+        self.multi = int(spec.get("multi", 0))
+        if self.multi:                                    # adapter of each request: none, or one of the adapters, seeded
+            self.sel = np.random.default_rng(seed + 7).integers(-1, self.multi, self.M).astype(np.int32)
+            self.sel_dev = torch.from_numpy(self.sel).cuda()
         W, A, B, x = synth.draw_layer(seed, d_in, d_out, self.M, self.r, spec.get("outlier", 0.0))
         if self.w_bits == 0 and self.sq:
             vals, pos = synth.prune_24(W.astype(np.float16))
@@ -139,6 +148,10 @@ class Linear:
             return
         if self.w_bits == 0:
             eora.linear_sp24(self.x, qw, sc, A, B, self.y, self.M, self.d_in, self.d_out, self.r, self.ws)
+            return
+        if self.multi:
+            eora.linear_q_multi(self.x, qw, sc, qz, A, B, As, Bs, self.sel_dev, self.y, self.M, self.d_in, self.d_out,
+                                self.r // self.multi, self.multi, self.w_bits, 128, self.ab_bits, self.ws)
             return
         eora.linear_q(self.x, qw, sc, qz, A, B, As, Bs, self.y, self.M, self.d_in, self.d_out, self.r,
                       self.w_bits, 128, self.ab_bits, self.ws)
@@ -230,7 +243,11 @@ def cpu_baseline(linears, names):
             Ap, As = layout.pack_q4(A[0], 128), layout.pack_scales(A[1])
             Bp, Bs = layout.pack_q4(B[0], min(128, L.r)), layout.pack_scales(B[1])
         t0 = time.perf_counter()
-        y = linear.eora_linear_q(x, qw, sc, qz, Ap, Bp, As, Bs, L.M, L.d_in, L.d_out, L.r, L.w_bits, 128, L.ab_bits)
+        if L.multi:
+            y = linear.eora_linear_q_multi(x, qw, sc, qz, Ap, Bp, As, Bs, L.sel, L.M, L.d_in, L.d_out, L.r // L.multi, L.multi,
+                                           L.w_bits, 128, L.ab_bits)
+        else:
+            y = linear.eora_linear_q(x, qw, sc, qz, Ap, Bp, As, Bs, L.M, L.d_in, L.d_out, L.r, L.w_bits, 128, L.ab_bits)
         total_t += time.perf_counter() - t0
         total_b += L.bytes
         worst = max(worst, linear.y_error(L.y.cpu().numpy(), y))

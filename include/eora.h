@@ -194,6 +194,24 @@ int eora_linear_q_group(const void* x, const eora_q_member* members, int n_membe
                         int M, int d_in, int r, int w_bits, int group, int ab_bits,
                         void* workspace, size_t workspace_bytes, void* stream);
 
+/* Several adapters over one backbone in one batch: token row m is compensated with the pair
+ * (A_a, B_a), a = adapter_of_row[m] in [0, n_adapters), or not at all for a = -1:
+ *      y[m] = x[m].What^T + (x[m].A_a^T).B_a^T
+ * (Sec. 1, Sec. 3: the compensation is a separate residual path that leaves What untouched, so pairs
+ * fitted for different tasks can be loaded next to one backbone and chosen per request.)
+ * A_all: the adapters' A stacked by rows, (n_adapters*r) x d_in, packed as ONE factor (eora_pack_factor_*);
+ * B_all: their B side by side, d_out x (n_adapters*r), packed as one factor; A_scales / B_scales likewise
+ * for ab_bits == 4.  adapter_of_row: DEVICE, M int32, read by the kernel (values outside [-1, n_adapters)
+ * behave as -1).  All adapters are streamed whatever the rows select; the backbone is streamed once.
+ * Constraints: as eora_linear_q with rank n_adapters*r (<= 512); r % 32 == 0 (r % 128 == 0 for
+ * ab_bits == 4, so that no scale group spans two adapters); workspace of
+ * eora_workspace_bytes(M, d_in, d_out, n_adapters*r).  Errors as eora_linear_q. */
+int eora_linear_q_multi(const void* x, const void* qweight, const void* scales, const void* qzeros,
+                        const void* A_all, const void* B_all, const void* A_scales, const void* B_scales,
+                        const void* adapter_of_row, void* y,
+                        int M, int d_in, int d_out, int r, int n_adapters, int w_bits, int group, int ab_bits,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
 /* Same layer with a 2:4 structured-sparse fp16 backbone (Sec. 1, Sec. 4.2); A, B are F16 tiles.
  * Constraints as above with r % 32 == 0. */
 int eora_linear_sp24(const void* x, const void* values, const void* indices,

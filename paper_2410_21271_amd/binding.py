@@ -58,6 +58,7 @@ def _load():
         "eora_pack_sp24": (ci, [vp, vp, ci, ci, vp, vp]),
         "eora_pack_sp24q4": (ci, [vp, vp, vp, vp, ci, ci, ci, vp, vp]),
         "eora_linear_q": (ci, [vp] * 9 + [ci] * 7 + [vp, sz, vp]),
+        "eora_linear_q_multi": (ci, [vp] * 10 + [ci] * 8 + [vp, sz, vp]),
         "eora_linear_q_group": (ci, [vp, ctypes.POINTER(QMember), ci] + [ci] * 6 + [vp, sz, vp]),
         "eora_linear_sp24": (ci, [vp] * 6 + [ci] * 4 + [vp, sz, vp]),
         "eora_linear_sp24q4": (ci, [vp] * 6 + [ci] * 4 + [vp, sz, vp]),
@@ -82,7 +83,7 @@ EXPORTS = ["eora_status_string", "eora_qweight_bytes", "eora_qzeros_bytes", "eor
            "eora_pack_factor_f16", "eora_pack_factor_q4", "eora_pack_sp24", "eora_linear_q",
            "eora_linear_q_group", "eora_linear_sp24", "eora_unpack_q", "eora_dequant_q", "eora_expand_sp24",
            "eora_sp24q4_tiles_bytes", "eora_sp24q4_meta_bytes", "eora_pack_sp24q4", "eora_linear_sp24q4", "eora_expand_sp24q4",
-           "eora_factors_workspace_bytes", "eora_factors"]
+           "eora_factors_workspace_bytes", "eora_factors", "eora_linear_q_multi"]
 
 
 def status_string(status):
@@ -281,6 +282,14 @@ def expand_sp24(values, indices, W_f16, d_in, d_out):
 
 def expand_sp24q4(qtiles, qmeta, W_f32, d_in, d_out):
     _check(lib.eora_expand_sp24q4(_dp(qtiles), _dp(qmeta), _dp(W_f32), d_in, d_out, _stream()), "expand_sp24q4")
+
+
+def linear_q_multi(x, qweight, scales, qzeros, A_all, B_all, A_scales, B_scales, adapter_of_row, y, M, d_in, d_out, r,
+                   n_adapters, w_bits, group, ab_bits, workspace):
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib.eora_linear_q_multi(_dp(x), _dp(qweight), _dp(scales), _dp(qzeros), _dp(A_all), _dp(B_all), _dp(A_scales),
+                                   _dp(B_scales), _dp(adapter_of_row), _dp(y), M, d_in, d_out, r, n_adapters, w_bits, group,
+                                   ab_bits, _dp(workspace), ws_bytes, _stream()), "linear_q_multi")
 
 
 # ------------------------------------------------------------------ calibration (Alg. 1 steps 1-6)

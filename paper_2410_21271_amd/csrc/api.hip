@@ -309,6 +309,50 @@ int eora_linear_q(const void* x, const void* qweight, const void* scales, const 
     return run_linear_q(x, e, M, d_in, r, w_bits, group, ab_bits, fa, fe, workspace, stream);
 }
 
+int eora_linear_q_multi(const void* x, const void* qweight, const void* scales, const void* qzeros,
+                        const void* A_all, const void* B_all, const void* A_scales, const void* B_scales,
+                        const void* adapter_of_row, void* y, int M, int d_in, int d_out, int r, int n_adapters,
+                        int w_bits, int group, int ab_bits, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (n_adapters < 1 || r < 1 || r % 32 || (ab_bits == 4 && r % 128)) return EORA_ERR_SHAPE;
+    if ((long long)n_adapters * r > MAX_RANK) return EORA_ERR_SHAPE;
+    if (!adapter_of_row) return EORA_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(adapter_of_row) & 3u) return EORA_ERR_ALIGN;
+    const int R = n_adapters * r;
+    const eora_q_member e{qweight, scales, qzeros, A_all, B_all, A_scales, B_scales, y, d_out};
+    int fa, fe;
+    const int rc = validate_linear_q(x, e, M, d_in, R, w_bits, group, ab_bits, workspace, workspace_bytes, &fa, &fe);
+    if (rc != EORA_OK) return rc;
+    if (M == 0) return EORA_OK;
+    const int kcn = pick_kcn(M, d_in);
+    for (int m0 = 0; m0 < M; m0 += CHUNK_TOKENS) {
+        FusedArgs a{};
+        a.x = (const _Float16*)x + (size_t)m0 * d_in;
+        a.w = qweight;
+        a.w_scales = (const _Float16*)scales;
+        a.w_zeros = (const uint32_t*)qzeros;
+        a.A = A_all;
+        a.A_scales = (const _Float16*)A_scales;
+        a.B = B_all;
+        a.B_scales = (const _Float16*)B_scales;
+        a.y = (_Float16*)y + (size_t)m0 * d_out;
+        a.hdr = (uint32_t*)workspace;
+        a.tpart = (float*)((char*)workspace + WS_PARTS);
+        a.tpair = (unsigned long long*)((char*)workspace + WS_PAIRS);
+        a.M = M - m0 < CHUNK_TOKENS ? M - m0 : CHUNK_TOKENS;
+        a.d_in = d_in;
+        a.d_out = d_out;
+        a.r = R;
+        a.group = group;
+        a.kcn = kcn;
+        a.spin_limit = g_spin_limit;
+        a.adapter = (const int*)adapter_of_row + m0;
+        a.r_per = r;
+        if (failed(launch_fused(a, w_bits == 4 ? S_Q4 : S_Q3, fa, fe, (hipStream_t)stream), "linear_q_multi")) return EORA_ERR_LAUNCH;
+    }
+    return EORA_OK;
+}
+
 int eora_linear_q_group(const void* x, const eora_q_member* members, int n_members,
                         int M, int d_in, int r, int w_bits, int group, int ab_bits,
                         void* workspace, size_t workspace_bytes, void* stream)

@@ -258,6 +258,9 @@ __global__ __launch_bounds__(NW * 64) void fused_kernel(FusedArgs a)
                     v[0] = w[0]; v[1] = w[1]; v[2] = w[2]; v[3] = w[3];
                 }
                 good_all = good_all && good;
+                if (a.adapter) {       // the four columns e % r .. + 3 belong to one adapter (r_per is a multiple of 4)
+                    if (a.adapter[m_blk + e / a.r] != (e % a.r) / a.r_per) v[0] = v[1] = v[2] = v[3] = 0.f;
+                }
                 *(f4*)(ts + e) = f4{v[0], v[1], v[2], v[3]};
             }
             if (!good_all) atomicOr(&a.hdr[HDR_ERROR], 1u);            // never expected

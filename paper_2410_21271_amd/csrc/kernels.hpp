@@ -39,6 +39,11 @@ struct FusedArgs {
     float* tpart;             // (timeline builds: stamps)
     unsigned long long* tpair;   // token blocks x kcn x 16 x r (value, tag) pairs: partials of t
     int M, d_in, d_out, r, group, kcn, spin_limit;
+    // several adapters side by side in A and B (r = their ranks together): token row m keeps only the
+    // r_per columns of t that belong to adapter[m] (-1: none).  nullptr: one adapter, nothing masked.
+    // Read by fused.hip only.
+    const int* adapter;
+    int r_per;
 };
 
 hipError_t launch_fused(const FusedArgs& a, int fm, int fa, int fe, hipStream_t stream);

@@ -82,3 +82,24 @@ def run_linear_sp24q4(c, ws=None):
     eora.linear_sp24q4(xd, t[0], t[1], A, B, y, c.M, c.d_in, c.d_out, c.r, ws)
     torch.cuda.synchronize()
     return y.cpu().numpy().reshape(c.M, c.d_out)
+
+
+def run_linear_q_multi(c, sel, r_per, ws=None):
+    """Run eora_linear_q_multi on case c, whose factors of rank c.r are c.r / r_per adapters side by side;
+    sel: int32 numpy, one adapter index (or -1) per token row.  Returns y as float16 numpy (M x d_out)."""
+    n = c.r // r_per
+    xd = dev(c.x)
+    qw, sc, qz = dev(c.qw), dev(c.sc), dev(c.qz)
+    A, B, As, Bs = dev(c.A), dev(c.B), dev(c.As), dev(c.Bs)
+    seld = torch.from_numpy(np.ascontiguousarray(sel, dtype=np.int32)).cuda()
+    ws = eora.new_workspace(c.M, c.d_in, c.d_out, c.r) if ws is None else ws
+    pad = 64
+    ybuf = torch.full((c.M * c.d_out + 2 * pad,), 777.0, dtype=torch.float16, device="cuda")
+    y = ybuf[pad: pad + c.M * c.d_out]
+    eora.linear_q_multi(xd, qw, sc, qz, A, B, As, Bs, seld, y, c.M, c.d_in, c.d_out, r_per, n, c.w_bits, c.group,
+                        c.ab_bits, ws)
+    torch.cuda.synchronize()
+    assert eora.workspace_error(ws) == 0
+    out = ybuf.cpu().numpy()
+    assert np.all(out[:pad] == 777.0) and np.all(out[pad + c.M * c.d_out:] == 777.0), "write outside y"
+    return out[pad: pad + c.M * c.d_out].reshape(c.M, c.d_out)

@@ -153,3 +153,18 @@ def test_factors_validation_codes_and_sizes():
     assert 5 * 8 * 4096 * 4096 <= n <= 5 * 8 * 4096 * 4096 + (1 << 24)
     assert eora.factors_workspace_bytes(4096, 4097, 128) == 0 and eora.factors_workspace_bytes(64, 64, 65) == 0
     assert eora.status_string(-9) == "Jacobi sweeps did not converge"
+
+
+def test_linear_q_multi_validation_codes():
+    L = eora.lib
+    good, odd, null = ctypes.c_void_p(0x1000), ctypes.c_void_p(0x1002), ctypes.c_void_p(0)
+
+    def call(sel=good, A=good, M=4, r=32, n=2, w_bits=4, ab_bits=16, As=null, Bs=null, ws=good, ws_bytes=1 << 24):
+        return L.eora_linear_q_multi(good, good, good, good, A, good, As, Bs, sel, good, M, 256, 32, r, n, w_bits, 128, ab_bits,
+                                     ws, ws_bytes, null)
+
+    assert call(sel=null) == -1 and call(A=null) == -1 and call(sel=odd) == -4
+    assert call(n=0) == -2 and call(r=16) == -2 and call(r=0) == -2 and call(n=17) == -2
+    assert call(ab_bits=4, r=64, As=good, Bs=good) == -2 and call(ab_bits=4, r=128, n=2) == -1
+    assert call(w_bits=5) == -3 and call(ws=null) == -5 and call(ws_bytes=16) == -5
+    assert call(M=0) == 0
