@@ -348,7 +348,10 @@ int eora_linear_q_multi(const void* x, const void* qweight, const void* scales, 
         a.spin_limit = g_spin_limit;
         a.adapter = (const int*)adapter_of_row + m0;
         a.r_per = r;
-        if (failed(launch_fused(a, w_bits == 4 ? S_Q4 : S_Q3, fa, fe, (hipStream_t)stream), "linear_q_multi")) return EORA_ERR_LAUNCH;
+        const int fm = w_bits == 4 ? S_Q4 : S_Q3;
+        const hipError_t err = wide_q_fits(a.M, d_in, d_out, R) ? launch_wide_q(a, fm, fa, fe, (hipStream_t)stream)
+                                                                 : launch_fused(a, fm, fa, fe, (hipStream_t)stream);
+        if (failed(err, "linear_q_multi")) return EORA_ERR_LAUNCH;
     }
     return EORA_OK;
 }

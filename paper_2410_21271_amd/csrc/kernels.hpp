@@ -41,7 +41,7 @@ struct FusedArgs {
     int M, d_in, d_out, r, group, kcn, spin_limit;
     // several adapters side by side in A and B (r = their ranks together): token row m keeps only the
     // r_per columns of t that belong to adapter[m] (-1: none).  nullptr: one adapter, nothing masked.
-    // Read by fused.hip only.
+    // Read by fused.hip and wideq.hip.
     const int* adapter;
     int r_per;
 };

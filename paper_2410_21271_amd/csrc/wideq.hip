@@ -319,6 +319,9 @@ __global__ __launch_bounds__(NWR * NWK * 64, 4) void wide_q_kernel(FusedArgs a)
                                 v0 = w[0]; v1 = w[1]; v2 = w[2]; v3 = w[3];
                             }
                             good_all = good_all && good;
+                            if (a.adapter) {   // several adapters side by side: a token row keeps its own adapter's columns
+                                if (a.adapter[16 * yq + e / a.r] != (e % a.r) / a.r_per) v0 = v1 = v2 = v3 = 0.f;
+                            }
                             *(f4*)(ts + q * tsz + e) = f4{v0, v1, v2, v3};
                         }
                     }

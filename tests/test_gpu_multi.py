@@ -40,6 +40,8 @@ SHAPES = [
     (40, 1024, 256, 4, 128, 4, 16),        # three token blocks, the last ragged; rank 512 together
     (17, 512, 80, 2, 128, 4, 4),           # 4-bit factors: a scale group never spans two adapters
     (300, 256, 64, 2, 32, 4, 16),          # two chunks of 256 tokens
+    (37, 2048, 2048, 2, 64, 4, 16),        # enough rows for the kernel that shares x through LDS; ragged last block
+    (21, 2048, 4096, 2, 128, 3, 4),        # the same with 3-bit backbone and 4-bit factors
 ]
 
 
