@@ -24,6 +24,12 @@ Q3  (3-bit codes, KT = 128): three words per lane, word index = tile*192 + 3*l +
     half is spare; the spare bits carry the last two codes: bit b of the code
     of column 30 + h is bit 16*h + 15 of word b.
 
+Q2  (2-bit codes, KT = 128): two words per lane, word index = tile*128 + 2*l + u.
+    The lane owns 32 columns cc = 0..31 of its quarter; column cc sits in word u = cc // 16 at bits
+    16*h + 2*p .. +1 with h = cc % 2 (the 16-bit half) and p = (cc % 16) // 2 (eight pairs of adjacent
+    columns per word, even column in the low half, odd column in the high half, same bit offset).
+    Zero-points (< 4) use the common nibble array.
+
 zeros   one nibble per (row, quantisation group), row-major, eight groups per
         32-bit word: word row*NGW + q // 8, nibble q % 8
         (NG = K / group, q = col // group, NGW = ceil(NG / 8))
@@ -161,6 +167,52 @@ def unpack_q3(words, rows, K):
     for b in range(3):
         spread |= ((words[base + b] >> s15) & 1) << np.uint32(b)
     return np.where(cc < 30, inplace, spread).astype(np.uint8)
+
+
+# ----------------------------------------------------------------------------
+# 2-bit codes
+# ----------------------------------------------------------------------------
+def q2_locate(o, i, K):
+    """(word index, bit shift) of the code of row o, column i."""
+    R, n = o // ROWS, o % ROWS
+    g, c = i // 128, i % 128
+    j, cc = c // 32, c % 32
+    u, p, h = cc // 16, (cc % 16) // 2, cc % 2
+    lane = 16 * j + n
+    tile = R * (K // 128) + g
+    return tile * 128 + 2 * lane + u, 16 * h + 2 * p
+
+
+def pack_q2(codes):
+    """Word-walk direction: every output word gathers the sixteen codes it holds."""
+    codes = np.asarray(codes)
+    rows, K = codes.shape
+    _check(rows, K, 128)
+    if codes.min(initial=0) < 0 or codes.max(initial=0) > 3:
+        raise ValueError("2-bit code out of range")
+    ntk = K // 128
+    w = np.arange(rows * K // 16)
+    tile, rem = w // 128, w % 128
+    lane, u = rem // 2, rem % 2
+    R, g = tile // ntk, tile % ntk
+    j, n = lane // 16, lane % 16
+    row = 16 * R + n
+    col0 = 128 * g + 32 * j + 16 * u
+    out = np.zeros(w.size, dtype=np.uint32)
+    for p in range(8):
+        for h in range(2):
+            out |= codes[row, col0 + 2 * p + h].astype(np.uint32) << np.uint32(16 * h + 2 * p)
+    return out
+
+
+def unpack_q2(words, rows, K):
+    words = np.asarray(words, dtype=np.uint32)
+    _check(rows, K, 128)
+    if words.size != rows * K // 16:
+        raise ValueError("wrong number of words")
+    o, i = np.meshgrid(np.arange(rows), np.arange(K), indexing="ij")
+    word, shift = q2_locate(o, i, K)
+    return ((words[word] >> shift.astype(np.uint32)) & 3).astype(np.uint8)
 
 
 # ----------------------------------------------------------------------------

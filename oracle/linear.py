@@ -34,8 +34,10 @@ def dequant_q(qweight, qzeros, scales_packed, d_in, d_out, bits, group):
         codes = layout.unpack_q4(qweight, d_out, d_in, 128)
     elif bits == 3:
         codes = layout.unpack_q3(qweight, d_out, d_in)
+    elif bits == 2:
+        codes = layout.unpack_q2(qweight, d_out, d_in)
     else:
-        raise ValueError("bits must be 3 or 4")
+        raise ValueError("bits must be 2, 3 or 4")
     zeros = layout.unpack_zeros(qzeros, d_out, NG)
     scales = layout.unpack_scales(scales_packed, d_out, NG)
     return dequant(codes, zeros, scales, group)

@@ -23,6 +23,21 @@ def decode_q4(words, rows, K, KT=128):
     return out
 
 
+def decode_q2(words, rows, K):
+    out = [[None] * K for _ in range(rows)]
+    ntk = K // 128
+    for w, word in enumerate(int(v) for v in words):
+        lane_global, u = divmod(w, 2)
+        tile, lane = divmod(lane_global, 64)
+        R, g = divmod(tile, ntk)
+        j, n = divmod(lane, 16)
+        for h in range(2):
+            half = (word >> (16 * h)) & 0xFFFF
+            for p in range(8):
+                out[16 * R + n][g * 128 + 32 * j + 16 * u + 2 * p + h] = (half >> (2 * p)) & 3
+    return out
+
+
 def decode_q3(words, rows, K):
     out = [[None] * K for _ in range(rows)]
     ntk = K // 128

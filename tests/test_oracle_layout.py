@@ -23,6 +23,13 @@ def _run_case(kind, prm, sets, expect):
             codes[o, i] = c
         words = layout.pack_q3(codes)
         back = layout.unpack_q3(words, rows, K)
+    elif kind == "q2":
+        rows, K = prm["rows"], prm["K"]
+        codes = np.zeros((rows, K), np.uint8)
+        for o, i, c in sets:
+            codes[o, i] = c
+        words = layout.pack_q2(codes)
+        back = layout.unpack_q2(words, rows, K)
     elif kind == "zeros":
         rows, NG = prm["rows"], prm["NG"]
         codes = np.zeros((rows, NG), np.uint8)
@@ -60,7 +67,7 @@ def _run_case(kind, prm, sets, expect):
     assert np.array_equal(back, codes)
 
 
-@pytest.mark.parametrize("name", ["layout_q4.txt", "layout_q3.txt", "layout_misc.txt"])
+@pytest.mark.parametrize("name", ["layout_q4.txt", "layout_q3.txt", "layout_q2.txt", "layout_misc.txt"])
 def test_golden_bit_positions(name):
     cases = read_cases(name)
     assert cases
@@ -117,6 +124,19 @@ def test_q3_roundtrip_and_word_walk(rows, K):
     assert words.size == rows * K * 3 // 32          # exactly 3.0 bits per weight
     assert np.array_equal(layout.unpack_q3(words, rows, K), codes)
     assert np.array_equal(np.array(pyref.decode_q3(words, rows, K), dtype=np.uint8), codes)
+
+
+@pytest.mark.parametrize("rows,K", [(16, 128), (48, 384)])
+def test_q2_roundtrip_and_word_walk(rows, K):
+    rng = np.random.default_rng(rows + K + 2)
+    codes = rng.integers(0, 4, (rows, K), dtype=np.uint8)
+    words = layout.pack_q2(codes)
+    assert words.size == rows * K // 16                     # 2.0 bits per weight, no padding
+    assert np.array_equal(layout.unpack_q2(words, rows, K), codes)
+    assert np.array_equal(np.array(pyref.decode_q2(words, rows, K), dtype=np.uint8), codes)
+    assert np.all(layout.pack_q2(np.full((16, 128), 3, np.uint8)) == 0xFFFFFFFF)
+    with pytest.raises(ValueError):
+        layout.pack_q2(np.full((16, 128), 4, np.uint8))
 
 
 def test_q3_all_ones_and_all_zero():

@@ -24,7 +24,7 @@ def test_dequant_hand_values():
 def _tiny_q(bits, rows=16, K=256, M=3, r=32, seed=0, ab_bits=16):
     W, A, B, x = synth.draw_layer(seed, K, rows, M, r)
     codes, zeros, scales = synth.quantize_rtn(W, bits, 128)
-    qw = layout.pack_q4(codes) if bits == 4 else layout.pack_q3(codes)
+    qw = {4: layout.pack_q4, 3: layout.pack_q3, 2: layout.pack_q2}[bits](codes)
     qz, sc = layout.pack_zeros(zeros), layout.pack_scales(scales)
     if ab_bits == 16:
         Ap, Bp, As, Bs = layout.pack_f16(A), layout.pack_f16(B), None, None
@@ -38,7 +38,7 @@ def _tiny_q(bits, rows=16, K=256, M=3, r=32, seed=0, ab_bits=16):
                 ab_bits=ab_bits, logical=(codes, zeros, scales, A, B))
 
 
-@pytest.mark.parametrize("bits,ab_bits,r", [(4, 16, 32), (3, 16, 32), (4, 4, 64), (3, 4, 128)])
+@pytest.mark.parametrize("bits,ab_bits,r", [(4, 16, 32), (3, 16, 32), (4, 4, 64), (3, 4, 128), (2, 16, 32)])
 def test_forward_exact_rational(bits, ab_bits, r):
     """All stored inputs are dyadic rationals, so y is computable exactly with
     Fractions from the raw words, by decoders that share nothing with the oracle."""
@@ -47,7 +47,7 @@ def test_forward_exact_rational(bits, ab_bits, r):
     y = linear.eora_linear_q(d["x"], d["qw"], d["sc"], d["qz"], d["A"], d["B"], d["As"], d["Bs"],
                              M, K, rows, r, bits, 128, ab_bits)
     NG = K // 128
-    q = pyref.decode_q4(d["qw"], rows, K) if bits == 4 else pyref.decode_q3(d["qw"], rows, K)
+    q = {4: pyref.decode_q4, 3: pyref.decode_q3, 2: pyref.decode_q2}[bits](d["qw"], rows, K)
     z = pyref.decode_zeros(d["qz"], rows, NG)
     s = pyref.decode_scales(d["sc"], rows, NG)
     What = [[s[o][i // 128] * (q[o][i] - z[o][i // 128]) for i in range(K)] for o in range(rows)]
