@@ -47,6 +47,11 @@ WORKLOADS["llama3-8b-layer-decode-w4g128-4xr128fp16-M64-multi"] = dict(model="8b
 WORKLOADS["llama3-8b-layer-decode-w4g128-4xr128fp16-M8-multi"] = dict(model="8b", w_bits=4, ab_bits=16, r=512, M=8, cfg=1, multi=4)
 WORKLOADS["llama3-8b-layer-decode-w4g128-r512fp16-M64"] = dict(model="8b", w_bits=4, ab_bits=16, r=512, M=64, cfg=1)    # same bytes, one adapter
 WORKLOADS["llama3-8b-layer-decode-w4g128-r128fp16-M64"] = dict(model="8b", w_bits=4, ab_bits=16, r=128, M=64, cfg=1)
+# 2-bit backbone (App. A.14 evaluates 2-bit models), same layer
+WORKLOADS["llama3-8b-layer-decode-w2g128-r128fp16-M1"] = dict(model="8b", w_bits=2, ab_bits=16, r=128, M=1, cfg=2)
+WORKLOADS["llama3-8b-layer-decode-w2g128-bare-M1"] = dict(model="8b", w_bits=2, ab_bits=16, r=0, M=1, cfg=2)
+WORKLOADS["llama3-8b-layer-decode-w2g128-r128fp16-M16"] = dict(model="8b", w_bits=2, ab_bits=16, r=128, M=16, cfg=2)
+WORKLOADS["llama3-8b-layer-prefill-w2g128-r256fp16-M2048"] = dict(model="8b", w_bits=2, ab_bits=16, r=256, M=2048, cfg=4, outlier=0.01)
 # the paper's speed table is on a 70B model: the quantised layer at those shapes (not a BASELINE config)
 WORKLOADS["llama3-70b-layer-decode-w3g128-r128fp16-M1"] = dict(model="70b", w_bits=3, ab_bits=16, r=128, M=1, cfg=2)
 WORKLOADS["llama3-70b-layer-decode-w3g128-bare-M1"] = dict(model="70b", w_bits=3, ab_bits=16, r=0, M=1, cfg=2)
@@ -55,7 +60,8 @@ for _n in ("llama3-8b-layer-decode-w3g128-r128fp16-M1", "llama3-8b-layer-decode-
            "llama3-8b-layer-decode-w4g128-r128fp16-M1", "llama3-8b-layer-decode-w4g128-r128q4-M1",
            "llama3-8b-layer-decode-w4g128-bare-M1", "llama3-8b-layer-prefill-w4g128-r256fp16-M2048",
            "llama3-8b-layer-prefill-w4g128-bare-M2048", "llama3-70b-layer-decode-w3g128-r128fp16-M1",
-           "llama3-70b-layer-decode-w3g128-bare-M1"):
+           "llama3-70b-layer-decode-w3g128-bare-M1", "llama3-8b-layer-decode-w2g128-r128fp16-M1",
+           "llama3-8b-layer-decode-w2g128-bare-M1", "llama3-8b-layer-prefill-w2g128-r256fp16-M2048"):
     WORKLOADS[_n + "-grouped"] = dict(WORKLOADS[_n], grouped=True)
 GROUPS = (("q", "k", "v"), ("o",), ("gate", "up"), ("down",))
 for _r in (64, 256, 512):
@@ -234,7 +240,7 @@ def cpu_baseline(linears, names):
             total_b += L.bytes
             worst = max(worst, linear.y_error(L.y.cpu().numpy(), y))
             continue
-        qw = layout.pack_q4(codes) if L.w_bits == 4 else layout.pack_q3(codes)
+        qw = {4: layout.pack_q4, 3: layout.pack_q3, 2: layout.pack_q2}[L.w_bits](codes)
         qz, sc = layout.pack_zeros(zeros), layout.pack_scales(scales)
         Ap = Bp = As = Bs = None
         if L.r and L.ab_bits == 16:

@@ -35,6 +35,10 @@
  *      tile*192 + 3*l + d.  Its 32 columns cc form pairs p = cc/2 (h = cc%2: 0 low / 1 high
  *      16-bit half).  Pairs 0..14 sit in word p/5 at bits 16h + 3*(p%5) .. +2.  Bit 15 of each
  *      half carries the last pair: bit b of the code of column 30+h is bit 16h+15 of word b.
+ *  Q2 (2-bit codes, KT = 128, backbone only; the 2-bit setting of App. A.14): lane l owns two
+ *      consecutive words tile*128 + 2*l + u; column cc = 0..31 of its quarter sits in word u = cc/16
+ *      at bits 16h + 2p .. +1, h = cc%2, p = (cc%16)/2: eight pairs of adjacent columns per word.
+ *      Zero-points (0..3) use the common nibble array below.
  *  zero-points: 4-bit, one per (row, group), row-major, eight groups per 32-bit word: word
  *      row*NGW + q/8, nibble q%8, with NG = K/group, q = col/group, NGW = ceil(NG/8) (so a lane
  *      finds the zero-points of four consecutive k-tiles of its row in one word).
@@ -124,7 +128,7 @@ void eora_debug_set_spin_limit(int iterations);
  * Constraints: d_out % 16 == 0, d_in % 128 == 0, group % 128 == 0, d_in % group == 0.
  * ------------------------------------------------------------------------------------------ */
 /* codes: d_out x d_in, values < 2^w_bits; zeros: d_out x d_in/group, same range;
- * scales: d_out x d_in/group fp16 bit patterns.  w_bits is 3 or 4. */
+ * scales: d_out x d_in/group fp16 bit patterns.  w_bits is 2, 3 or 4. */
 int eora_pack_q(const uint8_t* codes, const uint8_t* zeros, const uint16_t* scales,
                 int d_in, int d_out, int w_bits, int group,
                 void* qweight_out, void* qzeros_out, void* scales_out);
@@ -157,7 +161,7 @@ int eora_pack_sp24q4(const uint8_t* codes, const uint8_t* pos, const uint8_t* ze
  * y        fp16 row-major M x d_out, overwritten; fp32 accumulation, one round-to-nearest-even
  *          conversion at the end.
  * Constraints: M >= 0 (M == 0 is a no-op), d_out % 16 == 0, d_in % 128 == 0, group % 128 == 0,
- *          d_in % group == 0 (group == d_in is channel-wise quantisation), w_bits in {3,4},
+ *          d_in % group == 0 (group == d_in is channel-wise quantisation), w_bits in {2,3,4},
  *          ab_bits in {16,4}, r <= 512 and r % 32 == 0 (ab_bits 16) or r == 64 or r % 128 == 0
  *          (ab_bits 4).
  * ------------------------------------------------------------------------------------------ */

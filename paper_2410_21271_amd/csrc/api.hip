@@ -146,7 +146,7 @@ int launch_prefill_group(const void* x, const eora_q_member* members, int n, int
         p.y[m] = members[m].y; p.ldy[m] = members[m].d_out;
         p.N[m] = members[m].d_out;
     }
-    if (failed(launch_prefill(p, w_bits == 4 ? S_Q4 : S_Q3, r > 0, stream), "prefill")) return EORA_ERR_LAUNCH;
+    if (failed(launch_prefill(p, backbone_format(w_bits), r > 0, stream), "prefill")) return EORA_ERR_LAUNCH;
     return EORA_OK;
 }
 
@@ -177,7 +177,7 @@ int launch_group(const void* x, const eora_q_member* members, int n, int M, int 
     a.group = group;
     a.kcn = pick_kcn(M, d_in);
     a.spin_limit = g_spin_limit;
-    if (failed(launch_small(a, w_bits == 4 ? S_Q4 : S_Q3, fa, fe, nw, nq, stream), "linear_q (decode)")) return EORA_ERR_LAUNCH;
+    if (failed(launch_small(a, backbone_format(w_bits), fa, fe, nw, nq, stream), "linear_q (decode)")) return EORA_ERR_LAUNCH;
     return EORA_OK;
 }
 
@@ -229,7 +229,7 @@ static int validate_linear_q(const void* x, const eora_q_member& e, int M, int d
                              int ab_bits, const void* workspace, size_t workspace_bytes, int* fa, int* fe)
 {
     if (!x || !e.qweight || !e.scales || !e.qzeros || !e.y) return EORA_ERR_NULL;
-    if (w_bits != 3 && w_bits != 4) return EORA_ERR_UNSUPPORTED;
+    if (w_bits < 2 || w_bits > 4) return EORA_ERR_UNSUPPORTED;
     int rc = check_backbone_shape(M, d_in, e.d_out, r);
     if (rc != EORA_OK) return rc;
     rc = check_group(d_in, group);
@@ -289,7 +289,7 @@ static int run_linear_q(const void* x, const eora_q_member& e, int M, int d_in, 
         a.group = group;
         a.kcn = kcn;
         a.spin_limit = g_spin_limit;
-        const int fm = w_bits == 4 ? S_Q4 : S_Q3;
+        const int fm = backbone_format(w_bits);
         const hipError_t e = wide_q_fits(a.M, d_in, d_out, r) ? launch_wide_q(a, fm, fa, fe, (hipStream_t)stream)
                                                                : launch_fused(a, fm, fa, fe, (hipStream_t)stream);
         if (failed(e, "linear_q")) return EORA_ERR_LAUNCH;
@@ -348,7 +348,7 @@ int eora_linear_q_multi(const void* x, const void* qweight, const void* scales, 
         a.spin_limit = g_spin_limit;
         a.adapter = (const int*)adapter_of_row + m0;
         a.r_per = r;
-        const int fm = w_bits == 4 ? S_Q4 : S_Q3;
+        const int fm = backbone_format(w_bits);
         const hipError_t err = wide_q_fits(a.M, d_in, d_out, R) ? launch_wide_q(a, fm, fa, fe, (hipStream_t)stream)
                                                                  : launch_fused(a, fm, fa, fe, (hipStream_t)stream);
         if (failed(err, "linear_q_multi")) return EORA_ERR_LAUNCH;
@@ -448,7 +448,7 @@ int eora_unpack_q(const void* qweight, const void* qzeros, void* codes_u8, void*
                   int d_in, int d_out, int w_bits, int group, void* stream)
 {
     if (!qweight || !qzeros || !codes_u8 || !zeros_u8) return EORA_ERR_NULL;
-    if (w_bits != 3 && w_bits != 4) return EORA_ERR_UNSUPPORTED;
+    if (w_bits < 2 || w_bits > 4) return EORA_ERR_UNSUPPORTED;
     int rc = check_backbone_shape(1, d_in, d_out, 0);
     if (rc != EORA_OK) return rc;
     rc = check_group(d_in, group);
@@ -464,7 +464,7 @@ int eora_dequant_q(const void* qweight, const void* scales, const void* qzeros, 
                    int d_in, int d_out, int w_bits, int group, void* stream)
 {
     if (!qweight || !scales || !qzeros || !W_f32) return EORA_ERR_NULL;
-    if (w_bits != 3 && w_bits != 4) return EORA_ERR_UNSUPPORTED;
+    if (w_bits < 2 || w_bits > 4) return EORA_ERR_UNSUPPORTED;
     int rc = check_backbone_shape(1, d_in, d_out, 0);
     if (rc != EORA_OK) return rc;
     rc = check_group(d_in, group);

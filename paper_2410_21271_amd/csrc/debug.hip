@@ -22,6 +22,11 @@ __device__ __forceinline__ uint32_t code_q3(const uint32_t* w, int cc)
     return ((w[0] >> s) & 1u) | (((w[1] >> s) & 1u) << 1) | (((w[2] >> s) & 1u) << 2);
 }
 
+__device__ __forceinline__ uint32_t code_q2(const uint32_t* w, int cc)
+{
+    return (w[cc >> 4] >> (16 * (cc & 1) + 2 * ((cc & 15) >> 1))) & 3u;
+}
+
 template <bool DEQUANT>
 __global__ void unpack_q_kernel(const uint32_t* __restrict__ qweight, const _Float16* __restrict__ scales,
                                 const uint32_t* __restrict__ qzeros, uint8_t* __restrict__ codes,
@@ -41,12 +46,12 @@ __global__ void unpack_q_kernel(const uint32_t* __restrict__ qweight, const _Flo
     const int NGW = (NG + 7) / 8;
     const uint32_t z = (qzeros[(size_t)row * NGW + (q >> 3)] >> (4 * (q & 7))) & 0xFu;
     uint32_t w[4];
-    const int wpl = w_bits == 4 ? 4 : 3;
+    const int wpl = w_bits;                    // words per lane: 32 codes of w_bits bits
     for (int t = 0; t < wpl; ++t) w[t] = qweight[L * wpl + t];
     float s = 0.f;
     if (DEQUANT) s = (float)scales[(size_t)row * NG + q];
     for (int cc = 0; cc < 32; ++cc) {
-        const uint32_t c = w_bits == 4 ? code_q4(w, cc) : code_q3(w, cc);
+        const uint32_t c = w_bits == 4 ? code_q4(w, cc) : (w_bits == 3 ? code_q3(w, cc) : code_q2(w, cc));
         const size_t idx = (size_t)row * d_in + col0 + cc;
         if (DEQUANT) W[idx] = s * (float)((int)c - (int)z);      // 11-bit x 5-bit product: exact in fp32
         else codes[idx] = (uint8_t)c;

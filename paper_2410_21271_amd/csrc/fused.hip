@@ -378,6 +378,7 @@ hipError_t launch_fused(const FusedArgs& a, int fm, int fa, int fe, hipStream_t 
     switch (fm) {
         case S_Q4: return launch_ab<S_Q4>(a, fa, fe, stream);
         case S_Q3: return launch_ab<S_Q3>(a, fa, fe, stream);
+        case S_Q2: return launch_ab<S_Q2>(a, fa, fe, stream);
         default: return hipErrorInvalidValue;
     }
 }

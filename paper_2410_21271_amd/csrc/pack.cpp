@@ -60,6 +60,29 @@ int pack_q3_tiles(const uint8_t* codes, int rows, int K, uint32_t* out)
     return EORA_OK;
 }
 
+int pack_q2_tiles(const uint8_t* codes, int rows, int K, uint32_t* out)
+{
+    const int ntk = K / 128;
+    const size_t nlanes = (size_t)rows * K / 32;
+    for (size_t L = 0; L < nlanes; ++L) {
+        const size_t tile = L / 64;
+        const int lane = (int)(L % 64);
+        const int R = (int)(tile / ntk), g = (int)(tile % ntk);
+        const int j = lane / 16, n = lane % 16;
+        const uint8_t* src = codes + (size_t)(16 * R + n) * K + (size_t)g * 128 + 32 * j;
+        for (int u = 0; u < 2; ++u) {
+            uint32_t word = 0;
+            for (int c = 0; c < 16; ++c) {
+                const uint32_t q = src[16 * u + c];
+                if (q > 3) return EORA_ERR_VALUE;
+                word |= q << (16 * (c % 2) + 2 * (c / 2));      // pair c/2: even column low half, odd column high half
+            }
+            out[2 * L + u] = word;
+        }
+    }
+    return EORA_OK;
+}
+
 // scales are stored as they come: row-major rows x NG
 void pack_scale_tiles(const uint16_t* scales, int rows, int NG, uint16_t* out)
 {
@@ -72,7 +95,7 @@ extern "C" {
 
 size_t eora_qweight_bytes(int d_in, int d_out, int w_bits)
 {
-    if (!shape_ok(d_out, d_in, 128) || (w_bits != 3 && w_bits != 4)) return 0;
+    if (!shape_ok(d_out, d_in, 128) || w_bits < 2 || w_bits > 4) return 0;
     return (size_t)d_out * d_in * w_bits / 8;
 }
 
@@ -103,14 +126,15 @@ int eora_pack_q(const uint8_t* codes, const uint8_t* zeros, const uint16_t* scal
                 void* qweight_out, void* qzeros_out, void* scales_out)
 {
     if (!codes || !zeros || !scales || !qweight_out || !qzeros_out || !scales_out) return EORA_ERR_NULL;
-    if (w_bits != 3 && w_bits != 4) return EORA_ERR_UNSUPPORTED;
+    if (w_bits < 2 || w_bits > 4) return EORA_ERR_UNSUPPORTED;
     if (!shape_ok(d_out, d_in, 128) || group <= 0 || group % 128 || d_in % group) return EORA_ERR_SHAPE;
     const int NG = d_in / group;
     const int zmax = (1 << w_bits) - 1;
     for (size_t i = 0; i < (size_t)d_out * NG; ++i)
         if (zeros[i] > zmax) return EORA_ERR_VALUE;
-    int rc = (w_bits == 4) ? pack_q4_tiles(codes, d_out, d_in, 128, (uint32_t*)qweight_out)
-                           : pack_q3_tiles(codes, d_out, d_in, (uint32_t*)qweight_out);
+    int rc = (w_bits == 4)   ? pack_q4_tiles(codes, d_out, d_in, 128, (uint32_t*)qweight_out)
+             : (w_bits == 3) ? pack_q3_tiles(codes, d_out, d_in, (uint32_t*)qweight_out)
+                             : pack_q2_tiles(codes, d_out, d_in, (uint32_t*)qweight_out);
     if (rc != EORA_OK) return rc;
     uint32_t* zw = (uint32_t*)qzeros_out;
     const int NGW = (NG + 7) / 8;

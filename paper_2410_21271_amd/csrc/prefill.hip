@@ -400,6 +400,7 @@ hipError_t launch_prefill(const PrefillArgs& a, int fm, bool ext, hipStream_t st
     switch (fm) {
         case S_Q4: return ext ? launch_pf<S_Q4, true>(a, stream) : launch_pf<S_Q4, false>(a, stream);
         case S_Q3: return ext ? launch_pf<S_Q3, true>(a, stream) : launch_pf<S_Q3, false>(a, stream);
+        case S_Q2: return ext ? launch_pf<S_Q2, true>(a, stream) : launch_pf<S_Q2, false>(a, stream);
         case S_Q4S128: return ext ? hipErrorInvalidValue : launch_pf<S_Q4S128, false>(a, stream);
         case S_F16: return ext ? hipErrorInvalidValue : launch_pf<S_F16, false>(a, stream);
         default: return hipErrorInvalidValue;

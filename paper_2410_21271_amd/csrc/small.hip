@@ -464,6 +464,7 @@ hipError_t launch_small(const GroupArgs& a, int fm, int fa, int fe, int nw, int 
     switch (fm) {
         case S_Q4: return launch_small_ab<S_Q4>(a, fa, fe, nw, nq, stream);
         case S_Q3: return launch_small_ab<S_Q3>(a, fa, fe, nw, nq, stream);
+        case S_Q2: return launch_small_ab<S_Q2>(a, fa, fe, nw, nq, stream);
         default: return hipErrorInvalidValue;
     }
 }

@@ -72,6 +72,29 @@ __device__ __forceinline__ h8 dq4_word(uint32_t w, uint32_t c1024, uint32_t c64)
     return f.v;
 }
 
+// Sixteen 2-bit codes of one word -> (code - z) as two fragments of eight fp16, columns in natural order.
+// Pair p of adjacent columns sits at bits 2p of both 16-bit halves: masked in place it reads 1024 + 4^p * q
+// for p < 4 (bits 8..15 after a shift by 8), and one fused multiply-add brings it to q - z exactly.
+__device__ __forceinline__ void dq2_word(uint32_t w, uint32_t z, h8& lo, h8& hi8)
+{
+    const h2 quarter = {(_Float16)0.25f, (_Float16)0.25f};
+    const h2 sixteenth = {(_Float16)0.0625f, (_Float16)0.0625f};
+    const h2 sixtyfourth = {(_Float16)0.015625f, (_Float16)0.015625f};
+    const h2 c1024 = as_h2(k1024(z)), c256 = as_h2(0x5C005C00u | (z * 0x00040004u)), c64 = as_h2(k64(z)), c16 = as_h2(k16(z));
+    const uint32_t magic = in_vgpr(MAGIC);
+    const uint32_t half[2] = {w, w >> 8};
+    Frag f[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        f[i].p[0] = as_h2(and_or(half[i], 0x00030003u, magic)) - c1024;                                        // 1024+q
+        f[i].p[1] = __builtin_elementwise_fma(as_h2(and_or(half[i], 0x000C000Cu, magic)), quarter, -c256);      // 1024+4q
+        f[i].p[2] = __builtin_elementwise_fma(as_h2(and_or(half[i], 0x00300030u, magic)), sixteenth, -c64);     // 1024+16q
+        f[i].p[3] = __builtin_elementwise_fma(as_h2(and_or(half[i], 0x00C000C0u, magic)), sixtyfourth, -c16);   // 1024+64q
+    }
+    lo = f[0].v;
+    hi8 = f[1].v;
+}
+
 // Thirty-two 3-bit codes of one lane (three words) -> four fragments of (code - z).
 __device__ __forceinline__ void dq3_lane(uint32_t d0, uint32_t d1, uint32_t d2, uint32_t z, h8 out[4])
 {

@@ -18,7 +18,7 @@ class QCase:
         self.logical = dict(codes=codes, zeros=zeros, scales=scales, A=A, B=B)
         self.x = x
         # oracle side
-        self.o_qw = layout.pack_q4(codes) if w_bits == 4 else layout.pack_q3(codes)
+        self.o_qw = {4: layout.pack_q4, 3: layout.pack_q3, 2: layout.pack_q2}[w_bits](codes)
         self.o_qz, self.o_sc = layout.pack_zeros(zeros), layout.pack_scales(scales)
         self.o_A = self.o_B = self.o_As = self.o_Bs = None
         if r > 0 and ab_bits == 16:

@@ -26,7 +26,7 @@ def test_library_exports_every_declared_symbol():
         assert getattr(raw, name) is not None
 
 
-@pytest.mark.parametrize("w_bits,ab_bits,r", [(4, 16, 32), (3, 16, 64), (4, 4, 64), (3, 4, 128), (4, 16, 0)])
+@pytest.mark.parametrize("w_bits,ab_bits,r", [(4, 16, 32), (3, 16, 64), (4, 4, 64), (3, 4, 128), (4, 16, 0), (2, 16, 32)])
 def test_host_packers_match_oracle_bytes(w_bits, ab_bits, r):
     QCase(100 + w_bits + r, 256, 48, 2, r, w_bits, 128, ab_bits, packer=eora)      # asserts inside
     QCase(200 + w_bits + r, 256, 32, 1, r, w_bits, 256, ab_bits, packer=eora)      # channel-wise group
@@ -42,6 +42,7 @@ def test_sparse_packer_matches_oracle_bytes():
 def test_sizes():
     assert eora.qweight_bytes(4096, 4096, 4) == 4096 * 4096 // 2
     assert eora.qweight_bytes(4096, 4096, 3) == 4096 * 4096 * 3 // 8
+    assert eora.qweight_bytes(4096, 4096, 2) == 4096 * 4096 // 4 and eora.qweight_bytes(4096, 4096, 1) == 0
     assert eora.qzeros_bytes(4096, 4096, 128) == 4096 * 32 // 2
     assert eora.qzeros_bytes(4096, 4096, 4096) == 4096 * 4          # channel-wise: one padded word per row
     assert eora.scales_bytes(4096, 4096, 128) == 4096 * 32 * 2
@@ -95,7 +96,7 @@ def test_linear_q_validation_codes():
     assert call(x=null) == -1 and call(y=null) == -1 and call(A=null) == -1
     assert call(d_out=40) == -2 and call(d_in=200) == -2 and call(group=64) == -2 and call(group=384) == -2
     assert call(r=48) == -2 and call(r=1024) == -2 and call(M=-1) == -2
-    assert call(w_bits=2) == -3 and call(ab_bits=8) == -3
+    assert call(w_bits=1) == -3 and call(w_bits=5) == -3 and call(ab_bits=8) == -3
     assert call(ab_bits=4, As=good, Bs=good, r=96) == -2 and call(ab_bits=4, r=64) == -1
     assert call(qw=odd) == -4 and call(y=odd) == -4 and call(ws=odd) == -4
     assert call(ws=null) == -5 and call(ws_bytes=16) == -5

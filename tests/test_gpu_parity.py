@@ -23,7 +23,7 @@ def _check(y, ref, tol=TOL):
     return err
 
 
-@pytest.mark.parametrize("w_bits", [4, 3])
+@pytest.mark.parametrize("w_bits", [4, 3, 2])
 @pytest.mark.parametrize("group", [128, 384])
 def test_unpack_and_dequant_bit_exact(gpu, w_bits, group):
     import torch
@@ -49,6 +49,7 @@ def test_unpack_and_dequant_bit_exact(gpu, w_bits, group):
 @pytest.mark.parametrize("w_bits,ab_bits,r,M", [
     (4, 16, 0, 1), (4, 16, 32, 1), (4, 16, 128, 3), (3, 16, 0, 1), (3, 16, 64, 2),
     (4, 4, 64, 1), (4, 4, 128, 5), (3, 4, 256, 16), (4, 16, 96, 16), (4, 16, 64, 17), (3, 16, 32, 37),
+    (2, 16, 0, 1), (2, 16, 64, 2), (2, 4, 128, 5), (2, 16, 32, 37),
 ])
 def test_linear_q_small_shapes(gpu, w_bits, ab_bits, r, M):
     """Several row blocks and k-tiles, ragged token counts."""
@@ -122,6 +123,7 @@ def test_config_shapes_fp16_factors(gpu, name, d_in, d_out, w_bits, M):
     (3, 16, 128, 1, 4096, (4096, 1024, 1024)),      # query / key / value of the 8B layer, config 2
     (3, 16, 128, 1, 4096, (14336, 14336)),          # gate / up: enough row blocks that a workgroup takes two
     (4, 4, 128, 1, 4096, (1024, 2048)),             # 4-bit factors, config 3
+    (2, 16, 128, 1, 4096, (4096, 1024, 1024)),      # 2-bit backbone
     (4, 16, 32, 3, 1024, (64, 16, 48, 32)),         # four members, three tokens
     (4, 16, 0, 2, 2048, (128, 64)),                 # adapter off
     (3, 16, 64, 8, 512, (64, 32)),                  # a shape the decode kernel does not take: members run in turn
@@ -231,6 +233,9 @@ def test_linear_sp24_ragged_k_and_determinism(gpu):
     (4, 16, 128, 1, 8192, 1024),       # 70B-shaped quantised layers: eight wavefronts
     (3, 16, 128, 1, 28672, 512),       # and the 28672-long contraction
     (4, 16, 128, 4, 8192, 256),        # four tokens
+    (2, 16, 128, 1, 4096, 4096),       # 2-bit backbone at the 8B shapes
+    (2, 16, 128, 1, 14336, 1024),
+    (2, 4, 128, 3, 4096, 1024),
 ])
 def test_more_config_shapes(gpu, w_bits, ab_bits, r, M, d_in, d_out):
     """Full contraction lengths of the configured layers that the other tests do not reach (every
@@ -252,6 +257,8 @@ def test_more_config_shapes(gpu, w_bits, ab_bits, r, M, d_in, d_out):
     (4, 16, 512, 16, 2048, 4096, 128),     # the largest rank: t fills the LDS of the x slots
     (4, 16, 32, 5, 2048, 4096, 2048),      # channel-wise groups
     (4, 16, 128, 127, 4096, 512, 128),     # eight token blocks, the last one ragged
+    (2, 16, 128, 16, 2048, 8192, 128),     # 2-bit backbone
+    (2, 16, 64, 37, 2048, 8208, 256),
 ])
 def test_linear_q_mid_token_counts(gpu, w_bits, ab_bits, r, M, d_in, d_out, group):
     """The kernel for 5..127 tokens (x shared through LDS), every split of a workgroup it launches."""
@@ -300,7 +307,7 @@ def test_linear_sp24_many_tokens_many_rows(gpu, r, M, d_in, d_out):
     assert np.array_equal(y, run_linear_sp24(c))
 
 
-@pytest.mark.parametrize("w_bits,r,M,d_out", [(4, 0, 128, 128), (4, 128, 200, 192), (3, 256, 333, 144), (4, 128, 129, 16)])
+@pytest.mark.parametrize("w_bits,r,M,d_out", [(4, 0, 128, 128), (4, 128, 200, 192), (3, 256, 333, 144), (4, 128, 129, 16), (2, 128, 200, 192), (2, 0, 130, 48)])
 def test_prefill_gemm_small_shapes(gpu, w_bits, r, M, d_out):
     """The many-token GEMM path: ragged token and row tiles, with and without the low-rank extension."""
     from tests.cases import QCase
