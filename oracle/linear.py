@@ -54,6 +54,15 @@ def dequant_factor_q4(qcodes_packed, scales_packed, rows, K):
     return dequant(codes, zeros, scales, KT)
 
 
+def dequant_factor_q3(qcodes_packed, scales_packed, rows, K):
+    """3-bit EoRA factor (App. A.9 quantises the factors to 3 and 4 bits).  Symmetric: the zero-point is
+    the constant 4; one fp16 scale per row and per group of 128 columns along the contraction dimension."""
+    codes = layout.unpack_q3(qcodes_packed, rows, K)
+    scales = layout.unpack_scales(scales_packed, rows, K // 128)
+    zeros = np.full((rows, K // 128), 4, dtype=np.uint8)
+    return dequant(codes, zeros, scales, 128)
+
+
 def expand_sp24(vals, pos):
     """2:4 sparse -> dense float64: of every four consecutive input columns two
     are kept (Sec. 1), value v at column 4*group + position, the others zero."""
@@ -183,7 +192,10 @@ def _factors(A, B, A_scales, B_scales, d_in, d_out, r, ab_bits):
     if ab_bits == 4:
         return (dequant_factor_q4(A, A_scales, r, d_in),
                 dequant_factor_q4(B, B_scales, d_out, r))
-    raise ValueError("ab_bits must be 16 or 4")
+    if ab_bits == 3:
+        return (dequant_factor_q3(A, A_scales, r, d_in),
+                dequant_factor_q3(B, B_scales, d_out, r))
+    raise ValueError("ab_bits must be 16, 4 or 3")
 
 
 def y_error(y_test, y_ref):

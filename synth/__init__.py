@@ -83,6 +83,20 @@ def prune_24(W16):
     return vals, pos
 
 
+def quantize_sym3(Mat, KT=128):
+    """Symmetric 3-bit quantiser for an EoRA factor: implicit zero-point 4, one fp16 scale per
+    (row, group of KT columns).  Returns codes u8 in 1..7 and scales fp16."""
+    Mat = np.asarray(Mat, dtype=np.float32)
+    rows, K = Mat.shape
+    Mg = Mat.reshape(rows, K // KT, KT)
+    amax = np.abs(Mg).max(axis=2)
+    s16 = (amax / 3.0).astype(np.float16)
+    s16 = np.where(s16 == 0, np.float16(1.0), s16).astype(np.float16)
+    s = s16.astype(np.float32)
+    q = np.clip(np.rint(Mg / s[:, :, None]) + 4, 1, 7)
+    return q.reshape(rows, K).astype(np.uint8), s16
+
+
 def quantize_kept_rtn(vals, pos, group, bits=4):
     """Round-to-nearest min/max asymmetric quantiser of the KEPT values of a 2:4-pruned matrix, per
     (row, group of `group` dense columns); the group of a kept value is that of its dense column.

@@ -28,6 +28,11 @@ def _tiny_q(bits, rows=16, K=256, M=3, r=32, seed=0, ab_bits=16):
     qz, sc = layout.pack_zeros(zeros), layout.pack_scales(scales)
     if ab_bits == 16:
         Ap, Bp, As, Bs = layout.pack_f16(A), layout.pack_f16(B), None, None
+    elif ab_bits == 3:
+        ca, sa = synth.quantize_sym3(A)
+        cb, sb = synth.quantize_sym3(B)
+        Ap, As = layout.pack_q3(ca), layout.pack_scales(sa)
+        Bp, Bs = layout.pack_q3(cb), layout.pack_scales(sb)
     else:
         KTb = min(128, r)
         ca, sa = synth.quantize_sym4(A, 128)
@@ -38,7 +43,7 @@ def _tiny_q(bits, rows=16, K=256, M=3, r=32, seed=0, ab_bits=16):
                 ab_bits=ab_bits, logical=(codes, zeros, scales, A, B))
 
 
-@pytest.mark.parametrize("bits,ab_bits,r", [(4, 16, 32), (3, 16, 32), (4, 4, 64), (3, 4, 128), (2, 16, 32)])
+@pytest.mark.parametrize("bits,ab_bits,r", [(4, 16, 32), (3, 16, 32), (4, 4, 64), (3, 4, 128), (2, 16, 32), (4, 3, 128)])
 def test_forward_exact_rational(bits, ab_bits, r):
     """All stored inputs are dyadic rationals, so y is computable exactly with
     Fractions from the raw words, by decoders that share nothing with the oracle."""
@@ -53,6 +58,11 @@ def test_forward_exact_rational(bits, ab_bits, r):
     What = [[s[o][i // 128] * (q[o][i] - z[o][i // 128]) for i in range(K)] for o in range(rows)]
     if ab_bits == 16:
         Af, Bf = pyref.decode_f16(d["A"], r, K), pyref.decode_f16(d["B"], rows, r)
+    elif ab_bits == 3:
+        qa, sa = pyref.decode_q3(d["A"], r, K), pyref.decode_scales(d["As"], r, K // 128)
+        qb, sb = pyref.decode_q3(d["B"], rows, r), pyref.decode_scales(d["Bs"], rows, r // 128)
+        Af = [[sa[p][i // 128] * (qa[p][i] - 4) for i in range(K)] for p in range(r)]
+        Bf = [[sb[o][p // 128] * (qb[o][p] - 4) for p in range(r)] for o in range(rows)]
     else:
         KTb = min(128, r)
         qa, sa = pyref.decode_q4(d["A"], r, K), pyref.decode_scales(d["As"], r, K // 128)
