@@ -47,6 +47,8 @@ WORKLOADS["llama3-8b-layer-decode-w4g128-4xr128fp16-M64-multi"] = dict(model="8b
 WORKLOADS["llama3-8b-layer-decode-w4g128-4xr128fp16-M8-multi"] = dict(model="8b", w_bits=4, ab_bits=16, r=512, M=8, cfg=1, multi=4)
 WORKLOADS["llama3-8b-layer-decode-w4g128-r512fp16-M64"] = dict(model="8b", w_bits=4, ab_bits=16, r=512, M=64, cfg=1)    # same bytes, one adapter
 WORKLOADS["llama3-8b-layer-decode-w4g128-r128fp16-M64"] = dict(model="8b", w_bits=4, ab_bits=16, r=128, M=64, cfg=1)
+# 3-bit factors (App. A.9)
+WORKLOADS["llama3-8b-layer-decode-w4g128-r128q3-M1"] = dict(model="8b", w_bits=4, ab_bits=3, r=128, M=1, cfg=3)
 # 2-bit backbone (App. A.14 evaluates 2-bit models), same layer
 WORKLOADS["llama3-8b-layer-decode-w2g128-r128fp16-M1"] = dict(model="8b", w_bits=2, ab_bits=16, r=128, M=1, cfg=2)
 WORKLOADS["llama3-8b-layer-decode-w2g128-bare-M1"] = dict(model="8b", w_bits=2, ab_bits=16, r=0, M=1, cfg=2)
@@ -61,7 +63,8 @@ for _n in ("llama3-8b-layer-decode-w3g128-r128fp16-M1", "llama3-8b-layer-decode-
            "llama3-8b-layer-decode-w4g128-bare-M1", "llama3-8b-layer-prefill-w4g128-r256fp16-M2048",
            "llama3-8b-layer-prefill-w4g128-bare-M2048", "llama3-70b-layer-decode-w3g128-r128fp16-M1",
            "llama3-70b-layer-decode-w3g128-bare-M1", "llama3-8b-layer-decode-w2g128-r128fp16-M1",
-           "llama3-8b-layer-decode-w2g128-bare-M1", "llama3-8b-layer-prefill-w2g128-r256fp16-M2048"):
+           "llama3-8b-layer-decode-w2g128-bare-M1", "llama3-8b-layer-prefill-w2g128-r256fp16-M2048",
+           "llama3-8b-layer-decode-w4g128-r128q3-M1"):
     WORKLOADS[_n + "-grouped"] = dict(WORKLOADS[_n], grouped=True)
 GROUPS = (("q", "k", "v"), ("o",), ("gate", "up"), ("down",))
 for _r in (64, 256, 512):
@@ -88,6 +91,8 @@ def algorithmic_bytes(d_in, d_out, M, r, w_bits, ab_bits, group=128, sq=False):
     if r:
         if ab_bits == 16:
             b += 2 * r * (d_in + d_out)
+        elif ab_bits == 3:
+            b += r * d_in * 3 / 8 + 2 * r * (d_in // 128) + d_out * r * 3 / 8 + 2 * d_out * (r // 128)
         else:
             KTb = min(128, r)
             b += r * d_in / 2 + 2 * r * (d_in // 128) + d_out * r / 2 + 2 * d_out * (r // KTb)
@@ -132,6 +137,12 @@ class Linear:
             host = [qw, sc, qz, None, None, None, None]
         if self.r and self.ab_bits == 16:
             host[3], host[4] = eora.pack_factor_f16(A), eora.pack_factor_f16(B)
+        elif self.r and self.ab_bits == 3:
+            ca, sa = synth.quantize_sym3(A)
+            cb, sb = synth.quantize_sym3(B)
+            host[3], host[5] = eora.pack_factor_q3(ca, sa)
+            host[4], host[6] = eora.pack_factor_q3(cb, sb)
+            self.logical = (codes, zeros, scales, (ca, sa), (cb, sb), x)
         elif self.r:
             ca, sa = synth.quantize_sym4(A, 128)
             cb, sb = synth.quantize_sym4(B, min(128, self.r))
@@ -245,6 +256,9 @@ def cpu_baseline(linears, names):
         Ap = Bp = As = Bs = None
         if L.r and L.ab_bits == 16:
             Ap, Bp = layout.pack_f16(A), layout.pack_f16(B)
+        elif L.r and L.ab_bits == 3:
+            Ap, As = layout.pack_q3(A[0]), layout.pack_scales(A[1])
+            Bp, Bs = layout.pack_q3(B[0]), layout.pack_scales(B[1])
         elif L.r:
             Ap, As = layout.pack_q4(A[0], 128), layout.pack_scales(A[1])
             Bp, Bs = layout.pack_q4(B[0], min(128, L.r)), layout.pack_scales(B[1])

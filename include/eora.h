@@ -138,6 +138,10 @@ int eora_pack_factor_f16(const uint16_t* mat, int rows, int cols, void* out);
  * KT = min(128, cols).  rows % 16 == 0, cols == 64 or cols % 128 == 0. */
 int eora_pack_factor_q4(const uint8_t* codes, const uint16_t* scales, int rows, int cols,
                         void* q_out, void* scales_out);
+/* 3-bit symmetric factor (App. A.9 quantises the factors to 3 and 4 bits): codes rows x cols in 0..7
+ * (zero-point 4) in the Q3 tile layout, scales rows x cols/128 fp16.  rows % 16 == 0, cols % 128 == 0. */
+int eora_pack_factor_q3(const uint8_t* codes, const uint16_t* scales, int rows, int cols,
+                        void* q_out, void* scales_out);
 /* 2:4 sparse backbone: vals d_out x d_in/2 fp16 bit patterns (the kept values in column order),
  * pos d_out x d_in/2 their positions 0..3 inside the group of four, strictly ascending per pair. */
 int eora_pack_sp24(const uint16_t* vals, const uint8_t* pos, int d_in, int d_out,
@@ -155,15 +159,15 @@ int eora_pack_sp24q4(const uint8_t* codes, const uint8_t* pos, const uint8_t* ze
  *
  * x        fp16 row-major M x d_in
  * qweight  Q4 or Q3 tiles (w_bits), scales / qzeros as described above
- * A, B     F16 tiles (ab_bits == 16; A_scales = B_scales = NULL) or Q4 symmetric tiles with fp16
- *          scales (ab_bits == 4).  r == 0 (then A, B may be NULL) is the bare compressed layer,
+ * A, B     F16 tiles (ab_bits == 16; A_scales = B_scales = NULL), Q4 symmetric tiles with fp16
+ *          scales (ab_bits == 4) or Q3 symmetric tiles with fp16 scales (ab_bits == 3).  r == 0 (then A, B may be NULL) is the bare compressed layer,
  *          i.e. the adapter switched off.
  * y        fp16 row-major M x d_out, overwritten; fp32 accumulation, one round-to-nearest-even
  *          conversion at the end.
  * Constraints: M >= 0 (M == 0 is a no-op), d_out % 16 == 0, d_in % 128 == 0, group % 128 == 0,
  *          d_in % group == 0 (group == d_in is channel-wise quantisation), w_bits in {2,3,4},
- *          ab_bits in {16,4}, r <= 512 and r % 32 == 0 (ab_bits 16) or r == 64 or r % 128 == 0
- *          (ab_bits 4).
+ *          ab_bits in {16,4,3}, r <= 512 and r % 32 == 0 (ab_bits 16), r == 64 or r % 128 == 0
+ *          (ab_bits 4), r % 128 == 0 (ab_bits 3).
  * ------------------------------------------------------------------------------------------ */
 int eora_linear_q(const void* x, const void* qweight, const void* scales, const void* qzeros,
                   const void* A, const void* B, const void* A_scales, const void* B_scales,
@@ -205,10 +209,10 @@ int eora_linear_q_group(const void* x, const eora_q_member* members, int n_membe
  * fitted for different tasks can be loaded next to one backbone and chosen per request.)
  * A_all: the adapters' A stacked by rows, (n_adapters*r) x d_in, packed as ONE factor (eora_pack_factor_*);
  * B_all: their B side by side, d_out x (n_adapters*r), packed as one factor; A_scales / B_scales likewise
- * for ab_bits == 4.  adapter_of_row: DEVICE, M int32, read by the kernel (values outside [-1, n_adapters)
+ * for ab_bits 4 and 3.  adapter_of_row: DEVICE, M int32, read by the kernel (values outside [-1, n_adapters)
  * behave as -1).  All adapters are streamed whatever the rows select; the backbone is streamed once.
  * Constraints: as eora_linear_q with rank n_adapters*r (<= 512); r % 32 == 0 (r % 128 == 0 for
- * ab_bits == 4, so that no scale group spans two adapters); workspace of
+ * ab_bits 4 and 3, so that no scale group spans two adapters); workspace of
  * eora_workspace_bytes(M, d_in, d_out, n_adapters*r).  Errors as eora_linear_q. */
 int eora_linear_q_multi(const void* x, const void* qweight, const void* scales, const void* qzeros,
                         const void* A_all, const void* B_all, const void* A_scales, const void* B_scales,

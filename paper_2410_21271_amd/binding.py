@@ -55,6 +55,7 @@ def _load():
         "eora_pack_q": (ci, [vp, vp, vp, ci, ci, ci, ci, vp, vp, vp]),
         "eora_pack_factor_f16": (ci, [vp, ci, ci, vp]),
         "eora_pack_factor_q4": (ci, [vp, vp, ci, ci, vp, vp]),
+        "eora_pack_factor_q3": (ci, [vp, vp, ci, ci, vp, vp]),
         "eora_pack_sp24": (ci, [vp, vp, ci, ci, vp, vp]),
         "eora_pack_sp24q4": (ci, [vp, vp, vp, vp, ci, ci, ci, vp, vp]),
         "eora_linear_q": (ci, [vp] * 9 + [ci] * 7 + [vp, sz, vp]),
@@ -83,7 +84,7 @@ EXPORTS = ["eora_status_string", "eora_qweight_bytes", "eora_qzeros_bytes", "eor
            "eora_pack_factor_f16", "eora_pack_factor_q4", "eora_pack_sp24", "eora_linear_q",
            "eora_linear_q_group", "eora_linear_sp24", "eora_unpack_q", "eora_dequant_q", "eora_expand_sp24",
            "eora_sp24q4_tiles_bytes", "eora_sp24q4_meta_bytes", "eora_pack_sp24q4", "eora_linear_sp24q4", "eora_expand_sp24q4",
-           "eora_factors_workspace_bytes", "eora_factors", "eora_linear_q_multi"]
+           "eora_factors_workspace_bytes", "eora_factors", "eora_linear_q_multi", "eora_pack_factor_q3"]
 
 
 def status_string(status):
@@ -165,6 +166,17 @@ def pack_factor_q4(codes, scales):
     sc = np.empty(scales.size, np.float16)
     _check(lib.eora_pack_factor_q4(_np_ptr(codes), _np_ptr(scales), rows, cols, _np_ptr(q), _np_ptr(sc)),
            "pack_factor_q4")
+    return q, sc
+
+
+def pack_factor_q3(codes, scales):
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    scales = np.ascontiguousarray(scales, dtype=np.float16)
+    rows, cols = codes.shape
+    q = np.empty(rows * cols * 3 // 32, np.uint32)
+    sc = np.empty(scales.size, np.float16)
+    _check(lib.eora_pack_factor_q3(_np_ptr(codes), _np_ptr(scales), rows, cols, _np_ptr(q), _np_ptr(sc)),
+           "pack_factor_q3")
     return q, sc
 
 

@@ -62,6 +62,9 @@ int factor_formats(int r, int ab_bits, int* fa, int* fe)
         if (r != 64 && r % 128) return EORA_ERR_SHAPE;
         *fe = (r == 64) ? S_Q4S64 : S_Q4S128;
         *fa = S_Q4S128;
+    } else if (ab_bits == 3) {
+        if (r % 128) return EORA_ERR_SHAPE;
+        *fa = *fe = S_Q3S128;
     } else {
         return EORA_ERR_UNSUPPORTED;
     }
@@ -237,7 +240,8 @@ static int validate_linear_q(const void* x, const eora_q_member& e, int M, int d
     *fe = *fa = S_NONE;
     if (r > 0) {
         if (!e.A || !e.B) return EORA_ERR_NULL;
-        if (ab_bits == 4 && (!e.A_scales || !e.B_scales)) return EORA_ERR_NULL;
+        if (ab_bits != 16 && ab_bits != 4 && ab_bits != 3) return EORA_ERR_UNSUPPORTED;
+        if (ab_bits != 16 && (!e.A_scales || !e.B_scales)) return EORA_ERR_NULL;
         rc = factor_formats(r, ab_bits, fa, fe);
         if (rc != EORA_OK) return rc;
         if (!aligned16(e.A) || !aligned16(e.B) || !aligned16(e.A_scales) || !aligned16(e.B_scales)) return EORA_ERR_ALIGN;
@@ -314,7 +318,7 @@ int eora_linear_q_multi(const void* x, const void* qweight, const void* scales, 
                         const void* adapter_of_row, void* y, int M, int d_in, int d_out, int r, int n_adapters,
                         int w_bits, int group, int ab_bits, void* workspace, size_t workspace_bytes, void* stream)
 {
-    if (n_adapters < 1 || r < 1 || r % 32 || (ab_bits == 4 && r % 128)) return EORA_ERR_SHAPE;
+    if (n_adapters < 1 || r < 1 || r % 32 || (ab_bits != 16 && r % 128)) return EORA_ERR_SHAPE;
     if ((long long)n_adapters * r > MAX_RANK) return EORA_ERR_SHAPE;
     if (!adapter_of_row) return EORA_ERR_NULL;
     if (reinterpret_cast<uintptr_t>(adapter_of_row) & 3u) return EORA_ERR_ALIGN;

@@ -370,6 +370,7 @@ static hipError_t launch_ab(const FusedArgs& a, int fa, int fe, hipStream_t stre
     if (fa == S_F16 && fe == S_F16) return launch_cfg<FM, S_F16, S_F16>(a, stream);
     if (fa == S_Q4S128 && fe == S_Q4S128) return launch_cfg<FM, S_Q4S128, S_Q4S128>(a, stream);
     if (fa == S_Q4S128 && fe == S_Q4S64) return launch_cfg<FM, S_Q4S128, S_Q4S64>(a, stream);
+    if (fa == S_Q3S128 && fe == S_Q3S128) return launch_cfg<FM, S_Q3S128, S_Q3S128>(a, stream);
     return hipErrorInvalidValue;
 }
 

@@ -7,7 +7,7 @@
 namespace eora {
 
 // stored formats a contraction segment can read
-enum SegFmt { S_NONE = 0, S_Q4 = 1, S_Q3 = 2, S_Q4S128 = 3, S_Q4S64 = 4, S_F16 = 5, S_Q2 = 6 };
+enum SegFmt { S_NONE = 0, S_Q4 = 1, S_Q3 = 2, S_Q4S128 = 3, S_Q4S64 = 4, S_F16 = 5, S_Q2 = 6, S_Q3S128 = 7 };
 
 // backbone format of a bit width (2, 3 or 4)
 inline int backbone_format(int w_bits) { return w_bits == 4 ? S_Q4 : (w_bits == 3 ? S_Q3 : S_Q2); }

@@ -178,6 +178,17 @@ int eora_pack_factor_q4(const uint8_t* codes, const uint16_t* scales, int rows, 
     return EORA_OK;
 }
 
+int eora_pack_factor_q3(const uint8_t* codes, const uint16_t* scales, int rows, int cols,
+                        void* q_out, void* scales_out)
+{
+    if (!codes || !scales || !q_out || !scales_out) return EORA_ERR_NULL;
+    if (rows <= 0 || rows % 16 || cols <= 0 || cols % 128) return EORA_ERR_SHAPE;
+    int rc = pack_q3_tiles(codes, rows, cols, (uint32_t*)q_out);
+    if (rc != EORA_OK) return rc;
+    pack_scale_tiles(scales, rows, cols / 128, (uint16_t*)scales_out);
+    return EORA_OK;
+}
+
 int eora_pack_sp24(const uint16_t* vals, const uint8_t* pos, int d_in, int d_out,
                    void* values_out, void* indices_out)
 {

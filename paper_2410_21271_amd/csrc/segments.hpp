@@ -11,6 +11,7 @@ template <> struct Fmt<S_Q4> { static constexpr int KT = 128, WORDS = 4; static 
 template <> struct Fmt<S_Q3> { static constexpr int KT = 128, WORDS = 3; static constexpr bool ASYM = true; };
 template <> struct Fmt<S_Q2> { static constexpr int KT = 128, WORDS = 2; static constexpr bool ASYM = true; };
 template <> struct Fmt<S_Q4S128> { static constexpr int KT = 128, WORDS = 4; static constexpr bool ASYM = false; };
+template <> struct Fmt<S_Q3S128> { static constexpr int KT = 128, WORDS = 3; static constexpr bool ASYM = false; };
 template <> struct Fmt<S_Q4S64> { static constexpr int KT = 64, WORDS = 2; static constexpr bool ASYM = false; };
 template <> struct Fmt<S_F16> { static constexpr int KT = 32, WORDS = 4; static constexpr bool ASYM = false; };
 
@@ -79,6 +80,8 @@ __device__ __forceinline__ void decode_tile(const uint32_t (&w)[Fmt<FMT>::WORDS]
         b[0] = f.v;
     } else if constexpr (FMT == S_Q3) {
         dq3_lane(w[0], w[1], w[2], z, b);
+    } else if constexpr (FMT == S_Q3S128) {
+        dq3_lane(w[0], w[1], w[2], 4u, b);           // symmetric 3-bit factor: the zero-point is the constant 4
     } else if constexpr (FMT == S_Q2) {
         dq2_word(w[0], z, b[0], b[1]);
         dq2_word(w[1], z, b[2], b[3]);

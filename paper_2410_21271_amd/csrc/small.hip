@@ -428,6 +428,7 @@ static hipError_t launch_small_ab(const GroupArgs& a, int fa, int fe, int nw, in
     if (fa == S_F16 && fe == S_F16) return launch_small_shape<FM, S_F16, S_F16>(a, nw, nq, stream);
     if (fa == S_Q4S128 && fe == S_Q4S128) return launch_small_shape<FM, S_Q4S128, S_Q4S128>(a, nw, nq, stream);
     if (fa == S_Q4S128 && fe == S_Q4S64) return launch_small_shape<FM, S_Q4S128, S_Q4S64>(a, nw, nq, stream);
+    if (fa == S_Q3S128 && fe == S_Q3S128) return launch_small_shape<FM, S_Q3S128, S_Q3S128>(a, nw, nq, stream);
     return hipErrorInvalidValue;
 }
 

@@ -23,6 +23,12 @@ class QCase:
         self.o_A = self.o_B = self.o_As = self.o_Bs = None
         if r > 0 and ab_bits == 16:
             self.o_A, self.o_B = layout.pack_f16(A), layout.pack_f16(B)
+        elif r > 0 and ab_bits == 3:
+            ca, sa = synth.quantize_sym3(A)
+            cb, sb = synth.quantize_sym3(B)
+            self.logical.update(ca=ca, sa=sa, cb=cb, sb=sb)
+            self.o_A, self.o_As = layout.pack_q3(ca), layout.pack_scales(sa)
+            self.o_B, self.o_Bs = layout.pack_q3(cb), layout.pack_scales(sb)
         elif r > 0:
             KTb = min(128, r)
             ca, sa = synth.quantize_sym4(A, 128)
@@ -45,8 +51,9 @@ class QCase:
             assert np.array_equal(self.A.view(np.uint16), self.o_A.view(np.uint16))
             assert np.array_equal(self.B.view(np.uint16), self.o_B.view(np.uint16))
         elif self.r > 0:
-            self.A, self.As = e.pack_factor_q4(L["ca"], L["sa"])
-            self.B, self.Bs = e.pack_factor_q4(L["cb"], L["sb"])
+            pack = e.pack_factor_q3 if self.ab_bits == 3 else e.pack_factor_q4
+            self.A, self.As = pack(L["ca"], L["sa"])
+            self.B, self.Bs = pack(L["cb"], L["sb"])
             assert np.array_equal(self.A, self.o_A) and np.array_equal(self.B, self.o_B)
             assert np.array_equal(self.As.view(np.uint16), self.o_As.view(np.uint16))
             assert np.array_equal(self.Bs.view(np.uint16), self.o_Bs.view(np.uint16))

@@ -26,7 +26,7 @@ def test_library_exports_every_declared_symbol():
         assert getattr(raw, name) is not None
 
 
-@pytest.mark.parametrize("w_bits,ab_bits,r", [(4, 16, 32), (3, 16, 64), (4, 4, 64), (3, 4, 128), (4, 16, 0), (2, 16, 32)])
+@pytest.mark.parametrize("w_bits,ab_bits,r", [(4, 16, 32), (3, 16, 64), (4, 4, 64), (3, 4, 128), (4, 16, 0), (2, 16, 32), (4, 3, 128)])
 def test_host_packers_match_oracle_bytes(w_bits, ab_bits, r):
     QCase(100 + w_bits + r, 256, 48, 2, r, w_bits, 128, ab_bits, packer=eora)      # asserts inside
     QCase(200 + w_bits + r, 256, 32, 1, r, w_bits, 256, ab_bits, packer=eora)      # channel-wise group
@@ -98,6 +98,7 @@ def test_linear_q_validation_codes():
     assert call(r=48) == -2 and call(r=1024) == -2 and call(M=-1) == -2
     assert call(w_bits=1) == -3 and call(w_bits=5) == -3 and call(ab_bits=8) == -3
     assert call(ab_bits=4, As=good, Bs=good, r=96) == -2 and call(ab_bits=4, r=64) == -1
+    assert call(ab_bits=3, As=good, Bs=good, r=64) == -2 and call(ab_bits=3, r=128) == -1
     assert call(qw=odd) == -4 and call(y=odd) == -4 and call(ws=odd) == -4
     assert call(ws=null) == -5 and call(ws_bytes=16) == -5
     assert call(M=0) == 0                                   # empty input: nothing to do, nothing launched

@@ -50,6 +50,7 @@ def test_unpack_and_dequant_bit_exact(gpu, w_bits, group):
     (4, 16, 0, 1), (4, 16, 32, 1), (4, 16, 128, 3), (3, 16, 0, 1), (3, 16, 64, 2),
     (4, 4, 64, 1), (4, 4, 128, 5), (3, 4, 256, 16), (4, 16, 96, 16), (4, 16, 64, 17), (3, 16, 32, 37),
     (2, 16, 0, 1), (2, 16, 64, 2), (2, 4, 128, 5), (2, 16, 32, 37),
+    (4, 3, 128, 1), (3, 3, 128, 3), (2, 3, 256, 5), (4, 3, 128, 17),
 ])
 def test_linear_q_small_shapes(gpu, w_bits, ab_bits, r, M):
     """Several row blocks and k-tiles, ragged token counts."""
@@ -124,6 +125,8 @@ def test_config_shapes_fp16_factors(gpu, name, d_in, d_out, w_bits, M):
     (3, 16, 128, 1, 4096, (14336, 14336)),          # gate / up: enough row blocks that a workgroup takes two
     (4, 4, 128, 1, 4096, (1024, 2048)),             # 4-bit factors, config 3
     (2, 16, 128, 1, 4096, (4096, 1024, 1024)),      # 2-bit backbone
+    (4, 3, 128, 1, 4096, (4096, 1024, 1024)),       # 3-bit factors
+    (4, 3, 128, 150, 512, (64, 32)),                # 3-bit factors, many tokens (no GEMM path: chunks of the layer kernel)
     (4, 16, 32, 3, 1024, (64, 16, 48, 32)),         # four members, three tokens
     (4, 16, 0, 2, 2048, (128, 64)),                 # adapter off
     (3, 16, 64, 8, 512, (64, 32)),                  # a shape the decode kernel does not take: members run in turn
@@ -236,6 +239,8 @@ def test_linear_sp24_ragged_k_and_determinism(gpu):
     (2, 16, 128, 1, 4096, 4096),       # 2-bit backbone at the 8B shapes
     (2, 16, 128, 1, 14336, 1024),
     (2, 4, 128, 3, 4096, 1024),
+    (4, 3, 128, 1, 4096, 4096),        # 3-bit factors at the 8B shapes
+    (3, 3, 256, 2, 14336, 1024),
 ])
 def test_more_config_shapes(gpu, w_bits, ab_bits, r, M, d_in, d_out):
     """Full contraction lengths of the configured layers that the other tests do not reach (every
@@ -259,6 +264,8 @@ def test_more_config_shapes(gpu, w_bits, ab_bits, r, M, d_in, d_out):
     (4, 16, 128, 127, 4096, 512, 128),     # eight token blocks, the last one ragged
     (2, 16, 128, 16, 2048, 8192, 128),     # 2-bit backbone
     (2, 16, 64, 37, 2048, 8208, 256),
+    (4, 3, 128, 16, 2048, 8192, 128),      # 3-bit factors
+    (3, 3, 128, 64, 4096, 4096, 128),
 ])
 def test_linear_q_mid_token_counts(gpu, w_bits, ab_bits, r, M, d_in, d_out, group):
     """The kernel for 5..127 tokens (x shared through LDS), every split of a workgroup it launches."""
