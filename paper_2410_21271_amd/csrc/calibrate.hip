@@ -124,6 +124,168 @@ __global__ __launch_bounds__(NT) void jacobi_round_kernel(double* __restrict__ H
     }
 }
 
+// ------------------------------------------------------------------------------------------------------------
+// Block version of a round, for m % 16 == 0 and row lengths that are multiples of 128: a workgroup takes two
+// blocks of eight rows (16 x L), forms their 16 x 16 Gram matrix S with fp64 MFMAs, diagonalises S in LDS with a
+// small two-sided Jacobi iteration (S = J D J^T, J orthogonal), and replaces the rows by J^T times the rows
+// (MFMAs again), which makes all 16 mutually orthogonal at once: 120 row pairs for three passes over the rows
+// instead of one pair for two.  The eigenvector rows get the same J^T.
+//
+// v_mfma_f64_16x16x4_f64 operand layout (lane l, n = l % 16, g = l / 16): A[i = n][k = g], B[k = g][j = n],
+// result register v holds D[i = 4 v + g][j = n].
+typedef double d4 __attribute__((ext_vector_type(4)));
+constexpr int BJ_NT = 512, BJ_NW = BJ_NT / 64;
+constexpr int BJ_INNER_SWEEPS = 30;
+
+__device__ __forceinline__ d4 mfma64(double a, double b, d4 c) { return __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, c, 0, 0, 0); }
+
+// rows <- J^T rows for the 16 rows (block P, block Q) of X (row length len, a multiple of 128)
+__device__ __forceinline__ void apply_rotation(double* __restrict__ X, int len, int P, int Q, const double (*J)[17], int wave,
+                                               int lane)
+{
+    const int n = lane & 15, g = lane >> 4;
+    double aJ[4];                       // A operand of step kk: (J^T)[i = n][k = 4 kk + g] = J[4 kk + g][n]
+    size_t rowoff[4];                   // rows 4 kk + g (loads) = rows 4 v + g (stores)
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+        const int j = 4 * kk + g;
+        aJ[kk] = J[j][n];
+        rowoff[kk] = (size_t)(j < 8 ? 8 * P + j : 8 * Q + j - 8) * len;
+    }
+    const int ngroups = len / 128;      // a group: 128 columns = four chunks of 32 (two columns per lane)
+    for (int gi = wave; gi < ngroups; gi += BJ_NW) {
+        double2 ld[4][4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk)
+                ld[u][kk] = *reinterpret_cast<const double2*>(X + rowoff[kk] + 128 * gi + 32 * u + 2 * n);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            d4 d0 = {0, 0, 0, 0}, d1 = {0, 0, 0, 0};
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+                d0 = mfma64(aJ[kk], ld[u][kk].x, d0);
+                d1 = mfma64(aJ[kk], ld[u][kk].y, d1);
+            }
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+                *reinterpret_cast<double2*>(X + rowoff[v] + 128 * gi + 32 * u + 2 * n) = make_double2(d0[v], d1[v]);
+        }
+    }
+}
+
+__global__ __launch_bounds__(BJ_NT) void jacobi_block_round_kernel(double* __restrict__ H, int L, double* __restrict__ V, int m,
+                                                                    int round, double tol, double abs_floor,
+                                                                    unsigned* __restrict__ rotations)
+{
+    __shared__ double Sw[BJ_NW][16][17];
+    __shared__ double S[16][17], J[16][17];
+    __shared__ double rco[8], rsi[8];
+    __shared__ int rp[8], rq[8];
+    __shared__ int s_any[BJ_INNER_SWEEPS];      // one flag per sweep, so that none is ever cleared while in use
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int n = lane & 15, g = lane >> 4;
+    const int nb = m / 8, mm = nb - 1, i = blockIdx.x;
+    int P, Q;
+    if (i == 0) {
+        P = round;
+        Q = mm;
+    } else {
+        P = (round + i) % mm;
+        Q = (round + mm - i) % mm;
+    }
+    // ---- Gram matrix of the 16 rows: lane (n, g) feeds row n, both operands of the MFMA are the same register
+    {
+        const double* row = H + (size_t)(n < 8 ? 8 * P + n : 8 * Q + n - 8) * L;
+        d4 acc = {0, 0, 0, 0};
+        const int ngroups = L / 128;
+        for (int gi = wave; gi < ngroups; gi += BJ_NW) {
+            double2 ld[16];             // columns 128 gi + 8 e + 2 g + {0, 1}, e = 0 .. 15
+#pragma unroll
+            for (int e = 0; e < 16; ++e) ld[e] = *reinterpret_cast<const double2*>(row + 128 * gi + 8 * e + 2 * g);
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                acc = mfma64(ld[e].x, ld[e].x, acc);
+                acc = mfma64(ld[e].y, ld[e].y, acc);
+            }
+        }
+#pragma unroll
+        for (int v = 0; v < 4; ++v) Sw[wave][4 * v + g][n] = acc[v];
+    }
+    __syncthreads();
+    if (tid < 256) {
+        const int r = tid >> 4, c = tid & 15;
+        double t = 0;
+#pragma unroll
+        for (int w = 0; w < BJ_NW; ++w) t += Sw[w][r][c];
+        S[r][c] = t;
+        J[r][c] = r == c ? 1.0 : 0.0;
+    }
+    if (tid < BJ_INNER_SWEEPS) s_any[tid] = 0;
+    __syncthreads();
+    // ---- S = J D J^T by two-sided Jacobi: eight disjoint pairs per step, fifteen steps per sweep
+    bool rotated = false;
+    for (int sweep = 0; sweep < BJ_INNER_SWEEPS; ++sweep) {
+        for (int step = 0; step < 15; ++step) {
+            if (tid < 8) {
+                int p, q;
+                if (tid == 0) {
+                    p = step;
+                    q = 15;
+                } else {
+                    p = (step + tid) % 15;
+                    q = (step + 15 - tid) % 15;
+                }
+                const double a = S[p][p], b = S[q][q], c = S[p][q];
+                double co = 1.0, si = 0.0;
+                if (a > abs_floor && b > abs_floor && fabs(c) > tol * sqrt(a) * sqrt(b)) {
+                    const double zeta = (b - a) / (2.0 * c);
+                    const double t = copysign(1.0, zeta) / (fabs(zeta) + sqrt(1.0 + zeta * zeta));
+                    co = 1.0 / sqrt(1.0 + t * t);
+                    si = co * t;
+                    s_any[sweep] = 1;
+                }
+                rp[tid] = p;
+                rq[tid] = q;
+                rco[tid] = co;
+                rsi[tid] = si;
+            }
+            __syncthreads();
+            if (tid < 256) {            // rows of S (threads 0 .. 127), columns of J (128 .. 255)
+                const int k = (tid & 127) >> 4, c = tid & 15;
+                const int p = rp[k], q = rq[k];
+                const double co = rco[k], si = rsi[k];
+                if (tid < 128) {
+                    const double a = S[p][c], b = S[q][c];
+                    S[p][c] = co * a - si * b;
+                    S[q][c] = si * a + co * b;
+                } else {
+                    const double a = J[c][p], b = J[c][q];
+                    J[c][p] = co * a - si * b;
+                    J[c][q] = si * a + co * b;
+                }
+            }
+            __syncthreads();
+            if (tid < 128) {            // columns of S
+                const int k = tid >> 4, r = tid & 15;
+                const int p = rp[k], q = rq[k];
+                const double co = rco[k], si = rsi[k];
+                const double a = S[r][p], b = S[r][q];
+                S[r][p] = co * a - si * b;
+                S[r][q] = si * a + co * b;
+            }
+            __syncthreads();
+        }
+        if (s_any[sweep] == 0) break;       // written before the last barrier of the sweep: uniform
+        rotated = true;
+    }
+    if (!rotated) return;               // the 16 rows were orthogonal already (uniform over the workgroup)
+    if (tid == 0) atomicAdd(rotations, 1u);
+    apply_rotation(H, L, P, Q, J, wave, lane);
+    if (V) apply_rotation(V, m, P, Q, J, wave, lane);
+}
+
 // C[i][j] = sum_k A[i*ai + k*ak] * B[j*bj + k*bk], i < M, j < N, k < K.  64 x 64 outputs per workgroup of
 // 256 threads, 4 x 4 per thread, operands staged through LDS sixteen k at a time.
 template <typename TA, typename TB>
@@ -298,6 +460,8 @@ void gemm(const TA* A, long ai, long ak, const TB* B, long bj, long bk, double* 
                        ldc, M, N, K);
 }
 
+bool block_rounds_fit(int L, bool with_v, int m) { return m % 16 == 0 && m >= 32 && L % 128 == 0 && (!with_v || m % 128 == 0); }
+
 void jacobi_round(double* H, int L, double* V, int m, int round, double tol, double abs_floor, unsigned* rot, hipStream_t st)
 {
     const dim3 g(m / 2);
@@ -358,7 +522,12 @@ int jacobi_sweeps(double* H, int L, double* V, int m, double* sq, unsigned* rot,
     const double tol = sqrt((double)L) * 1.1102230246251565e-16;
     for (int sweep = 1; sweep <= MAX_SWEEPS; ++sweep) {
         hipLaunchKernelGGL(clear_counter_kernel, dim3(1), dim3(1), 0, st, rot);
-        for (int round = 0; round < m - 1; ++round) jacobi_round(H, L, V, m, round, tol, abs_floor, rot, st);
+        if (block_rounds_fit(L, V != nullptr, m) && !getenv("EORA_JACOBI_SCALAR")) {
+            for (int round = 0; round < m / 8 - 1; ++round)
+                hipLaunchKernelGGL(jacobi_block_round_kernel, dim3(m / 16), dim3(BJ_NT), 0, st, H, L, V, m, round, tol, abs_floor, rot);
+        } else {
+            for (int round = 0; round < m - 1; ++round) jacobi_round(H, L, V, m, round, tol, abs_floor, rot, st);
+        }
         unsigned n = 0;
         if (hipMemcpyAsync(&n, rot, sizeof(n), hipMemcpyDeviceToHost, st) != hipSuccess ||
             hipStreamSynchronize(st) != hipSuccess)
