@@ -317,14 +317,18 @@ def calibration_main(args):
         _, _, st = run(W, W_hat, Xt, d_in, d_out, n, r)
     torch.cuda.synchronize()
     sec = (time.perf_counter() - t0) / steps
-    # dominant kernel: Jacobi rounds of the eigendecomposition.  Algorithmic bytes of a round: every row of
-    # the Gram matrix read once; a rotated pair also writes its two rows and reads and writes two rows of V.
-    rounds = st["eig_sweeps"] * (d_in - 1)
-    bytes_total = rounds * 8.0 * d_in * d_in + st["eig_rotations"] * 8.0 * (2 * d_in + 4 * d_in)
+    # dominant kernel: Jacobi rounds of the eigendecomposition.  Algorithmic bytes of a round: every row of the
+    # Gram matrix read once (the dot products / the Gram blocks); a workgroup that rotates its rows (2 of them,
+    # or 16 in a block round, which reads them a second time for the MFMA product) also writes them and reads
+    # and writes as many rows of the eigenvector matrix.
+    rows = st["eig_rows"]
+    rounds = st["eig_sweeps"] * ((d_in - 1) if rows == 2 else (d_in // 8 - 1))
+    per_rotation = 8.0 * rows * ((1 if rows == 2 else 2) * d_in + 2 * d_in)
+    bytes_total = rounds * 8.0 * d_in * d_in + st["eig_rotations"] * per_rotation
     us_round = 1e3 * st["eig_ms"] / rounds
     roofline = dict(bound="hbm", achieved=round(bytes_total / rounds / us_round / 1e3, 1), peak=HBM_PEAK_GBS, unit="GB/s",
                     frac=round(bytes_total / rounds / us_round / 1e3 / HBM_PEAK_GBS, 4), traffic=None,
-                    kernel="Jacobi round of the eigendecomposition (rows of length %d, with eigenvector rows)" % d_in,
+                    kernel="Jacobi round of the eigendecomposition (%d rows of length %d per workgroup, with eigenvector rows)" % (rows, d_in),
                     bytes_per_launch=int(bytes_total / rounds), us_per_launch=round(us_round, 3), launches=rounds)
     out = dict(metric="seconds for Algorithm 1 steps 1-6 of one %d x %d linear (rank %d, %d calibration tokens)" % (d_out, d_in, r, n),
                value=round(sec, 4), unit="s", n_gpus=1, steps=steps, warmup=warmup, ms_per_step=round(1e3 * sec, 3),

@@ -264,10 +264,12 @@ size_t eora_factors_workspace_bytes(int d_in, int d_out, int r);
  * minimises || (W - What - B'A) X~ ||_F over rank-r corrections (Theorem 1).  Signs of the r components
  * are arbitrary (B'A is not).  eig_floor in [0, 1): eigenvalues of X~ X~^T below eig_floor times the
  * largest are raised to it before the inverse square root of step 6 (the paper assumes an invertible Q').
- * The eigendecomposition and the SVD are one-sided Jacobi iterations; the call SYNCHRONISES `stream`
+ * The eigendecomposition and the SVD are one-sided (block) Jacobi iterations; the call SYNCHRONISES `stream`
  * once per sweep and before returning, and allocates nothing on the device.
- * stats: HOST pointer to six doubles or NULL: for the eigendecomposition, then for the SVD, the number
- * of sweeps, the milliseconds its rounds took (events on `stream`) and the rotations applied.
+ * stats: HOST pointer to eight doubles or NULL: for the eigendecomposition, then for the SVD, the number
+ * of sweeps, the milliseconds its rounds took (events on `stream`), the workgroups that rotated their
+ * rows, and the rows a workgroup handles per round (16: block rounds, taken when the row count is a
+ * multiple of 16 and the row lengths are multiples of 128; 2: pair rounds).
  * Constraints: d_in, d_out even and <= 16384, 1 <= r <= min(d_in, d_out), n_tokens >= 1.
  * Errors: EORA_ERR_NULL / SHAPE / VALUE (eig_floor) / WORKSPACE / ALIGN / LAUNCH, and
  * EORA_ERR_NOT_CONVERGED (outputs then undefined). */

@@ -310,10 +310,11 @@ def factors_workspace_bytes(d_in, d_out, r):
 
 
 def factors(W_f32, W_hat_f32, Xt_f32, B_f64, A_f64, sigma_f64, n_tokens, d_in, d_out, r, eig_floor, workspace, stats=False):
-    """stats=True returns the six counters of eora_factors' `stats` argument as a dict."""
+    """stats=True returns the eight counters of eora_factors' `stats` argument as a dict."""
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
-    st = (ctypes.c_double * 6)() if stats else None
+    st = (ctypes.c_double * 8)() if stats else None
     _check(lib.eora_factors(_dp(W_f32), _dp(W_hat_f32), _dp(Xt_f32), n_tokens, d_in, d_out, r, float(eig_floor),
                             _dp(B_f64), _dp(A_f64), _dp(sigma_f64), _dp(workspace), ws_bytes, _stream(), st), "factors")
     if stats:
-        return dict(eig_sweeps=int(st[0]), eig_ms=st[1], eig_rotations=st[2], svd_sweeps=int(st[3]), svd_ms=st[4], svd_rotations=st[5])
+        return dict(eig_sweeps=int(st[0]), eig_ms=st[1], eig_rotations=st[2], eig_rows=int(st[3]),
+                    svd_sweeps=int(st[4]), svd_ms=st[5], svd_rotations=st[6], svd_rows=int(st[7]))

@@ -480,7 +480,8 @@ void jacobi_round(double* H, int L, double* V, int m, int round, double tol, dou
 
 // Sweeps until one passes without a rotation.  Synchronises the stream once per sweep.  sq: m doubles of
 // scratch.  Returns the number of sweeps, or -1 if MAX_SWEEPS did not suffice, or -2 on a runtime error.
-// stats (may be null): sweeps, milliseconds between two events around the sweeps, rotations applied.
+// stats (may be null): sweeps, milliseconds between two events around the sweeps, workgroups that rotated
+// their rows, rows per workgroup (2: pair rounds, 16: block rounds).
 int jacobi_sweeps(double* H, int L, double* V, int m, double* sq, unsigned* rot, hipStream_t st, double* rotations);
 
 int jacobi(double* H, int L, double* V, int m, double* sq, unsigned* rot, hipStream_t st, double* stats)
@@ -498,6 +499,7 @@ int jacobi(double* H, int L, double* V, int m, double* sq, unsigned* rot, hipStr
         stats[0] = sweeps;
         stats[1] = ms;
         stats[2] = rotations;
+        stats[3] = (block_rounds_fit(L, V != nullptr, m) && !getenv("EORA_JACOBI_SCALAR")) ? 16 : 2;
     }
     if (e0) hipEventDestroy(e0);
     if (e1) hipEventDestroy(e1);
@@ -642,7 +644,7 @@ extern "C" int eora_factors(const void* W_f32, const void* W_hat_f32, const void
         hipLaunchKernelGGL(scale_kernel, dim3(blocks(nw)), dim3(256), 0, st, T, d_out, k, root, 0);
         hipLaunchKernelGGL(copy_kernel, dim3(blocks(nw)), dim3(256), 0, st, T, T0, nw);
         // step 5: rows of T -> sigma_i v_i^T
-        sweeps = jacobi(T, k, nullptr, d_out, sq, rot, st, stats ? stats + 3 : nullptr);
+        sweeps = jacobi(T, k, nullptr, d_out, sq, rot, st, stats ? stats + 4 : nullptr);
         if (sweeps < 0) return sweeps == -1 ? EORA_ERR_NOT_CONVERGED : EORA_ERR_LAUNCH;
         hipLaunchKernelGGL(row_dot_kernel, dim3(d_out), dim3(256), 0, st, T, T, k, sq);
         hipLaunchKernelGGL(top_rows_kernel, dim3(blocks(d_out)), dim3(256), 0, st, sq, d_out, r, idx, sigma);
@@ -655,7 +657,7 @@ extern "C" int eora_factors(const void* W_f32, const void* W_hat_f32, const void
         hipLaunchKernelGGL(scale_kernel, dim3(blocks(nw)), dim3(256), 0, st, T, k, d_out, root, 1);
         hipLaunchKernelGGL(copy_kernel, dim3(blocks(nw)), dim3(256), 0, st, T, T0, nw);
         // step 5: rows of T -> sigma_i u_i^T, the columns of B'
-        sweeps = jacobi(T, d_out, nullptr, k, sq, rot, st, stats ? stats + 3 : nullptr);
+        sweeps = jacobi(T, d_out, nullptr, k, sq, rot, st, stats ? stats + 4 : nullptr);
         if (sweeps < 0) return sweeps == -1 ? EORA_ERR_NOT_CONVERGED : EORA_ERR_LAUNCH;
         hipLaunchKernelGGL(row_dot_kernel, dim3(k), dim3(256), 0, st, T, T, d_out, sq);
         hipLaunchKernelGGL(top_rows_kernel, dim3(blocks(k)), dim3(256), 0, st, sq, k, r, idx, sigma);
