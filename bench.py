@@ -75,6 +75,8 @@ DEFAULT = "llama3-8b-layer-decode-w3g128-r128fp16-M1-grouped"
 CALIBRATION = {
     "llama3-8b-q-factors-w4g128-r128-n8192": dict(d_in=4096, d_out=4096, n_tokens=8192, r=128, w_bits=4, sample=1536),
     "llama3-8b-k-factors-w4g128-r128-n8192": dict(d_in=4096, d_out=1024, n_tokens=8192, r=128, w_bits=4, sample=1536),
+    "llama3-8b-gate-factors-w4g128-r128-n8192": dict(d_in=4096, d_out=14336, n_tokens=8192, r=128, w_bits=4, sample=1536),
+    "llama3-8b-down-factors-w4g128-r128-n16384": dict(d_in=14336, d_out=4096, n_tokens=16384, r=128, w_bits=4, sample=1536),
     "small-factors-w4g128-r64-n2048": dict(d_in=1024, d_out=1024, n_tokens=2048, r=64, w_bits=4, sample=1024),
 }
 

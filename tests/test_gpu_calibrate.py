@@ -116,6 +116,22 @@ def test_planted_rank_r_error_is_recovered_and_served(gpu):
     assert err <= 2e-3, err
 
 
+def test_fewer_tokens_than_channels(gpu):
+    """Rank-deficient Gram matrix (tokens < d_in): its null space gets the floored eigenvalue on both sides
+    (the floor is isotropic there, so the basis chosen inside the null space does not matter).  The inverse
+    square root of the floor (1e4 relative to the largest root) amplifies rounding, hence the looser bound."""
+    from oracle import calibrate
+    d_in, d_out, n_tokens, r = 256, 64, 150, 8
+    W, W_hat, Xt = _inputs(7300, d_in, d_out, n_tokens)
+    B, A, sig = _run(gpu, W, W_hat, Xt, r, eig_floor=1e-8)
+    Bo, Ao = calibrate.eora_factors(W, W_hat, Xt, r, eig_floor=1e-8)
+    assert np.allclose(sig, np.linalg.norm(Bo, axis=0), rtol=1e-6, atol=0)
+    P, Po = B @ A, Bo @ Ao
+    assert np.abs(P - Po).max() <= 1e-5 * np.abs(Po).max(), np.abs(P - Po).max() / np.abs(Po).max()
+    # on the calibration activations themselves the two compensations act alike
+    assert np.abs(P @ Xt - Po @ Xt).max() <= 1e-6 * np.abs(Po @ Xt).max()
+
+
 def test_identity_gram_reduces_to_plain_svd(gpu):
     """Orthonormal rows of X~ make the projection trivial (Sec. 2, Eq. 2): B'A is the truncated SVD of dW."""
     from oracle import calibrate
