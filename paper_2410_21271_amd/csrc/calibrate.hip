@@ -436,7 +436,8 @@ __global__ void gather_rows_kernel(const double* __restrict__ src, int L, const 
     if (i >= (size_t)r * L) return;
     const int row = (int)(i / L), k = (int)(i % L);
     const double s = sigma[row];
-    const double f = power == 0 ? 1.0 : (power == -1 ? 1.0 / s : 1.0 / (s * s));
+    // a vanishing singular value (error of rank below r, or no error at all) gives a zero component, not 0/0
+    const double f = power == 0 ? 1.0 : (s > 0.0 ? (power == -1 ? 1.0 / s : 1.0 / (s * s)) : 0.0);
     dst[i] = src[(size_t)idx[row] * L + k] * f;
 }
 

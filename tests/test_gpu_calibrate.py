@@ -116,6 +116,26 @@ def test_planted_rank_r_error_is_recovered_and_served(gpu):
     assert err <= 2e-3, err
 
 
+@pytest.mark.parametrize("d_in,d_out", [(128, 64), (128, 160)])
+def test_error_of_rank_below_r(gpu, d_in, d_out):
+    """No compression error at all gives B'A = 0 with finite factors; an error of rank 2 asked for at rank 8
+    is returned exactly, the six spare components being zero."""
+    import synth
+    W, W_hat, _ = _inputs(7400 + d_out, d_in, d_out, 16)
+    Xt = synth.draw_calibration(7401, d_in, 300)
+    B, A, sig = _run(gpu, W_hat, W_hat, Xt, 8)
+    assert np.all(np.isfinite(B)) and np.all(np.isfinite(A)) and np.all(sig == 0)
+    assert np.all(B @ A == 0)
+    rng = np.random.default_rng(7402)
+    low = (rng.standard_normal((d_out, 2)) @ rng.standard_normal((2, d_in)) * 0.01)
+    W2 = (W_hat + low).astype(np.float32)
+    dW = W2.astype(np.float64) - W_hat
+    B, A, sig = _run(gpu, W2, W_hat, Xt, 8)
+    assert np.all(np.isfinite(B)) and np.all(np.isfinite(A))
+    assert np.abs(B @ A - dW).max() <= 1e-5 * np.abs(dW).max()          # dW is rank 2 up to the fp32 rounding of W2
+    assert sig[1] > 0 and np.all(sig[2:] <= 1e-5 * sig[0])
+
+
 def test_fewer_tokens_than_channels(gpu):
     """Rank-deficient Gram matrix (tokens < d_in): its null space gets the floored eigenvalue on both sides
     (the floor is isotropic there, so the basis chosen inside the null space does not matter).  The inverse
