@@ -64,7 +64,9 @@ for _n in ("llama3-8b-layer-decode-w3g128-r128fp16-M1", "llama3-8b-layer-decode-
            "llama3-8b-layer-prefill-w4g128-bare-M2048", "llama3-70b-layer-decode-w3g128-r128fp16-M1",
            "llama3-70b-layer-decode-w3g128-bare-M1", "llama3-8b-layer-decode-w2g128-r128fp16-M1",
            "llama3-8b-layer-decode-w2g128-bare-M1", "llama3-8b-layer-prefill-w2g128-r256fp16-M2048",
-           "llama3-8b-layer-decode-w4g128-r128q3-M1"):
+           "llama3-8b-layer-decode-w4g128-r128q3-M1", "llama3-8b-layer-decode-w4g128-r128fp16-M16",
+           "llama3-8b-layer-decode-w4g128-r128q4-M8", "llama3-8b-layer-decode-w4g128-bare-M8",
+           "llama3-8b-layer-decode-w4g128-r128fp16-M64"):
     WORKLOADS[_n + "-grouped"] = dict(WORKLOADS[_n], grouped=True)
 GROUPS = (("q", "k", "v"), ("o",), ("gate", "up"), ("down",))
 for _r in (64, 256, 512):

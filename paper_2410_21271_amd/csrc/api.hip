@@ -377,6 +377,47 @@ int eora_linear_q_group(const void* x, const eora_q_member* members, int n_membe
         return launch_group(x, members, n_members, M, d_in, r, w_bits, group, fa, fe, nw, nq, workspace, (hipStream_t)stream);
     if (prefill_fits(M, r, ab_bits) && workspace_bytes >= eora_workspace_bytes_group(M, d_in, r, n_members))
         return launch_prefill_group(x, members, n_members, M, d_in, r, w_bits, group, workspace, (hipStream_t)stream);
+    if (n_members > 1 && M > 4 && M < PREFILL_MIN_TOKENS) {
+        // 5 .. 127 tokens: the members' workgroups in one launch of the kernel that shares x through LDS, if together
+        // they have the rows it wants.  k-ranges: the members' partials and flags share the regions of one call.
+        int d_outs[MAX_GROUP];
+        for (int m = 0; m < n_members; ++m) d_outs[m] = members[m].d_out;
+        const int yblocks = (M + 15) / 16;
+        int kcn = 1;
+        for (int c = 2; c <= 4; ++c)
+            if ((d_in / 128) % c == 0 && n_members * yblocks * c <= 32) kcn = c;
+        const bool regions_ok = n_members * yblocks * kcn <= 32 && (r / 16) * kcn * n_members <= HDR_FLAGS_PER_BLOCK;
+        if (regions_ok && wide_q_group_fits(M, d_in, d_outs, n_members, r)) {
+            FusedArgs as[MAX_GROUP];
+            for (int m = 0; m < n_members; ++m) {
+                const eora_q_member& e = members[m];
+                FusedArgs a{};
+                a.x = (const _Float16*)x;
+                a.w = e.qweight;
+                a.w_scales = (const _Float16*)e.scales;
+                a.w_zeros = (const uint32_t*)e.qzeros;
+                a.A = e.A;
+                a.A_scales = (const _Float16*)e.A_scales;
+                a.B = e.B;
+                a.B_scales = (const _Float16*)e.B_scales;
+                a.y = (_Float16*)e.y;
+                a.hdr = (uint32_t*)workspace;
+                a.tpart = (float*)((char*)workspace + WS_PARTS);
+                a.tpair = (unsigned long long*)((char*)workspace + WS_PAIRS) + (size_t)m * yblocks * kcn * 16 * r;
+                a.M = M;
+                a.d_in = d_in;
+                a.d_out = e.d_out;
+                a.r = r;
+                a.group = group;
+                a.kcn = kcn;
+                a.spin_limit = g_spin_limit;
+                as[m] = a;
+            }
+            if (failed(launch_wide_q_group(as, n_members, backbone_format(w_bits), fa, fe, (hipStream_t)stream), "linear_q_group"))
+                return EORA_ERR_LAUNCH;
+            return EORA_OK;
+        }
+    }
     for (int m = 0; m < n_members; ++m) {               // other shapes (or a workspace sized for one member): one after the other
         const int rc = run_linear_q(x, members[m], M, d_in, r, w_bits, group, ab_bits, fa, fe, workspace, stream);
         if (rc != EORA_OK) return rc;

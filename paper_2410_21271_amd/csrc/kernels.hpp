@@ -54,6 +54,16 @@ hipError_t launch_fused(const FusedArgs& a, int fm, int fa, int fe, hipStream_t 
 // Kernel for 5 .. 127 tokens (wideq.hip): x shared through LDS by the wavefronts of a workgroup.
 bool wide_q_fits(int M, int d_in, int d_out, int r);
 hipError_t launch_wide_q(const FusedArgs& a, int fm, int fa, int fe, hipStream_t stream);
+// The same kernel for up to four linears that read the same x (same M, d_in, r, kcn, formats; own weights,
+// factors, y, d_out, tpair region): the members' workgroups follow one another in one launch.
+struct WideGroupArgs {
+    FusedArgs m[4];
+    int first[4];             // first workgroup of member i
+    int flag0[4];             // first flag of member i inside a token block's flags
+    int n;
+};
+bool wide_q_group_fits(int M, int d_in, const int* d_out, int n, int r);
+hipError_t launch_wide_q_group(const FusedArgs* members, int n, int fm, int fa, int fe, hipStream_t stream);
 
 // Decode kernel for 1..4 tokens (small.hip).  One launch serves up to MAX_GROUP linears that read the
 // same x (the q/k/v or the gate/up projections of a decoder layer): same d_in, rank and formats,

@@ -35,8 +35,16 @@ namespace eora {
 
 
 template <int FM, int FA, int FE, int NWR, int NWK, int TB>
-__global__ __launch_bounds__(NWR * NWK * 64, 4) void wide_q_kernel(FusedArgs a)
+__global__ __launch_bounds__(NWR * NWK * 64, 4) void wide_q_kernel(WideGroupArgs grp)
 {
+    // the member this workgroup works for (uniform): members' workgroups follow one another, each member's
+    // producers before its consumers, so a waiting workgroup's producers always have lower indices
+    int mem = 0;
+#pragma unroll
+    for (int i = 1; i < 4; ++i)
+        if (i < grp.n && (int)blockIdx.x >= grp.first[i]) mem = i;
+    const FusedArgs& a = grp.m[mem];
+    const int flag0 = grp.flag0[mem];
     constexpr int NW = NWR * NWK;
     constexpr bool LOWRANK = FA != S_NONE;
     constexpr int SLOT = TB * 4096;                       // bytes: 16 TB tokens x 128 columns
@@ -52,7 +60,7 @@ __global__ __launch_bounds__(NWR * NWK * 64, 4) void wide_q_kernel(FusedArgs a)
     const int yblocks = (a.M + 15) / 16;
     const int units = LOWRANK ? (a.r / 16) * a.kcn : 0;
     const int nprod = units * yblocks;
-    const int bid = blockIdx.x;
+    const int gbid = blockIdx.x, bid = gbid - grp.first[mem];
 
     CheckIn ci{0u, 0u, 0u};
     if constexpr (LOWRANK) {
@@ -72,7 +80,7 @@ __global__ __launch_bounds__(NWR * NWK * 64, 4) void wide_q_kernel(FusedArgs a)
             const f4 part = run_factor_a_eager<FA, NW>(fa, rho, kc * tpc, (kc + 1) * tpc, wave, lane,
                                                        a.x + (size_t)m_blk * a.d_in, a.d_in, n, n < mt);
             if (tid == 0) {
-                check_in_issue(ci, a.hdr, bid);
+                check_in_issue(ci, a.hdr, gbid);
                 s_epoch = ci.epoch;
             }
             WTL_STAMP(1);
@@ -96,7 +104,7 @@ __global__ __launch_bounds__(NWR * NWK * 64, 4) void wide_q_kernel(FusedArgs a)
                                            __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 WTL_STAMP(2);
                 if (lane == 0) {
-                    __hip_atomic_store(&a.hdr[HDR_FLAGS0 + HDR_FLAGS_PER_BLOCK * yb + u], s_epoch + 1, __ATOMIC_RELAXED,
+                    __hip_atomic_store(&a.hdr[HDR_FLAGS0 + HDR_FLAGS_PER_BLOCK * yb + flag0 + u], s_epoch + 1, __ATOMIC_RELAXED,
                                        __HIP_MEMORY_SCOPE_AGENT);
                     check_in_finish(ci, a.hdr, gridDim.x);
                 }
@@ -170,7 +178,7 @@ __global__ __launch_bounds__(NWR * NWK * 64, 4) void wide_q_kernel(FusedArgs a)
     if constexpr (LOWRANK) load_ftile<FE>(bpre, fb, R, wk < fb.ntk ? wk : 0, lane);
     if constexpr (LOWRANK) {
         if (tid == 0) {
-            check_in_issue(ci, a.hdr, bid);
+            check_in_issue(ci, a.hdr, gbid);
             s_epoch = ci.epoch;
         }
     }
@@ -196,7 +204,7 @@ __global__ __launch_bounds__(NWR * NWK * 64, 4) void wide_q_kernel(FusedArgs a)
     for (int qi = 0; qi < NQ; qi += 2) {
         if constexpr (LOWRANK && TB == 1) {
             if (wave == 0 && qi + 2 >= NQ)
-                early = ld_relaxed(a.hdr + HDR_FLAGS0 + HDR_FLAGS_PER_BLOCK * tg + (lane < units ? lane : units - 1));
+                early = ld_relaxed(a.hdr + HDR_FLAGS0 + HDR_FLAGS_PER_BLOCK * tg + flag0 + (lane < units ? lane : units - 1));
         }
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
@@ -255,7 +263,7 @@ __global__ __launch_bounds__(NWR * NWK * 64, 4) void wide_q_kernel(FusedArgs a)
             for (int tb = 0; tb < TB; ++tb) {
                 const int yb = tg * TB + tb;
                 if (yb >= yblocks || !ok || seen) continue;
-                const uint32_t* flags = a.hdr + HDR_FLAGS0 + HDR_FLAGS_PER_BLOCK * yb;
+                const uint32_t* flags = a.hdr + HDR_FLAGS0 + HDR_FLAGS_PER_BLOCK * yb + flag0;
                 bool up = false;
                 for (int spins = 0; spins <= a.spin_limit; ++spins) {
                     bool all = true;
@@ -427,53 +435,92 @@ bool wide_q_fits(int M, int d_in, int d_out, int r)
     return r <= 512 && pick_wide(M, d_in, d_out, r, &c);
 }
 
+template <int NWR, int TB>
+static int wide_blocks(const FusedArgs& a, bool lowrank)
+{
+    const int yblocks = (a.M + 15) / 16;
+    const int nprod = lowrank ? (a.r / 16) * a.kcn * yblocks : 0;
+    const int nrg = (a.d_out / 16 + NWR - 1) / NWR;
+    return nrg * ((yblocks + TB - 1) / TB) + nprod;
+}
+
 template <int FM, int FA, int FE, int NWR, int NWK, int TB>
-static hipError_t launch_wide_one(const FusedArgs& a, hipStream_t stream)
+static hipError_t launch_wide_one(const FusedArgs* members, int n, hipStream_t stream)
 {
     auto kern = wide_q_kernel<FM, FA, FE, NWR, NWK, TB>;
+    const FusedArgs& a = members[0];
     const size_t xb = (size_t)NWK * 2 * TB * 4096, tb = (size_t)16 * a.r * 4;
     const size_t lds = xb > tb ? xb : tb;
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    const int yblocks = (a.M + 15) / 16;
-    const int nprod = (FA != S_NONE) ? (a.r / 16) * a.kcn * yblocks : 0;
-    const int nrg = (a.d_out / 16 + NWR - 1) / NWR;
-    hipLaunchKernelGGL(kern, dim3(nrg * ((yblocks + TB - 1) / TB) + nprod), dim3(NWR * NWK * 64), lds, stream, a);
+    WideGroupArgs g{};
+    g.n = n;
+    int total = 0;
+    const int units = (FA != S_NONE) ? (a.r / 16) * a.kcn : 0;
+    for (int i = 0; i < 4; ++i) {
+        g.m[i] = members[i < n ? i : 0];
+        g.first[i] = total;
+        g.flag0[i] = (i < n ? i : 0) * units;
+        if (i < n) total += wide_blocks<NWR, TB>(members[i], FA != S_NONE);
+    }
+    hipLaunchKernelGGL(kern, dim3(total), dim3(NWR * NWK * 64), lds, stream, g);
     return hipGetLastError();
 }
 
+// one configuration for all members: chosen for the rows of all of them together
+static bool pick_wide_group(const FusedArgs* members, int n, WideCfg* c)
+{
+    int rows = 0;
+    for (int i = 0; i < n; ++i) rows += members[i].d_out;
+    return pick_wide(members[0].M, members[0].d_in, rows, members[0].r, c);
+}
+
 template <int FM, int FA, int FE>
-static hipError_t launch_wide_cfg(const FusedArgs& a, hipStream_t stream)
+static hipError_t launch_wide_cfg(const FusedArgs* members, int n, hipStream_t stream)
 {
     WideCfg c;
-    if (!pick_wide(a.M, a.d_in, a.d_out, a.r, &c)) return hipErrorInvalidValue;
-    if (c.nwr == 4) return launch_wide_one<FM, FA, FE, 4, 2, 1>(a, stream);
-    if (c.nwr == 2) return launch_wide_one<FM, FA, FE, 2, 4, 1>(a, stream);
-    if (c.nwk == 8) return launch_wide_one<FM, FA, FE, 1, 8, 1>(a, stream);
-    return launch_wide_one<FM, FA, FE, 1, 4, 1>(a, stream);
+    if (!pick_wide_group(members, n, &c)) return hipErrorInvalidValue;
+    if (c.nwr == 4) return launch_wide_one<FM, FA, FE, 4, 2, 1>(members, n, stream);
+    if (c.nwr == 2) return launch_wide_one<FM, FA, FE, 2, 4, 1>(members, n, stream);
+    if (c.nwk == 8) return launch_wide_one<FM, FA, FE, 1, 8, 1>(members, n, stream);
+    return launch_wide_one<FM, FA, FE, 1, 4, 1>(members, n, stream);
 }
 
 template <int FM>
-static hipError_t launch_wide_ab(const FusedArgs& a, int fa, int fe, hipStream_t stream)
+static hipError_t launch_wide_ab(const FusedArgs* members, int n, int fa, int fe, hipStream_t stream)
 {
-    if (fe == S_NONE) return launch_wide_cfg<FM, S_NONE, S_NONE>(a, stream);
-    if (fa == S_F16 && fe == S_F16) return launch_wide_cfg<FM, S_F16, S_F16>(a, stream);
-    if (fa == S_Q4S128 && fe == S_Q4S128) return launch_wide_cfg<FM, S_Q4S128, S_Q4S128>(a, stream);
-    if (fa == S_Q4S128 && fe == S_Q4S64) return launch_wide_cfg<FM, S_Q4S128, S_Q4S64>(a, stream);
-    if (fa == S_Q3S128 && fe == S_Q3S128) return launch_wide_cfg<FM, S_Q3S128, S_Q3S128>(a, stream);
+    if (fe == S_NONE) return launch_wide_cfg<FM, S_NONE, S_NONE>(members, n, stream);
+    if (fa == S_F16 && fe == S_F16) return launch_wide_cfg<FM, S_F16, S_F16>(members, n, stream);
+    if (fa == S_Q4S128 && fe == S_Q4S128) return launch_wide_cfg<FM, S_Q4S128, S_Q4S128>(members, n, stream);
+    if (fa == S_Q4S128 && fe == S_Q4S64) return launch_wide_cfg<FM, S_Q4S128, S_Q4S64>(members, n, stream);
+    if (fa == S_Q3S128 && fe == S_Q3S128) return launch_wide_cfg<FM, S_Q3S128, S_Q3S128>(members, n, stream);
     return hipErrorInvalidValue;
+}
+
+hipError_t launch_wide_q_group(const FusedArgs* members, int n, int fm, int fa, int fe, hipStream_t stream)
+{
+    if (n < 1 || n > 4) return hipErrorInvalidValue;
+    switch (fm) {
+        case S_Q4: return launch_wide_ab<S_Q4>(members, n, fa, fe, stream);
+        case S_Q3: return launch_wide_ab<S_Q3>(members, n, fa, fe, stream);
+        case S_Q2: return launch_wide_ab<S_Q2>(members, n, fa, fe, stream);
+        default: return hipErrorInvalidValue;
+    }
 }
 
 hipError_t launch_wide_q(const FusedArgs& a, int fm, int fa, int fe, hipStream_t stream)
 {
-    switch (fm) {
-        case S_Q4: return launch_wide_ab<S_Q4>(a, fa, fe, stream);
-        case S_Q3: return launch_wide_ab<S_Q3>(a, fa, fe, stream);
-        case S_Q2: return launch_wide_ab<S_Q2>(a, fa, fe, stream);
-        default: return hipErrorInvalidValue;
-    }
+    return launch_wide_q_group(&a, 1, fm, fa, fe, stream);
+}
+
+bool wide_q_group_fits(int M, int d_in, const int* d_out, int n, int r)
+{
+    int rows = 0;
+    for (int i = 0; i < n; ++i) rows += d_out[i];
+    WideCfg c;
+    return n >= 1 && n <= 4 && r <= 512 && pick_wide(M, d_in, rows, r, &c);
 }
 
 }  // namespace eora

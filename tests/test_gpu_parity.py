@@ -147,6 +147,27 @@ def test_group_of_layers_sharing_x(gpu, w_bits, ab_bits, r, M, d_in, d_outs):
             assert np.array_equal(y, run_linear_q(c, x=x))
 
 
+@pytest.mark.parametrize("w_bits,ab_bits,r,M,d_in,d_outs", [
+    (4, 16, 128, 16, 4096, (4096, 1024, 1024)),     # query / key / value at sixteen tokens
+    (3, 4, 64, 37, 2048, (2048, 512)),              # three token blocks (ragged), 4-bit factors of rank 64
+    (4, 16, 128, 64, 4096, (14336, 14336)),         # gate / up at 64 tokens
+    (2, 16, 0, 9, 2048, (1024, 1024, 1024, 1040)),  # four members, bare, a ragged last row group
+    (4, 3, 128, 100, 2048, (4096, 512)),            # seven token blocks: the members' partials share the scratch
+])
+def test_group_of_layers_sharing_x_mid_token_counts(gpu, w_bits, ab_bits, r, M, d_in, d_outs):
+    """5 .. 127 tokens: the members' workgroups run in one launch (the split of the sums may differ from a
+    separate call's, so members are compared with the oracle, and two runs with each other)."""
+    from tests.cases import QCase
+    from tests.gpu_util import run_linear_q_group
+    cases = [QCase(600 + 7 * i + d_in + M, d_in, d, M, r, w_bits, ab_bits=ab_bits, packer=gpu) for i, d in enumerate(d_outs)]
+    x = cases[0].x
+    ys = run_linear_q_group(cases, x)
+    again = run_linear_q_group(cases, x)
+    for c, y, y2 in zip(cases, ys, again):
+        _check(y, c.oracle_y(x=x))
+        assert np.array_equal(y, y2)
+
+
 def test_workspace_is_reusable_without_clearing(gpu):
     """Nothing in the workspace is reset between calls: flags are compared with an epoch that each
     low-rank launch advances by one, so one workspace serves any number of calls of any shapes."""
