@@ -178,11 +178,13 @@ int eora_linear_q(const void* x, const void* qweight, const void* scales, const 
  * gate / up projections, of a decoder layer (the paper compensates every linear of the model the
  * same way, Sec. 3; which of them share an input is the transformer's structure).  Member m is an
  * eora_linear_q layer of its own (own weights, factors, output and d_out); M, d_in, r, w_bits,
- * group and ab_bits are common.  Results are bit-identical to n_members separate eora_linear_q
- * calls.  For one to four tokens and group == 128 this is one launch, which pays the launch and
- * the hand-over of x.A^T once; for M >= 128 (fp16 factors, r % 128 == 0, or r == 0) the members'
- * rows form one GEMM, which keeps narrow members (d_out = 1024) from leaving most of the chip
- * idle; other shapes run the members one after the other.
+ * group and ab_bits are common.  For one to four tokens and group == 128 this is one launch, which
+ * pays the launch and the hand-over of x.A^T once, with results bit-identical to n_members separate
+ * eora_linear_q calls.  For 5 .. 127 tokens it is one launch too when the members together have enough
+ * rows to fill the chip, and for M >= 128 (fp16 factors, r % 128 == 0, or r == 0) the members' rows
+ * form one GEMM, which keeps narrow members (d_out = 1024) from leaving most of the chip idle; in
+ * these two cases sums may be split differently than in a separate call (results agree to rounding,
+ * and are the same from run to run).  Other shapes run the members one after the other.
  * members: HOST array (read during the call only) of 1..4 entries; pointers inside are DEVICE
  * pointers with the meaning and constraints of the eora_linear_q arguments of the same name.
  * workspace: at least the largest eora_workspace_bytes(M, d_in, d_out_m, r); see
