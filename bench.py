@@ -330,8 +330,13 @@ def calibration_main(args):
     per_rotation = 8.0 * rows * ((1 if rows == 2 else 2) * d_in + 2 * d_in)
     bytes_total = rounds * 8.0 * d_in * d_in + st["eig_rotations"] * per_rotation
     us_round = 1e3 * st["eig_ms"] / rounds
+    traffic = None                                    # HBM bytes per round from the committed counter runs
+    tpath = os.path.join(ROOT, "profiles", "factors_traffic.json")
+    if os.path.exists(tpath):
+        with open(tpath) as f:
+            traffic = json.load(f).get(args.workload)
     roofline = dict(bound="hbm", achieved=round(bytes_total / rounds / us_round / 1e3, 1), peak=HBM_PEAK_GBS, unit="GB/s",
-                    frac=round(bytes_total / rounds / us_round / 1e3 / HBM_PEAK_GBS, 4), traffic=None,
+                    frac=round(bytes_total / rounds / us_round / 1e3 / HBM_PEAK_GBS, 4), traffic=traffic,
                     kernel="Jacobi round of the eigendecomposition (%d rows of length %d per workgroup, with eigenvector rows)" % (rows, d_in),
                     bytes_per_launch=int(bytes_total / rounds), us_per_launch=round(us_round, 3), launches=rounds)
     out = dict(metric="seconds for Algorithm 1 steps 1-6 of one %d x %d linear (rank %d, %d calibration tokens)" % (d_out, d_in, r, n),
