@@ -170,3 +170,14 @@ def test_linear_q_multi_validation_codes():
     assert call(ab_bits=4, r=64, As=good, Bs=good) == -2 and call(ab_bits=4, r=128, n=2) == -1
     assert call(w_bits=5) == -3 and call(ws=null) == -5 and call(ws_bytes=16) == -5
     assert call(M=0) == 0
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU's share; asking for more ends with a message and a non-zero status
+    before anything touches a GPU."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    p = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert p.returncode != 0 and "not supported" in p.stderr and p.stdout.strip() == ""
