@@ -40,6 +40,33 @@ def eora_factors(W, W_hat, Xt, r, eig_floor=1e-12):
     return Bp, A
 
 
+def balance_factors(Bp, A):
+    """Rescale component i of the pair by s_i = sqrt(|B'_i| / |A_i|): (B'_i / s_i, s_i A_i).
+
+    Any invertible r x r matrix between the factors leaves B'A, and with it the compensated
+    layer of Sec. 3, unchanged; this diagonal one gives both factors of every component the norm
+    sqrt(|B'_i| |A_i|), so that neither leaves fp16's range when they are stored for inference
+    (B' = U' Sigma' carries the singular values, A the inverse square roots of Lambda).
+    A component with a zero factor is left as it is.
+    """
+    Bp = np.asarray(Bp, dtype=np.float64)
+    A = np.asarray(A, dtype=np.float64)
+    nb = np.sqrt(np.sum(Bp * Bp, axis=0))
+    na = np.sqrt(np.sum(A * A, axis=1))
+    ok = (nb > 0) & (na > 0)
+    s = np.where(ok, np.sqrt(np.where(ok, nb, 1.0) / np.where(ok, na, 1.0)), 1.0)
+    return Bp / s[None, :], A * s[:, None]
+
+
+def store_factors_f16(Bp, A, balance=True):
+    """The factors as inference reads them: (balanced,) rounded to fp16, in the F16 tile layout.
+    Returns (A_tiles, B_tiles)."""
+    from . import layout
+    if balance:
+        Bp, A = balance_factors(Bp, A)
+    return layout.pack_f16(np.asarray(A).astype(np.float16)), layout.pack_f16(np.asarray(Bp).astype(np.float16))
+
+
 def plain_svd_factors(W, W_hat, r):
     """Rank-r SVD of the raw error (Sec. 2, Eq. 2): the case Xt Xt^T = I of the above."""
     dW = np.asarray(W, dtype=np.float64) - np.asarray(W_hat, dtype=np.float64)

@@ -88,3 +88,31 @@ def test_full_rank_compensation_is_exact():
     W, W_hat, Xt = _setup(d=12, k=20, seed=6)
     Bp, A = calibrate.eora_factors(W, W_hat, Xt, 12)
     assert np.allclose(Bp @ A, W - W_hat, atol=1e-9)
+
+
+def test_balanced_factors_keep_the_product_and_share_the_norm():
+    rng = np.random.default_rng(30)
+    B = rng.standard_normal((24, 6)) * np.array([1e3, 1.0, 1e-3, 5.0, 0.0, 2.0])[None, :]
+    A = rng.standard_normal((6, 40)) * np.array([1e-2, 1.0, 1e4, 0.1, 1.0, 0.0])[:, None]
+    Bb, Ab = calibrate.balance_factors(B, A)
+    assert np.abs(Bb @ Ab - B @ A).max() <= 1e-13 * np.abs(B @ A).max()
+    nb, na = np.linalg.norm(Bb, axis=0), np.linalg.norm(Ab, axis=1)
+    want = np.sqrt(np.linalg.norm(B, axis=0) * np.linalg.norm(A, axis=1))
+    live = [0, 1, 2, 3]
+    assert np.allclose(nb[live], want[live], rtol=1e-13) and np.allclose(na[live], want[live], rtol=1e-13)
+    # a component with a zero factor is left alone
+    assert np.array_equal(Bb[:, 4:], B[:, 4:]) and np.array_equal(Ab[4:], A[4:])
+
+
+def test_stored_factors_are_the_fp16_rounding_in_tile_order():
+    from oracle import layout
+    rng = np.random.default_rng(31)
+    B, A = rng.standard_normal((32, 32)) * 50.0, rng.standard_normal((32, 64)) * 1e-3
+    At, Bt = calibrate.store_factors_f16(B, A, balance=False)
+    assert np.array_equal(layout.unpack_f16(At, 32, 64), A.astype(np.float16))
+    assert np.array_equal(layout.unpack_f16(Bt, 32, 32), B.astype(np.float16))
+    At, Bt = calibrate.store_factors_f16(B, A)
+    P = layout.unpack_f16(Bt, 32, 32).astype(np.float64) @ layout.unpack_f16(At, 32, 64).astype(np.float64)
+    assert np.abs(P - B @ A).max() <= 2e-3 * np.abs(B @ A).max()          # two fp16 roundings per product term
+    # without balancing the small factor would sit in fp16's subnormal range; with it both are near 0.2
+    assert np.abs(layout.unpack_f16(At, 32, 64)).max() > 0.05
