@@ -280,6 +280,18 @@ int eora_factors(const void* W_f32, const void* W_hat_f32, const void* Xt_f32,
                  void* B_f64, void* A_f64, void* sigma_f64,
                  void* workspace, size_t workspace_bytes, void* stream, double* stats);
 
+/* All pointers DEVICE, 16-byte aligned.  The factors of eora_factors() as the forward entry points read
+ * them (ab_bits == 16): rounded once to fp16 and written in the F16 tile layout, A_tiles r x d_in
+ * (2*r*d_in bytes), B_tiles d_out x r.  balance != 0 first rescales component i by
+ * s_i = sqrt(|B'_i| / |A_i|) (column i of B' divided by s_i, row i of A multiplied by it): B'A is
+ * unchanged and both factors of a component get the norm sqrt(|B'_i| |A_i|), which keeps them inside
+ * fp16's range whatever the singular values are (B' = U' Sigma' carries them, A the inverse square roots
+ * of Lambda; Alg. 1 steps 5 and 6).  scratch: r doubles (balance != 0 only).  Asynchronous on `stream`.
+ * Constraints: d_in % 32 == 0, d_out % 16 == 0, r % 32 == 0.
+ * Errors: EORA_ERR_NULL / SHAPE / ALIGN / WORKSPACE (scratch) / LAUNCH. */
+int eora_factors_store_f16(const void* B_f64, const void* A_f64, int d_in, int d_out, int r, int balance,
+                           void* A_tiles, void* B_tiles, void* scratch, size_t scratch_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -68,6 +68,7 @@ def _load():
         "eora_expand_sp24": (ci, [vp, vp, vp, ci, ci, vp]),
         "eora_expand_sp24q4": (ci, [vp, vp, vp, ci, ci, vp]),
         "eora_factors_workspace_bytes": (sz, [ci, ci, ci]),
+        "eora_factors_store_f16": (ci, [vp, vp, ci, ci, ci, ci, vp, vp, vp, sz, vp]),
         "eora_factors": (ci, [vp, vp, vp, ci, ci, ci, ci, ctypes.c_double, vp, vp, vp, vp, sz, vp, ctypes.POINTER(ctypes.c_double)]),
     }
     for name, (res, args) in sig.items():
@@ -84,7 +85,7 @@ EXPORTS = ["eora_status_string", "eora_qweight_bytes", "eora_qzeros_bytes", "eor
            "eora_pack_factor_f16", "eora_pack_factor_q4", "eora_pack_sp24", "eora_linear_q",
            "eora_linear_q_group", "eora_linear_sp24", "eora_unpack_q", "eora_dequant_q", "eora_expand_sp24",
            "eora_sp24q4_tiles_bytes", "eora_sp24q4_meta_bytes", "eora_pack_sp24q4", "eora_linear_sp24q4", "eora_expand_sp24q4",
-           "eora_factors_workspace_bytes", "eora_factors", "eora_linear_q_multi", "eora_pack_factor_q3"]
+           "eora_factors_workspace_bytes", "eora_factors", "eora_linear_q_multi", "eora_pack_factor_q3", "eora_factors_store_f16"]
 
 
 def status_string(status):
@@ -318,3 +319,9 @@ def factors(W_f32, W_hat_f32, Xt_f32, B_f64, A_f64, sigma_f64, n_tokens, d_in, d
     if stats:
         return dict(eig_sweeps=int(st[0]), eig_ms=st[1], eig_rotations=st[2], eig_rows=int(st[3]),
                     svd_sweeps=int(st[4]), svd_ms=st[5], svd_rotations=st[6], svd_rows=int(st[7]))
+
+
+def factors_store_f16(B_f64, A_f64, d_in, d_out, r, balance, A_tiles, B_tiles, scratch):
+    nbytes = 0 if scratch is None else scratch.numel() * scratch.element_size()
+    _check(lib.eora_factors_store_f16(_dp(B_f64), _dp(A_f64), d_in, d_out, r, int(bool(balance)), _dp(A_tiles), _dp(B_tiles),
+                                      _dp(scratch), nbytes, _stream()), "factors_store_f16")

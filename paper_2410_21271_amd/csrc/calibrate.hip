@@ -451,6 +451,51 @@ __global__ void gather_rows_transposed_kernel(const double* __restrict__ src, in
     dst[i] = src[(size_t)idx[c] * L + o];
 }
 
+// s[i] = sqrt(|B'_i| / |A_i|) for component i (column i of B: d_out x r, row i of A: r x d_in), 1 if either
+// vanishes; one workgroup of 256 per component
+__global__ __launch_bounds__(256) void balance_kernel(const double* __restrict__ B, const double* __restrict__ A, int d_in,
+                                                      int d_out, int r, double* __restrict__ s)
+{
+    const int i = blockIdx.x;
+    double nb = 0, na = 0;
+    for (int o = threadIdx.x; o < d_out; o += 256) nb += B[(size_t)o * r + i] * B[(size_t)o * r + i];
+    for (int k = threadIdx.x; k < d_in; k += 256) na += A[(size_t)i * d_in + k] * A[(size_t)i * d_in + k];
+    __shared__ double red[2][4];
+    nb = wave_sum(nb);
+    na = wave_sum(na);
+    if ((threadIdx.x & 63) == 0) {
+        red[0][threadIdx.x >> 6] = nb;
+        red[1][threadIdx.x >> 6] = na;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        nb = sqrt(red[0][0] + red[0][1] + red[0][2] + red[0][3]);
+        na = sqrt(red[1][0] + red[1][1] + red[1][2] + red[1][3]);
+        s[i] = (nb > 0.0 && na > 0.0) ? sqrt(nb / na) : 1.0;
+    }
+}
+
+// One thread per (tile, lane) of the F16 tile layout (tile = 16 rows x 32 columns, lane l = 16 j + n owns row n,
+// columns 8 j .. 8 j + 7): eight values of X (rows x K fp64 row-major), scaled, rounded once to fp16.
+// by_row: the scale of a value is s[row] (A: times s) or 1 / s[column] (B: divided by s); s == nullptr: 1.
+__global__ void store_f16_tiles_kernel(const double* __restrict__ X, int rows, int K, const double* __restrict__ s, int by_row,
+                                       _Float16* __restrict__ out)
+{
+    const size_t L = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (L >= (size_t)rows * K / 8) return;
+    const int ntk = K / 32;
+    const size_t tile = L / 64;
+    const int lane = (int)(L % 64);
+    const int R = (int)(tile / ntk), g = (int)(tile % ntk);
+    const int j = lane >> 4, n = lane & 15;
+    const int row = 16 * R + n, col0 = 32 * g + 8 * j;
+    for (int i = 0; i < 8; ++i) {
+        double v = X[(size_t)row * K + col0 + i];
+        if (s) v = by_row ? v * s[row] : v / s[col0 + i];
+        out[L * 8 + i] = (_Float16)v;
+    }
+}
+
 inline unsigned blocks(size_t n, int per = 256) { return (unsigned)((n + per - 1) / per); }
 
 template <typename TA, typename TB>
@@ -675,5 +720,29 @@ extern "C" int eora_factors(const void* W_f32, const void* W_hat_f32, const void
     if (sigma_f64) hipLaunchKernelGGL(copy_kernel, dim3(blocks(r)), dim3(256), 0, st, sigma, (double*)sigma_f64, (size_t)r);
     if (hipGetLastError() != hipSuccess) return EORA_ERR_LAUNCH;
     if (hipStreamSynchronize(st) != hipSuccess) return EORA_ERR_LAUNCH;
+    return EORA_OK;
+}
+
+extern "C" int eora_factors_store_f16(const void* B_f64, const void* A_f64, int d_in, int d_out, int r, int balance,
+                                      void* A_tiles, void* B_tiles, void* scratch, size_t scratch_bytes, void* stream)
+{
+    if (!B_f64 || !A_f64 || !A_tiles || !B_tiles) return EORA_ERR_NULL;
+    if (d_in <= 0 || d_out <= 0 || r <= 0 || d_in % 32 || d_out % 16 || r % 32) return EORA_ERR_SHAPE;
+    if ((reinterpret_cast<uintptr_t>(A_tiles) | reinterpret_cast<uintptr_t>(B_tiles) | reinterpret_cast<uintptr_t>(B_f64) |
+         reinterpret_cast<uintptr_t>(A_f64)) & 15u)
+        return EORA_ERR_ALIGN;
+    double* s = nullptr;
+    if (balance) {
+        if (!scratch || scratch_bytes < sizeof(double) * (size_t)r) return EORA_ERR_WORKSPACE;
+        if (reinterpret_cast<uintptr_t>(scratch) & 15u) return EORA_ERR_ALIGN;
+        s = (double*)scratch;
+    }
+    hipStream_t st = (hipStream_t)stream;
+    if (s) hipLaunchKernelGGL(balance_kernel, dim3(r), dim3(256), 0, st, (const double*)B_f64, (const double*)A_f64, d_in, d_out, r, s);
+    hipLaunchKernelGGL(store_f16_tiles_kernel, dim3(blocks((size_t)r * d_in / 8)), dim3(256), 0, st, (const double*)A_f64, r, d_in,
+                       (const double*)s, 1, (_Float16*)A_tiles);
+    hipLaunchKernelGGL(store_f16_tiles_kernel, dim3(blocks((size_t)d_out * r / 8)), dim3(256), 0, st, (const double*)B_f64, d_out, r,
+                       (const double*)s, 0, (_Float16*)B_tiles);
+    if (hipGetLastError() != hipSuccess) return EORA_ERR_LAUNCH;
     return EORA_OK;
 }

@@ -181,3 +181,16 @@ def test_bench_refuses_more_than_one_gpu():
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     p = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
     assert p.returncode != 0 and "not supported" in p.stderr and p.stdout.strip() == ""
+
+
+def test_factors_store_f16_validation_codes():
+    L = eora.lib
+    good, odd, null = ctypes.c_void_p(0x1000), ctypes.c_void_p(0x1008), ctypes.c_void_p(0)
+
+    def call(B=good, A=good, d_in=256, d_out=32, r=32, balance=1, At=good, Bt=good, scratch=good, nbytes=8 * 32):
+        return L.eora_factors_store_f16(B, A, d_in, d_out, r, balance, At, Bt, scratch, nbytes, null)
+
+    assert call(B=null) == -1 and call(At=null) == -1
+    assert call(d_in=250) == -2 and call(d_out=24) == -2 and call(r=16) == -2 and call(r=0) == -2
+    assert call(At=odd) == -4 and call(scratch=odd) == -4
+    assert call(scratch=null) == -5 and call(nbytes=8 * 31) == -5

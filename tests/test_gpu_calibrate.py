@@ -136,6 +136,71 @@ def test_error_of_rank_below_r(gpu, d_in, d_out):
     assert sig[1] > 0 and np.all(sig[2:] <= 1e-5 * sig[0])
 
 
+@pytest.mark.parametrize("balance", [False, True])
+def test_store_f16_matches_oracle_tiles(gpu, balance):
+    """fp64 factors -> fp16 tiles on the GPU against the oracle's rounding and layout.  Without balancing the
+    result is one rounding of the same number: bit-exact.  With it the scale s_i comes from sums taken in a
+    different order, so a value that sits within 1e-15 of a rounding boundary may fall on the other side: at
+    most one fp16 step, on a handful of entries."""
+    import torch
+    from oracle import calibrate, layout
+    rng = np.random.default_rng(7500)
+    d_in, d_out, r = 256, 80, 64
+    B = rng.standard_normal((d_out, r)) * np.exp(rng.uniform(-6, 6, r))[None, :]
+    A = rng.standard_normal((r, d_in)) * np.exp(rng.uniform(-6, 6, r))[:, None]
+    Bd, Ad = torch.from_numpy(B).cuda(), torch.from_numpy(A).cuda()
+    At = torch.full((r * d_in,), float("nan"), dtype=torch.float16, device="cuda")
+    Bt = torch.full((d_out * r,), float("nan"), dtype=torch.float16, device="cuda")
+    scratch = torch.empty(r, dtype=torch.float64, device="cuda")
+    gpu.factors_store_f16(Bd, Ad, d_in, d_out, r, balance, At, Bt, scratch if balance else None)
+    torch.cuda.synchronize()
+    oA, oB = calibrate.store_factors_f16(B, A, balance=balance)
+    for got, want, rows, K in ((At.cpu().numpy(), oA, r, d_in), (Bt.cpu().numpy(), oB, d_out, r)):
+        g, w = layout.unpack_f16(got, rows, K), layout.unpack_f16(want, rows, K)
+        if not balance:
+            assert np.array_equal(got.view(np.uint16), want.view(np.uint16))
+        else:
+            diff = np.abs(g.view(np.int16).astype(np.int32) - w.view(np.int16).astype(np.int32))
+            assert diff.max() <= 1 and np.count_nonzero(diff) <= 1e-3 * diff.size
+
+
+def test_calibrate_store_serve_on_the_gpu(gpu):
+    """Steps 1-7 without leaving the device: dequantise, eora_factors, eora_factors_store_f16, eora_linear_q.
+    The error has rank r, so the served layer reproduces x.W^T up to the fp16 roundings."""
+    import torch
+    import synth
+    from oracle import linear
+    from tests.cases import QCase
+    from tests.gpu_util import dev
+    d_in, d_out, r, M = 512, 256, 64, 7
+    c = QCase(7600, d_in, d_out, M, 0, 3, 128, packer=gpu)
+    qw, sc, qz = dev(c.qw), dev(c.sc), dev(c.qz)
+    W_hat = torch.empty((d_out, d_in), dtype=torch.float32, device="cuda")
+    gpu.dequant_q(qw, sc, qz, W_hat, d_in, d_out, 3, 128)
+    rng = np.random.default_rng(7601)
+    low = (rng.standard_normal((d_out, r)) @ rng.standard_normal((r, d_in)) * 0.002).astype(np.float32)
+    W = W_hat + torch.from_numpy(low).cuda()
+    Xt = torch.from_numpy(synth.draw_calibration(7602, d_in, 1100)).cuda()
+    B = torch.empty((d_out, r), dtype=torch.float64, device="cuda")
+    A = torch.empty((r, d_in), dtype=torch.float64, device="cuda")
+    ws = torch.empty(gpu.factors_workspace_bytes(d_in, d_out, r), dtype=torch.uint8, device="cuda")
+    gpu.factors(W, W_hat, Xt, B, A, None, 1100, d_in, d_out, r, 1e-12, ws)
+    At = torch.empty(r * d_in, dtype=torch.float16, device="cuda")
+    Bt = torch.empty(d_out * r, dtype=torch.float16, device="cuda")
+    gpu.factors_store_f16(B, A, d_in, d_out, r, True, At, Bt, torch.empty(r, dtype=torch.float64, device="cuda"))
+    y = torch.full((M * d_out,), 777.0, dtype=torch.float16, device="cuda")
+    lws = gpu.new_workspace(M, d_in, d_out, r)
+    gpu.linear_q(dev(c.x), qw, sc, qz, At, Bt, None, None, y, M, d_in, d_out, r, 3, 128, 16, lws)
+    torch.cuda.synchronize()
+    assert gpu.workspace_error(lws) == 0
+    ref = c.x.astype(np.float64) @ W.cpu().numpy().astype(np.float64).T
+    err = linear.y_error(y.cpu().numpy().reshape(M, d_out), ref)
+    assert err <= 2e-3, err
+    # and without the compensation the compressed layer is far off
+    bare = linear.y_error(c.oracle_y(), ref)
+    assert bare > 20 * err
+
+
 def test_fewer_tokens_than_channels(gpu):
     """Rank-deficient Gram matrix (tokens < d_in): its null space gets the floored eigenvalue on both sides
     (the floor is isotropic there, so the basis chosen inside the null space does not matter).  The inverse
