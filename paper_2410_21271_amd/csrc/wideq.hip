@@ -34,17 +34,11 @@ namespace eora {
 #endif
 
 
+// gbid: index of the workgroup in the launch; bid: its index among its member's workgroups; flag0: the member's
+// first flag inside a token block's flags
 template <int FM, int FA, int FE, int NWR, int NWK, int TB>
-__global__ __launch_bounds__(NWR * NWK * 64, 4) void wide_q_kernel(WideGroupArgs grp)
+__device__ __forceinline__ void wide_q_body(const FusedArgs& a, const int gbid, const int bid, const int flag0)
 {
-    // the member this workgroup works for (uniform): members' workgroups follow one another, each member's
-    // producers before its consumers, so a waiting workgroup's producers always have lower indices
-    int mem = 0;
-#pragma unroll
-    for (int i = 1; i < 4; ++i)
-        if (i < grp.n && (int)blockIdx.x >= grp.first[i]) mem = i;
-    const FusedArgs& a = grp.m[mem];
-    const int flag0 = grp.flag0[mem];
     constexpr int NW = NWR * NWK;
     constexpr bool LOWRANK = FA != S_NONE;
     constexpr int SLOT = TB * 4096;                       // bytes: 16 TB tokens x 128 columns
@@ -60,7 +54,6 @@ __global__ __launch_bounds__(NWR * NWK * 64, 4) void wide_q_kernel(WideGroupArgs
     const int yblocks = (a.M + 15) / 16;
     const int units = LOWRANK ? (a.r / 16) * a.kcn : 0;
     const int nprod = units * yblocks;
-    const int gbid = blockIdx.x, bid = gbid - grp.first[mem];
 
     CheckIn ci{0u, 0u, 0u};
     if constexpr (LOWRANK) {
@@ -408,6 +401,27 @@ __global__ __launch_bounds__(NWR * NWK * 64, 4) void wide_q_kernel(WideGroupArgs
     }
 }
 
+// one linear: the arguments sit at fixed places of the kernel's argument block
+template <int FM, int FA, int FE, int NWR, int NWK, int TB>
+__global__ __launch_bounds__(NWR * NWK * 64, 4) void wide_q_kernel(FusedArgs a)
+{
+    wide_q_body<FM, FA, FE, NWR, NWK, TB>(a, blockIdx.x, blockIdx.x, 0);
+}
+
+// several linears that share x: each workgroup first finds the member it works for (uniform; one more dependent
+// scalar load at the start than the kernel above, which is why that one is kept).  The members' workgroups
+// follow one another, each member's producers before its consumers, so a waiting workgroup's producers always
+// have lower indices.
+template <int FM, int FA, int FE, int NWR, int NWK, int TB>
+__global__ __launch_bounds__(NWR * NWK * 64, 4) void wide_q_group_kernel(WideGroupArgs grp)
+{
+    int mem = 0;
+#pragma unroll
+    for (int i = 1; i < 4; ++i)
+        if (i < grp.n && (int)blockIdx.x >= grp.first[i]) mem = i;
+    wide_q_body<FM, FA, FE, NWR, NWK, TB>(grp.m[mem], blockIdx.x, (int)blockIdx.x - grp.first[mem], grp.flag0[mem]);
+}
+
 // ------------------------------------------------------------------------------------------------
 struct WideCfg { int nwr, nwk, tb; };
 
@@ -447,10 +461,19 @@ static int wide_blocks(const FusedArgs& a, bool lowrank)
 template <int FM, int FA, int FE, int NWR, int NWK, int TB>
 static hipError_t launch_wide_one(const FusedArgs* members, int n, hipStream_t stream)
 {
-    auto kern = wide_q_kernel<FM, FA, FE, NWR, NWK, TB>;
     const FusedArgs& a = members[0];
     const size_t xb = (size_t)NWK * 2 * TB * 4096, tb = (size_t)16 * a.r * 4;
     const size_t lds = xb > tb ? xb : tb;
+    if (n == 1) {
+        auto kern1 = wide_q_kernel<FM, FA, FE, NWR, NWK, TB>;
+        if (lds > 48 * 1024) {
+            hipError_t e = hipFuncSetAttribute((const void*)kern1, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+        }
+        hipLaunchKernelGGL(kern1, dim3(wide_blocks<NWR, TB>(a, FA != S_NONE)), dim3(NWR * NWK * 64), lds, stream, a);
+        return hipGetLastError();
+    }
+    auto kern = wide_q_group_kernel<FM, FA, FE, NWR, NWK, TB>;
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
