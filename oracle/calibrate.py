@@ -67,6 +67,45 @@ def store_factors_f16(Bp, A, balance=True):
     return layout.pack_f16(np.asarray(A).astype(np.float16)), layout.pack_f16(np.asarray(Bp).astype(np.float16))
 
 
+def quantize_factor(Mat, bits):
+    """Symmetric round-to-nearest quantisation of a factor to `bits` in {4, 3} (Sec. 4.5 and App. A.9
+    quantise the factors; the paper names no quantiser, this is the plain one): per row and per group of
+    min(128, K) columns, scale = fp16(max |v| / qpos) with qpos = 2^(bits-1) - 1 (1 where the group is all
+    zero), code = clip(rint(v / scale) + zp, 1, 2 zp - 1) with the implicit zero-point zp = 2^(bits-1).
+    Returns (codes uint8 rows x K, scales fp16 rows x K/KT); the value a code stands for is scale (code - zp)."""
+    Mat = np.asarray(Mat, dtype=np.float64)
+    rows, K = Mat.shape
+    KT = min(128, K)
+    zp = 1 << (bits - 1)
+    qpos = zp - 1
+    codes = np.empty((rows, K), dtype=np.uint8)
+    scales = np.empty((rows, K // KT), dtype=np.float16)
+    for g in range(K // KT):
+        blk = Mat[:, g * KT:(g + 1) * KT]
+        s16 = (np.max(np.abs(blk), axis=1) / qpos).astype(np.float16)
+        s16[s16 == 0] = np.float16(1.0)
+        q = np.rint(blk / s16.astype(np.float64)[:, None]) + zp
+        codes[:, g * KT:(g + 1) * KT] = np.clip(q, 1, 2 * zp - 1).astype(np.uint8)
+        scales[:, g] = s16
+    return codes, scales
+
+
+def store_factors_q(Bp, A, bits, balance=True):
+    """The factors quantised (quantize_factor) and packed as inference reads them.
+    Returns (A_q, A_scales, B_q, B_scales)."""
+    from . import layout
+    if balance:
+        Bp, A = balance_factors(Bp, A)
+    ca, sa = quantize_factor(A, bits)
+    cb, sb = quantize_factor(Bp, bits)
+    if bits == 4:
+        return (layout.pack_q4(ca, 128), layout.pack_scales(sa),
+                layout.pack_q4(cb, min(128, cb.shape[1])), layout.pack_scales(sb))
+    if bits == 3:
+        return layout.pack_q3(ca), layout.pack_scales(sa), layout.pack_q3(cb), layout.pack_scales(sb)
+    raise ValueError("bits must be 4 or 3")
+
+
 def plain_svd_factors(W, W_hat, r):
     """Rank-r SVD of the raw error (Sec. 2, Eq. 2): the case Xt Xt^T = I of the above."""
     dW = np.asarray(W, dtype=np.float64) - np.asarray(W_hat, dtype=np.float64)

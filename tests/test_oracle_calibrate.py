@@ -116,3 +116,40 @@ def test_stored_factors_are_the_fp16_rounding_in_tile_order():
     assert np.abs(P - B @ A).max() <= 2e-3 * np.abs(B @ A).max()          # two fp16 roundings per product term
     # without balancing the small factor would sit in fp16's subnormal range; with it both are near 0.2
     assert np.abs(layout.unpack_f16(At, 32, 64)).max() > 0.05
+
+
+def test_factor_quantiser_hand_values_and_error_bound():
+    # fp16(0.7 / 7) = 0.0999755859375: 0.7 -> +7 -> code 15; -0.35 -> -3.5009 -> -4 -> code 4; 0.1 -> +1 -> code 9
+    row = np.zeros((1, 128))
+    row[0, :3] = [0.7, -0.35, 0.1]
+    codes, scales = calibrate.quantize_factor(row, 4)
+    assert float(scales[0, 0]) == 0.0999755859375
+    assert list(codes[0, :4]) == [15, 4, 9, 8]
+    # 3 bits: fp16(0.7 / 3) = 1911 * 2^-13 = 0.2332763671875: 0.7 -> 3.0007 -> +3 -> code 7; -0.35 -> -1.5004 -> -2 -> code 2;
+    # 0.1 -> 0.43 -> 0 -> code 4
+    codes, scales = calibrate.quantize_factor(row, 3)
+    assert float(scales[0, 0]) == 0.2332763671875 and list(codes[0, :4]) == [7, 2, 4, 4]
+    # an all-zero group gets scale 1 and the zero-point everywhere
+    codes, scales = calibrate.quantize_factor(np.zeros((2, 256)), 4)
+    assert np.all(scales == 1) and np.all(codes == 8)
+    rng = np.random.default_rng(32)
+    for bits, zp in ((4, 8), (3, 4)):
+        M = rng.standard_normal((16, 256)) * np.exp(rng.uniform(-3, 3, (16, 1)))
+        codes, scales = calibrate.quantize_factor(M, bits)
+        assert codes.min() >= 1 and codes.max() <= 2 * zp - 1
+        back = (codes.astype(np.float64) - zp) * np.repeat(scales.astype(np.float64), 128, axis=1)
+        # half a step, plus the fp16 rounding of the scale on the largest magnitude (qpos steps of 2^-11 each)
+        assert np.all(np.abs(back - M) <= np.repeat(scales.astype(np.float64), 128, axis=1) * (0.5 + 0.004))
+
+
+def test_stored_quantised_factors_dequantise_to_the_quantiser_values():
+    from oracle import linear
+    rng = np.random.default_rng(33)
+    B, A = rng.standard_normal((32, 128)) * 3.0, rng.standard_normal((128, 256)) * 1e-2
+    for bits, deq in ((4, linear.dequant_factor_q4), (3, linear.dequant_factor_q3)):
+        Aq, As, Bq, Bs = calibrate.store_factors_q(B, A, bits, balance=False)
+        ca, sa = calibrate.quantize_factor(A, bits)
+        zp = 1 << (bits - 1)
+        want = (ca.astype(np.float64) - zp) * np.repeat(sa.astype(np.float64), 128, axis=1)
+        assert np.array_equal(deq(Aq, As, 128, 256), want)
+        assert deq(Bq, Bs, 32, 128).shape == (32, 128)
