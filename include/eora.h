@@ -292,6 +292,18 @@ int eora_factors(const void* W_f32, const void* W_hat_f32, const void* Xt_f32,
 int eora_factors_store_f16(const void* B_f64, const void* A_f64, int d_in, int d_out, int r, int balance,
                            void* A_tiles, void* B_tiles, void* scratch, size_t scratch_bytes, void* stream);
 
+/* The same hand-over with QUANTISED factors (Sec. 4.5, App. A.9), ab_bits in {4, 3}: symmetric
+ * round-to-nearest per row and group of min(128, K) columns of the contraction dimension,
+ * scale = fp16(max |v| / qpos), qpos = 7 (4-bit) or 3 (3-bit), 1 for an all-zero group;
+ * code = clip(rint(v / scale) + zp, 1, 2 zp - 1) with the implicit zero-point zp = 8 or 4.  Outputs in the
+ * Q4 / Q3 symmetric factor formats the forward entry points read with the same ab_bits: A_q r x d_in,
+ * A_scales r x d_in/128 fp16, B_q d_out x r, B_scales d_out x r/min(128, r) fp16.  balance, scratch as
+ * for eora_factors_store_f16.  Constraints: d_in % 128 == 0, d_out % 16 == 0, r % 128 == 0 (or r == 64
+ * with ab_bits 4).  Errors: EORA_ERR_NULL / UNSUPPORTED / SHAPE / ALIGN / WORKSPACE / LAUNCH. */
+int eora_factors_store_q(const void* B_f64, const void* A_f64, int d_in, int d_out, int r, int ab_bits, int balance,
+                         void* A_q, void* A_scales, void* B_q, void* B_scales,
+                         void* scratch, size_t scratch_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

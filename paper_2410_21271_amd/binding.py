@@ -69,6 +69,7 @@ def _load():
         "eora_expand_sp24q4": (ci, [vp, vp, vp, ci, ci, vp]),
         "eora_factors_workspace_bytes": (sz, [ci, ci, ci]),
         "eora_factors_store_f16": (ci, [vp, vp, ci, ci, ci, ci, vp, vp, vp, sz, vp]),
+        "eora_factors_store_q": (ci, [vp, vp, ci, ci, ci, ci, ci, vp, vp, vp, vp, vp, sz, vp]),
         "eora_factors": (ci, [vp, vp, vp, ci, ci, ci, ci, ctypes.c_double, vp, vp, vp, vp, sz, vp, ctypes.POINTER(ctypes.c_double)]),
     }
     for name, (res, args) in sig.items():
@@ -85,7 +86,7 @@ EXPORTS = ["eora_status_string", "eora_qweight_bytes", "eora_qzeros_bytes", "eor
            "eora_pack_factor_f16", "eora_pack_factor_q4", "eora_pack_sp24", "eora_linear_q",
            "eora_linear_q_group", "eora_linear_sp24", "eora_unpack_q", "eora_dequant_q", "eora_expand_sp24",
            "eora_sp24q4_tiles_bytes", "eora_sp24q4_meta_bytes", "eora_pack_sp24q4", "eora_linear_sp24q4", "eora_expand_sp24q4",
-           "eora_factors_workspace_bytes", "eora_factors", "eora_linear_q_multi", "eora_pack_factor_q3", "eora_factors_store_f16"]
+           "eora_factors_workspace_bytes", "eora_factors", "eora_linear_q_multi", "eora_pack_factor_q3", "eora_factors_store_f16", "eora_factors_store_q"]
 
 
 def status_string(status):
@@ -325,3 +326,9 @@ def factors_store_f16(B_f64, A_f64, d_in, d_out, r, balance, A_tiles, B_tiles, s
     nbytes = 0 if scratch is None else scratch.numel() * scratch.element_size()
     _check(lib.eora_factors_store_f16(_dp(B_f64), _dp(A_f64), d_in, d_out, r, int(bool(balance)), _dp(A_tiles), _dp(B_tiles),
                                       _dp(scratch), nbytes, _stream()), "factors_store_f16")
+
+
+def factors_store_q(B_f64, A_f64, d_in, d_out, r, ab_bits, balance, A_q, A_scales, B_q, B_scales, scratch):
+    nbytes = 0 if scratch is None else scratch.numel() * scratch.element_size()
+    _check(lib.eora_factors_store_q(_dp(B_f64), _dp(A_f64), d_in, d_out, r, ab_bits, int(bool(balance)), _dp(A_q), _dp(A_scales),
+                                    _dp(B_q), _dp(B_scales), _dp(scratch), nbytes, _stream()), "factors_store_q")

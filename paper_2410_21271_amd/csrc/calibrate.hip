@@ -496,6 +496,66 @@ __global__ void store_f16_tiles_kernel(const double* __restrict__ X, int rows, i
     }
 }
 
+// Symmetric quantisation of a factor X (rows x K fp64) into the Q4 (BITS = 4, KT = 128 or 64) or Q3 (BITS = 3,
+// KT = 128) tile layout with one fp16 scale per row and group of KT columns (Sec. 4.5, App. A.9: quantised
+// factors).  One wavefront per tile: lane l = 16 j + n owns row n and columns (KT/4) j .. of the tile; the four
+// lanes of a row find the group's largest magnitude with two shuffles.  scale = fp16(max |v| / qpos)
+// (1 for an all-zero group), code = clip(rint(v / scale) + zp, 1, 2 zp - 1), zp = 2^(BITS-1), qpos = zp - 1.
+// s / by_row: the balancing scale of store_f16_tiles_kernel.
+template <int BITS, int KT>
+__global__ __launch_bounds__(64) void store_q_tiles_kernel(const double* __restrict__ X, int rows, int K, const double* __restrict__ s,
+                                                           int by_row, uint32_t* __restrict__ out, _Float16* __restrict__ scales)
+{
+    constexpr int CPL = KT / 4, ZP = 1 << (BITS - 1), QPOS = ZP - 1;
+    const int tile = blockIdx.x, lane = threadIdx.x;
+    const int ntk = K / KT;
+    const int R = tile / ntk, g = tile % ntk;
+    const int j = lane >> 4, n = lane & 15;
+    const int row = 16 * R + n, col0 = KT * g + CPL * j;
+    double v[CPL];
+    double amax = 0.0;
+#pragma unroll
+    for (int c = 0; c < CPL; ++c) {
+        double x = X[(size_t)row * K + col0 + c];
+        if (s) x = by_row ? x * s[row] : x / s[col0 + c];
+        v[c] = x;
+        amax = fmax(amax, fabs(x));
+    }
+    amax = fmax(amax, __shfl_xor(amax, 16, 64));
+    amax = fmax(amax, __shfl_xor(amax, 32, 64));
+    _Float16 sc = (_Float16)(amax / (double)QPOS);
+    if (sc == (_Float16)0.0f) sc = (_Float16)1.0f;
+    const double scd = (double)sc;
+    uint32_t code[CPL];
+#pragma unroll
+    for (int c = 0; c < CPL; ++c) {
+        double q = rint(v[c] / scd) + (double)ZP;
+        q = fmin(fmax(q, 1.0), (double)(2 * ZP - 1));
+        code[c] = (uint32_t)q;
+    }
+    if (j == 0) scales[(size_t)row * ntk + g] = sc;
+    if constexpr (BITS == 4) {
+        constexpr int WPL = KT / 32;
+#pragma unroll
+        for (int t = 0; t < WPL; ++t) {
+            uint32_t w = 0;
+#pragma unroll
+            for (int kk = 0; kk < 8; ++kk) w |= code[8 * t + kk] << (4 * (4 * (kk % 2) + kk / 2));
+            out[((size_t)tile * 64 + lane) * WPL + t] = w;
+        }
+    } else {
+        uint32_t d[3] = {0u, 0u, 0u};
+#pragma unroll
+        for (int cc = 0; cc < 30; ++cc) d[(cc / 2) / 5] |= code[cc] << (16 * (cc % 2) + 3 * ((cc / 2) % 5));
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int b = 0; b < 3; ++b) d[b] |= ((code[30 + h] >> b) & 1u) << (16 * h + 15);
+#pragma unroll
+        for (int b = 0; b < 3; ++b) out[((size_t)tile * 64 + lane) * 3 + b] = d[b];
+    }
+}
+
 inline unsigned blocks(size_t n, int per = 256) { return (unsigned)((n + per - 1) / per); }
 
 template <typename TA, typename TB>
@@ -743,6 +803,42 @@ extern "C" int eora_factors_store_f16(const void* B_f64, const void* A_f64, int 
                        (const double*)s, 1, (_Float16*)A_tiles);
     hipLaunchKernelGGL(store_f16_tiles_kernel, dim3(blocks((size_t)d_out * r / 8)), dim3(256), 0, st, (const double*)B_f64, d_out, r,
                        (const double*)s, 0, (_Float16*)B_tiles);
+    if (hipGetLastError() != hipSuccess) return EORA_ERR_LAUNCH;
+    return EORA_OK;
+}
+
+extern "C" int eora_factors_store_q(const void* B_f64, const void* A_f64, int d_in, int d_out, int r, int ab_bits, int balance,
+                                    void* A_q, void* A_scales, void* B_q, void* B_scales, void* scratch, size_t scratch_bytes,
+                                    void* stream)
+{
+    if (!B_f64 || !A_f64 || !A_q || !A_scales || !B_q || !B_scales) return EORA_ERR_NULL;
+    if (ab_bits != 4 && ab_bits != 3) return EORA_ERR_UNSUPPORTED;
+    if (d_in <= 0 || d_out <= 0 || r <= 0 || d_in % 128 || d_out % 16) return EORA_ERR_SHAPE;
+    if (!(r % 128 == 0 || (ab_bits == 4 && r == 64))) return EORA_ERR_SHAPE;
+    if ((reinterpret_cast<uintptr_t>(A_q) | reinterpret_cast<uintptr_t>(B_q) | reinterpret_cast<uintptr_t>(A_scales) |
+         reinterpret_cast<uintptr_t>(B_scales) | reinterpret_cast<uintptr_t>(B_f64) | reinterpret_cast<uintptr_t>(A_f64)) & 15u)
+        return EORA_ERR_ALIGN;
+    double* s = nullptr;
+    if (balance) {
+        if (!scratch || scratch_bytes < sizeof(double) * (size_t)r) return EORA_ERR_WORKSPACE;
+        if (reinterpret_cast<uintptr_t>(scratch) & 15u) return EORA_ERR_ALIGN;
+        s = (double*)scratch;
+    }
+    hipStream_t st = (hipStream_t)stream;
+    const double* A = (const double*)A_f64;
+    const double* B = (const double*)B_f64;
+    if (s) hipLaunchKernelGGL(balance_kernel, dim3(r), dim3(256), 0, st, B, A, d_in, d_out, r, s);
+    const dim3 ga((r / 16) * (d_in / 128)), gb((d_out / 16) * (r / (r == 64 ? 64 : 128)));
+    if (ab_bits == 4) {
+        hipLaunchKernelGGL((store_q_tiles_kernel<4, 128>), ga, dim3(64), 0, st, A, r, d_in, (const double*)s, 1, (uint32_t*)A_q, (_Float16*)A_scales);
+        if (r == 64)
+            hipLaunchKernelGGL((store_q_tiles_kernel<4, 64>), gb, dim3(64), 0, st, B, d_out, r, (const double*)s, 0, (uint32_t*)B_q, (_Float16*)B_scales);
+        else
+            hipLaunchKernelGGL((store_q_tiles_kernel<4, 128>), gb, dim3(64), 0, st, B, d_out, r, (const double*)s, 0, (uint32_t*)B_q, (_Float16*)B_scales);
+    } else {
+        hipLaunchKernelGGL((store_q_tiles_kernel<3, 128>), ga, dim3(64), 0, st, A, r, d_in, (const double*)s, 1, (uint32_t*)A_q, (_Float16*)A_scales);
+        hipLaunchKernelGGL((store_q_tiles_kernel<3, 128>), gb, dim3(64), 0, st, B, d_out, r, (const double*)s, 0, (uint32_t*)B_q, (_Float16*)B_scales);
+    }
     if (hipGetLastError() != hipSuccess) return EORA_ERR_LAUNCH;
     return EORA_OK;
 }

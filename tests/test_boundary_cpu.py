@@ -194,3 +194,16 @@ def test_factors_store_f16_validation_codes():
     assert call(d_in=250) == -2 and call(d_out=24) == -2 and call(r=16) == -2 and call(r=0) == -2
     assert call(At=odd) == -4 and call(scratch=odd) == -4
     assert call(scratch=null) == -5 and call(nbytes=8 * 31) == -5
+
+
+def test_factors_store_q_validation_codes():
+    L = eora.lib
+    good, odd, null = ctypes.c_void_p(0x1000), ctypes.c_void_p(0x1008), ctypes.c_void_p(0)
+
+    def call(B=good, A=good, d_in=256, d_out=32, r=128, bits=4, balance=1, Aq=good, As=good, Bq=good, Bs=good, scratch=good,
+             nbytes=8 * 128):
+        return L.eora_factors_store_q(B, A, d_in, d_out, r, bits, balance, Aq, As, Bq, Bs, scratch, nbytes, null)
+
+    assert call(B=null) == -1 and call(As=null) == -1 and call(bits=16) == -3 and call(bits=2) == -3
+    assert call(d_in=192) == -2 and call(d_out=24) == -2 and call(r=96) == -2 and call(r=64, bits=3) == -2
+    assert call(Bq=odd) == -4 and call(scratch=null) == -5 and call(nbytes=8) == -5

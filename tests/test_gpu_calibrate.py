@@ -164,6 +164,89 @@ def test_store_f16_matches_oracle_tiles(gpu, balance):
             assert diff.max() <= 1 and np.count_nonzero(diff) <= 1e-3 * diff.size
 
 
+@pytest.mark.parametrize("bits,r", [(4, 128), (4, 64), (3, 128), (3, 256)])
+def test_store_q_matches_oracle_bytes(gpu, bits, r):
+    """Quantised storage without balancing is the same arithmetic on the same numbers (fp64 quotient, rint,
+    fp16 scale): codes, their packing and the scales are bit-exact.  With balancing the per-component scale
+    comes from sums in another order, which can move a value across a rounding boundary: the dequantised
+    factors then agree except on a few entries, by one step."""
+    import torch
+    from oracle import calibrate, linear
+    rng = np.random.default_rng(7700 + bits + r)
+    d_in, d_out = 384, 48
+    B = rng.standard_normal((d_out, r)) * np.exp(rng.uniform(-4, 4, r))[None, :]
+    A = rng.standard_normal((r, d_in)) * np.exp(rng.uniform(-4, 4, r))[:, None]
+    A[3, 128:256] = 0.0                                         # an all-zero group
+    Bd, Ad = torch.from_numpy(B).cuda(), torch.from_numpy(A).cuda()
+    KTb = min(128, r)
+    wpl = bits                                                  # 32-bit words per 32 codes
+    for balance in (False, True):
+        Aq = torch.full((r * d_in * wpl // 32,), -1, dtype=torch.int32, device="cuda")
+        Bq = torch.full((d_out * r * wpl // 32,), -1, dtype=torch.int32, device="cuda")
+        As = torch.full((r * d_in // 128,), float("nan"), dtype=torch.float16, device="cuda")
+        Bs = torch.full((d_out * r // KTb,), float("nan"), dtype=torch.float16, device="cuda")
+        scratch = torch.empty(r, dtype=torch.float64, device="cuda")
+        gpu.factors_store_q(Bd, Ad, d_in, d_out, r, bits, balance, Aq, As, Bq, Bs, scratch if balance else None)
+        torch.cuda.synchronize()
+        oAq, oAs, oBq, oBs = calibrate.store_factors_q(B, A, bits, balance=balance)
+        gAq, gBq = Aq.cpu().numpy().view(np.uint32), Bq.cpu().numpy().view(np.uint32)
+        gAs, gBs = As.cpu().numpy(), Bs.cpu().numpy()
+        if not balance:
+            assert np.array_equal(gAq, oAq) and np.array_equal(gBq, oBq)
+            assert np.array_equal(gAs.view(np.uint16), oAs.view(np.uint16)) and np.array_equal(gBs.view(np.uint16), oBs.view(np.uint16))
+        else:
+            deq = linear.dequant_factor_q4 if bits == 4 else linear.dequant_factor_q3
+            for g, gs, o, os_, rows, K in ((gAq, gAs, oAq, oAs, r, d_in), (gBq, gBs, oBq, oBs, d_out, r)):
+                dg, do = deq(g, gs, rows, K), deq(o, os_, rows, K)
+                step = np.repeat(layout_scales(os_, rows, K), min(128, K), axis=1)
+                assert np.all(np.abs(dg - do) <= 1.001 * step) and np.count_nonzero(dg != do) <= 2e-3 * dg.size
+
+
+def layout_scales(packed, rows, K):
+    from oracle import layout
+    return layout.unpack_scales(packed, rows, K // min(128, K)).astype(np.float64)
+
+
+def test_calibrate_quantise_serve_on_the_gpu(gpu):
+    """Algorithm 1, 4-bit storage of its factors and the forward pass, all on the device: y equals the oracle's
+    forward pass on the stored bytes (format consistency), and the 4-bit compensation removes most of the
+    compression error."""
+    import torch
+    import synth
+    from oracle import linear
+    from tests.cases import QCase
+    from tests.gpu_util import dev
+    d_in, d_out, r, M = 512, 256, 128, 6
+    c = QCase(7800, d_in, d_out, M, 0, 3, 128, packer=gpu)
+    qw, sc, qz = dev(c.qw), dev(c.sc), dev(c.qz)
+    W_hat = torch.empty((d_out, d_in), dtype=torch.float32, device="cuda")
+    gpu.dequant_q(qw, sc, qz, W_hat, d_in, d_out, 3, 128)
+    rng = np.random.default_rng(7801)
+    low = (rng.standard_normal((d_out, r)) @ rng.standard_normal((r, d_in)) * 0.002).astype(np.float32)
+    W = W_hat + torch.from_numpy(low).cuda()
+    Xt = torch.from_numpy(synth.draw_calibration(7802, d_in, 1100)).cuda()
+    B = torch.empty((d_out, r), dtype=torch.float64, device="cuda")
+    A = torch.empty((r, d_in), dtype=torch.float64, device="cuda")
+    ws = torch.empty(gpu.factors_workspace_bytes(d_in, d_out, r), dtype=torch.uint8, device="cuda")
+    gpu.factors(W, W_hat, Xt, B, A, None, 1100, d_in, d_out, r, 1e-12, ws)
+    Aq = torch.empty(r * d_in // 8, dtype=torch.int32, device="cuda")
+    Bq = torch.empty(d_out * r // 8, dtype=torch.int32, device="cuda")
+    As = torch.empty(r * d_in // 128, dtype=torch.float16, device="cuda")
+    Bs = torch.empty(d_out * r // 128, dtype=torch.float16, device="cuda")
+    gpu.factors_store_q(B, A, d_in, d_out, r, 4, True, Aq, As, Bq, Bs, torch.empty(r, dtype=torch.float64, device="cuda"))
+    y = torch.full((M * d_out,), 777.0, dtype=torch.float16, device="cuda")
+    lws = gpu.new_workspace(M, d_in, d_out, r)
+    gpu.linear_q(dev(c.x), qw, sc, qz, Aq, Bq, As, Bs, y, M, d_in, d_out, r, 3, 128, 4, lws)
+    torch.cuda.synchronize()
+    assert gpu.workspace_error(lws) == 0
+    y = y.cpu().numpy().reshape(M, d_out)
+    stored = linear.eora_linear_q(c.x, c.o_qw, c.o_sc, c.o_qz, Aq.cpu().numpy().view(np.uint32), Bq.cpu().numpy().view(np.uint32),
+                                  As.cpu().numpy(), Bs.cpu().numpy(), M, d_in, d_out, r, 3, 128, 4)
+    assert linear.y_error(y, stored) <= 2e-3
+    ref = c.x.astype(np.float64) @ W.cpu().numpy().astype(np.float64).T
+    assert linear.y_error(y, ref) < 0.25 * linear.y_error(c.oracle_y(), ref)
+
+
 def test_calibrate_store_serve_on_the_gpu(gpu):
     """Steps 1-7 without leaving the device: dequantise, eora_factors, eora_factors_store_f16, eora_linear_q.
     The error has rank r, so the served layer reproduces x.W^T up to the fp16 roundings."""
