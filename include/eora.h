@@ -238,6 +238,26 @@ int eora_linear_sp24q4(const void* x, const void* qtiles, const void* qmeta,
                        int M, int d_in, int d_out, int r,
                        void* workspace, size_t workspace_bytes, void* stream);
 
+/* Several 2:4 layers that read the SAME x in one launch (query / key / value, gate / up), as
+ * eora_linear_q_group does for quantised backbones: member m is an eora_linear_sp24 layer (values and
+ * indices given, qtiles = qmeta = NULL) or an eora_linear_sp24q4 layer (qtiles and qmeta given, values =
+ * indices = NULL) of its own; all members are of the same kind and share M, d_in and r.  One launch for
+ * M <= 256 (results equal those of separate calls to rounding; bit-identical for M <= 4); larger M runs
+ * the members one after the other.  members: HOST array of 1..4 entries, read during the call only.
+ * workspace: at least the largest eora_workspace_bytes(M, d_in, d_out_m, r).  Errors as eora_linear_sp24. */
+typedef struct {
+    const void* values;
+    const void* indices;
+    const void* qtiles;
+    const void* qmeta;
+    const void* A;
+    const void* B;
+    void* y;
+    int d_out;
+} eora_sp_member;
+int eora_linear_sp24_group(const void* x, const eora_sp_member* members, int n_members,
+                           int M, int d_in, int r, void* workspace, size_t workspace_bytes, void* stream);
+
 /* ---------------------------------------------------------------------------------------------
  * Parity exports (integer / exact work, compared bit for bit against the CPU oracle).
  * ------------------------------------------------------------------------------------------ */

@@ -28,6 +28,11 @@ class QMember(ctypes.Structure):
                [("d_out", ctypes.c_int)]
 
 
+class SpMember(ctypes.Structure):
+    """eora_sp_member of include/eora.h: one 2:4 layer of a group that shares x."""
+    _fields_ = [(n, ctypes.c_void_p) for n in ("values", "indices", "qtiles", "qmeta", "A", "B", "y")] + [("d_out", ctypes.c_int)]
+
+
 def _load():
     if not os.path.exists(_LIB_PATH):
         raise ImportError("libeora.so is not built: run `python paper_2410_21271_amd/build.py` "
@@ -61,6 +66,7 @@ def _load():
         "eora_linear_q": (ci, [vp] * 9 + [ci] * 7 + [vp, sz, vp]),
         "eora_linear_q_multi": (ci, [vp] * 10 + [ci] * 8 + [vp, sz, vp]),
         "eora_linear_q_group": (ci, [vp, ctypes.POINTER(QMember), ci] + [ci] * 6 + [vp, sz, vp]),
+        "eora_linear_sp24_group": (ci, [vp, ctypes.POINTER(SpMember), ci, ci, ci, ci, vp, sz, vp]),
         "eora_linear_sp24": (ci, [vp] * 6 + [ci] * 4 + [vp, sz, vp]),
         "eora_linear_sp24q4": (ci, [vp] * 6 + [ci] * 4 + [vp, sz, vp]),
         "eora_unpack_q": (ci, [vp, vp, vp, vp, ci, ci, ci, ci, vp]),
@@ -86,7 +92,7 @@ EXPORTS = ["eora_status_string", "eora_qweight_bytes", "eora_qzeros_bytes", "eor
            "eora_pack_factor_f16", "eora_pack_factor_q4", "eora_pack_sp24", "eora_linear_q",
            "eora_linear_q_group", "eora_linear_sp24", "eora_unpack_q", "eora_dequant_q", "eora_expand_sp24",
            "eora_sp24q4_tiles_bytes", "eora_sp24q4_meta_bytes", "eora_pack_sp24q4", "eora_linear_sp24q4", "eora_expand_sp24q4",
-           "eora_factors_workspace_bytes", "eora_factors", "eora_linear_q_multi", "eora_pack_factor_q3", "eora_factors_store_f16", "eora_factors_store_q"]
+           "eora_factors_workspace_bytes", "eora_factors", "eora_linear_q_multi", "eora_pack_factor_q3", "eora_factors_store_f16", "eora_factors_store_q", "eora_linear_sp24_group"]
 
 
 def status_string(status):
@@ -332,3 +338,12 @@ def factors_store_q(B_f64, A_f64, d_in, d_out, r, ab_bits, balance, A_q, A_scale
     nbytes = 0 if scratch is None else scratch.numel() * scratch.element_size()
     _check(lib.eora_factors_store_q(_dp(B_f64), _dp(A_f64), d_in, d_out, r, ab_bits, int(bool(balance)), _dp(A_q), _dp(A_scales),
                                     _dp(B_q), _dp(B_scales), _dp(scratch), nbytes, _stream()), "factors_store_q")
+
+
+def linear_sp24_group(x, members, M, d_in, r, workspace):
+    """members: sequence of (values, indices, qtiles, qmeta, A, B, y, d_out); tensors or None."""
+    arr = (SpMember * len(members))()
+    for i, (values, indices, qtiles, qmeta, A, B, y, d_out) in enumerate(members):
+        arr[i] = SpMember(*(None if t is None else t.data_ptr() for t in (values, indices, qtiles, qmeta, A, B, y)), int(d_out))
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib.eora_linear_sp24_group(_dp(x), arr, len(members), M, d_in, r, _dp(workspace), ws_bytes, _stream()), "linear_sp24_group")

@@ -469,6 +469,73 @@ int run_linear_sparse(const void* x, const void* values, const void* indices, co
 }
 }  // namespace
 
+int eora_linear_sp24_group(const void* x, const eora_sp_member* members, int n_members,
+                           int M, int d_in, int r, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!x || !members) return EORA_ERR_NULL;
+    if (n_members < 1 || n_members > MAX_GROUP) return EORA_ERR_SHAPE;
+    const bool vq = members[0].qtiles != nullptr;
+    for (int m = 0; m < n_members; ++m) {               // every member is validated before anything is enqueued
+        const eora_sp_member& e = members[m];
+        if (!e.y) return EORA_ERR_NULL;
+        if (vq ? (!e.qtiles || !e.qmeta || e.values || e.indices) : (!e.values || !e.indices || e.qtiles || e.qmeta)) return EORA_ERR_NULL;
+        int rc = check_backbone_shape(M, d_in, e.d_out, r);
+        if (rc != EORA_OK) return rc;
+        if (r > 0) {
+            if (!e.A || !e.B) return EORA_ERR_NULL;
+            if (r % 32) return EORA_ERR_SHAPE;
+            if (!aligned16(e.A) || !aligned16(e.B)) return EORA_ERR_ALIGN;
+        }
+        if (!aligned16(x) || !aligned16(e.values) || !aligned16(e.qtiles) || !aligned16(e.qmeta) || !aligned16(e.indices) || !aligned16(e.y))
+            return EORA_ERR_ALIGN;
+        if (!workspace) return EORA_ERR_WORKSPACE;
+        if (!aligned16(workspace)) return EORA_ERR_ALIGN;
+        if (workspace_bytes < eora_workspace_bytes(M, d_in, e.d_out, r)) return EORA_ERR_WORKSPACE;
+    }
+    if (M == 0) return EORA_OK;
+    // one launch when the members' partials and flags fit the regions of one call; else one after the other
+    const int yblocks = (M + 15) / 16;
+    int kcn = pick_kcn(M, d_in);
+    while (kcn > 1 && (n_members * yblocks * kcn > 32 || (d_in / 128) % kcn)) --kcn;
+    const bool one_launch = n_members > 1 && M <= CHUNK_TOKENS && n_members * yblocks * kcn <= 32 &&
+                            (r / 16) * kcn * n_members <= HDR_FLAGS_PER_BLOCK;
+    if (!one_launch) {
+        for (int m = 0; m < n_members; ++m) {
+            const eora_sp_member& e = members[m];
+            const int rc = run_linear_sparse(x, e.values, e.indices, e.qtiles, e.qmeta, e.A, e.B, e.y, M, d_in, e.d_out, r,
+                                             workspace, workspace_bytes, stream);
+            if (rc != EORA_OK) return rc;
+        }
+        return EORA_OK;
+    }
+    SparseArgs as[MAX_GROUP];
+    for (int m = 0; m < n_members; ++m) {
+        const eora_sp_member& e = members[m];
+        SparseArgs a{};
+        a.x = (const _Float16*)x;
+        a.values = (const _Float16*)e.values;
+        a.indices = (const uint32_t*)e.indices;
+        a.qtiles = (const uint32_t*)e.qtiles;
+        a.qmeta = (const uint32_t*)e.qmeta;
+        a.A = e.A;
+        a.B = e.B;
+        a.y = (_Float16*)e.y;
+        a.hdr = (uint32_t*)workspace;
+        const size_t region = (size_t)m * yblocks * kcn * 16 * r;        // this member's partials of t
+        a.tpart = (float*)((char*)workspace + WS_PARTS) + region;
+        a.tpair = (unsigned long long*)((char*)workspace + WS_PAIRS) + region;
+        a.M = M;
+        a.d_in = d_in;
+        a.d_out = e.d_out;
+        a.r = r;
+        a.kcn = kcn;
+        a.spin_limit = g_spin_limit;
+        as[m] = a;
+    }
+    if (failed(launch_sparse_group(as, n_members, (hipStream_t)stream), "linear_sp24_group")) return EORA_ERR_LAUNCH;
+    return EORA_OK;
+}
+
 int eora_linear_sp24(const void* x, const void* values, const void* indices,
                      const void* A, const void* B, void* y,
                      int M, int d_in, int d_out, int r,

@@ -106,6 +106,15 @@ struct SparseArgs {
 };
 
 hipError_t launch_sparse(const SparseArgs& a, hipStream_t stream);
+// up to four 2:4 linears that read the same x in one launch (same M, d_in, r, kcn, backbone kind; own weights,
+// factors, y, d_out and regions of the partials)
+struct SparseGroupArgs {
+    SparseArgs m[4];
+    int first[4];             // first workgroup of member i
+    int flag0[4];             // first flag of member i inside a token block's flags
+    int n;
+};
+hipError_t launch_sparse_group(const SparseArgs* members, int n, hipStream_t stream);
 
 // Prefill GEMM (prefill.hip): y[M x N] = act[M x K1] . W1^T (+ act2[M x K2] . W2^T), fp16 output, for up to
 // MAX_GROUP members that read the same act (own weights, second-segment operands, output and N).

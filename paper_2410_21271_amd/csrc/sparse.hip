@@ -93,8 +93,10 @@ __device__ __forceinline__ void stage_x(const _Float16* __restrict__ x, int mt, 
     }
 }
 
+// gbid: index of the workgroup in the launch; bid: its index among its member's workgroups; flag0: the member's
+// first flag inside a token block's flags (one linear: gbid == bid, flag0 == 0)
 template <int FA, int FE, int NW, bool XLDS, bool VQ>
-__global__ __launch_bounds__(NW * 64, 6) void sparse_kernel(SparseArgs a)
+__device__ __forceinline__ void sparse_body(const SparseArgs& a, const int gbid, const int bid, const int flag0)
 {
     constexpr bool LOWRANK = FA != S_NONE;
     constexpr int PD = 4;                                 // tiles of loads in flight per wavefront
@@ -109,7 +111,6 @@ __global__ __launch_bounds__(NW * 64, 6) void sparse_kernel(SparseArgs a)
     const int yblocks = (a.M + 15) / 16;
     const int units = LOWRANK ? (a.r / 16) * a.kcn : 0;
     const int nprod = units * yblocks;
-    const int bid = blockIdx.x;
     const bool producer = bid < nprod;
     // Consumers: workgroups are handed to the 8 XCDs round-robin, each with an L2 of its own.  With several
     // token blocks the blocks of one row block are therefore given indices 8 apart: they land on the same
@@ -140,7 +141,7 @@ __global__ __launch_bounds__(NW * 64, 6) void sparse_kernel(SparseArgs a)
             const Factor fa{(const uint32_t*)a.A, nullptr, a.d_in / KTA};
             const int tpc = fa.ntk / a.kcn;
             if (tid == 0) {
-                check_in_issue(ci, a.hdr, bid);
+                check_in_issue(ci, a.hdr, gbid);
                 s_epoch = ci.epoch;
             }
             if constexpr (XLDS) stage_x<NW>(xg, mt, a.d_in, tid);
@@ -166,7 +167,7 @@ __global__ __launch_bounds__(NW * 64, 6) void sparse_kernel(SparseArgs a)
             __syncthreads();                                      // all pairs are on their way
             if (tid == 0) {
                 for (int rep = 0; rep < HDR_FLAG_REPLICAS; ++rep)  // one copy per group of pollers
-                    __hip_atomic_store(&a.hdr[HDR_FLAGS0 + HDR_FLAGS_REPLICA_STRIDE * rep + HDR_FLAGS_PER_BLOCK * yb + u],
+                    __hip_atomic_store(&a.hdr[HDR_FLAGS0 + HDR_FLAGS_REPLICA_STRIDE * rep + HDR_FLAGS_PER_BLOCK * yb + flag0 + u],
                                        s_epoch + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 check_in_finish(ci, a.hdr, gridDim.x);
             }
@@ -190,7 +191,7 @@ __global__ __launch_bounds__(NW * 64, 6) void sparse_kernel(SparseArgs a)
     if constexpr (LOWRANK) load_ftile<S_F16>(bpre, fb, R, wave < fb.ntk ? wave : 0, lane);
     if constexpr (LOWRANK) {
         if (tid == 0) {
-            check_in_issue(ci, a.hdr, bid);
+            check_in_issue(ci, a.hdr, gbid);
             s_epoch = ci.epoch;
         }
     }
@@ -200,7 +201,7 @@ __global__ __launch_bounds__(NW * 64, 6) void sparse_kernel(SparseArgs a)
     if constexpr (LOWRANK) {
         if (wave == 0)
             early = ld_relaxed(a.hdr + HDR_FLAGS0 + HDR_FLAGS_REPLICA_STRIDE * (blockIdx.x % HDR_FLAG_REPLICAS) +
-                               HDR_FLAGS_PER_BLOCK * yb + (lane < units ? lane : units - 1));
+                               HDR_FLAGS_PER_BLOCK * yb + flag0 + (lane < units ? lane : units - 1));
     }
     if constexpr (XLDS) {
         stage_x<NW>(xg, mt, a.d_in, tid);
@@ -246,7 +247,7 @@ __global__ __launch_bounds__(NW * 64, 6) void sparse_kernel(SparseArgs a)
     if constexpr (LOWRANK) {
         const uint32_t epoch = s_epoch;
         if (wave == 0) {
-            const uint32_t* flags = a.hdr + HDR_FLAGS0 + HDR_FLAGS_REPLICA_STRIDE * (blockIdx.x % HDR_FLAG_REPLICAS) + HDR_FLAGS_PER_BLOCK * yb;
+            const uint32_t* flags = a.hdr + HDR_FLAGS0 + HDR_FLAGS_REPLICA_STRIDE * (blockIdx.x % HDR_FLAG_REPLICAS) + HDR_FLAGS_PER_BLOCK * yb + flag0;
             bool ok = units <= 64 && __all(early == epoch + 1);
             for (int spins = 0; !ok && spins <= a.spin_limit; ++spins) {
                 bool all = true;
@@ -360,7 +361,7 @@ __global__ __launch_bounds__(NW * 64, 6) void sparse_kernel(SparseArgs a)
 // 16 t + (q ^ (t & 15)): the 16 lanes that read one q for 16 tokens hit 16 different bank groups.
 // Producers, flags, partials and the continuation are those of the kernel above.
 template <int FA, int NW, int TB, int XW_D, bool VQ>      // XW_D: steps between a request and its use; divides d_in / 128
-__global__ __launch_bounds__(NW * 64) void sparse_wide_kernel(SparseArgs a)
+__device__ __forceinline__ void sparse_wide_body(const SparseArgs& a, const int gbid, const int bid, const int flag0)
 {
     constexpr bool LOWRANK = FA != S_NONE;
     constexpr int SLOT = TB * 16 * 256;                   // bytes per slot
@@ -375,7 +376,6 @@ __global__ __launch_bounds__(NW * 64) void sparse_wide_kernel(SparseArgs a)
     const int yblocks = (a.M + 15) / 16;
     const int units = LOWRANK ? (a.r / 16) * a.kcn : 0;
     const int nprod = units * yblocks;
-    const int bid = blockIdx.x;
     const bool producer = bid < nprod;
 
     CheckIn ci{0u, 0u, 0u};
@@ -394,7 +394,7 @@ __global__ __launch_bounds__(NW * 64) void sparse_wide_kernel(SparseArgs a)
             const Factor fa{(const uint32_t*)a.A, nullptr, a.d_in / KTA};
             const int tpc = fa.ntk / a.kcn;
             if (tid == 0) {
-                check_in_issue(ci, a.hdr, bid);
+                check_in_issue(ci, a.hdr, gbid);
                 s_epoch = ci.epoch;
             }
             __syncthreads();
@@ -415,7 +415,7 @@ __global__ __launch_bounds__(NW * 64) void sparse_wide_kernel(SparseArgs a)
             __syncthreads();
             if (tid == 0) {
                 for (int rep = 0; rep < HDR_FLAG_REPLICAS; ++rep)
-                    __hip_atomic_store(&a.hdr[HDR_FLAGS0 + HDR_FLAGS_REPLICA_STRIDE * rep + HDR_FLAGS_PER_BLOCK * yb + u],
+                    __hip_atomic_store(&a.hdr[HDR_FLAGS0 + HDR_FLAGS_REPLICA_STRIDE * rep + HDR_FLAGS_PER_BLOCK * yb + flag0 + u],
                                        s_epoch + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 check_in_finish(ci, a.hdr, gridDim.x);
             }
@@ -454,7 +454,7 @@ __global__ __launch_bounds__(NW * 64) void sparse_wide_kernel(SparseArgs a)
     }
     if constexpr (LOWRANK) {
         if (tid == 0) {
-            check_in_issue(ci, a.hdr, bid);
+            check_in_issue(ci, a.hdr, gbid);
             s_epoch = ci.epoch;
         }
     }
@@ -528,7 +528,7 @@ __global__ __launch_bounds__(NW * 64) void sparse_wide_kernel(SparseArgs a)
             for (int tb = 0; tb < TB; ++tb) {
                 const int yb = tg * TB + tb;
                 if (yb >= yblocks || !ok) continue;
-                const uint32_t* flags = a.hdr + HDR_FLAGS0 + HDR_FLAGS_REPLICA_STRIDE * (blockIdx.x % HDR_FLAG_REPLICAS) + HDR_FLAGS_PER_BLOCK * yb;
+                const uint32_t* flags = a.hdr + HDR_FLAGS0 + HDR_FLAGS_REPLICA_STRIDE * (blockIdx.x % HDR_FLAG_REPLICAS) + HDR_FLAGS_PER_BLOCK * yb + flag0;
                 bool up = false;
                 for (int spins = 0; spins <= a.spin_limit; ++spins) {
                     bool all = true;
@@ -619,82 +619,169 @@ __global__ __launch_bounds__(NW * 64) void sparse_wide_kernel(SparseArgs a)
     }
 }
 
-template <int FA, int NW, int TB, int XW_D, bool VQ>
-static hipError_t launch_sparse_wide(const SparseArgs& a, hipStream_t stream)
+// One linear: the arguments sit at fixed places of the kernel's argument block.  Several linears that share x
+// (SparseGroupArgs): each workgroup first finds its member (uniform; one more dependent scalar load at the
+// start, which is why single linears keep kernels of their own); the members' workgroups follow one another,
+// each member's producers before its consumers, so a waiting workgroup's producers always have lower indices.
+__device__ __forceinline__ int sparse_member(const SparseGroupArgs& grp)
 {
-    auto kern = sparse_wide_kernel<FA, NW, TB, XW_D, VQ>;
+    int mem = 0;
+#pragma unroll
+    for (int i = 1; i < 4; ++i)
+        if (i < grp.n && (int)blockIdx.x >= grp.first[i]) mem = i;
+    return mem;
+}
+
+template <int FA, int FE, int NW, bool XLDS, bool VQ>
+__global__ __launch_bounds__(NW * 64, 6) void sparse_kernel(SparseArgs a)
+{
+    sparse_body<FA, FE, NW, XLDS, VQ>(a, blockIdx.x, blockIdx.x, 0);
+}
+
+template <int FA, int FE, int NW, bool XLDS, bool VQ>
+__global__ __launch_bounds__(NW * 64, 6) void sparse_group_kernel(SparseGroupArgs grp)
+{
+    const int mem = sparse_member(grp);
+    sparse_body<FA, FE, NW, XLDS, VQ>(grp.m[mem], blockIdx.x, (int)blockIdx.x - grp.first[mem], grp.flag0[mem]);
+}
+
+template <int FA, int NW, int TB, int XW_D, bool VQ>
+__global__ __launch_bounds__(NW * 64) void sparse_wide_kernel(SparseArgs a)
+{
+    sparse_wide_body<FA, NW, TB, XW_D, VQ>(a, blockIdx.x, blockIdx.x, 0);
+}
+
+template <int FA, int NW, int TB, int XW_D, bool VQ>
+__global__ __launch_bounds__(NW * 64) void sparse_wide_group_kernel(SparseGroupArgs grp)
+{
+    const int mem = sparse_member(grp);
+    sparse_wide_body<FA, NW, TB, XW_D, VQ>(grp.m[mem], blockIdx.x, (int)blockIdx.x - grp.first[mem], grp.flag0[mem]);
+}
+
+// fills the member table; blocks(i) = workgroups of member i
+template <typename F>
+static int fill_group(SparseGroupArgs& g, const SparseArgs* members, int n, int units, F blocks)
+{
+    g.n = n;
+    int total = 0;
+    for (int i = 0; i < 4; ++i) {
+        g.m[i] = members[i < n ? i : 0];
+        g.first[i] = total;
+        g.flag0[i] = (i < n ? i : 0) * units;
+        if (i < n) total += blocks(members[i]);
+    }
+    return total;
+}
+
+template <int FA, int NW, int TB, int XW_D, bool VQ>
+static hipError_t launch_sparse_wide(const SparseArgs* members, int n, hipStream_t stream)
+{
+    const SparseArgs& a = members[0];
     const size_t xb = (size_t)2 * TB * 4096, tb = (size_t)16 * a.r * 4;
     const size_t lds = xb > tb ? xb : tb;
+    const int yblocks = (a.M + 15) / 16;
+    const int units = (FA != S_NONE) ? (a.r / 16) * a.kcn : 0;
+    auto blocks = [&](const SparseArgs& m) { return ((m.d_out / 16 + NW - 1) / NW) * ((yblocks + TB - 1) / TB) + units * yblocks; };
+    if (n == 1) {
+        auto kern = sparse_wide_kernel<FA, NW, TB, XW_D, VQ>;
+        if (lds > 48 * 1024) {
+            hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+        }
+        hipLaunchKernelGGL(kern, dim3(blocks(a)), dim3(NW * 64), lds, stream, a);
+        return hipGetLastError();
+    }
+    auto kern = sparse_wide_group_kernel<FA, NW, TB, XW_D, VQ>;
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    const int yblocks = (a.M + 15) / 16;
-    const int nprod = (FA != S_NONE) ? (a.r / 16) * a.kcn * yblocks : 0;
-    const int nrg = (a.d_out / 16 + NW - 1) / NW;
-    hipLaunchKernelGGL(kern, dim3(nrg * ((yblocks + TB - 1) / TB) + nprod), dim3(NW * 64), lds, stream, a);
+    SparseGroupArgs g{};
+    const int total = fill_group(g, members, n, units, blocks);
+    hipLaunchKernelGGL(kern, dim3(total), dim3(NW * 64), lds, stream, g);
     return hipGetLastError();
 }
 
 template <int FA, bool VQ>
-static hipError_t launch_sparse_wide_cfg(const SparseArgs& a, int nw, int tb, hipStream_t stream)
+static hipError_t launch_sparse_wide_cfg(const SparseArgs* members, int n, int nw, int tb, hipStream_t stream)
 {
     if (nw == 8) {                                        // eight row blocks: two or four token blocks (whole 1 KiB pieces per wavefront)
-        if (tb == 2) return launch_sparse_wide<FA, 8, 2, 4, VQ>(a, stream);
-        return launch_sparse_wide<FA, 8, 4, 4, VQ>(a, stream);
+        if (tb == 2) return launch_sparse_wide<FA, 8, 2, 4, VQ>(members, n, stream);
+        return launch_sparse_wide<FA, 8, 4, 4, VQ>(members, n, stream);
     }
     switch (tb) {
-    case 1: return launch_sparse_wide<FA, 4, 1, 4, VQ>(a, stream);
-    case 2: return launch_sparse_wide<FA, 4, 2, 4, VQ>(a, stream);
-    case 3: return launch_sparse_wide<FA, 4, 3, 4, VQ>(a, stream);
-    default: return launch_sparse_wide<FA, 4, 4, 4, VQ>(a, stream);
+    case 1: return launch_sparse_wide<FA, 4, 1, 4, VQ>(members, n, stream);
+    case 2: return launch_sparse_wide<FA, 4, 2, 4, VQ>(members, n, stream);
+    case 3: return launch_sparse_wide<FA, 4, 3, 4, VQ>(members, n, stream);
+    default: return launch_sparse_wide<FA, 4, 4, 4, VQ>(members, n, stream);
     }
 }
 
 template <int FA, int FE, int NW, bool XLDS, bool VQ>
-static hipError_t launch_sparse_one(const SparseArgs& a, hipStream_t stream)
+static hipError_t launch_sparse_one(const SparseArgs* members, int n, hipStream_t stream)
 {
-    auto kern = sparse_kernel<FA, FE, NW, XLDS, VQ>;
+    const SparseArgs& a = members[0];
     const int mt = a.M < 16 ? a.M : 16;
     const size_t lds = (XLDS ? (size_t)mt * (a.d_in + 32) * 2 : 0) + (size_t)mt * a.r * 4;      // x, then t
+    const int yblocks = (a.M + 15) / 16;
+    const int units = (FA != S_NONE) ? (a.r / 16) * a.kcn : 0;
+    auto blocks = [&](const SparseArgs& m) { return (m.d_out / 16) * yblocks + units * yblocks; };
+    if (n == 1) {
+        auto kern = sparse_kernel<FA, FE, NW, XLDS, VQ>;
+        if (lds > 48 * 1024) {
+            hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+        }
+        hipLaunchKernelGGL(kern, dim3(blocks(a)), dim3(NW * 64), lds, stream, a);
+        return hipGetLastError();
+    }
+    auto kern = sparse_group_kernel<FA, FE, NW, XLDS, VQ>;
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    const int yblocks = (a.M + 15) / 16;
-    const int nprod = (FA != S_NONE) ? (a.r / 16) * a.kcn * yblocks : 0;
-    hipLaunchKernelGGL(kern, dim3((a.d_out / 16) * yblocks + nprod), dim3(NW * 64), lds, stream, a);
+    SparseGroupArgs g{};
+    const int total = fill_group(g, members, n, units, blocks);
+    hipLaunchKernelGGL(kern, dim3(total), dim3(NW * 64), lds, stream, g);
     return hipGetLastError();
 }
 
 template <bool VQ>
-static hipError_t launch_sparse_vq(const SparseArgs& a, hipStream_t stream)
+static hipError_t launch_sparse_vq(const SparseArgs* members, int n, hipStream_t stream)
 {
+    const SparseArgs& a = members[0];
     // x in LDS for 1..4 tokens when it fits next to t (d_in a multiple of 512 for the 1 KiB copy chunks)
     const bool xlds = a.M <= 4 && a.d_in % 512 == 0 && (size_t)a.M * (a.d_in + 32) * 2 + a.M * (size_t)a.r * 4 <= 140 * 1024;
     // Several tokens and enough row groups: x shared through LDS.  A workgroup fetches all of its token
     // blocks' x, so more row blocks (8, then 4) and more token blocks (4, 2, 1) per workgroup come first, as
     // long as 192 (eight row blocks) or 256 workgroups remain (measured on the 70B shapes at 64 tokens: the gate
     // projection gains 15 % from eight row blocks with 224 workgroups, the 8192-row linears lose with 128).
-    const int yblocks = (a.M + 15) / 16, rbs = a.d_out / 16;
+    // The members of a group are counted together.
+    const int yblocks = (a.M + 15) / 16;
     if (a.M > 4 && a.d_in % 512 == 0 && a.r <= 512) {
         for (int nw = 8; nw >= 4; nw -= 4) {
             for (int tb = yblocks < 4 ? yblocks : 4; tb >= 1; tb = tb > 2 ? (tb + 1) / 2 : tb - 1) {
                 if (nw == 8 && tb != 2 && tb != 4) continue;
-                if (((rbs + nw - 1) / nw) * ((yblocks + tb - 1) / tb) >= (nw == 8 ? 192 : 256))
-                    return a.r == 0 ? launch_sparse_wide_cfg<S_NONE, VQ>(a, nw, tb, stream)
-                                    : launch_sparse_wide_cfg<S_F16, VQ>(a, nw, tb, stream);
+                int groups = 0;
+                for (int i = 0; i < n; ++i) groups += (members[i].d_out / 16 + nw - 1) / nw;
+                if (groups * ((yblocks + tb - 1) / tb) >= (nw == 8 ? 192 : 256))
+                    return a.r == 0 ? launch_sparse_wide_cfg<S_NONE, VQ>(members, n, nw, tb, stream)
+                                    : launch_sparse_wide_cfg<S_F16, VQ>(members, n, nw, tb, stream);
             }
         }
     }
-    if (a.r == 0) return xlds ? launch_sparse_one<S_NONE, S_NONE, 8, true, VQ>(a, stream)
-                              : launch_sparse_one<S_NONE, S_NONE, 8, false, VQ>(a, stream);
-    return xlds ? launch_sparse_one<S_F16, S_F16, 8, true, VQ>(a, stream) : launch_sparse_one<S_F16, S_F16, 8, false, VQ>(a, stream);
+    if (a.r == 0) return xlds ? launch_sparse_one<S_NONE, S_NONE, 8, true, VQ>(members, n, stream)
+                              : launch_sparse_one<S_NONE, S_NONE, 8, false, VQ>(members, n, stream);
+    return xlds ? launch_sparse_one<S_F16, S_F16, 8, true, VQ>(members, n, stream)
+                : launch_sparse_one<S_F16, S_F16, 8, false, VQ>(members, n, stream);
 }
 
-hipError_t launch_sparse(const SparseArgs& a, hipStream_t stream)
+hipError_t launch_sparse_group(const SparseArgs* members, int n, hipStream_t stream)
 {
-    return a.qtiles ? launch_sparse_vq<true>(a, stream) : launch_sparse_vq<false>(a, stream);
+    if (n < 1 || n > 4) return hipErrorInvalidValue;
+    return members[0].qtiles ? launch_sparse_vq<true>(members, n, stream) : launch_sparse_vq<false>(members, n, stream);
 }
+
+hipError_t launch_sparse(const SparseArgs& a, hipStream_t stream) { return launch_sparse_group(&a, 1, stream); }
 
 }  // namespace eora

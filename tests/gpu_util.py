@@ -103,3 +103,24 @@ def run_linear_q_multi(c, sel, r_per, ws=None):
     out = ybuf.cpu().numpy()
     assert np.all(out[:pad] == 777.0) and np.all(out[pad + c.M * c.d_out:] == 777.0), "write outside y"
     return out[pad: pad + c.M * c.d_out].reshape(c.M, c.d_out)
+
+
+def run_linear_sp24_group(cases, ws=None):
+    """Run eora_linear_sp24_group on 2:4 cases (all SparseCase or all SparseQCase) that share M, d_in, r and the
+    activations of the first case; returns the list of y (M x d_out fp16 numpy)."""
+    c0 = cases[0]
+    xd = dev(c0.x)
+    mem, ys = [], []
+    for c in cases:
+        y = torch.full((c0.M * c.d_out,), 777.0, dtype=torch.float16, device="cuda")
+        A, B = (dev(c.A), dev(c.B)) if c0.r > 0 else (None, None)
+        if hasattr(c, "tiles"):
+            mem.append((None, None, dev(c.tiles), dev(c.meta), A, B, y, c.d_out))
+        else:
+            mem.append((dev(c.values), dev(c.indices), None, None, A, B, y, c.d_out))
+        ys.append(y)
+    ws = eora.new_workspace(c0.M, c0.d_in, max(c.d_out for c in cases), c0.r) if ws is None else ws
+    eora.linear_sp24_group(xd, mem, c0.M, c0.d_in, c0.r, ws)
+    torch.cuda.synchronize()
+    assert eora.workspace_error(ws) == 0
+    return [y.cpu().numpy().reshape(c0.M, c.d_out) for y, c in zip(ys, cases)]

@@ -207,3 +207,25 @@ def test_factors_store_q_validation_codes():
     assert call(B=null) == -1 and call(As=null) == -1 and call(bits=16) == -3 and call(bits=2) == -3
     assert call(d_in=192) == -2 and call(d_out=24) == -2 and call(r=96) == -2 and call(r=64, bits=3) == -2
     assert call(Bq=odd) == -4 and call(scratch=null) == -5 and call(nbytes=8) == -5
+
+
+def test_linear_sp24_group_validation_codes():
+    L = eora.lib
+    S = eora.binding.SpMember
+    g, null = 0x1000, ctypes.c_void_p(0)
+    good = ctypes.c_void_p(g)
+
+    def call(members, n=None, M=1, d_in=256, r=32, ws=good, ws_bytes=1 << 24, x=good):
+        arr = (S * max(1, len(members)))(*members)
+        return L.eora_linear_sp24_group(x, arr, len(members) if n is None else n, M, d_in, r, ws, ws_bytes, null)
+
+    fp = S(g, g, None, None, g, g, g, 32)
+    q4 = S(None, None, g, g, g, g, g, 32)
+    # (only error paths and the empty batch are called: nothing here may reach a launch)
+    assert call([fp], n=0) == -2 and call([fp] * 5) == -2 and call([fp], x=null) == -1
+    assert call([fp, q4]) == -1                                   # members of different kinds
+    assert call([fp, S(g, g, None, None, g, g, None, 32)]) == -1  # no y
+    assert call([q4, S(None, None, g, g, g, g, g, 40)]) == -2
+    assert call([fp, S(g, 0x1008, None, None, g, g, g, 32)]) == -4
+    assert call([fp, fp], r=48) == -2 and call([fp, fp], ws=null) == -5 and call([fp, fp], ws_bytes=16) == -5
+    assert call([fp, fp], M=0) == 0

@@ -427,3 +427,29 @@ def test_sp24q4_70b_shape_k_projection(gpu, M):
     from tests.gpu_util import run_linear_sp24q4
     c = SparseQCase(synth.seed_for(5, 11), 8192, 1024, M, 128, packer=gpu)
     _check(run_linear_sp24q4(c), c.oracle_y())
+
+
+@pytest.mark.parametrize("quantised", [False, True])
+@pytest.mark.parametrize("r,M,d_in,d_outs", [
+    (32, 1, 1024, (256, 64, 64)),          # query / key / value in miniature, one token (x in LDS)
+    (0, 3, 1024, (128, 128)),              # bare
+    (64, 37, 1024, (192, 64, 48, 16)),     # four members, three token blocks: the kernel without shared x
+    (128, 64, 2048, (4096, 1024, 1024)),   # enough rows together for the kernel that shares x through LDS
+    (32, 300, 512, (64, 32)),              # more than 256 tokens: the members run one after the other
+])
+def test_sparse_group_of_layers_sharing_x(gpu, quantised, r, M, d_in, d_outs):
+    """2:4 layers that read the same x in one call: every member equals the oracle on its own weights and
+    factors; two runs are identical; for up to four tokens the result is that of a separate call, bit for bit."""
+    from tests.cases import SparseCase, SparseQCase
+    from tests.gpu_util import run_linear_sp24, run_linear_sp24_group, run_linear_sp24q4
+    make = SparseQCase if quantised else SparseCase
+    cases = [make(900 + 7 * i + M + d_in, d_in, d, M, r, packer=gpu) for i, d in enumerate(d_outs)]
+    for c in cases[1:]:
+        c.x = cases[0].x
+    ys = run_linear_sp24_group(cases)
+    again = run_linear_sp24_group(cases)
+    for c, y, y2 in zip(cases, ys, again):
+        _check(y, c.oracle_y())
+        assert np.array_equal(y, y2)
+        if M <= 4:
+            assert np.array_equal(y, run_linear_sp24q4(c) if quantised else run_linear_sp24(c))
