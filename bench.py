@@ -66,7 +66,10 @@ for _n in ("llama3-8b-layer-decode-w3g128-r128fp16-M1", "llama3-8b-layer-decode-
            "llama3-8b-layer-decode-w2g128-bare-M1", "llama3-8b-layer-prefill-w2g128-r256fp16-M2048",
            "llama3-8b-layer-decode-w4g128-r128q3-M1", "llama3-8b-layer-decode-w4g128-r128fp16-M16",
            "llama3-8b-layer-decode-w4g128-r128q4-M8", "llama3-8b-layer-decode-w4g128-bare-M8",
-           "llama3-8b-layer-decode-w4g128-r128fp16-M64"):
+           "llama3-8b-layer-decode-w4g128-r128fp16-M64", "llama3-70b-layer-decode-sp24-r128fp16-M1",
+           "llama3-70b-layer-decode-sp24-bare-M1", "llama3-70b-layer-decode-sp24-r128fp16-M64",
+           "llama3-70b-layer-decode-sp24q4-r128fp16-M1", "llama3-70b-layer-decode-sp24q4-bare-M1",
+           "llama3-70b-layer-decode-sp24q4-r128fp16-M64"):
     WORKLOADS[_n + "-grouped"] = dict(WORKLOADS[_n], grouped=True)
 GROUPS = (("q", "k", "v"), ("o",), ("gate", "up"), ("down",))
 for _r in (64, 256, 512):
@@ -200,6 +203,13 @@ class Group:
         m0 = self.members[0]
         if len(self.members) == 1:
             return m0.run(copy)
+        if m0.w_bits == 0:                                # 2:4 members: (values, indices) or (qtiles, qmeta)
+            mem = []
+            for L in self.members:
+                c = L.copies[copy % len(L.copies)]
+                mem.append((None, None, c[0], c[1], c[3], c[4], L.y, L.d_out) if L.sq else (c[0], c[1], None, None, c[3], c[4], L.y, L.d_out))
+            eora.linear_sp24_group(m0.x, mem, m0.M, m0.d_in, m0.r, self.ws)
+            return
         mem = [tuple(L.copies[copy % len(L.copies)]) + (L.y, L.d_out) for L in self.members]
         eora.linear_q_group(m0.x, mem, m0.M, m0.d_in, m0.r, m0.w_bits, 128, m0.ab_bits, self.ws)
 
