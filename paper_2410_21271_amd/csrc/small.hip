@@ -30,6 +30,20 @@ constexpr int TWO_BLOCKS_FROM = 1024;   // row blocks of a launch from which a w
 #define TL_STAMP(slot) do { } while (0)
 #endif
 
+// Member m's entry of a per-member argument array, chosen with scalar selects among the four entries (all at
+// fixed places of the argument block, requested with the first batch of scalar loads) instead of a load at a
+// computed offset, which could only be issued once m is known: one dependent round trip less at the start of
+// every workgroup.
+template <typename T>
+__device__ __forceinline__ T pick_member(const T (&arr)[MAX_GROUP], int m)
+{
+    T v = arr[0];
+    v = m == 1 ? arr[1] : v;
+    v = m == 2 ? arr[2] : v;
+    v = m == 3 ? arr[3] : v;
+    return v;
+}
+
 template <int FM, int FA, int FE, int NW, int NQ, bool M1, int RB>
 __global__ __launch_bounds__(NW * 64, (16 + NW - 1) / NW) void small_kernel(GroupArgs a)   // second bound: wavefronts per SIMD, i.e. at most 128 registers for four-wavefront workgroups
 {
@@ -73,7 +87,7 @@ __global__ __launch_bounds__(NW * 64, (16 + NW - 1) / NW) void small_kernel(Grou
         constexpr int KTA = Fmt<FA>::KT, NMF = KTA / 32;
         const int NRB = a.r / 16;
         const int u = blockIdx.x, mem = u / upl, ul = u % upl, rho = ul % NRB, kc = ul / NRB;
-        const Factor fa{(const uint32_t*)a.A[mem], a.A_scales[mem], a.d_in / KTA};
+        const Factor fa{(const uint32_t*)pick_member(a.A, mem), pick_member(a.A_scales, mem), a.d_in / KTA};
         const int tpc = fa.ntk / a.kcn;                  // k-tiles of this unit
         const int first = kc * tpc + wave;
         const int nsteps = wave < tpc ? (tpc - wave + NW - 1) / NW : 0;
@@ -149,13 +163,26 @@ __global__ __launch_bounds__(NW * 64, (16 + NW - 1) / NW) void small_kernel(Grou
 
     // =========================================================================== consumer
     int R = blockIdx.x - nprod, mem = 0;                 // strip of RB row blocks within its member
-    while (mem + 1 < a.n && R >= a.d_out[mem] / (16 * RB)) {
-        R -= a.d_out[mem] / (16 * RB);
-        ++mem;
+    {
+        const int s0 = a.d_out[0] / (16 * RB), s1 = a.d_out[1] / (16 * RB), s2 = a.d_out[2] / (16 * RB);
+        if (a.n > 1 && R >= s0) {
+            R -= s0;
+            mem = 1;
+            if (a.n > 2 && R >= s1) {
+                R -= s1;
+                mem = 2;
+                if (a.n > 3 && R >= s2) {
+                    R -= s2;
+                    mem = 3;
+                }
+            }
+        }
     }
-    const _Float16* const w_scales = a.w_scales[mem];
-    const uint32_t* const w_zeros = a.w_zeros[mem];
-    const uint32_t* const w_tiles = (const uint32_t*)a.w[mem];
+    const int d_out_m = pick_member(a.d_out, mem);
+    _Float16* const y_m = pick_member(a.y, mem);
+    const _Float16* const w_scales = pick_member(a.w_scales, mem);
+    const uint32_t* const w_zeros = pick_member(a.w_zeros, mem);
+    const uint32_t* const w_tiles = (const uint32_t*)pick_member(a.w, mem);
     const int G = a.d_in / 128;                          // == 4 * NW * NQ, one quantisation group per k-tile
     uint2 sc[RB][NQ];
     uint32_t zq[RB][NQ];
@@ -170,7 +197,7 @@ __global__ __launch_bounds__(NW * 64, (16 + NW - 1) / NW) void small_kernel(Grou
             zq[rb][q] = w_zeros[row * (G / 8) + (g0 >> 3)];
         }
     }
-    const Factor fb{(const uint32_t*)a.B[mem], a.B_scales[mem], LOWRANK ? a.r / Fmt<LOWRANK ? FE : S_F16>::KT : 0};
+    const Factor fb{(const uint32_t*)pick_member(a.B, mem), pick_member(a.B_scales, mem), LOWRANK ? a.r / Fmt<LOWRANK ? FE : S_F16>::KT : 0};
     FTile<LOWRANK ? FE : S_F16> bpre[RB];
     if constexpr (LOWRANK) {
 #pragma unroll
@@ -361,7 +388,7 @@ __global__ __launch_bounds__(NW * 64, (16 + NW - 1) / NW) void small_kernel(Grou
             float v = 0.f;
 #pragma unroll
             for (int w2 = 0; w2 < NW; ++w2) v += red[w2][rb][i][col];
-            a.y[mem][(size_t)i * a.d_out[mem] + (R * RB + rb) * 16 + col] = (_Float16)v;
+            y_m[(size_t)i * d_out_m + (R * RB + rb) * 16 + col] = (_Float16)v;
         }
     }
     TL_STAMP(6);
