@@ -403,7 +403,7 @@ __device__ __forceinline__ void wide_q_body(const FusedArgs& a, const int gbid, 
 
 // one linear: the arguments sit at fixed places of the kernel's argument block
 template <int FM, int FA, int FE, int NWR, int NWK, int TB>
-__global__ __launch_bounds__(NWR * NWK * 64, 4) void wide_q_kernel(FusedArgs a)
+__global__ __launch_bounds__(NWR * NWK * 64, TB == 1 ? 4 : 2) void wide_q_kernel(FusedArgs a)
 {
     wide_q_body<FM, FA, FE, NWR, NWK, TB>(a, blockIdx.x, blockIdx.x, 0);
 }
@@ -413,7 +413,7 @@ __global__ __launch_bounds__(NWR * NWK * 64, 4) void wide_q_kernel(FusedArgs a)
 // follow one another, each member's producers before its consumers, so a waiting workgroup's producers always
 // have lower indices.
 template <int FM, int FA, int FE, int NWR, int NWK, int TB>
-__global__ __launch_bounds__(NWR * NWK * 64, 4) void wide_q_group_kernel(WideGroupArgs grp)
+__global__ __launch_bounds__(NWR * NWK * 64, TB == 1 ? 4 : 2) void wide_q_group_kernel(WideGroupArgs grp)
 {
     int mem = 0;
 #pragma unroll
@@ -438,7 +438,21 @@ static bool pick_wide(int M, int d_in, int d_out, int r, WideCfg* out)
         const int nwr = cand[c][0], nwk = cand[c][1];
         if (d_in % (512 * nwk) != 0) continue;
         const int need = r > 0 ? 128 : (c == 0 ? 192 : 256);
-        if (((rbs + nwr - 1) / nwr) * yblocks >= need) { *out = {nwr, nwk, 1}; return true; }
+        const int groups = (rbs + nwr - 1) / nwr;
+        if (groups * yblocks >= need) {
+            // several token blocks per workgroup (a stored tile is decoded once for all of them, and the weights
+            // cross from L2 once per workgroup instead of once per token block) as long as the chip stays filled
+            // (192 workgroups, one per compute unit at their register count; measured at 64 tokens on the 8B
+            // shapes: the gate projection 39.8 -> 31.9 us with four token blocks per workgroup and 224 workgroups,
+            // the 4096-row linears lose with 128)
+            int tb = 1;
+            if (c == 0) {
+                if (yblocks >= 4 && groups * ((yblocks + 3) / 4) >= 192) tb = 4;
+                else if (yblocks >= 2 && groups * ((yblocks + 1) / 2) >= 192) tb = 2;
+            }
+            *out = {nwr, nwk, tb};
+            return true;
+        }
     }
     return false;                                         // too few rows to fill the chip this way
 }
@@ -505,6 +519,8 @@ static hipError_t launch_wide_cfg(const FusedArgs* members, int n, hipStream_t s
 {
     WideCfg c;
     if (!pick_wide_group(members, n, &c)) return hipErrorInvalidValue;
+    if (c.nwr == 4 && c.tb == 4) return launch_wide_one<FM, FA, FE, 4, 2, 4>(members, n, stream);
+    if (c.nwr == 4 && c.tb == 2) return launch_wide_one<FM, FA, FE, 4, 2, 2>(members, n, stream);
     if (c.nwr == 4) return launch_wide_one<FM, FA, FE, 4, 2, 1>(members, n, stream);
     if (c.nwr == 2) return launch_wide_one<FM, FA, FE, 2, 4, 1>(members, n, stream);
     if (c.nwk == 8) return launch_wide_one<FM, FA, FE, 1, 8, 1>(members, n, stream);
