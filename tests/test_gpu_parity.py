@@ -153,6 +153,8 @@ def test_group_of_layers_sharing_x(gpu, w_bits, ab_bits, r, M, d_in, d_outs):
     (4, 16, 128, 64, 4096, (14336, 14336)),         # gate / up at 64 tokens
     (2, 16, 0, 9, 2048, (1024, 1024, 1024, 1040)),  # four members, bare, a ragged last row group
     (4, 3, 128, 100, 2048, (4096, 512)),            # seven token blocks: the members' partials share the scratch
+    (4, 16, 512, 16, 2048, (1024, 1024, 1024, 1040)),   # four members at the largest rank: every flag of a token block in use
+    (3, 16, 128, 127, 2048, (1024, 1024, 1024, 1024)),  # four members x eight token blocks: one k-range each
 ])
 def test_group_of_layers_sharing_x_mid_token_counts(gpu, w_bits, ab_bits, r, M, d_in, d_outs):
     """5 .. 127 tokens: the members' workgroups run in one launch (the split of the sums may differ from a
@@ -436,6 +438,9 @@ def test_sp24q4_70b_shape_k_projection(gpu, M):
     (64, 37, 1024, (192, 64, 48, 16)),     # four members, three token blocks: the kernel without shared x
     (128, 64, 2048, (4096, 1024, 1024)),   # enough rows together for the kernel that shares x through LDS
     (32, 300, 512, (64, 32)),              # more than 256 tokens: the members run one after the other
+    (512, 16, 1024, (1024, 1024, 1024, 1040)),   # four members at the largest rank
+    (128, 127, 2048, (2048, 1024, 1024, 512)),   # four members x eight token blocks
+    (64, 256, 1024, (128, 64)),            # sixteen token blocks: the most one launch takes
 ])
 def test_sparse_group_of_layers_sharing_x(gpu, quantised, r, M, d_in, d_outs):
     """2:4 layers that read the same x in one call: every member equals the oracle on its own weights and
