@@ -110,7 +110,9 @@ size_t eora_workspace_bytes(int M, int d_in, int d_out, int r);
  * down-projections of all members then sit side by side in the scratch).  With a workspace of only
  * eora_workspace_bytes() such a call still works, member by member. */
 size_t eora_workspace_bytes_group(int M, int d_in, int r, int n_members);
-/* Enqueues the clearing of all `workspace_bytes` bytes on `stream`. */
+/* Enqueues the clearing of all `workspace_bytes` bytes on `stream` (and the start of the workspace's launch
+ * counter at a value no other initialisation in this process uses, so that memory which held a workspace
+ * before can never be mistaken for this one's). */
 int eora_workspace_init(void* workspace, size_t workspace_bytes, void* stream);
 /* Diagnostic.  SYNCHRONISES `stream`, then reports EORA_ERR_TIMEOUT if a kernel that used this
  * workspace gave up its bounded wait for the down-projection (its y is then invalid; re-initialise

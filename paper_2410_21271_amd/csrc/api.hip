@@ -3,6 +3,7 @@
 #include "eora.h"
 #include "kernels.hpp"
 
+#include <atomic>
 #include <cstdio>
 #include <cstdlib>
 
@@ -209,7 +210,12 @@ int eora_workspace_init(void* workspace, size_t workspace_bytes, void* stream)
     // everything is cleared, not only the header: the tagged partials must not hold a leftover word
     // that reads as the tag of a coming launch
     if (workspace_bytes / 4 > 0x7fffffffull) return EORA_ERR_WORKSPACE;
-    if (failed(launch_clear_words((uint32_t*)workspace, (int)(workspace_bytes / 4), (hipStream_t)stream), "workspace_init"))
+    // The epoch does not start at 0: tags and flags are compared with epoch + 1, and memory that held a workspace
+    // before (freed and handed out again) may still sit in a cache with that incarnation's tags.  Every
+    // initialisation in this process starts from its own range of 2^20 epochs, so a tag never means two things.
+    static std::atomic<uint32_t> incarnation{0};
+    const uint32_t epoch0 = ((incarnation.fetch_add(1) + 1u) & 0xFFFu) << 20;
+    if (failed(launch_clear_words((uint32_t*)workspace, (int)(workspace_bytes / 4), epoch0, (hipStream_t)stream), "workspace_init"))
         return EORA_ERR_LAUNCH;
     return EORA_OK;
 }

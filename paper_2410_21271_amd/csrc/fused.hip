@@ -384,15 +384,16 @@ hipError_t launch_fused(const FusedArgs& a, int fm, int fa, int fe, hipStream_t 
     }
 }
 
-__global__ void clear_words_kernel(uint32_t* p, int nwords)
+// every word 0, except the epoch word, which starts at `epoch0`
+__global__ void clear_words_kernel(uint32_t* p, int nwords, uint32_t epoch0)
 {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < nwords) p[i] = 0u;
+    if (i < nwords) p[i] = i == HDR_EPOCH ? epoch0 : 0u;
 }
 
-hipError_t launch_clear_words(uint32_t* p, int nwords, hipStream_t stream)
+hipError_t launch_clear_words(uint32_t* p, int nwords, uint32_t epoch0, hipStream_t stream)
 {
-    hipLaunchKernelGGL(clear_words_kernel, dim3((nwords + 255) / 256), dim3(256), 0, stream, p, nwords);
+    hipLaunchKernelGGL(clear_words_kernel, dim3((nwords + 255) / 256), dim3(256), 0, stream, p, nwords, epoch0);
     return hipGetLastError();
 }
 

@@ -88,7 +88,7 @@ struct GroupArgs {
 // whether the shape fits the decode kernel, with its wavefront / quad split
 bool small_kernel_fits(int M, int d_in, int group, int* nw, int* nq);
 hipError_t launch_small(const GroupArgs& a, int fm, int fa, int fe, int nw, int nq, hipStream_t stream);
-hipError_t launch_clear_words(uint32_t* p, int nwords, hipStream_t stream);
+hipError_t launch_clear_words(uint32_t* p, int nwords, uint32_t epoch0, hipStream_t stream);
 
 struct SparseArgs {
     const _Float16* x;        // M x d_in fp16 row-major

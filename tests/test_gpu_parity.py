@@ -179,12 +179,15 @@ def test_workspace_is_reusable_without_clearing(gpu):
     big = QCase(21, 1024, 512, 16, 128, 4, packer=gpu)
     small = QCase(22, 256, 64, 3, 32, 3, packer=gpu)
     ws = gpu.new_workspace(16, 1024, 512, 128)
+    torch.cuda.synchronize()
+    e0 = int(ws[:4].view(torch.int32).cpu().numpy()[0])
+    assert e0 != 0 and e0 % (1 << 20) == 0        # every initialisation starts its own range of epochs
     y1 = run_linear_q(big, ws=ws)
     y2 = run_linear_q(small, ws=ws)
     y0 = run_linear_q(big, ws=ws, r=0)            # no low-rank path: does not touch the header
     y3 = run_linear_q(big, ws=ws)
     hdr = ws[:256].view(torch.int32).cpu().numpy()
-    assert hdr[0] == 3 and hdr[1] == 0            # epoch after three low-rank launches, no error
+    assert hdr[0] == e0 + 3 and hdr[1] == 0       # epoch after three low-rank launches, no error
     assert not ws[128:128 + 33 * 128].view(torch.int32).cpu().numpy().any()      # arrival counters back at zero
     assert np.array_equal(y1, y3)
     _check(y1, big.oracle_y())
