@@ -86,6 +86,18 @@ CALIBRATION = {
 }
 
 
+def dev(a):
+    """numpy array -> device tensor (uint32 words travel as int32)."""
+    import numpy as np
+    import torch
+    if a is None:
+        return None
+    a = np.ascontiguousarray(a)
+    if a.dtype == np.uint32:
+        return torch.from_numpy(a.view(np.int32)).cuda()
+    return torch.from_numpy(a).cuda()
+
+
 def algorithmic_bytes(d_in, d_out, M, r, w_bits, ab_bits, group=128, sq=False):
     """Bytes the method must move for one linear: packed codes, scales, zero-points, factors,
     x read once and y written once (the M x r intermediate never makes a y-sized round trip)."""
@@ -114,7 +126,6 @@ class Linear:
         import torch
         import synth
         import paper_2410_21271_amd as eora
-        from tests.gpu_util import dev
         self.name, self.d_in, self.d_out = name, d_in, d_out
         self.M, self.r, self.w_bits, self.ab_bits = spec["M"], spec["r"], spec["w_bits"], spec["ab_bits"]
         self.sq = bool(spec.get("sq", False))
@@ -214,9 +225,12 @@ class Group:
         eora.linear_q_group(m0.x, mem, m0.M, m0.d_in, m0.r, m0.w_bits, 128, m0.ab_bits, self.ws)
 
 
-def timed_graph(fn, count):
-    """Capture `count` calls fn(i) into one HIP graph, replay it once untimed and once between
-    two events on the launch stream; returns milliseconds per call."""
+BATCHES = 11
+
+
+def timed_graph(fn, count, batches=BATCHES):
+    """Capture `count` calls fn(i) into one HIP graph, replay it once untimed and then `batches` times, each
+    replay between two events on the launch stream; returns (median, min, max) milliseconds per call."""
     import torch
     g = torch.cuda.CUDAGraph()
     with torch.cuda.graph(g):
@@ -225,12 +239,89 @@ def timed_graph(fn, count):
     torch.cuda.synchronize()
     g.replay()
     torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    g.replay()
-    e1.record()
-    torch.cuda.synchronize()
-    return e0.elapsed_time(e1) / count
+    times = []
+    for _ in range(batches):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        times.append(e0.elapsed_time(e1) / count)
+    times.sort()
+    return times[len(times) // 2], times[0], times[-1]
+
+
+def parity_sample(linears, nblocks=6):
+    """Every linear of the step against the oracle on sampled 16-row blocks (first, last, seeded ones), all token
+    rows: the stored bytes of the sample are packed by the oracle's own packer from the logical arrays."""
+    import numpy as np
+    from oracle import layout, linear
+    worst = 0.0
+    for L in linears:
+        nb = L.d_out // 16
+        rng = np.random.default_rng(L.d_out + L.d_in)
+        blocks = sorted({0, nb - 1, *rng.integers(0, nb, nblocks).tolist()})
+        rows = np.concatenate([np.arange(16 * b, 16 * b + 16) for b in blocks])
+        codes, zeros, scales, A, B, x = L.logical
+        got = L.y.cpu().numpy()[:, rows]
+        n = len(rows)
+        if L.w_bits == 0:
+            Ap, Bp = (layout.pack_f16(A), layout.pack_f16(B[rows])) if L.r else (None, None)
+            if L.sq:
+                tiles, meta = layout.pack_sp24q4(codes[rows], zeros[rows], scales[0][rows], scales[1][rows], 128)
+                ref = linear.eora_linear_sp24q4(x, tiles, meta, Ap, Bp, L.M, L.d_in, n, L.r)
+            else:
+                values, indices = layout.pack_sp24(codes[rows], zeros[rows])
+                ref = linear.eora_linear_sp24(x, values, indices, Ap, Bp, L.M, L.d_in, n, L.r)
+        else:
+            qw = {4: layout.pack_q4, 3: layout.pack_q3, 2: layout.pack_q2}[L.w_bits](codes[rows])
+            qz, sc = layout.pack_zeros(zeros[rows]), layout.pack_scales(scales[rows])
+            Ap = Bp = As = Bs = None
+            if L.r and L.ab_bits == 16:
+                Ap, Bp = layout.pack_f16(A), layout.pack_f16(B[rows])
+            elif L.r and L.ab_bits == 3:
+                Ap, As = layout.pack_q3(A[0]), layout.pack_scales(A[1])
+                Bp, Bs = layout.pack_q3(B[0][rows]), layout.pack_scales(B[1][rows])
+            elif L.r:
+                Ap, As = layout.pack_q4(A[0], 128), layout.pack_scales(A[1])
+                Bp, Bs = layout.pack_q4(B[0][rows], min(128, L.r)), layout.pack_scales(B[1][rows])
+            if L.multi:
+                ref = linear.eora_linear_q_multi(x, qw, sc, qz, Ap, Bp, As, Bs, L.sel, L.M, L.d_in, n, L.r // L.multi, L.multi,
+                                                 L.w_bits, 128, L.ab_bits)
+            else:
+                ref = linear.eora_linear_q(x, qw, sc, qz, Ap, Bp, As, Bs, L.M, L.d_in, n, L.r, L.w_bits, 128, L.ab_bits)
+        worst = max(worst, linear.y_error(got, ref))
+    return worst
+
+
+def clocks():
+    """Clocks and power cap as rocm-smi reports them after the timed runs (best effort; None if unavailable)."""
+    import subprocess
+    try:
+        p = subprocess.run(["rocm-smi", "--showclocks", "--showmaxpower", "--json"], capture_output=True, text=True, timeout=20)
+        card = next(iter(json.loads(p.stdout).values()))
+        keep = {}
+        for k, v in card.items():
+            kl = k.lower()
+            if "sclk" in kl or "mclk" in kl or "fclk" in kl or "power" in kl:
+                keep[k] = v
+        return keep or None
+    except Exception:
+        return None
+
+
+def device_context(nbytes):
+    """Measured in this run, same protocol as the layer (graphs of 200 launches, median of BATCHES replays): the
+    launch floor (an empty kernel) and the rate of a kernel that only reads nbytes (rotating over > 1 GB)."""
+    import torch
+    import paper_2410_21271_amd as eora
+    sink = torch.zeros(256, dtype=torch.uint8, device="cuda")
+    floor_us = 1e3 * timed_graph(lambda i: eora.debug_probe(0, None, 0, sink), 200)[0]
+    nbytes = max(32768, int(nbytes) // 32768 * 32768)
+    ncop = max(2, int(1.1e9 // nbytes) + 1)
+    buf = torch.ones(ncop * nbytes, dtype=torch.uint8, device="cuda")
+    us = 1e3 * timed_graph(lambda i: eora.debug_probe(1, buf[(i % ncop) * nbytes:], nbytes, sink), 200)[0]
+    return round(floor_us, 3), round(nbytes / us / 1e3, 1), nbytes
 
 
 def cpu_baseline(linears, names):
@@ -292,7 +383,6 @@ def cpu_baseline(linears, names):
 
 def calibration_inputs(eora, synth, np, torch, seed, d_in, d_out, n_tokens, w_bits):
     """W (fp32), its compressed version from the library's own dequantisation, and X-tilde, all on the device."""
-    from tests.gpu_util import dev
     W, _, _, _ = synth.draw_layer(seed, d_in, d_out, 1, 0)
     codes, zeros, scales = synth.quantize_rtn(W, w_bits, 128)
     qw, qz, sc = eora.pack_q(codes, zeros, scales, w_bits, 128)
@@ -413,7 +503,11 @@ def main():
     shapes = synth.LLAMA3_8B if spec["model"] == "8b" else synth.LLAMA3_70B
     layer_bytes = sum(algorithmic_bytes(di, do, spec["M"], spec["r"], spec["w_bits"], spec["ab_bits"], sq=bool(spec.get("sq")))
                       for _, di, do in shapes)
-    ncopies = args.copies or max(2, int(1.2e9 / layer_bytes) + 1)
+    # enough copies that the whole layer rotates over 1.2 GB and, up to 8 GB in all, even its smallest launch
+    # over more than twice the 256 MB last-level cache
+    smallest = min(algorithmic_bytes(di, do, spec["M"], spec["r"], spec["w_bits"], spec["ab_bits"], sq=bool(spec.get("sq")))
+                   for n_, di, do in shapes if n_ in ("o", "down"))
+    ncopies = args.copies or max(2, int(1.2e9 / layer_bytes) + 1, min(int(600e6 / smallest) + 1, int(8e9 / layer_bytes)))
     if spec["M"] > 16:
         args.steps = min(args.steps, 50)
     linears = [Linear(n, di, do, spec, synth.seed_for(spec["cfg"], i), ncopies) for i, (n, di, do) in enumerate(shapes)]
@@ -430,15 +524,18 @@ def main():
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
-    ms_per_step = timed_graph(step, args.steps)
+    ms_per_step, ms_min, ms_max = timed_graph(step, args.steps)
 
     # each linear on its own (graph of back-to-back launches over the rotating copies)
     per_linear = {}
     for L in launches:
-        us = 1e3 * timed_graph(L.run, 200 if spec["M"] <= 16 else 40)
+        us = 1e3 * timed_graph(L.run, 200 if spec["M"] <= 16 else 40)[0]
         per_linear[L.name] = dict(us=round(us, 3), GBps=round(L.bytes / us / 1e3, 1),
                                   frac_hbm=round(L.bytes / us / 1e3 / HBM_PEAK_GBS, 4),
-                                  TFLOPs=round(L.flops / us / 1e6, 1))
+                                  TFLOPs=round(L.flops / us / 1e6, 1),
+                                  # alone, a launch rotates over its own copies only: below the 256 MB last-level
+                                  # cache (twice, to be safe) its figure may be cache-assisted; the layer's is not
+                                  rotation_MB=round(ncopies * L.bytes / 1e6, 1), cache_assisted=bool(ncopies * L.bytes < 512e6))
     # Dominant kernel: launches are grouped by the kernel instantiation that serves them (decode: one per
     # d_in, and a two-row-blocks-per-workgroup variant for single-token low-rank launches of more than
     # 1024 row blocks; prefill: one GEMM kernel); the group with the largest time per step is reported.
@@ -456,11 +553,15 @@ def main():
     dom = max(groups.values(), key=lambda g: sum(per_linear[L.name]["us"] for L in g))
     dom_bytes = sum(L.bytes for L in dom) / len(dom)
     dom_us = sum(per_linear[L.name]["us"] for L in dom) / len(dom)
-    traffic = None
+    # HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter runs of this workload (not
+    # collected in this run: counters and timing need runs of their own); null when no such run is recorded
+    traffic, traffic_source = None, None
     tpath = os.path.join(ROOT, "profiles", "decode_traffic.json")
     if os.path.exists(tpath):
         with open(tpath) as f:
             traffic = json.load(f).get(args.workload)
+        if traffic is not None:
+            traffic_source = "profiles/decode_traffic.json"
     prefill = spec["M"] >= 128
     if prefill:
         # dominant kernel: the GEMM kernel; a launch contracts one linear (or one group of them)
@@ -473,7 +574,9 @@ def main():
         roofline = dict(bound="hbm", achieved=round(dom_bytes / dom_us / 1e3, 1), peak=HBM_PEAK_GBS, unit="GB/s",
                         frac=round(dom_bytes / dom_us / 1e3 / HBM_PEAK_GBS, 4), traffic=traffic,
                         kernel="layer kernel instantiation of the d_in=%d launches (%s)" % (dom[0].d_in, ",".join(L.name for L in dom)),
-                        bytes_per_launch=int(dom_bytes), us_per_launch=round(dom_us, 3))
+                        bytes_per_launch=int(dom_bytes), us_per_launch=round(dom_us, 3), traffic_source=traffic_source)
+    floor_us, ceiling, probe_bytes = device_context(dom_bytes)
+    roofline.update(launch_floor_us=floor_us, stream_ceiling_GBps=ceiling, stream_probe_bytes=probe_bytes)
     layer_flops = sum(L.flops for L in linears)
     if prefill:
         out = dict(metric="prefill TFLOP/s over one 8B decoder layer's linears (M=%d)" % spec["M"],
@@ -485,14 +588,16 @@ def main():
                warmup=args.warmup, ms_per_step=round(ms_per_step, 6), higher_is_better=True, scaling="weak",
                vs_baseline=None, dtype="f16", data="synthetic",
                config=dict(workload=args.workload, layer_bytes=int(layer_bytes), layer_flops=int(layer_flops), weight_copies=ncopies,
-                           launches_per_step=len(launches),
-                           layer_us=round(1e3 * ms_per_step, 3), frac_hbm_peak=round(layer_bytes / ms_per_step / 1e6 / HBM_PEAK_GBS, 4),
+                           launches_per_step=len(launches), batches=BATCHES,
+                           layer_us=round(1e3 * ms_per_step, 3), layer_us_min=round(1e3 * ms_min, 3), layer_us_max=round(1e3 * ms_max, 3), frac_hbm_peak=round(layer_bytes / ms_per_step / 1e6 / HBM_PEAK_GBS, 4),
                            per_linear=per_linear),
                roofline=roofline)
+    out["config"]["clocks"] = clocks()
     if not args.no_cpu_baseline:
         base, worst = cpu_baseline(linears, ("q", "k", "v", "o", "gate") if spec["model"] == "8b" else ("k", "v"))
         out["cpu_baseline"] = base
-        out["config"]["max_err_vs_oracle"] = float("%.3g" % worst)
+        # every linear of the step on sampled row blocks, and the linears the baseline ran in full
+        out["config"]["max_err_vs_oracle"] = float("%.3g" % max(worst, parity_sample(linears)))
     print(json.dumps(out))
 
 

@@ -6,7 +6,7 @@
  * (arXiv 2410.21271, Sec. 3: forward equation "What X + B' A X", Algorithm 1 step 7; the paper
  * writes the column convention, this library the row convention: x is M x d_in, What is
  * d_out x d_in, A is r x d_in, B is d_out x r, y is M x d_out.)  What is the unmodified compressed
- * backbone weight (Sec. 2: "the compressed model's weights remain unchanged"), A and B the rank-r
+ * backbone weight (Sec. 2), A and B the rank-r
  * compensation factors produced offline by Algorithm 1 steps 1-6.
  *
  * General rules
@@ -120,9 +120,24 @@ int eora_workspace_init(void* workspace, size_t workspace_bytes, void* stream);
  * for are running and never wait themselves. */
 int eora_workspace_error(const void* workspace, void* stream);
 /* HOST, test hook: iterations of that bounded wait (process-wide; default 1 << 22, about a second).
- * 0 makes a wait give up at once if t is not ready yet, so that the error path can be exercised
- * with every kernel still terminating normally. */
+ * 0 makes a wait give up at once if t is not ready when it first looks.  A negative value makes every such
+ * wait count as expired without looking, so that the error path (EORA_ERR_TIMEOUT from eora_workspace_error,
+ * y without the low-rank term) can be exercised deterministically with every kernel still terminating
+ * normally. */
 void eora_debug_set_spin_limit(int iterations);
+/* HOST, test hook: writes into out (capacity bytes, NUL-terminated) the name and template parameters of the
+ * layer kernel the most recent forward launch of this process chose, e.g. "sparse_wide FA=5 NW=8 TB=4 VQ=0 n=1"
+ * (empty before the first launch), so that a test can assert that its shape reaches the instantiation it is
+ * meant to cover.  Process-wide, not synchronised with concurrent callers.  Errors: EORA_ERR_NULL. */
+int eora_debug_last_launch(char* out, size_t capacity);
+/* Measurement probes, enqueued on `stream` like a forward call, for quoting a layer kernel's time against what
+ * the device does with no arithmetic at all.  kind 0: an empty kernel of 256 workgroups (the launch floor; src
+ * and bytes ignored).  kind 1: a kernel that only reads `bytes` bytes from src (DEVICE, 16-byte aligned;
+ * 32 KiB per workgroup, every request of a workgroup in flight at once) and stores nothing: the streaming-read
+ * rate a launch of that size can reach.  sink: DEVICE, at least 256 bytes, 16-byte aligned (never written in
+ * practice).  Constraints: bytes > 0 and a multiple of 32768.  Errors: EORA_ERR_NULL / ALIGN / SHAPE /
+ * UNSUPPORTED (kind) / LAUNCH. */
+int eora_debug_probe(int kind, const void* src, size_t bytes, void* sink, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
  * Host-side packers: logical arrays (HOST pointers, row-major) -> stored bytes (HOST pointers).

@@ -57,6 +57,8 @@ def _load():
         "eora_workspace_init": (ci, [vp, sz, vp]),
         "eora_workspace_error": (ci, [vp, vp]),
         "eora_debug_set_spin_limit": (None, [ci]),
+        "eora_debug_last_launch": (ci, [ctypes.c_char_p, sz]),
+        "eora_debug_probe": (ci, [ci, vp, sz, vp, vp]),
         "eora_pack_q": (ci, [vp, vp, vp, ci, ci, ci, ci, vp, vp, vp]),
         "eora_pack_factor_f16": (ci, [vp, ci, ci, vp]),
         "eora_pack_factor_q4": (ci, [vp, vp, ci, ci, vp, vp]),
@@ -92,7 +94,8 @@ EXPORTS = ["eora_status_string", "eora_qweight_bytes", "eora_qzeros_bytes", "eor
            "eora_pack_factor_f16", "eora_pack_factor_q4", "eora_pack_sp24", "eora_linear_q",
            "eora_linear_q_group", "eora_linear_sp24", "eora_unpack_q", "eora_dequant_q", "eora_expand_sp24",
            "eora_sp24q4_tiles_bytes", "eora_sp24q4_meta_bytes", "eora_pack_sp24q4", "eora_linear_sp24q4", "eora_expand_sp24q4",
-           "eora_factors_workspace_bytes", "eora_factors", "eora_linear_q_multi", "eora_pack_factor_q3", "eora_factors_store_f16", "eora_factors_store_q", "eora_linear_sp24_group"]
+           "eora_factors_workspace_bytes", "eora_factors", "eora_linear_q_multi", "eora_pack_factor_q3", "eora_factors_store_f16", "eora_factors_store_q", "eora_linear_sp24_group",
+           "eora_debug_last_launch", "eora_debug_probe"]
 
 
 def status_string(status):
@@ -240,6 +243,18 @@ def workspace_error(workspace):
 
 def debug_set_spin_limit(iterations):
     lib.eora_debug_set_spin_limit(int(iterations))
+
+
+def debug_last_launch():
+    """Name and template parameters of the layer kernel the most recent forward launch chose (a string)."""
+    buf = ctypes.create_string_buffer(160)
+    _check(lib.eora_debug_last_launch(buf, len(buf)), "debug_last_launch")
+    return buf.value.decode()
+
+
+def debug_probe(kind, src, nbytes, sink):
+    """kind 0: empty launch; kind 1: streaming read of nbytes from src.  Enqueued on the current stream."""
+    _check(lib.eora_debug_probe(int(kind), _dp(src), int(nbytes), _dp(sink), _stream()), "debug_probe")
 
 
 def workspace_bytes_group(M, d_in, r, n_members):

@@ -22,8 +22,19 @@ def _hipcc():
     raise RuntimeError("hipcc not found")
 
 
+def _fresh(obj, src):
+    """EORA_INCREMENTAL=1 (development): keep an object that is newer than its source and every header."""
+    if not os.environ.get("EORA_INCREMENTAL") or os.environ.get("EORA_EXTRA_FLAGS") or not os.path.exists(obj):
+        return False
+    deps = [os.path.join(CSRC, src)] + [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".hpp")]
+    deps += [os.path.join(ROOT, "include", f) for f in os.listdir(os.path.join(ROOT, "include"))]
+    return all(os.path.getmtime(d) < os.path.getmtime(obj) for d in deps)
+
+
 def _compile(src):
     obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
+    if _fresh(obj, src):
+        return obj
     cmd = [_hipcc(), *FLAGS, "-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj]
     p = subprocess.run(cmd, capture_output=True, text=True)
     if p.returncode:

@@ -7,6 +7,17 @@
 #include <cstdio>
 #include <cstdlib>
 
+namespace eora {
+
+namespace {
+struct LaunchNote { const char* fmt; int v[6]; };
+LaunchNote g_last_launch = {nullptr, {0, 0, 0, 0, 0, 0}};
+}  // namespace
+
+void note_launch(const char* fmt, int a, int b, int c, int d, int e, int f) { g_last_launch = {fmt, {a, b, c, d, e, f}}; }
+
+}  // namespace eora
+
 namespace {
 
 using namespace eora;
@@ -33,7 +44,8 @@ int check_backbone_shape(int M, int d_in, int d_out, int r)
 bool failed(hipError_t e, const char* what)
 {
     if (e == hipSuccess) return false;
-    if (getenv("EORA_VERBOSE")) fprintf(stderr, "eora: %s: %s\n", what, hipGetErrorString(e));
+    static const bool verbose = getenv("EORA_VERBOSE") != nullptr;      // read once per process
+    if (verbose) fprintf(stderr, "eora: %s: %s\n", what, hipGetErrorString(e));
     return true;
 }
 
@@ -231,7 +243,35 @@ int eora_workspace_error(const void* workspace, void* stream)
     return flag ? EORA_ERR_TIMEOUT : EORA_OK;
 }
 
-void eora_debug_set_spin_limit(int iterations) { g_spin_limit = iterations < 0 ? 0 : iterations; }
+void eora_debug_set_spin_limit(int iterations) { g_spin_limit = iterations < 0 ? -1 : iterations; }
+
+int eora_debug_probe(int kind, const void* src, size_t bytes, void* sink, void* stream)
+{
+    if (!sink) return EORA_ERR_NULL;
+    if (!aligned16(sink)) return EORA_ERR_ALIGN;
+    if (kind == 0) {
+        if (failed(launch_probe_empty((uint32_t*)sink, (hipStream_t)stream), "probe (empty)")) return EORA_ERR_LAUNCH;
+        return EORA_OK;
+    }
+    if (kind != 1) return EORA_ERR_UNSUPPORTED;
+    if (!src) return EORA_ERR_NULL;
+    if (!aligned16(src)) return EORA_ERR_ALIGN;
+    if (bytes == 0 || bytes % 32768 || bytes / 32768 > 0x7fffffffull) return EORA_ERR_SHAPE;
+    if (failed(launch_probe_stream(src, bytes, (uint32_t*)sink, (hipStream_t)stream), "probe (stream)")) return EORA_ERR_LAUNCH;
+    return EORA_OK;
+}
+
+int eora_debug_last_launch(char* out, size_t capacity)
+{
+    if (!out || capacity == 0) return EORA_ERR_NULL;
+    const LaunchNote n = g_last_launch;
+    if (!n.fmt) {
+        out[0] = 0;
+        return EORA_OK;
+    }
+    snprintf(out, capacity, n.fmt, n.v[0], n.v[1], n.v[2], n.v[3], n.v[4], n.v[5]);
+    return EORA_OK;
+}
 
 // every check of one quantised layer; nothing is enqueued
 static int validate_linear_q(const void* x, const eora_q_member& e, int M, int d_in, int r, int w_bits, int group,

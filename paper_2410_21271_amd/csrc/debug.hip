@@ -152,4 +152,38 @@ hipError_t launch_expand_sp24q4(const uint32_t* qtiles, const uint32_t* qmeta, f
     return hipGetLastError();
 }
 
+// ---- measurement probes: what a launch costs and what a pure read of n bytes reaches on this device ----------
+typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+
+__global__ void probe_empty_kernel(uint32_t* sink)
+{
+    if (sink == nullptr && threadIdx.x == 4096) sink[0] = 1u;      // never true: the kernel does nothing
+}
+
+// every workgroup of 256 threads reads 32 KiB: eight 16-byte loads per lane, all in flight at once; the result
+// is consumed without being stored (the store's condition never holds for data that is not all-ones patterns)
+__global__ __launch_bounds__(256) void probe_stream_kernel(const u4* __restrict__ src, uint32_t* sink)
+{
+    const u4* p = src + (size_t)blockIdx.x * 2048 + threadIdx.x;
+    u4 v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = p[u * 256];
+    u4 acc = v[0];
+#pragma unroll
+    for (int u = 1; u < 8; ++u) acc ^= v[u];
+    if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x9E3779B9u && acc[0] == 0x7F4A7C15u) sink[blockIdx.x & 63] = 1u;
+}
+
+hipError_t launch_probe_empty(uint32_t* sink, hipStream_t stream)
+{
+    hipLaunchKernelGGL(probe_empty_kernel, dim3(256), dim3(256), 0, stream, sink);
+    return hipGetLastError();
+}
+
+hipError_t launch_probe_stream(const void* src, size_t bytes, uint32_t* sink, hipStream_t stream)
+{
+    hipLaunchKernelGGL(probe_stream_kernel, dim3((unsigned)(bytes / 32768)), dim3(256), 0, stream, (const u4*)src, sink);
+    return hipGetLastError();
+}
+
 }  // namespace eora

@@ -199,7 +199,7 @@ __global__ __launch_bounds__(NW * 64) void fused_kernel(FusedArgs a)
     if constexpr (LOWRANK) {
         const uint32_t* flags = a.hdr + HDR_FLAGS0 + HDR_FLAGS_PER_BLOCK * yb;
         if (wave == 0) {
-            bool ok = units <= 64 && __all(early == epoch + 1);
+            bool ok = a.spin_limit >= 0 && units <= 64 && __all(early == epoch + 1);      // a negative limit: every wait counts as expired (test hook)
             for (int spins = 0; !ok && spins <= a.spin_limit; ++spins) {
                 bool all = true;
                 for (int f = lane; f < units; f += 64) all = all && (ld_relaxed(&flags[f]) == epoch + 1);
@@ -337,6 +337,7 @@ static hipError_t launch_one(const FusedArgs& a, dim3 grid, size_t lds, hipStrea
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
+    note_launch("fused FM=%d FA=%d RB=%d NW=%d XLDS=%d", FM, FA, RB, NW, (int)XLDS);
     hipLaunchKernelGGL(kern, grid, dim3(NW * 64), lds, stream, a);
     return hipGetLastError();
 }

@@ -28,6 +28,11 @@ constexpr int HDR_FLAGS_REPLICA_STRIDE = HDR_FLAGS_PER_BLOCK * MAX_YBLOCKS;
 constexpr int HDR_WORDS = HDR_FLAGS0 + HDR_FLAGS_REPLICA_STRIDE * HDR_FLAG_REPLICAS;
 constexpr int MAX_KCN = 8;                      // k-ranges of the down-projection
 
+// Host-side record of the kernel instantiation the most recent layer launch of this process chose, read
+// back through eora_debug_last_launch() (tests assert that a shape reaches the instantiation it is meant to
+// cover).  `fmt` is a printf format for up to six ints and must be a string literal.  Not synchronised.
+void note_launch(const char* fmt, int a = 0, int b = 0, int c = 0, int d = 0, int e = 0, int f = 0);
+
 struct FusedArgs {
     const _Float16* x;        // M x d_in fp16 row-major
     const void* w;            // backbone tiles
@@ -153,5 +158,9 @@ hipError_t launch_dequant_q(const uint32_t* qweight, const _Float16* scales, con
 hipError_t launch_expand_sp24(const _Float16* values, const uint32_t* indices, _Float16* W,
                               int d_in, int d_out, hipStream_t stream);
 hipError_t launch_expand_sp24q4(const uint32_t* qtiles, const uint32_t* qmeta, float* W, int d_in, int d_out, hipStream_t stream);
+
+// measurement probes (debug.hip): an empty launch, and a pure streaming read of `bytes` (a multiple of 32 KiB)
+hipError_t launch_probe_empty(uint32_t* sink, hipStream_t stream);
+hipError_t launch_probe_stream(const void* src, size_t bytes, uint32_t* sink, hipStream_t stream);
 
 }  // namespace eora

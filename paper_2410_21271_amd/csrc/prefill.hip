@@ -375,6 +375,7 @@ static hipError_t launch_pf(const PrefillArgs& a, hipStream_t stream)
     int ntn = 0;
     for (int m = 0; m < a.n; ++m) ntn += (a.N[m] + PF_BN - 1) / PF_BN;
     const int ntm = (a.M + PF_BM - 1) / PF_BM;
+    note_launch("prefill FM=%d EXT=%d ksplit=%d n=%d", FM, (int)EXT, a.ksplit, a.n);
     hipLaunchKernelGGL(kern, dim3(ntn * ntm * (EXT ? 1 : a.ksplit)), dim3(PF_NT), PF_LDS, stream, a);
     return hipGetLastError();
 }

@@ -16,8 +16,6 @@
 // t split into a high and a low fp16 part.  Producers come first in dispatch order and never wait.
 #include "segments.hpp"
 
-#include <cstdlib>
-
 namespace eora {
 
 constexpr int XSTAGE = 4;   // 16-byte chunks of x a thread may stage
@@ -278,7 +276,7 @@ __global__ __launch_bounds__(NW * 64, (16 + NW - 1) / NW) void small_kernel(Grou
         if (wave == 0) {
             // the units of this workgroup's own member only
             const uint32_t* flags = a.hdr + HDR_FLAGS0 + HDR_FLAGS_REPLICA_STRIDE * (blockIdx.x % HDR_FLAG_REPLICAS) + mem * upl;
-            bool ok = upl <= 64 && __all(early == epoch + 1);
+            bool ok = a.spin_limit >= 0 && upl <= 64 && __all(early == epoch + 1);      // a negative limit: every wait counts as expired (test hook)
             for (int spins = 0; !ok && spins <= a.spin_limit; ++spins) {
                 bool all = true;
                 for (int f = lane; f < upl; f += 64) all = all && (ld_relaxed(&flags[f]) == epoch + 1);
@@ -409,6 +407,7 @@ static hipError_t launch_small_m(const GroupArgs& a, hipStream_t stream)
     }
     int blocks = (FA != S_NONE) ? (a.r / 16) * a.kcn * a.n : 0;     // producers first
     for (int m = 0; m < a.n; ++m) blocks += a.d_out[m] / (16 * RB);
+    note_launch("small FM=%d FA=%d NW=%d NQ=%d RB=%d n=%d", FM, FA, NW, NQ, RB, a.n);
     hipLaunchKernelGGL(kern, dim3(blocks), dim3(NW * 64), lds, stream, a);
     return hipGetLastError();
 }
@@ -466,17 +465,6 @@ bool small_kernel_fits(int M, int d_in, int group, int* nw, int* nq)
     if (M < 1 || M > 4 || group != 128 || d_in % 512) return false;
     const int Q = d_in / 512;
     static const int table[][2] = {{4, 2}, {7, 4}, {8, 2}, {14, 4}, {4, 1}, {8, 1}, {14, 2}, {16, 1}};   // first match wins
-    const char* force = getenv("EORA_SMALL_NW");         // experiment knob: preferred wavefront count
-    const int want = force ? atoi(force) : 0;
-    if (want) {
-        for (const auto& t : table) {
-            if (t[0] == want && t[0] * t[1] == Q && (size_t)M * (d_in / 8) <= (size_t)XSTAGE * t[0] * 64) {
-                *nw = t[0];
-                *nq = t[1];
-                return true;
-            }
-        }
-    }
     for (const auto& t : table) {
         if (t[0] * t[1] == Q && (size_t)M * (d_in / 8) <= (size_t)XSTAGE * t[0] * 64) {
             *nw = t[0];

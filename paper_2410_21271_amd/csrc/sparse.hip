@@ -13,8 +13,8 @@
 //
 // Launch structure, flag protocol and the low-rank continuation are those of the decode kernel:
 // producer workgroups first (one unit of t = x.A^T each, per token block), then one consumer
-// workgroup per (16 output rows, token block of 16).  For 1..4 tokens x is staged in LDS by direct
-// global-to-LDS loads (no registers); otherwise the fragments come from global memory.
+// workgroup per (16 output rows, token block of 16).  For 1..4 tokens x is staged in LDS through registers
+// (plain loads only); otherwise the fragments come from global memory.
 #include "segments.hpp"
 
 namespace eora {
@@ -248,7 +248,7 @@ __device__ __forceinline__ void sparse_body(const SparseArgs& a, const int gbid,
         const uint32_t epoch = s_epoch;
         if (wave == 0) {
             const uint32_t* flags = a.hdr + HDR_FLAGS0 + HDR_FLAGS_REPLICA_STRIDE * (blockIdx.x % HDR_FLAG_REPLICAS) + HDR_FLAGS_PER_BLOCK * yb + flag0;
-            bool ok = units <= 64 && __all(early == epoch + 1);
+            bool ok = a.spin_limit >= 0 && units <= 64 && __all(early == epoch + 1);      // a negative limit: every wait counts as expired (test hook)
             for (int spins = 0; !ok && spins <= a.spin_limit; ++spins) {
                 bool all = true;
                 for (int f = lane; f < units; f += 64) all = all && (ld_relaxed(&flags[f]) == epoch + 1);
@@ -682,6 +682,7 @@ static hipError_t launch_sparse_wide(const SparseArgs* members, int n, hipStream
     const int yblocks = (a.M + 15) / 16;
     const int units = (FA != S_NONE) ? (a.r / 16) * a.kcn : 0;
     auto blocks = [&](const SparseArgs& m) { return ((m.d_out / 16 + NW - 1) / NW) * ((yblocks + TB - 1) / TB) + units * yblocks; };
+    note_launch("sparse_wide FA=%d NW=%d TB=%d VQ=%d n=%d", FA, NW, TB, (int)VQ, n);
     if (n == 1) {
         auto kern = sparse_wide_kernel<FA, NW, TB, XW_D, VQ>;
         if (lds > 48 * 1024) {
@@ -709,12 +710,11 @@ static hipError_t launch_sparse_wide_cfg(const SparseArgs* members, int n, int n
         if (tb == 2) return launch_sparse_wide<FA, 8, 2, 4, VQ>(members, n, stream);
         return launch_sparse_wide<FA, 8, 4, 4, VQ>(members, n, stream);
     }
-    switch (tb) {
-    case 1: return launch_sparse_wide<FA, 4, 1, 4, VQ>(members, n, stream);
-    case 2: return launch_sparse_wide<FA, 4, 2, 4, VQ>(members, n, stream);
-    case 3: return launch_sparse_wide<FA, 4, 3, 4, VQ>(members, n, stream);
-    default: return launch_sparse_wide<FA, 4, 4, 4, VQ>(members, n, stream);
-    }
+    // four row blocks: one or two token blocks (with three or four of them the eight-row-block split above
+    // always has its 192 workgroups too, and comes first)
+    if (tb == 2) return launch_sparse_wide<FA, 4, 2, 4, VQ>(members, n, stream);
+    if (tb == 1) return launch_sparse_wide<FA, 4, 1, 4, VQ>(members, n, stream);
+    return hipErrorInvalidValue;
 }
 
 template <int FA, int FE, int NW, bool XLDS, bool VQ>
@@ -726,6 +726,7 @@ static hipError_t launch_sparse_one(const SparseArgs* members, int n, hipStream_
     const int yblocks = (a.M + 15) / 16;
     const int units = (FA != S_NONE) ? (a.r / 16) * a.kcn : 0;
     auto blocks = [&](const SparseArgs& m) { return (m.d_out / 16) * yblocks + units * yblocks; };
+    note_launch("sparse FA=%d NW=%d XLDS=%d VQ=%d n=%d", FA, NW, (int)XLDS, (int)VQ, n);
     if (n == 1) {
         auto kern = sparse_kernel<FA, FE, NW, XLDS, VQ>;
         if (lds > 48 * 1024) {

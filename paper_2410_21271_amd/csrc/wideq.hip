@@ -251,7 +251,7 @@ __device__ __forceinline__ void wide_q_body(const FusedArgs& a, const int gbid, 
         const uint32_t epoch = s_epoch;
         if (wave == 0) {
             bool ok = true;
-            const bool seen = TB == 1 && units <= 64 && __all(early == epoch + 1);
+            const bool seen = a.spin_limit >= 0 && TB == 1 && units <= 64 && __all(early == epoch + 1);   // a negative limit: every wait counts as expired (test hook)
 #pragma unroll
             for (int tb = 0; tb < TB; ++tb) {
                 const int yb = tg * TB + tb;
@@ -478,6 +478,7 @@ static hipError_t launch_wide_one(const FusedArgs* members, int n, hipStream_t s
     const FusedArgs& a = members[0];
     const size_t xb = (size_t)NWK * 2 * TB * 4096, tb = (size_t)16 * a.r * 4;
     const size_t lds = xb > tb ? xb : tb;
+    note_launch("wide_q FM=%d FA=%d NWR=%d NWK=%d TB=%d n=%d", FM, FA, NWR, NWK, TB, n);
     if (n == 1) {
         auto kern1 = wide_q_kernel<FM, FA, FE, NWR, NWK, TB>;
         if (lds > 48 * 1024) {

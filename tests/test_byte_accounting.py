@@ -14,6 +14,9 @@ def _factor_bytes(r, bits):
     for _, d_in, d_out in synth.LLAMA3_8B:
         if bits == 16:
             total += 2 * r * (d_in + d_out)
+        elif bits == 3:                                              # 3.0 bits per element, one fp16 scale per group of 128
+            total += r * d_in * 3 // 8 + 2 * r * (d_in // 128)
+            total += d_out * r * 3 // 8 + 2 * d_out * (r // 128)
         else:
             KTb = min(128, r)
             total += r * d_in // 2 + 2 * r * (d_in // 128)          # A codes + scales
@@ -33,6 +36,11 @@ def test_factor_bytes_match_paper_size_deltas():
             continue
         delta = size - rows[(bb, 0, 0)]
         ours = _factor_bytes(r, bits) / 2 ** 30       # the table's unit fits GiB: rank 512 fp16 is 2.50 exactly
+        if bits == 3:
+            # the paper does not give its 3-bit storage; its deltas (0.11-0.12 at rank 128, 0.52-0.55 at rank 512)
+            # come to about 3.5 bits per element, this project's tiles hold 3.0 bits plus one fp16 scale per 128
+            assert abs(ours - delta) <= 0.015 + 0.12 * delta and ours <= delta + 0.015, (bb, r, bits, ours, delta)
+            continue
         assert abs(ours - delta) <= 0.03 + 0.03 * delta, (bb, r, bits, ours, delta)
 
 

@@ -196,23 +196,47 @@ def test_workspace_is_reusable_without_clearing(gpu):
     assert gpu.workspace_error(ws) == 0
 
 
-def test_bounded_wait_gives_up_cleanly(gpu):
-    """With a spin limit of 0 a wavefront that finds t not ready yet gives up at once: the kernel
-    still terminates, the workspace reports the timeout, and after re-initialisation it works again."""
+@pytest.mark.parametrize("M,d_in,d_out", [(1, 4096, 1024), (16, 2048, 8192), (37, 640, 112)])
+def test_bounded_wait_gives_up_cleanly(gpu, M, d_in, d_out):
+    """With a negative spin limit every wait for t counts as expired: the kernel still terminates, y lacks the
+    low-rank term (so it differs from the oracle), the workspace reports the timeout, and after
+    re-initialisation the same workspace works again.  (Decode kernel, the kernel for 5..127 tokens, and the
+    general one.)"""
+    from oracle import linear
+    from tests.cases import QCase
+    from tests.gpu_util import run_linear_q
+    c = QCase(23 + M, d_in, d_out, M, 128, 4, packer=gpu)
+    ws = gpu.new_workspace(M, d_in, d_out, 128)
+    gpu.debug_set_spin_limit(-1)
+    try:
+        y = run_linear_q(c, ws=ws)
+        status = gpu.workspace_error(ws)
+    finally:
+        gpu.debug_set_spin_limit(1 << 22)
+    assert status == -8
+    assert linear.y_error(y, c.oracle_y()) > 2e-3            # the result of an expired wait is not the layer's
+    _check(y, c.oracle_y(r=0))                               # it is the bare backbone's
+    gpu.workspace_init(ws)
+    _check(run_linear_q(c, ws=ws), c.oracle_y())
+    assert gpu.workspace_error(ws) == 0
+
+
+def test_spin_limit_zero_never_hangs(gpu):
+    """A spin limit of 0 (give up if t is not ready at the first look) ends either way; when it reports no
+    timeout the result is the layer's."""
     from tests.cases import QCase
     from tests.gpu_util import run_linear_q
     c = QCase(23, 4096, 1024, 1, 128, 4, packer=gpu)
     ws = gpu.new_workspace(1, 4096, 1024, 128)
     gpu.debug_set_spin_limit(0)
     try:
-        run_linear_q(c, ws=ws)
+        y = run_linear_q(c, ws=ws)
         status = gpu.workspace_error(ws)
     finally:
         gpu.debug_set_spin_limit(1 << 22)
     assert status in (0, -8)
-    gpu.workspace_init(ws)
-    _check(run_linear_q(c, ws=ws), c.oracle_y())
-    assert gpu.workspace_error(ws) == 0
+    if status == 0:
+        _check(y, c.oracle_y())
 
 
 def test_mid_size_token_counts(gpu):

@@ -152,4 +152,19 @@ def test_stored_quantised_factors_dequantise_to_the_quantiser_values():
         zp = 1 << (bits - 1)
         want = (ca.astype(np.float64) - zp) * np.repeat(sa.astype(np.float64), 128, axis=1)
         assert np.array_equal(deq(Aq, As, 128, 256), want)
-        assert deq(Bq, Bs, 32, 128).shape == (32, 128)
+        cb, sb = calibrate.quantize_factor(B, bits)
+        want_b = (cb.astype(np.float64) - zp) * np.repeat(sb.astype(np.float64), 128, axis=1)
+        assert np.array_equal(deq(Bq, Bs, 32, 128), want_b)
+        # B is quantised along the rank: its largest entry of a row is hit exactly by the top code (|code - zp| = qpos)
+        assert np.all(np.abs(cb.astype(np.int64) - zp).max(axis=1) == zp - 1)
+        assert np.max(np.abs(want_b - B)) <= float(sb.max()) * 0.504
+    # rank 64 with 4 bits: B's groups are 64 columns wide (one scale per row), stored as 64-column tiles
+    B64, A64 = rng.standard_normal((32, 64)) * 0.5, rng.standard_normal((64, 256)) * 0.1
+    Aq, As, Bq, Bs = calibrate.store_factors_q(B64, A64, 4, balance=False)
+    cb, sb = calibrate.quantize_factor(B64, 4)
+    assert sb.shape == (32, 1) and np.asarray(Bs).size == 32
+    want_b = (cb.astype(np.float64) - 8) * sb.astype(np.float64)
+    assert np.array_equal(linear.dequant_factor_q4(Bq, Bs, 32, 64), want_b)
+    # hand value: row of B64 with largest magnitude m gets scale fp16(m / 7) and that entry the code 8 +- 7
+    i, j = np.unravel_index(np.argmax(np.abs(B64)), B64.shape)
+    assert float(sb[i, 0]) == float(np.float16(abs(B64[i, j]) / 7)) and cb[i, j] == (15 if B64[i, j] > 0 else 1)
