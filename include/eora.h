@@ -191,6 +191,21 @@ int eora_linear_q(const void* x, const void* qweight, const void* scales, const 
                   void* y, int M, int d_in, int d_out, int r, int w_bits, int group, int ab_bits,
                   void* workspace, size_t workspace_bytes, void* stream);
 
+/* eora_linear_q for callers that cannot allocate device memory or pass a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): same arguments without the workspace, same
+ * kernels, bit-identical results.  The workspace is an array inside the library's device code (3.3 MiB on every
+ * GPU the library runs on, held until the process ends), found once per device with hipGetSymbolAddress and
+ * cleared once, on the first call's stream; the call allocates nothing.
+ * Limit: M <= 127 (EORA_ERR_WORKSPACE beyond: the many-token path needs scratch that grows with M); all other
+ * constraints and errors as eora_linear_q.  Every call on a GPU shares that GPU's array: calls that may overlap
+ * in time on one GPU (different streams without ordering between them) race and must use eora_linear_q with
+ * workspaces of their own; so must a second call whose stream is not ordered after the first call's stream
+ * (which carries the one-time clearing). */
+int eora_linear_q_static(const void* x, const void* qweight, const void* scales, const void* qzeros,
+                         const void* A, const void* B, const void* A_scales, const void* B_scales,
+                         void* y, int M, int d_in, int d_out, int r, int w_bits, int group, int ab_bits,
+                         void* stream);
+
 /* Several layers that read the SAME x in one launch: the query / key / value projections, or the
  * gate / up projections, of a decoder layer (the paper compensates every linear of the model the
  * same way, Sec. 3; which of them share an input is the transformer's structure).  Member m is an

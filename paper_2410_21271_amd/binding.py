@@ -66,6 +66,7 @@ def _load():
         "eora_pack_sp24": (ci, [vp, vp, ci, ci, vp, vp]),
         "eora_pack_sp24q4": (ci, [vp, vp, vp, vp, ci, ci, ci, vp, vp]),
         "eora_linear_q": (ci, [vp] * 9 + [ci] * 7 + [vp, sz, vp]),
+        "eora_linear_q_static": (ci, [vp] * 9 + [ci] * 7 + [vp]),
         "eora_linear_q_multi": (ci, [vp] * 10 + [ci] * 8 + [vp, sz, vp]),
         "eora_linear_q_group": (ci, [vp, ctypes.POINTER(QMember), ci] + [ci] * 6 + [vp, sz, vp]),
         "eora_linear_sp24_group": (ci, [vp, ctypes.POINTER(SpMember), ci, ci, ci, ci, vp, sz, vp]),
@@ -95,7 +96,7 @@ EXPORTS = ["eora_status_string", "eora_qweight_bytes", "eora_qzeros_bytes", "eor
            "eora_linear_q_group", "eora_linear_sp24", "eora_unpack_q", "eora_dequant_q", "eora_expand_sp24",
            "eora_sp24q4_tiles_bytes", "eora_sp24q4_meta_bytes", "eora_pack_sp24q4", "eora_linear_sp24q4", "eora_expand_sp24q4",
            "eora_factors_workspace_bytes", "eora_factors", "eora_linear_q_multi", "eora_pack_factor_q3", "eora_factors_store_f16", "eora_factors_store_q", "eora_linear_sp24_group",
-           "eora_debug_last_launch", "eora_debug_probe"]
+           "eora_debug_last_launch", "eora_debug_probe", "eora_linear_q_static"]
 
 
 def status_string(status):
@@ -276,6 +277,12 @@ def linear_q(x, qweight, scales, qzeros, A, B, A_scales, B_scales, y, M, d_in, d
     _check(lib.eora_linear_q(_dp(x), _dp(qweight), _dp(scales), _dp(qzeros), _dp(A), _dp(B), _dp(A_scales),
                              _dp(B_scales), _dp(y), M, d_in, d_out, r, w_bits, group, ab_bits,
                              _dp(workspace), ws_bytes, _stream()), "linear_q")
+
+
+def linear_q_static(x, qweight, scales, qzeros, A, B, A_scales, B_scales, y, M, d_in, d_out, r, w_bits, group, ab_bits):
+    _check(lib.eora_linear_q_static(_dp(x), _dp(qweight), _dp(scales), _dp(qzeros), _dp(A), _dp(B), _dp(A_scales),
+                                    _dp(B_scales), _dp(y), M, d_in, d_out, r, w_bits, group, ab_bits, _stream()),
+           "linear_q_static")
 
 
 def linear_q_group(x, members, M, d_in, r, w_bits, group, ab_bits, workspace):

@@ -6,6 +6,7 @@
 #include <atomic>
 #include <cstdio>
 #include <cstdlib>
+#include <mutex>
 
 namespace eora {
 
@@ -357,6 +358,57 @@ int eora_linear_q(const void* x, const void* qweight, const void* scales, const 
     const int rc = validate_linear_q(x, e, M, d_in, r, w_bits, group, ab_bits, workspace, workspace_bytes, &fa, &fe);
     if (rc != EORA_OK) return rc;
     return run_linear_q(x, e, M, d_in, r, w_bits, group, ab_bits, fa, fe, workspace, stream);
+}
+
+// ---- the same layer for callers that cannot allocate ---------------------------------------------------------
+namespace {
+// Workspace of eora_linear_q_static: one array per GPU the library's code is loaded on, held until the process
+// ends.  Its size is that of eora_workspace_bytes() for any call below PREFILL_MIN_TOKENS tokens (header, tagged
+// partials, fp32 partials).  In host code the array's name is only a handle for hipGetSymbolAddress: the device
+// address it yields (per device) is what kernels and the clearing launch are given.
+constexpr size_t STATIC_SCRATCH_BYTES = WS_T;
+__device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[MAX_DEVICES] = {};
+bool g_scratch_cleared[MAX_DEVICES] = {};
+
+// the current device's array, cleared (enqueued on `stream`) the first time it is handed out
+int static_scratch(void** out, hipStream_t stream)
+{
+    int device = -1;
+    if (hipGetDevice(&device) != hipSuccess || device < 0 || device >= MAX_DEVICES) return EORA_ERR_LAUNCH;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[device]) {
+        void* p = nullptr;
+        if (failed(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)), "static scratch address") || !p) return EORA_ERR_LAUNCH;
+        g_scratch_ptr[device] = p;
+    }
+    if (!g_scratch_cleared[device]) {
+        const int rc = eora_workspace_init(g_scratch_ptr[device], STATIC_SCRATCH_BYTES, stream);
+        if (rc != EORA_OK) return rc;
+        g_scratch_cleared[device] = true;
+    }
+    *out = g_scratch_ptr[device];
+    return EORA_OK;
+}
+}  // namespace
+
+int eora_linear_q_static(const void* x, const void* qweight, const void* scales, const void* qzeros,
+                         const void* A, const void* B, const void* A_scales, const void* B_scales,
+                         void* y, int M, int d_in, int d_out, int r, int w_bits, int group, int ab_bits, void* stream)
+{
+    if (M >= PREFILL_MIN_TOKENS) return EORA_ERR_WORKSPACE;       // the many-token path needs scratch that grows with M
+    const eora_q_member e{qweight, scales, qzeros, A, B, A_scales, B_scales, y, d_out};
+    int fa, fe;
+    // every check before the array is touched (a placeholder stands in for the workspace pointer)
+    int rc = validate_linear_q(x, e, M, d_in, r, w_bits, group, ab_bits, x, STATIC_SCRATCH_BYTES, &fa, &fe);
+    if (rc != EORA_OK) return rc;
+    if (M == 0) return EORA_OK;
+    void* ws = nullptr;
+    rc = static_scratch(&ws, (hipStream_t)stream);
+    if (rc != EORA_OK) return rc;
+    return run_linear_q(x, e, M, d_in, r, w_bits, group, ab_bits, fa, fe, ws, stream);
 }
 
 int eora_linear_q_multi(const void* x, const void* qweight, const void* scales, const void* qzeros,
