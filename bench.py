@@ -476,6 +476,10 @@ def main():
     ap.add_argument("--workload", default=DEFAULT, choices=sorted(WORKLOADS) + sorted(CALIBRATION))
     ap.add_argument("--copies", type=int, default=0, help="distinct weight copies (0 = enough for 1.2 GB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--linears", default="", help="comma-separated subset of the layer's linears (q,k,v,o,gate,up,down) to run")
+    ap.add_argument("--profile-only", action="store_true",
+                    help="run --warmup + --steps steps eagerly (no graphs, no baselines) and exit: the program a "
+                         "rocprofv3 counter run profiles")
     ap.add_argument("--copy-probe", action="store_true",
                     help="only run plain device-to-device copies of 256 MiB (reference for the rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE counters) and exit")
@@ -510,12 +514,18 @@ def main():
     ncopies = args.copies or max(2, int(1.2e9 / layer_bytes) + 1, min(int(600e6 / smallest) + 1, int(8e9 / layer_bytes)))
     if spec["M"] > 16:
         args.steps = min(args.steps, 50)
-    linears = [Linear(n, di, do, spec, synth.seed_for(spec["cfg"], i), ncopies) for i, (n, di, do) in enumerate(shapes)]
+    only = [n for n in args.linears.split(",") if n]
+    if only:
+        ncopies = 2 if args.profile_only else ncopies
+    linears = [Linear(n, di, do, spec, synth.seed_for(spec["cfg"], i), ncopies) for i, (n, di, do) in enumerate(shapes)
+               if not only or n in only]
 
     launches = linears
     if spec.get("grouped"):
-        launches = [Group([L for L in linears if L.name in g]) for g in GROUPS]
+        launches = [Group([L for L in linears if L.name in g]) for g in GROUPS if any(L.name in g for L in linears)]
         layer_bytes = sum(G.bytes for G in launches)
+    elif only:
+        layer_bytes = sum(L.bytes for L in linears)
 
     def step(i):
         for L in launches:
@@ -524,6 +534,13 @@ def main():
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
+    if args.profile_only:
+        for i in range(args.steps):
+            step(i)
+        torch.cuda.synchronize()
+        print(json.dumps(dict(profile_only=True, workload=args.workload, linears=[L.name for L in linears],
+                              steps=args.steps, warmup=args.warmup, launches_per_step=len(launches))))
+        return
     ms_per_step, ms_min, ms_max = timed_graph(step, args.steps)
 
     # each linear on its own (graph of back-to-back launches over the rotating copies)
