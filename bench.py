@@ -480,6 +480,9 @@ def main():
     ap.add_argument("--profile-only", action="store_true",
                     help="run --warmup + --steps steps eagerly (no graphs, no baselines) and exit: the program a "
                          "rocprofv3 counter run profiles")
+    ap.add_argument("--spin-limit", type=int, default=None,
+                    help="diagnosis: eora_debug_set_spin_limit before the runs (negative: every wait for t counts as "
+                         "expired, so the low-rank term is skipped and results are NOT the layer's)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="only run plain device-to-device copies of 256 MiB (reference for the rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE counters) and exit")
@@ -501,6 +504,9 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"copy_probe_bytes_read": src.numel(), "copy_probe_bytes_written": src.numel(), "copies": 10}))
         return
+    if args.spin_limit is not None:
+        import paper_2410_21271_amd as eora
+        eora.debug_set_spin_limit(args.spin_limit)
     if args.workload in CALIBRATION:
         return calibration_main(args)
     spec = WORKLOADS[args.workload]

@@ -92,6 +92,9 @@ int pick_kcn(int M, int d_in)
     // (token blocks) x kcn <= 32: the partials' region is sized for that
     const int yblocks = ((M < CHUNK_TOKENS ? M : CHUNK_TOKENS) + 15) / 16;
     int cap = 32 / yblocks < MAX_KCN ? 32 / yblocks : MAX_KCN;
+#ifdef EORA_KCN_CAP
+    cap = cap > EORA_KCN_CAP ? EORA_KCN_CAP : cap;
+#endif
     // with more than 4 tokens every consumer reads (tokens x r x kcn) partials: few ranges
     if (M > 4 && cap > 4) cap = 4;
     int kcn = 1;

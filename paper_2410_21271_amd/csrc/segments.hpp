@@ -321,4 +321,32 @@ __device__ __forceinline__ void check_in_finish(const CheckIn& c, uint32_t* hdr,
     }
 }
 
+// The same bookkeeping without a returning atomic on anybody's path (decode kernel): every workgroup reads the
+// epoch and, once it has the value, ARRIVES on one of the HDR_NSUB counters with an atomic whose answer nobody
+// waits for; the launch's last workgroup (by index), at its very end, waits until all have arrived (they all
+// have long since: arriving is the first thing a workgroup does), clears the counters and advances the epoch.
+// Compatible with check_in_* on the same workspace: both leave the counters at zero.
+__device__ __forceinline__ void arrive(uint32_t epoch, uint32_t* hdr, uint32_t lin)
+{
+    asm volatile("" : "+v"(epoch) : : "memory");          // the epoch has been READ before this workgroup counts as arrived
+    __hip_atomic_fetch_add(&hdr[HDR_SUB0 + HDR_SUB_STRIDE * (lin % HDR_NSUB)], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// one wavefront of the launch's last workgroup; lane k < HDR_NSUB looks after counter k.  Returns false when the
+// bounded wait expired (the counters are then left as they are and the epoch does not advance).
+__device__ __forceinline__ bool advance_epoch(uint32_t epoch, uint32_t* hdr, uint32_t total, int lane, int spin_limit)
+{
+    const uint32_t quota = lane < HDR_NSUB ? (total - lane + HDR_NSUB - 1) / HDR_NSUB : 0u;      // workgroups with lin % HDR_NSUB == lane
+    bool all = false;
+    for (int spins = 0; spins <= (spin_limit < 0 ? 0 : spin_limit); ++spins) {
+        const uint32_t c = lane < HDR_NSUB ? ld_relaxed(&hdr[HDR_SUB0 + HDR_SUB_STRIDE * lane]) : 0u;
+        if (__all(c == quota)) { all = true; break; }
+        __builtin_amdgcn_s_sleep(8);
+    }
+    if (!all) return false;
+    if (lane < HDR_NSUB) __hip_atomic_store(&hdr[HDR_SUB0 + HDR_SUB_STRIDE * lane], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (lane == 0) __hip_atomic_store(&hdr[HDR_EPOCH], epoch + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return true;
+}
+
 }  // namespace eora

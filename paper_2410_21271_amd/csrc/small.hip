@@ -16,17 +16,17 @@
 // t split into a high and a low fp16 part.  Producers come first in dispatch order and never wait.
 #include "segments.hpp"
 
+#include <type_traits>
+
 namespace eora {
 
-constexpr int XSTAGE = 4;   // 16-byte chunks of x a thread may stage
-constexpr int TWO_BLOCKS_FROM = 1024;   // row blocks of a launch from which a workgroup takes two
-
-#ifdef EORA_TIMELINE
-// debug build only: per-workgroup time stamps (100 MHz counter) behind the partials of t
-#define TL_STAMP(slot) do { if (tid == 0) (a.tpair + (1 << 20))[blockIdx.x * 8 + (slot)] = wall_clock64(); } while (0)
+#ifdef EORA_DIAG_NOCHECKIN
+constexpr bool DIAG_NOCHECKIN = true;      // timing experiment only: the epoch never advances
 #else
-#define TL_STAMP(slot) do { } while (0)
+constexpr bool DIAG_NOCHECKIN = false;
 #endif
+constexpr int XSTAGE = 4;   // 16-byte chunks of x a thread may stage
+
 
 // Member m's entry of a per-member argument array, chosen with scalar selects among the four entries (all at
 // fixed places of the argument block, requested with the first batch of scalar loads) instead of a load at a
@@ -42,14 +42,52 @@ __device__ __forceinline__ T pick_member(const T (&arr)[MAX_GROUP], int m)
     return v;
 }
 
+template <int K>
+__device__ __forceinline__ float dpp_row_shr(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x110 + K, 0xF, 0xF, true));
+}
+
+// x of the token block -> LDS.  PLAIN: as it is (producers: A's product needs x itself).  Otherwise multiplied
+// column by column with the position factors of the backbone format (tiles.hpp, xscale_chunk), and the sum of
+// each group of 128 columns of the UNSCALED x, times 2^-24, goes to gs[row * G + group] (fp32): the zero-point
+// term of the group.  Chunk (tid + k * NT) of the staged block is chunk tid + (k % NQ) * NT of token row k / NQ.
+template <int WORDS, int NT, int NQ, int XS, bool PLAIN>
+__device__ __forceinline__ void stage_x_small(const u4 (&xstage)[XS], _Float16* xs, float* gs, int mt, int ldxs, int G, int tid)
+{
+    const h8 pat = PLAIN ? h8{} : xscale_chunk<WORDS>(tid & 3);       // NT is a multiple of 4: the chunk's place in its lane's 32 columns
+#pragma unroll
+    for (int k = 0; k < XS; ++k) {
+        const int row = k / NQ, chunk = tid + (k % NQ) * NT;
+        const bool live = row < mt;
+        Frag f;
+        f.q = xstage[k];
+        if constexpr (!PLAIN) {
+            const h2 ones = {(_Float16)1.0f, (_Float16)1.0f};
+            float sum = 0.f;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) sum = __builtin_amdgcn_fdot2(f.p[e], ones, sum, false);     // fp32 sum of the pair, one instruction
+            // the 16 chunks of a group sit in the 16 lanes of one DPP row: inclusive scan by row shifts (lanes
+            // shifted in from outside the row read 0), fixed order; the row's last lane ends with the group's sum
+            sum += dpp_row_shr<1>(sum);
+            sum += dpp_row_shr<2>(sum);
+            sum += dpp_row_shr<4>(sum);
+            sum += dpp_row_shr<8>(sum);
+            if (live && (tid & 15) == 15) gs[row * G + (chunk >> 4)] = sum * 0x1p-24f;
+            f.v = f.v * pat;
+        }
+        if (live) *(u4*)(xs + row * ldxs + chunk * 8) = f.q;
+    }
+}
+
 template <int FM, int FA, int FE, int NW, int NQ, bool M1, int RB>
-__global__ __launch_bounds__(NW * 64, (16 + NW - 1) / NW) void small_kernel(GroupArgs a)   // second bound: wavefronts per SIMD, i.e. at most 128 registers for four-wavefront workgroups
+__global__ __launch_bounds__(NW * 64, 4) void small_kernel(GroupArgs a)   // second bound: wavefronts per SIMD, i.e. at most 128 registers (two 7- or 8-wavefront workgroups per compute unit)
 {
     constexpr bool LOWRANK = FA != S_NONE;
     constexpr int NT = NW * 64;
     constexpr int WORDS = Fmt<FM>::WORDS;
     __shared__ float red[NW][RB][4][16];
-    __shared__ uint32_t s_epoch, s_ok;
+    __shared__ uint32_t s_epoch, s_bad;
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int n = lane & 15, j = lane >> 4;
@@ -58,11 +96,12 @@ __global__ __launch_bounds__(NW * 64, (16 + NW - 1) / NW) void small_kernel(Grou
     const int upl = LOWRANK ? (a.r / 16) * a.kcn : 0;    // units of t (= producer workgroups) per member
     const int nprod = upl * a.n;                         // producer workgroups
     const int ldxs = a.d_in + 32;                        // LDS row stride of x in halves (64 bytes of padding)
+    const int G = a.d_in / 128;                          // == 4 * NW * NQ, one quantisation group per k-tile
     _Float16* xs = (_Float16*)eora_smem;
-    float* ts = (float*)(eora_smem + (size_t)mt * ldxs * 2);     // t, fp32 mt x r (consumers)
+    float* gs = (float*)(eora_smem + (size_t)mt * ldxs * 2);      // zero-point terms: (M1 ? 1 : 4) x G, rows beyond the tokens zero
+    float* ts = gs + (M1 ? 1 : 4) * G;                            // t as two partial sums, fp32 2 x mt x r (consumers)
 
     CheckIn ci{0u, 0u, 0u};
-    TL_STAMP(0);
     if constexpr (LOWRANK) {
         if (tid == 0) check_in_load(ci, a.hdr);          // first request of the kernel: it returns first
     }
@@ -98,11 +137,9 @@ __global__ __launch_bounds__(NW * 64, (16 + NW - 1) / NW) void small_kernel(Grou
         }
         __builtin_amdgcn_sched_barrier(0);               // all requests are out before the first result is used
         if (tid == 0) s_epoch = ci.epoch;
-#pragma unroll
-        for (int k = 0; k < XS; ++k) *(u4*)(xs + ((k / NQ) < mt ? (k / NQ) : 0) * ldxs + (tid + (k % NQ) * NT) * 8) = xstage[k];
+        stage_x_small<WORDS, NT, NQ, XS, true>(xstage, xs, gs, mt, ldxs, G, tid);
         __syncthreads();
-        if (tid == 0) check_in_issue(ci, a.hdr, blockIdx.x);
-        TL_STAMP(1);
+        if (tid == 0 && !DIAG_NOCHECKIN) arrive(ci.epoch, a.hdr, blockIdx.x);
         const uint32_t epoch = s_epoch;
         f4 acc = {0.f, 0.f, 0.f, 0.f};
         for (int base = 0; base < nsteps; base += PD) {
@@ -134,7 +171,6 @@ __global__ __launch_bounds__(NW * 64, (16 + NW - 1) / NW) void small_kernel(Grou
             for (int i = 0; i < 4; ++i) red[wave][0][i][n] = acc[i];
         }
         __syncthreads();
-        TL_STAMP(2);
         if (tid < 16 * mt) {
             const int i = tid >> 4, col = tid & 15;
             float v = 0.f;
@@ -142,18 +178,10 @@ __global__ __launch_bounds__(NW * 64, (16 + NW - 1) / NW) void small_kernel(Grou
             for (int w2 = 0; w2 < NW; ++w2) v += red[w2][0][i][col];
             // partial layout: [kc][token row (16)][r], every element an 8-byte (value, epoch + 1) pair
             // written by ONE write-through store: a reader that finds this launch's tag has this
-            // launch's value, so the flag below need not wait for these stores to be acknowledged
+            // launch's value; nothing else is signalled
             const unsigned long long pr = ((unsigned long long)(epoch + 1) << 32) | __builtin_bit_cast(uint32_t, v);
             __hip_atomic_store(&a.tpair[(((size_t)mem * a.kcn + kc) * 16 + i) * a.r + 16 * rho + col], pr, __ATOMIC_RELAXED,
                                __HIP_MEMORY_SCOPE_AGENT);
-        }
-        // (tid < 16 * mt) is within wavefront 0, whose lane 0 raises the flag: same wavefront, later instruction
-        TL_STAMP(3);
-        if (tid == 0) {
-            for (int rep = 0; rep < HDR_FLAG_REPLICAS; ++rep)      // one copy per group of pollers
-                __hip_atomic_store(&a.hdr[HDR_FLAGS0 + HDR_FLAGS_REPLICA_STRIDE * rep + u], epoch + 1, __ATOMIC_RELAXED,
-                                   __HIP_MEMORY_SCOPE_AGENT);
-            check_in_finish(ci, a.hdr, gridDim.x);
         }
         return;
     }
@@ -181,167 +209,192 @@ __global__ __launch_bounds__(NW * 64, (16 + NW - 1) / NW) void small_kernel(Grou
     const _Float16* const w_scales = pick_member(a.w_scales, mem);
     const uint32_t* const w_zeros = pick_member(a.w_zeros, mem);
     const uint32_t* const w_tiles = (const uint32_t*)pick_member(a.w, mem);
-    const int G = a.d_in / 128;                          // == 4 * NW * NQ, one quantisation group per k-tile
-    uint2 sc[RB][NQ];
-    uint32_t zq[RB][NQ];
-    uint32_t wd[RB][NQ][4][WORDS];
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-        const size_t row = (size_t)(R * RB + rb) * 16 + n;
-#pragma unroll
-        for (int q = 0; q < NQ; ++q) {
-            const int g0 = 4 * (wave + q * NW);
-            sc[rb][q] = *(const uint2*)(w_scales + row * G + g0);
-            zq[rb][q] = w_zeros[row * (G / 8) + (g0 >> 3)];
-        }
-    }
-    const Factor fb{(const uint32_t*)pick_member(a.B, mem), pick_member(a.B_scales, mem), LOWRANK ? a.r / Fmt<LOWRANK ? FE : S_F16>::KT : 0};
-    FTile<LOWRANK ? FE : S_F16> bpre[RB];
-    if constexpr (LOWRANK) {
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb) load_ftile<FE>(bpre[rb], fb, R * RB + rb, wave < fb.ntk ? wave : 0, lane);
-    }
-    // the first row block's tiles now; a further row block's quad q is requested when quad q of the
-    // row block before it has been consumed (same registers, no second buffer)
+    // The strip's RB * NQ quads are consumed in order with two of them in flight: quad L + 2 is requested (scales,
+    // zero-points, tiles) when quad L has been consumed, into the registers that one has just left.
+#ifndef EORA_WQ
+#define EORA_WQ 2
+#endif
+    constexpr int WQ0 = LOWRANK ? EORA_WQ : 4;             // (the bare kernel has the registers for four)
+    constexpr int NL = RB * NQ, WQ = NL < WQ0 ? NL : WQ0;
+    uint2 sc[NL];
+    uint32_t zq[NL];
+    uint32_t wd[NL][4][WORDS];
+    constexpr int FEB = LOWRANK ? FE : S_F16;              // (a valid format also where the low-rank code is compiled out)
+    const Factor fb{(const uint32_t*)pick_member(a.B, mem), pick_member(a.B_scales, mem), LOWRANK ? a.r / Fmt<FEB>::KT : 0};
+    FTile<FEB> bpre[RB];                  // B's first tile per row block: requested at the strip's midpoint
     // this lane's words of tile (R * RB) * G + 4 * wave; every other tile it reads is a compile-time
     // number of tiles further on (32-bit word index: a matrix of this format stays far below 16 GiB)
     const uint32_t* const wp = w_tiles + (uint32_t)((((uint32_t)(R * RB) * G + 4 * wave) * 64 + lane) * WORDS);
+    const size_t row0 = (size_t)(R * RB) * 16 + n;
+    auto request = [&](auto Lc) __attribute__((always_inline)) {
+        constexpr int L = decltype(Lc)::value, rb = L / NQ, q = L % NQ;
+        const int g0 = 4 * (wave + q * NW);
+        sc[L] = *(const uint2*)(w_scales + (row0 + 16 * rb) * G + g0);
+        zq[L] = w_zeros[(row0 + 16 * rb) * (G / 8) + (g0 >> 3)];
 #pragma unroll
-    for (int q = 0; q < NQ; ++q) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) load_words<WORDS>(wd[0][q][i], wp + (4 * q * NW + i) * 64 * WORDS);
-    }
+        for (int i = 0; i < 4; ++i) load_words<WORDS>(wd[L][i], wp + ((size_t)rb * G + 4 * q * NW + i) * 64 * WORDS);
+    };
+    request(std::integral_constant<int, 0>{});
+    if constexpr (WQ > 1) request(std::integral_constant<int, 1>{});
+    if constexpr (WQ > 2) request(std::integral_constant<int, 2>{});
+    if constexpr (WQ > 3) request(std::integral_constant<int, 3>{});
     // Every request above is in flight before anything below consumes one: without this fence the
     // scheduler moves uses of the first results (zero-point constants, x to LDS) in between the
     // requests, and the tiles requested after such a use wait a whole round trip longer.
     __builtin_amdgcn_sched_barrier(0);
     if constexpr (LOWRANK) {
-        if (tid == 0) s_epoch = ci.epoch;
+        if (tid == 0) {
+            s_epoch = ci.epoch;
+            s_bad = 0u;
+        }
     }
-#pragma unroll
-    for (int k = 0; k < XS; ++k) *(u4*)(xs + ((k / NQ) < mt ? (k / NQ) : 0) * ldxs + (tid + (k % NQ) * NT) * 8) = xstage[k];
+    if constexpr (!M1) {
+        for (int e = tid; e < 4 * G; e += NT) gs[e] = 0.f;           // rows beyond the tokens: no zero-point term
+        __syncthreads();
+    }
+    stage_x_small<WORDS, NT, NQ, XS, false>(xstage, xs, gs, mt, ldxs, G, tid);
     __syncthreads();
+    if constexpr (LOWRANK) {
+        if (tid == 0 && !DIAG_NOCHECKIN) arrive(ci.epoch, a.hdr, blockIdx.x);      // (its value was needed for s_epoch: no new wait)
+    }
 
-    TL_STAMP(1);
-    uint32_t early = 0;
+    // ---- the partials of t (this launch's producers write them; the tag tells) ------------------------------------
+    // t[e] = H0[e] + H1[e], H0 the sum of the partials of the k-ranges 0..3 in their order, H1 that of 4..7.  A work
+    // item is (element, half); thread tid takes items tid, tid + NT, ...  With one token the first item's four
+    // pairs are requested before the last quad of the backbone: in a launch that streams for longer than the
+    // producers take they carry this launch's tag by then and cost no round trip at the end; otherwise the wait
+    // below reads them again, in the same order.
+    constexpr bool TEARLY = LOWRANK && M1 && RB * NQ >= 4;   // (a short strip ends before the producers do)
+    constexpr int KH = MAX_KCN / 2;
+    const uint32_t epoch = LOWRANK ? s_epoch : 0u;
+    const int T = LOWRANK ? mt * a.r : 0;                // elements of t
+    float* hp = ts;                                      // [2][T]
+    auto item_src = [&](int it, int& klo, int& khi) __attribute__((always_inline)) {    // first pair of item it < 2 T and its k-ranges [klo, khi)
+        const int half = it >= T ? 1 : 0, e = it - half * T;
+        klo = half * KH;
+        khi = a.kcn < klo + KH ? a.kcn : klo + KH;
+        int row = 0;                                     // e / r for at most four token rows, without a division
+        if constexpr (!M1) row = (e >= a.r ? 1 : 0) + (e >= 2 * a.r ? 1 : 0) + (e >= 3 * a.r ? 1 : 0);
+        return a.tpair + ((size_t)mem * a.kcn * 16 + row) * a.r + (e - row * a.r);
+    };
+    unsigned long long tp[KH];
+    int eklo = 0, ekhi = 0;
+    const unsigned long long* tsrc = nullptr;
+    if constexpr (TEARLY) tsrc = item_src(tid < 2 * T ? tid : 0, eklo, ekhi);
+
     // ---- backbone ------------------------------------------------------------------------------------
     f4 acc[RB];
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) acc[rb] = f4{0.f, 0.f, 0.f, 0.f};
+#ifdef EORA_EL_LAST
+    constexpr int EL = NL - 1;
+#else
+    constexpr int EL = NL / 2;
+#endif
+    //                       // the strip's midpoint: B's first tiles and the early look at t go out here
+    auto consume = [&](auto Lc) __attribute__((always_inline)) {
+        constexpr int L = decltype(Lc)::value, rb = L / NQ, q = L % NQ;
+        if constexpr (LOWRANK && L == (NL >= 4 ? EL : 0)) {
 #pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-        // a first look at the flags, requested before the last row block and examined after it: when
-        // the producers are done by the time this request reaches memory, the poll below costs no
-        // round trip
-        if constexpr (LOWRANK) {
-            if (rb == RB - 1 && wave == 0)
-                early = ld_relaxed(a.hdr + HDR_FLAGS0 + HDR_FLAGS_REPLICA_STRIDE * (blockIdx.x % HDR_FLAG_REPLICAS) + mem * upl +
-                                   (lane < upl ? lane : upl - 1));
+            for (int r2 = 0; r2 < RB; ++r2) load_ftile<FEB>(bpre[r2], fb, R * RB + r2, wave < fb.ntk ? wave : 0, lane);
         }
+        if constexpr (TEARLY && L == EL) {
 #pragma unroll
-        for (int q = 0; q < NQ; ++q) {
-            const int g0 = 4 * (wave + q * NW);
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                h8 xa[4], b[4];
-                const _Float16* px = xs + mrow * ldxs + (g0 + i) * 128 + 32 * j;
-#pragma unroll
-                for (int t = 0; t < 4; ++t) xa[t] = *(const h8*)(px + 8 * t);
-                decode_tile<FM>(wd[rb][q][i], (zq[rb][q] >> (4 * ((g0 & 7) + i))) & 0xFu, b);
-                f4 part = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int t = 0; t < 4; ++t) part = mfma16(xa[t], b[t], part);
-                const uint32_t sw = (i < 2) ? sc[rb][q].x : sc[rb][q].y;
-                const _Float16 s16 = __builtin_bit_cast(_Float16, (uint16_t)((i & 1) ? (sw >> 16) : (sw & 0xFFFFu)));
-                // exact integers times x, scaled once per group in fp32 (one token: only register 0 is ever stored)
-                if constexpr (M1) acc[rb][0] += (float)s16 * part[0];
-                else acc[rb] += (float)s16 * part;
-            }
-            if constexpr (RB > 1) {
-                if (rb + 1 < RB) {
-#pragma unroll
-                    for (int i = 0; i < 4; ++i)
-                        load_words<WORDS>(wd[rb + 1][q][i], wp + ((size_t)(rb + 1) * G + 4 * q * NW + i) * 64 * WORDS);
-                }
+            for (int k = 0; k < KH; ++k) {                          // past the item's last range: that one again (never added)
+                const int kc = eklo + k < a.kcn ? eklo + k : a.kcn - 1;
+                tp[k] = tsrc[(size_t)kc * 16 * a.r];               // an ordinary, cached load: hundreds of workgroups read these few KiB
             }
         }
-    }
+        const int g0 = 4 * (wave + q * NW);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            h8 xa[4], b[4];
+            const _Float16* px = xs + mrow * ldxs + (g0 + i) * 128 + 32 * j;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) xa[t] = *(const h8*)(px + 8 * t);
+            raw_tile<WORDS>(wd[L][i], b);
+            // the accumulator starts at the zero-point term -z * 2^-24 * sum(x) of its token
+            const float zf = -(float)((zq[L] >> (4 * ((g0 & 7) + i))) & 0xFu);
+            f4 part;
+            if constexpr (M1) part = f4{zf * gs[g0 + i], 0.f, 0.f, 0.f};
+            else part = f4{zf * gs[g0 + i], zf * gs[G + g0 + i], zf * gs[2 * G + g0 + i], zf * gs[3 * G + g0 + i]};
+#pragma unroll
+            for (int t = 0; t < 4; ++t) part = mfma16(xa[t], b[t], part);
+            const uint32_t sw = (i < 2) ? sc[L].x : sc[L].y;
+            const _Float16 s16 = __builtin_bit_cast(_Float16, (uint16_t)((i & 1) ? (sw >> 16) : (sw & 0xFFFFu)));
+            // 2^-24 (code - zero) . x, exact products, scaled once per group in fp32 (one token: only register 0 is ever stored)
+            if constexpr (M1) acc[rb][0] += (float)s16 * part[0];
+            else acc[rb] += (float)s16 * part;
+        }
+        if constexpr (L + WQ < NL) request(std::integral_constant<int, L + WQ>{});
+    };
+    static_assert(NL <= 8, "strip longer than the unrolled sequence below");
+    consume(std::integral_constant<int, 0>{});
+    if constexpr (NL > 1) consume(std::integral_constant<int, 1>{});
+    if constexpr (NL > 2) consume(std::integral_constant<int, 2>{});
+    if constexpr (NL > 3) consume(std::integral_constant<int, 3>{});
+    if constexpr (NL > 4) consume(std::integral_constant<int, 4>{});
+    if constexpr (NL > 5) consume(std::integral_constant<int, 5>{});
+    if constexpr (NL > 6) consume(std::integral_constant<int, 6>{});
+    if constexpr (NL > 7) consume(std::integral_constant<int, 7>{});
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) acc[rb] *= 0x1p24f;  // the subnormal codes' common factor
 
-    TL_STAMP(2);
     // ---- low-rank continuation ---------------------------------------------------------------------
     if constexpr (LOWRANK) {
-        // checks in now, with every tile consumed: the atomic's answer is needed at the very end only
-        if (tid == 0) check_in_issue(ci, a.hdr, blockIdx.x);
-        const uint32_t epoch = s_epoch;
-        if (wave == 0) {
-            // the units of this workgroup's own member only
-            const uint32_t* flags = a.hdr + HDR_FLAGS0 + HDR_FLAGS_REPLICA_STRIDE * (blockIdx.x % HDR_FLAG_REPLICAS) + mem * upl;
-            bool ok = a.spin_limit >= 0 && upl <= 64 && __all(early == epoch + 1);      // a negative limit: every wait counts as expired (test hook)
-            for (int spins = 0; !ok && spins <= a.spin_limit; ++spins) {
-                bool all = true;
-                for (int f = lane; f < upl; f += 64) all = all && (ld_relaxed(&flags[f]) == epoch + 1);
-                if (__all(all)) { ok = true; break; }
-                __builtin_amdgcn_s_sleep(2);
-            }
-            TL_STAMP(4);
-            if (ok) {
-                // The partials are read with ordinary (cached) loads first: the flags are up, so their
-                // stores were issued long ago and have all but certainly landed, and caches hold
-                // nothing of them from before the launch.  The tags say whether that held; a lane
-                // that finds an old tag reads again past the caches until it does (bounded).
-                const int T = mt * a.r;                  // elements of t; a.r is a multiple of 32
-                for (int e = 4 * lane; e < T; e += 256) {
-                    const int i = e / a.r, col = e % a.r;
-                    const unsigned long long* p = a.tpair + ((size_t)mem * a.kcn * 16 + i) * a.r + col;
-                    float v0 = 0.f, v1 = 0.f, v2 = 0.f, v3 = 0.f;
+        bool fine = true;
+        for (int it = tid; it < 2 * T; it += NT) {
+            int klo, khi;
+            const unsigned long long* p = item_src(it, klo, khi);
+            float v = 0.f;
+            bool good = klo >= khi;                      // no k-range in this half: the sum is 0
+            if constexpr (TEARLY) {
+                if (it == tid && !good && a.spin_limit >= 0) {       // the early read (a negative limit: every wait counts as expired)
                     uint32_t bad = 0;
-#pragma unroll 4
-                    for (int kc = 0; kc < a.kcn; ++kc) {                       // fixed order
-                        const uint2* pk = (const uint2*)(p + (size_t)kc * 16 * a.r);
-                        const uint2 p0 = pk[0], p1 = pk[1], p2 = pk[2], p3 = pk[3];      // .x value, .y tag
-                        bad |= (p0.y ^ (epoch + 1)) | (p1.y ^ (epoch + 1)) | (p2.y ^ (epoch + 1)) | (p3.y ^ (epoch + 1));
-                        v0 += __builtin_bit_cast(float, p0.x);
-                        v1 += __builtin_bit_cast(float, p1.x);
-                        v2 += __builtin_bit_cast(float, p2.x);
-                        v3 += __builtin_bit_cast(float, p3.x);
-                    }
-                    bool good = bad == 0;
-                    for (int spins = 0; !good && spins <= a.spin_limit; ++spins) {
-                        bad = 0;
-                        float w[4] = {0.f, 0.f, 0.f, 0.f};
-                        for (int kc = 0; kc < a.kcn; ++kc) {
 #pragma unroll
-                            for (int c = 0; c < 4; ++c) {
-                                const unsigned long long pr = __hip_atomic_load(p + (size_t)kc * 16 * a.r + c, __ATOMIC_RELAXED,
-                                                                                __HIP_MEMORY_SCOPE_AGENT);
-                                bad |= (uint32_t)(pr >> 32) ^ (epoch + 1);
-                                w[c] += __builtin_bit_cast(float, (uint32_t)pr);
-                            }
+                    for (int k = 0; k < KH; ++k) {
+                        if (klo + k < khi) {
+                            bad |= (uint32_t)(tp[k] >> 32) ^ (epoch + 1);
+                            v += __builtin_bit_cast(float, (uint32_t)tp[k]);
                         }
-                        good = bad == 0;
-                        v0 = w[0]; v1 = w[1]; v2 = w[2]; v3 = w[3];
                     }
-                    const f4 v = {v0, v1, v2, v3};
-                    ok = ok && good;
-                    *(f4*)(ts + e) = v;
+                    good = bad == 0;
                 }
-                ok = __all(ok);
             }
-            TL_STAMP(5);
-            if (lane == 0) {
-                s_ok = ok ? 1u : 0u;
-                if (!ok) atomicOr(&a.hdr[HDR_ERROR], 1u);          // never expected: producers do not wait
+#ifdef EORA_DIAG_NOWAIT
+            good = true;      // timing experiment only: results are wrong when t was not ready
+#endif
+            for (int spins = 0; !good && spins <= a.spin_limit; ++spins) {
+                if (spins > 0) __builtin_amdgcn_s_sleep(4);
+                uint32_t bad = 0;
+                v = 0.f;
+                for (int kc = klo; kc < khi; ++kc) {                         // fixed order
+                    const unsigned long long pr = __hip_atomic_load(p + (size_t)kc * 16 * a.r, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    bad |= (uint32_t)(pr >> 32) ^ (epoch + 1);
+                    v += __builtin_bit_cast(float, (uint32_t)pr);
+                }
+                good = bad == 0;
             }
+            fine = fine && good;
+            hp[it] = v;
+        }
+        if (!fine) {
+            s_bad = 1u;
+            atomicOr(&a.hdr[HDR_ERROR], 1u);             // never expected: producers do not wait
         }
         __syncthreads();
-        if (s_ok) {
+#ifdef EORA_DIAG_NOB
+        if (false) {
+#else
+        if (s_bad == 0u) {
+#endif
             constexpr int KTB = Fmt<FE>::KT, NMF = KTB / 32;
             for (int g = wave; g < fb.ntk; g += NW) {
                 h8 hi[NMF], lo[NMF];                     // t split once, used for the RB row blocks
 #pragma unroll
                 for (int q = 0; q < NMF; ++q) {
-                    const float* p = ts + mrow * a.r + g * KTB + (KTB / 4) * j + 8 * q;
-                    const f4 v0 = *(const f4*)p, v1 = *(const f4*)(p + 4);
+                    const float* p = hp + mrow * a.r + g * KTB + (KTB / 4) * j + 8 * q;
+                    const f4 v0 = *(const f4*)p + *(const f4*)(p + T), v1 = *(const f4*)(p + 4) + *(const f4*)(p + T + 4);
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
                         const _Float16 h0 = (_Float16)v0[i], h1 = (_Float16)v1[i];
@@ -389,9 +442,11 @@ __global__ __launch_bounds__(NW * 64, (16 + NW - 1) / NW) void small_kernel(Grou
             y_m[(size_t)i * d_out_m + (R * RB + rb) * 16 + col] = (_Float16)v;
         }
     }
-    TL_STAMP(6);
     if constexpr (LOWRANK) {
-        if (tid == 0) check_in_finish(ci, a.hdr, gridDim.x);
+        // the launch's last workgroup advances the epoch for the next launch, once everyone has arrived
+        if (blockIdx.x == gridDim.x - 1 && wave == 0 && !DIAG_NOCHECKIN) {
+            if (!advance_epoch(epoch, a.hdr, gridDim.x, lane, a.spin_limit) && lane == 0) atomicOr(&a.hdr[HDR_ERROR], 1u);
+        }
     }
 }
 
@@ -400,11 +455,16 @@ template <int FM, int FA, int FE, int NW, int NQ, bool M1, int RB>
 static hipError_t launch_small_m(const GroupArgs& a, hipStream_t stream)
 {
     auto kern = small_kernel<FM, FA, FE, NW, NQ, M1, RB>;
-    const size_t lds = (size_t)a.M * (a.d_in + 32) * 2 + (size_t)a.M * a.r * 4;
+    const size_t lds = (size_t)a.M * (a.d_in + 32) * 2 + (size_t)(M1 ? 1 : 4) * (a.d_in / 128) * 4 + (size_t)2 * a.M * a.r * 4;   // x, zero-point terms, the two halves of t
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
+#ifdef EORA_PAD_LDS
+    const size_t lds_pad = lds + EORA_PAD_LDS;
+    hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_pad);
+#define lds lds_pad
+#endif
     int blocks = (FA != S_NONE) ? (a.r / 16) * a.kcn * a.n : 0;     // producers first
     for (int m = 0; m < a.n; ++m) blocks += a.d_out[m] / (16 * RB);
     note_launch("small FM=%d FA=%d NW=%d NQ=%d RB=%d n=%d", FM, FA, NW, NQ, RB, a.n);
@@ -416,16 +476,34 @@ template <int FM, int FA, int FE, int NW, int NQ>
 static hipError_t launch_small_one(const GroupArgs& a, hipStream_t stream)
 {
     if (a.M == 1) {
-        // Launches of more row blocks than can be resident at once give every workgroup two of them:
-        // then all workgroups start together and each pays the wait for t once, at its very end.
-        if constexpr (NQ <= 2 && FA != S_NONE) {           // (the bare layer has no such wait: one row block each streams best)
+        // A low-rank launch wants ALL its workgroups resident from the start: a consumer that only gets a slot when
+        // the producers have left starts microseconds late and then still needs the whole streaming time, and a
+        // consumer that waits for t at its end holds its slot.  So a workgroup takes 2 or 4 row blocks (a strip)
+        // when one each would not fit next to the producers, with some slack (the dispatcher does not fill the
+        // compute units evenly).  128 registers: 16 wavefronts, i.e. 16 / NW workgroups, per compute unit.
+        // (The bare layer has no such wait: one row block each streams best; with 3-bit factors, and with 4-bit
+        // factors on a 4-bit backbone, the strip instantiations do not fit 128 registers.)
+#ifdef EORA_FORCE_RB
+        if constexpr (NQ <= 2 && FA != S_Q3S128) {
+            bool ev = true;
+            for (int m = 0; m < a.n; ++m) ev = ev && a.d_out[m] % 32 == 0;
+            if (EORA_FORCE_RB == 2 && ev) return launch_small_m<FM, FA, FE, NW, NQ, true, 2>(a, stream);
+            return launch_small_m<FM, FA, FE, NW, NQ, true, 1>(a, stream);
+        }
+#endif
+        if constexpr (NQ <= 2 && FA != S_NONE && FA != S_Q3S128 && !(FM == S_Q4 && FA == S_Q4S128)) {
             int blocks = 0;
-            bool even = true;
+            bool even2 = true, even4 = true;
             for (int m = 0; m < a.n; ++m) {
                 blocks += a.d_out[m] / 16;
-                even = even && a.d_out[m] % 32 == 0;
+                even2 = even2 && a.d_out[m] % 32 == 0;
+                even4 = even4 && a.d_out[m] % 64 == 0;
             }
-            if (even && blocks > TWO_BLOCKS_FROM) return launch_small_m<FM, FA, FE, NW, NQ, true, 2>(a, stream);
+            const int nprod = (a.r / 16) * a.kcn * a.n, room = 256 * (16 / NW) * 7 / 8;
+            if (blocks + nprod > room) {
+                // (a four-block strip as straight-line code does not fit 128 registers)
+                if (even2) return launch_small_m<FM, FA, FE, NW, NQ, true, 2>(a, stream);
+            }
         }
         return launch_small_m<FM, FA, FE, NW, NQ, true, 1>(a, stream);
     }

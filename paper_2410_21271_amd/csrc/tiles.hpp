@@ -128,6 +128,86 @@ __device__ __forceinline__ void dq3_lane(uint32_t d0, uint32_t d1, uint32_t d2, 
     }
 }
 
+// ------------------------------------------------------------------------------------------------
+// Codes as fp16 SUBNORMALS (decode kernel for one to four tokens).  A b-bit code left in place at bit p
+// (p + b <= 10) of a 16-bit half, everything else masked off, IS the fp16 subnormal code * 2^(p-24): one AND per
+// two weights, no OR and no subtraction (the fp16 MFMAs of this chip honour subnormal inputs exactly; checked
+// on the device).  The position factor 2^p is taken out by the activations, which the kernel stages
+// multiplied column by column with 2^-p (xscale_chunk below; exact in fp16 down to its subnormals), the common
+// 2^-24 by one multiplication of the finished accumulator, and the zero-point by
+//      sum_i (q_i - z) x_i = sum_i q_i x_i - z sum_i x_i
+// with sum_i x_i formed once per (token, group) when x is staged.
+template <int WORDS>
+__device__ __forceinline__ void raw_tile(const uint32_t (&w)[WORDS], h8 (&b)[4])
+{
+    Frag f[4];
+    if constexpr (WORDS == 4) {                            // Q4: word t = columns 8t .. 8t+7, pairs at bits 0, 4, 8, 12
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const uint32_t hi = w[t] >> 8;
+            f[t].u[0] = w[t] & 0x000F000Fu;                // 2^-24
+            f[t].u[1] = w[t] & 0x00F000F0u;                // 2^-20
+            f[t].u[2] = hi & 0x000F000Fu;
+            f[t].u[3] = hi & 0x00F000F0u;
+        }
+    } else if constexpr (WORDS == 3) {                     // Q3: pair p < 15 in word p/5 at bits 3(p%5); pair 15 in bit 15 of the words
+        uint32_t pr[16];
+#pragma unroll
+        for (int i = 0; i < 3; ++i) {
+            const uint32_t hi = w[i] >> 9;
+            pr[5 * i + 0] = w[i] & 0x00070007u;            // 2^-24
+            pr[5 * i + 1] = w[i] & 0x00380038u;            // 2^-21
+            pr[5 * i + 2] = w[i] & 0x01C001C0u;            // 2^-18
+            pr[5 * i + 3] = hi & 0x00070007u;
+            pr[5 * i + 4] = hi & 0x00380038u;
+        }
+        uint32_t last = (w[0] >> 15) & 0x00010001u;
+        last = and_or(w[1] >> 14, 0x00020002u, last);
+        last = and_or(w[2] >> 13, 0x00040004u, last);
+        pr[15] = last;
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) f[t].u[e] = pr[4 * t + e];
+    } else {                                               // Q2: word u = columns 16u .. 16u+15, pairs at bits 2p
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const uint32_t half[2] = {w[u], w[u] >> 8};
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                f[2 * u + h].u[0] = half[h] & 0x00030003u; // 2^-24
+                f[2 * u + h].u[1] = half[h] & 0x000C000Cu; // 2^-22
+                f[2 * u + h].u[2] = half[h] & 0x00300030u; // 2^-20
+                f[2 * u + h].u[3] = half[h] & 0x00C000C0u; // 2^-18
+            }
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < 4; ++t) b[t] = f[t].v;
+}
+
+// What the staged activations are multiplied with so that raw_tile's position factors cancel: the factors of
+// the eight columns 8c .. 8c+7 (c = 0..3) of a lane's 32 columns of a tile, i.e. of the 16-byte chunk number
+// 4j + c of the tile's 128 columns.
+template <int WORDS>
+__device__ __forceinline__ h8 xscale_chunk(int c)
+{
+    const _Float16 o = (_Float16)1.0f, e = (_Float16)0.125f, q = (_Float16)0.25f, s = (_Float16)0.0625f, x = (_Float16)0.015625f;
+    if constexpr (WORDS == 4) {
+        return h8{o, o, s, s, o, o, s, s};
+    } else if constexpr (WORDS == 2) {
+        return h8{o, o, q, q, s, s, x, x};
+    } else {
+        // pairs 4c .. 4c+3 of the lane; pair p < 15 has the factor {1, 1/8, 1/64, 1, 1/8}[p % 5], pair 15 the factor 1
+        const h8 c0 = {o, o, e, e, x, x, o, o}, c1 = {e, e, o, o, e, e, x, x}, c2 = {o, o, e, e, o, o, e, e}, c3 = {x, x, o, o, e, e, o, o};
+        h8 r = c0;
+        r = c == 1 ? c1 : r;
+        r = c == 2 ? c2 : r;
+        r = c == 3 ? c3 : r;
+        return r;
+    }
+}
+
 // zero-point nibble of row n of (row block R, quantisation group q)
 __device__ __forceinline__ uint32_t load_zero(const uint32_t* __restrict__ qzeros, size_t rq, int n)
 {
