@@ -118,7 +118,8 @@ int pick_ksplit(int M, int d_in, int r)
 }
 
 // Many tokens: MFMA-bound GEMM (t = x.A^T first, then one GEMM over d_in and r)
-bool prefill_fits(int M, int r, int ab_bits) { return M >= PREFILL_MIN_TOKENS && (r == 0 || (ab_bits == 16 && r % 128 == 0)); }
+// (fp16, 4-bit or 3-bit factors; the rank in whole steps of 128)
+bool prefill_fits(int M, int r, int ab_bits) { return M >= PREFILL_MIN_TOKENS && (r == 0 || r % 128 == 0) && (ab_bits == 16 || ab_bits == 4 || ab_bits == 3 || r == 0); }
 
 // scratch of the prefill path for n members: t (fp16, M x n*r) and the fp32 parts of its split contraction
 size_t prefill_scratch_bytes(int M, int d_in, int r, int n)
@@ -130,12 +131,13 @@ size_t prefill_scratch_bytes(int M, int d_in, int r, int n)
 // validated members that share x, as GEMMs: one launch for every member's t (the members' A side by side), one
 // for every member's y
 int launch_prefill_group(const void* x, const eora_q_member* members, int n, int M, int d_in, int r, int w_bits, int group,
-                         void* workspace, hipStream_t stream)
+                         int fa, int fe, const int* adapter, int r_per, void* workspace, hipStream_t stream)
 {
     _Float16* T = (_Float16*)((char*)workspace + WS_T);           // M x (n * r): member m owns columns m*r ..
     if (r > 0) {
         PrefillArgs p{};
         p.x = (const _Float16*)x; p.ldx = d_in;
+        p.group = 128;
         p.M = M; p.K1 = d_in;
         p.n = n;
         p.ksplit = pick_ksplit(M, d_in, n * r);
@@ -143,12 +145,15 @@ int launch_prefill_group(const void* x, const eora_q_member* members, int n, int
         p.ldp = n * r;
         for (int m = 0; m < n; ++m) {
             p.w[m] = members[m].A;
+            p.w_scales[m] = (const _Float16*)members[m].A_scales;
             p.y[m] = T + (size_t)m * r; p.ldy[m] = n * r;
             p.N[m] = r; p.pcol[m] = m * r;
         }
-        if (failed(launch_prefill(p, S_F16, false, stream), "prefill down-projection")) return EORA_ERR_LAUNCH;
+        if (failed(launch_prefill(p, fa, S_NONE, stream), "prefill down-projection")) return EORA_ERR_LAUNCH;
         if (p.ksplit > 1 && failed(launch_reduce_parts(p.part, T, (size_t)M * n * r, p.ksplit, stream), "prefill down-projection sum"))
             return EORA_ERR_LAUNCH;
+        // several adapters side by side (one member): a token row keeps its own adapter's columns of t
+        if (adapter && failed(launch_mask_t(T, adapter, M, n * r, r_per, stream), "prefill adapter mask")) return EORA_ERR_LAUNCH;
     }
     PrefillArgs p{};
     p.x = (const _Float16*)x; p.ldx = d_in;
@@ -163,16 +168,17 @@ int launch_prefill_group(const void* x, const eora_q_member* members, int n, int
         p.w_zeros[m] = (const uint32_t*)members[m].qzeros;
         p.x2[m] = T + (size_t)m * r;
         p.w2[m] = members[m].B;
+        p.w2_scales[m] = (const _Float16*)members[m].B_scales;
         p.y[m] = members[m].y; p.ldy[m] = members[m].d_out;
         p.N[m] = members[m].d_out;
     }
-    if (failed(launch_prefill(p, backbone_format(w_bits), r > 0, stream), "prefill")) return EORA_ERR_LAUNCH;
+    if (failed(launch_prefill(p, backbone_format(w_bits), r > 0 ? fe : S_NONE, stream), "prefill")) return EORA_ERR_LAUNCH;
     return EORA_OK;
 }
 
 // one launch of the decode kernel for validated members that share x
 int launch_group(const void* x, const eora_q_member* members, int n, int M, int d_in, int r, int w_bits, int group,
-                 int fa, int fe, int nw, int nq, void* workspace, hipStream_t stream)
+                 int fa, int fe, int nw, int nq, void* workspace, hipStream_t stream, const int* adapter = nullptr, int r_per = 0)
 {
     if (M == 0) return EORA_OK;
     GroupArgs a{};
@@ -197,6 +203,8 @@ int launch_group(const void* x, const eora_q_member* members, int n, int M, int 
     a.group = group;
     a.kcn = pick_kcn(M, d_in);
     a.spin_limit = g_spin_limit;
+    a.adapter = adapter;
+    a.r_per = r_per;
     if (failed(launch_small(a, backbone_format(w_bits), fa, fe, nw, nq, stream), "linear_q (decode)")) return EORA_ERR_LAUNCH;
     return EORA_OK;
 }
@@ -314,7 +322,7 @@ static int run_linear_q(const void* x, const eora_q_member& e, int M, int d_in, 
     const int d_out = e.d_out;
     if (M == 0) return EORA_OK;
 
-    if (prefill_fits(M, r, ab_bits)) return launch_prefill_group(x, &e, 1, M, d_in, r, w_bits, group, workspace, (hipStream_t)stream);
+    if (prefill_fits(M, r, ab_bits)) return launch_prefill_group(x, &e, 1, M, d_in, r, w_bits, group, fa, fe, nullptr, 0, workspace, (hipStream_t)stream);
 
     int nw = 0, nq = 0;
     if (small_kernel_fits(M, d_in, group, &nw, &nq))
@@ -429,6 +437,13 @@ int eora_linear_q_multi(const void* x, const void* qweight, const void* scales, 
     const int rc = validate_linear_q(x, e, M, d_in, R, w_bits, group, ab_bits, workspace, workspace_bytes, &fa, &fe);
     if (rc != EORA_OK) return rc;
     if (M == 0) return EORA_OK;
+    // many tokens: the GEMM path, with t masked per row between its two launches
+    if (prefill_fits(M, R, ab_bits))
+        return launch_prefill_group(x, &e, 1, M, d_in, R, w_bits, group, fa, fe, (const int*)adapter_of_row, r, workspace, (hipStream_t)stream);
+    // one to four tokens: the decode kernel, with t masked where it is gathered
+    int nw = 0, nq = 0;
+    if (small_kernel_fits(M, d_in, group, &nw, &nq))
+        return launch_group(x, &e, 1, M, d_in, R, w_bits, group, fa, fe, nw, nq, workspace, (hipStream_t)stream, (const int*)adapter_of_row, r);
     const int kcn = pick_kcn(M, d_in);
     for (int m0 = 0; m0 < M; m0 += CHUNK_TOKENS) {
         FusedArgs a{};
@@ -477,7 +492,7 @@ int eora_linear_q_group(const void* x, const eora_q_member* members, int n_membe
         (r == 0 || (r / 16) * pick_kcn(M, d_in) * n_members <= HDR_FLAGS_PER_BLOCK))
         return launch_group(x, members, n_members, M, d_in, r, w_bits, group, fa, fe, nw, nq, workspace, (hipStream_t)stream);
     if (prefill_fits(M, r, ab_bits) && workspace_bytes >= eora_workspace_bytes_group(M, d_in, r, n_members))
-        return launch_prefill_group(x, members, n_members, M, d_in, r, w_bits, group, workspace, (hipStream_t)stream);
+        return launch_prefill_group(x, members, n_members, M, d_in, r, w_bits, group, fa, fe, nullptr, 0, workspace, (hipStream_t)stream);
     if (n_members > 1 && M > 4 && M < PREFILL_MIN_TOKENS) {
         // 5 .. 127 tokens: the members' workgroups in one launch of the kernel that shares x through LDS, if together
         // they have the rows it wants.  k-ranges: the members' partials and flags share the regions of one call.

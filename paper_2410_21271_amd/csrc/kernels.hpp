@@ -89,6 +89,10 @@ struct GroupArgs {
     uint32_t* hdr;                      // workspace header
     unsigned long long* tpair;          // members x kcn x 16 x r (value, tag) pairs: partials of t
     int M, d_in, r, group, kcn, spin_limit;
+    // several adapters side by side in A and B (one member; r = their ranks together): token row m keeps only the
+    // r_per columns of t that belong to adapter[m] (anything else: none).  nullptr: nothing masked.
+    const int* adapter;
+    int r_per;
 };
 // whether the shape fits the decode kernel, with its wavefront / quad split
 bool small_kernel_fits(int M, int d_in, int group, int* nw, int* nq);
@@ -137,19 +141,21 @@ struct PrefillArgs {
     const _Float16* w_scales[MAX_GROUP];
     const uint32_t* w_zeros[MAX_GROUP];
     const _Float16* x2[MAX_GROUP];       // second segment's activations (t)
-    const void* w2[MAX_GROUP];           // second segment's fp16 tiles (N rows, K2 columns)
+    const void* w2[MAX_GROUP];           // second segment's tiles (N rows, K2 columns)
+    const _Float16* w2_scales[MAX_GROUP];   // their scales (quantised B)
     void* y[MAX_GROUP];                  // fp16, row stride ldy
     int ldy[MAX_GROUP];
     int N[MAX_GROUP];
     int pcol[MAX_GROUP];
 };
 
-hipError_t launch_prefill(const PrefillArgs& a, int fm, bool ext, hipStream_t stream);
+// fm: format of the first segment's weights; fe2: S_NONE, or the format of the second segment's tiles
+hipError_t launch_prefill(const PrefillArgs& a, int fm, int fe2, hipStream_t stream);
+// T (fp16 M x R, R adapters' ranks together): zero wherever a column does not belong to adapter[m]'s r_per columns
+hipError_t launch_mask_t(void* T, const int* adapter, int M, int R, int r_per, hipStream_t stream);
 
 // T[i] = fp16(sum over ks, in order, of part[ks][i]), i < count (count % 4 == 0)
 hipError_t launch_reduce_parts(const float* part, void* T, size_t count, int ksplit, hipStream_t stream);
-
-hipError_t launch_prefill(const PrefillArgs& a, int fm, bool ext, hipStream_t stream);
 
 hipError_t launch_unpack_q(const uint32_t* qweight, const uint32_t* qzeros, uint8_t* codes, uint8_t* zeros,
                            int d_in, int d_out, int w_bits, int group, hipStream_t stream);

@@ -46,6 +46,7 @@ struct PfView {
     const _Float16* x2;
     int ldx2;
     const void* w2;
+    const _Float16* w2_scales;
     void* y;
     int ldy;
     int M, N, K1, K2;
@@ -57,7 +58,7 @@ struct PfView {
 constexpr int PF_BM = 128, PF_BN = 256;
 constexpr int PF_NW = 8, PF_NT = PF_NW * 64;         // wavefronts: 2 (tokens) x 4 (rows)
 constexpr int PF_XS = 32 * 1024;                      // one x slab: 4 token blocks x 8 slices x 1 KiB
-constexpr int PF_LDS = PF_NW * 128 * 40 * 2;          // the epilogue's staging tiles (80 KiB) need more than the two x slabs (64 KiB)
+constexpr int PF_LDS = 2 * PF_XS;                     // the two x slabs; the epilogue's staging tiles (40 KiB) reuse them
 
 __device__ __forceinline__ f16v mfma32(h8 a, h8 b, f16v c) { return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0); }
 
@@ -76,28 +77,36 @@ struct WPre<S_F16> {
     u4 v[8];                                          // [slice]: four tiles of 32 columns = eight slices of 16
 };
 
-// Rl: the row block (2*wn + h, clamped) whose row n this lane supplies
+// Rl: the row block (2*wn + h, clamped) whose row n this lane supplies.  tiles / scales / zeros / K / group: the
+// segment's stored operand (first segment: the backbone, or A for the down-projection launch; second: B).
 template <int FMT>
-__device__ __forceinline__ void load_wpre(WPre<FMT>& r, const PfView& a, int Rl, int g, int lane)
+__device__ __forceinline__ void load_wpre_from(WPre<FMT>& r, const void* tiles, const _Float16* scales, const uint32_t* zeros,
+                                               int K, int group, int Rl, int g, int lane)
 {
     const int n = lane & 15, kg = lane >> 5;
     constexpr int WORDS = Fmt<FMT>::WORDS;
-    const int G = a.K1 / 128;
-    const int NG = Fmt<FMT>::ASYM ? a.K1 / a.group : G, grp = Fmt<FMT>::ASYM ? (g * 128) / a.group : g;
+    const int G = K / 128;
+    const int NG = Fmt<FMT>::ASYM ? K / group : G, grp = Fmt<FMT>::ASYM ? (g * 128) / group : g;
     r.zshift = 4 * (grp & 7);
-    const uint32_t* tile = (const uint32_t*)a.w + ((size_t)Rl * G + g) * 64 * WORDS;
+    const uint32_t* tile = (const uint32_t*)tiles + ((size_t)Rl * G + g) * 64 * WORDS;
 #pragma unroll
     for (int jp = 0; jp < 2; ++jp) load_words<WORDS>(r.w[jp], tile + (16 * (2 * jp + kg) + n) * WORDS);
     const size_t row = (size_t)Rl * 16 + n;
-    r.sraw = ((const uint16_t*)a.w_scales)[row * NG + grp];
-    if constexpr (Fmt<FMT>::ASYM) r.zraw = a.w_zeros[row * ((NG + 7) / 8) + (grp >> 3)];
+    r.sraw = ((const uint16_t*)scales)[row * NG + grp];
+    if constexpr (Fmt<FMT>::ASYM) r.zraw = zeros[row * ((NG + 7) / 8) + (grp >> 3)];
+}
+
+template <int FMT>
+__device__ __forceinline__ void load_wpre(WPre<FMT>& r, const PfView& a, int Rl, int g, int lane)
+{
+    load_wpre_from<FMT>(r, a.w, a.w_scales, a.w_zeros, a.K1, a.group, Rl, g, lane);
 }
 
 // decode to operands bf[slice], slice = 4*jp + t, scale folded in fp16
 template <int FMT>
 __device__ __forceinline__ void decode_wpre(const WPre<FMT>& r, h8 (&bf)[8])
 {
-    const uint32_t z = Fmt<FMT>::ASYM ? (r.zraw >> r.zshift) & 0xFu : 8u;
+    const uint32_t z = Fmt<FMT>::ASYM ? (r.zraw >> r.zshift) & 0xFu : 8u;       // (symmetric formats carry their constant themselves)
     const _Float16 sc = __builtin_bit_cast(_Float16, (uint16_t)r.sraw);
     const h8 s = {sc, sc, sc, sc, sc, sc, sc, sc};
 #pragma unroll
@@ -183,11 +192,15 @@ __device__ __forceinline__ void contract_step(f16v (&acc)[4], const h8 (&bf)[8],
 
 template <bool V> struct PfFlag { static constexpr bool value = V; };
 
-// FM: format of the first segment's weights (S_Q4, S_Q3 asymmetric; S_Q4S128; S_F16).  EXT: continue over a
+// FM: format of the first segment's weights (S_Q4, S_Q3, S_Q2 asymmetric; S_Q4S128, S_Q3S128, S_F16 for the
+// down-projection launch).  FE2: S_NONE, or the format of a second segment's tiles (B: S_F16, S_Q4S128, S_Q3S128):
+// the kernel then continues over a
 // second segment of fp16 tiles (B) with its own activations (t).
-template <int FM, bool EXT>
+template <int FM, int FE2>
 __global__ __launch_bounds__(PF_NT, 2) void prefill_kernel(PrefillArgs ga)
 {
+    constexpr bool EXT = FE2 != S_NONE;
+    constexpr bool E16 = FE2 == S_F16 || FE2 == S_NONE;           // second segment's tiles are fp16 (or there is none)
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int wn = wave;                                          // this wavefront's 128 tokens x 32 rows of the 128 x 256 tile
     int ntn = 0;                                                  // column tiles of all members
@@ -200,7 +213,7 @@ __global__ __launch_bounds__(PF_NT, 2) void prefill_kernel(PrefillArgs ga)
         nt -= (ga.N[mem] + PF_BN - 1) / PF_BN;
         ++mem;
     }
-    const PfView a{ga.x, ga.ldx, ga.w[mem], ga.w_scales[mem], ga.w_zeros[mem], ga.group, ga.x2[mem], ga.ldx2, ga.w2[mem],
+    const PfView a{ga.x, ga.ldx, ga.w[mem], ga.w_scales[mem], ga.w_zeros[mem], ga.group, ga.x2[mem], ga.ldx2, ga.w2[mem], ga.w2_scales[mem],
                    ga.y[mem], ga.ldy[mem], ga.M, ga.N[mem], ga.K1, ga.K2, ga.ksplit, ga.part, ga.ldp, ga.pcol[mem]};
     const int R0 = nt * (PF_BN / 16);
     const int nblk = a.N / 16;
@@ -261,7 +274,13 @@ __global__ __launch_bounds__(PF_NT, 2) void prefill_kernel(PrefillArgs ga)
     };
     auto prep_ext = [&](int s) {
         s = s < GT ? s : GT - 1;
-        load_b_frags(bf, a.w2, a.K2, Rl, s - G1, lane);
+        if constexpr (E16) {
+            load_b_frags(bf, a.w2, a.K2, Rl, s - G1, lane);
+        } else {                                                  // quantised B: a handful of steps, loaded and decoded in place
+            WPre<E16 ? S_Q4S128 : FE2> wb;
+            load_wpre_from<E16 ? S_Q4S128 : FE2>(wb, a.w2, a.w2_scales, nullptr, a.K2, 128, Rl, s - G1, lane);
+            decode_wpre<E16 ? S_Q4S128 : FE2>(wb, bf);
+        }
     };
     // The two wavefronts that share a SIMD (w and w + 4) run the two halves of a step in opposite order,
     // so that one decodes (VALU) while the other contracts (MFMA): wavefronts 0..3 decode step s at the
@@ -290,7 +309,7 @@ __global__ __launch_bounds__(PF_NT, 2) void prefill_kernel(PrefillArgs ga)
         PF_STAMP(1);
 #endif
         // the next step's slab goes to the other buffer (free since the barrier of the step before)
-        store_x(xr, nxt, !(W16 || (EXT && s + 1 >= G1)), tid);
+        store_x(xr, nxt, !((EXT && s + 1 >= G1) ? E16 : W16), tid);      // the fragment order follows the weight operand's
         fetch_x(xr, s + 2);
         if constexpr (LATE) {
             __builtin_amdgcn_sched_barrier(0);
@@ -349,33 +368,40 @@ __global__ __launch_bounds__(PF_NT, 2) void prefill_kernel(PrefillArgs ga)
         return;
     }
     // ---- epilogue: fp32 -> fp16, transpose through LDS, 128-byte row stores ----------------------------
+    // (wavefront-private staging tiles of 64 tokens, two passes: 40 KiB, so that the kernel's LDS stays at the
+    // two x slabs and two workgroups fit a compute unit)
     constexpr int TS = 40;                                        // halves per token row in the staging tile (32 + pad)
-    _Float16* tile = (_Float16*)eora_smem + wave * 128 * TS;
+    _Float16* tile = (_Float16*)eora_smem + wave * 64 * TS;
 #pragma unroll
-    for (int mb = 0; mb < 4; ++mb)
+    for (int pass = 0; pass < 2; ++pass) {
+        if (pass) __syncthreads();                                // (keeps the two passes of a wavefront apart in program order)
 #pragma unroll
-        for (int v = 0; v < 16; ++v)
-            tile[(32 * mb + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3)) * TS + (lane & 31)] = (_Float16)acc[mb][v];
-    __syncthreads();
+        for (int mb2 = 0; mb2 < 2; ++mb2)
 #pragma unroll
-    for (int it = 0; it < 8; ++it) {
-        const int tok = 16 * it + (lane >> 2), chunk = lane & 3;      // 64-byte rows: four 16-byte chunks
-        const int m = m0 + tok, o = (R0 + 2 * wn) * 16 + chunk * 8;
-        const u4 v = *(const u4*)(tile + tok * TS + chunk * 8);
-        if (m < a.M && o < a.N) *(u4*)((_Float16*)a.y + (size_t)m * a.ldy + o) = v;
+            for (int v = 0; v < 16; ++v)
+                tile[(32 * mb2 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3)) * TS + (lane & 31)] = (_Float16)acc[2 * pass + mb2][v];
+        __syncthreads();
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            const int tok = 16 * it + (lane >> 2), chunk = lane & 3;  // 64-byte rows: four 16-byte chunks
+            const int m = m0 + 64 * pass + tok, o = (R0 + 2 * wn) * 16 + chunk * 8;
+            const u4 v = *(const u4*)(tile + tok * TS + chunk * 8);
+            if (m < a.M && o < a.N) *(u4*)((_Float16*)a.y + (size_t)m * a.ldy + o) = v;
+        }
     }
 }
 
-template <int FM, bool EXT>
+template <int FM, int FE2>
 static hipError_t launch_pf(const PrefillArgs& a, hipStream_t stream)
 {
-    auto kern = prefill_kernel<FM, EXT>;
+    constexpr bool EXT = FE2 != S_NONE;
+    auto kern = prefill_kernel<FM, FE2>;
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, PF_LDS);
     if (e != hipSuccess) return e;
     int ntn = 0;
     for (int m = 0; m < a.n; ++m) ntn += (a.N[m] + PF_BN - 1) / PF_BN;
     const int ntm = (a.M + PF_BM - 1) / PF_BM;
-    note_launch("prefill FM=%d EXT=%d ksplit=%d n=%d", FM, (int)EXT, a.ksplit, a.n);
+    note_launch("prefill FM=%d EXT=%d ksplit=%d n=%d FE=%d", FM, (int)EXT, a.ksplit, a.n, FE2);
     hipLaunchKernelGGL(kern, dim3(ntn * ntm * (EXT ? 1 : a.ksplit)), dim3(PF_NT), PF_LDS, stream, a);
     return hipGetLastError();
 }
@@ -396,16 +422,46 @@ hipError_t launch_reduce_parts(const float* part, void* T, size_t count, int ksp
     return hipGetLastError();
 }
 
-hipError_t launch_prefill(const PrefillArgs& a, int fm, bool ext, hipStream_t stream)
+template <int FM>
+static hipError_t launch_pf_ext(const PrefillArgs& a, int fe2, hipStream_t stream)
 {
-    switch (fm) {
-        case S_Q4: return ext ? launch_pf<S_Q4, true>(a, stream) : launch_pf<S_Q4, false>(a, stream);
-        case S_Q3: return ext ? launch_pf<S_Q3, true>(a, stream) : launch_pf<S_Q3, false>(a, stream);
-        case S_Q2: return ext ? launch_pf<S_Q2, true>(a, stream) : launch_pf<S_Q2, false>(a, stream);
-        case S_Q4S128: return ext ? hipErrorInvalidValue : launch_pf<S_Q4S128, false>(a, stream);
-        case S_F16: return ext ? hipErrorInvalidValue : launch_pf<S_F16, false>(a, stream);
+    switch (fe2) {
+        case S_NONE: return launch_pf<FM, S_NONE>(a, stream);
+        case S_F16: return launch_pf<FM, S_F16>(a, stream);
+        case S_Q4S128: return launch_pf<FM, S_Q4S128>(a, stream);
+        case S_Q3S128: return launch_pf<FM, S_Q3S128>(a, stream);
         default: return hipErrorInvalidValue;
     }
+}
+
+// fe2: S_NONE, or the format of the second segment's tiles
+hipError_t launch_prefill(const PrefillArgs& a, int fm, int fe2, hipStream_t stream)
+{
+    switch (fm) {
+        case S_Q4: return launch_pf_ext<S_Q4>(a, fe2, stream);
+        case S_Q3: return launch_pf_ext<S_Q3>(a, fe2, stream);
+        case S_Q2: return launch_pf_ext<S_Q2>(a, fe2, stream);
+        case S_Q4S128: return fe2 != S_NONE ? hipErrorInvalidValue : launch_pf<S_Q4S128, S_NONE>(a, stream);
+        case S_Q3S128: return fe2 != S_NONE ? hipErrorInvalidValue : launch_pf<S_Q3S128, S_NONE>(a, stream);
+        case S_F16: return fe2 != S_NONE ? hipErrorInvalidValue : launch_pf<S_F16, S_NONE>(a, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+// T[m][c] = 0 wherever column c does not belong to the adapter of token row m (several adapters side by side)
+__global__ __launch_bounds__(256) void mask_t_kernel(_Float16* __restrict__ T, const int* __restrict__ adapter, int M, int R, int r_per)
+{
+    const size_t i = 8 * ((size_t)blockIdx.x * 256 + threadIdx.x);       // eight columns of one row (R and r_per are multiples of 8)
+    if (i >= (size_t)M * R) return;
+    const int m = (int)(i / R), c = (int)(i % R);
+    if (adapter[m] != c / r_per) *(u4*)(T + i) = u4{0u, 0u, 0u, 0u};
+}
+
+hipError_t launch_mask_t(void* T, const int* adapter, int M, int R, int r_per, hipStream_t stream)
+{
+    const size_t chunks = (size_t)M * R / 8;
+    hipLaunchKernelGGL(mask_t_kernel, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, stream, (_Float16*)T, adapter, M, R, r_per);
+    return hipGetLastError();
 }
 
 }  // namespace eora

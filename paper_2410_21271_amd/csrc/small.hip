@@ -120,6 +120,10 @@ __global__ __launch_bounds__(NW * 64, 4) void small_kernel(GroupArgs a)   // sec
     if constexpr (LOWRANK) {
     if ((int)blockIdx.x < nprod) {
         // ======================================================================= producer
+#ifdef EORA_DIAG_NOPROD
+        if (tid == 0) arrive(ci.epoch, a.hdr, blockIdx.x);      // timing experiment only: no t is produced
+        return;
+#endif
         __builtin_amdgcn_s_setprio(3);                   // everyone's critical path: issue ahead of the consumers' dequant
         constexpr int KTA = Fmt<FA>::KT, NMF = KTA / 32;
         const int NRB = a.r / 16;
@@ -264,7 +268,12 @@ __global__ __launch_bounds__(NW * 64, 4) void small_kernel(GroupArgs a)   // sec
     // pairs are requested before the last quad of the backbone: in a launch that streams for longer than the
     // producers take they carry this launch's tag by then and cost no round trip at the end; otherwise the wait
     // below reads them again, in the same order.
-    constexpr bool TEARLY = LOWRANK && M1 && RB * NQ >= 4;   // (a short strip ends before the producers do)
+#ifdef EORA_DIAG_NOEARLY
+    constexpr bool TEARLY = false;
+#else
+    constexpr bool TEARLY = LOWRANK && M1 && RB * NQ >= 4;
+#endif
+    //   // (a short strip ends before the producers do)
     constexpr int KH = MAX_KCN / 2;
     const uint32_t epoch = LOWRANK ? s_epoch : 0u;
     const int T = LOWRANK ? mt * a.r : 0;                // elements of t
@@ -376,6 +385,13 @@ __global__ __launch_bounds__(NW * 64, 4) void small_kernel(GroupArgs a)   // sec
                 good = bad == 0;
             }
             fine = fine && good;
+            if (a.adapter) {                             // several adapters: a token row keeps its own adapter's columns of t
+                const int e = it >= T ? it - T : it;
+                int row = 0;
+                if constexpr (!M1) row = (e >= a.r ? 1 : 0) + (e >= 2 * a.r ? 1 : 0) + (e >= 3 * a.r ? 1 : 0);
+                const int col = e - row * a.r, lo = a.adapter[row] * a.r_per;
+                if (a.adapter[row] < 0 || col < lo || col >= lo + a.r_per) v = 0.f;
+            }
             hp[it] = v;
         }
         if (!fine) {

@@ -169,7 +169,7 @@ def test_prefill_config4_qkv_group(gpu):
     from tests.gpu_util import run_linear_q_group
     cs = [QCase(synth.seed_for(4, i), 4096, d, 2048, 256, 4, outlier_frac=0.01, packer=gpu) for i, d in enumerate((4096, 1024, 1024))]
     ys = run_linear_q_group(cs, cs[0].x)
-    assert gpu.debug_last_launch() == "prefill FM=1 EXT=1 ksplit=1 n=3", gpu.debug_last_launch()
+    assert gpu.debug_last_launch() == "prefill FM=1 EXT=1 ksplit=1 n=3 FE=5", gpu.debug_last_launch()
     rows = _token_rows(2048, 4, 14)
     for c, y in zip(cs, ys):
         _check(y[rows], c.oracle_y(rows=rows, x=cs[0].x))

@@ -42,6 +42,11 @@ SHAPES = [
     (300, 256, 64, 2, 32, 4, 16),          # two chunks of 256 tokens
     (37, 2048, 2048, 2, 64, 4, 16),        # enough rows for the kernel that shares x through LDS; ragged last block
     (21, 2048, 4096, 2, 128, 3, 4),        # the same with 3-bit backbone and 4-bit factors
+    (4, 4096, 1024, 4, 128, 4, 16),        # the decode kernel at an 8B shape: four adapters, four tokens
+    (2, 14336, 512, 2, 128, 3, 4),         # the decode kernel's long contraction, 4-bit factors
+    (200, 512, 192, 2, 128, 4, 16),        # many tokens: the GEMM path, t masked between its two launches (ragged tiles)
+    (333, 1024, 144, 4, 128, 3, 4),        # the same with four adapters of 4-bit factors
+    (130, 512, 64, 2, 128, 2, 3),          # 2-bit backbone, 3-bit factors
 ]
 
 

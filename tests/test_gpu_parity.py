@@ -126,7 +126,7 @@ def test_config_shapes_fp16_factors(gpu, name, d_in, d_out, w_bits, M):
     (4, 4, 128, 1, 4096, (1024, 2048)),             # 4-bit factors, config 3
     (2, 16, 128, 1, 4096, (4096, 1024, 1024)),      # 2-bit backbone
     (4, 3, 128, 1, 4096, (4096, 1024, 1024)),       # 3-bit factors
-    (4, 3, 128, 150, 512, (64, 32)),                # 3-bit factors, many tokens (no GEMM path: chunks of the layer kernel)
+    (4, 3, 128, 150, 512, (64, 32)),                # 3-bit factors, many tokens: the members' rows form one GEMM
     (4, 16, 32, 3, 1024, (64, 16, 48, 32)),         # four members, three tokens
     (4, 16, 0, 2, 2048, (128, 64)),                 # adapter off
     (3, 16, 64, 8, 512, (64, 32)),                  # a shape the decode kernel does not take: members run in turn
@@ -371,6 +371,18 @@ def test_prefill_gemm_small_shapes(gpu, w_bits, r, M, d_out):
     from tests.gpu_util import run_linear_q
     c = QCase(3000 + r + M, 512, d_out, M, r, w_bits, packer=gpu)
     _check(run_linear_q(c), c.oracle_y())
+
+
+@pytest.mark.parametrize("w_bits,ab_bits,r,M,d_out", [(4, 4, 128, 200, 192), (3, 4, 256, 333, 144), (4, 3, 128, 129, 16), (2, 3, 256, 200, 272)])
+def test_prefill_gemm_quantised_factors(gpu, w_bits, ab_bits, r, M, d_out):
+    """The many-token GEMM path with 4-bit and 3-bit factors (quantised EoRA, Sec. 4.5 / App. A.9): A is the weight
+    operand of the down-projection launch, B's tiles are decoded in the second segment."""
+    from tests.cases import QCase
+    from tests.gpu_util import run_linear_q
+    c = QCase(3100 + r + M, 512, d_out, M, r, w_bits, ab_bits=ab_bits, packer=gpu)
+    _check(run_linear_q(c), c.oracle_y())
+    assert gpu.debug_last_launch().startswith("prefill FM=%d EXT=1" % {4: 1, 3: 2, 2: 6}[w_bits]), gpu.debug_last_launch()
+    assert gpu.debug_last_launch().endswith("FE=%d" % {4: 3, 3: 7}[ab_bits])
 
 
 def test_prefill_config4_shape_sampled_rows(gpu):
