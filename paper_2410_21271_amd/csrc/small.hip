@@ -48,6 +48,36 @@ __device__ __forceinline__ float dpp_row_shr(float v)
     return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x110 + K, 0xF, 0xF, true));
 }
 
+// One 32-column slice of a row block of B: the unit the wavefronts of a workgroup share B's product in.  fp16 tiles are
+// one slice each; a 4-bit tile of KT columns is KT / 32 slices, one stored word per lane each (word q of the lane
+// holds its columns 8q .. 8q+7 of the tile's quarter); 3-bit tiles cannot be cut by words and stay whole.
+template <int FMT> struct BSlice {
+    static constexpr bool SLICED = FMT == S_Q4S128 || FMT == S_Q4S64;
+    static constexpr int NMF = SLICED ? 1 : Fmt<FMT>::KT / 32;       // MFMA steps per unit
+    static constexpr int UNITS_PER_TILE = SLICED ? Fmt<FMT>::KT / 32 : 1;
+    uint32_t w[SLICED ? 1 : Fmt<FMT>::WORDS];
+    _Float16 sc;
+};
+
+template <int FMT>
+__device__ __forceinline__ void load_bslice(BSlice<FMT>& s, const Factor& f, int R, int unit, int lane)
+{
+    constexpr int WORDS = Fmt<FMT>::WORDS, UPT = BSlice<FMT>::UNITS_PER_TILE;
+    const int g = unit / UPT, q = unit % UPT;
+    if constexpr (FMT != S_F16) s.sc = f.scales[((size_t)R * 16 + (lane & 15)) * f.ntk + g];
+    else s.sc = (_Float16)1.0f;
+    const uint32_t* p = f.w + (((size_t)R * f.ntk + g) * 64 + lane) * WORDS;
+    if constexpr (BSlice<FMT>::SLICED) s.w[0] = p[q];
+    else load_words<WORDS>(s.w, p);
+}
+
+template <int FMT>
+__device__ __forceinline__ void decode_bslice(const BSlice<FMT>& s, h8 (&b)[BSlice<FMT>::NMF])
+{
+    if constexpr (BSlice<FMT>::SLICED) b[0] = dq4_word(s.w[0], k1024(8u), k64(8u));
+    else decode_tile<FMT>(s.w, 8u, b);
+}
+
 // x of the token block -> LDS.  PLAIN: as it is (producers: A's product needs x itself).  Otherwise multiplied
 // column by column with the position factors of the backbone format (tiles.hpp, xscale_chunk), and the sum of
 // each group of 128 columns of the UNSCALED x, times 2^-24, goes to gs[row * G + group] (fp32): the zero-point
@@ -225,7 +255,8 @@ __global__ __launch_bounds__(NW * 64, 4) void small_kernel(GroupArgs a)   // sec
     uint32_t wd[NL][4][WORDS];
     constexpr int FEB = LOWRANK ? FE : S_F16;              // (a valid format also where the low-rank code is compiled out)
     const Factor fb{(const uint32_t*)pick_member(a.B, mem), pick_member(a.B_scales, mem), LOWRANK ? a.r / Fmt<FEB>::KT : 0};
-    FTile<FEB> bpre[RB];                  // B's first tile per row block: requested at the strip's midpoint
+    BSlice<FEB> bpre[RB];
+    const int bunits = LOWRANK ? fb.ntk * BSlice<FEB>::UNITS_PER_TILE : 0;      // units of B's product per row block                  // B's first tile per row block: requested at the strip's midpoint
     // this lane's words of tile (R * RB) * G + 4 * wave; every other tile it reads is a compile-time
     // number of tiles further on (32-bit word index: a matrix of this format stays far below 16 GiB)
     const uint32_t* const wp = w_tiles + (uint32_t)((((uint32_t)(R * RB) * G + 4 * wave) * 64 + lane) * WORDS);
@@ -305,7 +336,7 @@ __global__ __launch_bounds__(NW * 64, 4) void small_kernel(GroupArgs a)   // sec
         constexpr int L = decltype(Lc)::value, rb = L / NQ, q = L % NQ;
         if constexpr (LOWRANK && L == (NL >= 4 ? EL : 0)) {
 #pragma unroll
-            for (int r2 = 0; r2 < RB; ++r2) load_ftile<FEB>(bpre[r2], fb, R * RB + r2, wave < fb.ntk ? wave : 0, lane);
+            for (int r2 = 0; r2 < RB; ++r2) load_bslice<FEB>(bpre[r2], fb, R * RB + r2, wave < bunits ? wave : 0, lane);
         }
         if constexpr (TEARLY && L == EL) {
 #pragma unroll
@@ -404,12 +435,14 @@ __global__ __launch_bounds__(NW * 64, 4) void small_kernel(GroupArgs a)   // sec
 #else
         if (s_bad == 0u) {
 #endif
-            constexpr int KTB = Fmt<FE>::KT, NMF = KTB / 32;
-            for (int g = wave; g < fb.ntk; g += NW) {
+            constexpr int NMF = BSlice<FE>::NMF;
+            for (int u = wave; u < bunits; u += NW) {    // unit u covers columns 32 NMF u .. of t
                 h8 hi[NMF], lo[NMF];                     // t split once, used for the RB row blocks
 #pragma unroll
                 for (int q = 0; q < NMF; ++q) {
-                    const float* p = hp + mrow * a.r + g * KTB + (KTB / 4) * j + 8 * q;
+                    // the lane's eight columns of this MFMA step: tile u / UPT, the lane's quarter j of it, word (u % UPT) + q
+                    constexpr int KTB = Fmt<FE>::KT, UPT = BSlice<FE>::UNITS_PER_TILE;
+                    const float* p = hp + mrow * a.r + (u / UPT) * KTB + (KTB / 4) * j + 8 * (u % UPT + q);
                     const f4 v0 = *(const f4*)p + *(const f4*)(p + T), v1 = *(const f4*)(p + 4) + *(const f4*)(p + T + 4);
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
@@ -422,11 +455,11 @@ __global__ __launch_bounds__(NW * 64, 4) void small_kernel(GroupArgs a)   // sec
                 }
 #pragma unroll
                 for (int rb = 0; rb < RB; ++rb) {
-                    FTile<FE> cur;
-                    if (g == wave) cur = bpre[rb];
-                    else load_ftile<FE>(cur, fb, R * RB + rb, g, lane);
+                    BSlice<FE> cur;
+                    if (u == wave) cur = bpre[rb];
+                    else load_bslice<FE>(cur, fb, R * RB + rb, u, lane);
                     h8 b[NMF];
-                    decode_tile<FE>(cur.w, 8u, b);
+                    decode_bslice<FE>(cur, b);
                     f4 part = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                     for (int q = 0; q < NMF; ++q) {
@@ -507,7 +540,7 @@ static hipError_t launch_small_one(const GroupArgs& a, hipStream_t stream)
             return launch_small_m<FM, FA, FE, NW, NQ, true, 1>(a, stream);
         }
 #endif
-        if constexpr (NQ <= 2 && FA != S_NONE && FA != S_Q3S128 && !(FM == S_Q4 && FA == S_Q4S128)) {
+        if constexpr (NQ <= 2 && FA != S_NONE && FA != S_Q3S128) {
             int blocks = 0;
             bool even2 = true, even4 = true;
             for (int m = 0; m < a.n; ++m) {
