@@ -125,6 +125,11 @@ int eora_workspace_error(const void* workspace, void* stream);
  * y without the low-rank term) can be exercised deterministically with every kernel still terminating
  * normally. */
 void eora_debug_set_spin_limit(int iterations);
+/* HOST, test hook: the fewest 16-row blocks (all members of a launch together) for which a call with 5 .. 16 tokens
+ * and d_in of 1024, 2048 or 4096 takes the kernel that keeps x resident in LDS (process-wide; default 384, the
+ * measured crossover: launches with fewer rows are faster in the kernel that serves 5 .. 127 tokens).  Tests lower
+ * it to reach that kernel with small shapes; a negative value restores the default. */
+void eora_debug_set_resident_min_blocks(int blocks);
 /* HOST, test hook: writes into out (capacity bytes, NUL-terminated) the name and template parameters of the
  * layer kernel the most recent forward launch of this process chose, e.g. "sparse_wide FA=5 NW=8 TB=4 VQ=0 n=1"
  * (empty before the first launch), so that a test can assert that its shape reaches the instantiation it is

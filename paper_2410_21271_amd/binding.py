@@ -57,6 +57,7 @@ def _load():
         "eora_workspace_init": (ci, [vp, sz, vp]),
         "eora_workspace_error": (ci, [vp, vp]),
         "eora_debug_set_spin_limit": (None, [ci]),
+        "eora_debug_set_resident_min_blocks": (None, [ci]),
         "eora_debug_last_launch": (ci, [ctypes.c_char_p, sz]),
         "eora_debug_probe": (ci, [ci, vp, sz, vp, vp]),
         "eora_pack_q": (ci, [vp, vp, vp, ci, ci, ci, ci, vp, vp, vp]),
@@ -96,7 +97,7 @@ EXPORTS = ["eora_status_string", "eora_qweight_bytes", "eora_qzeros_bytes", "eor
            "eora_linear_q_group", "eora_linear_sp24", "eora_unpack_q", "eora_dequant_q", "eora_expand_sp24",
            "eora_sp24q4_tiles_bytes", "eora_sp24q4_meta_bytes", "eora_pack_sp24q4", "eora_linear_sp24q4", "eora_expand_sp24q4",
            "eora_factors_workspace_bytes", "eora_factors", "eora_linear_q_multi", "eora_pack_factor_q3", "eora_factors_store_f16", "eora_factors_store_q", "eora_linear_sp24_group",
-           "eora_debug_last_launch", "eora_debug_probe", "eora_linear_q_static"]
+           "eora_debug_last_launch", "eora_debug_probe", "eora_linear_q_static", "eora_debug_set_resident_min_blocks"]
 
 
 def status_string(status):
@@ -244,6 +245,11 @@ def workspace_error(workspace):
 
 def debug_set_spin_limit(iterations):
     lib.eora_debug_set_spin_limit(int(iterations))
+
+
+def debug_set_resident_min_blocks(blocks):
+    """Test hook: fewest 16-row blocks of a launch that takes the kernel with x resident in LDS (negative: default)."""
+    lib.eora_debug_set_resident_min_blocks(int(blocks))
 
 
 def debug_last_launch():

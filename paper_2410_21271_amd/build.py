@@ -9,7 +9,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.environ.get("EORA_OBJ_DIR") or os.path.join(HERE, "_build")
 LIB = os.environ.get("EORA_LIB_OUT") or os.path.join(HERE, "libeora.so")      # override: debug variants
-SOURCES = ["api.hip", "fused.hip", "small.hip", "sparse.hip", "wideq.hip", "prefill.hip", "calibrate.hip", "debug.hip", "pack.cpp"]
+SOURCES = ["api.hip", "fused.hip", "small.hip", "sparse.hip", "wideq.hip", "stream.hip", "prefill.hip", "calibrate.hip", "debug.hip", "pack.cpp"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC] + os.environ.get("EORA_EXTRA_FLAGS", "").split()

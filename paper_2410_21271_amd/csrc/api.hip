@@ -64,6 +64,36 @@ constexpr size_t WS_PAIRS = WS_HEADER;
 constexpr size_t WS_PARTS = WS_PAIRS + MAX_PART_ELEMS * 8;
 constexpr size_t WS_T = WS_PARTS + MAX_PART_ELEMS * 4;
 
+// one launch of the kernel for 5 .. 16 tokens (x resident in LDS) for validated members that share x; the caller has
+// checked stream_fits
+int launch_stream_group(const void* x, const eora_q_member* members, int n, int M, int d_in, int r, int w_bits,
+                        int fa, int fe, void* workspace, hipStream_t stream)
+{
+    StreamArgs a{};
+    a.x = (const _Float16*)x;
+    for (int m = 0; m < 4; ++m) {
+        const eora_q_member& e = members[m < n ? m : 0];
+        a.w[m] = e.qweight;
+        a.w_scales[m] = (const _Float16*)e.scales;
+        a.w_zeros[m] = (const uint32_t*)e.qzeros;
+        a.A[m] = e.A;
+        a.A_scales[m] = (const _Float16*)e.A_scales;
+        a.B[m] = e.B;
+        a.B_scales[m] = (const _Float16*)e.B_scales;
+        a.y[m] = (_Float16*)e.y;
+        a.d_out[m] = m < n ? e.d_out : 0;
+    }
+    a.n = n;
+    a.hdr = (uint32_t*)workspace;
+    a.tpair = (unsigned long long*)((char*)workspace + WS_PAIRS);
+    a.M = M;
+    a.d_in = d_in;
+    a.r = r;
+    a.spin_limit = g_spin_limit;
+    if (failed(launch_stream(a, backbone_format(w_bits), fa, fe, stream), "linear_q (stream)")) return EORA_ERR_LAUNCH;
+    return EORA_OK;
+}
+
 // factor formats of the (r, ab_bits) a call names
 int factor_formats(int r, int ab_bits, int* fa, int* fe)
 {
@@ -92,9 +122,6 @@ int pick_kcn(int M, int d_in)
     // (token blocks) x kcn <= 32: the partials' region is sized for that
     const int yblocks = ((M < CHUNK_TOKENS ? M : CHUNK_TOKENS) + 15) / 16;
     int cap = 32 / yblocks < MAX_KCN ? 32 / yblocks : MAX_KCN;
-#ifdef EORA_KCN_CAP
-    cap = cap > EORA_KCN_CAP ? EORA_KCN_CAP : cap;
-#endif
     // with more than 4 tokens every consumer reads (tokens x r x kcn) partials: few ranges
     if (M > 4 && cap > 4) cap = 4;
     int kcn = 1;
@@ -257,6 +284,8 @@ int eora_workspace_error(const void* workspace, void* stream)
 
 void eora_debug_set_spin_limit(int iterations) { g_spin_limit = iterations < 0 ? -1 : iterations; }
 
+void eora_debug_set_resident_min_blocks(int blocks) { set_resident_min_blocks(blocks); }
+
 int eora_debug_probe(int kind, const void* src, size_t bytes, void* sink, void* stream)
 {
     if (!sink) return EORA_ERR_NULL;
@@ -327,6 +356,9 @@ static int run_linear_q(const void* x, const eora_q_member& e, int M, int d_in, 
     int nw = 0, nq = 0;
     if (small_kernel_fits(M, d_in, group, &nw, &nq))
         return launch_group(x, &e, 1, M, d_in, r, w_bits, group, fa, fe, nw, nq, workspace, (hipStream_t)stream);
+
+    if (stream_fits(M, d_in, group, r, backbone_format(w_bits), fa, &d_out, 1))
+        return launch_stream_group(x, &e, 1, M, d_in, r, w_bits, fa, fe, workspace, (hipStream_t)stream);
 
     // k-ranges of the down-projection: a divisor of the number of 128-wide k-tiles
     const int kcn = pick_kcn(M, d_in);
@@ -493,6 +525,12 @@ int eora_linear_q_group(const void* x, const eora_q_member* members, int n_membe
         return launch_group(x, members, n_members, M, d_in, r, w_bits, group, fa, fe, nw, nq, workspace, (hipStream_t)stream);
     if (prefill_fits(M, r, ab_bits) && workspace_bytes >= eora_workspace_bytes_group(M, d_in, r, n_members))
         return launch_prefill_group(x, members, n_members, M, d_in, r, w_bits, group, fa, fe, nullptr, 0, workspace, (hipStream_t)stream);
+    if (n_members >= 1) {
+        int rows[MAX_GROUP] = {0, 0, 0, 0};
+        for (int m = 0; m < n_members; ++m) rows[m] = members[m].d_out;
+        if (stream_fits(M, d_in, group, r, backbone_format(w_bits), fa, rows, n_members))
+            return launch_stream_group(x, members, n_members, M, d_in, r, w_bits, fa, fe, workspace, (hipStream_t)stream);
+    }
     if (n_members > 1 && M > 4 && M < PREFILL_MIN_TOKENS) {
         // 5 .. 127 tokens: the members' workgroups in one launch of the kernel that shares x through LDS, if together
         // they have the rows it wants.  k-ranges: the members' partials and flags share the regions of one call.

@@ -605,7 +605,7 @@ int jacobi(double* H, int L, double* V, int m, double* sq, unsigned* rot, hipStr
         stats[0] = sweeps;
         stats[1] = ms;
         stats[2] = rotations;
-        stats[3] = (block_rounds_fit(L, V != nullptr, m) && !getenv("EORA_JACOBI_SCALAR")) ? 16 : 2;
+        stats[3] = (block_rounds_fit(L, V != nullptr, m)) ? 16 : 2;
     }
     if (e0) hipEventDestroy(e0);
     if (e1) hipEventDestroy(e1);
@@ -630,7 +630,7 @@ int jacobi_sweeps(double* H, int L, double* V, int m, double* sq, unsigned* rot,
     const double tol = sqrt((double)L) * 1.1102230246251565e-16;
     for (int sweep = 1; sweep <= MAX_SWEEPS; ++sweep) {
         hipLaunchKernelGGL(clear_counter_kernel, dim3(1), dim3(1), 0, st, rot);
-        if (block_rounds_fit(L, V != nullptr, m) && !getenv("EORA_JACOBI_SCALAR")) {
+        if (block_rounds_fit(L, V != nullptr, m)) {
             for (int round = 0; round < m / 8 - 1; ++round)
                 hipLaunchKernelGGL(jacobi_block_round_kernel, dim3(m / 16), dim3(BJ_NT), 0, st, H, L, V, m, round, tol, abs_floor, rot);
         } else {

@@ -70,6 +70,30 @@ struct WideGroupArgs {
 bool wide_q_group_fits(int M, int d_in, const int* d_out, int n, int r);
 hipError_t launch_wide_q_group(const FusedArgs* members, int n, int fm, int fa, int fe, hipStream_t stream);
 
+// Kernel for 5 .. 16 tokens with x resident in LDS (stream.hip): one workgroup of 16 wavefronts per compute unit keeps
+// the whole x (d_in <= 4096) and finishes every output tile it starts; t is handed over as tagged pairs.
+struct StreamArgs {
+    const _Float16* x;                  // M x d_in fp16 row-major, shared
+    const void* w[4];                   // backbone tiles
+    const _Float16* w_scales[4];
+    const uint32_t* w_zeros[4];
+    const void* A[4];                   // r x d_in tiles
+    const _Float16* A_scales[4];
+    const void* B[4];                   // d_out x r tiles
+    const _Float16* B_scales[4];
+    _Float16* y[4];                     // M x d_out fp16 row-major
+    int d_out[4];
+    int n;                              // members, 1..4
+    uint32_t* hdr;                      // workspace header
+    unsigned long long* tpair;          // [member][16 tokens][r] tagged t
+    int M, d_in, r, spin_limit;
+    int q, qp;                          // output row blocks per workgroup; per workgroup that begins with a block of A (set by the launcher)
+};
+// d_out: the members' rows (n of them)
+bool stream_fits(int M, int d_in, int group, int r, int fm, int fa, const int* d_out, int n);
+hipError_t launch_stream(const StreamArgs& a, int fm, int fa, int fe, hipStream_t stream);
+void set_resident_min_blocks(int blocks);      // test hook: stream_fits' lower limit of row blocks (negative: the default)
+
 // Decode kernel for 1..4 tokens (small.hip).  One launch serves up to MAX_GROUP linears that read the
 // same x (the q/k/v or the gate/up projections of a decoder layer): same d_in, rank and formats,
 // own weights, factors, output and d_out.

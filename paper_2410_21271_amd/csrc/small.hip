@@ -20,11 +20,6 @@
 
 namespace eora {
 
-#ifdef EORA_DIAG_NOCHECKIN
-constexpr bool DIAG_NOCHECKIN = true;      // timing experiment only: the epoch never advances
-#else
-constexpr bool DIAG_NOCHECKIN = false;
-#endif
 constexpr int XSTAGE = 4;   // 16-byte chunks of x a thread may stage
 
 
@@ -150,10 +145,6 @@ __global__ __launch_bounds__(NW * 64, 4) void small_kernel(GroupArgs a)   // sec
     if constexpr (LOWRANK) {
     if ((int)blockIdx.x < nprod) {
         // ======================================================================= producer
-#ifdef EORA_DIAG_NOPROD
-        if (tid == 0) arrive(ci.epoch, a.hdr, blockIdx.x);      // timing experiment only: no t is produced
-        return;
-#endif
         __builtin_amdgcn_s_setprio(3);                   // everyone's critical path: issue ahead of the consumers' dequant
         constexpr int KTA = Fmt<FA>::KT, NMF = KTA / 32;
         const int NRB = a.r / 16;
@@ -173,7 +164,7 @@ __global__ __launch_bounds__(NW * 64, 4) void small_kernel(GroupArgs a)   // sec
         if (tid == 0) s_epoch = ci.epoch;
         stage_x_small<WORDS, NT, NQ, XS, true>(xstage, xs, gs, mt, ldxs, G, tid);
         __syncthreads();
-        if (tid == 0 && !DIAG_NOCHECKIN) arrive(ci.epoch, a.hdr, blockIdx.x);
+        if (tid == 0) arrive(ci.epoch, a.hdr, blockIdx.x);
         const uint32_t epoch = s_epoch;
         f4 acc = {0.f, 0.f, 0.f, 0.f};
         for (int base = 0; base < nsteps; base += PD) {
@@ -245,10 +236,7 @@ __global__ __launch_bounds__(NW * 64, 4) void small_kernel(GroupArgs a)   // sec
     const uint32_t* const w_tiles = (const uint32_t*)pick_member(a.w, mem);
     // The strip's RB * NQ quads are consumed in order with two of them in flight: quad L + 2 is requested (scales,
     // zero-points, tiles) when quad L has been consumed, into the registers that one has just left.
-#ifndef EORA_WQ
-#define EORA_WQ 2
-#endif
-    constexpr int WQ0 = LOWRANK ? EORA_WQ : 4;             // (the bare kernel has the registers for four)
+    constexpr int WQ0 = LOWRANK ? 2 : 4;                   // (the bare kernel has the registers for four)
     constexpr int NL = RB * NQ, WQ = NL < WQ0 ? NL : WQ0;
     uint2 sc[NL];
     uint32_t zq[NL];
@@ -290,7 +278,7 @@ __global__ __launch_bounds__(NW * 64, 4) void small_kernel(GroupArgs a)   // sec
     stage_x_small<WORDS, NT, NQ, XS, false>(xstage, xs, gs, mt, ldxs, G, tid);
     __syncthreads();
     if constexpr (LOWRANK) {
-        if (tid == 0 && !DIAG_NOCHECKIN) arrive(ci.epoch, a.hdr, blockIdx.x);      // (its value was needed for s_epoch: no new wait)
+        if (tid == 0) arrive(ci.epoch, a.hdr, blockIdx.x);      // (its value was needed for s_epoch: no new wait)
     }
 
     // ---- the partials of t (this launch's producers write them; the tag tells) ------------------------------------
@@ -299,12 +287,7 @@ __global__ __launch_bounds__(NW * 64, 4) void small_kernel(GroupArgs a)   // sec
     // pairs are requested before the last quad of the backbone: in a launch that streams for longer than the
     // producers take they carry this launch's tag by then and cost no round trip at the end; otherwise the wait
     // below reads them again, in the same order.
-#ifdef EORA_DIAG_NOEARLY
-    constexpr bool TEARLY = false;
-#else
-    constexpr bool TEARLY = LOWRANK && M1 && RB * NQ >= 4;
-#endif
-    //   // (a short strip ends before the producers do)
+    constexpr bool TEARLY = LOWRANK && M1 && RB * NQ >= 4;      // (a shorter strip ends before the producers do)
     constexpr int KH = MAX_KCN / 2;
     const uint32_t epoch = LOWRANK ? s_epoch : 0u;
     const int T = LOWRANK ? mt * a.r : 0;                // elements of t
@@ -326,12 +309,7 @@ __global__ __launch_bounds__(NW * 64, 4) void small_kernel(GroupArgs a)   // sec
     f4 acc[RB];
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) acc[rb] = f4{0.f, 0.f, 0.f, 0.f};
-#ifdef EORA_EL_LAST
-    constexpr int EL = NL - 1;
-#else
-    constexpr int EL = NL / 2;
-#endif
-    //                       // the strip's midpoint: B's first tiles and the early look at t go out here
+    constexpr int EL = NL / 2;                           // the strip's midpoint: B's first tiles and the early look at t go out here
     auto consume = [&](auto Lc) __attribute__((always_inline)) {
         constexpr int L = decltype(Lc)::value, rb = L / NQ, q = L % NQ;
         if constexpr (LOWRANK && L == (NL >= 4 ? EL : 0)) {
@@ -401,9 +379,6 @@ __global__ __launch_bounds__(NW * 64, 4) void small_kernel(GroupArgs a)   // sec
                     good = bad == 0;
                 }
             }
-#ifdef EORA_DIAG_NOWAIT
-            good = true;      // timing experiment only: results are wrong when t was not ready
-#endif
             for (int spins = 0; !good && spins <= a.spin_limit; ++spins) {
                 if (spins > 0) __builtin_amdgcn_s_sleep(4);
                 uint32_t bad = 0;
@@ -430,11 +405,7 @@ __global__ __launch_bounds__(NW * 64, 4) void small_kernel(GroupArgs a)   // sec
             atomicOr(&a.hdr[HDR_ERROR], 1u);             // never expected: producers do not wait
         }
         __syncthreads();
-#ifdef EORA_DIAG_NOB
-        if (false) {
-#else
         if (s_bad == 0u) {
-#endif
             constexpr int NMF = BSlice<FE>::NMF;
             for (int u = wave; u < bunits; u += NW) {    // unit u covers columns 32 NMF u .. of t
                 h8 hi[NMF], lo[NMF];                     // t split once, used for the RB row blocks
@@ -493,7 +464,7 @@ __global__ __launch_bounds__(NW * 64, 4) void small_kernel(GroupArgs a)   // sec
     }
     if constexpr (LOWRANK) {
         // the launch's last workgroup advances the epoch for the next launch, once everyone has arrived
-        if (blockIdx.x == gridDim.x - 1 && wave == 0 && !DIAG_NOCHECKIN) {
+        if (blockIdx.x == gridDim.x - 1 && wave == 0) {
             if (!advance_epoch(epoch, a.hdr, gridDim.x, lane, a.spin_limit) && lane == 0) atomicOr(&a.hdr[HDR_ERROR], 1u);
         }
     }
@@ -509,11 +480,6 @@ static hipError_t launch_small_m(const GroupArgs& a, hipStream_t stream)
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-#ifdef EORA_PAD_LDS
-    const size_t lds_pad = lds + EORA_PAD_LDS;
-    hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_pad);
-#define lds lds_pad
-#endif
     int blocks = (FA != S_NONE) ? (a.r / 16) * a.kcn * a.n : 0;     // producers first
     for (int m = 0; m < a.n; ++m) blocks += a.d_out[m] / (16 * RB);
     note_launch("small FM=%d FA=%d NW=%d NQ=%d RB=%d n=%d", FM, FA, NW, NQ, RB, a.n);
@@ -532,14 +498,6 @@ static hipError_t launch_small_one(const GroupArgs& a, hipStream_t stream)
         // compute units evenly).  128 registers: 16 wavefronts, i.e. 16 / NW workgroups, per compute unit.
         // (The bare layer has no such wait: one row block each streams best; with 3-bit factors, and with 4-bit
         // factors on a 4-bit backbone, the strip instantiations do not fit 128 registers.)
-#ifdef EORA_FORCE_RB
-        if constexpr (NQ <= 2 && FA != S_Q3S128) {
-            bool ev = true;
-            for (int m = 0; m < a.n; ++m) ev = ev && a.d_out[m] % 32 == 0;
-            if (EORA_FORCE_RB == 2 && ev) return launch_small_m<FM, FA, FE, NW, NQ, true, 2>(a, stream);
-            return launch_small_m<FM, FA, FE, NW, NQ, true, 1>(a, stream);
-        }
-#endif
         if constexpr (NQ <= 2 && FA != S_NONE && FA != S_Q3S128) {
             int blocks = 0;
             bool even2 = true, even4 = true;

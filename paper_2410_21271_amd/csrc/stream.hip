@@ -1,0 +1,551 @@
+// The compensated quantised layer for 5 .. 16 tokens with x resident in LDS:
+//
+//      y = x.What^T + (x.A^T).B^T          (Sec. 3 forward equation, Alg. 1 step 7)
+//
+// HBM-bound: every stored byte is read once.  With 16 tokens a token block's x is as many bytes as four row blocks
+// of 4-bit weights, so x must stay put while the weights stream past it.  For d_in <= 4096 the whole x (16 tokens x
+// d_in halves, 128 KiB at 4096) fits the LDS of a compute unit: ONE workgroup of 16 wavefronts per compute unit keeps
+// it there for its whole life, and every output tile is finished inside the workgroup that started it: no partial
+// tile ever goes through memory.
+//
+// A workgroup owns a contiguous run of 16-row blocks of the launch's members.  Its wavefronts are KS ranges of the
+// contraction length x SLOTS row blocks at a time (KS * SLOTS = 16); a wavefront's work is a fixed sequence of
+// units (up to four stored tiles, with one load for their scales and one for their zero-points), requested three
+// units ahead into the registers just consumed, the first ones before x is staged.  The accumulators stay in
+// registers until the workgroup's last tile is consumed; then x is dead, and its LDS takes the KS partial tiles of
+// every row block and t.  One wavefront per row block adds the partial tiles in the order of the ranges, continues
+// with t.B^T and stores y.  Two barriers per workgroup after the staging of x.
+//
+// Low-rank path: the launch's first workgroups each begin with one 16-row block of A: all sixteen wavefronts take a
+// sixteenth of the contraction, the partial tiles are added through LDS in a fixed order, and that 16 x 16 tile of
+// t = x.A^T is published as (value, launch tag) pairs, one 8-byte write-through store each.  These workgroups own
+// fewer output row blocks, by about the bytes of their block of A.  After the first barrier every thread reads its
+// few pairs of t: a pair with this launch's tag is this launch's value; a stale one is read again, past the caches
+// (bounded).  Nobody waits for an acknowledgement.  (Asking for the pairs earlier, while stored tiles are still in
+// flight, was measured slower: the registers it holds cost more than the round trip it hides.)
+//
+// Arithmetic is the decode kernel's: codes as fp16 subnormals, position factors in the staged x, zero-points as
+// -z sum(x) per (token, group), fp32 accumulation per group scaled once (tiles.hpp); t in fp32, split into a high
+// and a low fp16 part for B's product.
+// A wavefront that waits for t relies on the workgroups that hold A's blocks running: they are the launch's first,
+// and the grid never exceeds one workgroup per compute unit.
+#include "segments.hpp"
+
+namespace eora {
+
+constexpr int RX_NW = 16, RX_NT = RX_NW * 64;
+constexpr int RX_RMAX = 4;                       // rounds of SLOTS row blocks a workgroup takes at most
+constexpr int RX_TP = 4;                         // pairs of t a thread requests together
+
+template <typename T>
+__device__ __forceinline__ T sk_pick(const T (&arr)[MAX_GROUP], int m)
+{
+    T v = arr[0];
+    v = m == 1 ? arr[1] : v;
+    v = m == 2 ? arr[2] : v;
+    v = m == 3 ? arr[3] : v;
+    return v;
+}
+
+template <int K>
+__device__ __forceinline__ float sk_row_shr(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x110 + K, 0xF, 0xF, true));
+}
+
+// 1 / xscale_chunk: brings a staged fragment back to x itself (A's product needs x, not x times the position factors)
+template <int WORDS>
+__device__ __forceinline__ h8 sk_unscale(int c)
+{
+    const _Float16 o = (_Float16)1.0f, e = (_Float16)8.0f, q = (_Float16)4.0f, s = (_Float16)16.0f, x = (_Float16)64.0f;
+    if constexpr (WORDS == 4) {
+        return h8{o, o, s, s, o, o, s, s};
+    } else if constexpr (WORDS == 2) {
+        return h8{o, o, q, q, s, s, x, x};
+    } else {
+        const h8 c0 = {o, o, e, e, x, x, o, o}, c1 = {e, e, o, o, e, e, x, x}, c2 = {o, o, e, e, o, o, e, e}, c3 = {x, x, o, o, e, e, o, o};
+        h8 r = c0;
+        r = c == 1 ? c1 : r;
+        r = c == 2 ? c2 : r;
+        r = c == 3 ? c3 : r;
+        return r;
+    }
+}
+
+
+template <int FM, int FA, int FE, int NTW>       // NTW: stored tiles of a row block per wavefront
+__global__ __launch_bounds__(RX_NT) void resident_kernel(StreamArgs a)
+{
+    constexpr bool LOWRANK = FA != S_NONE;
+    constexpr int WORDS = Fmt<FM>::WORDS;
+    constexpr int FAB = LOWRANK ? FA : S_F16, FEB = LOWRANK ? FE : S_F16;     // (valid formats also where the low-rank code is compiled out)
+    constexpr int UT = NTW < 4 ? NTW : 4, UPR = NTW / UT;                       // tiles per unit, units per round
+    constexpr int NL = RX_RMAX * UPR;                                           // units of a wavefront at most
+    constexpr int WQ = 3;                                                       // units in flight
+    __shared__ uint32_t s_epoch, s_err;
+
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;    // (wave: uniform, in a scalar register)
+    const int n = lane & 15, j = lane >> 4;
+    const int G = a.d_in / 128, ldx = a.d_in + 8;                     // halves per staged row of x (16 bytes of padding: conflict-free fragment reads)
+    const int KS = G / NTW, SLOTS = RX_NW / KS;
+    const int ks = wave % KS, slot = wave / KS;
+    _Float16* xs = (_Float16*)eora_smem;                              // [16][ldx]
+    float* gs = (float*)(eora_smem + (size_t)16 * ldx * 2);           // [G][16]: -z's factor of (group, token)
+    f4* pa = (f4*)(gs + G * 16);                                      // [16][64]: partial tiles of a block of A
+    // after the backbone, over x: the row blocks' partial tiles [round][wavefront][64], then t [member][16][r + 4]
+    f4* p2 = (f4*)eora_smem;
+    float* ts = (float*)(eora_smem + (size_t)RX_RMAX * RX_NW * 64 * 16);
+    const int ldt = a.r + 4;
+
+    const int NAm = LOWRANK ? a.r / 16 : 0, nprod = NAm * a.n;        // A's row blocks: per member, in all (one per workgroup, the first ones)
+    const int nb0 = a.d_out[0] / 16, nb1 = a.n > 1 ? a.d_out[1] / 16 : 0, nb2 = a.n > 2 ? a.d_out[2] / 16 : 0,
+              nb3 = a.n > 3 ? a.d_out[3] / 16 : 0;
+    const int NO = nb0 + nb1 + nb2 + nb3;
+    const int bid = (int)blockIdx.x;
+    const bool producer = bid < nprod;
+    // output row blocks [b0, b1) of this workgroup
+    int b0 = producer ? bid * a.qp : nprod * a.qp + (bid - nprod) * a.q;
+    int b1 = b0 + (producer ? a.qp : a.q);
+    b0 = b0 < NO ? b0 : NO;
+    b1 = b1 < NO ? b1 : NO;
+    const int nblk = b1 - b0;
+    const int rounds_w = slot < nblk ? (nblk - slot + SLOTS - 1) / SLOTS : 0;
+    const int nunits = rounds_w * UPR;
+
+    uint32_t epoch_v = 0;
+    if (LOWRANK && tid == 0) epoch_v = ld_relaxed(&a.hdr[HDR_EPOCH]);
+
+    // output block o of the launch -> its member and row block there
+    auto locate = [&](int o, int& mem, int& rb) __attribute__((always_inline)) {
+        mem = 0;
+        rb = o;
+        if (a.n > 1 && rb >= nb0) {
+            rb -= nb0;
+            mem = 1;
+            if (a.n > 2 && rb >= nb1) {
+                rb -= nb1;
+                mem = 2;
+                if (a.n > 3 && rb >= nb2) {
+                    rb -= nb2;
+                    mem = 3;
+                }
+            }
+        }
+    };
+
+    // ---- stored tiles: unit L = round L / UPR, tiles ks * NTW + (L % UPR) * UT .. + UT - 1 of its row block ---------
+    uint2 sc[WQ];
+    uint32_t zq[WQ];
+    uint32_t wq[WQ][UT][WORDS];
+    auto request = [&](auto Lc) __attribute__((always_inline)) {
+        constexpr int L = decltype(Lc)::value, Q = L % WQ;
+        int mem, rb;
+        locate(b0 + (L / UPR) * SLOTS + slot, mem, rb);
+        const int g0 = ks * NTW + (L % UPR) * UT;
+        const size_t row = (size_t)rb * 16 + n;
+        if constexpr (UT == 4) sc[Q] = *(const uint2*)(sk_pick(a.w_scales, mem) + row * G + g0);
+        else sc[Q] = uint2{*(const uint32_t*)(sk_pick(a.w_scales, mem) + row * G + g0), 0u};
+        zq[Q] = sk_pick(a.w_zeros, mem)[row * (G / 8) + (g0 >> 3)] >> (4 * (g0 & 7));
+        const uint32_t* wp = (const uint32_t*)sk_pick(a.w, mem) + (((size_t)rb * G + g0) * 64 + lane) * WORDS;
+#pragma unroll
+        for (int i = 0; i < UT; ++i) load_words<WORDS>(wq[Q][i], wp + (size_t)i * 64 * WORDS);
+    };
+    // The first requests go out before x is staged.  A workgroup that begins with a block of A asks for ALL of that
+    // block's tiles instead (its critical path: every workgroup of the launch ends up waiting for t), and for its first
+    // stored tiles of the backbone once those are consumed.
+    constexpr int KTA = Fmt<FAB>::KT, NMFA = KTA / 32, ATW = 256 / KTA;     // ATW: tiles of A per wavefront at most (d_in <= 4096: 256 columns)
+    const Factor fa{(const uint32_t*)sk_pick(a.A, producer ? bid / (NAm > 0 ? NAm : 1) : 0),
+                    sk_pick(a.A_scales, producer ? bid / (NAm > 0 ? NAm : 1) : 0), a.d_in / KTA};
+    const int nwa = fa.ntk < RX_NW ? fa.ntk : RX_NW, tpw = fa.ntk / nwa;      // wavefronts that take part in a block of A, tiles of each
+    FTile<FAB> abuf[ATW];
+    auto first_requests = [&]() __attribute__((always_inline)) {
+        if (0 < nunits) request(std::integral_constant<int, 0>{});
+        if (1 < nunits) request(std::integral_constant<int, 1>{});
+        if (2 < nunits) request(std::integral_constant<int, 2>{});
+    };
+    if (LOWRANK && producer) {
+        if (wave < nwa) {
+            const int rho = bid % NAm;
+#pragma unroll
+            for (int u = 0; u < ATW; ++u)
+                if (u < tpw) load_ftile<FAB>(abuf[u], fa, rho, wave * tpw + u, lane);
+        }
+    } else {
+        first_requests();
+    }
+    __builtin_amdgcn_sched_barrier(0);                                // (all of them out before anything below waits)
+
+    // ---- x: 16 x d_in halves, d_in / 512 16-byte chunks per thread ---------------------------------------------------
+    {
+        const int cpr = a.d_in / 8, lcpr = 31 - __builtin_clz(cpr);   // chunks per row (a power of two)
+        const int nk = a.d_in / 512;
+        const h8 pat = xscale_chunk<WORDS>(tid & 3);                  // RX_NT is a multiple of 4: the chunk's place in its lane's 32 columns
+        const h2 ones = {(_Float16)1.0f, (_Float16)1.0f};
+        constexpr int XB = 4;                                         // chunks requested together
+        for (int k0 = 0; k0 < nk; k0 += XB) {
+            u4 xv[XB];
+#pragma unroll
+            for (int k = 0; k < XB; ++k) {
+                const int c = tid + (k0 + k < nk ? k0 + k : 0) * RX_NT, row = c >> lcpr, cc = c & (cpr - 1);
+                const int m = row < a.M ? row : 0;                    // rows beyond the tokens repeat row 0; never stored
+                xv[k] = *(const u4*)(a.x + (size_t)m * a.d_in + cc * 8);
+            }
+#pragma unroll
+            for (int k = 0; k < XB; ++k) {
+                if (k0 + k < nk) {
+                    const int c = tid + (k0 + k) * RX_NT, row = c >> lcpr, cc = c & (cpr - 1);
+                    Frag f;
+                    f.q = xv[k];
+                    float sum = 0.f;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) sum = __builtin_amdgcn_fdot2(f.p[e], ones, sum, false);
+                    // the 16 chunks of a group sit in the 16 lanes of one DPP row: inclusive scan, the last lane ends with the sum
+                    sum += sk_row_shr<1>(sum);
+                    sum += sk_row_shr<2>(sum);
+                    sum += sk_row_shr<4>(sum);
+                    sum += sk_row_shr<8>(sum);
+                    if ((tid & 15) == 15) gs[(cc >> 4) * 16 + row] = sum * 0x1p-24f;
+                    f.v = f.v * pat;
+                    *(u4*)(xs + (size_t)row * ldx + cc * 8) = f.q;
+                }
+            }
+        }
+    }
+    if (tid == 0) {
+        s_epoch = epoch_v;
+        s_err = 0u;
+    }
+    __syncthreads();
+    const uint32_t tag = s_epoch + 1;
+    bool fine = true;
+    if (LOWRANK && tid == 0) arrive(epoch_v, a.hdr, bid);             // (an atomic nobody waits for; the epoch has been read)
+
+    // ---- a block of A: t's 16 x 16 tile (member, rows 16 rho ..) over the whole contraction --------------------------
+    if constexpr (LOWRANK) {
+        if (producer) {
+            const int mem = bid / NAm, rho = bid - mem * NAm;
+            f4 acc_a = {0.f, 0.f, 0.f, 0.f};
+            if (wave < nwa) {
+                const int t0 = wave * tpw;
+#pragma unroll
+                for (int u = 0; u < ATW; ++u) {
+                    if (u < tpw) {
+                        h8 b[NMFA];
+                        decode_tile<FAB>(abuf[u].w, 8u, b);
+                        const _Float16* px = xs + (size_t)n * ldx + (t0 + u) * KTA + (KTA / 4) * j;
+                        f4 part = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                        for (int q = 0; q < NMFA; ++q) {
+                            // chunk number of these eight columns modulo 4: the fragment's position factors
+                            const h8 xa = *(const h8*)(px + 8 * q) * sk_unscale<WORDS>(NMFA == 1 ? j : q);
+                            part = mfma16(xa, b[q], part);
+                        }
+                        if constexpr (FAB == S_F16) acc_a += part;
+                        else acc_a += (float)abuf[u].sc * part;
+                    }
+                }
+            }
+            first_requests();
+            pa[wave * 64 + lane] = acc_a;
+            __syncthreads();
+            if (wave == 0) {
+                f4 v = pa[lane];
+                for (int k = 1; k < nwa; ++k) v += pa[k * 64 + lane];
+                // register v of lane (n, j): token 4j + v, row 16 rho + n of t
+                const float tv[4] = {v.x, v.y, v.z, v.w};
+                unsigned long long* const dst = a.tpair + ((size_t)mem * 16) * a.r + 16 * rho + n;
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    __hip_atomic_store(dst + (size_t)(4 * j + i) * a.r, ((unsigned long long)tag << 32) | __builtin_bit_cast(uint32_t, tv[i]),
+                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+    }
+
+    // ---- the backbone --------------------------------------------------------------------------------------------
+    // this thread's pairs of t: elements tid, tid + 1024, ... of [member][16][r], read after the backbone
+    const int T = LOWRANK ? a.n * 16 * a.r : 0;
+    unsigned long long tp[RX_TP];
+    // the wavefront that finishes local row block `wave` asks for B's first tiles of it when its last stored tile is consumed
+    constexpr int KTB = Fmt<FEB>::KT, NMFB = KTB / 32, BPRE = NMFB == 1 ? 4 : 1;
+    const bool reducer = wave < nblk;
+    int rmem = 0, rrb = 0;
+    if (reducer) locate(b0 + wave, rmem, rrb);
+    const Factor fb{(const uint32_t*)sk_pick(a.B, rmem), sk_pick(a.B_scales, rmem), LOWRANK ? a.r / KTB : 0};
+    FTile<FEB> bt[BPRE];
+    f4 acc[RX_RMAX];
+#pragma unroll
+    for (int r2 = 0; r2 < RX_RMAX; ++r2) acc[r2] = f4{0.f, 0.f, 0.f, 0.f};
+    auto consume = [&](auto Lc) __attribute__((always_inline)) {
+        constexpr int L = decltype(Lc)::value, Q = L % WQ;
+        const int g0 = ks * NTW + (L % UPR) * UT;
+#pragma unroll
+        for (int i = 0; i < UT; ++i) {
+            h8 b[4];
+            raw_tile<WORDS>(wq[Q][i], b);
+            const float zf = -(float)((zq[Q] >> (4 * i)) & 0xFu);
+            f4 part = zf * *(const f4*)(gs + (g0 + i) * 16 + 4 * j);  // tokens 4j .. 4j+3: the registers of this lane
+            const _Float16* px = xs + (size_t)n * ldx + (g0 + i) * 128 + 32 * j;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) part = mfma16(*(const h8*)(px + 8 * t), b[t], part);
+            const uint32_t sw = (i < 2) ? sc[Q].x : sc[Q].y;
+            const _Float16 s16 = __builtin_bit_cast(_Float16, (uint16_t)((i & 1) ? (sw >> 16) : (sw & 0xFFFFu)));
+            acc[L / UPR] += (float)s16 * part;
+        }
+        if constexpr (L + WQ < NL) {
+            if (L + WQ < nunits) request(std::integral_constant<int, L + WQ>{});
+        }
+    };
+    static_assert(NL <= 8, "more units than the unrolled sequence below");
+    if (0 < nunits) consume(std::integral_constant<int, 0>{});
+    if (1 < nunits) consume(std::integral_constant<int, 1>{});
+    if (2 < nunits) consume(std::integral_constant<int, 2>{});
+    if (3 < nunits) consume(std::integral_constant<int, 3>{});
+    if constexpr (NL > 4) {
+        if (4 < nunits) consume(std::integral_constant<int, 4>{});
+        if (5 < nunits) consume(std::integral_constant<int, 5>{});
+        if (6 < nunits) consume(std::integral_constant<int, 6>{});
+        if (7 < nunits) consume(std::integral_constant<int, 7>{});
+    }
+
+    if constexpr (LOWRANK) {
+        if (reducer) {
+#pragma unroll
+            for (int u = 0; u < BPRE; ++u) load_ftile<FEB>(bt[u], fb, rrb, u < fb.ntk ? u : 0, lane);
+        }
+    }
+
+    // ---- x is dead: its LDS takes the partial tiles and t -----------------------------------------------------------
+    __syncthreads();
+#pragma unroll
+    for (int r2 = 0; r2 < RX_RMAX; ++r2)
+        if (r2 < rounds_w) p2[(r2 * RX_NW + wave) * 64 + lane] = acc[r2] * 0x1p24f;      // (the subnormal codes' common factor)
+    if constexpr (LOWRANK) {
+        for (int e0 = 0; e0 < T; e0 += RX_TP * RX_NT) {
+            // first an ordinary, cached load: the workgroups of an XCD share its L2's copy (a stale copy shows by its tag)
+#pragma unroll
+            for (int u = 0; u < RX_TP; ++u) {
+                const int e = e0 + tid + u * RX_NT;
+                tp[u] = a.tpair[e < T ? e : 0];
+            }
+            // a pair with this launch's tag is this launch's value; stale ones: all of the thread's pairs again, together
+            bool good = a.spin_limit >= 0;                            // (a negative limit: every wait counts as expired)
+            for (int sp = 0;; ++sp) {
+                uint32_t bad = 0;
+#pragma unroll
+                for (int u = 0; u < RX_TP; ++u)
+                    if (e0 + tid + u * RX_NT < T) bad |= (uint32_t)(tp[u] >> 32) ^ tag;
+                good = good && bad == 0;
+                if (good || sp >= a.spin_limit) break;
+                good = true;
+                __builtin_amdgcn_s_sleep(2);
+#pragma unroll
+                for (int u = 0; u < RX_TP; ++u) {
+                    const int e = e0 + tid + u * RX_NT;
+                    tp[u] = __hip_atomic_load(a.tpair + (e < T ? e : 0), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+            }
+            fine = fine && good;
+#pragma unroll
+            for (int u = 0; u < RX_TP; ++u) {
+                const int e = e0 + tid + u * RX_NT;
+                if (e < T) {
+                    const int row = e / a.r;                          // member * 16 + token
+                    ts[row * ldt + (e - row * a.r)] = __builtin_bit_cast(float, (uint32_t)tp[u]);
+                }
+            }
+        }
+        if (!__all(fine)) s_err = 1u;
+    }
+    __syncthreads();
+
+    // ---- one wavefront per row block: the ranges' partial tiles in their order, t.B^T, y -----------------------------
+    if (reducer) {
+        const int rnd = wave / SLOTS, sl = wave % SLOTS;
+        const f4* src = p2 + ((size_t)rnd * RX_NW + sl * KS) * 64 + lane;
+        f4 ysum = src[0];
+        for (int k = 1; k < KS; ++k) ysum += src[k * 64];
+        if constexpr (LOWRANK) {
+            if (s_err == 0u) {                                        // (t never came: y lacks the low-rank term, the launch reports it)
+                const float* trow = ts + (size_t)(rmem * 16 + n) * ldt + (KTB / 4) * j;
+                auto ext_tile = [&](const FTile<FEB>& cw, int g) __attribute__((always_inline)) {
+                    h8 b[NMFB];
+                    decode_tile<FEB>(cw.w, 8u, b);
+                    f4 part = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int q = 0; q < NMFB; ++q) {
+                        const float* p = trow + g * KTB + 8 * q;
+                        const f4 v0 = *(const f4*)p, v1 = *(const f4*)(p + 4);
+                        const float e0[4] = {v0.x, v0.y, v0.z, v0.w}, e1[4] = {v1.x, v1.y, v1.z, v1.w};
+                        h8 hi, lo;
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const _Float16 h0 = (_Float16)e0[i], h1 = (_Float16)e1[i];
+                            hi[i] = h0;
+                            hi[4 + i] = h1;
+                            lo[i] = (_Float16)(e0[i] - (float)h0);
+                            lo[4 + i] = (_Float16)(e1[i] - (float)h1);
+                        }
+                        part = mfma16(hi, b[q], part);
+                        part = mfma16(lo, b[q], part);
+                    }
+                    if constexpr (FEB == S_F16) ysum += part;
+                    else ysum += (float)cw.sc * part;
+                };
+                for (int g0 = 0; g0 < fb.ntk; g0 += BPRE) {
+#pragma unroll
+                    for (int u = 0; u < BPRE; ++u) {
+                        if (g0 + u < fb.ntk) {
+                            const FTile<FEB> cw = bt[u];
+                            if (g0 + u + BPRE < fb.ntk) load_ftile<FEB>(bt[u], fb, rrb, g0 + u + BPRE, lane);
+                            ext_tile(cw, g0 + u);
+                        }
+                    }
+                }
+            }
+        }
+        const float yv[4] = {ysum.x, ysum.y, ysum.z, ysum.w};
+        _Float16* const y = sk_pick(a.y, rmem);
+        const int d_out = sk_pick(a.d_out, rmem);
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+            if (4 * j + v < a.M) y[(size_t)(4 * j + v) * d_out + rrb * 16 + n] = (_Float16)yv[v];
+    }
+
+    // ---- the launch's last workgroup (by index) advances the launch counter once every workgroup has arrived ---------
+    if constexpr (LOWRANK) {
+        if (tid == 0 && s_err) atomicOr(&a.hdr[HDR_ERROR], 1u);
+        if (bid == (int)gridDim.x - 1 && wave == RX_NW - 1) {
+            if (!advance_epoch(s_epoch, a.hdr, gridDim.x, lane, a.spin_limit) && lane == 0) atomicOr(&a.hdr[HDR_ERROR], 1u);
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------------------------
+constexpr size_t RX_LDS_MAX = 159 * 1024;       // dynamic LDS of a workgroup at most (a compute unit has 160 KiB; a few static bytes beside)
+
+static size_t resident_lds(int d_in, int r, int n)
+{
+    const size_t front = (size_t)16 * (d_in + 8) * 2 + (size_t)(d_in / 128) * 16 * 4 + (size_t)RX_NW * 64 * 16;
+    const size_t back = (size_t)RX_RMAX * RX_NW * 64 * 16 + (size_t)n * 16 * (r + 4) * 4;
+    return front > back ? front : back;
+}
+
+// how a launch is cut: NTW tiles per wavefront, q row blocks per workgroup (qp for one that begins with a block of A)
+struct ResidentPlan {
+    int ntw, q, qp, wgs;
+};
+
+static int device_cus()
+{
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return 0;
+        cus = prop.multiProcessorCount;
+    }
+    return cus;
+}
+
+// Below this many row blocks in a launch the kernel for 5 .. 127 tokens is the faster one (measured: every workgroup
+// here stages the whole x, which a launch of few rows does not earn back).
+constexpr int RX_MIN_BLOCKS = 384;
+static int g_min_blocks = RX_MIN_BLOCKS;
+void set_resident_min_blocks(int blocks) { g_min_blocks = blocks < 0 ? RX_MIN_BLOCKS : blocks; }
+
+static bool resident_plan(int d_in, int r, int fm, int fa, const int* d_out, int n, ResidentPlan& p)
+{
+    const int cus = device_cus();
+    if (cus <= 0) return false;
+    int NO = 0;
+    for (int m = 0; m < n; ++m) NO += d_out[m] / 16;
+    const int nprod = r > 0 ? n * (r / 16) : 0;
+    if (nprod > cus / 2) return false;
+    // a block of A in output row blocks, by stored bytes
+    const int wbits = fm == S_Q4 ? 4 : fm == S_Q3 ? 3 : 2, abits = fa == S_F16 ? 16 : 4;
+    const int acost = r > 0 ? (abits + wbits - 1) / wbits : 0;
+    p.q = (NO + nprod * acost + cus - 1) / cus;
+    p.q = p.q < 1 ? 1 : p.q;
+    p.qp = p.q > acost ? p.q - acost : 0;
+    const int rest = NO - nprod * p.qp;
+    p.wgs = nprod + (rest > 0 ? (rest + p.q - 1) / p.q : 0);
+    if (p.wgs > cus) return false;
+    const int G = d_in / 128;
+    for (int ntw = 2; ntw <= 8; ntw *= 2) {
+        const int KS = G / ntw;
+        if (KS < 1 || KS > RX_NW || G % ntw != 0 || RX_NW % KS != 0) continue;
+        const int slots = RX_NW / KS, rounds = (p.q + slots - 1) / slots;
+        if (rounds <= RX_RMAX && rounds * slots <= RX_NW && (slots >= p.q || slots >= 4 || ntw == 8)) {
+            p.ntw = ntw;
+            return true;
+        }
+    }
+    return false;
+}
+
+bool stream_fits(int M, int d_in, int group, int r, int fm, int fa, const int* d_out, int n)
+{
+    if (M < 5 || M > 16 || group != 128) return false;
+    if (d_in != 1024 && d_in != 2048 && d_in != 4096) return false;
+    if (r > 0 && fa != S_F16 && fa != S_Q4S128) return false;
+    if (r > 0 && fa == S_Q4S128 && r % 128 != 0) return false;        // (B's 64-column tiles of a rank-64 pair: not instantiated here)
+    if (r % 32 != 0 || n * r > 512 || resident_lds(d_in, r, n) > RX_LDS_MAX) return false;
+    int NO = 0;
+    for (int m = 0; m < n; ++m) NO += d_out[m] / 16;
+    if (NO < g_min_blocks) return false;
+    ResidentPlan p;
+    return resident_plan(d_in, r, fm, fa, d_out, n, p);
+}
+
+template <int FM, int FA, int FE, int NTW>
+static hipError_t launch_resident_one(StreamArgs a, const ResidentPlan& p, hipStream_t stream)
+{
+    auto kern = resident_kernel<FM, FA, FE, NTW>;
+    const size_t lds = resident_lds(a.d_in, FA != S_NONE ? a.r : 0, a.n);
+    static bool prepared = false;
+    if (!prepared) {
+        const hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)RX_LDS_MAX);
+        if (e != hipSuccess) return e;
+        prepared = true;
+    }
+    a.q = p.q;
+    a.qp = p.qp;
+    note_launch("resident FM=%d FA=%d NTW=%d n=%d wgs=%d q=%d", FM, FA, NTW, a.n, p.wgs, p.q);
+    hipLaunchKernelGGL(kern, dim3(p.wgs), dim3(RX_NT), lds, stream, a);
+    return hipGetLastError();
+}
+
+template <int FM, int FA, int FE>
+static hipError_t launch_resident_ntw(const StreamArgs& a, const ResidentPlan& p, hipStream_t stream)
+{
+    switch (p.ntw) {
+        case 2: return launch_resident_one<FM, FA, FE, 2>(a, p, stream);
+        case 4: return launch_resident_one<FM, FA, FE, 4>(a, p, stream);
+        case 8: return launch_resident_one<FM, FA, FE, 8>(a, p, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+template <int FM>
+static hipError_t launch_stream_ab(const StreamArgs& a, const ResidentPlan& p, int fa, int fe, hipStream_t stream)
+{
+    if (fe == S_NONE) return launch_resident_ntw<FM, S_NONE, S_NONE>(a, p, stream);
+    if (fa == S_F16 && fe == S_F16) return launch_resident_ntw<FM, S_F16, S_F16>(a, p, stream);
+    if (fa == S_Q4S128 && fe == S_Q4S128) return launch_resident_ntw<FM, S_Q4S128, S_Q4S128>(a, p, stream);
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_stream(const StreamArgs& a, int fm, int fa, int fe, hipStream_t stream)
+{
+    ResidentPlan p;
+    if (!resident_plan(a.d_in, fe == S_NONE ? 0 : a.r, fm, fa, a.d_out, a.n, p)) return hipErrorInvalidValue;
+    switch (fm) {
+        case S_Q4: return launch_stream_ab<S_Q4>(a, p, fa, fe, stream);
+        case S_Q3: return launch_stream_ab<S_Q3>(a, p, fa, fe, stream);
+        case S_Q2: return launch_stream_ab<S_Q2>(a, p, fa, fe, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace eora

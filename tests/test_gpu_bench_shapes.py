@@ -178,7 +178,7 @@ def test_prefill_config4_qkv_group(gpu):
 @pytest.mark.parametrize("w_bits,ab_bits,M,d_in,d_outs,want", [
     (3, 16, 1, 4096, (14336, 14336), "small FM=2 FA=5 NW=4 NQ=2 RB=2 n=2"),     # default workload: gate + up
     (3, 16, 1, 4096, (4096, 1024, 1024), "small FM=2 FA=5 NW=4 NQ=2 RB=1 n=3"),  # query + key + value
-    (4, 16, 16, 4096, (14336, 14336), "wide_q FM=1 FA=5 NWR=4 NWK=2 TB=1 n=2"),  # config 1 shapes at 16 tokens, grouped
+    (4, 16, 16, 4096, (14336, 14336), "resident FM=1 FA=5 NTW=8 n=2 wgs=232 q=8"),      # config 1 shapes at 16 tokens, grouped
     (4, 16, 64, 4096, (14336, 14336), "wide_q FM=1 FA=5 NWR=4 NWK=2 TB=4 n=2"),  # four token blocks per workgroup
 ])
 def test_quantised_groups_reach_their_kernels(gpu, w_bits, ab_bits, M, d_in, d_outs, want):
