@@ -559,44 +559,45 @@ def main():
                                   # alone, a launch rotates over its own copies only: below the 256 MB last-level
                                   # cache (twice, to be safe) its figure may be cache-assisted; the layer's is not
                                   rotation_MB=round(ncopies * L.bytes / 1e6, 1), cache_assisted=bool(ncopies * L.bytes < 512e6))
-    # Dominant kernel: launches are grouped by the kernel instantiation that serves them (decode: one per
-    # d_in, and a two-row-blocks-per-workgroup variant for single-token low-rank launches of more than
-    # 1024 row blocks; prefill: one GEMM kernel); the group with the largest time per step is reported.
-    # Its average launch moves the average algorithmic bytes of its launches; its average duration is
-    # the mean of their event-timed back-to-back launches (which includes the gap between launches).
-    def kernel_key(L):
-        members = getattr(L, "members", [L])
-        blocks = sum(m.d_out // 16 for m in members)
-        two = (spec["M"] == 1 and spec["r"] > 0 and spec["w_bits"] != 0 and L.d_in in (4096, 8192) and blocks > 1024
-               and all(m.d_out % 32 == 0 for m in members))
-        return (L.d_in, two)
+    # Dominant kernel: launches are grouped by the kernel instantiation that serves them, as the library reports it
+    # (eora_debug_last_launch without the run-time arguments); the instantiation whose launches move the most
+    # algorithmic bytes per step is reported.  Its average launch moves the average algorithmic bytes of its
+    # launches; its average duration is the mean of their event-timed back-to-back launches (which includes the
+    # gap between launches).
+    import re
+    import paper_2410_21271_amd as eora
+    for L in launches:
+        L.run(0)
+        torch.cuda.synchronize()
+        L.kernel = re.sub(r" (n|wgs|q|ksplit)=\d+", "", eora.debug_last_launch())
+        per_linear[L.name]["kernel"] = L.kernel
     groups = {}
     for L in launches:
-        groups.setdefault(kernel_key(L), []).append(L)
-    dom = max(groups.values(), key=lambda g: sum(per_linear[L.name]["us"] for L in g))
+        groups.setdefault(L.kernel, []).append(L)
+    dom = max(groups.values(), key=lambda g: (sum(L.bytes for L in g), sum(per_linear[L.name]["us"] for L in g)))
     dom_bytes = sum(L.bytes for L in dom) / len(dom)
     dom_us = sum(per_linear[L.name]["us"] for L in dom) / len(dom)
-    # HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter runs of this workload (not
-    # collected in this run: counters and timing need runs of their own); null when no such run is recorded
+    # HBM bytes per launch of that kernel from the committed rocprofv3 counter runs of this workload (not collected
+    # in this run: counters and timing need runs of their own); null when no such run is recorded for this kernel
     traffic, traffic_source = None, None
     tpath = os.path.join(ROOT, "profiles", "decode_traffic.json")
     if os.path.exists(tpath):
         with open(tpath) as f:
-            traffic = json.load(f).get(args.workload)
-        if traffic is not None:
-            traffic_source = "profiles/decode_traffic.json"
+            rec = json.load(f).get(args.workload)
+        if isinstance(rec, dict) and rec.get("kernel") == dom[0].kernel:
+            traffic, traffic_source = rec.get("bytes"), "profiles/decode_traffic.json"
     prefill = spec["M"] >= 128
     if prefill:
         # dominant kernel: the GEMM kernel; a launch contracts one linear (or one group of them)
         dom_flops = sum(L.flops for L in dom) / len(dom)
         roofline = dict(bound="mfma", achieved=round(dom_flops / dom_us / 1e6, 1), peak=MFMA_PEAK_TFLOPS, unit="TFLOP/s",
                         frac=round(dom_flops / dom_us / 1e6 / MFMA_PEAK_TFLOPS, 4), traffic=None,
-                        kernel="prefill GEMM kernel on the d_in=%d launches (%s)" % (dom[0].d_in, ",".join(L.name for L in dom)),
+                        kernel="%s (%s)" % (dom[0].kernel, ",".join(L.name for L in dom)),
                         flops_per_launch=int(dom_flops), us_per_launch=round(dom_us, 3))
     else:
         roofline = dict(bound="hbm", achieved=round(dom_bytes / dom_us / 1e3, 1), peak=HBM_PEAK_GBS, unit="GB/s",
                         frac=round(dom_bytes / dom_us / 1e3 / HBM_PEAK_GBS, 4), traffic=traffic,
-                        kernel="layer kernel instantiation of the d_in=%d launches (%s)" % (dom[0].d_in, ",".join(L.name for L in dom)),
+                        kernel="%s (%s)" % (dom[0].kernel, ",".join(L.name for L in dom)),
                         bytes_per_launch=int(dom_bytes), us_per_launch=round(dom_us, 3), traffic_source=traffic_source)
     floor_us, ceiling, probe_bytes = device_context(dom_bytes)
     roofline.update(launch_floor_us=floor_us, stream_ceiling_GBps=ceiling, stream_probe_bytes=probe_bytes)
