@@ -1,5 +1,6 @@
 """Build libeora.so (HIP, gfx950 only) in-tree with hipcc.  Usage: python paper_2410_21271_amd/build.py (run by path: the package itself cannot be imported before the library exists)"""
 import os
+import re
 import subprocess
 import sys
 from concurrent.futures import ThreadPoolExecutor
@@ -31,14 +32,41 @@ def _fresh(obj, src):
     return all(os.path.getmtime(d) < os.path.getmtime(obj) for d in deps)
 
 
+# Kernels of these files stream weights at four wavefronts per SIMD with every tile request in flight: an
+# instantiation that spills even a few bytes stores freshly requested data to scratch, waits for it first, and runs
+# 1.5 to 2 times slower with all tests still passing.  The build therefore reads the compiler's resource remarks
+# and refuses an instantiation with a non-zero scratch size.
+NO_SPILL = {"small.hip": "small_kernel", "stream.hip": "resident_kernel"}
+
+
+def _check_resources(src, remarks):
+    name, bad = None, []
+    for line in remarks.splitlines():
+        m = re.search(r"remark: Function Name: (\S+)", line)
+        if m:
+            name = m.group(1)
+        m = re.search(r"ScratchSize \[bytes/lane\]: (\d+)", line)
+        if m and name and NO_SPILL[src] in name and int(m.group(1)) > 0:
+            bad.append("%s: %s bytes of scratch per lane" % (name, m.group(1)))
+    if bad:
+        raise RuntimeError("%s: register spills in a kernel that must not have any:\n  %s" % (src, "\n  ".join(bad)))
+
+
 def _compile(src):
     obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
     if _fresh(obj, src):
         return obj
-    cmd = [_hipcc(), *FLAGS, "-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj]
+    extra = ["-Rpass-analysis=kernel-resource-usage"] if src in NO_SPILL else []
+    cmd = [_hipcc(), *FLAGS, *extra, "-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj]
     p = subprocess.run(cmd, capture_output=True, text=True)
     if p.returncode:
         raise RuntimeError("hipcc failed on %s:\n%s" % (src, p.stderr[-6000:]))
+    if src in NO_SPILL:
+        try:
+            _check_resources(src, p.stderr)
+        except RuntimeError:
+            os.remove(obj)
+            raise
     return obj
 
 

@@ -11,11 +11,11 @@
 namespace eora {
 
 namespace {
-struct LaunchNote { const char* fmt; int v[6]; };
-LaunchNote g_last_launch = {nullptr, {0, 0, 0, 0, 0, 0}};
+struct LaunchNote { const char* fmt; int v[7]; };
+LaunchNote g_last_launch = {nullptr, {0, 0, 0, 0, 0, 0, 0}};
 }  // namespace
 
-void note_launch(const char* fmt, int a, int b, int c, int d, int e, int f) { g_last_launch = {fmt, {a, b, c, d, e, f}}; }
+void note_launch(const char* fmt, int a, int b, int c, int d, int e, int f, int g) { g_last_launch = {fmt, {a, b, c, d, e, f, g}}; }
 
 }  // namespace eora
 
@@ -310,7 +310,7 @@ int eora_debug_last_launch(char* out, size_t capacity)
         out[0] = 0;
         return EORA_OK;
     }
-    snprintf(out, capacity, n.fmt, n.v[0], n.v[1], n.v[2], n.v[3], n.v[4], n.v[5]);
+    snprintf(out, capacity, n.fmt, n.v[0], n.v[1], n.v[2], n.v[3], n.v[4], n.v[5], n.v[6]);
     return EORA_OK;
 }
 

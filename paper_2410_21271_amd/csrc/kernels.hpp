@@ -31,7 +31,7 @@ constexpr int MAX_KCN = 8;                      // k-ranges of the down-projecti
 // Host-side record of the kernel instantiation the most recent layer launch of this process chose, read
 // back through eora_debug_last_launch() (tests assert that a shape reaches the instantiation it is meant to
 // cover).  `fmt` is a printf format for up to six ints and must be a string literal.  Not synchronised.
-void note_launch(const char* fmt, int a = 0, int b = 0, int c = 0, int d = 0, int e = 0, int f = 0);
+void note_launch(const char* fmt, int a = 0, int b = 0, int c = 0, int d = 0, int e = 0, int f = 0, int g = 0);
 
 struct FusedArgs {
     const _Float16* x;        // M x d_in fp16 row-major
@@ -88,6 +88,9 @@ struct StreamArgs {
     unsigned long long* tpair;          // [member][16 tokens][r] tagged t
     int M, d_in, r, spin_limit;
     int q, qp;                          // output row blocks per workgroup; per workgroup that begins with a block of A (set by the launcher)
+    uint32_t cpr_magic;                 // ceil(2^32 / (16-byte chunks of x per row of a range)): division by multiply-high (set by the launcher)
+    int S;                              // ranges of the contraction, one workgroup each per run of row blocks (set by the launcher)
+    unsigned long long* part;           // tagged partial tiles that cross ranges, behind t in the same region (set by the launcher)
 };
 // d_out: the members' rows (n of them)
 bool stream_fits(int M, int d_in, int group, int r, int fm, int fa, const int* d_out, int n);

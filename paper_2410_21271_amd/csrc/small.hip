@@ -8,12 +8,19 @@
 // the compiler can keep every request of a wavefront in flight and consume tiles as they arrive.
 //
 // Roles are split by workgroup index.  The first `units` workgroups are PRODUCERS: each computes one
-// unit of t = x.A^T ((16 rows of A) x (one of kcn ranges of k-tiles)), writes its fp32 partial
-// through to memory and raises flag[u] = epoch + 1; it owns no output rows, so nothing waits on its
-// critical path but the consumers.  The other workgroups are CONSUMERS: one strip of 16 output rows
-// each; backbone first, then one wavefront polls the flags, adds the kcn partials in a fixed order
-// into t (fp32, in LDS), and the wavefronts that own tiles of B continue the same accumulators with
+// unit of t = x.A^T ((16 rows of A) x (one of kcn ranges of k-tiles)) and writes it as (value, launch tag)
+// pairs, one 8-byte write-through store each; it owns no output rows and signals nothing else.  The other
+// workgroups are CONSUMERS: a strip of one or two 16-row blocks each, its stored tiles requested quad by quad
+// into the registers just consumed; after the backbone every thread reads its elements of t (the pairs of the
+// kcn ranges, added as two partial sums in a fixed order into LDS; a pair with an older tag is read again,
+// bounded), and the wavefronts share B's product in 32-column slices, continuing the same accumulators with
 // t split into a high and a low fp16 part.  Producers come first in dispatch order and never wait.
+//
+// The stored codes enter the MFMA as they are: masked in place they are fp16 subnormals (tiles.hpp), the
+// position factors sit in the staged x, the zero-points in one term per (token, group), the scale and the
+// common 2^24 in fp32 on the accumulator.  Nobody waits on a returning atomic: a workgroup announces that it
+// has read the launch counter with an atomic whose answer it ignores, and the launch's last workgroup
+// advances the counter at its very end.
 #include "segments.hpp"
 
 #include <type_traits>

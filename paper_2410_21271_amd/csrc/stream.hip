@@ -73,6 +73,66 @@ __device__ __forceinline__ h8 sk_unscale(int c)
 }
 
 
+// A partial tile handed from one range's workgroup to another's: 256 (value, launch tag) pairs, pair (i, lane) =
+// register i of the lane at i * 64 + lane, so that one store instruction of a wavefront fills four whole
+// 128-byte lines (write-through stores of parts of a line are read-modify-writes at the memory).
+__device__ __forceinline__ void rx_store_tile(unsigned long long* dst, const f4& v, uint32_t tag)
+{
+    const unsigned long long t = (unsigned long long)tag << 32;
+    const float vs[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        __hip_atomic_store(dst + i * 64, t | __builtin_bit_cast(uint32_t, vs[i]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// The owner's sum over the S ranges in ascending order: its own tile `mine` at position `own`, the others' from
+// slots[(k < own ? k : k - 1) * stride] (this lane's pairs), up to three ranges requested together; a tile whose
+// tags are stale is read again (bounded).  Returns false if a wait expired.
+__device__ __forceinline__ bool rx_cross_sum(const unsigned long long* slots, size_t stride, int S, int own, const f4& mine,
+                                             uint32_t tag, int spin_limit, f4& out)
+{
+    constexpr int KB = 3;
+    const int lim = spin_limit < 0 ? (1 << 22) : spin_limit;         // (a negative limit expires the waits for t only)
+    f4 sum = {0.f, 0.f, 0.f, 0.f};
+    bool fine = true;
+    bool mine_added = false;
+    for (int i0 = 0; i0 < S - 1; i0 += KB) {              // i: slot index of the other ranges, range k = i < own ? i : i + 1
+        unsigned long long pr[KB][4] = {};
+        bool good = false;
+        for (int sp = 0; !good && sp <= lim; ++sp) {
+            if (sp > 0) __builtin_amdgcn_s_sleep(2);
+            uint32_t bad = 0;
+#pragma unroll
+            for (int kk = 0; kk < KB; ++kk) {
+                const int i = i0 + kk < S - 1 ? i0 + kk : S - 2;      // past the last: that one again (not added)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) pr[kk][e] = __hip_atomic_load(slots + (size_t)i * stride + e * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+#pragma unroll
+            for (int kk = 0; kk < KB; ++kk)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) bad |= (uint32_t)(pr[kk][e] >> 32) ^ tag;
+            good = bad == 0;
+        }
+        fine = fine && good;
+#pragma unroll
+        for (int kk = 0; kk < KB; ++kk) {
+            const int i = i0 + kk;
+            if (i < S - 1) {
+                if (i == own) {                           // range `own` comes before range i + 1
+                    sum += mine;
+                    mine_added = true;
+                }
+                sum += f4{__builtin_bit_cast(float, (uint32_t)pr[kk][0]), __builtin_bit_cast(float, (uint32_t)pr[kk][1]),
+                          __builtin_bit_cast(float, (uint32_t)pr[kk][2]), __builtin_bit_cast(float, (uint32_t)pr[kk][3])};
+            }
+        }
+    }
+    if (!mine_added) sum += mine;                         // the owner is the last range
+    out = sum;
+    return fine;
+}
+
 template <int FM, int FA, int FE, int NTW>       // NTW: stored tiles of a row block per wavefront
 __global__ __launch_bounds__(RX_NT) void resident_kernel(StreamArgs a)
 {
@@ -81,17 +141,20 @@ __global__ __launch_bounds__(RX_NT) void resident_kernel(StreamArgs a)
     constexpr int FAB = LOWRANK ? FA : S_F16, FEB = LOWRANK ? FE : S_F16;     // (valid formats also where the low-rank code is compiled out)
     constexpr int UT = NTW < 4 ? NTW : 4, UPR = NTW / UT;                       // tiles per unit, units per round
     constexpr int NL = RX_RMAX * UPR;                                           // units of a wavefront at most
-    constexpr int WQ = 3;                                                       // units in flight
+    constexpr int WQ = FA == S_F16 ? 2 : 3;                                     // units in flight (with fp16 factors there are no registers for a third: eight tiles of A are held across the staging of x)
     __shared__ uint32_t s_epoch, s_err;
 
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;    // (wave: uniform, in a scalar register)
     const int n = lane & 15, j = lane >> 4;
-    const int G = a.d_in / 128, ldx = a.d_in + 8;                     // halves per staged row of x (16 bytes of padding: conflict-free fragment reads)
-    const int KS = G / NTW, SLOTS = RX_NW / KS;
+    // d_in beyond 4096: S ranges of KC = d_in / S columns; a workgroup belongs to range s and keeps that range's x
+    const int S = a.S, KC = a.d_in / S;
+    const int bid = (int)blockIdx.x, s = bid % S, wi = bid / S;       // range, index among the range's workgroups
+    const int G = a.d_in / 128, GL = KC / 128, ldx = KC + 8;          // halves per staged row of x (16 bytes of padding: conflict-free fragment reads)
+    const int KS = GL / NTW, SLOTS = RX_NW / KS;                      // (KS * SLOTS wavefronts stream; with 28 groups in a range 14 of the 16)
     const int ks = wave % KS, slot = wave / KS;
     _Float16* xs = (_Float16*)eora_smem;                              // [16][ldx]
-    float* gs = (float*)(eora_smem + (size_t)16 * ldx * 2);           // [G][16]: -z's factor of (group, token)
-    f4* pa = (f4*)(gs + G * 16);                                      // [16][64]: partial tiles of a block of A
+    float* gs = (float*)(eora_smem + (size_t)16 * ldx * 2);           // [GL][16]: -z's factor of (group, token)
+    f4* pa = (f4*)(gs + GL * 16);                                     // [16][64]: partial tiles of a block of A
     // after the backbone, over x: the row blocks' partial tiles [round][wavefront][64], then t [member][16][r + 4]
     f4* p2 = (f4*)eora_smem;
     float* ts = (float*)(eora_smem + (size_t)RX_RMAX * RX_NW * 64 * 16);
@@ -101,19 +164,19 @@ __global__ __launch_bounds__(RX_NT) void resident_kernel(StreamArgs a)
     const int nb0 = a.d_out[0] / 16, nb1 = a.n > 1 ? a.d_out[1] / 16 : 0, nb2 = a.n > 2 ? a.d_out[2] / 16 : 0,
               nb3 = a.n > 3 ? a.d_out[3] / 16 : 0;
     const int NO = nb0 + nb1 + nb2 + nb3;
-    const int bid = (int)blockIdx.x;
-    const bool producer = bid < nprod;
-    // output row blocks [b0, b1) of this workgroup
-    int b0 = producer ? bid * a.qp : nprod * a.qp + (bid - nprod) * a.q;
+    const bool producer = wi < nprod;
+    const bool tagged = LOWRANK || S > 1;                             // the launch uses (and advances) the workspace's launch counter
+    // output row blocks [b0, b1) of this workgroup (every range's workgroups cut the blocks alike)
+    int b0 = producer ? wi * a.qp : nprod * a.qp + (wi - nprod) * a.q;
     int b1 = b0 + (producer ? a.qp : a.q);
     b0 = b0 < NO ? b0 : NO;
     b1 = b1 < NO ? b1 : NO;
     const int nblk = b1 - b0;
-    const int rounds_w = slot < nblk ? (nblk - slot + SLOTS - 1) / SLOTS : 0;
+    const int rounds_w = (slot < SLOTS && slot < nblk) ? (nblk - slot + SLOTS - 1) / SLOTS : 0;
     const int nunits = rounds_w * UPR;
 
     uint32_t epoch_v = 0;
-    if (LOWRANK && tid == 0) epoch_v = ld_relaxed(&a.hdr[HDR_EPOCH]);
+    if (tagged && tid == 0) epoch_v = ld_relaxed(&a.hdr[HDR_EPOCH]);
 
     // output block o of the launch -> its member and row block there
     auto locate = [&](int o, int& mem, int& rb) __attribute__((always_inline)) {
@@ -141,7 +204,7 @@ __global__ __launch_bounds__(RX_NT) void resident_kernel(StreamArgs a)
         constexpr int L = decltype(Lc)::value, Q = L % WQ;
         int mem, rb;
         locate(b0 + (L / UPR) * SLOTS + slot, mem, rb);
-        const int g0 = ks * NTW + (L % UPR) * UT;
+        const int g0 = s * GL + ks * NTW + (L % UPR) * UT;            // (group of the whole contraction)
         const size_t row = (size_t)rb * 16 + n;
         if constexpr (UT == 4) sc[Q] = *(const uint2*)(sk_pick(a.w_scales, mem) + row * G + g0);
         else sc[Q] = uint2{*(const uint32_t*)(sk_pick(a.w_scales, mem) + row * G + g0), 0u};
@@ -153,32 +216,40 @@ __global__ __launch_bounds__(RX_NT) void resident_kernel(StreamArgs a)
     // The first requests go out before x is staged.  A workgroup that begins with a block of A asks for ALL of that
     // block's tiles instead (its critical path: every workgroup of the launch ends up waiting for t), and for its first
     // stored tiles of the backbone once those are consumed.
-    constexpr int KTA = Fmt<FAB>::KT, NMFA = KTA / 32, ATW = 256 / KTA;     // ATW: tiles of A per wavefront at most (d_in <= 4096: 256 columns)
-    const Factor fa{(const uint32_t*)sk_pick(a.A, producer ? bid / (NAm > 0 ? NAm : 1) : 0),
-                    sk_pick(a.A_scales, producer ? bid / (NAm > 0 ? NAm : 1) : 0), a.d_in / KTA};
-    const int nwa = fa.ntk < RX_NW ? fa.ntk : RX_NW, tpw = fa.ntk / nwa;      // wavefronts that take part in a block of A, tiles of each
+    constexpr int KTA = Fmt<FAB>::KT, NMFA = KTA / 32, ATW = 256 / KTA;     // ATW: tiles of A per wavefront at most (a range has <= 4096 columns: 256 each)
+    const Factor fa{(const uint32_t*)sk_pick(a.A, producer ? wi / (NAm > 0 ? NAm : 1) : 0),
+                    sk_pick(a.A_scales, producer ? wi / (NAm > 0 ? NAm : 1) : 0), a.d_in / KTA};
+    const int ntkl = KC / KTA;                                        // A's tiles of a row block inside the range
+    int nwa = RX_NW;                                                  // wavefronts that take part in a block of A: the largest divisor of ntkl up to 16
+    while (ntkl % nwa != 0) --nwa;
+    const int tpw = ntkl / nwa;                                       // tiles of each
     FTile<FAB> abuf[ATW];
     auto first_requests = [&]() __attribute__((always_inline)) {
         if (0 < nunits) request(std::integral_constant<int, 0>{});
         if (1 < nunits) request(std::integral_constant<int, 1>{});
-        if (2 < nunits) request(std::integral_constant<int, 2>{});
+        if constexpr (WQ > 2) {
+            if (2 < nunits) request(std::integral_constant<int, 2>{});
+        }
     };
-    if (LOWRANK && producer) {
+    bool a_first = false;
+    if constexpr (LOWRANK) a_first = producer;
+    if (a_first) {
         if (wave < nwa) {
-            const int rho = bid % NAm;
+            const int rho = wi % (NAm > 0 ? NAm : 1);
 #pragma unroll
             for (int u = 0; u < ATW; ++u)
-                if (u < tpw) load_ftile<FAB>(abuf[u], fa, rho, wave * tpw + u, lane);
+                if (u < tpw) load_ftile<FAB>(abuf[u], fa, rho, s * ntkl + wave * tpw + u, lane);
         }
     } else {
         first_requests();
     }
     __builtin_amdgcn_sched_barrier(0);                                // (all of them out before anything below waits)
 
-    // ---- x: 16 x d_in halves, d_in / 512 16-byte chunks per thread ---------------------------------------------------
+    // ---- x of the range: 16 x KC halves, KC / 512 16-byte chunks per thread ------------------------------------------
     {
-        const int cpr = a.d_in / 8, lcpr = 31 - __builtin_clz(cpr);   // chunks per row (a power of two)
-        const int nk = a.d_in / 512;
+        const int cpr = KC / 8;                                       // chunks per row (a multiple of 16: a group's chunks stay in one DPP row)
+        const int nk = KC / 512;
+        const _Float16* const xsrc = a.x + (size_t)s * KC;
         const h8 pat = xscale_chunk<WORDS>(tid & 3);                  // RX_NT is a multiple of 4: the chunk's place in its lane's 32 columns
         const h2 ones = {(_Float16)1.0f, (_Float16)1.0f};
         constexpr int XB = 4;                                         // chunks requested together
@@ -186,14 +257,14 @@ __global__ __launch_bounds__(RX_NT) void resident_kernel(StreamArgs a)
             u4 xv[XB];
 #pragma unroll
             for (int k = 0; k < XB; ++k) {
-                const int c = tid + (k0 + k < nk ? k0 + k : 0) * RX_NT, row = c >> lcpr, cc = c & (cpr - 1);
+                const int c = tid + (k0 + k < nk ? k0 + k : 0) * RX_NT, row = (int)__umulhi((uint32_t)c, a.cpr_magic), cc = c - row * cpr;
                 const int m = row < a.M ? row : 0;                    // rows beyond the tokens repeat row 0; never stored
-                xv[k] = *(const u4*)(a.x + (size_t)m * a.d_in + cc * 8);
+                xv[k] = *(const u4*)(xsrc + (size_t)m * a.d_in + cc * 8);
             }
 #pragma unroll
             for (int k = 0; k < XB; ++k) {
                 if (k0 + k < nk) {
-                    const int c = tid + (k0 + k) * RX_NT, row = c >> lcpr, cc = c & (cpr - 1);
+                    const int c = tid + (k0 + k) * RX_NT, row = (int)__umulhi((uint32_t)c, a.cpr_magic), cc = c - row * cpr;
                     Frag f;
                     f.q = xv[k];
                     float sum = 0.f;
@@ -218,12 +289,16 @@ __global__ __launch_bounds__(RX_NT) void resident_kernel(StreamArgs a)
     __syncthreads();
     const uint32_t tag = s_epoch + 1;
     bool fine = true;
-    if (LOWRANK && tid == 0) arrive(epoch_v, a.hdr, bid);             // (an atomic nobody waits for; the epoch has been read)
+    if (tagged && tid == 0) arrive(epoch_v, a.hdr, bid);              // (an atomic nobody waits for; the epoch has been read)
+    // partial tiles that cross ranges (S > 1): for t [S - 1][A blocks][256] pairs, then for y [S - 1][output blocks][256];
+    // the owner of block b is range b mod S and keeps its own tile in registers
+    unsigned long long* const part_t = a.part;
+    unsigned long long* const part_y = a.part + (size_t)(S - 1) * nprod * 256;
 
     // ---- a block of A: t's 16 x 16 tile (member, rows 16 rho ..) over the whole contraction --------------------------
     if constexpr (LOWRANK) {
         if (producer) {
-            const int mem = bid / NAm, rho = bid - mem * NAm;
+            const int mem = wi / NAm, rho = wi - mem * NAm;
             f4 acc_a = {0.f, 0.f, 0.f, 0.f};
             if (wave < nwa) {
                 const int t0 = wave * tpw;
@@ -251,13 +326,23 @@ __global__ __launch_bounds__(RX_NT) void resident_kernel(StreamArgs a)
             if (wave == 0) {
                 f4 v = pa[lane];
                 for (int k = 1; k < nwa; ++k) v += pa[k * 64 + lane];
-                // register v of lane (n, j): token 4j + v, row 16 rho + n of t
-                const float tv[4] = {v.x, v.y, v.z, v.w};
-                unsigned long long* const dst = a.tpair + ((size_t)mem * 16) * a.r + 16 * rho + n;
+                const int own = wi % S;                               // the range that adds this block's S partial tiles and publishes t
+                if (s != own) {
+                    rx_store_tile(part_t + ((size_t)(s < own ? s : s - 1) * nprod + wi) * 256 + lane, v, tag);
+                } else {
+                    if (S > 1) {
+                        f4 all;
+                        fine = rx_cross_sum(part_t + (size_t)wi * 256 + lane, (size_t)nprod * 256, S, own, v, tag, a.spin_limit, all) && fine;
+                        v = all;
+                    }
+                    // register v of lane (n, j): token 4j + v, row 16 rho + n of t
+                    const float tv[4] = {v.x, v.y, v.z, v.w};
+                    unsigned long long* const dst = a.tpair + ((size_t)mem * 16) * a.r + 16 * rho + n;
 #pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    __hip_atomic_store(dst + (size_t)(4 * j + i) * a.r, ((unsigned long long)tag << 32) | __builtin_bit_cast(uint32_t, tv[i]),
-                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    for (int i = 0; i < 4; ++i)
+                        __hip_atomic_store(dst + (size_t)(4 * j + i) * a.r, ((unsigned long long)tag << 32) | __builtin_bit_cast(uint32_t, tv[i]),
+                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
             }
         }
     }
@@ -271,6 +356,8 @@ __global__ __launch_bounds__(RX_NT) void resident_kernel(StreamArgs a)
     const bool reducer = wave < nblk;
     int rmem = 0, rrb = 0;
     if (reducer) locate(b0 + wave, rmem, rrb);
+    const int yown = (b0 + wave) % S;                                 // the range that finishes this row block (adds t.B^T, the other ranges' tiles, stores y)
+    const bool finisher = reducer && s == yown;
     const Factor fb{(const uint32_t*)sk_pick(a.B, rmem), sk_pick(a.B_scales, rmem), LOWRANK ? a.r / KTB : 0};
     FTile<FEB> bt[BPRE];
     f4 acc[RX_RMAX];
@@ -309,7 +396,7 @@ __global__ __launch_bounds__(RX_NT) void resident_kernel(StreamArgs a)
     }
 
     if constexpr (LOWRANK) {
-        if (reducer) {
+        if (finisher) {
 #pragma unroll
             for (int u = 0; u < BPRE; ++u) load_ftile<FEB>(bt[u], fb, rrb, u < fb.ntk ? u : 0, lane);
         }
@@ -366,7 +453,7 @@ __global__ __launch_bounds__(RX_NT) void resident_kernel(StreamArgs a)
         f4 ysum = src[0];
         for (int k = 1; k < KS; ++k) ysum += src[k * 64];
         if constexpr (LOWRANK) {
-            if (s_err == 0u) {                                        // (t never came: y lacks the low-rank term, the launch reports it)
+            if (finisher && s_err == 0u) {                            // (t never came: y lacks the low-rank term, the launch reports it)
                 const float* trow = ts + (size_t)(rmem * 16 + n) * ldt + (KTB / 4) * j;
                 auto ext_tile = [&](const FTile<FEB>& cw, int g) __attribute__((always_inline)) {
                     h8 b[NMFB];
@@ -404,16 +491,27 @@ __global__ __launch_bounds__(RX_NT) void resident_kernel(StreamArgs a)
                 }
             }
         }
-        const float yv[4] = {ysum.x, ysum.y, ysum.z, ysum.w};
-        _Float16* const y = sk_pick(a.y, rmem);
-        const int d_out = sk_pick(a.d_out, rmem);
+        const int o = b0 + wave;
+        if (!finisher) {
+            rx_store_tile(part_y + ((size_t)(s < yown ? s : s - 1) * NO + o) * 256 + lane, ysum, tag);
+        } else {
+            if (S > 1) {
+                f4 all;
+                if (!rx_cross_sum(part_y + (size_t)o * 256 + lane, (size_t)NO * 256, S, yown, ysum, tag, a.spin_limit, all) && lane == 0)
+                    atomicOr(&a.hdr[HDR_ERROR], 1u);
+                ysum = all;
+            }
+            const float yv[4] = {ysum.x, ysum.y, ysum.z, ysum.w};
+            _Float16* const y = sk_pick(a.y, rmem);
+            const int d_out = sk_pick(a.d_out, rmem);
 #pragma unroll
-        for (int v = 0; v < 4; ++v)
-            if (4 * j + v < a.M) y[(size_t)(4 * j + v) * d_out + rrb * 16 + n] = (_Float16)yv[v];
+            for (int v = 0; v < 4; ++v)
+                if (4 * j + v < a.M) y[(size_t)(4 * j + v) * d_out + rrb * 16 + n] = (_Float16)yv[v];
+        }
     }
 
     // ---- the launch's last workgroup (by index) advances the launch counter once every workgroup has arrived ---------
-    if constexpr (LOWRANK) {
+    if (tagged) {
         if (tid == 0 && s_err) atomicOr(&a.hdr[HDR_ERROR], 1u);
         if (bid == (int)gridDim.x - 1 && wave == RX_NW - 1) {
             if (!advance_epoch(s_epoch, a.hdr, gridDim.x, lane, a.spin_limit) && lane == 0) atomicOr(&a.hdr[HDR_ERROR], 1u);
@@ -424,16 +522,21 @@ __global__ __launch_bounds__(RX_NT) void resident_kernel(StreamArgs a)
 // ------------------------------------------------------------------------------------------------------------------
 constexpr size_t RX_LDS_MAX = 159 * 1024;       // dynamic LDS of a workgroup at most (a compute unit has 160 KiB; a few static bytes beside)
 
+// ranges of the contraction: one while x fits a compute unit's LDS, else the fewest of at most 4096 columns each
+static int resident_ranges(int d_in) { return (d_in + 4095) / 4096; }
+
 static size_t resident_lds(int d_in, int r, int n)
 {
-    const size_t front = (size_t)16 * (d_in + 8) * 2 + (size_t)(d_in / 128) * 16 * 4 + (size_t)RX_NW * 64 * 16;
+    const int KC = d_in / resident_ranges(d_in);
+    const size_t front = (size_t)16 * (KC + 8) * 2 + (size_t)(KC / 128) * 16 * 4 + (size_t)RX_NW * 64 * 16;
     const size_t back = (size_t)RX_RMAX * RX_NW * 64 * 16 + (size_t)n * 16 * (r + 4) * 4;
     return front > back ? front : back;
 }
 
-// how a launch is cut: NTW tiles per wavefront, q row blocks per workgroup (qp for one that begins with a block of A)
+// how a launch is cut: S ranges, NTW tiles per wavefront, q row blocks per workgroup (qp for one that begins with a
+// block of A), wgs workgroups (a multiple of S)
 struct ResidentPlan {
-    int ntw, q, qp, wgs;
+    int S, ntw, q, qp, wgs;
 };
 
 static int device_cus()
@@ -448,8 +551,8 @@ static int device_cus()
     return cus;
 }
 
-// Below this many row blocks in a launch the kernel for 5 .. 127 tokens is the faster one (measured: every workgroup
-// here stages the whole x, which a launch of few rows does not earn back).
+// Below this many row blocks in a launch the kernel for 5 .. 127 tokens is the faster one when x is one range
+// (measured: every workgroup here stages the whole x, which a launch of few rows does not earn back).
 constexpr int RX_MIN_BLOCKS = 384;
 static int g_min_blocks = RX_MIN_BLOCKS;
 void set_resident_min_blocks(int blocks) { g_min_blocks = blocks < 0 ? RX_MIN_BLOCKS : blocks; }
@@ -458,42 +561,61 @@ static bool resident_plan(int d_in, int r, int fm, int fa, const int* d_out, int
 {
     const int cus = device_cus();
     if (cus <= 0) return false;
+    p.S = resident_ranges(d_in);
+    if (d_in % (p.S * 512) != 0) return false;
+    const int per_range = cus / p.S;                                  // workgroups of a range: one workgroup per compute unit in all
     int NO = 0;
     for (int m = 0; m < n; ++m) NO += d_out[m] / 16;
     const int nprod = r > 0 ? n * (r / 16) : 0;
-    if (nprod > cus / 2) return false;
+    if (nprod > per_range / 2) return false;
     // a block of A in output row blocks, by stored bytes
     const int wbits = fm == S_Q4 ? 4 : fm == S_Q3 ? 3 : 2, abits = fa == S_F16 ? 16 : 4;
     const int acost = r > 0 ? (abits + wbits - 1) / wbits : 0;
-    p.q = (NO + nprod * acost + cus - 1) / cus;
+    p.q = (NO + nprod * acost + per_range - 1) / per_range;
     p.q = p.q < 1 ? 1 : p.q;
     p.qp = p.q > acost ? p.q - acost : 0;
     const int rest = NO - nprod * p.qp;
-    p.wgs = nprod + (rest > 0 ? (rest + p.q - 1) / p.q : 0);
-    if (p.wgs > cus) return false;
-    const int G = d_in / 128;
+    const int w = nprod + (rest > 0 ? (rest + p.q - 1) / p.q : 0);
+    if (w > per_range) return false;
+    p.wgs = w * p.S;
+    // the smallest NTW whose row-block slots reach min(q, 4); failing that, the admissible one with the most slots
+    const int GL = d_in / p.S / 128;
+    int best = 0, best_slots = 0;
     for (int ntw = 2; ntw <= 8; ntw *= 2) {
-        const int KS = G / ntw;
-        if (KS < 1 || KS > RX_NW || G % ntw != 0 || RX_NW % KS != 0) continue;
+        if (GL % ntw != 0) continue;
+        const int KS = GL / ntw;
+        if (KS < 1 || KS > RX_NW) continue;
         const int slots = RX_NW / KS, rounds = (p.q + slots - 1) / slots;
-        if (rounds <= RX_RMAX && rounds * slots <= RX_NW && (slots >= p.q || slots >= 4 || ntw == 8)) {
+        if (rounds > RX_RMAX || p.q > RX_NW) continue;
+        if (slots >= (p.q < 4 ? p.q : 4)) {
             p.ntw = ntw;
             return true;
         }
+        if (slots > best_slots) {
+            best = ntw;
+            best_slots = slots;
+        }
     }
-    return false;
+    p.ntw = best;
+    return best != 0;
 }
+
+// pairs of the workspace's region of tagged values: t itself first, the partial tiles that cross ranges behind it
+constexpr size_t RX_T_PAIRS = 8192;                                   // n * 16 * r <= 16 * 512
+constexpr size_t RX_REGION_PAIRS = 32 * 16 * 512;                     // (the region's size, api.hip: MAX_PART_ELEMS)
 
 bool stream_fits(int M, int d_in, int group, int r, int fm, int fa, const int* d_out, int n)
 {
     if (M < 5 || M > 16 || group != 128) return false;
-    if (d_in != 1024 && d_in != 2048 && d_in != 4096) return false;
+    const int S = resident_ranges(d_in);
+    if (S == 1 && d_in != 1024 && d_in != 2048 && d_in != 4096) return false;
     if (r > 0 && fa != S_F16 && fa != S_Q4S128) return false;
     if (r > 0 && fa == S_Q4S128 && r % 128 != 0) return false;        // (B's 64-column tiles of a rank-64 pair: not instantiated here)
     if (r % 32 != 0 || n * r > 512 || resident_lds(d_in, r, n) > RX_LDS_MAX) return false;
     int NO = 0;
     for (int m = 0; m < n; ++m) NO += d_out[m] / 16;
-    if (NO < g_min_blocks) return false;
+    if (S == 1 && NO < g_min_blocks) return false;
+    if (S > 1 && RX_T_PAIRS + (size_t)(S - 1) * (NO + n * (r / 16)) * 256 > RX_REGION_PAIRS) return false;
     ResidentPlan p;
     return resident_plan(d_in, r, fm, fa, d_out, n, p);
 }
@@ -511,7 +633,11 @@ static hipError_t launch_resident_one(StreamArgs a, const ResidentPlan& p, hipSt
     }
     a.q = p.q;
     a.qp = p.qp;
-    note_launch("resident FM=%d FA=%d NTW=%d n=%d wgs=%d q=%d", FM, FA, NTW, a.n, p.wgs, p.q);
+    a.S = p.S;
+    a.cpr_magic = (uint32_t)((0x100000000ull + (uint64_t)(a.d_in / p.S / 8) - 1) / (uint64_t)(a.d_in / p.S / 8));     // exact for c * cpr < 2^32
+    a.part = a.tpair + RX_T_PAIRS;
+    if (p.S > 1) note_launch("resident FM=%d FA=%d NTW=%d S=%d n=%d wgs=%d q=%d", FM, FA, NTW, p.S, a.n, p.wgs, p.q);
+    else note_launch("resident FM=%d FA=%d NTW=%d n=%d wgs=%d q=%d", FM, FA, NTW, a.n, p.wgs, p.q);
     hipLaunchKernelGGL(kern, dim3(p.wgs), dim3(RX_NT), lds, stream, a);
     return hipGetLastError();
 }

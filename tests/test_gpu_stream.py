@@ -47,6 +47,14 @@ def _check(y, ref):
     (4, 16, 16, 4096, 1024, 0, 2),         # bare layer
     (3, 16, 6, 1024, 256, 0, 2),
     (2, 16, 11, 4096, 12288, 0, 8),
+    # contractions longer than 4096: ranges of the contraction in different workgroups, partial tiles of t and of y
+    # handed over as tagged pairs and added in the order of the ranges by the range that owns the row block
+    (4, 16, 16, 14336, 4096, 128, None),   # the down projection: four ranges of 3584 columns (28 groups: 14 of 16 wavefronts stream)
+    (3, 4, 9, 8192, 1024, 128, None),      # two ranges of 4096, 4-bit factors
+    (2, 16, 16, 14336, 512, 0, None),      # bare: the launch counter is used for the tiles of y alone
+    (4, 16, 12, 6144, 768, 64, None),      # two ranges of 3072 (24 groups)
+    (4, 4, 7, 5120, 1280, 128, None),      # two ranges of 2560 (20 groups; A's 20 tiles per range over ten wavefronts)
+    (3, 16, 16, 28672, 256, 32, None),     # seven ranges
 ])
 def test_stream_matches_oracle(gpu, w_bits, ab_bits, M, d_in, d_out, r, ntw):
     from tests.cases import QCase
@@ -54,7 +62,10 @@ def test_stream_matches_oracle(gpu, w_bits, ab_bits, M, d_in, d_out, r, ntw):
     c = QCase(5100 + M + d_out + r + w_bits, d_in, d_out, M, r, w_bits, ab_bits=ab_bits, packer=gpu)
     y = run_linear_q(c)
     assert gpu.debug_last_launch().startswith("resident FM=%d " % {4: 1, 3: 2, 2: 6}[w_bits]), gpu.debug_last_launch()
-    assert " NTW=%d " % ntw in gpu.debug_last_launch(), gpu.debug_last_launch()
+    if ntw is not None:
+        assert " NTW=%d " % ntw in gpu.debug_last_launch(), gpu.debug_last_launch()
+    else:
+        assert " S=%d " % (-(-d_in // 4096)) in gpu.debug_last_launch(), gpu.debug_last_launch()
     _check(y, c.oracle_y())
 
 
@@ -63,6 +74,7 @@ def test_stream_matches_oracle(gpu, w_bits, ab_bits, M, d_in, d_out, r, ntw):
     (3, 16, 10, 4096, (1024, 1024), 64),
     (4, 4, 12, 2048, (256, 512, 256, 128), 128),
     (2, 16, 16, 1024, (256, 256, 256, 256), 0),
+    (4, 16, 16, 14336, (1024, 512), 128),      # two members, four ranges
 ])
 def test_stream_groups(gpu, w_bits, ab_bits, M, d_in, d_outs, r):
     from tests.cases import QCase
