@@ -394,9 +394,9 @@ def calibration_inputs(eora, synth, np, torch, seed, d_in, d_out, n_tokens, w_bi
 
 def calibration_main(args):
     """One step = Algorithm 1 steps 1-6 for one linear (eora_factors).  The call synchronises, so steps are
-    timed with the host clock between device synchronisations; the dominant kernel (a Jacobi round of the
-    eigendecomposition: two rows of the Gram matrix and of the eigenvector matrix per workgroup) is timed by
-    the library with events on the launch stream."""
+    timed with the host clock between device synchronisations; the dominant kernel (a Jacobi round of the SVD of
+    step 5, or of the eigendecomposition when the Gram matrix needs it) is timed by the library with events on the
+    launch stream."""
     import numpy as np
     import torch
     import synth
@@ -421,28 +421,41 @@ def calibration_main(args):
         _, _, st = run(W, W_hat, Xt, d_in, d_out, n, r)
     torch.cuda.synchronize()
     sec = (time.perf_counter() - t0) / steps
-    # dominant kernel: Jacobi rounds of the eigendecomposition.  Algorithmic bytes of a round: every row of the
-    # Gram matrix read once (the dot products / the Gram blocks); a workgroup that rotates its rows (2 of them,
-    # or 16 in a block round, which reads them a second time for the MFMA product) also writes them and reads
-    # and writes as many rows of the eigenvector matrix.
-    rows = st["eig_rows"]
-    rounds = st["eig_sweeps"] * ((d_in - 1) if rows == 2 else (d_in // 8 - 1))
-    per_rotation = 8.0 * rows * ((1 if rows == 2 else 2) * d_in + 2 * d_in)
-    bytes_total = rounds * 8.0 * d_in * d_in + st["eig_rotations"] * per_rotation
-    us_round = 1e3 * st["eig_ms"] / rounds
-    traffic = None                                    # HBM bytes per round from the committed counter runs
+    # Dominant kernel: the Jacobi rounds of the SVD of step 5 (and of the eigendecomposition, when the Gram matrix
+    # took that route: its rounds then dominate).  Algorithmic bytes of a round: every row of the rotated matrix
+    # read once (the dot products / the Gram blocks); a workgroup that rotates its rows (2 of them, or 16 in a block
+    # round, which reads them a second time for the MFMA product) also writes them, and with an eigenvector matrix
+    # reads and writes as many rows of it.
+    def jacobi_round(prefix, m, L, with_v):
+        rows = st[prefix + "_rows"]
+        rounds = st[prefix + "_sweeps"] * ((m - 1) if rows == 2 else (m // 8 - 1))
+        per_rotation = 8.0 * rows * ((1 if rows == 2 else 2) * L + (2 * L if with_v else 0))
+        return rows, rounds, rounds * 8.0 * m * L + st[prefix + "_rotations"] * per_rotation, st[prefix + "_ms"]
+    if st["eig_rows"] > 0:
+        what = "eigendecomposition"
+        rows, rounds, bytes_total, ms = jacobi_round("eig", d_in, d_in, True)
+        m_rows, length = d_in, d_in
+    else:
+        what = "SVD of step 5"
+        m_rows, length = (d_out, d_in) if d_out <= d_in else (d_in, d_out)
+        rows, rounds, bytes_total, ms = jacobi_round("svd", m_rows, length, False)
+    us_round = 1e3 * ms / rounds
+    kernel = "Jacobi round of the %s (%d rows of length %d per workgroup)" % (what, rows, length)
+    traffic = None                                    # HBM bytes per round from the committed counter runs, if they are of this kernel
     tpath = os.path.join(ROOT, "profiles", "factors_traffic.json")
     if os.path.exists(tpath):
         with open(tpath) as f:
-            traffic = json.load(f).get(args.workload)
+            rec = json.load(f).get(args.workload)
+        if isinstance(rec, dict) and rec.get("kernel") == kernel:
+            traffic = rec.get("bytes")
     roofline = dict(bound="hbm", achieved=round(bytes_total / rounds / us_round / 1e3, 1), peak=HBM_PEAK_GBS, unit="GB/s",
-                    frac=round(bytes_total / rounds / us_round / 1e3 / HBM_PEAK_GBS, 4), traffic=traffic,
-                    kernel="Jacobi round of the eigendecomposition (%d rows of length %d per workgroup, with eigenvector rows)" % (rows, d_in),
+                    frac=round(bytes_total / rounds / us_round / 1e3 / HBM_PEAK_GBS, 4), traffic=traffic, kernel=kernel,
                     bytes_per_launch=int(bytes_total / rounds), us_per_launch=round(us_round, 3), launches=rounds)
     out = dict(metric="seconds for Algorithm 1 steps 1-6 of one %d x %d linear (rank %d, %d calibration tokens)" % (d_out, d_in, r, n),
                value=round(sec, 4), unit="s", n_gpus=1, steps=steps, warmup=warmup, ms_per_step=round(1e3 * sec, 3),
                higher_is_better=False, scaling="weak", vs_baseline=None, dtype="f64", data="synthetic",
-               config=dict(workload=args.workload, eig_sweeps=st["eig_sweeps"], eig_seconds=round(st["eig_ms"] / 1e3, 4),
+               config=dict(workload=args.workload, gram_route="cholesky" if st["eig_rows"] == 0 else "eigendecomposition",
+                           eig_sweeps=st["eig_sweeps"], eig_seconds=round(st["eig_ms"] / 1e3, 4),
                            svd_sweeps=st["svd_sweeps"], svd_seconds=round(st["svd_ms"] / 1e3, 4)),
                roofline=roofline)
     if not args.no_cpu_baseline:

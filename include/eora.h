@@ -130,6 +130,10 @@ void eora_debug_set_spin_limit(int iterations);
  * measured crossover: launches with fewer rows are faster in the kernel that serves 5 .. 127 tokens).  Tests lower
  * it to reach that kernel with small shapes; a negative value restores the default. */
 void eora_debug_set_resident_min_blocks(int blocks);
+/* HOST, test hook: route != 0 makes eora_factors() always take the eigendecomposition of the Gram matrix (the
+ * route of a nearly singular one), so that tests reach it with well-conditioned inputs too; 0 restores the choice
+ * by the pivots (process-wide). */
+void eora_debug_set_factors_route(int route);
 /* HOST, test hook: writes into out (capacity bytes, NUL-terminated) the name and template parameters of the
  * layer kernel the most recent forward launch of this process chose, e.g. "sparse_wide FA=5 NW=8 TB=4 VQ=0 n=1"
  * (empty before the first launch), so that a test can assert that its shape reaches the instantiation it is
@@ -323,12 +327,17 @@ size_t eora_factors_workspace_bytes(int d_in, int d_out, int r);
  * minimises || (W - What - B'A) X~ ||_F over rank-r corrections (Theorem 1).  Signs of the r components
  * are arbitrary (B'A is not).  eig_floor in [0, 1): eigenvalues of X~ X~^T below eig_floor times the
  * largest are raised to it before the inverse square root of step 6 (the paper assumes an invertible Q').
- * The eigendecomposition and the SVD are one-sided (block) Jacobi iterations; the call SYNCHRONISES `stream`
- * once per sweep and before returning, and allocates nothing on the device.
- * stats: HOST pointer to eight doubles or NULL: for the eigendecomposition, then for the SVD, the number
- * of sweeps, the milliseconds its rounds took (events on `stream`), the workgroups that rotated their
- * rows, and the rows a workgroup handles per round (16: block rounds, taken when the row count is a
- * multiple of 16 and the row lengths are multiples of 128; 2: pair rounds).
+ * How steps 2-4 and 6 are computed: with X~ X~^T = L L^T (Cholesky), dW L is dW Q sqrt(Lambda) times an orthogonal
+ * matrix on the right, so step 5 finds the same U' and Sigma' and step 6's A is Sigma'^-1 U'^T dW: the same B' and A
+ * as the eigendecomposition gives whenever no eigenvalue is clamped.  That route is taken when every pivot of the
+ * factorisation stays above 1e4 * eig_floor * max diag(X~ X~^T); otherwise (a Gram matrix that close to singular,
+ * e.g. fewer tokens than channels) the eigendecomposition with the clamp is computed, by a one-sided (block)
+ * Jacobi iteration.  The SVD of step 5 is such an iteration in both cases.  The call SYNCHRONISES `stream` once
+ * after the factorisation, once per sweep and before returning, and allocates nothing on the device.
+ * stats: HOST pointer to eight doubles or NULL: for steps 2-3, then for the SVD, the number of sweeps, the
+ * milliseconds its rounds took (events on `stream`), the workgroups that rotated their rows, and the rows a
+ * workgroup handles per round (16: block rounds, taken when the row count is a multiple of 16 and the row
+ * lengths are multiples of 128; 2: pair rounds).  The Cholesky route reports 0 sweeps, its milliseconds, 0, 0.
  * Constraints: d_in, d_out even and <= 16384, 1 <= r <= min(d_in, d_out), n_tokens >= 1.
  * Errors: EORA_ERR_NULL / SHAPE / VALUE (eig_floor) / WORKSPACE / ALIGN / LAUNCH, and
  * EORA_ERR_NOT_CONVERGED (outputs then undefined). */

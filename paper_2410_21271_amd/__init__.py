@@ -8,7 +8,7 @@ when the shared library has not been built (python paper_2410_21271_amd/build.py
 from .binding import (  # noqa: F401
     EoraError, lib, lib_path, status_string,
     qweight_bytes, qzeros_bytes, scales_bytes, sp24_values_bytes, sp24_indices_bytes, workspace_bytes, workspace_bytes_group,
-    workspace_init, workspace_error, debug_set_spin_limit, debug_set_resident_min_blocks, debug_last_launch, debug_probe, new_workspace,
+    workspace_init, workspace_error, debug_set_spin_limit, debug_set_resident_min_blocks, debug_set_factors_route, debug_last_launch, debug_probe, new_workspace,
     pack_q, pack_factor_f16, pack_factor_q4, pack_factor_q3, pack_sp24,
     linear_q, linear_q_static, linear_q_group, linear_sp24, unpack_q, dequant_q, expand_sp24,
     sp24q4_tiles_bytes, sp24q4_meta_bytes, pack_sp24q4, linear_sp24q4, expand_sp24q4,

@@ -58,6 +58,7 @@ def _load():
         "eora_workspace_error": (ci, [vp, vp]),
         "eora_debug_set_spin_limit": (None, [ci]),
         "eora_debug_set_resident_min_blocks": (None, [ci]),
+        "eora_debug_set_factors_route": (None, [ci]),
         "eora_debug_last_launch": (ci, [ctypes.c_char_p, sz]),
         "eora_debug_probe": (ci, [ci, vp, sz, vp, vp]),
         "eora_pack_q": (ci, [vp, vp, vp, ci, ci, ci, ci, vp, vp, vp]),
@@ -97,7 +98,7 @@ EXPORTS = ["eora_status_string", "eora_qweight_bytes", "eora_qzeros_bytes", "eor
            "eora_linear_q_group", "eora_linear_sp24", "eora_unpack_q", "eora_dequant_q", "eora_expand_sp24",
            "eora_sp24q4_tiles_bytes", "eora_sp24q4_meta_bytes", "eora_pack_sp24q4", "eora_linear_sp24q4", "eora_expand_sp24q4",
            "eora_factors_workspace_bytes", "eora_factors", "eora_linear_q_multi", "eora_pack_factor_q3", "eora_factors_store_f16", "eora_factors_store_q", "eora_linear_sp24_group",
-           "eora_debug_last_launch", "eora_debug_probe", "eora_linear_q_static", "eora_debug_set_resident_min_blocks"]
+           "eora_debug_last_launch", "eora_debug_probe", "eora_linear_q_static", "eora_debug_set_resident_min_blocks", "eora_debug_set_factors_route"]
 
 
 def status_string(status):
@@ -250,6 +251,11 @@ def debug_set_spin_limit(iterations):
 def debug_set_resident_min_blocks(blocks):
     """Test hook: fewest 16-row blocks of a launch that takes the kernel with x resident in LDS (negative: default)."""
     lib.eora_debug_set_resident_min_blocks(int(blocks))
+
+
+def debug_set_factors_route(route):
+    """Test hook: 1 makes factors() always take the eigendecomposition route, 0 restores the choice by the pivots."""
+    lib.eora_debug_set_factors_route(int(route))
 
 
 def debug_last_launch():

@@ -286,15 +286,18 @@ __global__ __launch_bounds__(BJ_NT) void jacobi_block_round_kernel(double* __res
     if (V) apply_rotation(V, m, P, Q, J, wave, lane);
 }
 
-// C[i][j] = sum_k A[i*ai + k*ak] * B[j*bj + k*bk], i < M, j < N, k < K.  64 x 64 outputs per workgroup of
-// 256 threads, 4 x 4 per thread, operands staged through LDS sixteen k at a time.
+// C[i][j] = beta * C[i][j] + alpha * sum_k A[i*ai + k*ak] * B[j*bj + k*bk], i < M, j < N, k < K (beta == 0: C is
+// not read).  64 x 64 outputs per workgroup of 256 threads, 4 x 4 per thread, operands staged through LDS sixteen k
+// at a time.  lower != 0: only the tiles that touch the lower triangle (j0 <= i0) are computed (symmetric updates).
 template <typename TA, typename TB>
 __global__ __launch_bounds__(256) void gemm_kernel(const TA* __restrict__ A, long ai, long ak, const TB* __restrict__ B,
-                                                   long bj, long bk, double* __restrict__ C, long ldc, int M, int N, int K)
+                                                   long bj, long bk, double* C, long ldc, int M, int N, int K,
+                                                   double alpha, double beta, int lower)
 {
     __shared__ double As[16][65], Bs[16][65];
     const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
     const int i0 = blockIdx.y * 64, j0 = blockIdx.x * 64;
+    if (lower && j0 > i0) return;
     double acc[4][4] = {};
     for (int k0 = 0; k0 < K; k0 += 16) {
 #pragma unroll
@@ -341,8 +344,118 @@ __global__ __launch_bounds__(256) void gemm_kernel(const TA* __restrict__ A, lon
 #pragma unroll
         for (int f = 0; f < 4; ++f) {
             const int gi = i0 + ty + 16 * e, gj = j0 + tx + 16 * f;
-            if (gi < M && gj < N) C[(size_t)gi * ldc + gj] = acc[e][f];
+            if (gi < M && gj < N) {
+                double v = alpha * acc[e][f];
+                if (beta != 0.0) v += beta * C[(size_t)gi * ldc + gj];
+                C[(size_t)gi * ldc + gj] = v;
+            }
         }
+}
+
+// ------------------------------------------------------------------------------------------------------------
+// Cholesky factor of the Gram matrix, G = L L^T, in place in the lower triangle (right-looking, blocks of 64):
+// any S with S S^T = X~ X~^T serves Algorithm 1 as the eigenvectors times the roots of the eigenvalues do (the
+// two differ by an orthogonal factor on the right, which the SVD of step 5 absorbs), and L costs n^3 / 3 flops.
+constexpr int CH_NB = 64;
+
+// thr[0] = rel * max_i G[i][i]: pivots at or below it make the factorisation give up (flag)
+__global__ __launch_bounds__(1024) void pivot_floor_kernel(const double* __restrict__ G, int n, double rel, double* __restrict__ thr)
+{
+    __shared__ double red[1024];
+    double m = 0.0;
+    for (int i = threadIdx.x; i < n; i += 1024) m = fmax(m, G[(size_t)i * n + i]);
+    red[threadIdx.x] = m;
+    __syncthreads();
+    for (int s2 = 512; s2 > 0; s2 >>= 1) {
+        if ((int)threadIdx.x < s2) red[threadIdx.x] = fmax(red[threadIdx.x], red[threadIdx.x + s2]);
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) thr[0] = rel * red[0];
+}
+
+// the nb x nb diagonal block at (j0, j0): unblocked factorisation in LDS; the block's strict upper part is zeroed
+__global__ __launch_bounds__(256) void potrf_block_kernel(double* __restrict__ A, long lda, int j0, int nb,
+                                                          const double* __restrict__ thr, unsigned* __restrict__ flag)
+{
+    __shared__ double S[CH_NB][CH_NB + 1];
+    const int tid = threadIdx.x;
+    double* const blk = A + (size_t)j0 * lda + j0;
+    for (int e = tid; e < CH_NB * CH_NB; e += 256) {
+        const int i = e >> 6, c = e & 63;
+        S[i][c] = (i < nb && c <= i) ? blk[(size_t)i * lda + c] : 0.0;
+    }
+    __syncthreads();
+    const double floor_abs = thr[0];
+    for (int j = 0; j < nb; ++j) {
+        if (tid == 0) {
+            double d = S[j][j];
+            if (!(d > floor_abs)) {                       // not (numerically) positive definite: give up, stay finite
+                atomicOr(flag, 1u);
+                d = floor_abs > 0.0 ? floor_abs : 1.0;
+            }
+            S[j][j] = sqrt(d);
+        }
+        __syncthreads();
+        if (tid > j && tid < nb) S[tid][j] /= S[j][j];
+        __syncthreads();
+        for (int e = tid; e < CH_NB * CH_NB; e += 256) {
+            const int i = e >> 6, c = e & 63;
+            if (c > j && i >= c && i < nb) S[i][c] -= S[i][j] * S[c][j];
+        }
+        __syncthreads();
+    }
+    for (int e = tid; e < CH_NB * CH_NB; e += 256) {
+        const int i = e >> 6, c = e & 63;
+        if (i < nb && c < nb) blk[(size_t)i * lda + c] = c <= i ? S[i][c] : 0.0;
+    }
+}
+
+// rows j0 + nb .. n - 1 of the block column at j0: x L11^T = a, one thread per row, L11 (the factored diagonal
+// block) in LDS, every thread reading the same entry at the same time
+__global__ __launch_bounds__(256) void panel_solve_kernel(double* __restrict__ A, long lda, int j0, int nb, int n)
+{
+    __shared__ double L[CH_NB][CH_NB + 1];
+    const int tid = threadIdx.x;
+    for (int e = tid; e < CH_NB * CH_NB; e += 256) {
+        const int i = e >> 6, c = e & 63;
+        L[i][c] = (i < nb && c <= i) ? A[(size_t)(j0 + i) * lda + j0 + c] : (i == c ? 1.0 : 0.0);
+    }
+    __syncthreads();
+    const int row = j0 + nb + blockIdx.x * 256 + tid;
+    if (row >= n) return;
+    double* const a = A + (size_t)row * lda + j0;
+    double x[CH_NB];
+#pragma unroll
+    for (int c = 0; c < CH_NB; ++c) x[c] = c < nb ? a[c] : 0.0;
+#pragma unroll
+    for (int c = 0; c < CH_NB; ++c) {
+        double v = x[c];
+#pragma unroll
+        for (int e = 0; e < c; ++e) v -= x[e] * L[c][e];
+        x[c] = v / L[c][c];
+    }
+#pragma unroll
+    for (int c = 0; c < CH_NB; ++c)
+        if (c < nb) a[c] = x[c];
+}
+
+__global__ void zero_upper_kernel(double* __restrict__ A, int n)
+{
+    const size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= (size_t)n * n) return;
+    const int i = (int)(e / n), c = (int)(e - (size_t)i * n);
+    if (c > i) A[e] = 0.0;
+}
+
+// Bn[i][o] = B[o][i] / sigma[i]^2 (B: d_out x r)
+__global__ void scaled_transpose_kernel(const double* __restrict__ B, const double* __restrict__ sigma, int d_out, int r,
+                                        double* __restrict__ Bn)
+{
+    const size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= (size_t)d_out * r) return;
+    const int i = (int)(e / d_out), o = (int)(e - (size_t)i * d_out);
+    const double sg = sigma[i];
+    Bn[e] = sg > 0.0 ? B[(size_t)o * r + i] / (sg * sg) : 0.0;
 }
 
 __global__ void sub_kernel(const float* __restrict__ W, const float* __restrict__ What, double* __restrict__ dW, size_t n)
@@ -560,10 +673,28 @@ inline unsigned blocks(size_t n, int per = 256) { return (unsigned)((n + per - 1
 
 template <typename TA, typename TB>
 void gemm(const TA* A, long ai, long ak, const TB* B, long bj, long bk, double* C, long ldc, int M, int N, int K,
-          hipStream_t st)
+          hipStream_t st, double alpha = 1.0, double beta = 0.0, int lower = 0)
 {
     hipLaunchKernelGGL((gemm_kernel<TA, TB>), dim3((N + 63) / 64, (M + 63) / 64), dim3(256), 0, st, A, ai, ak, B, bj, bk, C,
-                       ldc, M, N, K);
+                       ldc, M, N, K, alpha, beta, lower);
+}
+
+// G (n x n, row-major, symmetric) -> L in its lower triangle, zeros above.  Enqueues only; *flag (device, cleared
+// here) is raised if a pivot is not above rel * max diag(G): the factor is then unusable.
+void cholesky(double* G, int n, double rel, double* thr, unsigned* flag, hipStream_t st)
+{
+    hipLaunchKernelGGL(clear_counter_kernel, dim3(1), dim3(1), 0, st, flag);
+    hipLaunchKernelGGL(pivot_floor_kernel, dim3(1), dim3(1024), 0, st, G, n, rel, thr);
+    for (int j0 = 0; j0 < n; j0 += CH_NB) {
+        const int nb = n - j0 < CH_NB ? n - j0 : CH_NB, rest = n - j0 - nb;
+        hipLaunchKernelGGL(potrf_block_kernel, dim3(1), dim3(256), 0, st, G, (long)n, j0, nb, thr, flag);
+        if (rest <= 0) break;
+        hipLaunchKernelGGL(panel_solve_kernel, dim3((rest + 255) / 256), dim3(256), 0, st, G, (long)n, j0, nb, n);
+        // trailing matrix -= panel . panel^T (the tiles of its lower triangle)
+        double* const P = G + (size_t)(j0 + nb) * n + j0;
+        gemm(P, (long)n, 1L, P, (long)n, 1L, G + (size_t)(j0 + nb) * n + (j0 + nb), (long)n, rest, rest, nb, st, -1.0, 1.0, 1);
+    }
+    hipLaunchKernelGGL(zero_upper_kernel, dim3(blocks((size_t)n * n)), dim3(256), 0, st, G, n);
 }
 
 bool block_rounds_fit(int L, bool with_v, int m) { return m % 16 == 0 && m >= 32 && L % 128 == 0 && (!with_v || m % 128 == 0); }
@@ -681,6 +812,8 @@ Layout layout(int d_in, int d_out, int r)
     return l;
 }
 
+int g_factors_route = 0;                    // test hook: 0 = Cholesky factor when the Gram matrix allows it, 1 = always the eigendecomposition
+
 int check_shape(int n_tokens, int d_in, int d_out, int r)
 {
     if (n_tokens < 1 || d_in < 2 || d_out < 2 || r < 1) return EORA_ERR_SHAPE;
@@ -693,6 +826,8 @@ int check_shape(int n_tokens, int d_in, int d_out, int r)
 }  // namespace eora
 
 using namespace eora;
+
+extern "C" void eora_debug_set_factors_route(int route) { g_factors_route = route == 1 ? 1 : 0; }
 
 extern "C" size_t eora_factors_workspace_bytes(int d_in, int d_out, int r)
 {
@@ -733,21 +868,63 @@ extern "C" int eora_factors(const void* W_f32, const void* W_hat_f32, const void
     const size_t nw = (size_t)d_out * d_in;
     const int k = d_in;
 
-    // steps 1, 2: error and Gram matrix, eigenvectors as the rows of V
+    // steps 1, 2: error and Gram matrix
     hipLaunchKernelGGL(sub_kernel, dim3(blocks(nw)), dim3(256), 0, st, W, What, dW, nw);
     gemm(Xt, (long)n_tokens, 1L, Xt, (long)n_tokens, 1L, H, (long)k, k, k, n_tokens, st);
-    hipLaunchKernelGGL(identity_kernel, dim3(blocks((size_t)k * k)), dim3(256), 0, st, V, k);
-    int sweeps = jacobi(H, k, V, k, sq, rot, st, stats);
-    if (sweeps < 0) return sweeps == -1 ? EORA_ERR_NOT_CONVERGED : EORA_ERR_LAUNCH;
-    hipLaunchKernelGGL(row_dot_kernel, dim3(k), dim3(256), 0, st, H, V, k, lam);
-    // step 3: sqrt(Lambda), with eigenvalues below eig_floor * max raised to it
-    hipLaunchKernelGGL(eig_roots_kernel, dim3(1), dim3(1024), 0, st, lam, k, eig_floor, root, inv);
+
+    // Steps 2-4 and 6 by a Cholesky factor.  With X~ X~^T = L L^T, dW L equals dW Q sqrt(Lambda) times an orthogonal
+    // matrix on the right, so step 5 finds the same U' and Sigma', and step 6's A = Sigma'^-1 U'^T (dW L) L^-1 is
+    // Sigma'^-1 U'^T dW: no inverse at all.  Identical B' and A (up to the signs of the components) whenever no
+    // eigenvalue is clamped; taken when every pivot stays above 1e4 * eig_floor * max diag (a Gram matrix that
+    // close to singular may have clamped eigenvalues: then the eigendecomposition below decides, as it does when
+    // the test hook asks for it).
+    bool chol = false;
+    if (g_factors_route == 0) {
+        unsigned* flag = rot + 16;
+        double* thr = (double*)(rot + 32);
+        hipEvent_t e0 = nullptr, e1 = nullptr;
+        const bool timed = stats && hipEventCreate(&e0) == hipSuccess && hipEventCreate(&e1) == hipSuccess;
+        if (timed) hipEventRecord(e0, st);
+        cholesky(H, k, 1e4 * eig_floor, thr, flag, st);
+        if (timed) hipEventRecord(e1, st);
+        unsigned bad = 1;
+        const bool copied = hipMemcpyAsync(&bad, flag, sizeof(bad), hipMemcpyDeviceToHost, st) == hipSuccess &&
+                            hipStreamSynchronize(st) == hipSuccess;
+        if (timed) {
+            float ms = 0;
+            hipEventElapsedTime(&ms, e0, e1);
+            stats[0] = 0;                        // no sweeps, no rotations, no rows: the Cholesky route
+            stats[1] = ms;
+            stats[2] = 0;
+            stats[3] = 0;
+        }
+        if (e0) hipEventDestroy(e0);
+        if (e1) hipEventDestroy(e1);
+        if (!copied) return EORA_ERR_LAUNCH;
+        chol = bad == 0;
+        if (!chol) gemm(Xt, (long)n_tokens, 1L, Xt, (long)n_tokens, 1L, H, (long)k, k, k, n_tokens, st);      // the Gram matrix again
+    }
+    int sweeps = 0;
+    if (!chol) {
+        // step 2: eigenvectors as the rows of V
+        hipLaunchKernelGGL(identity_kernel, dim3(blocks((size_t)k * k)), dim3(256), 0, st, V, k);
+        sweeps = jacobi(H, k, V, k, sq, rot, st, stats);
+        if (sweeps < 0) return sweeps == -1 ? EORA_ERR_NOT_CONVERGED : EORA_ERR_LAUNCH;
+        hipLaunchKernelGGL(row_dot_kernel, dim3(k), dim3(256), 0, st, H, V, k, lam);
+        // step 3: sqrt(Lambda), with eigenvalues below eig_floor * max raised to it
+        hipLaunchKernelGGL(eig_roots_kernel, dim3(1), dim3(1024), 0, st, lam, k, eig_floor, root, inv);
+    }
 
     const bool by_rows = d_out <= d_in;         // which side of dW' has fewer rows to rotate
     if (by_rows) {
-        // step 4: T = dW' (d_out x k): T[o][j] = root[j] * sum_i dW[o][i] V[j][i]
-        gemm(dW, (long)k, 1L, V, (long)k, 1L, T, (long)k, d_out, k, k, st);
-        hipLaunchKernelGGL(scale_kernel, dim3(blocks(nw)), dim3(256), 0, st, T, d_out, k, root, 0);
+        if (chol) {
+            // step 4: T = dW L (d_out x k): T[o][j] = sum_i dW[o][i] L[i][j]
+            gemm(dW, (long)k, 1L, H, 1L, (long)k, T, (long)k, d_out, k, k, st);
+        } else {
+            // step 4: T = dW' (d_out x k): T[o][j] = root[j] * sum_i dW[o][i] V[j][i]
+            gemm(dW, (long)k, 1L, V, (long)k, 1L, T, (long)k, d_out, k, k, st);
+            hipLaunchKernelGGL(scale_kernel, dim3(blocks(nw)), dim3(256), 0, st, T, d_out, k, root, 0);
+        }
         hipLaunchKernelGGL(copy_kernel, dim3(blocks(nw)), dim3(256), 0, st, T, T0, nw);
         // step 5: rows of T -> sigma_i v_i^T
         sweeps = jacobi(T, k, nullptr, d_out, sq, rot, st, stats ? stats + 4 : nullptr);
@@ -757,10 +934,17 @@ extern "C" int eora_factors(const void* W_f32, const void* W_hat_f32, const void
         hipLaunchKernelGGL(gather_rows_kernel, dim3(blocks((size_t)r * k)), dim3(256), 0, st, T, k, idx, sigma, -1, Ap, r);
         // B' = U' Sigma' = dW' A'^T
         gemm(T0, (long)k, 1L, Ap, (long)k, 1L, (double*)B_f64, (long)r, d_out, r, k, st);
+        // Cholesky route, step 6: A = Sigma'^-2 B'^T dW
+        if (chol) hipLaunchKernelGGL(scaled_transpose_kernel, dim3(blocks((size_t)r * d_out)), dim3(256), 0, st, (const double*)B_f64, sigma, d_out, r, Bn);
     } else {
-        // step 4, transposed: T = dW'^T (k x d_out): T[j][o] = root[j] * sum_i V[j][i] dW[o][i]
-        gemm(V, (long)k, 1L, dW, (long)k, 1L, T, (long)d_out, k, d_out, k, st);
-        hipLaunchKernelGGL(scale_kernel, dim3(blocks(nw)), dim3(256), 0, st, T, k, d_out, root, 1);
+        if (chol) {
+            // step 4, transposed: T = (dW L)^T (k x d_out): T[j][o] = sum_i L[i][j] dW[o][i]
+            gemm(H, 1L, (long)k, dW, (long)k, 1L, T, (long)d_out, k, d_out, k, st);
+        } else {
+            // step 4, transposed: T = dW'^T (k x d_out): T[j][o] = root[j] * sum_i V[j][i] dW[o][i]
+            gemm(V, (long)k, 1L, dW, (long)k, 1L, T, (long)d_out, k, d_out, k, st);
+            hipLaunchKernelGGL(scale_kernel, dim3(blocks(nw)), dim3(256), 0, st, T, k, d_out, root, 1);
+        }
         hipLaunchKernelGGL(copy_kernel, dim3(blocks(nw)), dim3(256), 0, st, T, T0, nw);
         // step 5: rows of T -> sigma_i u_i^T, the columns of B'
         sweeps = jacobi(T, d_out, nullptr, k, sq, rot, st, stats ? stats + 4 : nullptr);
@@ -772,11 +956,16 @@ extern "C" int eora_factors(const void* W_f32, const void* W_hat_f32, const void
         // A' = Sigma'^-1 U'^T dW' : A'[i][j] = sum_o (sigma_i u_i[o] / sigma_i^2) dW'[o][j]
         hipLaunchKernelGGL(gather_rows_kernel, dim3(blocks((size_t)r * d_out)), dim3(256), 0, st, T, d_out, idx, sigma, -2, Bn,
                            r);
-        gemm(Bn, (long)d_out, 1L, T0, (long)d_out, 1L, Ap, (long)k, r, k, d_out, st);
+        if (!chol) gemm(Bn, (long)d_out, 1L, T0, (long)d_out, 1L, Ap, (long)k, r, k, d_out, st);
     }
-    // step 6: A = A' sqrt(Lambda)^-1 Q^T : A[i][j] = sum_e A'[i][e] inv[e] V[e][j]
-    hipLaunchKernelGGL(scale_kernel, dim3(blocks((size_t)r * k)), dim3(256), 0, st, Ap, r, k, inv, 0);
-    gemm(Ap, (long)k, 1L, V, 1L, (long)k, (double*)A_f64, (long)k, r, k, k, st);
+    if (chol) {
+        // step 6 without an inverse: A[i][j] = sum_o (sigma_i u_i[o] / sigma_i^2) dW[o][j]
+        gemm(Bn, (long)d_out, 1L, dW, 1L, (long)k, (double*)A_f64, (long)k, r, k, d_out, st);
+    } else {
+        // step 6: A = A' sqrt(Lambda)^-1 Q^T : A[i][j] = sum_e A'[i][e] inv[e] V[e][j]
+        hipLaunchKernelGGL(scale_kernel, dim3(blocks((size_t)r * k)), dim3(256), 0, st, Ap, r, k, inv, 0);
+        gemm(Ap, (long)k, 1L, V, 1L, (long)k, (double*)A_f64, (long)k, r, k, k, st);
+    }
     if (sigma_f64) hipLaunchKernelGGL(copy_kernel, dim3(blocks(r)), dim3(256), 0, st, sigma, (double*)sigma_f64, (size_t)r);
     if (hipGetLastError() != hipSuccess) return EORA_ERR_LAUNCH;
     if (hipStreamSynchronize(st) != hipSuccess) return EORA_ERR_LAUNCH;

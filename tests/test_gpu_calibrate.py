@@ -31,7 +31,8 @@ def _inputs(seed, d_in, d_out, n_tokens, w_bits=4, group=128):
     return W, W_hat, Xt
 
 
-def _run(eora, W, W_hat, Xt, r, eig_floor=1e-12):
+def _run(eora, W, W_hat, Xt, r, eig_floor=1e-12, want_route=None):
+    """want_route: "cholesky" or "eig": assert (from the call's counters) which route steps 2-4 took."""
     import torch
     d_out, d_in = W.shape
     n = Xt.shape[1]
@@ -40,8 +41,10 @@ def _run(eora, W, W_hat, Xt, r, eig_floor=1e-12):
     A = torch.full((r, d_in), float("nan"), dtype=torch.float64, device="cuda")
     sig = torch.full((r,), float("nan"), dtype=torch.float64, device="cuda")
     ws = torch.empty(eora.factors_workspace_bytes(d_in, d_out, r), dtype=torch.uint8, device="cuda")
-    eora.factors(Wd, Whd, Xd, B, A, sig, n, d_in, d_out, r, eig_floor, ws)
+    st = eora.factors(Wd, Whd, Xd, B, A, sig, n, d_in, d_out, r, eig_floor, ws, stats=True)
     torch.cuda.synchronize()
+    if want_route is not None:
+        assert (st["eig_rows"] == 0) == (want_route == "cholesky"), st
     return B.cpu().numpy(), A.cpu().numpy(), sig.cpu().numpy()
 
 
@@ -73,10 +76,18 @@ SHAPES = [
 ]
 
 
+@pytest.mark.parametrize("route", ["cholesky", "eig"])
 @pytest.mark.parametrize("d_in,d_out,n_tokens,r", SHAPES)
-def test_factors_match_oracle(gpu, d_in, d_out, n_tokens, r):
+def test_factors_match_oracle(gpu, d_in, d_out, n_tokens, r, route):
+    """Both ways of steps 2-4 and 6 against the oracle (which takes the paper's steps with LAPACK): the Cholesky
+    factor of the Gram matrix (the route a well-conditioned Gram matrix takes) and the eigendecomposition by Jacobi
+    sweeps (the route of a nearly singular one, forced here by the test hook)."""
     W, W_hat, Xt = _inputs(7000 + d_in + d_out, d_in, d_out, n_tokens)
-    B, A, sig = _run(gpu, W, W_hat, Xt, r)
+    gpu.debug_set_factors_route(1 if route == "eig" else 0)
+    try:
+        B, A, sig = _run(gpu, W, W_hat, Xt, r, want_route=route)
+    finally:
+        gpu.debug_set_factors_route(0)
     _compare(W, W_hat, Xt, r, B, A, sig)
 
 
@@ -291,7 +302,7 @@ def test_fewer_tokens_than_channels(gpu):
     from oracle import calibrate
     d_in, d_out, n_tokens, r = 256, 64, 150, 8
     W, W_hat, Xt = _inputs(7300, d_in, d_out, n_tokens)
-    B, A, sig = _run(gpu, W, W_hat, Xt, r, eig_floor=1e-8)
+    B, A, sig = _run(gpu, W, W_hat, Xt, r, eig_floor=1e-8, want_route="eig")      # the factorisation meets a zero pivot and gives up
     Bo, Ao = calibrate.eora_factors(W, W_hat, Xt, r, eig_floor=1e-8)
     assert np.allclose(sig, np.linalg.norm(Bo, axis=0), rtol=1e-6, atol=0)
     P, Po = B @ A, Bo @ Ao
