@@ -168,3 +168,27 @@ def test_stored_quantised_factors_dequantise_to_the_quantiser_values():
     # hand value: row of B64 with largest magnitude m gets scale fp16(m / 7) and that entry the code 8 +- 7
     i, j = np.unravel_index(np.argmax(np.abs(B64)), B64.shape)
     assert float(sb[i, 0]) == float(np.float16(abs(B64[i, j]) / 7)) and cb[i, j] == (15 if B64[i, j] > 0 else 1)
+
+
+def test_any_square_root_of_the_gram_matrix_gives_the_same_factors():
+    """What the library's Cholesky route rests on (Alg. 1 steps 2-6): with S S^T = X~ X~^T for ANY square S, not only
+    S = Q sqrt(Lambda), the matrix dW S is dW Q sqrt(Lambda) times an orthogonal factor on the right, so its left
+    singular vectors and singular values are those of step 5, and step 6's A' (S)^-1 is Sigma'^-1 U'^T dW.  Checked
+    with the Cholesky factor and with a randomly rotated square root, against the oracle's own route."""
+    for d, k in ((24, 40), (40, 24)):
+        W, W_hat, Xt = _setup(d=d, k=k, n=300, seed=3)
+        r = 6
+        Bo, Ao = calibrate.eora_factors(W, W_hat, Xt, r)
+        dW = W - W_hat
+        G = calibrate.gram(Xt)
+        rot, _ = np.linalg.qr(np.random.default_rng(4).standard_normal((k, k)))
+        for S in (np.linalg.cholesky(G), np.linalg.cholesky(G) @ rot):
+            assert np.allclose(S @ S.T, G, rtol=1e-10, atol=1e-10 * np.abs(G).max())
+            U, sig, _ = np.linalg.svd(dW @ S, full_matrices=False)
+            B = U[:, :r] * sig[None, :r]
+            A = (U[:, :r] / sig[None, :r]).T @ dW
+            assert np.allclose(sig[:r], np.linalg.norm(Bo, axis=0), rtol=1e-9)
+            assert np.abs(B @ A - Bo @ Ao).max() <= 1e-9 * np.abs(Bo @ Ao).max()
+            sign = np.sign(np.sum(B * Bo, axis=0))
+            assert np.abs(B * sign[None, :] - Bo).max() <= 1e-8 * np.abs(Bo).max()
+            assert np.abs(A * sign[:, None] - Ao).max() <= 1e-8 * np.abs(Ao).max()
