@@ -437,7 +437,7 @@ def calibration_main(args):
         m_rows, length = d_in, d_in
     else:
         what = "SVD of step 5"
-        m_rows, length = (d_out, d_in) if d_out <= d_in else (d_in, d_out)
+        m_rows, length = min(d_out, d_in), int(st["eig_rotations"])      # (Cholesky route: that counter holds the rotated rows' length)
         rows, rounds, bytes_total, ms = jacobi_round("svd", m_rows, length, False)
     us_round = 1e3 * ms / rounds
     kernel = "Jacobi round of the %s (%d rows of length %d per workgroup)" % (what, rows, length)

@@ -337,7 +337,11 @@ size_t eora_factors_workspace_bytes(int d_in, int d_out, int r);
  * stats: HOST pointer to eight doubles or NULL: for steps 2-3, then for the SVD, the number of sweeps, the
  * milliseconds its rounds took (events on `stream`), the workgroups that rotated their rows, and the rows a
  * workgroup handles per round (16: block rounds, taken when the row count is a multiple of 16 and the row
- * lengths are multiples of 128; 2: pair rounds).  The Cholesky route reports 0 sweeps, its milliseconds, 0, 0.
+ * lengths are multiples of 128; 2: pair rounds).  The Cholesky route reports, in place of the first four, 0 sweeps,
+ * its milliseconds, the length of the rows the SVD's sweeps rotated, and 0.  That length is min(d_in, d_out) when the
+ * matrix of step 5, at least twice as long as it has rows, was first reduced to a square factor with the same singular
+ * values and left singular vectors (T T^T = C C^T by a second Cholesky factorisation; not possible for an error of
+ * rank below min(d_in, d_out)), else max(d_in, d_out).
  * Constraints: d_in, d_out even and <= 16384, 1 <= r <= min(d_in, d_out), n_tokens >= 1.
  * Errors: EORA_ERR_NULL / SHAPE / VALUE (eig_floor) / WORKSPACE / ALIGN / LAUNCH, and
  * EORA_ERR_NOT_CONVERGED (outputs then undefined). */

@@ -447,6 +447,24 @@ __global__ void zero_upper_kernel(double* __restrict__ A, int n)
     if (c > i) A[e] = 0.0;
 }
 
+// dst[c][i] = src[i][c] for an n x n matrix
+__global__ void transpose_kernel(const double* __restrict__ src, double* __restrict__ dst, int n)
+{
+    __shared__ double tile[32][33];
+    const int bx = blockIdx.x * 32, by = blockIdx.y * 32, tx = threadIdx.x & 31, ty = threadIdx.x >> 5;      // 256 threads: 32 x 8
+    for (int e = ty; e < 32; e += 8)
+        tile[e][tx] = (by + e < n && bx + tx < n) ? src[(size_t)(by + e) * n + bx + tx] : 0.0;
+    __syncthreads();
+    for (int e = ty; e < 32; e += 8)
+        if (bx + e < n && by + tx < n) dst[(size_t)(bx + e) * n + by + tx] = tile[tx][e];
+}
+
+__global__ void iota_kernel(int* __restrict__ idx, int r)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < r) idx[i] = i;
+}
+
 // Bn[i][o] = B[o][i] / sigma[i]^2 (B: d_out x r)
 __global__ void scaled_transpose_kernel(const double* __restrict__ B, const double* __restrict__ sigma, int d_out, int r,
                                         double* __restrict__ Bn)
@@ -916,47 +934,84 @@ extern "C" int eora_factors(const void* W_f32, const void* W_hat_f32, const void
     }
 
     const bool by_rows = d_out <= d_in;         // which side of dW' has fewer rows to rotate
+    const int m = by_rows ? d_out : k, n = by_rows ? k : d_out;       // T: m rows of length n, m <= n
+    // step 4: T = dW' (by_rows) or its transpose
     if (by_rows) {
         if (chol) {
-            // step 4: T = dW L (d_out x k): T[o][j] = sum_i dW[o][i] L[i][j]
+            // T = dW L (d_out x k): T[o][j] = sum_i dW[o][i] L[i][j]
             gemm(dW, (long)k, 1L, H, 1L, (long)k, T, (long)k, d_out, k, k, st);
         } else {
-            // step 4: T = dW' (d_out x k): T[o][j] = root[j] * sum_i dW[o][i] V[j][i]
+            // T[o][j] = root[j] * sum_i dW[o][i] V[j][i]
             gemm(dW, (long)k, 1L, V, (long)k, 1L, T, (long)k, d_out, k, k, st);
             hipLaunchKernelGGL(scale_kernel, dim3(blocks(nw)), dim3(256), 0, st, T, d_out, k, root, 0);
         }
-        hipLaunchKernelGGL(copy_kernel, dim3(blocks(nw)), dim3(256), 0, st, T, T0, nw);
-        // step 5: rows of T -> sigma_i v_i^T
-        sweeps = jacobi(T, k, nullptr, d_out, sq, rot, st, stats ? stats + 4 : nullptr);
-        if (sweeps < 0) return sweeps == -1 ? EORA_ERR_NOT_CONVERGED : EORA_ERR_LAUNCH;
-        hipLaunchKernelGGL(row_dot_kernel, dim3(d_out), dim3(256), 0, st, T, T, k, sq);
-        hipLaunchKernelGGL(top_rows_kernel, dim3(blocks(d_out)), dim3(256), 0, st, sq, d_out, r, idx, sigma);
-        hipLaunchKernelGGL(gather_rows_kernel, dim3(blocks((size_t)r * k)), dim3(256), 0, st, T, k, idx, sigma, -1, Ap, r);
-        // B' = U' Sigma' = dW' A'^T
-        gemm(T0, (long)k, 1L, Ap, (long)k, 1L, (double*)B_f64, (long)r, d_out, r, k, st);
-        // Cholesky route, step 6: A = Sigma'^-2 B'^T dW
-        if (chol) hipLaunchKernelGGL(scaled_transpose_kernel, dim3(blocks((size_t)r * d_out)), dim3(256), 0, st, (const double*)B_f64, sigma, d_out, r, Bn);
     } else {
         if (chol) {
-            // step 4, transposed: T = (dW L)^T (k x d_out): T[j][o] = sum_i L[i][j] dW[o][i]
+            // T = (dW L)^T (k x d_out): T[j][o] = sum_i L[i][j] dW[o][i]
             gemm(H, 1L, (long)k, dW, (long)k, 1L, T, (long)d_out, k, d_out, k, st);
         } else {
-            // step 4, transposed: T = dW'^T (k x d_out): T[j][o] = root[j] * sum_i V[j][i] dW[o][i]
+            // T[j][o] = root[j] * sum_i V[j][i] dW[o][i]
             gemm(V, (long)k, 1L, dW, (long)k, 1L, T, (long)d_out, k, d_out, k, st);
             hipLaunchKernelGGL(scale_kernel, dim3(blocks(nw)), dim3(256), 0, st, T, k, d_out, root, 1);
         }
-        hipLaunchKernelGGL(copy_kernel, dim3(blocks(nw)), dim3(256), 0, st, T, T0, nw);
-        // step 5: rows of T -> sigma_i u_i^T, the columns of B'
-        sweeps = jacobi(T, d_out, nullptr, k, sq, rot, st, stats ? stats + 4 : nullptr);
+    }
+
+    // Step 5 on a square factor when T is at least twice as long as it has rows (Cholesky route only; H and V are
+    // free by now): with T T^T = C C^T (Cholesky, C lower), T = C F^T for an F with orthonormal columns, so T and C
+    // have the same singular values and left singular vectors w_i; the sweeps rotate the m rows of C^T (length m
+    // instead of n) to sigma_i w_i^T, and w_i^T T is the row sigma_i z_i^T the sweeps over T itself would have
+    // ended with.  The r largest components are accurate to the rounding of T T^T relative to sigma_1^2; a T of
+    // rank below m (an error of low rank) has no such factor: then, as before, the rows of T are rotated.
+    bool square = false;
+    if (chol && n >= 2 * m) {
+        unsigned* flag = rot + 16;
+        double* thr = (double*)(rot + 32);
+        gemm(T, (long)n, 1L, T, (long)n, 1L, H, (long)m, m, m, n, st);
+        cholesky(H, m, 1e-14, thr, flag, st);
+        unsigned bad = 1;
+        if (hipMemcpyAsync(&bad, flag, sizeof(bad), hipMemcpyDeviceToHost, st) != hipSuccess || hipStreamSynchronize(st) != hipSuccess)
+            return EORA_ERR_LAUNCH;
+        square = bad == 0;
+    }
+    const double* Tkeep = T;                    // T as step 4 left it
+    if (square) {
+        double* Y = V;                          // C^T
+        hipLaunchKernelGGL(transpose_kernel, dim3((m + 31) / 32, (m + 31) / 32), dim3(256), 0, st, (const double*)H, Y, m);
+        sweeps = jacobi(Y, m, nullptr, m, sq, rot, st, stats ? stats + 4 : nullptr);
         if (sweeps < 0) return sweeps == -1 ? EORA_ERR_NOT_CONVERGED : EORA_ERR_LAUNCH;
-        hipLaunchKernelGGL(row_dot_kernel, dim3(k), dim3(256), 0, st, T, T, d_out, sq);
-        hipLaunchKernelGGL(top_rows_kernel, dim3(blocks(k)), dim3(256), 0, st, sq, k, r, idx, sigma);
-        hipLaunchKernelGGL(gather_rows_transposed_kernel, dim3(blocks((size_t)r * d_out)), dim3(256), 0, st, T, d_out, idx,
+        hipLaunchKernelGGL(row_dot_kernel, dim3(m), dim3(256), 0, st, Y, Y, m, sq);
+        hipLaunchKernelGGL(top_rows_kernel, dim3(blocks(m)), dim3(256), 0, st, sq, m, r, idx, sigma);
+        // the r rows sigma_i z_i^T = w_i^T T, into T0 (r x n)
+        double* Wr = by_rows ? Bn : Ap;         // r x m unit rows w_i^T (Bn: r x d_out, Ap: r x k)
+        hipLaunchKernelGGL(gather_rows_kernel, dim3(blocks((size_t)r * m)), dim3(256), 0, st, Y, m, idx, sigma, -1, Wr, r);
+        gemm(Wr, (long)m, 1L, T, 1L, (long)n, T0, (long)n, r, n, m, st);
+        hipLaunchKernelGGL(iota_kernel, dim3(blocks(r)), dim3(256), 0, st, idx, r);
+        if (stats) stats[2] = m;                // (Cholesky route: the length of the rows the SVD's sweeps rotated)
+    } else {
+        hipLaunchKernelGGL(copy_kernel, dim3(blocks(nw)), dim3(256), 0, st, T, T0, nw);
+        Tkeep = T0;
+        // step 5: rows of T -> sigma_i z_i^T
+        sweeps = jacobi(T, n, nullptr, m, sq, rot, st, stats ? stats + 4 : nullptr);
+        if (sweeps < 0) return sweeps == -1 ? EORA_ERR_NOT_CONVERGED : EORA_ERR_LAUNCH;
+        hipLaunchKernelGGL(row_dot_kernel, dim3(m), dim3(256), 0, st, T, T, n, sq);
+        hipLaunchKernelGGL(top_rows_kernel, dim3(blocks(m)), dim3(256), 0, st, sq, m, r, idx, sigma);
+        if (stats && chol) stats[2] = n;
+    }
+    const double* Tc = square ? T0 : T;         // rows idx[i]: sigma_i z_i^T
+    if (by_rows) {
+        // z_i = v_i: A' = rows of V'^T; B' = U' Sigma' = dW' A'^T
+        hipLaunchKernelGGL(gather_rows_kernel, dim3(blocks((size_t)r * k)), dim3(256), 0, st, Tc, k, idx, sigma, -1, Ap, r);
+        gemm(Tkeep, (long)k, 1L, Ap, (long)k, 1L, (double*)B_f64, (long)r, d_out, r, k, st);
+        // Cholesky route, step 6: A = Sigma'^-2 B'^T dW
+        if (chol) hipLaunchKernelGGL(scaled_transpose_kernel, dim3(blocks((size_t)r * d_out)), dim3(256), 0, st, (const double*)B_f64, sigma, d_out, r, Bn);
+    } else {
+        // z_i = u_i: the columns of B' are sigma_i u_i
+        hipLaunchKernelGGL(gather_rows_transposed_kernel, dim3(blocks((size_t)r * d_out)), dim3(256), 0, st, Tc, d_out, idx,
                            (double*)B_f64, r);
         // A' = Sigma'^-1 U'^T dW' : A'[i][j] = sum_o (sigma_i u_i[o] / sigma_i^2) dW'[o][j]
-        hipLaunchKernelGGL(gather_rows_kernel, dim3(blocks((size_t)r * d_out)), dim3(256), 0, st, T, d_out, idx, sigma, -2, Bn,
+        hipLaunchKernelGGL(gather_rows_kernel, dim3(blocks((size_t)r * d_out)), dim3(256), 0, st, Tc, d_out, idx, sigma, -2, Bn,
                            r);
-        if (!chol) gemm(Bn, (long)d_out, 1L, T0, (long)d_out, 1L, Ap, (long)k, r, k, d_out, st);
+        if (!chol) gemm(Bn, (long)d_out, 1L, Tkeep, (long)d_out, 1L, Ap, (long)k, r, k, d_out, st);
     }
     if (chol) {
         // step 6 without an inverse: A[i][j] = sum_o (sigma_i u_i[o] / sigma_i^2) dW[o][j]

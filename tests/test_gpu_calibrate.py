@@ -45,6 +45,10 @@ def _run(eora, W, W_hat, Xt, r, eig_floor=1e-12, want_route=None):
     torch.cuda.synchronize()
     if want_route is not None:
         assert (st["eig_rows"] == 0) == (want_route == "cholesky"), st
+        if want_route == "cholesky":
+            # step 5's matrix (min x max) is reduced to a square factor when it is at least twice as long as it has rows
+            lo, hi = min(d_in, d_out), max(d_in, d_out)
+            assert int(st["eig_rotations"]) == (lo if hi >= 2 * lo else hi), st
     return B.cpu().numpy(), A.cpu().numpy(), sig.cpu().numpy()
 
 
@@ -73,6 +77,7 @@ SHAPES = [
     (256, 256, 600, 32),
     (384, 130, 1000, 2),         # ragged tiles of the GEMM, tiny rank
     (640, 256, 1300, 64),        # rows longer than one 64-lane pass
+    (128, 320, 300, 16),         # many more output rows: dW'^T reduced to a square factor before the sweeps
 ]
 
 
