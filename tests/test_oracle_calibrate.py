@@ -192,3 +192,20 @@ def test_any_square_root_of_the_gram_matrix_gives_the_same_factors():
             sign = np.sign(np.sum(B * Bo, axis=0))
             assert np.abs(B * sign[None, :] - Bo).max() <= 1e-8 * np.abs(Bo).max()
             assert np.abs(A * sign[:, None] - Ao).max() <= 1e-8 * np.abs(Ao).max()
+
+
+def test_square_factor_of_step5_has_the_same_singular_values_and_left_vectors():
+    """What the library's shortening of step 5 rests on: for T (m x n, m <= n, full row rank) and the Cholesky factor
+    C of T T^T, the matrix C has T's singular values and left singular vectors w_i, and w_i^T T = sigma_i z_i^T with
+    z_i the right singular vectors of T."""
+    rng = np.random.default_rng(11)
+    m, n, r = 12, 40, 4
+    T = rng.standard_normal((m, n)) * np.exp(rng.uniform(-1, 1, m))[:, None]
+    C = np.linalg.cholesky(T @ T.T)
+    Uc, sc, _ = np.linalg.svd(C)
+    Ut, st, Vt = np.linalg.svd(T, full_matrices=False)
+    assert np.allclose(sc, st, rtol=1e-10)
+    sign = np.sign(np.sum(Uc * Ut, axis=0))
+    assert np.allclose(Uc * sign[None, :], Ut, atol=1e-8)
+    rows = (Uc[:, :r] * sign[None, :r]).T @ T
+    assert np.allclose(rows, st[:r, None] * Vt[:r], atol=1e-9 * st[0])
