@@ -90,9 +90,10 @@ class SparseCase:
         if self.r > 0:
             self.A, self.B = e.pack_factor_f16(L["A"]), e.pack_factor_f16(L["B"])
 
-    def oracle_y(self, rows=None):
+    def oracle_y(self, rows=None, x=None):
         from oracle import linear
-        x = self.x if rows is None else self.x[rows]
+        x = self.x if x is None else x
+        x = x if rows is None else x[rows]
         return linear.eora_linear_sp24(x, self.o_values, self.o_indices, self.o_A, self.o_B,
                                        x.shape[0], self.d_in, self.d_out, self.r)
 

@@ -364,6 +364,24 @@ def test_linear_sp24_many_tokens_many_rows(gpu, r, M, d_in, d_out):
     assert np.array_equal(y, run_linear_sp24(c))
 
 
+def test_sparse_many_tokens_different_inputs_on_one_workspace(gpu):
+    """The many-token 2:4 kernel hands t over as untagged fp32 partials behind flags: two different activations, then
+    a different layer, then the first again, back to back on ONE workspace that is never cleared in between.  A
+    partial of an earlier call read in place of this call's would show against the oracle (the inputs differ)."""
+    import synth
+    from tests.cases import SparseCase
+    from tests.gpu_util import run_linear_sp24
+    a = SparseCase(2401, 2048, 16384, 64, 128, packer=gpu)
+    b = SparseCase(2402, 2048, 16384, 48, 128, packer=gpu)
+    ws = gpu.new_workspace(64, 2048, 16384, 128)
+    x2 = synth.draw_layer(2403, 2048, 16, 64, 0)[3]
+    for c, x in ((a, a.x), (a, x2), (b, b.x), (a, a.x), (b, b.x[::-1].copy())):
+        y = run_linear_sp24(c, x=x, ws=ws)
+        assert gpu.debug_last_launch().startswith("sparse_wide"), gpu.debug_last_launch()
+        _check(y, c.oracle_y(x=x))
+    assert gpu.workspace_error(ws) == 0
+
+
 @pytest.mark.parametrize("w_bits,r,M,d_out", [(4, 0, 128, 128), (4, 128, 200, 192), (3, 256, 333, 144), (4, 128, 129, 16), (2, 128, 200, 192), (2, 0, 130, 48)])
 def test_prefill_gemm_small_shapes(gpu, w_bits, r, M, d_out):
     """The many-token GEMM path: ragged token and row tiles, with and without the low-rank extension."""
