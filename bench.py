@@ -631,7 +631,8 @@ def main():
                roofline=roofline)
     out["config"]["clocks"] = clocks()
     if not args.no_cpu_baseline:
-        base, worst = cpu_baseline(linears, ("q", "k", "v", "o", "gate") if spec["model"] == "8b" else ("k", "v"))
+        # the 8B layer in full (about 10 s of CPU work for the default workload); of the 70B layer the two narrow linears
+        base, worst = cpu_baseline(linears, ("q", "k", "v", "o", "gate", "up", "down") if spec["model"] == "8b" else ("k", "v"))
         out["cpu_baseline"] = base
         # every linear of the step on sampled row blocks, and the linears the baseline ran in full
         out["config"]["max_err_vs_oracle"] = float("%.3g" % max(worst, parity_sample(linears)))
