@@ -87,6 +87,18 @@ def test_stream_groups(gpu, w_bits, ab_bits, M, d_in, d_outs, r):
         _check(y, c.oracle_y(x=cases[0].x))
 
 
+@pytest.mark.parametrize("M", list(range(5, 17)))
+def test_stream_every_token_count(gpu, M):
+    """Every token count the kernel serves, on one small layer with a rank that is not a power of two (rows beyond
+    the tokens repeat row 0 in LDS and are never stored)."""
+    from tests.cases import QCase
+    from tests.gpu_util import run_linear_q
+    c = QCase(6000 + M, 2048, 768, M, 96, 3, packer=gpu)
+    y = run_linear_q(c)
+    assert gpu.debug_last_launch().startswith("resident FM=2 "), gpu.debug_last_launch()
+    _check(y, c.oracle_y())
+
+
 def test_stream_result_is_independent_of_timing(gpu):
     """The partial tiles are added in the order of the ranges: repeated calls agree bit for bit."""
     from tests.cases import QCase
