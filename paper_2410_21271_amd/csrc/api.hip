@@ -67,7 +67,7 @@ constexpr size_t WS_T = WS_PARTS + MAX_PART_ELEMS * 4;
 // one launch of the kernel for 5 .. 16 tokens (x resident in LDS) for validated members that share x; the caller has
 // checked stream_fits
 int launch_stream_group(const void* x, const eora_q_member* members, int n, int M, int d_in, int r, int w_bits,
-                        int fa, int fe, void* workspace, hipStream_t stream)
+                        int fa, int fe, void* workspace, hipStream_t stream, const int* adapter = nullptr, int r_per = 0)
 {
     StreamArgs a{};
     a.x = (const _Float16*)x;
@@ -90,6 +90,8 @@ int launch_stream_group(const void* x, const eora_q_member* members, int n, int 
     a.d_in = d_in;
     a.r = r;
     a.spin_limit = g_spin_limit;
+    a.adapter = adapter;
+    a.r_per = r_per;
     if (failed(launch_stream(a, backbone_format(w_bits), fa, fe, stream), "linear_q (stream)")) return EORA_ERR_LAUNCH;
     return EORA_OK;
 }
@@ -476,6 +478,9 @@ int eora_linear_q_multi(const void* x, const void* qweight, const void* scales, 
     int nw = 0, nq = 0;
     if (small_kernel_fits(M, d_in, group, &nw, &nq))
         return launch_group(x, &e, 1, M, d_in, R, w_bits, group, fa, fe, nw, nq, workspace, (hipStream_t)stream, (const int*)adapter_of_row, r);
+    // 5 .. 16 tokens and enough rows: the kernel with x resident in LDS, with t masked where it goes to LDS
+    if (stream_fits(M, d_in, group, R, backbone_format(w_bits), fa, &d_out, 1))
+        return launch_stream_group(x, &e, 1, M, d_in, R, w_bits, fa, fe, workspace, (hipStream_t)stream, (const int*)adapter_of_row, r);
     const int kcn = pick_kcn(M, d_in);
     for (int m0 = 0; m0 < M; m0 += CHUNK_TOKENS) {
         FusedArgs a{};

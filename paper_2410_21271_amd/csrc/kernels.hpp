@@ -88,6 +88,8 @@ struct StreamArgs {
     unsigned long long* tpair;          // [member][16 tokens][r] tagged t
     int M, d_in, r, spin_limit;
     int q, qp;                          // output row blocks per workgroup; per workgroup that begins with a block of A (set by the launcher)
+    const int* adapter;                 // null, or one adapter index per token row (several adapters side by side in A and B)
+    int r_per;                          // rank of one adapter (adapter != null)
     uint32_t cpr_magic;                 // ceil(2^32 / (16-byte chunks of x per row of a range)): division by multiply-high (set by the launcher)
     int S;                              // ranges of the contraction, one workgroup each per run of row blocks (set by the launcher)
     unsigned long long* part;           // tagged partial tiles that cross ranges, behind t in the same region (set by the launcher)

@@ -437,8 +437,11 @@ __global__ __launch_bounds__(RX_NT) void resident_kernel(StreamArgs a)
             for (int u = 0; u < RX_TP; ++u) {
                 const int e = e0 + tid + u * RX_NT;
                 if (e < T) {
-                    const int row = e / a.r;                          // member * 16 + token
-                    ts[row * ldt + (e - row * a.r)] = __builtin_bit_cast(float, (uint32_t)tp[u]);
+                    const int row = e / a.r, col = e - row * a.r;     // row: member * 16 + token
+                    float v = __builtin_bit_cast(float, (uint32_t)tp[u]);
+                    // several adapters side by side (one member): a token row keeps its own adapter's columns of t
+                    if (a.adapter && a.adapter[row < a.M ? row : 0] != col / a.r_per) v = 0.f;
+                    ts[row * ldt + col] = v;
                 }
             }
         }

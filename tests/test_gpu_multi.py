@@ -68,6 +68,29 @@ def test_multi_adapter_shapes(gpu, M, d_in, d_out, n, r, w_bits, ab_bits):
         assert linear.y_error(bare[on], ref[on]) > 10 * TOL or ab_bits == 4
 
 
+@pytest.mark.parametrize("M,d_in,d_out,n,r,w_bits,ab_bits,launch", [
+    (16, 4096, 8192, 4, 128, 4, 16, "resident FM=1 FA=5 "),      # 512 row blocks: the kernel with x resident in LDS, rank 512 together
+    (9, 2048, 6144, 2, 64, 3, 16, "resident FM=2 FA=5 "),
+    (12, 4096, 6144, 2, 128, 4, 4, "resident FM=1 FA=3 "),       # 4-bit factors
+    (16, 14336, 4096, 2, 128, 4, 16, "resident FM=1 FA=5 "),     # ranges of the contraction in different workgroups
+])
+def test_multi_adapter_5_to_16_tokens_many_rows(gpu, M, d_in, d_out, n, r, w_bits, ab_bits, launch):
+    """5 .. 16 tokens with enough rows take the kernel that keeps x in LDS; the mask is applied where t goes to LDS."""
+    from oracle import linear
+    from tests.cases import QCase
+    from tests.gpu_util import run_linear_q_multi
+    c = QCase(8400 + M + d_out, d_in, d_out, M, n * r, w_bits, 128, ab_bits, packer=gpu)
+    sel = _sel(8500 + M, M, n)
+    y = run_linear_q_multi(c, sel, r)
+    assert gpu.debug_last_launch().startswith(launch), gpu.debug_last_launch()
+    rows = np.arange(M)
+    ref = _oracle(c, sel, r, rows)
+    assert np.all(np.isfinite(y.astype(np.float32)))
+    assert linear.y_error(y, ref) <= TOL, linear.y_error(y, ref)
+    none = run_linear_q_multi(c, np.full(M, -1, np.int32), r)           # no adapter anywhere: the bare layer
+    assert linear.y_error(none, c.oracle_y(r=0)) <= TOL
+
+
 def test_multi_adapter_none_selected_is_the_bare_layer_bit_for_bit(gpu):
     """Rows without an adapter add exact zeros to the backbone's accumulators."""
     from tests.cases import QCase
