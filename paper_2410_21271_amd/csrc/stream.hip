@@ -253,34 +253,45 @@ __global__ __launch_bounds__(RX_NT) void resident_kernel(StreamArgs a)
         const h8 pat = xscale_chunk<WORDS>(tid & 3);                  // RX_NT is a multiple of 4: the chunk's place in its lane's 32 columns
         const h2 ones = {(_Float16)1.0f, (_Float16)1.0f};
         constexpr int XB = 4;                                         // chunks requested together
-        for (int k0 = 0; k0 < nk; k0 += XB) {
-            u4 xv[XB];
+        // ALL: sixteen tokens, every row is staged (no test of the row: measurably faster than testing a scalar)
+        auto stage = [&](auto all_c) __attribute__((always_inline)) {
+            constexpr bool ALL = decltype(all_c)::value;
+            for (int k0 = 0; k0 < nk; k0 += XB) {
+                u4 xv[XB];
 #pragma unroll
-            for (int k = 0; k < XB; ++k) {
-                const int c = tid + (k0 + k < nk ? k0 + k : 0) * RX_NT, row = (int)__umulhi((uint32_t)c, a.cpr_magic), cc = c - row * cpr;
-                const int m = row < a.M ? row : 0;                    // rows beyond the tokens repeat row 0; never stored
-                xv[k] = *(const u4*)(xsrc + (size_t)m * a.d_in + cc * 8);
-            }
+                for (int k = 0; k < XB; ++k) {
+                    const int c = tid + (k0 + k < nk ? k0 + k : 0) * RX_NT;
+                    // a wavefront's 64 chunks lie in one row (cpr is a multiple of 64): the row is a scalar
+                    const int row = __builtin_amdgcn_readfirstlane((int)__umulhi((uint32_t)c, a.cpr_magic)), cc = c - row * cpr;
+                    // rows beyond the tokens are neither fetched nor staged: what LDS holds there reaches only
+                    // accumulator rows that are never stored (the rows of a matrix product are independent)
+                    xv[k] = u4{0u, 0u, 0u, 0u};
+                    if (ALL || row < a.M) xv[k] = *(const u4*)(xsrc + (size_t)row * a.d_in + cc * 8);
+                }
 #pragma unroll
-            for (int k = 0; k < XB; ++k) {
-                if (k0 + k < nk) {
-                    const int c = tid + (k0 + k) * RX_NT, row = (int)__umulhi((uint32_t)c, a.cpr_magic), cc = c - row * cpr;
-                    Frag f;
-                    f.q = xv[k];
-                    float sum = 0.f;
+                for (int k = 0; k < XB; ++k) {
+                    const int c = tid + (k0 + k) * RX_NT;
+                    const int row = __builtin_amdgcn_readfirstlane((int)__umulhi((uint32_t)c, a.cpr_magic)), cc = c - row * cpr;
+                    if (k0 + k < nk && (ALL || row < a.M)) {
+                        Frag f;
+                        f.q = xv[k];
+                        float sum = 0.f;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) sum = __builtin_amdgcn_fdot2(f.p[e], ones, sum, false);
-                    // the 16 chunks of a group sit in the 16 lanes of one DPP row: inclusive scan, the last lane ends with the sum
-                    sum += sk_row_shr<1>(sum);
-                    sum += sk_row_shr<2>(sum);
-                    sum += sk_row_shr<4>(sum);
-                    sum += sk_row_shr<8>(sum);
-                    if ((tid & 15) == 15) gs[(cc >> 4) * 16 + row] = sum * 0x1p-24f;
-                    f.v = f.v * pat;
-                    *(u4*)(xs + (size_t)row * ldx + cc * 8) = f.q;
+                        for (int e = 0; e < 4; ++e) sum = __builtin_amdgcn_fdot2(f.p[e], ones, sum, false);
+                        // the 16 chunks of a group sit in the 16 lanes of one DPP row: inclusive scan, the last lane ends with the sum
+                        sum += sk_row_shr<1>(sum);
+                        sum += sk_row_shr<2>(sum);
+                        sum += sk_row_shr<4>(sum);
+                        sum += sk_row_shr<8>(sum);
+                        if ((tid & 15) == 15) gs[(cc >> 4) * 16 + row] = sum * 0x1p-24f;
+                        f.v = f.v * pat;
+                        *(u4*)(xs + (size_t)row * ldx + cc * 8) = f.q;
+                    }
                 }
             }
-        }
+        };
+        if (a.M == 16) stage(std::true_type{});
+        else stage(std::false_type{});
     }
     if (tid == 0) {
         s_epoch = epoch_v;

@@ -90,7 +90,7 @@ def test_stream_groups(gpu, w_bits, ab_bits, M, d_in, d_outs, r):
 @pytest.mark.parametrize("M", list(range(5, 17)))
 def test_stream_every_token_count(gpu, M):
     """Every token count the kernel serves, on one small layer with a rank that is not a power of two (rows beyond
-    the tokens repeat row 0 in LDS and are never stored)."""
+    the tokens are not staged; what LDS holds there reaches only accumulator rows that are never stored)."""
     from tests.cases import QCase
     from tests.gpu_util import run_linear_q
     c = QCase(6000 + M, 2048, 768, M, 96, 3, packer=gpu)
