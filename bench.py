@@ -582,7 +582,7 @@ def main():
     for L in launches:
         L.run(0)
         torch.cuda.synchronize()
-        L.kernel = re.sub(r" (n|wgs|q|ksplit)=\d+", "", eora.debug_last_launch())
+        L.kernel = re.sub(r" (n|wgs|q|ksplit|c2)=-?\d+", "", eora.debug_last_launch())
         per_linear[L.name]["kernel"] = L.kernel
     groups = {}
     for L in launches:

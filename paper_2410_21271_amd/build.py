@@ -27,7 +27,7 @@ def _fresh(obj, src):
     """EORA_INCREMENTAL=1 (development): keep an object that is newer than its source and every header."""
     if not os.environ.get("EORA_INCREMENTAL") or os.environ.get("EORA_EXTRA_FLAGS") or not os.path.exists(obj):
         return False
-    deps = [os.path.join(CSRC, src)] + [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".hpp")]
+    deps = [os.path.join(CSRC, src)] + [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith((".hpp", ".inc"))]
     deps += [os.path.join(ROOT, "include", f) for f in os.listdir(os.path.join(ROOT, "include"))]
     return all(os.path.getmtime(d) < os.path.getmtime(obj) for d in deps)
 

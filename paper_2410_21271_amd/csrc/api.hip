@@ -234,6 +234,7 @@ int launch_group(const void* x, const eora_q_member* members, int n, int M, int 
     a.spin_limit = g_spin_limit;
     a.adapter = adapter;
     a.r_per = r_per;
+    a.c2n = -1;
     if (failed(launch_small(a, backbone_format(w_bits), fa, fe, nw, nq, stream), "linear_q (decode)")) return EORA_ERR_LAUNCH;
     return EORA_OK;
 }

@@ -122,6 +122,7 @@ struct GroupArgs {
     // r_per columns of t that belong to adapter[m] (anything else: none).  nullptr: nothing masked.
     const int* adapter;
     int r_per;
+    int c2n;                            // set by the launcher: -1, or the number of leading consumer strips of two row blocks in a launch whose later strips are single row blocks
 };
 // whether the shape fits the decode kernel, with its wavefront / quad split
 bool small_kernel_fits(int M, int d_in, int group, int* nw, int* nq);

@@ -29,6 +29,20 @@ namespace eora {
 
 constexpr int XSTAGE = 4;   // 16-byte chunks of x a thread may stage
 
+#ifdef EORA_TIMELINE
+// debug build only (never part of libeora.so): per-workgroup time stamps (100 MHz counter) kept in LDS and written 32 MiB behind the partials of t at the end
+#define STL_DECL __shared__ unsigned long long s_tl[16]; if (threadIdx.x < 16) s_tl[threadIdx.x] = 0ull; \
+    if (threadIdx.x == 0) { s_tl[12] = __builtin_amdgcn_s_getreg(63492); s_tl[13] = __builtin_amdgcn_s_getreg(63508); }
+#define STL_STAMP(slot) do { if (threadIdx.x == 0) s_tl[slot] = wall_clock64(); } while (0)
+#define STL_COUNT(slot, v) atomicAdd(&s_tl[slot], (unsigned long long)(v))
+#define STL_FLUSH() do { __syncthreads(); if (threadIdx.x < 16) (a.tpair + (1 << 22))[blockIdx.x * 16 + threadIdx.x] = s_tl[threadIdx.x]; } while (0)
+#else
+#define STL_DECL do { } while (0)
+#define STL_STAMP(slot) do { } while (0)
+#define STL_COUNT(slot, v) do { } while (0)
+#define STL_FLUSH() do { } while (0)
+#endif
+
 
 // Member m's entry of a per-member argument array, chosen with scalar selects among the four entries (all at
 // fixed places of the argument block, requested with the first batch of scalar loads) instead of a load at a
@@ -112,14 +126,16 @@ __device__ __forceinline__ void stage_x_small(const u4 (&xstage)[XS], _Float16* 
     }
 }
 
-template <int FM, int FA, int FE, int NW, int NQ, bool M1, int RB>
+template <int FM, int FA, int FE, int NW, int NQ, bool M1, int RBK, bool MIX>          // RBK: row blocks of the launch's longest strips; MIX: the later strips are single row blocks
 __global__ __launch_bounds__(NW * 64, 4) void small_kernel(GroupArgs a)   // second bound: wavefronts per SIMD, i.e. at most 128 registers (two 7- or 8-wavefront workgroups per compute unit)
 {
     constexpr bool LOWRANK = FA != S_NONE;
     constexpr int NT = NW * 64;
     constexpr int WORDS = Fmt<FM>::WORDS;
-    __shared__ float red[NW][RB][4][16];
+    __shared__ float red[NW][RBK][4][16];
     __shared__ uint32_t s_epoch, s_bad;
+    STL_DECL;
+    STL_STAMP(0);
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int n = lane & 15, j = lane >> 4;
@@ -172,6 +188,7 @@ __global__ __launch_bounds__(NW * 64, 4) void small_kernel(GroupArgs a)   // sec
         stage_x_small<WORDS, NT, NQ, XS, true>(xstage, xs, gs, mt, ldxs, G, tid);
         __syncthreads();
         if (tid == 0) arrive(ci.epoch, a.hdr, blockIdx.x);
+        STL_STAMP(1);
         const uint32_t epoch = s_epoch;
         f4 acc = {0.f, 0.f, 0.f, 0.f};
         for (int base = 0; base < nsteps; base += PD) {
@@ -215,14 +232,42 @@ __global__ __launch_bounds__(NW * 64, 4) void small_kernel(GroupArgs a)   // sec
             __hip_atomic_store(&a.tpair[(((size_t)mem * a.kcn + kc) * 16 + i) * a.r + 16 * rho + col], pr, __ATOMIC_RELAXED,
                                __HIP_MEMORY_SCOPE_AGENT);
         }
+        STL_STAMP(7);
+        STL_FLUSH();
         return;
     }
     }
 
     // =========================================================================== consumer
-    int R = blockIdx.x - nprod, mem = 0;                 // strip of RB row blocks within its member
-    {
-        const int s0 = a.d_out[0] / (16 * RB), s1 = a.d_out[1] / (16 * RB), s2 = a.d_out[2] / (16 * RB);
+    // The strip: its first row block g0 counted over all members, then the member and the row block within it.  Uniform
+    // launches give every workgroup RBK row blocks.  A mixed launch (MIX) gives the first a.c2n consumers RBK == 2
+    // and all later ones a single row block (the kernel then holds both straight-line bodies and a workgroup takes one of
+    // them under a uniform branch), which lets the launcher even out the row blocks per compute unit.
+    int rbn = RBK, mem = 0, rb0;                         // row blocks of this strip, its member, its first row block within the member
+    if constexpr (MIX) {
+        const int c = blockIdx.x - nprod;
+        int g0 = c * RBK;                                // first row block counted over all members
+        if (c >= a.c2n) {
+            g0 = a.c2n + c;
+            rbn = 1;
+        }
+        const int s0 = a.d_out[0] / 16, s1 = a.d_out[1] / 16, s2 = a.d_out[2] / 16;
+        if (a.n > 1 && g0 >= s0) {
+            g0 -= s0;
+            mem = 1;
+            if (a.n > 2 && g0 >= s1) {
+                g0 -= s1;
+                mem = 2;
+                if (a.n > 3 && g0 >= s2) {
+                    g0 -= s2;
+                    mem = 3;
+                }
+            }
+        }
+        rb0 = g0;
+    } else {
+        int R = blockIdx.x - nprod;                      // strip of RBK row blocks within its member
+        const int s0 = a.d_out[0] / (16 * RBK), s1 = a.d_out[1] / (16 * RBK), s2 = a.d_out[2] / (16 * RBK);
         if (a.n > 1 && R >= s0) {
             R -= s0;
             mem = 1;
@@ -235,261 +280,50 @@ __global__ __launch_bounds__(NW * 64, 4) void small_kernel(GroupArgs a)   // sec
                 }
             }
         }
+        rb0 = R * RBK;
     }
-    const int d_out_m = pick_member(a.d_out, mem);
-    _Float16* const y_m = pick_member(a.y, mem);
-    const _Float16* const w_scales = pick_member(a.w_scales, mem);
-    const uint32_t* const w_zeros = pick_member(a.w_zeros, mem);
-    const uint32_t* const w_tiles = (const uint32_t*)pick_member(a.w, mem);
-    // The strip's RB * NQ quads are consumed in order with two of them in flight: quad L + 2 is requested (scales,
-    // zero-points, tiles) when quad L has been consumed, into the registers that one has just left.
-    constexpr int WQ0 = LOWRANK ? 2 : 4;                   // (the bare kernel has the registers for four)
-    constexpr int NL = RB * NQ, WQ = NL < WQ0 ? NL : WQ0;
-    uint2 sc[NL];
-    uint32_t zq[NL];
-    uint32_t wd[NL][4][WORDS];
-    constexpr int FEB = LOWRANK ? FE : S_F16;              // (a valid format also where the low-rank code is compiled out)
-    const Factor fb{(const uint32_t*)pick_member(a.B, mem), pick_member(a.B_scales, mem), LOWRANK ? a.r / Fmt<FEB>::KT : 0};
-    BSlice<FEB> bpre[RB];
-    const int bunits = LOWRANK ? fb.ntk * BSlice<FEB>::UNITS_PER_TILE : 0;      // units of B's product per row block                  // B's first tile per row block: requested at the strip's midpoint
-    // this lane's words of tile (R * RB) * G + 4 * wave; every other tile it reads is a compile-time
-    // number of tiles further on (32-bit word index: a matrix of this format stays far below 16 GiB)
-    const uint32_t* const wp = w_tiles + (uint32_t)((((uint32_t)(R * RB) * G + 4 * wave) * 64 + lane) * WORDS);
-    const size_t row0 = (size_t)(R * RB) * 16 + n;
-    auto request = [&](auto Lc) __attribute__((always_inline)) {
-        constexpr int L = decltype(Lc)::value, rb = L / NQ, q = L % NQ;
-        const int g0 = 4 * (wave + q * NW);
-        sc[L] = *(const uint2*)(w_scales + (row0 + 16 * rb) * G + g0);
-        zq[L] = w_zeros[(row0 + 16 * rb) * (G / 8) + (g0 >> 3)];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) load_words<WORDS>(wd[L][i], wp + ((size_t)rb * G + 4 * q * NW + i) * 64 * WORDS);
-    };
-    request(std::integral_constant<int, 0>{});
-    if constexpr (WQ > 1) request(std::integral_constant<int, 1>{});
-    if constexpr (WQ > 2) request(std::integral_constant<int, 2>{});
-    if constexpr (WQ > 3) request(std::integral_constant<int, 3>{});
-    // Every request above is in flight before anything below consumes one: without this fence the
-    // scheduler moves uses of the first results (zero-point constants, x to LDS) in between the
-    // requests, and the tiles requested after such a use wait a whole round trip longer.
-    __builtin_amdgcn_sched_barrier(0);
-    if constexpr (LOWRANK) {
-        if (tid == 0) {
-            s_epoch = ci.epoch;
-            s_bad = 0u;
-        }
+    if constexpr (MIX) {
+        // both straight-line bodies; a workgroup takes one of them under a uniform branch
+        auto strip = [&](auto RBc) __attribute__((always_inline)) {
+            constexpr int RB = decltype(RBc)::value;
+#include "small_strip.inc"
+        };
+        if (rbn == 1) strip(std::integral_constant<int, 1>{});
+        else strip(std::integral_constant<int, RBK>{});
+    } else {
+        constexpr int RB = RBK;
+#include "small_strip.inc"
     }
-    if constexpr (!M1) {
-        for (int e = tid; e < 4 * G; e += NT) gs[e] = 0.f;           // rows beyond the tokens: no zero-point term
-        __syncthreads();
-    }
-    stage_x_small<WORDS, NT, NQ, XS, false>(xstage, xs, gs, mt, ldxs, G, tid);
-    __syncthreads();
-    if constexpr (LOWRANK) {
-        if (tid == 0) arrive(ci.epoch, a.hdr, blockIdx.x);      // (its value was needed for s_epoch: no new wait)
-    }
-
-    // ---- the partials of t (this launch's producers write them; the tag tells) ------------------------------------
-    // t[e] = H0[e] + H1[e], H0 the sum of the partials of the k-ranges 0..3 in their order, H1 that of 4..7.  A work
-    // item is (element, half); thread tid takes items tid, tid + NT, ...  With one token the first item's four
-    // pairs are requested before the last quad of the backbone: in a launch that streams for longer than the
-    // producers take they carry this launch's tag by then and cost no round trip at the end; otherwise the wait
-    // below reads them again, in the same order.
-    constexpr bool TEARLY = LOWRANK && M1 && RB * NQ >= 4;      // (a shorter strip ends before the producers do)
-    constexpr int KH = MAX_KCN / 2;
-    const uint32_t epoch = LOWRANK ? s_epoch : 0u;
-    const int T = LOWRANK ? mt * a.r : 0;                // elements of t
-    float* hp = ts;                                      // [2][T]
-    auto item_src = [&](int it, int& klo, int& khi) __attribute__((always_inline)) {    // first pair of item it < 2 T and its k-ranges [klo, khi)
-        const int half = it >= T ? 1 : 0, e = it - half * T;
-        klo = half * KH;
-        khi = a.kcn < klo + KH ? a.kcn : klo + KH;
-        int row = 0;                                     // e / r for at most four token rows, without a division
-        if constexpr (!M1) row = (e >= a.r ? 1 : 0) + (e >= 2 * a.r ? 1 : 0) + (e >= 3 * a.r ? 1 : 0);
-        return a.tpair + ((size_t)mem * a.kcn * 16 + row) * a.r + (e - row * a.r);
-    };
-    unsigned long long tp[KH];
-    int eklo = 0, ekhi = 0;
-    const unsigned long long* tsrc = nullptr;
-    if constexpr (TEARLY) tsrc = item_src(tid < 2 * T ? tid : 0, eklo, ekhi);
-
-    // ---- backbone ------------------------------------------------------------------------------------
-    f4 acc[RB];
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) acc[rb] = f4{0.f, 0.f, 0.f, 0.f};
-    constexpr int EL = NL / 2;                           // the strip's midpoint: B's first tiles and the early look at t go out here
-    auto consume = [&](auto Lc) __attribute__((always_inline)) {
-        constexpr int L = decltype(Lc)::value, rb = L / NQ, q = L % NQ;
-        if constexpr (LOWRANK && L == (NL >= 4 ? EL : 0)) {
-#pragma unroll
-            for (int r2 = 0; r2 < RB; ++r2) load_bslice<FEB>(bpre[r2], fb, R * RB + r2, wave < bunits ? wave : 0, lane);
-        }
-        if constexpr (TEARLY && L == EL) {
-#pragma unroll
-            for (int k = 0; k < KH; ++k) {                          // past the item's last range: that one again (never added)
-                const int kc = eklo + k < a.kcn ? eklo + k : a.kcn - 1;
-                tp[k] = tsrc[(size_t)kc * 16 * a.r];               // an ordinary, cached load: hundreds of workgroups read these few KiB
-            }
-        }
-        const int g0 = 4 * (wave + q * NW);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            h8 xa[4], b[4];
-            const _Float16* px = xs + mrow * ldxs + (g0 + i) * 128 + 32 * j;
-#pragma unroll
-            for (int t = 0; t < 4; ++t) xa[t] = *(const h8*)(px + 8 * t);
-            raw_tile<WORDS>(wd[L][i], b);
-            // the accumulator starts at the zero-point term -z * 2^-24 * sum(x) of its token
-            const float zf = -(float)((zq[L] >> (4 * ((g0 & 7) + i))) & 0xFu);
-            f4 part;
-            if constexpr (M1) part = f4{zf * gs[g0 + i], 0.f, 0.f, 0.f};
-            else part = f4{zf * gs[g0 + i], zf * gs[G + g0 + i], zf * gs[2 * G + g0 + i], zf * gs[3 * G + g0 + i]};
-#pragma unroll
-            for (int t = 0; t < 4; ++t) part = mfma16(xa[t], b[t], part);
-            const uint32_t sw = (i < 2) ? sc[L].x : sc[L].y;
-            const _Float16 s16 = __builtin_bit_cast(_Float16, (uint16_t)((i & 1) ? (sw >> 16) : (sw & 0xFFFFu)));
-            // 2^-24 (code - zero) . x, exact products, scaled once per group in fp32 (one token: only register 0 is ever stored)
-            if constexpr (M1) acc[rb][0] += (float)s16 * part[0];
-            else acc[rb] += (float)s16 * part;
-        }
-        if constexpr (L + WQ < NL) request(std::integral_constant<int, L + WQ>{});
-    };
-    static_assert(NL <= 8, "strip longer than the unrolled sequence below");
-    consume(std::integral_constant<int, 0>{});
-    if constexpr (NL > 1) consume(std::integral_constant<int, 1>{});
-    if constexpr (NL > 2) consume(std::integral_constant<int, 2>{});
-    if constexpr (NL > 3) consume(std::integral_constant<int, 3>{});
-    if constexpr (NL > 4) consume(std::integral_constant<int, 4>{});
-    if constexpr (NL > 5) consume(std::integral_constant<int, 5>{});
-    if constexpr (NL > 6) consume(std::integral_constant<int, 6>{});
-    if constexpr (NL > 7) consume(std::integral_constant<int, 7>{});
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) acc[rb] *= 0x1p24f;  // the subnormal codes' common factor
-
-    // ---- low-rank continuation ---------------------------------------------------------------------
-    if constexpr (LOWRANK) {
-        bool fine = true;
-        for (int it = tid; it < 2 * T; it += NT) {
-            int klo, khi;
-            const unsigned long long* p = item_src(it, klo, khi);
-            float v = 0.f;
-            bool good = klo >= khi;                      // no k-range in this half: the sum is 0
-            if constexpr (TEARLY) {
-                if (it == tid && !good && a.spin_limit >= 0) {       // the early read (a negative limit: every wait counts as expired)
-                    uint32_t bad = 0;
-#pragma unroll
-                    for (int k = 0; k < KH; ++k) {
-                        if (klo + k < khi) {
-                            bad |= (uint32_t)(tp[k] >> 32) ^ (epoch + 1);
-                            v += __builtin_bit_cast(float, (uint32_t)tp[k]);
-                        }
-                    }
-                    good = bad == 0;
-                }
-            }
-            for (int spins = 0; !good && spins <= a.spin_limit; ++spins) {
-                if (spins > 0) __builtin_amdgcn_s_sleep(4);
-                uint32_t bad = 0;
-                v = 0.f;
-                for (int kc = klo; kc < khi; ++kc) {                         // fixed order
-                    const unsigned long long pr = __hip_atomic_load(p + (size_t)kc * 16 * a.r, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    bad |= (uint32_t)(pr >> 32) ^ (epoch + 1);
-                    v += __builtin_bit_cast(float, (uint32_t)pr);
-                }
-                good = bad == 0;
-            }
-            fine = fine && good;
-            if (a.adapter) {                             // several adapters: a token row keeps its own adapter's columns of t
-                const int e = it >= T ? it - T : it;
-                int row = 0;
-                if constexpr (!M1) row = (e >= a.r ? 1 : 0) + (e >= 2 * a.r ? 1 : 0) + (e >= 3 * a.r ? 1 : 0);
-                const int col = e - row * a.r, lo = a.adapter[row] * a.r_per;
-                if (a.adapter[row] < 0 || col < lo || col >= lo + a.r_per) v = 0.f;
-            }
-            hp[it] = v;
-        }
-        if (!fine) {
-            s_bad = 1u;
-            atomicOr(&a.hdr[HDR_ERROR], 1u);             // never expected: producers do not wait
-        }
-        __syncthreads();
-        if (s_bad == 0u) {
-            constexpr int NMF = BSlice<FE>::NMF;
-            for (int u = wave; u < bunits; u += NW) {    // unit u covers columns 32 NMF u .. of t
-                h8 hi[NMF], lo[NMF];                     // t split once, used for the RB row blocks
-#pragma unroll
-                for (int q = 0; q < NMF; ++q) {
-                    // the lane's eight columns of this MFMA step: tile u / UPT, the lane's quarter j of it, word (u % UPT) + q
-                    constexpr int KTB = Fmt<FE>::KT, UPT = BSlice<FE>::UNITS_PER_TILE;
-                    const float* p = hp + mrow * a.r + (u / UPT) * KTB + (KTB / 4) * j + 8 * (u % UPT + q);
-                    const f4 v0 = *(const f4*)p + *(const f4*)(p + T), v1 = *(const f4*)(p + 4) + *(const f4*)(p + T + 4);
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const _Float16 h0 = (_Float16)v0[i], h1 = (_Float16)v1[i];
-                        hi[q][i] = h0;
-                        hi[q][4 + i] = h1;
-                        lo[q][i] = (_Float16)(v0[i] - (float)h0);
-                        lo[q][4 + i] = (_Float16)(v1[i] - (float)h1);
-                    }
-                }
-#pragma unroll
-                for (int rb = 0; rb < RB; ++rb) {
-                    BSlice<FE> cur;
-                    if (u == wave) cur = bpre[rb];
-                    else load_bslice<FE>(cur, fb, R * RB + rb, u, lane);
-                    h8 b[NMF];
-                    decode_bslice<FE>(cur, b);
-                    f4 part = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                    for (int q = 0; q < NMF; ++q) {
-                        part = mfma16(hi[q], b[q], part);
-                        part = mfma16(lo[q], b[q], part);
-                    }
-                    if constexpr (M1) acc[rb][0] += (float)cur.sc * part[0];
-                    else acc[rb] += (float)cur.sc * part;
-                }
-            }
-        }
-    }
-
-    // ---- combine, convert, store -------------------------------------------------------------------
-    if (j == 0) {
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-            for (int i = 0; i < (M1 ? 1 : 4); ++i) red[wave][rb][i][n] = acc[rb][i];
-    }
-    __syncthreads();
-    if (tid < 16 * mt) {
-        const int i = tid >> 4, col = tid & 15;
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb) {
-            float v = 0.f;
-#pragma unroll
-            for (int w2 = 0; w2 < NW; ++w2) v += red[w2][rb][i][col];
-            y_m[(size_t)i * d_out_m + (R * RB + rb) * 16 + col] = (_Float16)v;
-        }
-    }
-    if constexpr (LOWRANK) {
-        // the launch's last workgroup advances the epoch for the next launch, once everyone has arrived
-        if (blockIdx.x == gridDim.x - 1 && wave == 0) {
-            if (!advance_epoch(epoch, a.hdr, gridDim.x, lane, a.spin_limit) && lane == 0) atomicOr(&a.hdr[HDR_ERROR], 1u);
-        }
-    }
+    STL_FLUSH();
 }
 
 // ------------------------------------------------------------------------------------------------
-template <int FM, int FA, int FE, int NW, int NQ, bool M1, int RB>
+// Instantiations whose kernel with both strip lengths stays within 128 registers without scratch (the build refuses
+// scratch in this file, so a wrong entry here fails the build).
+template <int FM, int FA, int FE, int NW, int NQ>
+constexpr bool mixed_fits()
+{
+    return NW == 4 && NQ == 2 && FA != S_Q3S128 && !(FM == S_Q3 && FE == S_Q4S64) && !(FM == S_Q4 && FA == S_F16);
+}
+
+template <int FM, int FA, int FE, int NW, int NQ, bool M1, int RB, bool MIX = false>
 static hipError_t launch_small_m(const GroupArgs& a, hipStream_t stream)
 {
-    auto kern = small_kernel<FM, FA, FE, NW, NQ, M1, RB>;
+    auto kern = small_kernel<FM, FA, FE, NW, NQ, M1, RB, MIX>;
     const size_t lds = (size_t)a.M * (a.d_in + 32) * 2 + (size_t)(M1 ? 1 : 4) * (a.d_in / 128) * 4 + (size_t)2 * a.M * a.r * 4;   // x, zero-point terms, the two halves of t
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
     int blocks = (FA != S_NONE) ? (a.r / 16) * a.kcn * a.n : 0;     // producers first
-    for (int m = 0; m < a.n; ++m) blocks += a.d_out[m] / (16 * RB);
-    note_launch("small FM=%d FA=%d NW=%d NQ=%d RB=%d n=%d", FM, FA, NW, NQ, RB, a.n);
+    if (MIX) {
+        int nb = 0;
+        for (int m = 0; m < a.n; ++m) nb += a.d_out[m] / 16;
+        blocks += nb - a.c2n;                                       // c2n strips of two, the other row blocks one by one
+    } else {
+        for (int m = 0; m < a.n; ++m) blocks += a.d_out[m] / (16 * RB);
+    }
+    note_launch("small FM=%d FA=%d NW=%d NQ=%d RB=%d n=%d c2=%d", FM, FA, NW, NQ, RB, a.n, MIX ? a.c2n : -1);
     hipLaunchKernelGGL(kern, dim3(blocks), dim3(NW * 64), lds, stream, a);
     return hipGetLastError();
 }
@@ -516,7 +350,21 @@ static hipError_t launch_small_one(const GroupArgs& a, hipStream_t stream)
             const int nprod = (a.r / 16) * a.kcn * a.n, room = 256 * (16 / NW) * 7 / 8;
             if (blocks + nprod > room) {
                 // (a four-block strip as straight-line code does not fit 128 registers)
-                if (even2) return launch_small_m<FM, FA, FE, NW, NQ, true, 2>(a, stream);
+                if (even2) {
+                    // Workgroups go to the compute units round-robin by index, 16 / NW to each.  With strips of two
+                    // everywhere, the units whose first workgroup is a producer stream two row blocks less than the
+                    // others and the launch ends with the others.  Mixed strips even that out: every slot but a unit's
+                    // last takes a strip of two (or a producer), the last slot of the units without a producer and the
+                    // slots the producers leave behind take the remaining row blocks one by one.
+                    if constexpr (mixed_fits<FM, FA, FE, NW, NQ>()) {
+                        GroupArgs b = a;
+                        const int cus = 256, slots = cus * (16 / NW);
+                        b.c2n = slots - cus;
+                        const int c1n = blocks - 2 * b.c2n;
+                        if (nprod <= cus && c1n >= cus - nprod && c1n <= 2 * cus) return launch_small_m<FM, FA, FE, NW, NQ, true, 2, true>(b, stream);
+                    }
+                    return launch_small_m<FM, FA, FE, NW, NQ, true, 2>(a, stream);
+                }
             }
         }
         return launch_small_m<FM, FA, FE, NW, NQ, true, 1>(a, stream);

@@ -176,8 +176,14 @@ def test_prefill_config4_qkv_group(gpu):
 
 
 @pytest.mark.parametrize("w_bits,ab_bits,M,d_in,d_outs,want", [
-    (3, 16, 1, 4096, (14336, 14336), "small FM=2 FA=5 NW=4 NQ=2 RB=2 n=2"),     # default workload: gate + up
-    (3, 16, 1, 4096, (4096, 1024, 1024), "small FM=2 FA=5 NW=4 NQ=2 RB=1 n=3"),  # query + key + value
+    (3, 16, 1, 4096, (14336, 14336), "small FM=2 FA=5 NW=4 NQ=2 RB=2 n=2 c2=768"),     # default workload: gate + up, strips of two then single row blocks
+    (3, 16, 1, 4096, (4096, 1024, 1024), "small FM=2 FA=5 NW=4 NQ=2 RB=1 n=3 c2=-1"),  # query + key + value
+    (3, 16, 1, 4096, (28672,), "small FM=2 FA=5 NW=4 NQ=2 RB=2 n=1 c2=768"),           # mixed strips, one member
+    (3, 4, 1, 4096, (13312, 13312), "small FM=2 FA=3 NW=4 NQ=2 RB=2 n=2 c2=768"),      # fewest single row blocks a mixed launch takes (128), 4-bit factors
+    (2, 16, 1, 4096, (16384, 8192, 8192), "small FM=6 FA=5 NW=4 NQ=2 RB=2 n=3 c2=768"),  # most (512), three members, 2-bit backbone
+    (3, 16, 1, 4096, (16384, 16416), "small FM=2 FA=5 NW=4 NQ=2 RB=2 n=2 c2=-1"),      # too many row blocks for mixed strips: strips of two throughout
+    (4, 16, 1, 4096, (14336, 14336), "small FM=1 FA=5 NW=4 NQ=2 RB=2 n=2 c2=-1"),      # 4-bit backbone, fp16 factors: no kernel with both strip lengths (registers)
+    (4, 4, 1, 4096, (14336, 14336), "small FM=1 FA=3 NW=4 NQ=2 RB=2 n=2 c2=768"),      # 4-bit backbone, 4-bit factors: mixed strips without the early look at t
     (4, 16, 16, 4096, (14336, 14336), "resident FM=1 FA=5 NTW=8 n=2 wgs=232 q=8"),      # config 1 shapes at 16 tokens, grouped
     (4, 16, 64, 4096, (14336, 14336), "wide_q FM=1 FA=5 NWR=4 NWK=2 TB=4 n=2"),  # four token blocks per workgroup
 ])
