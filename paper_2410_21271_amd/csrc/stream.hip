@@ -33,6 +33,21 @@
 
 namespace eora {
 
+#ifdef EORA_TIMELINE
+// debug build only (never part of libeora.so): per-workgroup time stamps (100 MHz counter) kept in LDS and written 32 MiB behind t at the end
+#define RTL_DECL __shared__ unsigned long long s_tl[16]; __shared__ unsigned long long s_tlw[64]; if (threadIdx.x < 16) s_tl[threadIdx.x] = 0ull; \
+    if (threadIdx.x == 0) { s_tl[12] = __builtin_amdgcn_s_getreg(63492); s_tl[13] = __builtin_amdgcn_s_getreg(63508); }
+#define RTL_STAMP(slot) do { if (threadIdx.x == 0) s_tl[slot] = wall_clock64(); } while (0)
+#define RTL_WSTAMP(i) do { if ((threadIdx.x & 63) == 0) s_tlw[(threadIdx.x >> 6) * 4 + (i)] = wall_clock64(); } while (0)
+#define RTL_FLUSH() do { __syncthreads(); if (threadIdx.x < 16) (a.tpair + (1 << 22))[blockIdx.x * 16 + threadIdx.x] = s_tl[threadIdx.x]; \
+    if (threadIdx.x < 64) (a.tpair + (1 << 22) + (1 << 16))[blockIdx.x * 64 + threadIdx.x] = s_tlw[threadIdx.x]; } while (0)
+#else
+#define RTL_DECL do { } while (0)
+#define RTL_STAMP(slot) do { } while (0)
+#define RTL_WSTAMP(i) do { } while (0)
+#define RTL_FLUSH() do { } while (0)
+#endif
+
 constexpr int RX_NW = 16, RX_NT = RX_NW * 64;
 constexpr int RX_RMAX = 4;                       // rounds of SLOTS row blocks a workgroup takes at most
 constexpr int RX_TP = 4;                         // pairs of t a thread requests together
@@ -143,6 +158,9 @@ __global__ __launch_bounds__(RX_NT) void resident_kernel(StreamArgs a)
     constexpr int NL = RX_RMAX * UPR;                                           // units of a wavefront at most
     constexpr int WQ = FA == S_F16 ? 2 : 3;                                     // units in flight (with fp16 factors there are no registers for a third: eight tiles of A are held across the staging of x)
     __shared__ uint32_t s_epoch, s_err;
+    RTL_DECL;
+    RTL_STAMP(0);
+    RTL_WSTAMP(3);
 
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;    // (wave: uniform, in a scalar register)
     const int n = lane & 15, j = lane >> 4;
@@ -179,32 +197,25 @@ __global__ __launch_bounds__(RX_NT) void resident_kernel(StreamArgs a)
     if (tagged && tid == 0) epoch_v = ld_relaxed(&a.hdr[HDR_EPOCH]);
 
     // output block o of the launch -> its member and row block there
-    auto locate = [&](int o, int& mem, int& rb) __attribute__((always_inline)) {
-        mem = 0;
-        rb = o;
-        if (a.n > 1 && rb >= nb0) {
-            rb -= nb0;
-            mem = 1;
-            if (a.n > 2 && rb >= nb1) {
-                rb -= nb1;
-                mem = 2;
-                if (a.n > 3 && rb >= nb2) {
-                    rb -= nb2;
-                    mem = 3;
-                }
-            }
-        }
+    auto locate = [&](int o, int& mem, int& rb) __attribute__((always_inline)) {      // (selects, no branches: a request must not sit behind a merge of paths)
+        const int c1 = nb0, c2 = nb0 + nb1, c3 = nb0 + nb1 + nb2;
+        const bool m1 = a.n > 1 && o >= c1, m2 = a.n > 2 && o >= c2, m3 = a.n > 3 && o >= c3;
+        mem = (m1 ? 1 : 0) + (m2 ? 1 : 0) + (m3 ? 1 : 0);
+        rb = o - (m3 ? c3 : (m2 ? c2 : (m1 ? c1 : 0)));
     };
 
     // ---- stored tiles: unit L = round L / UPR, tiles ks * NTW + (L % UPR) * UT .. + UT - 1 of its row block ---------
     uint2 sc[WQ];
     uint32_t zq[WQ];
     uint32_t wq[WQ][UT][WORDS];
-    auto request = [&](auto Lc) __attribute__((always_inline)) {
+    // (le: the unit whose tiles are fetched into the registers of unit L; le == L except for the first requests of a
+    // wavefront with fewer units than it has in flight, which fetch a valid unit again instead of branching)
+    auto request_at = [&](auto Lc, int le) __attribute__((always_inline)) {
         constexpr int L = decltype(Lc)::value, Q = L % WQ;
         int mem, rb;
-        locate(b0 + (L / UPR) * SLOTS + slot, mem, rb);
-        const int g0 = s * GL + ks * NTW + (L % UPR) * UT;            // (group of the whole contraction)
+        const int o = b0 + (le / UPR) * SLOTS + slot;
+        locate(o < NO ? o : NO - 1, mem, rb);
+        const int g0 = s * GL + ks * NTW + (le % UPR) * UT;           // (group of the whole contraction)
         const size_t row = (size_t)rb * 16 + n;
         if constexpr (UT == 4) sc[Q] = *(const uint2*)(sk_pick(a.w_scales, mem) + row * G + g0);
         else sc[Q] = uint2{*(const uint32_t*)(sk_pick(a.w_scales, mem) + row * G + g0), 0u};
@@ -213,6 +224,7 @@ __global__ __launch_bounds__(RX_NT) void resident_kernel(StreamArgs a)
 #pragma unroll
         for (int i = 0; i < UT; ++i) load_words<WORDS>(wq[Q][i], wp + (size_t)i * 64 * WORDS);
     };
+    auto request = [&](auto Lc) __attribute__((always_inline)) { request_at(Lc, decltype(Lc)::value); };
     // The first requests go out before x is staged.  A workgroup that begins with a block of A asks for ALL of that
     // block's tiles instead (its critical path: every workgroup of the launch ends up waiting for t), and for its first
     // stored tiles of the backbone once those are consumed.
@@ -231,73 +243,99 @@ __global__ __launch_bounds__(RX_NT) void resident_kernel(StreamArgs a)
             if (2 < nunits) request(std::integral_constant<int, 2>{});
         }
     };
+    // ---- x of the range first: 16 x KC halves, KC / 512 <= 8 16-byte chunks per thread, ALL requested before any stored
+    // tile.  Loads return to a wavefront in the order it issued them: x asked for after the first stored tiles waited
+    // behind 12 KiB of them per wavefront (192 KiB per compute unit, 9 of a launch's 20 us) although it comes from the
+    // L2 cache.  Every load below is unconditional (a chunk past the range's last, or a row beyond the tokens, reads
+    // chunk 0 / row 0 again and is not staged), so the compiler's wait counts for x stay exact while the stored tiles
+    // requested after it are still in flight.
+    const int cpr_ = KC / 8;
+    const int nkm = ((a.M < 16 ? a.M : 16) * cpr_ + RX_NT - 1) / RX_NT;      // chunks per thread that reach a token row (<= KC / 512 <= 8)
     bool a_first = false;
     if constexpr (LOWRANK) a_first = producer;
-    if (a_first) {
-        if (wave < nwa) {
-            const int rho = wi % (NAm > 0 ? NAm : 1);
-#pragma unroll
-            for (int u = 0; u < ATW; ++u)
-                if (u < tpw) load_ftile<FAB>(abuf[u], fa, rho, s * ntkl + wave * tpw + u, lane);
+    // (XB: chunks a thread requests, 4 while that covers the tokens, e.g. up to eight tokens at d_in 4096: half the requests)
+    auto front = [&](auto XBc) __attribute__((always_inline)) {
+        constexpr int XB = decltype(XBc)::value;
+        const int cpr = cpr_;                                             // chunks per row (a multiple of 16: a group's chunks stay in one DPP row)
+        // (the bare layer keeps its stored tiles ahead of x: it has three units in flight and launches with a single
+        // unit per wavefront would fetch that unit three times below; measured slower there, faster with factors)
+        if constexpr (!LOWRANK) {
+            first_requests();
+            __builtin_amdgcn_sched_barrier(0);
         }
-    } else {
-        first_requests();
-    }
-    __builtin_amdgcn_sched_barrier(0);                                // (all of them out before anything below waits)
-
-    // ---- x of the range: 16 x KC halves, KC / 512 16-byte chunks per thread ------------------------------------------
-    {
-        const int cpr = KC / 8;                                       // chunks per row (a multiple of 16: a group's chunks stay in one DPP row)
-        const int nk = KC / 512;
-        const _Float16* const xsrc = a.x + (size_t)s * KC;
-        const h8 pat = xscale_chunk<WORDS>(tid & 3);                  // RX_NT is a multiple of 4: the chunk's place in its lane's 32 columns
-        const h2 ones = {(_Float16)1.0f, (_Float16)1.0f};
-        constexpr int XB = 4;                                         // chunks requested together
-        // ALL: sixteen tokens, every row is staged (no test of the row: measurably faster than testing a scalar)
-        auto stage = [&](auto all_c) __attribute__((always_inline)) {
-            constexpr bool ALL = decltype(all_c)::value;
-            for (int k0 = 0; k0 < nk; k0 += XB) {
-                u4 xv[XB];
+        u4 xv[XB];
+        {
+            const _Float16* const xsrc = a.x + (size_t)s * KC;
 #pragma unroll
-                for (int k = 0; k < XB; ++k) {
-                    const int c = tid + (k0 + k < nk ? k0 + k : 0) * RX_NT;
-                    // a wavefront's 64 chunks lie in one row (cpr is a multiple of 64): the row is a scalar
-                    const int row = __builtin_amdgcn_readfirstlane((int)__umulhi((uint32_t)c, a.cpr_magic)), cc = c - row * cpr;
-                    // rows beyond the tokens are neither fetched nor staged: what LDS holds there reaches only
-                    // accumulator rows that are never stored (the rows of a matrix product are independent)
-                    xv[k] = u4{0u, 0u, 0u, 0u};
-                    if (ALL || row < a.M) xv[k] = *(const u4*)(xsrc + (size_t)row * a.d_in + cc * 8);
-                }
+            for (int k = 0; k < XB; ++k) {
+                const int c = tid + (k < nkm ? k : 0) * RX_NT;
+                // a wavefront's 64 chunks lie in one row (cpr is a multiple of 64): the row is a scalar
+                const int row = __builtin_amdgcn_readfirstlane((int)__umulhi((uint32_t)c, a.cpr_magic)), cc = c - row * cpr;
+                xv[k] = *(const u4*)(xsrc + (size_t)(row < a.M ? row : 0) * a.d_in + cc * 8);
+            }
+        }
+        RTL_STAMP(9);
+        RTL_WSTAMP(0);
+        // rows beyond the tokens are not staged: what LDS holds there reaches only accumulator rows that are never
+        // stored (the rows of a matrix product are independent)
+        auto stage_x = [&]() __attribute__((always_inline)) {
+            const h8 pat = xscale_chunk<WORDS>(tid & 3);                  // RX_NT is a multiple of 4: the chunk's place in its lane's 32 columns
+            const h2 ones = {(_Float16)1.0f, (_Float16)1.0f};
 #pragma unroll
-                for (int k = 0; k < XB; ++k) {
-                    const int c = tid + (k0 + k) * RX_NT;
-                    const int row = __builtin_amdgcn_readfirstlane((int)__umulhi((uint32_t)c, a.cpr_magic)), cc = c - row * cpr;
-                    if (k0 + k < nk && (ALL || row < a.M)) {
-                        Frag f;
-                        f.q = xv[k];
-                        float sum = 0.f;
+            for (int k = 0; k < XB; ++k) {
+                const int c = tid + k * RX_NT;
+                const int row = __builtin_amdgcn_readfirstlane((int)__umulhi((uint32_t)c, a.cpr_magic)), cc = c - row * cpr;
+                if (k < nkm && row < a.M) {
+                    Frag f;
+                    f.q = xv[k];
+                    float sum = 0.f;
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) sum = __builtin_amdgcn_fdot2(f.p[e], ones, sum, false);
-                        // the 16 chunks of a group sit in the 16 lanes of one DPP row: inclusive scan, the last lane ends with the sum
-                        sum += sk_row_shr<1>(sum);
-                        sum += sk_row_shr<2>(sum);
-                        sum += sk_row_shr<4>(sum);
-                        sum += sk_row_shr<8>(sum);
-                        if ((tid & 15) == 15) gs[(cc >> 4) * 16 + row] = sum * 0x1p-24f;
-                        f.v = f.v * pat;
-                        *(u4*)(xs + (size_t)row * ldx + cc * 8) = f.q;
-                    }
+                    for (int e = 0; e < 4; ++e) sum = __builtin_amdgcn_fdot2(f.p[e], ones, sum, false);
+                    // the 16 chunks of a group sit in the 16 lanes of one DPP row: inclusive scan, the last lane ends with the sum
+                    sum += sk_row_shr<1>(sum);
+                    sum += sk_row_shr<2>(sum);
+                    sum += sk_row_shr<4>(sum);
+                    sum += sk_row_shr<8>(sum);
+                    if ((tid & 15) == 15) gs[(cc >> 4) * 16 + row] = sum * 0x1p-24f;
+                    f.v = f.v * pat;
+                    *(u4*)(xs + (size_t)row * ldx + cc * 8) = f.q;
                 }
             }
         };
-        if (a.M == 16) stage(std::true_type{});
-        else stage(std::false_type{});
-    }
+        // The first stored tiles (for a workgroup that begins with a block of A: that block's tiles) go out behind x and
+        // before x is staged, as a fixed number of unconditional loads on either path (a wavefront with fewer units, or
+        // with no part in the block of A, fetches a valid tile again and never uses it).  More paths, one per number
+        // of units, were tried: where paths with different numbers of loads in flight meet, the compiler waits for all
+        // of them, and the barrier behind the staging then waited for every stored tile requested so far.
+        if (a_first) {
+            const int rho = wi % (NAm > 0 ? NAm : 1), wv = wave < nwa ? wave : 0;
+#pragma unroll
+            for (int u = 0; u < ATW; ++u) load_ftile<FAB>(abuf[u], fa, rho, s * ntkl + wv * tpw + (u < tpw ? u : tpw - 1), lane);
+            __builtin_amdgcn_sched_barrier(0);                            // (all of them out before anything below waits)
+            RTL_WSTAMP(1);
+            stage_x();
+        } else {
+            if constexpr (LOWRANK) {
+                const int last = nunits > 0 ? nunits - 1 : 0;
+                request_at(std::integral_constant<int, 0>{}, 0);
+                request_at(std::integral_constant<int, 1>{}, 1 < nunits ? 1 : last);
+                if constexpr (WQ > 2) request_at(std::integral_constant<int, 2>{}, 2 < nunits ? 2 : last);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            RTL_WSTAMP(1);
+            stage_x();
+        }
+    };
+    if (nkm <= 4) front(std::integral_constant<int, 4>{});
+    else front(std::integral_constant<int, 8>{});
+    RTL_STAMP(11);
+    RTL_WSTAMP(2);
     if (tid == 0) {
         s_epoch = epoch_v;
         s_err = 0u;
     }
     __syncthreads();
+    RTL_STAMP(1);
     const uint32_t tag = s_epoch + 1;
     bool fine = true;
     if (tagged && tid == 0) arrive(epoch_v, a.hdr, bid);              // (an atomic nobody waits for; the epoch has been read)
@@ -355,6 +393,7 @@ __global__ __launch_bounds__(RX_NT) void resident_kernel(StreamArgs a)
                                            __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 }
             }
+            RTL_STAMP(8);
         }
     }
 
@@ -396,6 +435,7 @@ __global__ __launch_bounds__(RX_NT) void resident_kernel(StreamArgs a)
     };
     static_assert(NL <= 8, "more units than the unrolled sequence below");
     if (0 < nunits) consume(std::integral_constant<int, 0>{});
+    RTL_STAMP(2);
     if (1 < nunits) consume(std::integral_constant<int, 1>{});
     if (2 < nunits) consume(std::integral_constant<int, 2>{});
     if (3 < nunits) consume(std::integral_constant<int, 3>{});
@@ -414,7 +454,9 @@ __global__ __launch_bounds__(RX_NT) void resident_kernel(StreamArgs a)
     }
 
     // ---- x is dead: its LDS takes the partial tiles and t -----------------------------------------------------------
+    RTL_STAMP(3);
     __syncthreads();
+    RTL_STAMP(4);
 #pragma unroll
     for (int r2 = 0; r2 < RX_RMAX; ++r2)
         if (r2 < rounds_w) p2[(r2 * RX_NW + wave) * 64 + lane] = acc[r2] * 0x1p24f;      // (the subnormal codes' common factor)
@@ -458,7 +500,9 @@ __global__ __launch_bounds__(RX_NT) void resident_kernel(StreamArgs a)
         }
         if (!__all(fine)) s_err = 1u;
     }
+    RTL_STAMP(5);
     __syncthreads();
+    RTL_STAMP(6);
 
     // ---- one wavefront per row block: the ranges' partial tiles in their order, t.B^T, y -----------------------------
     if (reducer) {
@@ -524,6 +568,8 @@ __global__ __launch_bounds__(RX_NT) void resident_kernel(StreamArgs a)
         }
     }
 
+    RTL_STAMP(7);
+    RTL_FLUSH();
     // ---- the launch's last workgroup (by index) advances the launch counter once every workgroup has arrived ---------
     if (tagged) {
         if (tid == 0 && s_err) atomicOr(&a.hdr[HDR_ERROR], 1u);
