@@ -126,7 +126,7 @@ int eora_workspace_error(const void* workspace, void* stream);
  * normally. */
 void eora_debug_set_spin_limit(int iterations);
 /* HOST, test hook: the fewest 16-row blocks (all members of a launch together) for which a call with 5 .. 16 tokens
- * and d_in of 1024, 2048 or 4096 takes the kernel that keeps x resident in LDS (process-wide; default 384, the
+ * and d_in of 1024, 2048 or 4096 takes the kernel that keeps x resident in LDS (process-wide; default 256, the
  * measured crossover: launches with fewer rows are faster in the kernel that serves 5 .. 127 tokens).  Tests lower
  * it to reach that kernel with small shapes; a negative value restores the default. */
 void eora_debug_set_resident_min_blocks(int blocks);

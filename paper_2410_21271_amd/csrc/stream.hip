@@ -613,7 +613,7 @@ static int device_cus()
 
 // Below this many row blocks in a launch the kernel for 5 .. 127 tokens is the faster one when x is one range
 // (measured: every workgroup here stages the whole x, which a launch of few rows does not earn back).
-constexpr int RX_MIN_BLOCKS = 384;
+constexpr int RX_MIN_BLOCKS = 256;
 static int g_min_blocks = RX_MIN_BLOCKS;
 void set_resident_min_blocks(int blocks) { g_min_blocks = blocks < 0 ? RX_MIN_BLOCKS : blocks; }
 

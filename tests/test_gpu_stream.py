@@ -132,7 +132,7 @@ def test_stream_workspace_shared_by_different_calls(gpu):
 def test_few_rows_take_the_other_kernel_by_default(gpu):
     from tests.cases import QCase
     from tests.gpu_util import run_linear_q
-    c = QCase(5901, 4096, 4096, 16, 128, 4, packer=gpu)         # 256 row blocks: below the crossover
+    c = QCase(5901, 4096, 2048, 16, 128, 4, packer=gpu)         # 128 row blocks: below the crossover (256)
     gpu.debug_set_resident_min_blocks(-1)
     try:
         y = run_linear_q(c)
