@@ -247,7 +247,8 @@ size_t eora_workspace_bytes(int M, int d_in, int d_out, int r)
 {
     if (check_backbone_shape(M, d_in, d_out, r) != EORA_OK) return 0;
     // partials of t for the small-M kernels, and t itself as fp16 M x r for the prefill GEMM
-    return WS_T + (M >= PREFILL_MIN_TOKENS ? prefill_scratch_bytes(M, d_in, r, 1) : 0);
+    // (and, for a 2:4 call with a long contraction at 5 .. 127 tokens, the partial outputs of its ranges)
+    return WS_T + (M >= PREFILL_MIN_TOKENS ? prefill_scratch_bytes(M, d_in, r, 1) : sparse_split_bytes(M, d_in, d_out));
 }
 
 size_t eora_workspace_bytes_group(int M, int d_in, int r, int n_members)
@@ -623,6 +624,8 @@ int run_linear_sparse(const void* x, const void* values, const void* indices, co
         a.r = r;
         a.kcn = kcn;
         a.spin_limit = g_spin_limit;
+        a.ksplit = 1;
+        a.ypart = sparse_split_bytes(M, d_in, d_out) ? (float*)((char*)workspace + WS_T) : nullptr;
         if (failed(launch_sparse(a, (hipStream_t)stream), "linear_sp24")) return EORA_ERR_LAUNCH;
     }
     return EORA_OK;
@@ -690,6 +693,7 @@ int eora_linear_sp24_group(const void* x, const eora_sp_member* members, int n_m
         a.r = r;
         a.kcn = kcn;
         a.spin_limit = g_spin_limit;
+        a.ksplit = 1;                                                    // (grouped launches never split the contraction)
         as[m] = a;
     }
     if (failed(launch_sparse_group(as, n_members, (hipStream_t)stream), "linear_sp24_group")) return EORA_ERR_LAUNCH;

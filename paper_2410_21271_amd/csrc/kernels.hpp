@@ -142,7 +142,16 @@ struct SparseArgs {
     float* tpart;             // token blocks x kcn x 16 x r fp32 partials of t (kernel for many tokens and rows)
     unsigned long long* tpair;   // the same as (value, tag) pairs (decode kernel)
     int M, d_in, d_out, r, kcn, spin_limit;
+    // long contractions at 5 .. 127 tokens (kernel for many tokens, one linear): room for the fp32 partial outputs of
+    // up to SP_MAX_SPLIT ranges of the contraction, [range][M][d_out] (null: the contraction is never split); the
+    // launcher sets ksplit
+    float* ypart;
+    int ksplit;
 };
+constexpr int SP_MAX_SPLIT = 4;
+constexpr int SP_SPLIT_MIN_D_IN = 16384;        // contractions from this length on may be split
+// bytes of SparseArgs::ypart a call of this shape needs (0: no split is ever chosen for it)
+size_t sparse_split_bytes(int M, int d_in, int d_out);
 
 hipError_t launch_sparse(const SparseArgs& a, hipStream_t stream);
 // up to four 2:4 linears that read the same x in one launch (same M, d_in, r, kcn, backbone kind; own weights,

@@ -426,13 +426,17 @@ __device__ __forceinline__ void sparse_wide_body(const SparseArgs& a, const int 
     // ========================================================================= consumer
     const int RBs = a.d_out / 16;
     const int NTG = (yblocks + TB - 1) / TB;              // groups of TB token blocks
-    const int cidx = bid - nprod;
+    // ranges of the contraction (a.ksplit > 1: a long contraction with few rows): range ks of KS covers chunks
+    // [c0, c0 + Gs); every range writes its fp32 partial output, the launcher's second kernel adds them in order
+    const int KS = a.ksplit, ks = (bid - nprod) % KS;
+    const int cidx = (bid - nprod) / KS;
     const int tg = cidx % NTG, rg = cidx / NTG;
     const int m0 = tg * TB * 16;                          // first token of the group
     const int Rw = rg * NW + wave;
     const bool active = Rw < RBs;                         // a ragged last row group: the wavefront only helps staging
     const int R = active ? Rw : RBs - 1;
     const int G = a.d_in / 128;                           // chunks = stored tiles per row block
+    const int Gs = G / KS, c0 = ks * Gs;                  // this range's chunks
     // piece q of a chunk: token rows 4 q .. 4 q + 3, lane -> row 4 q + lane / 16, 16-byte piece lane % 16
     const _Float16* xsrc[XN];
     int xdst[XN];
@@ -440,14 +444,14 @@ __device__ __forceinline__ void sparse_wide_body(const SparseArgs& a, const int 
     for (int i = 0; i < XN; ++i) {
         const int trow = 4 * (wave + i * NW) + (lane >> 4);
         const int grow = m0 + trow < a.M ? m0 + trow : a.M - 1;      // rows beyond the tokens: a valid row, results dropped
-        xsrc[i] = a.x + (size_t)grow * a.d_in + 8 * (lane & 15);
+        xsrc[i] = a.x + (size_t)grow * a.d_in + (size_t)c0 * 128 + 8 * (lane & 15);      // (chunk s of the range at + s * 128)
         xdst[i] = (trow * 16 + ((lane & 15) ^ (trow & 15))) * 16;
     }
-    auto load_tile = [&](SpT<VQ>& t, int c) { load_sptile<VQ>(t, a, R, c, G, lane); };
+    auto load_tile = [&](SpT<VQ>& t, int c) { load_sptile<VQ>(t, a, R, c0 + c, G, lane); };      // c: chunk within the range
     SpT<VQ> buf[XW_D];
     u4 xr[XW_D][XN];
 #pragma unroll
-    for (int s = 0; s < XW_D; ++s) {                      // G is a multiple of XW_D
+    for (int s = 0; s < XW_D; ++s) {                      // Gs is a multiple of XW_D
 #pragma unroll
         for (int i = 0; i < XN; ++i) xr[s][i] = *(const u4*)(xsrc[i] + s * 128);
         load_tile(buf[s], s);
@@ -462,7 +466,7 @@ __device__ __forceinline__ void sparse_wide_body(const SparseArgs& a, const int 
 #pragma unroll
     for (int i = 0; i < XN; ++i) {
         *(u4*)(eora_smem + xdst[i]) = xr[0][i];
-        xr[0][i] = *(const u4*)(xsrc[i] + (XW_D < G ? XW_D : G - 1) * 128);
+        xr[0][i] = *(const u4*)(xsrc[i] + (XW_D < Gs ? XW_D : Gs - 1) * 128);
     }
 
     f4 acc[TB];
@@ -473,7 +477,7 @@ __device__ __forceinline__ void sparse_wide_body(const SparseArgs& a, const int 
 #pragma unroll
     for (int q = 0; q < 4; ++q) poff[q] = (n * 16 + ((8 * (q >> 1) + 4 * (q & 1) + j) ^ n)) * 16;
 
-    for (int base = 0; base < G; base += XW_D) {
+    for (int base = 0; base < Gs; base += XW_D) {
 #pragma unroll
         for (int s = 0; s < XW_D; ++s) {
             const int c = base + s;
@@ -482,7 +486,7 @@ __device__ __forceinline__ void sparse_wide_body(const SparseArgs& a, const int 
             // chunk c + 1 -> the slot everyone has just left; its registers take the chunk XW_D further on
             // (past the end: the last chunk again, never used)
             const int s1 = (s + 1) % XW_D;
-            const int cx = c + 1 + XW_D < G ? c + 1 + XW_D : G - 1;
+            const int cx = c + 1 + XW_D < Gs ? c + 1 + XW_D : Gs - 1;
 #pragma unroll
             for (int i = 0; i < XN; ++i) {
                 *(u4*)(eora_smem + ((c + 1) & 1) * SLOT + xdst[i]) = xr[s1][i];
@@ -504,12 +508,13 @@ __device__ __forceinline__ void sparse_wide_body(const SparseArgs& a, const int 
             }
             // the tile's registers are free again: the request for the tile XW_D chunks on goes out last
             __builtin_amdgcn_sched_barrier(0);
-            load_tile(buf[s], c + XW_D < G ? c + XW_D : G - 1);
+            load_tile(buf[s], c + XW_D < Gs ? c + XW_D : Gs - 1);
         }
     }
 
-    // ---- low-rank continuation: acc[row][token] += B[row][:] . t[token][:] ----------------------------------
+    // ---- low-rank continuation: acc[row][token] += B[row][:] . t[token][:] (range 0 adds it) ----------------
     if constexpr (LOWRANK) {
+      if (ks == 0) {
         // t (16 x r fp32 per token block) goes over the x slots, as many token blocks at a time as fit
         float* ts = (float*)eora_smem;
         const int tsz = 16 * a.r;                         // floats per token block
@@ -601,6 +606,7 @@ __device__ __forceinline__ void sparse_wide_body(const SparseArgs& a, const int 
                 }
             }
         }
+      }
     }
 
     // ---- convert, store: lane holds rows 4*j+i of its row block for token n of each token block ----------
@@ -608,10 +614,14 @@ __device__ __forceinline__ void sparse_wide_body(const SparseArgs& a, const int 
     for (int tb = 0; tb < TB; ++tb) {
         const int m = m0 + 16 * tb + n;
         if (active && m < a.M) {
-            typedef _Float16 h4 __attribute__((ext_vector_type(4)));
             const f4 v = acc[tb];
-            const h4 o = {(_Float16)v.x, (_Float16)v.y, (_Float16)v.z, (_Float16)v.w};
-            *(h4*)(a.y + (size_t)m * a.d_out + R * 16 + 4 * j) = o;
+            if (KS > 1) {                                 // this range's fp32 partial output
+                *(f4*)(a.ypart + ((size_t)ks * a.M + m) * a.d_out + R * 16 + 4 * j) = v;
+            } else {
+                typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+                const h4 o = {(_Float16)v.x, (_Float16)v.y, (_Float16)v.z, (_Float16)v.w};
+                *(h4*)(a.y + (size_t)m * a.d_out + R * 16 + 4 * j) = o;
+            }
         }
     }
     if constexpr (LOWRANK) {
@@ -681,8 +691,8 @@ static hipError_t launch_sparse_wide(const SparseArgs* members, int n, hipStream
     const size_t lds = xb > tb ? xb : tb;
     const int yblocks = (a.M + 15) / 16;
     const int units = (FA != S_NONE) ? (a.r / 16) * a.kcn : 0;
-    auto blocks = [&](const SparseArgs& m) { return ((m.d_out / 16 + NW - 1) / NW) * ((yblocks + TB - 1) / TB) + units * yblocks; };
-    note_launch("sparse_wide FA=%d NW=%d TB=%d VQ=%d n=%d", FA, NW, TB, (int)VQ, n);
+    auto blocks = [&](const SparseArgs& m) { return ((m.d_out / 16 + NW - 1) / NW) * ((yblocks + TB - 1) / TB) * m.ksplit + units * yblocks; };
+    note_launch("sparse_wide FA=%d NW=%d TB=%d VQ=%d n=%d ksplit=%d", FA, NW, TB, (int)VQ, n, a.ksplit);
     if (n == 1) {
         auto kern = sparse_wide_kernel<FA, NW, TB, XW_D, VQ>;
         if (lds > 48 * 1024) {
@@ -690,7 +700,10 @@ static hipError_t launch_sparse_wide(const SparseArgs* members, int n, hipStream
             if (e != hipSuccess) return e;
         }
         hipLaunchKernelGGL(kern, dim3(blocks(a)), dim3(NW * 64), lds, stream, a);
-        return hipGetLastError();
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess || a.ksplit == 1) return e;
+        // y = fp16(sum of the ranges' partial outputs, in the order of the ranges)
+        return launch_reduce_parts(a.ypart, a.y, (size_t)a.M * a.d_out, a.ksplit, stream);
     }
     auto kern = sparse_wide_group_kernel<FA, NW, TB, XW_D, VQ>;
     if (lds > 48 * 1024) {
@@ -703,9 +716,16 @@ static hipError_t launch_sparse_wide(const SparseArgs* members, int n, hipStream
     return hipGetLastError();
 }
 
+size_t sparse_split_bytes(int M, int d_in, int d_out)
+{
+    if (M <= 4 || M >= 128 || d_in < SP_SPLIT_MIN_D_IN) return 0;
+    return (size_t)SP_MAX_SPLIT * M * d_out * sizeof(float);
+}
+
 template <int FA, bool VQ>
 static hipError_t launch_sparse_wide_cfg(const SparseArgs* members, int n, int nw, int tb, hipStream_t stream)
 {
+    if (nw == 16) return launch_sparse_wide<FA, 16, 4, 4, VQ>(members, n, stream);      // sixteen row blocks: four token blocks (one 1 KiB piece per wavefront)
     if (nw == 8) {                                        // eight row blocks: two or four token blocks (whole 1 KiB pieces per wavefront)
         if (tb == 2) return launch_sparse_wide<FA, 8, 2, 4, VQ>(members, n, stream);
         return launch_sparse_wide<FA, 8, 4, 4, VQ>(members, n, stream);
@@ -760,14 +780,25 @@ static hipError_t launch_sparse_vq(const SparseArgs* members, int n, hipStream_t
     // The members of a group are counted together.
     const int yblocks = (a.M + 15) / 16;
     if (a.M > 4 && a.d_in % 512 == 0 && a.r <= 512) {
-        for (int nw = 8; nw >= 4; nw -= 4) {
+        for (int nw = 16; nw >= 4; nw = nw > 8 ? 8 : nw - 4) {
             for (int tb = yblocks < 4 ? yblocks : 4; tb >= 1; tb = tb > 2 ? (tb + 1) / 2 : tb - 1) {
+                if (nw == 16 && tb != 4) continue;
                 if (nw == 8 && tb != 2 && tb != 4) continue;
                 int groups = 0;
                 for (int i = 0; i < n; ++i) groups += (members[i].d_out / 16 + nw - 1) / nw;
-                if (groups * ((yblocks + tb - 1) / tb) >= (nw == 8 ? 192 : 256))
-                    return a.r == 0 ? launch_sparse_wide_cfg<S_NONE, VQ>(members, n, nw, tb, stream)
-                                    : launch_sparse_wide_cfg<S_F16, VQ>(members, n, nw, tb, stream);
+                // a long contraction with few rows (one linear, room for the partial outputs): 2 or 4 ranges of it in
+                // different workgroups before the workgroup gets smaller (the down projection of the 70B layer at 64
+                // tokens: 256 workgroups of four wavefronts over 224 steps each, or 256 of eight over 56)
+                const int smax = (n == 1 && a.ypart && a.d_in >= SP_SPLIT_MIN_D_IN && nw >= 8) ? SP_MAX_SPLIT : 1;
+                for (int ks = 1; ks <= smax; ks *= 2) {
+                    if ((a.d_in / 128) % (ks * 4) != 0) break;
+                    if (groups * ((yblocks + tb - 1) / tb) * ks >= (nw >= 8 ? 192 : 256)) {
+                        SparseArgs m[4] = {members[0], members[n > 1 ? 1 : 0], members[n > 2 ? 2 : 0], members[n > 3 ? 3 : 0]};
+                        for (int i = 0; i < 4; ++i) m[i].ksplit = ks;
+                        return a.r == 0 ? launch_sparse_wide_cfg<S_NONE, VQ>(m, n, nw, tb, stream)
+                                        : launch_sparse_wide_cfg<S_F16, VQ>(m, n, nw, tb, stream);
+                    }
+                }
             }
         }
     }

@@ -93,17 +93,19 @@ def _run_sparse(gpu, quantised, seed, d_in, d_out, M, r, want, nw):
 
 
 @pytest.mark.parametrize("quantised", [False, True])
-@pytest.mark.parametrize("name,d_in,d_out,M,nw,tb", [
-    ("gate", 8192, 28672, 64, 8, 4),      # config 5 at 64 tokens: eight row blocks x four token blocks per workgroup
-    ("q", 8192, 8192, 64, 4, 2),          # four row blocks x two token blocks
-    ("down", 28672, 8192, 64, 4, 2),      # the 28672-long contraction
-    ("mid", 8192, 14336, 64, 8, 2),       # a row count that selects eight row blocks x two token blocks
-    ("gate48", 8192, 28672, 48, 8, 2),    # three token blocks (two per workgroup, the last group ragged)
+@pytest.mark.parametrize("name,d_in,d_out,M,nw,tb,ks", [
+    ("gate", 8192, 28672, 64, 8, 4, 1),      # config 5 at 64 tokens: eight row blocks x four token blocks per workgroup
+    ("q", 8192, 8192, 64, 4, 2, 1),          # four row blocks x two token blocks
+    ("down", 28672, 8192, 64, 8, 4, 4),      # the 28672-long contraction: four ranges of it in different workgroups
+    ("down48", 28672, 8192, 48, 8, 2, 2),    # three token blocks, two ranges
+    ("long", 16384, 4096, 37, 8, 2, 4),      # the shortest contraction that is split; ragged tokens
+    ("mid", 8192, 14336, 64, 8, 2, 1),       # a row count that selects eight row blocks x two token blocks
+    ("gate48", 8192, 28672, 48, 8, 2, 1),    # three token blocks (two per workgroup, the last group ragged)
 ])
-def test_sparse_many_tokens_at_bench_shapes(gpu, quantised, name, d_in, d_out, M, nw, tb):
+def test_sparse_many_tokens_at_bench_shapes(gpu, quantised, name, d_in, d_out, M, nw, tb, ks):
     import synth
-    want = "sparse_wide FA=5 NW=%d TB=%d VQ=%d n=1" % (nw, tb, int(quantised))
-    _run_sparse(gpu, quantised, synth.seed_for(5, {"gate": 4, "q": 0, "down": 6, "mid": 7, "gate48": 4}[name]),
+    want = "sparse_wide FA=5 NW=%d TB=%d VQ=%d n=1 ksplit=%d" % (nw, tb, int(quantised), ks)
+    _run_sparse(gpu, quantised, synth.seed_for(5, {"gate": 4, "q": 0, "down": 6, "down48": 6, "long": 8, "mid": 7, "gate48": 4}[name]),
                 d_in, d_out, M, 128, want, nw)
 
 
@@ -136,7 +138,7 @@ def test_sparse_group_gate_up_at_bench_shape(gpu, quantised):
     ws = gpu.new_workspace(M, d_in, d_out, r)
     gpu.linear_sp24_group(dev(x), [stored + (A_t, B_t, y, d_out) for y in ys], M, d_in, r, ws)
     torch.cuda.synchronize()
-    assert gpu.debug_last_launch() == "sparse_wide FA=5 NW=8 TB=4 VQ=%d n=2" % int(quantised), gpu.debug_last_launch()
+    assert gpu.debug_last_launch() == "sparse_wide FA=5 NW=16 TB=4 VQ=%d n=2 ksplit=1" % int(quantised), gpu.debug_last_launch()
     assert gpu.workspace_error(ws) == 0
     for y in ys:
         _check(y.cpu().numpy()[:, rows], ref)
