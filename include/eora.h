@@ -104,7 +104,9 @@ size_t eora_sp24q4_meta_bytes(int d_in, int d_out);                  /* d_out*(d
  * first forward call on it; every forward call leaves it usable for the next, so no per-call
  * clearing (and nothing a HIP graph could not replay) is needed.  Calls that may overlap in time
  * (different streams) need different workspaces.  r == 0 still needs a workspace.  A workspace of
- * the size of the largest (M, r) serves smaller calls too. */
+ * the size of the largest (M, r) serves smaller calls too.  For 5 .. 127 tokens and d_in >= 16384 the
+ * size also holds 4 * M * d_out floats: a 2:4 call of such a shape may cut its contraction into ranges
+ * whose partial outputs are added, in a fixed order, by a second kernel of the same call. */
 size_t eora_workspace_bytes(int M, int d_in, int d_out, int r);
 /* Size that lets eora_linear_q_group() serve n_members members in one pass also for M >= 128 (the
  * down-projections of all members then sit side by side in the scratch).  With a workspace of only
