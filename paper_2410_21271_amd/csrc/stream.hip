@@ -369,9 +369,12 @@ __global__ __launch_bounds__(RX_NT) void resident_kernel(StreamArgs a)
                     }
                 }
             }
-            first_requests();
+            // (the block's first stored tiles are requested behind the publication of t: issuing requests can take
+            // a wavefront more than a microsecond while the memory pipeline is full, and every workgroup of the
+            // launch ends up waiting for t)
             pa[wave * 64 + lane] = acc_a;
             __syncthreads();
+            if (wave != 0) first_requests();
             if (wave == 0) {
                 f4 v = pa[lane];
                 for (int k = 1; k < nwa; ++k) v += pa[k * 64 + lane];
@@ -393,6 +396,7 @@ __global__ __launch_bounds__(RX_NT) void resident_kernel(StreamArgs a)
                                            __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 }
             }
+            if (wave == 0) first_requests();
             RTL_STAMP(8);
         }
     }
