@@ -328,13 +328,24 @@ def test_linear_q_mid_token_counts(gpu, w_bits, ab_bits, r, M, d_in, d_out, grou
     assert np.array_equal(y, run_linear_q(c))
 
 
-def test_config5_shape_long_contraction(gpu):
-    """BASELINE config 5, the 28672-long contraction of the 70B-shaped down projection (1024 of its rows)."""
+@pytest.mark.parametrize("M,r", [(1, 128), (3, 512), (4, 32)])
+def test_config5_shape_long_contraction(gpu, M, r):
+    """BASELINE config 5, the 28672-long contraction of the 70B-shaped down projection (1024 of its rows): sixteen
+    k-ranges of t; with rank 512 every flag of a token block is in use."""
     import synth
     from tests.cases import SparseCase
     from tests.gpu_util import run_linear_sp24
-    c = SparseCase(synth.seed_for(5, 6), 28672, 1024, 1, 128, packer=gpu)
+    c = SparseCase(synth.seed_for(5, 6), 28672, 1024, M, r, packer=gpu)
     _check(run_linear_sp24(c), c.oracle_y())
+
+
+def test_config5_shape_long_contraction_quantised_values(gpu):
+    """The same contraction with 4-bit kept values."""
+    import synth
+    from tests.cases import SparseQCase
+    from tests.gpu_util import run_linear_sp24q4
+    c = SparseQCase(synth.seed_for(5, 6), 28672, 512, 2, 128, packer=gpu)
+    _check(run_linear_sp24q4(c), c.oracle_y())
 
 
 @pytest.mark.parametrize("M", [1, 64])
