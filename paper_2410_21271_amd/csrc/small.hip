@@ -335,8 +335,10 @@ static hipError_t launch_small_one(const GroupArgs& a, hipStream_t stream)
         // A low-rank launch wants ALL its workgroups resident from the start: a consumer that only gets a slot when
         // the producers have left starts microseconds late and then still needs the whole streaming time, and a
         // consumer that waits for t at its end holds its slot.  So a workgroup takes 2 or 4 row blocks (a strip)
-        // when one each would not fit next to the producers, with some slack (the dispatcher does not fill the
-        // compute units evenly).  128 registers: 16 wavefronts, i.e. 16 / NW workgroups, per compute unit.
+        // when one each would not fit next to the producers (the dispatcher deals workgroups to the compute units
+        // round-robin, so a launch fits exactly when it has no more workgroups than slots; an eighth of slack, kept
+        // at first, sent a single 14336-row linear to strips of two on a half-empty chip: 9.65 -> 9.25 us without).
+        // 128 registers: 16 wavefronts, i.e. 16 / NW workgroups, per compute unit.
         // (The bare layer has no such wait: one row block each streams best; with 3-bit factors, and with 4-bit
         // factors on a 4-bit backbone, the strip instantiations do not fit 128 registers.)
         if constexpr (NQ <= 2 && FA != S_NONE && FA != S_Q3S128) {
@@ -347,7 +349,7 @@ static hipError_t launch_small_one(const GroupArgs& a, hipStream_t stream)
                 even2 = even2 && a.d_out[m] % 32 == 0;
                 even4 = even4 && a.d_out[m] % 64 == 0;
             }
-            const int nprod = (a.r / 16) * a.kcn * a.n, room = 256 * (16 / NW) * 7 / 8;
+            const int nprod = (a.r / 16) * a.kcn * a.n, room = 256 * (16 / NW);
             if (blocks + nprod > room) {
                 // (a four-block strip as straight-line code does not fit 128 registers)
                 if (even2) {
