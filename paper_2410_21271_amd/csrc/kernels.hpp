@@ -26,7 +26,7 @@ constexpr int MAX_YBLOCKS = 16;                 // token blocks per launch (256 
 constexpr int HDR_FLAG_REPLICAS = 8;             // the decode kernels keep 8 copies of the flags, one per group of pollers
 constexpr int HDR_FLAGS_REPLICA_STRIDE = HDR_FLAGS_PER_BLOCK * MAX_YBLOCKS;
 constexpr int HDR_WORDS = HDR_FLAGS0 + HDR_FLAGS_REPLICA_STRIDE * HDR_FLAG_REPLICAS;
-constexpr int MAX_KCN = 8;                      // k-ranges of the down-projection
+constexpr int MAX_KCN = 8;                      // k-ranges of the down-projection (quantised backbones; the 2:4 decode kernel takes up to 16)
 
 // Host-side record of the kernel instantiation the most recent layer launch of this process chose, read
 // back through eora_debug_last_launch() (tests assert that a shape reaches the instantiation it is meant to
