@@ -22,10 +22,27 @@ __device__ __forceinline__ uint32_t ld_relaxed(const uint32_t* p)
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-template <int WORDS>
+// ONCE: the launch reads these bytes exactly once (every token of the call is in the workgroup that streams
+// them): the request carries the non-temporal hint, so the line is not kept in the caches at the cost of lines
+// that are read again (x, t, scales).  Kernels in which several workgroups read the same stored tile (one
+// per group of token blocks) leave it off: there the second reader would miss.
+template <int WORDS, bool ONCE = false>
 __device__ __forceinline__ void load_words(uint32_t (&w)[WORDS], const uint32_t* __restrict__ p)
 {
-    if constexpr (WORDS == 4) {
+    if constexpr (ONCE) {
+        typedef uint32_t u3a __attribute__((ext_vector_type(3), aligned(4)));
+        typedef uint32_t u2v __attribute__((ext_vector_type(2)));
+        if constexpr (WORDS == 4) {
+            const u4 v = __builtin_nontemporal_load((const u4*)p);
+            w[0] = v[0]; w[1] = v[1]; w[2] = v[2]; w[3] = v[3];
+        } else if constexpr (WORDS == 3) {
+            const u3a v = __builtin_nontemporal_load((const u3a*)p);
+            w[0] = v[0]; w[1] = v[1]; w[2] = v[2];
+        } else {
+            const u2v v = __builtin_nontemporal_load((const u2v*)p);
+            w[0] = v[0]; w[1] = v[1];
+        }
+    } else if constexpr (WORDS == 4) {
         const u4 v = *(const u4*)p;
         w[0] = v[0]; w[1] = v[1]; w[2] = v[2]; w[3] = v[3];
     } else if constexpr (WORDS == 3) {
@@ -195,14 +212,14 @@ struct FTile {
     _Float16 sc;
 };
 
-template <int FMT>
+template <int FMT, bool ONCE = false>
 __device__ __forceinline__ void load_ftile(FTile<FMT>& s, const Factor& f, int R, int g, int lane)
 {
     constexpr int WORDS = Fmt<FMT>::WORDS;
     if constexpr (FMT != S_F16) s.sc = f.scales[((size_t)R * 16 + (lane & 15)) * f.ntk + g];
     else s.sc = (_Float16)1.0f;
     const size_t tile = (size_t)R * f.ntk + g;
-    load_words<WORDS>(s.w, f.w + (tile * 64 + lane) * WORDS);
+    load_words<WORDS, ONCE>(s.w, f.w + (tile * 64 + lane) * WORDS);
 }
 
 // phase A: partial of t over k-tiles g_begin + wave, + NW, ... < g_end of row block R of A

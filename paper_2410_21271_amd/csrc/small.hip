@@ -84,7 +84,7 @@ __device__ __forceinline__ void load_bslice(BSlice<FMT>& s, const Factor& f, int
     else s.sc = (_Float16)1.0f;
     const uint32_t* p = f.w + (((size_t)R * f.ntk + g) * 64 + lane) * WORDS;
     if constexpr (BSlice<FMT>::SLICED) s.w[0] = p[q];
-    else load_words<WORDS>(s.w, p);
+    else load_words<WORDS, true>(s.w, p);
 }
 
 template <int FMT>
@@ -181,7 +181,7 @@ __global__ __launch_bounds__(NW * 64, 4) void small_kernel(GroupArgs a)   // sec
 #pragma unroll
         for (int s = 0; s < PD; ++s) {
             const int ss = s < nsteps ? s : (nsteps > 0 ? nsteps - 1 : 0);
-            load_ftile<FA>(buf[s], fa, rho, (nsteps > 0 ? first : kc * tpc) + ss * NW, lane);
+            load_ftile<FA, true>(buf[s], fa, rho, (nsteps > 0 ? first : kc * tpc) + ss * NW, lane);
         }
         __builtin_amdgcn_sched_barrier(0);               // all requests are out before the first result is used
         if (tid == 0) s_epoch = ci.epoch;
@@ -197,7 +197,7 @@ __global__ __launch_bounds__(NW * 64, 4) void small_kernel(GroupArgs a)   // sec
                 if (base + s < nsteps) {
                     const FTile<FA> cur = buf[s];
                     const int g = first + (base + s) * NW;
-                    if (base + s + PD < nsteps) load_ftile<FA>(buf[s], fa, rho, first + (base + s + PD) * NW, lane);
+                    if (base + s + PD < nsteps) load_ftile<FA, true>(buf[s], fa, rho, first + (base + s + PD) * NW, lane);
                     h8 xa[NMF], b[NMF];
                     const _Float16* px = xs + mrow * ldxs + g * KTA + (KTA / 4) * j;
 #pragma unroll

@@ -33,17 +33,24 @@ template <> struct SpT<true> {
 typedef _Float16 h16 __attribute__((ext_vector_type(16)));
 
 // tile g of row block R (G tiles per row block).  Nothing loaded is touched here.
-template <bool VQ>
+// ONCE: no other workgroup of the launch reads this tile (non-temporal requests, see load_words).
+template <bool VQ, bool ONCE>
 __device__ __forceinline__ void load_sptile(SpT<VQ>& t, const SparseArgs& a, int R, int g, int G, int lane)
 {
     const size_t tile = (size_t)R * G + g;
     if constexpr (!VQ) {
-        t.idx = a.indices[tile * 64 + lane];
         const u4* p = (const u4*)(a.values + tile * 1024) + lane;
-        t.v0 = p[0];
-        t.v1 = p[64];
+        if constexpr (ONCE) {
+            t.idx = __builtin_nontemporal_load(a.indices + tile * 64 + lane);
+            t.v0 = __builtin_nontemporal_load(p);
+            t.v1 = __builtin_nontemporal_load(p + 64);
+        } else {
+            t.idx = a.indices[tile * 64 + lane];
+            t.v0 = p[0];
+            t.v1 = p[64];
+        }
     } else {
-        load_words<3>(t.w, a.qtiles + (tile * 64 + lane) * 3);       // one 12-byte request
+        load_words<3, ONCE>(t.w, a.qtiles + (tile * 64 + lane) * 3);       // one 12-byte request
         t.meta = a.qmeta[tile * 16 + (lane & 15)];
     }
 }
@@ -185,10 +192,10 @@ __device__ __forceinline__ void sparse_body(const SparseArgs& a, const int gbid,
     const int g_first = nsteps > 0 ? wave : 0;
     SpT<VQ> buf[PD];
 #pragma unroll
-    for (int s = 0; s < PD; ++s) load_sptile<VQ>(buf[s], a, R, g_first + (s < nsteps ? s : last) * NW, G, lane);
+    for (int s = 0; s < PD; ++s) load_sptile<VQ, XLDS>(buf[s], a, R, g_first + (s < nsteps ? s : last) * NW, G, lane);
     const Factor fb{(const uint32_t*)a.B, nullptr, LOWRANK ? a.r / 32 : 0};
     FTile<S_F16> bpre;
-    if constexpr (LOWRANK) load_ftile<S_F16>(bpre, fb, R, wave < fb.ntk ? wave : 0, lane);
+    if constexpr (LOWRANK) load_ftile<S_F16, XLDS>(bpre, fb, R, wave < fb.ntk ? wave : 0, lane);
     if constexpr (LOWRANK) {
         if (tid == 0) {
             check_in_issue(ci, a.hdr, gbid);
@@ -239,7 +246,7 @@ __device__ __forceinline__ void sparse_body(const SparseArgs& a, const int gbid,
             }
             __builtin_amdgcn_sched_barrier(0);
             const int sn = base + s + PD;
-            load_sptile<VQ>(buf[s], a, R, g_first + (sn < nsteps ? sn : last) * NW, G, lane);
+            load_sptile<VQ, XLDS>(buf[s], a, R, g_first + (sn < nsteps ? sn : last) * NW, G, lane);
         }
     }
 
@@ -307,7 +314,7 @@ __device__ __forceinline__ void sparse_body(const SparseArgs& a, const int gbid,
             for (int g = wave; g < fb.ntk; g += NW) {
                 FTile<S_F16> cur;
                 if (g == wave) cur = bpre;
-                else load_ftile<S_F16>(cur, fb, R, g, lane);
+                else load_ftile<S_F16, XLDS>(cur, fb, R, g, lane);
                 h8 b[1];
                 decode_tile<S_F16>(cur.w, 0u, b);
                 const float* p = ts + mrow * a.r + g * 32 + 8 * j;
@@ -360,7 +367,7 @@ __device__ __forceinline__ void sparse_body(const SparseArgs& a, const int gbid,
 // LDS slot layout: 16-byte piece q of token row t (columns 8q .. 8q+7 of the chunk) sits at piece index
 // 16 t + (q ^ (t & 15)): the 16 lanes that read one q for 16 tokens hit 16 different bank groups.
 // Producers, flags, partials and the continuation are those of the kernel above.
-template <int FA, int NW, int TB, int XW_D, bool VQ>      // XW_D: steps between a request and its use; divides d_in / 128
+template <int FA, int NW, int TB, int XW_D, bool VQ, bool ONCE>      // XW_D: steps between a request and its use; divides d_in / 128; ONCE: one group of token blocks, so every stored tile is read by one workgroup
 __device__ __forceinline__ void sparse_wide_body(const SparseArgs& a, const int gbid, const int bid, const int flag0)
 {
     constexpr bool LOWRANK = FA != S_NONE;
@@ -447,7 +454,7 @@ __device__ __forceinline__ void sparse_wide_body(const SparseArgs& a, const int 
         xsrc[i] = a.x + (size_t)grow * a.d_in + (size_t)c0 * 128 + 8 * (lane & 15);      // (chunk s of the range at + s * 128)
         xdst[i] = (trow * 16 + ((lane & 15) ^ (trow & 15))) * 16;
     }
-    auto load_tile = [&](SpT<VQ>& t, int c) { load_sptile<VQ>(t, a, R, c0 + c, G, lane); };      // c: chunk within the range
+    auto load_tile = [&](SpT<VQ>& t, int c) { load_sptile<VQ, ONCE>(t, a, R, c0 + c, G, lane); };      // c: chunk within the range
     SpT<VQ> buf[XW_D];
     u4 xr[XW_D][XN];
 #pragma unroll
@@ -524,7 +531,7 @@ __device__ __forceinline__ void sparse_wide_body(const SparseArgs& a, const int 
         constexpr int BPRE = 4;                           // B's first tiles are requested before the wait for t
         FTile<S_F16> bt[BPRE];
 #pragma unroll
-        for (int g = 0; g < BPRE; ++g) load_ftile<S_F16>(bt[g], fb, R, g < fb.ntk ? g : 0, lane);
+        for (int g = 0; g < BPRE; ++g) load_ftile<S_F16, ONCE>(bt[g], fb, R, g < fb.ntk ? g : 0, lane);
         __syncthreads();                                  // nobody reads x any more
         const uint32_t epoch = s_epoch;
         if (wave == 0) {
@@ -600,7 +607,7 @@ __device__ __forceinline__ void sparse_wide_body(const SparseArgs& a, const int 
                         if (g < fb.ntk) contract(bt[g], g);
                     for (int g = BPRE; g < fb.ntk; ++g) {
                         FTile<S_F16> cur;
-                        load_ftile<S_F16>(cur, fb, R, g, lane);
+                        load_ftile<S_F16, ONCE>(cur, fb, R, g, lane);
                         contract(cur, g);
                     }
                 }
@@ -655,17 +662,17 @@ __global__ __launch_bounds__(NW * 64, 6) void sparse_group_kernel(SparseGroupArg
     sparse_body<FA, FE, NW, XLDS, VQ>(grp.m[mem], blockIdx.x, (int)blockIdx.x - grp.first[mem], grp.flag0[mem]);
 }
 
-template <int FA, int NW, int TB, int XW_D, bool VQ>
+template <int FA, int NW, int TB, int XW_D, bool VQ, bool ONCE>
 __global__ __launch_bounds__(NW * 64) void sparse_wide_kernel(SparseArgs a)
 {
-    sparse_wide_body<FA, NW, TB, XW_D, VQ>(a, blockIdx.x, blockIdx.x, 0);
+    sparse_wide_body<FA, NW, TB, XW_D, VQ, ONCE>(a, blockIdx.x, blockIdx.x, 0);
 }
 
-template <int FA, int NW, int TB, int XW_D, bool VQ>
+template <int FA, int NW, int TB, int XW_D, bool VQ, bool ONCE>
 __global__ __launch_bounds__(NW * 64) void sparse_wide_group_kernel(SparseGroupArgs grp)
 {
     const int mem = sparse_member(grp);
-    sparse_wide_body<FA, NW, TB, XW_D, VQ>(grp.m[mem], blockIdx.x, (int)blockIdx.x - grp.first[mem], grp.flag0[mem]);
+    sparse_wide_body<FA, NW, TB, XW_D, VQ, ONCE>(grp.m[mem], blockIdx.x, (int)blockIdx.x - grp.first[mem], grp.flag0[mem]);
 }
 
 // fills the member table; blocks(i) = workgroups of member i
@@ -683,7 +690,7 @@ static int fill_group(SparseGroupArgs& g, const SparseArgs* members, int n, int 
     return total;
 }
 
-template <int FA, int NW, int TB, int XW_D, bool VQ>
+template <int FA, int NW, int TB, int XW_D, bool VQ, bool ONCE = false>
 static hipError_t launch_sparse_wide(const SparseArgs* members, int n, hipStream_t stream)
 {
     const SparseArgs& a = members[0];
@@ -694,7 +701,7 @@ static hipError_t launch_sparse_wide(const SparseArgs* members, int n, hipStream
     auto blocks = [&](const SparseArgs& m) { return ((m.d_out / 16 + NW - 1) / NW) * ((yblocks + TB - 1) / TB) * m.ksplit + units * yblocks; };
     note_launch("sparse_wide FA=%d NW=%d TB=%d VQ=%d n=%d ksplit=%d", FA, NW, TB, (int)VQ, n, a.ksplit);
     if (n == 1) {
-        auto kern = sparse_wide_kernel<FA, NW, TB, XW_D, VQ>;
+        auto kern = sparse_wide_kernel<FA, NW, TB, XW_D, VQ, ONCE>;
         if (lds > 48 * 1024) {
             hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
             if (e != hipSuccess) return e;
@@ -705,7 +712,7 @@ static hipError_t launch_sparse_wide(const SparseArgs* members, int n, hipStream
         // y = fp16(sum of the ranges' partial outputs, in the order of the ranges)
         return launch_reduce_parts(a.ypart, a.y, (size_t)a.M * a.d_out, a.ksplit, stream);
     }
-    auto kern = sparse_wide_group_kernel<FA, NW, TB, XW_D, VQ>;
+    auto kern = sparse_wide_group_kernel<FA, NW, TB, XW_D, VQ, ONCE>;
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
@@ -725,10 +732,15 @@ size_t sparse_split_bytes(int M, int d_in, int d_out)
 template <int FA, bool VQ>
 static hipError_t launch_sparse_wide_cfg(const SparseArgs* members, int n, int nw, int tb, hipStream_t stream)
 {
-    if (nw == 16) return launch_sparse_wide<FA, 16, 4, 4, VQ>(members, n, stream);      // sixteen row blocks: four token blocks (one 1 KiB piece per wavefront)
+    // up to 64 tokens in workgroups of four token blocks: every stored tile is read by one workgroup, once
+    // (70B 2:4 layer at 64 tokens: gate+up 120.7 -> 110.2 us with non-temporal requests; the launches in which two
+    // groups of token blocks read the same tiles lose 6-10 % with them and keep ordinary loads)
+    const bool once = members[0].M <= 16 * tb;
+    if (nw == 16) return once ? launch_sparse_wide<FA, 16, 4, 4, VQ, true>(members, n, stream)       // sixteen row blocks: four token blocks (one 1 KiB piece per wavefront)
+                              : launch_sparse_wide<FA, 16, 4, 4, VQ>(members, n, stream);
     if (nw == 8) {                                        // eight row blocks: two or four token blocks (whole 1 KiB pieces per wavefront)
         if (tb == 2) return launch_sparse_wide<FA, 8, 2, 4, VQ>(members, n, stream);
-        return launch_sparse_wide<FA, 8, 4, 4, VQ>(members, n, stream);
+        return once ? launch_sparse_wide<FA, 8, 4, 4, VQ, true>(members, n, stream) : launch_sparse_wide<FA, 8, 4, 4, VQ>(members, n, stream);
     }
     // four row blocks: one or two token blocks (with three or four of them the eight-row-block split above
     // always has its 192 workgroups too, and comes first)

@@ -222,7 +222,7 @@ __global__ __launch_bounds__(RX_NT) void resident_kernel(StreamArgs a)
         zq[Q] = sk_pick(a.w_zeros, mem)[row * (G / 8) + (g0 >> 3)] >> (4 * (g0 & 7));
         const uint32_t* wp = (const uint32_t*)sk_pick(a.w, mem) + (((size_t)rb * G + g0) * 64 + lane) * WORDS;
 #pragma unroll
-        for (int i = 0; i < UT; ++i) load_words<WORDS>(wq[Q][i], wp + (size_t)i * 64 * WORDS);
+        for (int i = 0; i < UT; ++i) load_words<WORDS, true>(wq[Q][i], wp + (size_t)i * 64 * WORDS);
     };
     auto request = [&](auto Lc) __attribute__((always_inline)) { request_at(Lc, decltype(Lc)::value); };
     // The first requests go out before x is staged.  A workgroup that begins with a block of A asks for ALL of that
@@ -310,7 +310,7 @@ __global__ __launch_bounds__(RX_NT) void resident_kernel(StreamArgs a)
         if (a_first) {
             const int rho = wi % (NAm > 0 ? NAm : 1), wv = wave < nwa ? wave : 0;
 #pragma unroll
-            for (int u = 0; u < ATW; ++u) load_ftile<FAB>(abuf[u], fa, rho, s * ntkl + wv * tpw + (u < tpw ? u : tpw - 1), lane);
+            for (int u = 0; u < ATW; ++u) load_ftile<FAB, true>(abuf[u], fa, rho, s * ntkl + wv * tpw + (u < tpw ? u : tpw - 1), lane);
             __builtin_amdgcn_sched_barrier(0);                            // (all of them out before anything below waits)
             RTL_WSTAMP(1);
             stage_x();
@@ -453,7 +453,7 @@ __global__ __launch_bounds__(RX_NT) void resident_kernel(StreamArgs a)
     if constexpr (LOWRANK) {
         if (finisher) {
 #pragma unroll
-            for (int u = 0; u < BPRE; ++u) load_ftile<FEB>(bt[u], fb, rrb, u < fb.ntk ? u : 0, lane);
+            for (int u = 0; u < BPRE; ++u) load_ftile<FEB, true>(bt[u], fb, rrb, u < fb.ntk ? u : 0, lane);
         }
     }
 
@@ -546,7 +546,7 @@ __global__ __launch_bounds__(RX_NT) void resident_kernel(StreamArgs a)
                     for (int u = 0; u < BPRE; ++u) {
                         if (g0 + u < fb.ntk) {
                             const FTile<FEB> cw = bt[u];
-                            if (g0 + u + BPRE < fb.ntk) load_ftile<FEB>(bt[u], fb, rrb, g0 + u + BPRE, lane);
+                            if (g0 + u + BPRE < fb.ntk) load_ftile<FEB, true>(bt[u], fb, rrb, g0 + u + BPRE, lane);
                             ext_tile(cw, g0 + u);
                         }
                     }
