@@ -161,13 +161,15 @@ __global__ void probe_empty_kernel(uint32_t* sink)
 }
 
 // every workgroup of 256 threads reads 32 KiB: eight 16-byte loads per lane, all in flight at once; the result
-// is consumed without being stored (the store's condition never holds for data that is not all-ones patterns)
+// is consumed without being stored (the store's condition never holds for data that is not all-ones patterns).
+// The requests carry the non-temporal hint, as the layer kernels' requests for stored tiles do: a pure read of
+// 56 MB reaches 6.15 TB/s with it and 5.7 TB/s without, of 241 MB 6.85 against 6.3.
 __global__ __launch_bounds__(256) void probe_stream_kernel(const u4* __restrict__ src, uint32_t* sink)
 {
     const u4* p = src + (size_t)blockIdx.x * 2048 + threadIdx.x;
     u4 v[8];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) v[u] = p[u * 256];
+    for (int u = 0; u < 8; ++u) v[u] = __builtin_nontemporal_load(p + u * 256);
     u4 acc = v[0];
 #pragma unroll
     for (int u = 1; u < 8; ++u) acc ^= v[u];
